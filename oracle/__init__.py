@@ -1,0 +1,96 @@
+"""CPU checker for the tree-network forward pass: ctypes front end of tree_oracle.c.
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
+benchmark's CPU-baseline leg.  The GPU library and its Python binding never import
+this package, and this package never imports them.  See the header of
+tree_oracle.c for what is computed and how it is pinned (and what is not).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+from .build import LIB, build
+
+_lib = None
+_F = ctypes.POINTER(ctypes.c_float)
+_I = ctypes.POINTER(ctypes.c_int32)
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(LIB)
+        lib.oracle_structure.restype = ctypes.c_int
+        lib.oracle_structure.argtypes = [ctypes.c_int, ctypes.c_int, _I, _I, _I, _I, _I, _I]
+        lib.oracle_forward.restype = ctypes.c_int
+        lib.oracle_forward.argtypes = ([ctypes.c_int] * 5 + [_F] * 6 + [ctypes.c_int, ctypes.c_int] + [_I] * 4
+                                       + [ctypes.c_int, ctypes.c_int] + [_F] * 4)
+        _lib = lib
+    return _lib
+
+
+def _f(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.dtype == np.float32 and a.flags.c_contiguous
+    return a.ctypes.data_as(_F)
+
+
+def _i(a: np.ndarray):
+    assert a.dtype == np.int32 and a.flags.c_contiguous
+    return a.ctypes.data_as(_I)
+
+
+def to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest bfloat16 (ties to even), kept in an fp32 array."""
+    bits = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (bits >> np.uint64(16)) & np.uint64(1)
+    bits = (bits + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    return bits.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def structure(tree_off, left, right):
+    """(parent, root, height) by plain traversal; raises ValueError on a malformed batch."""
+    lib = _load()
+    n_trees, n_nodes = len(tree_off) - 1, len(left)
+    parent = np.empty(max(n_nodes, 1), dtype=np.int32)
+    height = np.zeros(max(n_nodes, 1), dtype=np.int32)
+    root = np.empty(max(n_trees, 1), dtype=np.int32)
+    rc = lib.oracle_structure(n_trees, n_nodes, _i(tree_off), _i(left), _i(right), _i(parent), _i(root), _i(height))
+    if rc != 0:
+        raise ValueError("malformed tree batch")
+    return parent[:n_nodes], root[:n_trees], height[:n_nodes]
+
+
+def forward(cell, vocab, embed_dim, hidden, emb, w_leaf, b_leaf, u, b, v,
+            tree_off, left, right, word, order="recursive", n_threads=1, round_bf16=False):
+    """Evaluate every node.  Returns dict(h, c, h_root, c_root) of fp32 arrays (c* None unless TreeLSTM)."""
+    lib = _load()
+    n_trees, n_nodes = len(tree_off) - 1, len(left)
+    H = hidden
+    h = np.zeros((n_nodes, H), dtype=np.float32)
+    h_root = np.zeros((n_trees, H), dtype=np.float32)
+    c = c_root = None
+    if cell == 0:
+        c = np.zeros((n_nodes, H), dtype=np.float32)
+        c_root = np.zeros((n_trees, H), dtype=np.float32)
+    rc = lib.oracle_forward(cell, vocab, embed_dim, H, int(bool(round_bf16)),
+                            _f(emb), _f(w_leaf), _f(b_leaf), _f(u), _f(b), _f(v),
+                            n_trees, n_nodes, _i(tree_off), _i(left), _i(right), _i(word),
+                            {"recursive": 0, "topological": 1}[order], int(n_threads),
+                            _f(h), _f(c), _f(h_root), _f(c_root))
+    if rc != 0:
+        raise ValueError("malformed tree batch")
+    return {"h": h, "c": c, "h_root": h_root, "c_root": c_root}
+
+
+def forward_params(params, trees, **kw):
+    """Convenience: same as forward() for objects carrying the fields by name."""
+    return forward(params.cell, params.vocab, params.embed_dim, params.hidden, params.emb, params.w_leaf,
+                   params.b_leaf, params.u, params.b, params.v,
+                   trees.tree_off, trees.left, trees.right, trees.word, **kw)

@@ -1,0 +1,251 @@
+/*
+ * CPU checker for batched forward evaluation of recursive tree networks.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the GPU
+ * library is compared against.  It shares no code with the GPU library and must
+ * never be linked into, imported by, or called from the product path.
+ *
+ * What it follows:
+ *  - Evaluation order "recursive": the recursive definition of the paper's
+ *    Figure 2 (a node is a leaf -> embed + cell; otherwise evaluate both
+ *    children, then the two-input cell).
+ *  - Evaluation order "topological": the iterative formulation of Figure 1
+ *    (all leaves, then internal nodes in an order in which children precede
+ *    parents).  Section 6.2 ("Convergence") states both give numerically
+ *    identical results; here they are bit-identical because each node's
+ *    arithmetic is the same sequence of operations.
+ *  - The paper names the cells (TreeLSTM, TreeRNN, RNTN; Section 6.1) without
+ *    printing equations.  The forms used are the standard binary ones:
+ *
+ *    TreeLSTM leaf     g = x W_x + b_x, g = [gi|go|gu] each H wide
+ *                      i = s(gi) o = s(go) u = tanh(gu);  c = i*u;  h = o*tanh(c)
+ *    TreeLSTM internal a = [h_l ; h_r];  g = a U + b, g = [gi|gfl|gfr|go|gu]
+ *                      c = s(gi)*tanh(gu) + s(gfl)*c_l + s(gfr)*c_r;  h = s(go)*tanh(c)
+ *    TreeRNN           leaf h = x;  internal h = tanh(a W + b)
+ *    RNTN              leaf h = x;  internal h_k = tanh(sum_pq a_p V[k][p][q] a_q + (a W)_k + b_k)
+ *
+ *    with s(t) = 1/(1+exp(-t)).
+ *
+ * Arithmetic: inputs are fp32; every sum is accumulated in double in ascending
+ * index order; s() and tanh() are libm in double; each stored h / c element is
+ * rounded to fp32 once.  A parent consumes the *stored* fp32 h / c of its children.
+ * With round_bf16 != 0 the gathered operand vector (embedding row or [h_l;h_r]) is
+ * rounded to bfloat16 (round to nearest even) before it enters a contraction, which
+ * models a matrix unit fed with bf16 operands; the caller passes weights that are
+ * already bf16-representable.  c is never rounded to bf16.
+ *
+ * Parity status: the cell equations are pinned by tests against closed forms,
+ * hand-worked small trees, torch.nn.RNN / torch.nn.LSTM special cases and an
+ * independent numpy evaluation.  Agreement with the *paper authors'* own TreeLSTM
+ * variant (leaf treatment, bias sharing, hyper-parameters) is PARITY UNPINNED: the
+ * paper prints no equations, weights or activations.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { CELL_TREELSTM = 0, CELL_TREERNN = 1, CELL_RNTN = 2 };
+
+typedef struct {
+    int cell, vocab, E, H, round_bf16;
+    const float *emb, *w_leaf, *b_leaf, *u, *b, *v;
+    const int32_t *left, *right, *word;
+    float *h, *c;
+} model_t;
+
+static double sigm(double t) { return 1.0 / (1.0 + exp(-t)); }
+
+/* fp32 -> nearest bfloat16 (ties to even), returned as fp32. Finite inputs only. */
+static float to_bf16(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    uint32_t lsb = (bits >> 16) & 1u;
+    bits += 0x7FFFu + lsb;
+    bits &= 0xFFFF0000u;
+    memcpy(&x, &bits, 4);
+    return x;
+}
+
+static void load_operand(const model_t *m, double *dst, const float *src, int n)
+{
+    for (int k = 0; k < n; ++k)
+        dst[k] = m->round_bf16 ? (double)to_bf16(src[k]) : (double)src[k];
+}
+
+/* g[j] = bias[j] + sum_k a[k] * W[k][j],  W row-major [K x ncol] */
+static void affine(const double *a, int K, const float *W, const float *bias, int ncol, double *g)
+{
+    for (int j = 0; j < ncol; ++j) g[j] = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const double ak = a[k];
+        const float *row = W + (size_t)k * ncol;
+        for (int j = 0; j < ncol; ++j) g[j] += ak * (double)row[j];
+    }
+    for (int j = 0; j < ncol; ++j) g[j] += (double)bias[j];
+}
+
+static void leaf_cell(const model_t *m, int n, double *a, double *g)
+{
+    const int H = m->H, E = m->E;
+    const float *x = m->emb + (size_t)m->word[n] * E;
+    float *h = m->h + (size_t)n * H;
+    if (m->cell == CELL_TREELSTM) {
+        float *c = m->c + (size_t)n * H;
+        load_operand(m, a, x, E);
+        affine(a, E, m->w_leaf, m->b_leaf, 3 * H, g);
+        for (int j = 0; j < H; ++j) {
+            double i = sigm(g[j]), o = sigm(g[H + j]), u = tanh(g[2 * H + j]);
+            double cc = i * u;
+            c[j] = (float)cc;
+            h[j] = (float)(o * tanh(cc));
+        }
+    } else {
+        for (int j = 0; j < H; ++j) h[j] = x[j];   /* E == H for these cells */
+    }
+}
+
+static void internal_cell(const model_t *m, int n, double *a, double *g)
+{
+    const int H = m->H;
+    const int l = m->left[n], r = m->right[n];
+    float *h = m->h + (size_t)n * H;
+    load_operand(m, a, m->h + (size_t)l * H, H);
+    load_operand(m, a + H, m->h + (size_t)r * H, H);
+    if (m->cell == CELL_TREELSTM) {
+        const float *cl = m->c + (size_t)l * H, *cr = m->c + (size_t)r * H;
+        float *c = m->c + (size_t)n * H;
+        affine(a, 2 * H, m->u, m->b, 5 * H, g);
+        for (int j = 0; j < H; ++j) {
+            double i = sigm(g[j]), fl = sigm(g[H + j]), fr = sigm(g[2 * H + j]);
+            double o = sigm(g[3 * H + j]), u = tanh(g[4 * H + j]);
+            double cc = i * u + fl * (double)cl[j] + fr * (double)cr[j];
+            c[j] = (float)cc;
+            h[j] = (float)(o * tanh(cc));
+        }
+    } else {
+        affine(a, 2 * H, m->u, m->b, H, g);
+        if (m->cell == CELL_RNTN) {
+            const int D2 = 2 * H;
+            for (int k = 0; k < H; ++k) {
+                const float *Vk = m->v + (size_t)k * D2 * D2;
+                double s = 0.0;
+                for (int p = 0; p < D2; ++p) {
+                    double t = 0.0;
+                    for (int q = 0; q < D2; ++q) t += (double)Vk[(size_t)p * D2 + q] * a[q];
+                    s += a[p] * t;
+                }
+                g[k] += s;
+            }
+        }
+        for (int j = 0; j < H; ++j) h[j] = (float)tanh(g[j]);
+    }
+}
+
+static void eval_recursive(const model_t *m, int n, double *a, double *g)
+{
+    if (m->left[n] < 0) {
+        leaf_cell(m, n, a, g);
+    } else {
+        eval_recursive(m, m->left[n], a, g);
+        eval_recursive(m, m->right[n], a, g);
+        internal_cell(m, n, a, g);
+    }
+}
+
+static int height_of(const int32_t *left, const int32_t *right, int n, int32_t *height)
+{
+    if (left[n] < 0) { height[n] = 0; return 0; }
+    int hl = height_of(left, right, left[n], height);
+    int hr = height_of(left, right, right[n], height);
+    height[n] = 1 + (hl > hr ? hl : hr);
+    return height[n];
+}
+
+/*
+ * Plain traversal of the batch structure.
+ *   parent[n] : global index of n's parent, -1 for roots
+ *   root[t]   : the node of tree t that is nobody's child
+ *   height[n] : 0 at leaves, 1 + max(children) otherwise
+ * Returns 0, or -1 if a tree does not have exactly one root / a child index leaves
+ * its tree's range / a node has two parents.
+ */
+int oracle_structure(int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+                     const int32_t *right, int32_t *parent, int32_t *root, int32_t *height)
+{
+    for (int n = 0; n < n_nodes; ++n) parent[n] = -1;
+    for (int t = 0; t < n_trees; ++t) {
+        for (int n = tree_off[t]; n < tree_off[t + 1]; ++n) {
+            if ((left[n] < 0) != (right[n] < 0)) return -1;
+            if (left[n] < 0) continue;
+            const int ch[2] = { left[n], right[n] };
+            for (int s = 0; s < 2; ++s) {
+                if (ch[s] < tree_off[t] || ch[s] >= tree_off[t + 1]) return -1;
+                if (parent[ch[s]] != -1) return -1;
+                parent[ch[s]] = n;
+            }
+        }
+    }
+    for (int t = 0; t < n_trees; ++t) {
+        int found = -1;
+        for (int n = tree_off[t]; n < tree_off[t + 1]; ++n)
+            if (parent[n] == -1) { if (found >= 0) return -1; found = n; }
+        if (found < 0) return -1;
+        root[t] = found;
+        height_of(left, right, found, height);
+    }
+    return 0;
+}
+
+/*
+ * Forward evaluation of every node of every tree.
+ *   order 0: recursive (Figure 2).  order 1: leaves first, then internal nodes by
+ *   ascending height, ties in index order (Figure 1 with a valid topological order).
+ *   n_threads: trees are independent, so they may be spread over threads; the
+ *   per-node arithmetic is unaffected.
+ * h, c: [n_nodes x H] row-major outputs (c is ignored for TreeRNN / RNTN and may be NULL).
+ * h_root, c_root: [n_trees x H], may be NULL.  Returns 0 or -1 on a malformed batch.
+ */
+int oracle_forward(int cell, int vocab, int E, int H, int round_bf16,
+                   const float *emb, const float *w_leaf, const float *b_leaf,
+                   const float *u, const float *b, const float *v,
+                   int n_trees, int n_nodes, const int32_t *tree_off,
+                   const int32_t *left, const int32_t *right, const int32_t *word,
+                   int order, int n_threads,
+                   float *h, float *c, float *h_root, float *c_root)
+{
+    model_t m = { cell, vocab, E, H, round_bf16, emb, w_leaf, b_leaf, u, b, v, left, right, word, h, c };
+    int32_t *parent = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *height = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *root = malloc(sizeof(int32_t) * (size_t)(n_trees > 0 ? n_trees : 1));
+    int rc = oracle_structure(n_trees, n_nodes, tree_off, left, right, parent, root, height);
+    for (int n = 0; rc == 0 && n < n_nodes; ++n)
+        if (left[n] < 0 && (word[n] < 0 || word[n] >= vocab)) rc = -1;
+    if (rc == 0) {
+        const int K = (2 * H > E ? 2 * H : E), G = 5 * H;
+        if (n_threads < 1) n_threads = 1;
+        #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+        for (int t = 0; t < n_trees; ++t) {
+            double *a = malloc(sizeof(double) * (size_t)K);
+            double *g = malloc(sizeof(double) * (size_t)G);
+            if (order == 0) {
+                eval_recursive(&m, root[t], a, g);
+            } else {
+                const int lo = tree_off[t], hi = tree_off[t + 1];
+                for (int lvl = 0; lvl <= height[root[t]]; ++lvl)
+                    for (int n = lo; n < hi; ++n)
+                        if (height[n] == lvl) {
+                            if (lvl == 0) leaf_cell(&m, n, a, g); else internal_cell(&m, n, a, g);
+                        }
+            }
+            for (int j = 0; j < H; ++j) {
+                if (h_root) h_root[(size_t)t * H + j] = h[(size_t)root[t] * H + j];
+                if (c_root && cell == CELL_TREELSTM) c_root[(size_t)t * H + j] = c[(size_t)root[t] * H + j];
+            }
+            free(a); free(g);
+        }
+    }
+    free(parent); free(height); free(root);
+    return rc;
+}
