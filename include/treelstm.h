@@ -1,0 +1,163 @@
+/*
+ * treelstm.h - batched forward evaluation of recursive tree networks on one AMD
+ * MI355X (gfx950).  C ABI; every pointer is a plain pointer, marked below as HOST or
+ * DEVICE memory.
+ *
+ * What is computed.  A batch of full binary trees is evaluated bottom-up: a leaf's
+ * state comes from the embedding of its word, an internal node's state from the
+ * states of its two children (the recursive definition of the paper's Figure 2).
+ * A node's cell runs as soon as its children are done, so independent subtrees and
+ * independent trees proceed concurrently (Section 4.1, "Recursive Execution": ready
+ * queue fed by unresolved-input counters), instead of one node at a time in a
+ * topologically sorted order (Figure 1).  The result is the same set of numbers
+ * either way (Section 6.2, "Convergence").
+ *
+ * The paper names its cells (Section 6.1: TreeLSTM, TreeRNN, RNTN) without printing
+ * them; this library uses the standard binary forms.  With s(t) = 1/(1+exp(-t)),
+ * x = embedding row of a leaf's word, a = [h_left ; h_right] (length 2H):
+ *
+ *   TL_TREELSTM  leaf      [gi|go|gu] = x W_leaf + b_leaf         (each block H wide)
+ *                          c = s(gi)*tanh(gu);  h = s(go)*tanh(c)
+ *                internal  [gi|gfl|gfr|go|gu] = a U + b
+ *                          c = s(gi)*tanh(gu) + s(gfl)*c_left + s(gfr)*c_right
+ *                          h = s(go)*tanh(c)
+ *   TL_TREERNN   leaf h = x (embed_dim == hidden);  internal h = tanh(a U + b)
+ *   TL_RNTN      leaf h = x;  internal h_k = tanh(sum_pq a_p V[k][p][q] a_q + (a U)_k + b_k)
+ *
+ * Tree encoding (the paper's tree.children[idx] / tree.leaves[idx] index arrays of
+ * Figures 1-2, flattened over the batch): tree t owns nodes tree_off[t] ..
+ * tree_off[t+1]-1; left[n] / right[n] are GLOBAL node indices of n's children inside
+ * the same tree, or -1 at a leaf; word[n] is the word id of a leaf (ignored at
+ * internal nodes).  Nodes of a tree may be numbered in ANY order - no topological
+ * sorting is required (Section 2.1 explains that only the iterative form needs it).
+ * A single-node tree (the root is a leaf) is legal.
+ *
+ * Threading: a context is not thread safe; one forward may be in flight per context.
+ * Errors: functions return TL_OK (0) or a negative tl_error.
+ */
+#ifndef TREELSTM_H
+#define TREELSTM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tl_ctx tl_ctx;
+
+enum tl_cell { TL_TREELSTM = 0, TL_TREERNN = 1, TL_RNTN = 2 };
+
+/* TL_F32: fp32 operands, fp32 accumulation.  TL_BF16_IN: weights, embeddings and the
+ * gathered child h are rounded to bfloat16 (nearest even) as matrix operands;
+ * accumulation, gate functions, c and the stored h stay fp32. */
+enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
+
+/* How internal nodes are scheduled (Section 4.1 versus the depth-wise batching that
+ * Section 6.3, "Comparison with Folding", describes):
+ *  TL_SCHED_READY        one persistent kernel; every node has a counter of unfinished
+ *                        children; the workgroup that finishes the last child pushes the
+ *                        parent on a device ready queue, from which tiles of ready nodes
+ *                        are formed.  Needs no heights and no per-level barrier.
+ *  TL_SCHED_LEVEL_DEVICE node heights and per-height node lists are built on the device;
+ *                        one persistent kernel walks the heights with a grid-wide barrier.
+ *  TL_SCHED_LEVEL_HOST   same lists, one kernel launch per height from the host (the host
+ *                        reads the number of heights back first).  Comparison baseline. */
+enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2 };
+
+enum tl_error {
+    TL_OK = 0,
+    TL_EINVAL = -1,    /* null pointer, negative size, unsupported dimension or enum          */
+    TL_ENOMEM = -2,    /* device or host allocation failed                                     */
+    TL_EHIP = -3,      /* a HIP runtime call failed                                            */
+    TL_ESTRUCT = -4,   /* malformed batch: offsets not ascending / child outside its tree /
+                          node with two parents / tree without exactly one root / leaf word id
+                          outside the vocabulary / node count inconsistent with full binary trees */
+    TL_ESTALL = -5     /* the scheduler made no progress within its spin budget (nodes that are
+                          unreachable from any leaf, e.g. a cycle); outputs are incomplete      */
+};
+
+typedef struct {
+    int cell;          /* enum tl_cell      */
+    int precision;     /* enum tl_precision */
+    int scheduler;     /* enum tl_scheduler */
+    int validate;      /* != 0: additionally prove, before any cell runs, that every node is
+                          reachable bottom-up from the leaves (costs one pass whose length is the
+                          tree height).  The cheap checks listed under TL_ESTRUCT always run.    */
+    int vocab;         /* rows of emb                                                           */
+    int embed_dim;     /* E.  TL_TREERNN / TL_RNTN require embed_dim == hidden                  */
+    int hidden;        /* H (called d for TreeRNN / RNTN)                                       */
+    int spin_limit;    /* 0 = default.  Upper bound on consecutive unsuccessful polls of a
+                          waiting workgroup before it gives up with TL_ESTALL.                   */
+    /* All parameter arrays: DEVICE pointers, fp32, row-major, read during tl_create only
+     * (the library keeps its own re-packed copies; the caller may free them afterwards). */
+    const float *emb;     /* [vocab x E]                                                          */
+    const float *w_leaf;  /* TL_TREELSTM: [E x 3H], column blocks i | o | u.   Else NULL.         */
+    const float *b_leaf;  /* TL_TREELSTM: [3H].                                Else NULL.         */
+    const float *u;       /* TL_TREELSTM: [2H x 5H], column blocks i | f_l | f_r | o | u; rows
+                             0..H-1 multiply h_left, rows H..2H-1 multiply h_right.
+                             TL_TREERNN / TL_RNTN: W [2d x d].                                    */
+    const float *b;       /* TL_TREELSTM: [5H];  TL_TREERNN / TL_RNTN: [d]                        */
+    const float *v;       /* TL_RNTN: [d x 2d x 2d], index order (k, p, q).    Else NULL.         */
+} tl_config;
+
+/* Creates a context on the current HIP device.  cfg is HOST memory; *out receives the
+ * context.  Synchronous (returns after the parameter copies are packed). */
+int tl_create(const tl_config *cfg, tl_ctx **out);
+
+/*
+ * Evaluates every node of a batch.  Asynchronous: all work is enqueued on hip_stream
+ * (a hipStream_t passed as void*, NULL = the default stream), except that
+ * TL_SCHED_LEVEL_HOST waits for the structure pass to learn the number of heights,
+ * and that the first call with a larger batch than any before (re)allocates the
+ * context's workspace, which synchronises the device.
+ *
+ *   n_trees >= 1, n_nodes >= n_trees                          HOST scalars
+ *   tree_off [n_trees+1]  int32, tree_off[0]=0, ascending,
+ *                         tree_off[n_trees]=n_nodes            DEVICE, read-only
+ *   left, right, word [n_nodes] int32                          DEVICE, read-only
+ *   h [n_nodes x H] fp32 out, row n = state of node n          DEVICE
+ *   c [n_nodes x H] fp32 out (TL_TREELSTM; ignored and may be
+ *                         NULL for the other cells)            DEVICE
+ *   h_root, c_root [n_trees x H] fp32 out, may be NULL         DEVICE
+ *   root [n_trees] int32 out: global index of each tree's root,
+ *                         may be NULL                          DEVICE
+ *
+ * Input arrays must stay valid and unmodified until the stream has passed the call.
+ * Host-detectable errors are returned at once.  Errors found on the device (TL_ESTRUCT,
+ * TL_ESTALL) are latched and reported by tl_status; after such an error no cell kernel
+ * reads through a bad index, and the output contents are unspecified.
+ */
+int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes,
+               const int32_t *tree_off, const int32_t *left, const int32_t *right,
+               const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+               int32_t *root, void *hip_stream);
+
+/* Waits for the stream of the last tl_forward and returns its latched device-side
+ * error (TL_OK if none). */
+int tl_status(tl_ctx *ctx);
+
+/* Stage timing.  tl_set_profiling(ctx, 1) makes every later tl_forward record HIP events
+ * between its stages on the caller's stream.  tl_last_stage_ms waits for the last
+ * forward and writes TL_N_STAGES durations in milliseconds to ms (HOST):
+ *   [0] structure pass (parents, counters, roots; heights and per-height lists if used)
+ *   [1] leaf cells   [2] internal cells incl. scheduling   [3] root gather   [4] total */
+enum { TL_N_STAGES = 5 };
+int tl_set_profiling(tl_ctx *ctx, int on);
+int tl_last_stage_ms(tl_ctx *ctx, float *ms);
+
+/* Facts about the last forward, for reports and tests (HOST out-parameters, any may be
+ * NULL): number of heights seen by a level scheduler (0 for TL_SCHED_READY), number of
+ * tiles of ready nodes formed by TL_SCHED_READY (0 otherwise), workgroups launched for the
+ * internal-node kernel.  Waits for the stream. */
+int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
+
+const char *tl_strerror(int code);
+
+/* Frees the context and everything it owns.  Waits for the device. */
+int tl_destroy(tl_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TREELSTM_H */

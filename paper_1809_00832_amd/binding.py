@@ -1,0 +1,184 @@
+"""ctypes binding of libtreelstm.so: same entry points as include/treelstm.h.
+
+Argument marshalling only - every step of the forward pass runs in the HIP library.
+PyTorch is used for device memory and for the stream handle.  There is no CPU
+fallback: if the library has not been built, loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtreelstm.so")
+
+TL_TREELSTM, TL_TREERNN, TL_RNTN = 0, 1, 2
+TL_F32, TL_BF16_IN = 0, 1
+TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST = 0, 1, 2
+TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4, -5
+TL_N_STAGES = 5
+SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
+
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_last_stage_ms", "tl_last_stats",
+           "tl_strerror", "tl_destroy")
+
+
+class tl_config(ctypes.Structure):
+    _fields_ = [("cell", ctypes.c_int), ("precision", ctypes.c_int), ("scheduler", ctypes.c_int),
+                ("validate", ctypes.c_int), ("vocab", ctypes.c_int), ("embed_dim", ctypes.c_int),
+                ("hidden", ctypes.c_int), ("spin_limit", ctypes.c_int),
+                ("emb", ctypes.c_void_p), ("w_leaf", ctypes.c_void_p), ("b_leaf", ctypes.c_void_p),
+                ("u", ctypes.c_void_p), ("b", ctypes.c_void_p), ("v", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_1809_00832_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libtreelstm.so is missing: build it with `python -m paper_1809_00832_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        L.tl_create.restype = ci
+        L.tl_create.argtypes = [ctypes.POINTER(tl_config), ctypes.POINTER(vp)]
+        L.tl_forward.restype = ci
+        L.tl_forward.argtypes = [vp, ci, ci] + [vp] * 10
+        L.tl_status.restype = ci
+        L.tl_status.argtypes = [vp]
+        L.tl_set_profiling.restype = ci
+        L.tl_set_profiling.argtypes = [vp, ci]
+        L.tl_last_stage_ms.restype = ci
+        L.tl_last_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.tl_last_stats.restype = ci
+        L.tl_last_stats.argtypes = [vp] + [ctypes.POINTER(ci)] * 3
+        L.tl_strerror.restype = ctypes.c_char_p
+        L.tl_strerror.argtypes = [ci]
+        L.tl_destroy.restype = ci
+        L.tl_destroy.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+class TLError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, lib().tl_strerror(code).decode(), code))
+
+
+def _check(code: int, where: str):
+    if code != TL_OK:
+        raise TLError(code, where)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def tl_create(cell, precision, scheduler, vocab, embed_dim, hidden, emb, w_leaf=None, b_leaf=None, u=None, b=None,
+              v=None, validate=0, spin_limit=0) -> int:
+    """Device tensors (fp32, contiguous) in, context handle out."""
+    for t in (emb, w_leaf, b_leaf, u, b, v):
+        if t is not None:
+            assert t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4
+    cfg = tl_config(cell, precision, scheduler, validate, vocab, embed_dim, hidden, spin_limit,
+                    _ptr(emb), _ptr(w_leaf), _ptr(b_leaf), _ptr(u), _ptr(b), _ptr(v))
+    out = ctypes.c_void_p()
+    _check(lib().tl_create(ctypes.byref(cfg), ctypes.byref(out)), "tl_create")
+    return out.value
+
+
+def tl_forward(ctx, n_trees, n_nodes, tree_off, left, right, word, h, c=None, h_root=None, c_root=None, root=None,
+               stream=None) -> None:
+    """int32 / fp32 device tensors in and out; `stream` is a raw hipStream_t (int) or None for torch's current one."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().tl_forward(ctx, n_trees, n_nodes, _ptr(tree_off), _ptr(left), _ptr(right), _ptr(word), _ptr(h),
+                            _ptr(c), _ptr(h_root), _ptr(c_root), _ptr(root), stream), "tl_forward")
+
+
+def tl_status(ctx) -> int:
+    return lib().tl_status(ctx)
+
+
+def tl_set_profiling(ctx, on: bool) -> None:
+    _check(lib().tl_set_profiling(ctx, int(on)), "tl_set_profiling")
+
+
+def tl_last_stage_ms(ctx):
+    ms = (ctypes.c_float * TL_N_STAGES)()
+    _check(lib().tl_last_stage_ms(ctx, ms), "tl_last_stage_ms")
+    return dict(zip(("structure", "leaves", "internal", "roots", "total"), [float(x) for x in ms]))
+
+
+def tl_last_stats(ctx):
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().tl_last_stats(ctx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "tl_last_stats")
+    return {"n_levels": a.value, "n_tiles": b.value, "n_workgroups": c.value}
+
+
+def tl_strerror(code: int) -> str:
+    return lib().tl_strerror(code).decode()
+
+
+def tl_destroy(ctx) -> None:
+    _check(lib().tl_destroy(ctx), "tl_destroy")
+
+
+class TreeNet:
+    """Holds a context plus device copies of a batch; thin convenience over the calls above."""
+
+    def __init__(self, params, scheduler="ready", precision=TL_F32, validate=0, spin_limit=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.device = torch.device(device)
+        dev = lambda a: None if a is None else torch.from_numpy(a).to(self.device).contiguous()
+        self.cell, self.H = params.cell, params.hidden
+        self.ctx = tl_create(params.cell, precision, SCHEDULERS[scheduler], params.vocab, params.embed_dim,
+                             params.hidden, dev(params.emb), dev(params.w_leaf), dev(params.b_leaf), dev(params.u),
+                             dev(params.b), dev(params.v), validate=validate, spin_limit=spin_limit)
+        self.batch = None
+
+    def load(self, trees):
+        """Copies a batch (numpy int32 arrays) to the device and allocates the outputs."""
+        torch = self.torch
+        dev = lambda a: torch.from_numpy(a).to(self.device).contiguous()
+        B, N, H = trees.n_trees, trees.n_nodes, self.H
+        out = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        self.batch = dict(B=B, N=N, tree_off=dev(trees.tree_off), left=dev(trees.left), right=dev(trees.right),
+                          word=dev(trees.word), h=out(N, H), c=out(N, H) if self.cell == TL_TREELSTM else None,
+                          h_root=out(B, H), c_root=out(B, H) if self.cell == TL_TREELSTM else None,
+                          root=torch.empty(B, dtype=torch.int32, device=self.device))
+        return self.batch
+
+    def forward(self, stream=None):
+        b = self.batch
+        tl_forward(self.ctx, b["B"], b["N"], b["tree_off"], b["left"], b["right"], b["word"], b["h"], b["c"],
+                   b["h_root"], b["c_root"], b["root"], stream)
+
+    def run(self, trees):
+        """load + forward + status check; returns host numpy copies of the outputs."""
+        self.load(trees)
+        self.forward()
+        code = tl_status(self.ctx)
+        if code != TL_OK:
+            raise TLError(code, "tl_forward (device)")
+        b = self.batch
+        host = lambda t: None if t is None else t.cpu().numpy()
+        return {k: host(b[k]) for k in ("h", "c", "h_root", "c_root", "root")}
+
+    def close(self):
+        if self.ctx:
+            tl_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

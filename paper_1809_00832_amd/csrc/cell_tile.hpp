@@ -1,0 +1,225 @@
+// The fused cell: gather -> LDS -> MFMA contraction -> gate epilogue -> h/c rows.
+//
+// One call evaluates up to TILE_ROWS nodes for one column group of HU hidden units:
+//   leaf tile      A row = embedding row of the leaf's word            (Figure 2, base case)
+//   internal tile  A row = [h(left child) ; h(right child)]            (Figure 2, recursive case)
+// G = A * W (+ bias) is accumulated in fp32 on 16x16 MFMA tiles; the packed weights put all
+// gates of a hidden unit into the same lane, so sigmoid/tanh, the c update and the h output
+// are computed on the accumulators and written straight to the node-major h/c arrays.
+#pragma once
+
+#include "common.hpp"
+
+namespace tl {
+
+enum Epi { EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2 };
+
+template <int EPI> struct EpiTraits;
+template <> struct EpiTraits<EPI_LSTM_LEAF>  { static constexpr int NG = 3, SEG = 1; };
+template <> struct EpiTraits<EPI_LSTM_INNER> { static constexpr int NG = 5, SEG = 2; };
+template <> struct EpiTraits<EPI_RNN_INNER>  { static constexpr int NG = 1, SEG = 2; };
+
+// LDS carve-up (dynamic shared memory, 16-byte aligned).
+struct TileSmem {
+    float a[2][TILE_ROWS * A_LD];                   // A chunks, double buffered
+    floatx4 b[2][(KC / STEP_K) * MAX_GATES * 64];    // B chunks, double buffered
+    int node[TILE_ROWS];                             // node index per row (-1: unused row)
+    int src0[TILE_ROWS];                             // first source row (word id / left child), -1: none
+    int src1[TILE_ROWS];                             // second source row (right child)
+    int cmd[8];                                      // scheduler broadcast slots
+};
+constexpr size_t TILE_SMEM_BYTES = sizeof(TileSmem);
+
+__device__ inline float sigmoid_f(float x) { return __frcp_rn(1.f + __expf(-x)); }
+__device__ inline float tanh_f(float x)
+{
+    // 1 - 2/(1+e^{2x}); the clamp keeps e^{2x} finite, beyond it tanh is 1 to fp32 precision
+    float t = __expf(2.f * fminf(fmaxf(x, -15.f), 15.f));
+    return 1.f - 2.f * __frcp_rn(1.f + t);
+}
+
+// Fills node/src0/src1 for `count` rows from a list of node indices.  Threads >= count mark
+// their row unused.  Caller synchronises afterwards.
+template <int EPI>
+__device__ inline void tile_set_rows(TileSmem &sm, const Fwd &f, int row, int node)
+{
+    if (row >= TILE_ROWS) return;
+    int s0 = -1, s1 = -1;
+    if (node >= 0) {
+        if (EPI == EPI_LSTM_LEAF) {
+            s0 = f.word[node];
+        } else {
+            s0 = f.left[node];
+            s1 = f.right[node];
+        }
+    }
+    sm.node[row] = node;
+    sm.src0[row] = s0;
+    sm.src1[row] = s1;
+}
+
+// Loads one 4-float granule of a gathered A row: K position k of the padded axis.
+template <int SEG, bool VEC4>
+__device__ inline floatx4 load_a_granule(const float *__restrict__ table, int L, int Lp, int s0, int s1, int k)
+{
+    floatx4 v = {0.f, 0.f, 0.f, 0.f};
+    int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
+    int off = k - seg * Lp;
+    int src = seg ? s1 : s0;
+    if (src < 0 || off >= L || (SEG == 1 && k >= Lp)) return v;
+    const float *p = table + (size_t)src * L + off;
+    if (VEC4) {
+        v = *reinterpret_cast<const floatx4 *>(p);
+    } else {
+        v.x = p[0];
+        if (off + 1 < L) v.y = p[1];
+        if (off + 2 < L) v.z = p[2];
+        if (off + 3 < L) v.w = p[3];
+    }
+    return v;
+}
+
+// The tile.  All WG_THREADS threads of the workgroup call it together; sm.node/src0/src1 hold
+// the rows (see tile_set_rows) and a __syncthreads() has been passed since they were written.
+//   table : source rows of the gather (embedding table, or h)
+//   count : rows in use (1..TILE_ROWS);  cg : column group
+template <int EPI, bool VEC4>
+__device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
+                                 int count, int cg)
+{
+    constexpr int NG = EpiTraits<EPI>::NG;
+    constexpr int SEG = EpiTraits<EPI>::SEG;
+    constexpr int STEPS = KC / STEP_K;          // 4 k-steps per chunk
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nrb = (count + 15) >> 4;          // 16-row blocks in use
+    // Waves: one row block each when there are 3-4; with fewer row blocks the K axis is split
+    // between waves instead (interleaved k-steps) and the partial sums meet in LDS.
+    const int KS = nrb == 1 ? 4 : (nrb == 2 ? 2 : 1);
+    const int rb = KS == 4 ? 0 : (KS == 2 ? (wave & 1) : wave);
+    const int ks = KS == 4 ? wave : (KS == 2 ? (wave >> 1) : 0);
+    const bool active = rb < nrb;
+    const int L = gm.L, Lp = gm.Lp;
+    const int n_steps = gm.n_chunks * STEPS;
+    const floatx4 *wp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * n_steps * NG * 64;
+
+    floatx4 acc[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // staging registers: A granules (rows tid/16 + 16 j, granule tid%16), B float4s
+    floatx4 ra[4], rbuf[NG];
+    const int a_row0 = tid >> 4, a_k4 = tid & 15;
+    int s0[4], s1[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int row = a_row0 + 16 * j;
+        s0[j] = row < nrb * 16 ? sm.src0[row] : -1;
+        s1[j] = row < nrb * 16 ? sm.src1[row] : -1;
+    }
+    auto load_chunk = [&](int chunk) {
+        const int k = chunk * KC + a_k4 * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4>(table, L, Lp, s0[j], s1[j], k);
+        const floatx4 *src = wp + (size_t)chunk * STEPS * NG * 64;
+#pragma unroll
+        for (int j = 0; j < NG; ++j) rbuf[j] = src[tid + WG_THREADS * j];
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nrb)
+                *reinterpret_cast<floatx4 *>(&sm.a[buf][(a_row0 + 16 * j) * A_LD + a_k4 * 4]) = ra[j];
+#pragma unroll
+        for (int j = 0; j < NG; ++j) sm.b[buf][tid + WG_THREADS * j] = rbuf[j];
+    };
+
+    load_chunk(0);
+    store_chunk(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < gm.n_chunks; ++chunk) {
+        const int buf = chunk & 1;
+        const bool more = chunk + 1 < gm.n_chunks;
+        if (more) load_chunk(chunk + 1);
+        if (active) {
+            const float *arow = &sm.a[buf][(rb * 16 + (lane & 15)) * A_LD + (lane >> 4) * 4];
+            for (int s = ks; s < STEPS; s += KS) {
+                const floatx4 av = *reinterpret_cast<const floatx4 *>(arow + s * STEP_K);
+                floatx4 bv[NG];
+#pragma unroll
+                for (int g = 0; g < NG; ++g) bv[g] = sm.b[buf][(s * NG + g) * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int g = 0; g < NG; ++g)
+                        acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[g][i], acc[g], 0, 0, 0);
+            }
+        }
+        if (more) store_chunk(buf ^ 1);
+        __syncthreads();
+    }
+
+    // K-split: partial accumulators of the waves with ks > 0 go through LDS (re-using the A
+    // buffers, which nobody reads any more) to the wave with ks == 0 of the same row block.
+    if (KS > 1) {
+        float *red = &sm.a[0][0];               // [wave][g*4+v][lane], 4*20*64 floats <= sizeof a
+        if (active && ks > 0) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(wave * NG * 4 + g * 4 + v) * 64 + lane] = acc[g][v];
+        }
+        __syncthreads();
+        if (active && ks == 0) {
+            for (int other = 1; other < KS; ++other) {
+                const int w2 = KS == 4 ? other : wave + 2;
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[g][v] += red[(w2 * NG * 4 + g * 4 + v) * 64 + lane];
+            }
+        }
+    }
+
+    // Epilogue on the accumulators: lane holds hidden unit cg*16 + lane%16 of rows 4*(lane/16)+v.
+    if (active && ks == 0) {
+        const int hu = cg * HU + (lane & 15);
+        const int H = f.H;
+        if (hu < H) {
+            float bias[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = rb * 16 + (lane >> 4) * 4 + v;
+                if (row >= count) continue;
+                const int node = sm.node[row];
+                const size_t o = (size_t)node * H + hu;
+                if (EPI == EPI_LSTM_LEAF) {
+                    const float i = sigmoid_f(acc[0][v] + bias[0]);
+                    const float og = sigmoid_f(acc[1][v] + bias[1]);
+                    const float u = tanh_f(acc[2][v] + bias[2]);
+                    const float cc = i * u;
+                    f.c[o] = cc;
+                    f.h[o] = og * tanh_f(cc);
+                } else if (EPI == EPI_LSTM_INNER) {
+                    const float cl = f.c[(size_t)sm.src0[row] * H + hu];
+                    const float cr = f.c[(size_t)sm.src1[row] * H + hu];
+                    const float i = sigmoid_f(acc[0][v] + bias[0]);
+                    const float fl = sigmoid_f(acc[1][v] + bias[1]);
+                    const float fr = sigmoid_f(acc[2][v] + bias[2]);
+                    const float og = sigmoid_f(acc[3][v] + bias[3]);
+                    const float u = tanh_f(acc[4][v] + bias[4]);
+                    const float cc = i * u + fl * cl + fr * cr;
+                    f.c[o] = cc;
+                    f.h[o] = og * tanh_f(cc);
+                } else {
+                    f.h[o] = tanh_f(acc[0][v] + bias[0]);
+                }
+            }
+        }
+    }
+    __syncthreads();   // the row tables and the LDS buffers may be rewritten after this call
+}
+
+}  // namespace tl

@@ -1,0 +1,188 @@
+// Structure pass: integer-only kernels that turn the child arrays of a batch into what the
+// schedulers need.  This is the device counterpart of the master that sorts operations into a
+// ready queue or a waiting list by their number of unresolved inputs (Section 4.1, Figure 4
+// step 2) and of the parent pointers that stand in for a call stack ("Graph execution stack").
+#pragma once
+
+#include "common.hpp"
+
+namespace tl {
+
+// Largest t with tree_off[t] <= n, by bisection over [0, n_trees).  Always returns an index in
+// range, whatever the array holds.
+__device__ inline int tree_of(const int32_t *tree_off, int n_trees, int n)
+{
+    int lo = 0, hi = n_trees - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (tree_off[mid] <= n) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Resets the per-forward scheduler state.  A fill kernel rather than memsets so that a caller
+// may capture the forward in a HIP graph.
+__global__ void k_reset(Fwd f, int with_levels)
+{
+    const int N = f.n_nodes;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t total = (size_t)N + 1 > 64 ? (size_t)N + 1 : 64;   // also covers the control block
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        if (i < (size_t)N) {
+            f.parent[i] = -1;
+            f.pending[i] = 0;
+            if (with_levels) { f.height[i] = 0; f.arrive[i] = 0; f.level_fill[i] = 0; }
+        }
+        if (with_levels && i <= (size_t)N) f.level_cnt[i] = 0;
+        if (i < (size_t)f.n_int) { f.q_nodes[i] = 0; f.tile_desc[i] = 0; f.tile_done[i] = 0; }
+        if (i < (size_t)f.n_trees) f.root_ws[i] = -1;
+        if (i < sizeof(Ctl) / 4) ((unsigned int *)f.ctl)[i] = 0;
+    }
+}
+
+// One thread per node: checks, parent scatter, leaf list, counters of unfinished children.
+// Leaves are evaluated by a kernel of their own before any internal node, so pending[] counts
+// internal children only, and an internal node whose children are both leaves starts ready.
+__global__ void k_scatter(Fwd f)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    Ctl *ctl = f.ctl;
+    if (n <= f.n_trees) {   // offsets: 0 = off[0] < off[1] < ... < off[B] = N
+        int v = f.tree_off[n];
+        bool ok = (n == 0) ? (v == 0) : (v > f.tree_off[n - 1]);
+        if (n == f.n_trees) ok = ok && (v == f.n_nodes);
+        if (!ok) latch_error(ctl, TL_ESTRUCT);
+    }
+    if (n >= f.n_nodes) return;
+    const int t = tree_of(f.tree_off, f.n_trees, n);
+    const int lo = f.tree_off[t], hi = f.tree_off[t + 1];
+    if (n < lo || n >= hi) { latch_error(ctl, TL_ESTRUCT); return; }
+    const int l = f.left[n], r = f.right[n];
+    if (l < 0 && r < 0) {
+        const int w = f.word[n];
+        if (w < 0 || w >= f.vocab) { latch_error(ctl, TL_ESTRUCT); return; }
+        const int slot = atomicAdd(&ctl->n_leaf_seen, 1);
+        if (slot < f.n_leaf) f.leaf_list[slot] = n;
+        return;
+    }
+    const bool ok = l >= lo && l < hi && r >= lo && r < hi && l < f.n_nodes && r < f.n_nodes && l != r && l != n &&
+                    r != n && l >= 0 && r >= 0;
+    if (!ok) { latch_error(ctl, TL_ESTRUCT); return; }
+    if (atomicCAS(&f.parent[l], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
+    if (atomicCAS(&f.parent[r], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
+    const int pend = (f.left[l] >= 0) + (f.left[r] >= 0);
+    f.pending[n] = pend;
+    if (pend == 0) {
+        const unsigned slot = atomicAdd(&ctl->q_tail, 1u);
+        if (slot < (unsigned)f.n_int) f.q_nodes[slot] = (unsigned)n + 1u;
+    }
+}
+
+// One thread per node: the node nobody points to is its tree's root; there must be exactly one.
+__global__ void k_roots(Fwd f)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    Ctl *ctl = f.ctl;
+    if (n == 0 && ctl->n_leaf_seen != f.n_leaf) latch_error(ctl, TL_ESTRUCT);
+    if (n >= f.n_nodes || f.parent[n] != -1) return;
+    const int t = tree_of(f.tree_off, f.n_trees, n);
+    if (atomicCAS(&f.root_ws[t], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
+}
+
+__global__ void k_check_roots(Fwd f)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < f.n_trees && f.root_ws[t] < 0) latch_error(f.ctl, TL_ESTRUCT);
+}
+
+// Heights by climbing: one thread per leaf walks towards the root; at every internal node the
+// first child to arrive stops, the second continues with height 1 + max.  Also histograms the
+// heights.  The walk visits each node once, so a thread's loop is bounded by the tree height.
+__global__ void k_climb(Fwd f)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    Ctl *ctl = f.ctl;
+    if (ctl->status != 0 || i >= f.n_leaf) return;
+    int n = f.leaf_list[i];
+    int hcur = 0;
+    atomicAdd(&f.level_cnt[0], 1);
+    for (int guard = 0; guard < f.n_nodes; ++guard) {
+        const int p = f.parent[n];
+        if (p < 0) break;
+        atomicMax(&f.height[p], hcur + 1);
+        __threadfence();
+        if (atomicAdd(&f.arrive[p], 1) == 0) break;
+        __threadfence();
+        hcur = ld_relaxed(&f.height[p]);
+        atomicAdd(&f.level_cnt[hcur], 1);
+        atomicMax(&ctl->max_height, hcur);
+        n = p;
+    }
+}
+
+// Single workgroup: exclusive scan of the height histogram into level offsets.
+__global__ void k_scan_levels(Fwd f)
+{
+    __shared__ int s_part[1024];
+    __shared__ int s_carry;
+    Ctl *ctl = f.ctl;
+    const int tid = threadIdx.x;
+    if (ctl->status != 0) {
+        if (tid == 0) ctl->n_levels = 0;
+        return;
+    }
+    const int n_levels = ctl->max_height + 1;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n_levels; base += 1024) {
+        const int idx = base + tid;
+        const int v = idx < n_levels ? f.level_cnt[idx] : 0;
+        s_part[tid] = v;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            int add = tid >= d ? s_part[tid - d] : 0;
+            __syncthreads();
+            s_part[tid] += add;
+            __syncthreads();
+        }
+        const int carry = s_carry;
+        if (idx < n_levels) f.level_off[idx] = carry + s_part[tid] - v;
+        __syncthreads();
+        if (tid == 1023) s_carry = carry + s_part[1023];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        f.level_off[n_levels] = s_carry;
+        ctl->n_levels = n_levels;
+        ctl->reached = s_carry;
+        if (s_carry != f.n_nodes) latch_error(ctl, TL_ESTRUCT);   // nodes no leaf leads to (cycle)
+    }
+}
+
+// One thread per node: append the node to the list of its height.
+__global__ void k_fill_levels(Fwd f)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f.ctl->status != 0 || n >= f.n_nodes) return;
+    const bool leaf = f.left[n] < 0;
+    if (!leaf && f.arrive[n] != 2) return;
+    const int hgt = leaf ? 0 : f.height[n];
+    const int slot = f.level_off[hgt] + atomicAdd(&f.level_fill[hgt], 1);
+    if (slot < f.n_nodes) f.level_nodes[slot] = n;
+}
+
+// h_root / c_root / root outputs.
+__global__ void k_root_gather(Fwd f)
+{
+    if (f.ctl->status != 0) return;
+    const int t = blockIdx.x;
+    const int r = f.root_ws[t];
+    if (r < 0) return;
+    if (threadIdx.x == 0 && f.root_out) f.root_out[t] = r;
+    for (int j = threadIdx.x; j < f.H; j += blockDim.x) {
+        if (f.h_root) f.h_root[(size_t)t * f.H + j] = f.h[(size_t)r * f.H + j];
+        if (f.c_root && f.c) f.c_root[(size_t)t * f.H + j] = f.c[(size_t)r * f.H + j];
+    }
+}
+
+}  // namespace tl

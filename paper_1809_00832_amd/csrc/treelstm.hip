@@ -1,0 +1,443 @@
+// C ABI of the tree-network forward library (see include/treelstm.h).
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "treelstm.h"
+#include "common.hpp"
+#include "pack.hpp"
+#include "structure.hpp"
+#include "cell_tile.hpp"
+#include "schedulers.hpp"
+
+using namespace tl;
+
+namespace {
+
+constexpr int DEFAULT_SPIN_LIMIT = 1 << 20;
+
+struct DevBuf {
+    void *p = nullptr;
+    size_t bytes = 0;
+};
+
+}  // namespace
+
+struct tl_ctx {
+    tl_config cfg{};
+    int device = 0;
+    int n_cu = 0;
+    int n_cg = 0;
+    // packed parameters
+    float *emb = nullptr;
+    void *wp_leaf = nullptr, *wp_inner = nullptr;
+    float *bp_leaf = nullptr, *bp_inner = nullptr;
+    Gemm g_leaf{}, g_inner{};
+    // workspace
+    unsigned char *ws = nullptr;
+    size_t ws_bytes = 0;
+    int cap_nodes = 0, cap_trees = 0;
+    int32_t *host_levels = nullptr;   // pinned, cap_nodes + 2
+    Ctl *host_ctl = nullptr;          // pinned
+    Fwd last{};                       // pointers of the last forward (workspace part is reused)
+    hipStream_t last_stream = nullptr;
+    bool ran = false;
+    int persistent_grid = 0;          // workgroups of the persistent kernels
+    int last_grid = 0;
+    int last_levels = 0;
+    // profiling
+    int profiling = 0;
+    hipEvent_t ev[TL_N_STAGES + 1]{};
+    bool ev_valid = false;
+};
+
+namespace {
+
+#define TL_HIP(call)                                   \
+    do {                                               \
+        hipError_t e_ = (call);                        \
+        if (e_ != hipSuccess) return hip_fail(e_);     \
+    } while (0)
+
+int hip_fail(hipError_t e)
+{
+    if (getenv("TL_DEBUG")) fprintf(stderr, "treelstm: HIP error: %s\n", hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? TL_ENOMEM : TL_EHIP;
+}
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+typedef void (*fwd_kernel)(Fwd);
+typedef void (*tiles_kernel)(Fwd, const int32_t *, int, int);
+
+fwd_kernel ready_kernel(int cell, bool vec4)
+{
+    if (cell == TL_TREELSTM) return vec4 ? k_ready_persistent<EPI_LSTM_INNER, true> : k_ready_persistent<EPI_LSTM_INNER, false>;
+    return vec4 ? k_ready_persistent<EPI_RNN_INNER, true> : k_ready_persistent<EPI_RNN_INNER, false>;
+}
+fwd_kernel levels_kernel(int cell, bool vec4)
+{
+    if (cell == TL_TREELSTM) return vec4 ? k_levels_persistent<EPI_LSTM_INNER, true> : k_levels_persistent<EPI_LSTM_INNER, false>;
+    return vec4 ? k_levels_persistent<EPI_RNN_INNER, true> : k_levels_persistent<EPI_RNN_INNER, false>;
+}
+tiles_kernel static_kernel(int epi, bool vec4)
+{
+    switch (epi) {
+    case EPI_LSTM_LEAF: return vec4 ? k_tiles_static<EPI_LSTM_LEAF, true> : k_tiles_static<EPI_LSTM_LEAF, false>;
+    case EPI_LSTM_INNER: return vec4 ? k_tiles_static<EPI_LSTM_INNER, true> : k_tiles_static<EPI_LSTM_INNER, false>;
+    default: return vec4 ? k_tiles_static<EPI_RNN_INNER, true> : k_tiles_static<EPI_RNN_INNER, false>;
+    }
+}
+
+template <typename K> int allow_lds(K kernel)
+{
+    TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)TILE_SMEM_BYTES));
+    return TL_OK;
+}
+
+// Packs one weight matrix [SEG*L x NG*H] and its bias; fills the Gemm descriptor.
+int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, Gemm *g, void **wp_out,
+              float **bp_out)
+{
+    const int Lp = round_up(L, 4);
+    const int Kp = round_up(SEG * Lp, KC);
+    const int n_steps = Kp / STEP_K;
+    const size_t n_w = (size_t)n_cg * n_steps * NG * 64 * 4;
+    float *wp = nullptr, *bp = nullptr;
+    TL_HIP(hipMalloc(&wp, n_w * sizeof(float)));
+    TL_HIP(hipMalloc(&bp, (size_t)n_cg * NG * HU * sizeof(float)));
+    hipLaunchKernelGGL(k_pack_f32, dim3(1024), dim3(256), 0, 0, w, wp, NG, H, SEG, L, Lp, n_steps, n_cg);
+    hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, 0, b, bp, NG, H, n_cg);
+    TL_HIP(hipGetLastError());
+    g->wp = wp;
+    g->bp = bp;
+    g->L = L;
+    g->Lp = Lp;
+    g->n_chunks = Kp / KC;
+    *wp_out = wp;
+    *bp_out = bp;
+    return TL_OK;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Workspace for batches of up to n_nodes nodes / n_trees trees.
+int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
+{
+    if (n_nodes <= ctx->cap_nodes && n_trees <= ctx->cap_trees) return TL_OK;
+    TL_HIP(hipDeviceSynchronize());
+    const int N = n_nodes > ctx->cap_nodes ? n_nodes : ctx->cap_nodes;
+    const int B = n_trees > ctx->cap_trees ? n_trees : ctx->cap_trees;
+    if (ctx->ws) { TL_HIP(hipFree(ctx->ws)); ctx->ws = nullptr; }
+    if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
+    ctx->cap_nodes = ctx->cap_trees = 0;
+    const size_t n4 = align256((size_t)(N + 2) * 4);
+    const size_t bytes = n4 * 11 + align256((size_t)N * 8) + align256((size_t)B * 4) + align256(sizeof(Ctl));
+    TL_HIP(hipMalloc(&ctx->ws, bytes));
+    TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
+    ctx->ws_bytes = bytes;
+    ctx->cap_nodes = N;
+    ctx->cap_trees = B;
+    return TL_OK;
+}
+
+void carve_workspace(const tl_ctx *ctx, Fwd *f)
+{
+    const size_t n4 = align256((size_t)(ctx->cap_nodes + 2) * 4);
+    unsigned char *p = ctx->ws;
+    auto take = [&](size_t b) { unsigned char *r = p; p += b; return r; };
+    f->parent = (int32_t *)take(n4);
+    f->pending = (int32_t *)take(n4);
+    f->leaf_list = (int32_t *)take(n4);
+    f->height = (int32_t *)take(n4);
+    f->arrive = (int32_t *)take(n4);
+    f->level_cnt = (int32_t *)take(n4);
+    f->level_off = (int32_t *)take(n4);
+    f->level_fill = (int32_t *)take(n4);
+    f->level_nodes = (int32_t *)take(n4);
+    f->q_nodes = (unsigned int *)take(n4);
+    f->tile_done = (unsigned int *)take(n4);
+    f->tile_desc = (unsigned long long *)take(align256((size_t)ctx->cap_nodes * 8));
+    f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
+    f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
+}
+
+void free_all(tl_ctx *ctx)
+{
+    (void)hipFree(ctx->emb);
+    (void)hipFree(ctx->wp_leaf);
+    (void)hipFree(ctx->wp_inner);
+    (void)hipFree(ctx->bp_leaf);
+    (void)hipFree(ctx->bp_inner);
+    (void)hipFree(ctx->ws);
+    if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
+    if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
+    for (auto &e : ctx->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+int create_impl(const tl_config *cfg, tl_ctx *ctx)
+{
+    ctx->cfg = *cfg;
+    TL_HIP(hipGetDevice(&ctx->device));
+    hipDeviceProp_t prop;
+    TL_HIP(hipGetDeviceProperties(&prop, ctx->device));
+    ctx->n_cu = prop.multiProcessorCount;
+    const int H = cfg->hidden, E = cfg->embed_dim;
+    ctx->n_cg = (H + HU - 1) / HU;
+
+    const size_t emb_bytes = (size_t)cfg->vocab * E * sizeof(float);
+    TL_HIP(hipMalloc(&ctx->emb, emb_bytes));
+    TL_HIP(hipMemcpy(ctx->emb, cfg->emb, emb_bytes, hipMemcpyDeviceToDevice));
+
+    int rc;
+    if (cfg->cell == TL_TREELSTM) {
+        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+        if (rc != TL_OK) return rc;
+        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        if (rc != TL_OK) return rc;
+    } else {
+        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        if (rc != TL_OK) return rc;
+    }
+    TL_HIP(hipDeviceSynchronize());
+
+    // every kernel instantiation that stages tiles needs more than the default LDS limit
+    for (int v = 0; v < 2; ++v) {
+        for (int cell = 0; cell < 2; ++cell) {
+            if ((rc = allow_lds(ready_kernel(cell, v))) != TL_OK) return rc;
+            if ((rc = allow_lds(levels_kernel(cell, v))) != TL_OK) return rc;
+        }
+        for (int epi = 0; epi < 3; ++epi)
+            if ((rc = allow_lds(static_kernel(epi, v))) != TL_OK) return rc;
+    }
+    int occ = 0;
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true)),
+                                                        WG_THREADS, TILE_SMEM_BYTES));
+    int occ2 = 0;
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, false)),
+                                                        WG_THREADS, TILE_SMEM_BYTES));
+    if (occ2 < occ) occ = occ2;
+    if (occ < 1) return TL_EHIP;
+    if (occ > 2) occ = 2;
+    ctx->persistent_grid = occ * ctx->n_cu;
+
+    TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
+    for (auto &e : ctx->ev) TL_HIP(hipEventCreate(&e));
+    return TL_OK;
+}
+
+int read_ctl(tl_ctx *ctx)
+{
+    TL_HIP(hipMemcpyAsync(ctx->host_ctl, ctx->last.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, ctx->last_stream));
+    TL_HIP(hipStreamSynchronize(ctx->last_stream));
+    return TL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tl_create(const tl_config *cfg, tl_ctx **out)
+{
+    if (!cfg || !out) return TL_EINVAL;
+    *out = nullptr;
+    if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN) return TL_EINVAL;   // TL_RNTN: not available yet
+    if (cfg->precision != TL_F32) return TL_EINVAL;                               // TL_BF16_IN: not available yet
+    if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_LEVEL_HOST) return TL_EINVAL;
+    if (cfg->vocab < 1 || cfg->embed_dim < 1 || cfg->hidden < 1 || cfg->spin_limit < 0) return TL_EINVAL;
+    if (cfg->hidden > (1 << 14) || cfg->embed_dim > (1 << 16)) return TL_EINVAL;
+    if (!cfg->emb || !cfg->u || !cfg->b) return TL_EINVAL;
+    if (cfg->cell == TL_TREELSTM && (!cfg->w_leaf || !cfg->b_leaf)) return TL_EINVAL;
+    if (cfg->cell != TL_TREELSTM && cfg->embed_dim != cfg->hidden) return TL_EINVAL;
+    tl_ctx *ctx = new (std::nothrow) tl_ctx();
+    if (!ctx) return TL_ENOMEM;
+    int rc = create_impl(cfg, ctx);
+    if (rc != TL_OK) {
+        free_all(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return TL_OK;
+}
+
+int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+               const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+               int32_t *root, void *hip_stream)
+{
+    if (!ctx || !tree_off || !left || !right || !word || !h) return TL_EINVAL;
+    if (n_trees < 1 || n_nodes < n_trees) return TL_EINVAL;
+    const tl_config &cfg = ctx->cfg;
+    if (cfg.cell == TL_TREELSTM && !c) return TL_EINVAL;
+    if (((long long)n_nodes + n_trees) % 2 != 0) return TL_ESTRUCT;   // full binary trees: N = 2 leaves - trees
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = ensure_workspace(ctx, n_nodes, n_trees);
+    if (rc != TL_OK) return rc;
+
+    Fwd f{};
+    f.n_trees = n_trees;
+    f.n_nodes = n_nodes;
+    f.n_leaf = (int)(((long long)n_nodes + n_trees) / 2);
+    f.n_int = n_nodes - f.n_leaf;
+    f.tree_off = tree_off; f.left = left; f.right = right; f.word = word;
+    f.h = h; f.c = cfg.cell == TL_TREELSTM ? c : nullptr;
+    f.h_root = h_root; f.c_root = c_root; f.root_out = root;
+    f.cell = cfg.cell; f.H = cfg.hidden; f.E = cfg.embed_dim; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg; f.bf16 = 0;
+    f.emb = ctx->emb;
+    f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
+    carve_workspace(ctx, &f);
+    f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
+    const int grid_p = ctx->persistent_grid;
+    f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
+
+    const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
+    const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
+    const bool vec4_leaf = cfg.embed_dim % 4 == 0;
+    const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : EPI_RNN_INNER;
+    const bool prof = ctx->profiling != 0;
+    const int nb_nodes = (n_nodes + 1 + 255) / 256;
+
+    ctx->last = f;
+    ctx->last_stream = st;
+    ctx->ran = true;
+    ctx->last_grid = 0;
+    ctx->last_levels = 0;
+    ctx->ev_valid = false;
+
+    if (prof) TL_HIP(hipEventRecord(ctx->ev[0], st));
+    // ---- structure pass ----------------------------------------------------------------
+    hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
+    hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_check_roots, dim3((n_trees + 255) / 256), dim3(256), 0, st, f);
+    if (need_levels) {
+        hipLaunchKernelGGL(k_climb, dim3((f.n_leaf + 255) / 256), dim3(256), 0, st, f);
+        hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
+        hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
+    }
+    TL_HIP(hipGetLastError());
+    if (prof) TL_HIP(hipEventRecord(ctx->ev[1], st));
+
+    // ---- leaves ------------------------------------------------------------------------
+    if (cfg.cell == TL_TREELSTM) {
+        const int tiles = (f.n_leaf + TILE_ROWS - 1) / TILE_ROWS;
+        hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf), dim3(tiles * ctx->n_cg), dim3(WG_THREADS),
+                           TILE_SMEM_BYTES, st, f, (const int32_t *)f.leaf_list, f.n_leaf, TILE_ROWS);
+    } else {
+        hipLaunchKernelGGL(k_leaf_copy, dim3(f.n_leaf), dim3(128), 0, st, f);
+    }
+    TL_HIP(hipGetLastError());
+    if (prof) TL_HIP(hipEventRecord(ctx->ev[2], st));
+
+    // ---- internal nodes ------------------------------------------------------------------
+    if (f.n_int > 0) {
+        if (cfg.scheduler == TL_SCHED_READY) {
+            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner), dim3(grid_p), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            ctx->last_grid = grid_p;
+        } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
+            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner), dim3(grid_p), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            ctx->last_grid = grid_p;
+        } else {
+            // the host needs the number of heights and the offsets of their node lists
+            if ((rc = read_ctl(ctx)) != TL_OK) return rc;
+            const int n_levels = ctx->host_ctl->status == 0 ? ctx->host_ctl->n_levels : 0;
+            if (n_levels > 1) {
+                TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
+                TL_HIP(hipStreamSynchronize(st));
+                int max_grid = 0;
+                for (int lvl = 1; lvl < n_levels; ++lvl) {
+                    const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
+                    if (rows <= 0 || lo < 0 || lo + rows > n_nodes) return TL_EHIP;
+                    const int m = tile_rows_for((unsigned)rows, (unsigned)f.cap_tiles);
+                    const int tiles = (rows + m - 1) / m;
+                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner), dim3(tiles * ctx->n_cg), dim3(WG_THREADS),
+                                       TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, m);
+                    if (tiles * ctx->n_cg > max_grid) max_grid = tiles * ctx->n_cg;
+                }
+                ctx->last_grid = max_grid;
+            }
+            ctx->last_levels = n_levels;
+        }
+        TL_HIP(hipGetLastError());
+    }
+    if (prof) TL_HIP(hipEventRecord(ctx->ev[3], st));
+
+    // ---- roots ---------------------------------------------------------------------------
+    hipLaunchKernelGGL(k_root_gather, dim3(n_trees), dim3(128), 0, st, f);
+    TL_HIP(hipGetLastError());
+    if (prof) {
+        TL_HIP(hipEventRecord(ctx->ev[4], st));
+        ctx->ev_valid = true;
+    }
+    return TL_OK;
+}
+
+int tl_status(tl_ctx *ctx)
+{
+    if (!ctx) return TL_EINVAL;
+    if (!ctx->ran) return TL_OK;
+    int rc = read_ctl(ctx);
+    if (rc != TL_OK) return rc;
+    return ctx->host_ctl->status;
+}
+
+int tl_set_profiling(tl_ctx *ctx, int on)
+{
+    if (!ctx) return TL_EINVAL;
+    ctx->profiling = on != 0;
+    ctx->ev_valid = false;
+    return TL_OK;
+}
+
+int tl_last_stage_ms(tl_ctx *ctx, float *ms)
+{
+    if (!ctx || !ms) return TL_EINVAL;
+    if (!ctx->ev_valid) return TL_EINVAL;
+    TL_HIP(hipEventSynchronize(ctx->ev[4]));
+    for (int i = 0; i < 4; ++i) TL_HIP(hipEventElapsedTime(&ms[i], ctx->ev[i], ctx->ev[i + 1]));
+    TL_HIP(hipEventElapsedTime(&ms[4], ctx->ev[0], ctx->ev[4]));
+    return TL_OK;
+}
+
+int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups)
+{
+    if (!ctx) return TL_EINVAL;
+    if (n_levels) *n_levels = 0;
+    if (n_tiles) *n_tiles = 0;
+    if (n_workgroups) *n_workgroups = 0;
+    if (!ctx->ran) return TL_OK;
+    int rc = read_ctl(ctx);
+    if (rc != TL_OK) return rc;
+    if (n_levels) *n_levels = ctx->host_ctl->n_levels;
+    if (n_tiles) *n_tiles = (int)(ctx->host_ctl->formed >> 32);
+    if (n_workgroups) *n_workgroups = ctx->last_grid;
+    return TL_OK;
+}
+
+const char *tl_strerror(int code)
+{
+    switch (code) {
+    case TL_OK: return "ok";
+    case TL_EINVAL: return "invalid argument";
+    case TL_ENOMEM: return "out of memory";
+    case TL_EHIP: return "HIP runtime error";
+    case TL_ESTRUCT: return "malformed tree batch";
+    case TL_ESTALL: return "scheduler made no progress (unreachable nodes)";
+    default: return "unknown error";
+    }
+}
+
+int tl_destroy(tl_ctx *ctx)
+{
+    if (!ctx) return TL_EINVAL;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    return TL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,155 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU checker, element by element.
+
+Tolerance (fp32 path): |gpu - ref| <= 1e-4 + 1e-3 |ref| per element; child / root indices bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1809_00832_amd import binding, synth
+from paper_1809_00832_amd.synth import CELL_TREELSTM
+
+pytestmark = pytest.mark.gpu
+
+SCHEDULERS = ["level_host", "level_device", "ready"]
+ATOL, RTOL = 1e-4, 1e-3
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def assert_close(got, ref, what):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = ATOL + RTOL * np.abs(ref.astype(np.float64))
+    worst = int(np.argmax(err - bound))
+    assert (err <= bound).all(), "%s: max abs err %.3e at flat index %d (ref %.6g, got %.6g)" % (
+        what, err.max(), worst, ref.flat[worst], got.flat[worst])
+    return float(err.max())
+
+
+def check_against_oracle(params, trees, got, ref=None, what=""):
+    if ref is None:
+        ref = oracle.forward_params(params, trees, n_threads=8)
+    e1 = assert_close(got["h"], ref["h"], what + " h")
+    assert_close(got["h_root"], ref["h_root"], what + " h_root")
+    if params.cell == CELL_TREELSTM:
+        assert_close(got["c"], ref["c"], what + " c")
+        assert_close(got["c_root"], ref["c_root"], what + " c_root")
+    _, root, _ = oracle.structure(trees.tree_off, trees.left, trees.right)
+    assert np.array_equal(got["root"], root), what + " root indices"
+    assert np.array_equal(got["h_root"], got["h"][root]), what + " h_root is a copy of the root rows"
+    return e1
+
+
+_ref_cache = {}
+
+
+def reference(name):
+    if name not in _ref_cache:
+        w = synth.workload(name)
+        _ref_cache[name] = (w, oracle.forward_params(w.params, w.trees, n_threads=8))
+    return _ref_cache[name]
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+@pytest.mark.parametrize("name", ["tiny", "sentence", "treernn", "throughput"])
+def test_workload_matches_oracle(name, sched):
+    say("case", name, sched)
+    w, ref = reference(name)
+    net = binding.TreeNet(w.params, scheduler=sched)
+    try:
+        got = net.run(w.trees)
+        err = check_against_oracle(w.params, w.trees, got, ref, "%s/%s" % (name, sched))
+        say("   max abs err h %.3e" % err, binding.tl_last_stats(net.ctx))
+    finally:
+        net.close()
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+def test_stress_shapes_sampled_trees(sched):
+    """Full 64-tree batch of 1024-leaf chains and balanced trees on the GPU; the checker evaluates four of
+    the trees on their own (a tree's values do not depend on the rest of the batch)."""
+    say("case stress", sched)
+    w = synth.workload("stress")
+    net = binding.TreeNet(w.params, scheduler=sched)
+    try:
+        got = net.run(w.trees)
+        pick = [0, 1, 62, 63]
+        sub, orig = synth.subset(w.trees, pick)
+        ref = oracle.forward_params(w.params, sub, n_threads=4)
+        assert_close(got["h"][orig], ref["h"], "stress h")
+        assert_close(got["c"][orig], ref["c"], "stress c")
+        assert_close(got["h_root"][pick], ref["h_root"], "stress h_root")
+        _, root, height = oracle.structure(w.trees.tree_off, w.trees.left, w.trees.right)
+        assert np.array_equal(got["root"], root)
+        assert np.isfinite(got["h"]).all() and np.isfinite(got["c"]).all()
+        stats = binding.tl_last_stats(net.ctx)
+        say("   ", stats)
+        if sched != "ready":
+            assert stats["n_levels"] == 1024
+    finally:
+        net.close()
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+@pytest.mark.parametrize("mode", ["post", "random"])
+def test_node_numbering_is_immaterial(mode, sched):
+    say("case numbering", mode, sched)
+    w, ref = reference("sentence")
+    tb, new_of_old = synth.renumber(w.trees, mode, seed=5)
+    net = binding.TreeNet(w.params, scheduler=sched)
+    try:
+        got = net.run(tb)
+        assert_close(got["h"][new_of_old], ref["h"], "h")
+        assert_close(got["c"][new_of_old], ref["c"], "c")
+        _, root, _ = oracle.structure(tb.tree_off, tb.left, tb.right)
+        assert np.array_equal(got["root"], root)
+    finally:
+        net.close()
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+def test_ragged_and_degenerate_batches(sched):
+    """Single-node trees, a batch of one tree, two-leaf trees, tiles with a ragged tail, H not a multiple
+    of 16 or 4, E not a multiple of 4."""
+    say("case ragged", sched)
+    cases = [
+        (dict(vocab=50, E=7, H=5), [1]),
+        (dict(vocab=50, E=7, H=5), [1, 1, 1]),
+        (dict(vocab=50, E=12, H=20), [2]),
+        (dict(vocab=50, E=9, H=33), [1, 2, 3, 1, 70, 5]),
+        (dict(vocab=50, E=64, H=64), [17] * 9 + [1] + [130]),
+    ]
+    for i, (dims, leaves) in enumerate(cases):
+        params = synth.make_treelstm_params(40 + i, dims["vocab"], dims["E"], dims["H"], "xavier")
+        trees = synth.make_trees(40 + i, leaves, ["random"] * len(leaves), dims["vocab"])
+        net = binding.TreeNet(params, scheduler=sched)
+        try:
+            got = net.run(trees)
+            check_against_oracle(params, trees, got, None, "ragged%d/%s" % (i, sched))
+            # second, smaller batch through the same context (workspace and queue are reused)
+            small = synth.make_trees(90 + i, leaves[:1], ["random"], dims["vocab"])
+            got = net.run(small)
+            check_against_oracle(params, small, got, None, "ragged%d-again/%s" % (i, sched))
+        finally:
+            net.close()
+
+
+def test_repeated_forward_is_stable():
+    """The same batch evaluated repeatedly by the ready-queue scheduler stays within tolerance of the
+    checker every time (tile composition differs from run to run, values must not)."""
+    say("case repeat")
+    w, ref = reference("sentence")
+    net = binding.TreeNet(w.params, scheduler="ready")
+    try:
+        net.load(w.trees)
+        for it in range(20):
+            net.batch["h"].fill_(float("nan"))
+            net.batch["c"].fill_(float("nan"))
+            net.forward()
+            assert binding.tl_status(net.ctx) == 0
+            assert_close(net.batch["h"].cpu().numpy(), ref["h"], "h iter %d" % it)
+            assert_close(net.batch["c"].cpu().numpy(), ref["c"], "c iter %d" % it)
+    finally:
+        net.close()
