@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched tree-network forward pass on one MI355X.
+
+One step = one tl_forward over one batch: structure pass, leaf cells, internal cells (scheduling
+included) and root gather, with the batch and the parameters already resident in device memory.
+
+Prints ONE JSON line.  `value` is trees/s of the whole step; `roofline` is about the dominant
+kernel (the internal-node kernel) with its duration taken from HIP events recorded by the library on
+the stream it launches on; `cpu_baseline` is the CPU checker timed on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}      # MI355X dense matrix peaks
+HBM_GBS = 8000.0
+
+
+def algorithmic_work(w):
+    """(flops of the internal cells, flops of the leaf cells, bytes) that the method must do:
+    20 H^2 per internal TreeLSTM node (2 * 2H * 5H), 6 E H per leaf; bytes = every h/c row written once,
+    every non-root row read once by its parent, one embedding row per leaf, the weights once, the indices."""
+    from paper_1809_00832_amd import synth
+    p, t = w.params, w.trees
+    H, E = p.hidden, p.embed_dim
+    n_int, n_leaf, N, B = t.n_internal, t.n_leaves, t.n_nodes, t.n_trees
+    if p.cell == synth.CELL_TREELSTM:
+        f_int, f_leaf, states = 20.0 * H * H * n_int, 6.0 * E * H * n_leaf, 2
+        weights = (2 * H * 5 * H + E * 3 * H + 8 * H) * 4
+    elif p.cell == synth.CELL_TREERNN:
+        f_int, f_leaf, states = 4.0 * H * H * n_int, 0.0, 1
+        weights = (2 * H * H + H) * 4
+    else:
+        f_int, f_leaf, states = (8.0 * H ** 3 + 4.0 * H * H) * n_int, 0.0, 1
+        weights = (4 * H ** 3 + 2 * H * H + H) * 4
+    bytes_ = states * N * H * 4 + states * (N - B) * H * 4 + n_leaf * E * 4 + weights + 3 * N * 4 + (B + 1) * 4
+    return f_int, f_leaf, float(bytes_)
+
+
+def time_steps(net, steps):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.forward()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def run_scheduler(w, sched, precision, steps, warmup):
+    from paper_1809_00832_amd import binding
+    net = binding.TreeNet(w.params, scheduler=sched, precision=precision)
+    try:
+        net.load(w.trees)
+        for _ in range(warmup):
+            net.forward()
+        code = binding.tl_status(net.ctx)
+        if code != 0:
+            raise binding.TLError(code, "warm-up forward")
+        sec = time_steps(net, steps)
+        # same steps again with the library's stage events switched on
+        binding.tl_set_profiling(net.ctx, True)
+        k = min(steps, binding.TL_PROFILE_RING)
+        sec_prof = time_steps(net, k)
+        stages = [binding.tl_stage_ms(net.ctx, back) for back in range(k)]
+        binding.tl_set_profiling(net.ctx, False)
+        avg = {key: sum(s[key] for s in stages) / k for key in stages[0]}
+        stats = binding.tl_last_stats(net.ctx)
+        code = binding.tl_status(net.ctx)
+        if code != 0:
+            raise binding.TLError(code, "timed forward")
+        return dict(sec=sec, sec_profiled=sec_prof, stage_ms=avg, stats=stats)
+    finally:
+        net.close()
+
+
+def cpu_baseline(w):
+    """The CPU checker as it stands, all trees once, one thread per host core (at most 16)."""
+    import oracle
+    cores = min(16, os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    oracle.forward_params(w.params, w.trees, n_threads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": w.trees.n_trees / dt, "unit": "trees/s", "cores": cores, "kind": "oracle",
+            "nodes_per_sec": w.trees.n_nodes / dt, "seconds": dt,
+            "sample": "all %d trees of the workload, one pass, trees spread over %d threads" % (w.trees.n_trees, cores)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="throughput")
+    ap.add_argument("--scheduler", default="ready", choices=["ready", "level_device", "level_host"])
+    ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build evaluates on ONE GPU only (trees are independent; see DESIGN.md for how "
+                 "a batch would be sharded); run with --gpus 1")
+
+    import torch
+    from paper_1809_00832_amd import binding, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    torch.cuda.set_device(0)
+    precision = binding.TL_F32 if args.precision == "f32" else binding.TL_BF16_IN
+
+    w = synth.workload(args.workload)
+    t = w.trees
+    f_int, f_leaf, bytes_ = algorithmic_work(w)
+
+    main_run = run_scheduler(w, args.scheduler, precision, args.steps, args.warmup)
+    sec = main_run["sec"]
+    peak = PEAK_TFLOPS[args.precision]
+    kernel_ms = main_run["stage_ms"]["internal"]
+    achieved = f_int / (kernel_ms * 1e-3) / 1e12
+    out = {
+        "metric": "TreeLSTM forward trees/sec" if w.params.cell == 0 else "tree network forward trees/sec",
+        "value": t.n_trees / sec,
+        "unit": "trees/s",
+        "nodes_per_sec": t.n_nodes / sec,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.precision, "data": "synthetic",
+        "config": {"workload": args.workload, "scheduler": args.scheduler, "trees": t.n_trees, "nodes": t.n_nodes,
+                   "leaves": t.n_leaves, "hidden": w.params.hidden, "embed_dim": w.params.embed_dim,
+                   "vocab": w.params.vocab},
+        "step_tflops": (f_int + f_leaf) / sec / 1e12,
+        "step_frac_mfma_peak": (f_int + f_leaf) / sec / 1e12 / peak,
+        "step_algorithmic_gbs": bytes_ / sec / 1e9,
+        "stage_ms": main_run["stage_ms"],
+        "ms_per_step_with_stage_events": main_run["sec_profiled"] * 1e3,
+        "tiles_formed": main_run["stats"]["n_tiles"],
+        "roofline": {"bound": "mfma", "kernel": "internal-node kernel (%s scheduler)" % args.scheduler,
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "flops_per_launch": f_int, "kernel_ms": kernel_ms, "traffic": None},
+    }
+    if not args.no_compare:
+        comp = {}
+        for sched in ("ready", "level_device", "level_host"):
+            if sched == args.scheduler:
+                continue
+            r = run_scheduler(w, sched, precision, args.steps, args.warmup)
+            comp[sched] = {"trees_per_sec": t.n_trees / r["sec"], "ms_per_step": r["sec"] * 1e3,
+                           "stage_ms": r["stage_ms"], "n_levels": r["stats"]["n_levels"]}
+        out["comparison"] = comp
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

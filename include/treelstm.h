@@ -137,14 +137,16 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes,
  * error (TL_OK if none). */
 int tl_status(tl_ctx *ctx);
 
-/* Stage timing.  tl_set_profiling(ctx, 1) makes every later tl_forward record HIP events
- * between its stages on the caller's stream.  tl_last_stage_ms waits for the last
- * forward and writes TL_N_STAGES durations in milliseconds to ms (HOST):
+/* Stage timing.  After tl_set_profiling(ctx, 1) every tl_forward records HIP events between
+ * its stages on the caller's stream; the events of the last TL_PROFILE_RING forwards are kept.
+ * tl_stage_ms waits for the forward that lies `back` calls in the past (0 = the last one) and
+ * writes TL_N_STAGES durations in milliseconds to ms (HOST):
  *   [0] structure pass (parents, counters, roots; heights and per-height lists if used)
- *   [1] leaf cells   [2] internal cells incl. scheduling   [3] root gather   [4] total */
-enum { TL_N_STAGES = 5 };
+ *   [1] leaf cells   [2] internal cells incl. scheduling   [3] root gather   [4] total
+ * TL_EINVAL if that forward was not recorded. */
+enum { TL_N_STAGES = 5, TL_PROFILE_RING = 128 };
 int tl_set_profiling(tl_ctx *ctx, int on);
-int tl_last_stage_ms(tl_ctx *ctx, float *ms);
+int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
 
 /* Facts about the last forward, for reports and tests (HOST out-parameters, any may be
  * NULL): number of heights seen by a level scheduler (0 for TL_SCHED_READY), number of

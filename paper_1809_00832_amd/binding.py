@@ -17,10 +17,10 @@ TL_TREELSTM, TL_TREERNN, TL_RNTN = 0, 1, 2
 TL_F32, TL_BF16_IN = 0, 1
 TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST = 0, 1, 2
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4, -5
-TL_N_STAGES = 5
+TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_last_stage_ms", "tl_last_stats",
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats",
            "tl_strerror", "tl_destroy")
 
 
@@ -52,8 +52,8 @@ def lib():
         L.tl_status.argtypes = [vp]
         L.tl_set_profiling.restype = ci
         L.tl_set_profiling.argtypes = [vp, ci]
-        L.tl_last_stage_ms.restype = ci
-        L.tl_last_stage_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.tl_stage_ms.restype = ci
+        L.tl_stage_ms.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float)]
         L.tl_last_stats.restype = ci
         L.tl_last_stats.argtypes = [vp] + [ctypes.POINTER(ci)] * 3
         L.tl_strerror.restype = ctypes.c_char_p
@@ -110,9 +110,9 @@ def tl_set_profiling(ctx, on: bool) -> None:
     _check(lib().tl_set_profiling(ctx, int(on)), "tl_set_profiling")
 
 
-def tl_last_stage_ms(ctx):
+def tl_stage_ms(ctx, back: int = 0):
     ms = (ctypes.c_float * TL_N_STAGES)()
-    _check(lib().tl_last_stage_ms(ctx, ms), "tl_last_stage_ms")
+    _check(lib().tl_stage_ms(ctx, back, ms), "tl_stage_ms")
     return dict(zip(("structure", "leaves", "internal", "roots", "total"), [float(x) for x in ms]))
 
 

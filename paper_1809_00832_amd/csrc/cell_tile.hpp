@@ -1,4 +1,4 @@
-// The fused cell: gather -> LDS -> MFMA contraction -> gate epilogue -> h/c rows.
+// The fused cell: gather -> MFMA contraction -> gate epilogue -> h/c rows.
 //
 // One call evaluates up to TILE_ROWS nodes for one column group of HU hidden units:
 //   leaf tile      A row = embedding row of the leaf's word            (Figure 2, base case)
@@ -6,6 +6,16 @@
 // G = A * W (+ bias) is accumulated in fp32 on 16x16 MFMA tiles; the packed weights put all
 // gates of a hidden unit into the same lane, so sigmoid/tanh, the c update and the h output
 // are computed on the accumulators and written straight to the node-major h/c arrays.
+//
+// Two data paths feed the MFMAs:
+//   staged  (33..64 rows) A and B chunks go through LDS, shared by the four waves, each wave
+//           owning one block of 16 rows;
+//   direct  (1..32 rows)  few rows mean the K axis is split between the waves instead, so no
+//           two waves need the same weights: every wave loads its operands from global memory
+//           straight into registers, several k-steps ahead, and the partial sums meet in LDS.
+//           With so few rows the tile is latency-bound, and this path has no barrier in its loop.
+// Template parameter COH selects device-scope loads/stores for h and c (see common.hpp); it is
+// set inside persistent kernels, where producers and consumers of a row run concurrently.
 #pragma once
 
 #include "common.hpp"
@@ -38,8 +48,7 @@ __device__ inline float tanh_f(float x)
     return 1.f - 2.f * __frcp_rn(1.f + t);
 }
 
-// Fills node/src0/src1 for `count` rows from a list of node indices.  Threads >= count mark
-// their row unused.  Caller synchronises afterwards.
+// Fills node/src0/src1 of one row.  Rows without a node are marked unused.  Caller synchronises.
 template <int EPI>
 __device__ inline void tile_set_rows(TileSmem &sm, const Fwd &f, int row, int node)
 {
@@ -59,7 +68,7 @@ __device__ inline void tile_set_rows(TileSmem &sm, const Fwd &f, int row, int no
 }
 
 // Loads one 4-float granule of a gathered A row: K position k of the padded axis.
-template <int SEG, bool VEC4>
+template <int SEG, bool VEC4, bool COH>
 __device__ inline floatx4 load_a_granule(const float *__restrict__ table, int L, int Lp, int s0, int s1, int k)
 {
     floatx4 v = {0.f, 0.f, 0.f, 0.f};
@@ -69,34 +78,156 @@ __device__ inline floatx4 load_a_granule(const float *__restrict__ table, int L,
     if (src < 0 || off >= L || (SEG == 1 && k >= Lp)) return v;
     const float *p = table + (size_t)src * L + off;
     if (VEC4) {
-        v = *reinterpret_cast<const floatx4 *>(p);
+        v = ld_f4<COH>(p);
     } else {
-        v.x = p[0];
-        if (off + 1 < L) v.y = p[1];
-        if (off + 2 < L) v.z = p[2];
-        if (off + 3 < L) v.w = p[3];
+        v.x = ld_f<COH>(p);
+        if (off + 1 < L) v.y = ld_f<COH>(p + 1);
+        if (off + 2 < L) v.z = ld_f<COH>(p + 2);
+        if (off + 3 < L) v.w = ld_f<COH>(p + 3);
     }
     return v;
 }
 
-// The tile.  All WG_THREADS threads of the workgroup call it together; sm.node/src0/src1 hold
-// the rows (see tile_set_rows) and a __syncthreads() has been passed since they were written.
-//   table : source rows of the gather (embedding table, or h)
-//   count : rows in use (1..TILE_ROWS);  cg : column group
-template <int EPI, bool VEC4>
-__device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
-                                 int count, int cg)
+// Gate functions and h/c stores for the 4 accumulator rows a lane holds.
+template <int EPI, bool COH, int NG>
+__device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG],
+                                     int rb, int count, int cg, int lane)
+{
+    const int hu = cg * HU + (lane & 15);
+    const int H = f.H;
+    if (hu >= H) return;
+    float bias[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int row = rb * 16 + (lane >> 4) * 4 + v;
+        if (row >= count) continue;
+        const int node = sm.node[row];
+        const size_t o = (size_t)node * H + hu;
+        if (EPI == EPI_LSTM_LEAF) {
+            const float i = sigmoid_f(acc[0][v] + bias[0]);
+            const float og = sigmoid_f(acc[1][v] + bias[1]);
+            const float u = tanh_f(acc[2][v] + bias[2]);
+            const float cc = i * u;
+            st_f<COH>(f.c + o, cc);
+            st_f<COH>(f.h + o, og * tanh_f(cc));
+        } else if (EPI == EPI_LSTM_INNER) {
+            const float cl = ld_f<COH>(f.c + (size_t)sm.src0[row] * H + hu);
+            const float cr = ld_f<COH>(f.c + (size_t)sm.src1[row] * H + hu);
+            const float i = sigmoid_f(acc[0][v] + bias[0]);
+            const float fl = sigmoid_f(acc[1][v] + bias[1]);
+            const float fr = sigmoid_f(acc[2][v] + bias[2]);
+            const float og = sigmoid_f(acc[3][v] + bias[3]);
+            const float u = tanh_f(acc[4][v] + bias[4]);
+            const float cc = i * u + fl * cl + fr * cr;
+            st_f<COH>(f.c + o, cc);
+            st_f<COH>(f.h + o, og * tanh_f(cc));
+        } else {
+            st_f<COH>(f.h + o, tanh_f(acc[0][v] + bias[0]));
+        }
+    }
+}
+
+// Partial accumulators of the waves with ks > 0 go through LDS to the wave with ks == 0 of the
+// same row block.  Re-uses the A buffers; the caller guarantees nobody reads them any more.
+template <int NG>
+__device__ inline void ksplit_reduce(TileSmem &sm, floatx4 (&acc)[NG], int KS, int ks, bool active, int wave, int lane)
+{
+    float *red = &sm.a[0][0];               // [wave][g*4+v][lane]: 4*20*64 floats <= sizeof(a)
+    if (active && ks > 0) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(wave * NG * 4 + g * 4 + v) * 64 + lane] = acc[g][v];
+    }
+    __syncthreads();
+    if (active && ks == 0) {
+        for (int other = 1; other < KS; ++other) {
+            const int w2 = KS == 4 ? other : wave + 2;
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[g][v] += red[(w2 * NG * 4 + g * 4 + v) * 64 + lane];
+        }
+    }
+}
+
+// ---- direct path: 1..32 rows ------------------------------------------------------------
+template <int EPI, bool VEC4, bool COH>
+__device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
+                                        int count, int cg)
+{
+    constexpr int NG = EpiTraits<EPI>::NG;
+    constexpr int SEG = EpiTraits<EPI>::SEG;
+    constexpr int U = NG >= 5 ? 3 : 4;          // k-steps per register group (two groups are in flight)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nrb = (count + 15) >> 4;          // 1 or 2
+    const int KS = nrb == 1 ? 4 : 2;
+    const int rb = KS == 4 ? 0 : (wave & 1);
+    const int ks = KS == 4 ? wave : (wave >> 1);
+    const int L = gm.L, Lp = gm.Lp;
+    const int n_steps = gm.n_chunks * (KC / STEP_K);
+    const floatx4 *wp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * n_steps * NG * 64 + lane;
+    const int row = rb * 16 + (lane & 15);
+    const int s0 = sm.src0[row], s1 = sm.src1[row];   // -1 beyond count
+    const int kl = (lane >> 4) * 4;
+
+    floatx4 acc[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    floatx4 a0[U], b0[U][NG], a1[U], b1[U][NG];
+    const int my_steps = (n_steps - ks + KS - 1) / KS;      // k-steps ks, ks+KS, ... of this wave
+    const int n_groups = (my_steps + U - 1) / U;
+    auto load_group = [&](int grp, floatx4 (&a)[U], floatx4 (&b)[U][NG]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = ks + KS * (grp * U + u);
+            if (s < n_steps) {
+                a[u] = load_a_granule<SEG, VEC4, COH>(table, L, Lp, s0, s1, s * STEP_K + kl);
+#pragma unroll
+                for (int g = 0; g < NG; ++g) b[u][g] = wp[(size_t)(s * NG + g) * 64];
+            } else {
+                a[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int g = 0; g < NG; ++g) b[u][g] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+    auto mma_group = [&](const floatx4 (&a)[U], const floatx4 (&b)[U][NG]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][i], b[u][g][i], acc[g], 0, 0, 0);
+    };
+    load_group(0, a0, b0);
+    for (int grp = 0; grp < n_groups; grp += 2) {
+        if (grp + 1 < n_groups) load_group(grp + 1, a1, b1);
+        mma_group(a0, b0);
+        if (grp + 1 < n_groups) {
+            if (grp + 2 < n_groups) load_group(grp + 2, a0, b0);
+            mma_group(a1, b1);
+        }
+    }
+    ksplit_reduce<NG>(sm, acc, KS, ks, true, wave, lane);
+    if (ks == 0) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
+}
+
+// ---- staged path: 33..64 rows -----------------------------------------------------------
+template <int EPI, bool VEC4, bool COH>
+__device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
+                                        int count, int cg)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
     constexpr int STEPS = KC / STEP_K;          // 4 k-steps per chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nrb = (count + 15) >> 4;          // 16-row blocks in use
-    // Waves: one row block each when there are 3-4; with fewer row blocks the K axis is split
-    // between waves instead (interleaved k-steps) and the partial sums meet in LDS.
-    const int KS = nrb == 1 ? 4 : (nrb == 2 ? 2 : 1);
-    const int rb = KS == 4 ? 0 : (KS == 2 ? (wave & 1) : wave);
-    const int ks = KS == 4 ? wave : (KS == 2 ? (wave >> 1) : 0);
+    const int nrb = (count + 15) >> 4;          // 3 or 4 row blocks, one per wave
+    const int rb = wave;
     const bool active = rb < nrb;
     const int L = gm.L, Lp = gm.Lp;
     const int n_steps = gm.n_chunks * STEPS;
@@ -120,7 +251,7 @@ __device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, con
         const int k = chunk * KC + a_k4 * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4>(table, L, Lp, s0[j], s1[j], k);
+            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4, COH>(table, L, Lp, s0[j], s1[j], k);
         const floatx4 *src = wp + (size_t)chunk * STEPS * NG * 64;
 #pragma unroll
         for (int j = 0; j < NG; ++j) rbuf[j] = src[tid + WG_THREADS * j];
@@ -143,7 +274,8 @@ __device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, con
         if (more) load_chunk(chunk + 1);
         if (active) {
             const float *arow = &sm.a[buf][(rb * 16 + (lane & 15)) * A_LD + (lane >> 4) * 4];
-            for (int s = ks; s < STEPS; s += KS) {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
                 const floatx4 av = *reinterpret_cast<const floatx4 *>(arow + s * STEP_K);
                 floatx4 bv[NG];
 #pragma unroll
@@ -158,67 +290,19 @@ __device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, con
         if (more) store_chunk(buf ^ 1);
         __syncthreads();
     }
+    if (active) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
+}
 
-    // K-split: partial accumulators of the waves with ks > 0 go through LDS (re-using the A
-    // buffers, which nobody reads any more) to the wave with ks == 0 of the same row block.
-    if (KS > 1) {
-        float *red = &sm.a[0][0];               // [wave][g*4+v][lane], 4*20*64 floats <= sizeof a
-        if (active && ks > 0) {
-#pragma unroll
-            for (int g = 0; g < NG; ++g)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) red[(wave * NG * 4 + g * 4 + v) * 64 + lane] = acc[g][v];
-        }
-        __syncthreads();
-        if (active && ks == 0) {
-            for (int other = 1; other < KS; ++other) {
-                const int w2 = KS == 4 ? other : wave + 2;
-#pragma unroll
-                for (int g = 0; g < NG; ++g)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[g][v] += red[(w2 * NG * 4 + g * 4 + v) * 64 + lane];
-            }
-        }
-    }
-
-    // Epilogue on the accumulators: lane holds hidden unit cg*16 + lane%16 of rows 4*(lane/16)+v.
-    if (active && ks == 0) {
-        const int hu = cg * HU + (lane & 15);
-        const int H = f.H;
-        if (hu < H) {
-            float bias[NG];
-#pragma unroll
-            for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = rb * 16 + (lane >> 4) * 4 + v;
-                if (row >= count) continue;
-                const int node = sm.node[row];
-                const size_t o = (size_t)node * H + hu;
-                if (EPI == EPI_LSTM_LEAF) {
-                    const float i = sigmoid_f(acc[0][v] + bias[0]);
-                    const float og = sigmoid_f(acc[1][v] + bias[1]);
-                    const float u = tanh_f(acc[2][v] + bias[2]);
-                    const float cc = i * u;
-                    f.c[o] = cc;
-                    f.h[o] = og * tanh_f(cc);
-                } else if (EPI == EPI_LSTM_INNER) {
-                    const float cl = f.c[(size_t)sm.src0[row] * H + hu];
-                    const float cr = f.c[(size_t)sm.src1[row] * H + hu];
-                    const float i = sigmoid_f(acc[0][v] + bias[0]);
-                    const float fl = sigmoid_f(acc[1][v] + bias[1]);
-                    const float fr = sigmoid_f(acc[2][v] + bias[2]);
-                    const float og = sigmoid_f(acc[3][v] + bias[3]);
-                    const float u = tanh_f(acc[4][v] + bias[4]);
-                    const float cc = i * u + fl * cl + fr * cr;
-                    f.c[o] = cc;
-                    f.h[o] = og * tanh_f(cc);
-                } else {
-                    f.h[o] = tanh_f(acc[0][v] + bias[0]);
-                }
-            }
-        }
-    }
+// The tile.  All WG_THREADS threads of the workgroup call it together; sm.node/src0/src1 hold
+// the rows (see tile_set_rows) and a __syncthreads() has been passed since they were written.
+//   table : source rows of the gather (embedding table, or h)
+//   count : rows in use (1..TILE_ROWS);  cg : column group
+template <int EPI, bool VEC4, bool COH>
+__device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
+                                 int count, int cg)
+{
+    if (count <= 32) cell_tile_direct<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
+    else cell_tile_staged<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     __syncthreads();   // the row tables and the LDS buffers may be rewritten after this call
 }
 

@@ -11,8 +11,7 @@ namespace tl {
 // ---- tiling constants ---------------------------------------------------------------
 // A tile is up to TILE_ROWS ready nodes times one column group of HU hidden units (all
 // gates of those units, so that the gate epilogue stays in registers).  The contraction
-// runs on v_mfma_f32_16x16x4_f32 / v_mfma_f32_16x16x32_bf16: 16 rows x 16 hidden units
-// per wave, K consumed in chunks of KC staged through LDS.
+// runs on v_mfma_f32_16x16x4_f32: 16 rows x 16 hidden units per wave and k-step of 16.
 constexpr int TILE_ROWS = 64;
 constexpr int HU = 16;
 constexpr int KC = 64;            // K elements per LDS chunk (4 MFMA k-steps of 16)
@@ -21,24 +20,47 @@ constexpr int A_LD = KC + 4;      // LDS row stride of the A chunk in floats (pa
 constexpr int WG_THREADS = 256;   // 4 waves
 constexpr int MAX_GATES = 5;
 constexpr int N_XCD = 8;          // L2 domains of the chip; workgroups are dealt to them round-robin
+constexpr int MAX_GANGS = 64;
+constexpr int LINE = 128;         // bytes; every word that is polled or hammered gets its own line
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+struct alignas(LINE) Line {
+    unsigned int v;
+    unsigned int pad[LINE / 4 - 1];
+};
+struct alignas(LINE) Line64 {
+    unsigned long long v;
+    unsigned long long pad[LINE / 8 - 1];
+};
+
 // ---- scheduler control block (device memory, zeroed at the start of every forward) ---
-struct Ctl {
-    unsigned long long formed;    // low 32: ready-queue entries consumed into tiles; high 32: tiles formed
-    unsigned int q_tail;          // ready-queue entries reserved by producers
-    unsigned int tiles_done;      // tiles whose every column group has finished
-    unsigned int part_next[N_XCD];// next (tile, column group) item of each column-group partition
-    unsigned int bar_count;       // grid barrier arrivals (level scheduler)
+struct alignas(LINE) Ctl {
+    // line 0: written rarely, read by the host
     int status;                   // first latched tl_error
-    int abort;                    // set when a waiting workgroup gives up; everybody leaves
     int n_leaf_seen;              // leaves counted by the structure pass
+    int n_seed;                   // internal nodes that start ready (both children are leaves)
     int max_height;
     int n_levels;
     int reached;                  // nodes reached bottom-up from the leaves
-    int pad;
+    int tiles_formed;             // ready scheduler: tiles of ready nodes formed
+    int pad0[LINE / 4 - 7];
+    Line abort;                   // set when a waiting workgroup gives up; everybody leaves
+    Line q_head;                  // ready-queue entries consumed into tiles
+    Line q_tail;                  // ready-queue entries reserved by producers
+    Line tiles;                   // tiles formed (statistics only)
+    // grid barrier of the level scheduler: arrivals per L2 domain, then across domains
+    Line bar_xcd[N_XCD];
+    Line bar_all;
+    Line bar_flag[N_XCD];
 };
+
+// Mailbox of one gang (a set of workgroups that together cover all column groups of a tile).
+struct alignas(LINE) GangBox {
+    Line64 desc;                  // sequence << 40 | rows << 32 | queue position ; written by the leader
+    Line done;                    // workgroups of the gang that finished tiles (cumulative)
+};
+constexpr unsigned long long GANG_EXIT_ROWS = 0xffull;   // rows field of the "leave" message
 
 // One contraction: rows gathered from `SEG` source rows of length L, times packed weights.
 struct Gemm {
@@ -59,63 +81,82 @@ struct Fwd {
     // model
     int cell, H, E, vocab, n_cg, bf16;
     const float *emb;           // fp32 embedding table (as given)
-    const void *emb_lo;         // bf16 copy (bf16-operand mode)
-    void *h_lo;                 // bf16 shadow of h, [n_nodes x H] (bf16-operand mode)
     Gemm leaf, inner;
     // workspace
     int32_t *parent, *pending, *leaf_list, *root_ws;
     int32_t *height, *arrive, *level_cnt, *level_off, *level_fill, *level_nodes;
     unsigned int *q_nodes;            // ready queue: node index + 1, 0 = slot not written yet
-    unsigned long long *tile_desc;    // per formed tile: start | rows << 32 | 1 << 63
-    unsigned int *tile_done;          // per formed tile: column groups finished
+    GangBox *gangs;
     Ctl *ctl;
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once
+    int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size
 };
 
-// ---- agent-scope atomics ---------------------------------------------------------------
-template <typename T> __device__ inline T ld_relaxed(const T *p)
+// ---- device-scope accesses -------------------------------------------------------------
+// Inside a persistent kernel data written by one workgroup is read by workgroups on other L2
+// domains.  The L2s are not coherent with each other, so such data is written with
+// device-scope write-through stores and read with device-scope loads (relaxed agent-scope
+// atomics compile to exactly these: global_store/global_load with the sc1 bit), and a writer
+// waits for its stores to be acknowledged (s_waitcnt) before it signals.  This avoids
+// whole-L2 write-back / invalidate fences, which cost tens of microseconds under load.
+template <typename T> __device__ inline T ld_dev(const T *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <typename T> __device__ inline void st_release(T *p, T v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T> __device__ inline void st_relaxed(T *p, T v)
+template <typename T> __device__ inline void st_dev(T *p, T v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <typename T> __device__ inline T add_acq_rel(T *p, T v)
-{
-    return __hip_atomic_fetch_add(p, v, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T> __device__ inline T add_relaxed(T *p, T v)
+template <typename T> __device__ inline T add_dev(T *p, T v)
 {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <typename T> __device__ inline bool cas_acq_rel(T *p, T *expected, T desired)
+template <typename T> __device__ inline bool cas_dev(T *p, T *expected, T desired)
 {
-    return __hip_atomic_compare_exchange_strong(p, expected, desired, __ATOMIC_ACQ_REL, __ATOMIC_RELAXED,
+    return __hip_atomic_compare_exchange_strong(p, expected, desired, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                 __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ inline void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
-__device__ inline void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+// All earlier loads and stores of this wave have completed (stores: acknowledged by memory).
+__device__ inline void wait_mem()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // compiler: keep earlier accesses before this point
+    __builtin_amdgcn_s_waitcnt(0);
+}
+
+template <bool COH> __device__ inline float ld_f(const float *p) { return COH ? ld_dev(p) : *p; }
+template <bool COH> __device__ inline void st_f(float *p, float v)
+{
+    if (COH) st_dev(p, v); else *p = v;
+}
+// 16-byte aligned 4-float load
+template <bool COH> __device__ inline floatx4 ld_f4(const float *p)
+{
+    if (!COH) return *reinterpret_cast<const floatx4 *>(p);
+    const unsigned long long *q = reinterpret_cast<const unsigned long long *>(p);
+    const unsigned long long a = ld_dev(q), b = ld_dev(q + 1);
+    floatx4 v;
+    v.x = __uint_as_float((unsigned)a);
+    v.y = __uint_as_float((unsigned)(a >> 32));
+    v.z = __uint_as_float((unsigned)b);
+    v.w = __uint_as_float((unsigned)(b >> 32));
+    return v;
+}
 
 __device__ inline void latch_error(Ctl *ctl, int code)
 {
     int expected = 0;
-    __hip_atomic_compare_exchange_strong(&ctl->status, &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+    cas_dev(&ctl->status, &expected, code);
 }
 
+__device__ inline void backoff() { __builtin_amdgcn_s_sleep(2); }
+
 // Rows per tile when `avail` ready rows meet room for `free_tiles` more tiles: spread the rows
-// over the free room in units of 16, at most TILE_ROWS; with no room only full tiles are worth
-// forming (0 = wait for more rows).
+// over the free room in units of 16, at most TILE_ROWS.
 __host__ __device__ inline int tile_rows_for(unsigned avail, unsigned free_tiles)
 {
     if (avail == 0) return 0;
-    if (free_tiles == 0) return avail >= (unsigned)TILE_ROWS ? TILE_ROWS : 0;
+    if (free_tiles == 0) free_tiles = 1;
     unsigned per = (avail + free_tiles - 1) / free_tiles;
     unsigned m = (per + 15u) & ~15u;
     if (m < 16u) m = 16u;
@@ -123,8 +164,45 @@ __host__ __device__ inline int tile_rows_for(unsigned avail, unsigned free_tiles
     return (int)(m < avail ? m : avail);
 }
 
-// Column groups are split into min(n_cg, N_XCD) contiguous partitions; the workgroups of one
-// L2 domain prefer one partition, so that its slice of the weights stays in that L2.
-__host__ __device__ inline int part_start(int p, int n_cg, int n_parts) { return (int)((long long)p * n_cg / n_parts); }
+// How one height's rows are cut into tiles for a grid with room for `cap` tiles at a time:
+// whole rounds of full tiles first, then the remainder spread evenly over one more round in
+// smaller tiles (a tile of <= 16 / <= 32 rows takes a quarter / half of a full tile's time).
+struct LevelPlan {
+    int n_full;     // tiles of TILE_ROWS rows
+    int m_rem;      // rows per remainder tile
+    int n_tiles;    // all tiles
+};
+__host__ __device__ inline LevelPlan plan_level(int rows, int cap)
+{
+    LevelPlan p;
+    if (cap < 1) cap = 1;
+    p.n_full = rows / TILE_ROWS / cap * cap;
+    const int rem = rows - p.n_full * TILE_ROWS;
+    p.m_rem = rem > 0 ? tile_rows_for((unsigned)rem, (unsigned)cap) : TILE_ROWS;
+    p.n_tiles = p.n_full + (rem + p.m_rem - 1) / p.m_rem;
+    return p;
+}
+__host__ __device__ inline void plan_tile(const LevelPlan &p, int rows, int tile, int *start, int *count)
+{
+    if (tile < p.n_full) {
+        *start = tile * TILE_ROWS;
+        *count = TILE_ROWS;
+    } else {
+        *start = p.n_full * TILE_ROWS + (tile - p.n_full) * p.m_rem;
+        const int left = rows - *start;
+        *count = left < p.m_rem ? left : p.m_rem;
+    }
+}
+
+// Column group of member j of a gang of `gang_size` workgroups, pass i (a workgroup covers the
+// column groups j, j + gang_size, ... when there are more column groups than gang members).
+// Consecutive workgroups sit on consecutive L2 domains; when the count allows it, each domain
+// is given a contiguous range of column groups so that its slice of the weights stays in its L2
+// and neighbouring 64-byte pieces of an output row are written from the same L2.
+__host__ __device__ inline int gang_cg(int j, int gang_size, int n_cg)
+{
+    if (gang_size == n_cg && n_cg % N_XCD == 0) return (j % N_XCD) * (n_cg / N_XCD) + j / N_XCD;
+    return j;
+}
 
 }  // namespace tl

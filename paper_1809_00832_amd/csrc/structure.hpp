@@ -2,6 +2,9 @@
 // schedulers need.  This is the device counterpart of the master that sorts operations into a
 // ready queue or a waiting list by their number of unresolved inputs (Section 4.1, Figure 4
 // step 2) and of the parent pointers that stand in for a call stack ("Graph execution stack").
+//
+// Counters that many threads bump at once are bumped once per wave (ballot + popcount) or once
+// per workgroup (LDS histogram): atomics on one address are served one after the other.
 #pragma once
 
 #include "common.hpp"
@@ -20,13 +23,30 @@ __device__ inline int tree_of(const int32_t *tree_off, int n_trees, int n)
     return lo;
 }
 
+// Slot in an append-only list for every lane with pred set: one atomic per wave.  Must be
+// called by all lanes of the wave.  Returns -1 for lanes without pred.
+template <typename T> __device__ inline int wave_append(T *counter, bool pred)
+{
+    const unsigned long long mask = __ballot(pred);
+    if (mask == 0) return -1;
+    const int lane = threadIdx.x & 63;
+    const int first = __ffsll((long long)mask) - 1;
+    T base = 0;
+    if (lane == first) base = atomicAdd(counter, (T)__popcll(mask));
+    base = __shfl(base, first);
+    return pred ? (int)base + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
+}
+
 // Resets the per-forward scheduler state.  A fill kernel rather than memsets so that a caller
 // may capture the forward in a HIP graph.
 __global__ void k_reset(Fwd f, int with_levels)
 {
     const int N = f.n_nodes;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    const size_t total = (size_t)N + 1 > 64 ? (size_t)N + 1 : 64;   // also covers the control block
+    const size_t ctl_words = sizeof(Ctl) / 4, gang_words = (size_t)MAX_GANGS * sizeof(GangBox) / 4;
+    size_t total = (size_t)N + 1;
+    if (total < ctl_words) total = ctl_words;
+    if (total < gang_words) total = gang_words;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         if (i < (size_t)N) {
             f.parent[i] = -1;
@@ -34,9 +54,10 @@ __global__ void k_reset(Fwd f, int with_levels)
             if (with_levels) { f.height[i] = 0; f.arrive[i] = 0; f.level_fill[i] = 0; }
         }
         if (with_levels && i <= (size_t)N) f.level_cnt[i] = 0;
-        if (i < (size_t)f.n_int) { f.q_nodes[i] = 0; f.tile_desc[i] = 0; f.tile_done[i] = 0; }
+        if (i < (size_t)f.n_int) f.q_nodes[i] = 0;
         if (i < (size_t)f.n_trees) f.root_ws[i] = -1;
-        if (i < sizeof(Ctl) / 4) ((unsigned int *)f.ctl)[i] = 0;
+        if (i < ctl_words) ((unsigned int *)f.ctl)[i] = 0;
+        if (i < gang_words) ((unsigned int *)f.gangs)[i] = 0;
     }
 }
 
@@ -53,29 +74,31 @@ __global__ void k_scatter(Fwd f)
         if (n == f.n_trees) ok = ok && (v == f.n_nodes);
         if (!ok) latch_error(ctl, TL_ESTRUCT);
     }
-    if (n >= f.n_nodes) return;
-    const int t = tree_of(f.tree_off, f.n_trees, n);
-    const int lo = f.tree_off[t], hi = f.tree_off[t + 1];
-    if (n < lo || n >= hi) { latch_error(ctl, TL_ESTRUCT); return; }
-    const int l = f.left[n], r = f.right[n];
-    if (l < 0 && r < 0) {
-        const int w = f.word[n];
-        if (w < 0 || w >= f.vocab) { latch_error(ctl, TL_ESTRUCT); return; }
-        const int slot = atomicAdd(&ctl->n_leaf_seen, 1);
-        if (slot < f.n_leaf) f.leaf_list[slot] = n;
-        return;
+    bool is_leaf = false, is_seed = false;
+    if (n < f.n_nodes) {
+        const int t = tree_of(f.tree_off, f.n_trees, n);
+        const int lo = f.tree_off[t], hi = f.tree_off[t + 1];
+        const int l = f.left[n], r = f.right[n];
+        if (n < lo || n >= hi) {
+            latch_error(ctl, TL_ESTRUCT);
+        } else if (l < 0 && r < 0) {
+            const int w = f.word[n];
+            if (w < 0 || w >= f.vocab) latch_error(ctl, TL_ESTRUCT); else is_leaf = true;
+        } else if (l >= lo && l < hi && r >= lo && r < hi && l < f.n_nodes && r < f.n_nodes && l != r && l != n &&
+                   r != n) {
+            if (atomicCAS(&f.parent[l], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
+            if (atomicCAS(&f.parent[r], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
+            const int pend = (f.left[l] >= 0) + (f.left[r] >= 0);
+            f.pending[n] = pend;
+            is_seed = pend == 0;
+        } else {
+            latch_error(ctl, TL_ESTRUCT);
+        }
     }
-    const bool ok = l >= lo && l < hi && r >= lo && r < hi && l < f.n_nodes && r < f.n_nodes && l != r && l != n &&
-                    r != n && l >= 0 && r >= 0;
-    if (!ok) { latch_error(ctl, TL_ESTRUCT); return; }
-    if (atomicCAS(&f.parent[l], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
-    if (atomicCAS(&f.parent[r], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
-    const int pend = (f.left[l] >= 0) + (f.left[r] >= 0);
-    f.pending[n] = pend;
-    if (pend == 0) {
-        const unsigned slot = atomicAdd(&ctl->q_tail, 1u);
-        if (slot < (unsigned)f.n_int) f.q_nodes[slot] = (unsigned)n + 1u;
-    }
+    const int leaf_slot = wave_append(&ctl->n_leaf_seen, is_leaf);
+    if (is_leaf && leaf_slot < f.n_leaf) f.leaf_list[leaf_slot] = n;
+    const int seed_slot = wave_append(&ctl->q_tail.v, is_seed);
+    if (is_seed && seed_slot < f.n_int) f.q_nodes[seed_slot] = (unsigned)n + 1u;
 }
 
 // One thread per node: the node nobody points to is its tree's root; there must be exactly one.
@@ -96,16 +119,14 @@ __global__ void k_check_roots(Fwd f)
 }
 
 // Heights by climbing: one thread per leaf walks towards the root; at every internal node the
-// first child to arrive stops, the second continues with height 1 + max.  Also histograms the
-// heights.  The walk visits each node once, so a thread's loop is bounded by the tree height.
+// first child to arrive stops, the second continues with height 1 + max.  The walk passes each
+// node once, so a thread's loop is bounded by the tree height.
 __global__ void k_climb(Fwd f)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    Ctl *ctl = f.ctl;
-    if (ctl->status != 0 || i >= f.n_leaf) return;
+    if (f.ctl->status != 0 || i >= f.n_leaf) return;
     int n = f.leaf_list[i];
     int hcur = 0;
-    atomicAdd(&f.level_cnt[0], 1);
     for (int guard = 0; guard < f.n_nodes; ++guard) {
         const int p = f.parent[n];
         if (p < 0) break;
@@ -113,14 +134,37 @@ __global__ void k_climb(Fwd f)
         __threadfence();
         if (atomicAdd(&f.arrive[p], 1) == 0) break;
         __threadfence();
-        hcur = ld_relaxed(&f.height[p]);
-        atomicAdd(&f.level_cnt[hcur], 1);
-        atomicMax(&ctl->max_height, hcur);
+        hcur = ld_dev(&f.height[p]);
         n = p;
     }
 }
 
-// Single workgroup: exclusive scan of the height histogram into level offsets.
+constexpr int HIST_BINS = 1024;
+
+// One thread per node: histogram of the heights of the internal nodes that the climb reached
+// (both children arrived), and the largest height.
+__global__ void k_level_hist(Fwd f)
+{
+    __shared__ int s_hist[HIST_BINS];
+    __shared__ int s_max;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f.ctl->status != 0) return;
+    for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x) s_hist[b] = 0;
+    if (threadIdx.x == 0) s_max = 0;
+    __syncthreads();
+    if (n < f.n_nodes && f.left[n] >= 0 && f.arrive[n] == 2) {
+        const int hgt = f.height[n];
+        if (hgt < HIST_BINS) atomicAdd(&s_hist[hgt], 1); else atomicAdd(&f.level_cnt[hgt], 1);
+        atomicMax(&s_max, hgt);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x)
+        if (s_hist[b]) atomicAdd(&f.level_cnt[b], s_hist[b]);
+    if (threadIdx.x == 0 && s_max > 0) atomicMax(&f.ctl->max_height, s_max);
+}
+
+// Single workgroup: exclusive scan of the height histogram into level offsets.  Height 0 (the
+// leaves) has no list: leaves are taken from leaf_list.
 __global__ void k_scan_levels(Fwd f)
 {
     __shared__ int s_part[1024];
@@ -154,21 +198,34 @@ __global__ void k_scan_levels(Fwd f)
     if (tid == 0) {
         f.level_off[n_levels] = s_carry;
         ctl->n_levels = n_levels;
-        ctl->reached = s_carry;
-        if (s_carry != f.n_nodes) latch_error(ctl, TL_ESTRUCT);   // nodes no leaf leads to (cycle)
+        ctl->reached = s_carry + f.n_leaf;
+        if (s_carry != f.n_int) latch_error(ctl, TL_ESTRUCT);   // nodes no leaf leads to (cycle)
     }
 }
 
-// One thread per node: append the node to the list of its height.
+// One thread per node: append every reached internal node to the list of its height.
 __global__ void k_fill_levels(Fwd f)
 {
+    __shared__ int s_hist[HIST_BINS];
+    __shared__ int s_base[HIST_BINS];
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f.ctl->status != 0 || n >= f.n_nodes) return;
-    const bool leaf = f.left[n] < 0;
-    if (!leaf && f.arrive[n] != 2) return;
-    const int hgt = leaf ? 0 : f.height[n];
-    const int slot = f.level_off[hgt] + atomicAdd(&f.level_fill[hgt], 1);
-    if (slot < f.n_nodes) f.level_nodes[slot] = n;
+    if (f.ctl->status != 0) return;
+    for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x) s_hist[b] = 0;
+    __syncthreads();
+    const bool mine = n < f.n_nodes && f.left[n] >= 0 && f.arrive[n] == 2;
+    int hgt = 0, rank = 0;
+    if (mine) {
+        hgt = f.height[n];
+        rank = hgt < HIST_BINS ? atomicAdd(&s_hist[hgt], 1) : atomicAdd(&f.level_fill[hgt], 1);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x)
+        if (s_hist[b]) s_base[b] = atomicAdd(&f.level_fill[b], s_hist[b]);
+    __syncthreads();
+    if (mine) {
+        const int slot = f.level_off[hgt] + rank + (hgt < HIST_BINS ? s_base[hgt] : 0);
+        if (slot < f.n_int) f.level_nodes[slot] = n;
+    }
 }
 
 // h_root / c_root / root outputs.

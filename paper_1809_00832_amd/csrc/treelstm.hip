@@ -50,8 +50,8 @@ struct tl_ctx {
     int last_levels = 0;
     // profiling
     int profiling = 0;
-    hipEvent_t ev[TL_N_STAGES + 1]{};
-    bool ev_valid = false;
+    hipEvent_t ev[TL_PROFILE_RING][TL_N_STAGES]{};   // created on first use
+    long long n_recorded = 0;                        // forwards recorded since profiling was switched on
 };
 
 namespace {
@@ -71,7 +71,7 @@ int hip_fail(hipError_t e)
 inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 typedef void (*fwd_kernel)(Fwd);
-typedef void (*tiles_kernel)(Fwd, const int32_t *, int, int);
+typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
 
 fwd_kernel ready_kernel(int cell, bool vec4)
 {
@@ -136,7 +136,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 11 + align256((size_t)N * 8) + align256((size_t)B * 4) + align256(sizeof(Ctl));
+    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS);
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
     ctx->ws_bytes = bytes;
@@ -160,10 +160,9 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->level_fill = (int32_t *)take(n4);
     f->level_nodes = (int32_t *)take(n4);
     f->q_nodes = (unsigned int *)take(n4);
-    f->tile_done = (unsigned int *)take(n4);
-    f->tile_desc = (unsigned long long *)take(align256((size_t)ctx->cap_nodes * 8));
     f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
+    f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
 }
 
 void free_all(tl_ctx *ctx)
@@ -176,8 +175,9 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->ws);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
-    for (auto &e : ctx->ev)
-        if (e) (void)hipEventDestroy(e);
+    for (auto &set : ctx->ev)
+        for (auto &e : set)
+            if (e) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -225,10 +225,10 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     if (occ2 < occ) occ = occ2;
     if (occ < 1) return TL_EHIP;
     if (occ > 2) occ = 2;
-    ctx->persistent_grid = occ * ctx->n_cu;
+    ctx->persistent_grid = occ * ctx->n_cu / N_XCD * N_XCD;
+    if (ctx->persistent_grid < N_XCD) return TL_EHIP;
 
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
-    for (auto &e : ctx->ev) TL_HIP(hipEventCreate(&e));
     return TL_OK;
 }
 
@@ -294,6 +294,8 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
     const int grid_p = ctx->persistent_grid;
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
+    f.gang_size = ctx->n_cg < grid_p ? ctx->n_cg : grid_p;
+    f.n_gangs = grid_p / f.gang_size < MAX_GANGS ? grid_p / f.gang_size : MAX_GANGS;
 
     const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
     const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
@@ -307,9 +309,12 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     ctx->ran = true;
     ctx->last_grid = 0;
     ctx->last_levels = 0;
-    ctx->ev_valid = false;
-
-    if (prof) TL_HIP(hipEventRecord(ctx->ev[0], st));
+    hipEvent_t *ev = ctx->ev[ctx->n_recorded % TL_PROFILE_RING];
+    if (prof) {
+        for (int i = 0; i < TL_N_STAGES; ++i)
+            if (!ev[i]) TL_HIP(hipEventCreate(&ev[i]));
+        TL_HIP(hipEventRecord(ev[0], st));
+    }
     // ---- structure pass ----------------------------------------------------------------
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
     hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
@@ -317,28 +322,30 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     hipLaunchKernelGGL(k_check_roots, dim3((n_trees + 255) / 256), dim3(256), 0, st, f);
     if (need_levels) {
         hipLaunchKernelGGL(k_climb, dim3((f.n_leaf + 255) / 256), dim3(256), 0, st, f);
+        hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
         hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
         hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
     }
     TL_HIP(hipGetLastError());
-    if (prof) TL_HIP(hipEventRecord(ctx->ev[1], st));
+    if (prof) TL_HIP(hipEventRecord(ev[1], st));
 
     // ---- leaves ------------------------------------------------------------------------
     if (cfg.cell == TL_TREELSTM) {
-        const int tiles = (f.n_leaf + TILE_ROWS - 1) / TILE_ROWS;
-        hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf), dim3(tiles * ctx->n_cg), dim3(WG_THREADS),
-                           TILE_SMEM_BYTES, st, f, (const int32_t *)f.leaf_list, f.n_leaf, TILE_ROWS);
+        const LevelPlan plan = plan_level(f.n_leaf, f.cap_tiles);
+        hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                           TILE_SMEM_BYTES, st, f, (const int32_t *)f.leaf_list, f.n_leaf, plan);
     } else {
         hipLaunchKernelGGL(k_leaf_copy, dim3(f.n_leaf), dim3(128), 0, st, f);
     }
     TL_HIP(hipGetLastError());
-    if (prof) TL_HIP(hipEventRecord(ctx->ev[2], st));
+    if (prof) TL_HIP(hipEventRecord(ev[2], st));
 
     // ---- internal nodes ------------------------------------------------------------------
     if (f.n_int > 0) {
         if (cfg.scheduler == TL_SCHED_READY) {
-            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner), dim3(grid_p), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
-            ctx->last_grid = grid_p;
+            const int grid_r = f.n_gangs * f.gang_size;
+            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner), dim3(grid_r), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
             hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner), dim3(grid_p), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_p;
@@ -352,12 +359,11 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
                 int max_grid = 0;
                 for (int lvl = 1; lvl < n_levels; ++lvl) {
                     const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
-                    if (rows <= 0 || lo < 0 || lo + rows > n_nodes) return TL_EHIP;
-                    const int m = tile_rows_for((unsigned)rows, (unsigned)f.cap_tiles);
-                    const int tiles = (rows + m - 1) / m;
-                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner), dim3(tiles * ctx->n_cg), dim3(WG_THREADS),
-                                       TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, m);
-                    if (tiles * ctx->n_cg > max_grid) max_grid = tiles * ctx->n_cg;
+                    if (rows <= 0 || lo < 0 || lo + rows > f.n_int) return TL_EHIP;
+                    const LevelPlan plan = plan_level(rows, f.cap_tiles);
+                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                                       TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, plan);
+                    if (plan.n_tiles * ctx->n_cg > max_grid) max_grid = plan.n_tiles * ctx->n_cg;
                 }
                 ctx->last_grid = max_grid;
             }
@@ -365,14 +371,14 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
         }
         TL_HIP(hipGetLastError());
     }
-    if (prof) TL_HIP(hipEventRecord(ctx->ev[3], st));
+    if (prof) TL_HIP(hipEventRecord(ev[3], st));
 
     // ---- roots ---------------------------------------------------------------------------
     hipLaunchKernelGGL(k_root_gather, dim3(n_trees), dim3(128), 0, st, f);
     TL_HIP(hipGetLastError());
     if (prof) {
-        TL_HIP(hipEventRecord(ctx->ev[4], st));
-        ctx->ev_valid = true;
+        TL_HIP(hipEventRecord(ev[4], st));
+        ctx->n_recorded += 1;
     }
     return TL_OK;
 }
@@ -390,17 +396,18 @@ int tl_set_profiling(tl_ctx *ctx, int on)
 {
     if (!ctx) return TL_EINVAL;
     ctx->profiling = on != 0;
-    ctx->ev_valid = false;
+    ctx->n_recorded = 0;
     return TL_OK;
 }
 
-int tl_last_stage_ms(tl_ctx *ctx, float *ms)
+int tl_stage_ms(tl_ctx *ctx, int back, float *ms)
 {
-    if (!ctx || !ms) return TL_EINVAL;
-    if (!ctx->ev_valid) return TL_EINVAL;
-    TL_HIP(hipEventSynchronize(ctx->ev[4]));
-    for (int i = 0; i < 4; ++i) TL_HIP(hipEventElapsedTime(&ms[i], ctx->ev[i], ctx->ev[i + 1]));
-    TL_HIP(hipEventElapsedTime(&ms[4], ctx->ev[0], ctx->ev[4]));
+    if (!ctx || !ms || back < 0) return TL_EINVAL;
+    if (back >= ctx->n_recorded || back >= TL_PROFILE_RING) return TL_EINVAL;
+    hipEvent_t *ev = ctx->ev[(ctx->n_recorded - 1 - back) % TL_PROFILE_RING];
+    TL_HIP(hipEventSynchronize(ev[4]));
+    for (int i = 0; i < 4; ++i) TL_HIP(hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]));
+    TL_HIP(hipEventElapsedTime(&ms[4], ev[0], ev[4]));
     return TL_OK;
 }
 
@@ -414,7 +421,7 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups)
     int rc = read_ctl(ctx);
     if (rc != TL_OK) return rc;
     if (n_levels) *n_levels = ctx->host_ctl->n_levels;
-    if (n_tiles) *n_tiles = (int)(ctx->host_ctl->formed >> 32);
+    if (n_tiles) *n_tiles = (int)ctx->host_ctl->tiles.v;
     if (n_workgroups) *n_workgroups = ctx->last_grid;
     return TL_OK;
 }
