@@ -67,23 +67,29 @@ __device__ inline void tile_set_rows(TileSmem &sm, const Fwd &f, int row, int no
     sm.src1[row] = s1;
 }
 
-// Loads one 4-float granule of a gathered A row: K position k of the padded axis.
+// Loads one 4-float granule of a gathered A row: K position k of the padded axis.  Branch-free
+// and select-free: whatever lies outside the row is read from a block of zeros in device
+// memory, so that nothing has to wait for the load until the MFMA (or the LDS store) that uses
+// it, and the loads of several k-steps can be in flight together.
 template <int SEG, bool VEC4, bool COH>
-__device__ inline floatx4 load_a_granule(const float *__restrict__ table, int L, int Lp, int s0, int s1, int k)
+__device__ inline floatx4 load_a_granule(const float *__restrict__ table, const float *__restrict__ zeros, int L, int Lp,
+                                         int s0, int s1, int k)
 {
-    floatx4 v = {0.f, 0.f, 0.f, 0.f};
-    int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
-    int off = k - seg * Lp;
-    int src = seg ? s1 : s0;
-    if (src < 0 || off >= L || (SEG == 1 && k >= Lp)) return v;
-    const float *p = table + (size_t)src * L + off;
+    const int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
+    const int off = k - seg * Lp;
+    const int src = seg ? s1 : s0;
+    const bool ok = src >= 0 && off < L;
+    const float *p = ok ? table + ((size_t)src * L + off) : zeros;
+    floatx4 v;
     if (VEC4) {
         v = ld_f4<COH>(p);
     } else {
+        // rows need not be 16-byte aligned here; element i is real iff off + i < L
+        const int n = ok ? L - off : 4;
         v.x = ld_f<COH>(p);
-        if (off + 1 < L) v.y = ld_f<COH>(p + 1);
-        if (off + 2 < L) v.z = ld_f<COH>(p + 2);
-        if (off + 3 < L) v.w = ld_f<COH>(p + 3);
+        v.y = ld_f<COH>(n > 1 ? p + 1 : zeros);
+        v.z = ld_f<COH>(n > 2 ? p + 2 : zeros);
+        v.w = ld_f<COH>(n > 3 ? p + 3 : zeros);
     }
     return v;
 }
@@ -160,7 +166,7 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
-    constexpr int U = NG >= 5 ? 3 : 4;          // k-steps per register group (two groups are in flight)
+    constexpr int U = NG >= 5 ? (COH ? 2 : 3) : 4;   // k-steps per register group (two groups are in flight)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nrb = (count + 15) >> 4;          // 1 or 2
     const int KS = nrb == 1 ? 4 : 2;
@@ -183,16 +189,13 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
     auto load_group = [&](int grp, floatx4 (&a)[U], floatx4 (&b)[U][NG]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int s = ks + KS * (grp * U + u);
-            if (s < n_steps) {
-                a[u] = load_a_granule<SEG, VEC4, COH>(table, L, Lp, s0, s1, s * STEP_K + kl);
+            // a k-step past the end re-reads the last one with a zeroed A operand
+            const int s_raw = ks + KS * (grp * U + u);
+            const bool real = s_raw < n_steps;
+            const int s = real ? s_raw : n_steps - 1;
+            a[u] = load_a_granule<SEG, VEC4, COH>(table, f.zeros, L, Lp, real ? s0 : -1, real ? s1 : -1, s * STEP_K + kl);
 #pragma unroll
-                for (int g = 0; g < NG; ++g) b[u][g] = wp[(size_t)(s * NG + g) * 64];
-            } else {
-                a[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int g = 0; g < NG; ++g) b[u][g] = floatx4{0.f, 0.f, 0.f, 0.f};
-            }
+            for (int g = 0; g < NG; ++g) b[u][g] = wp[(size_t)(s * NG + g) * 64];
         }
     };
     auto mma_group = [&](const floatx4 (&a)[U], const floatx4 (&b)[U][NG]) {
@@ -204,13 +207,20 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
                 for (int g = 0; g < NG; ++g)
                     acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][i], b[u][g][i], acc[g], 0, 0, 0);
     };
+    // Two register groups alternate: the loads of one group are issued, then the MFMAs of the
+    // other run.  The scheduling barriers keep the compiler from sinking the loads below the
+    // MFMAs (which would expose the full memory latency once per group).
     load_group(0, a0, b0);
     for (int grp = 0; grp < n_groups; grp += 2) {
         if (grp + 1 < n_groups) load_group(grp + 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
         mma_group(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
         if (grp + 1 < n_groups) {
             if (grp + 2 < n_groups) load_group(grp + 2, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
             mma_group(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     ksplit_reduce<NG>(sm, acc, KS, ks, true, wave, lane);
@@ -251,7 +261,7 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
         const int k = chunk * KC + a_k4 * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4, COH>(table, L, Lp, s0[j], s1[j], k);
+            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4, COH>(table, f.zeros, L, Lp, s0[j], s1[j], k);
         const floatx4 *src = wp + (size_t)chunk * STEPS * NG * 64;
 #pragma unroll
         for (int j = 0; j < NG; ++j) rbuf[j] = src[tid + WG_THREADS * j];
@@ -272,6 +282,7 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
         const int buf = chunk & 1;
         const bool more = chunk + 1 < gm.n_chunks;
         if (more) load_chunk(chunk + 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the global loads ahead of the MFMAs that hide them
         if (active) {
             const float *arow = &sm.a[buf][(rb * 16 + (lane & 15)) * A_LD + (lane >> 4) * 4];
 #pragma unroll
@@ -287,6 +298,7 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
                         acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[g][i], acc[g], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
         if (more) store_chunk(buf ^ 1);
         __syncthreads();
     }

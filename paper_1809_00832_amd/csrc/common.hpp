@@ -87,6 +87,7 @@ struct Fwd {
     int32_t *height, *arrive, *level_cnt, *level_off, *level_fill, *level_nodes;
     unsigned int *q_nodes;            // ready queue: node index + 1, 0 = slot not written yet
     GangBox *gangs;
+    const float *zeros;               // 256 bytes of zeros (stand-in source for padded operand granules)
     Ctl *ctl;
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once

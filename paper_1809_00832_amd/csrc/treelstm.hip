@@ -136,8 +136,9 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS);
+    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 256;
     TL_HIP(hipMalloc(&ctx->ws, bytes));
+    TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
     TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
     ctx->ws_bytes = bytes;
     ctx->cap_nodes = N;
@@ -163,6 +164,7 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
     f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
+    f->zeros = (const float *)take(256);
 }
 
 void free_all(tl_ctx *ctx)
