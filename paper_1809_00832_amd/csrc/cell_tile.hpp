@@ -110,6 +110,7 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
         const int row = rb * 16 + (lane >> 4) * 4 + v;
         if (row >= count) continue;
         const int node = sm.node[row];
+        if (node < 0) continue;
         const size_t o = (size_t)node * H + hu;
         if (EPI == EPI_LSTM_LEAF) {
             const float i = sigmoid_f(acc[0][v] + bias[0]);
@@ -166,7 +167,7 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
-    constexpr int U = NG >= 5 ? (COH ? 2 : 3) : 4;   // k-steps per register group (two groups are in flight)
+    constexpr int U = NG >= 5 ? (COH ? 2 : 4) : 4;   // k-steps per register group (two groups are in flight)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nrb = (count + 15) >> 4;          // 1 or 2
     const int KS = nrb == 1 ? 4 : 2;
@@ -209,19 +210,19 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
     };
     // Two register groups alternate: the loads of one group are issued, then the MFMAs of the
     // other run.  The scheduling barriers keep the compiler from sinking the loads below the
-    // MFMAs (which would expose the full memory latency once per group).
+    // MFMAs (which would expose the full memory latency once per group).  Nothing in the loop is
+    // conditional: a branch around loads would make the wait counters at its join pessimistic.
+    // Groups past the end multiply a zero A operand.
     load_group(0, a0, b0);
     for (int grp = 0; grp < n_groups; grp += 2) {
-        if (grp + 1 < n_groups) load_group(grp + 1, a1, b1);
+        load_group(grp + 1, a1, b1);
         __builtin_amdgcn_sched_barrier(0);
         mma_group(a0, b0);
         __builtin_amdgcn_sched_barrier(0);
-        if (grp + 1 < n_groups) {
-            if (grp + 2 < n_groups) load_group(grp + 2, a0, b0);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_group(a1, b1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        load_group(grp + 2, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_group(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     ksplit_reduce<NG>(sm, acc, KS, ks, true, wave, lane);
     if (ks == 0) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);

@@ -55,12 +55,19 @@ struct alignas(LINE) Ctl {
     Line bar_flag[N_XCD];
 };
 
-// Mailbox of one gang (a set of workgroups that together cover all column groups of a tile).
+// Mailbox of one gang: a scheduler workgroup plus workgroups that together cover all column
+// groups of a tile.  The scheduler posts tiles into a ring of GANG_RING slots.  A slot holds, for
+// each of the TILE_ROWS rows, the node index and its two source rows, every entry tagged with the
+// tile's sequence number and row count: tag << 32 | value, tag = sequence << 8 | rows.  An entry
+// is valid for tile number q exactly when its tag says so, so that a reader needs no separate
+// "published" flag and may request the entry before it is known to be there.
+constexpr int GANG_RING = 2;
+constexpr int SLOT_ENTRIES = 3 * TILE_ROWS;
+constexpr int VALUE_EXIT = -2;            // node value of row 0 in the "leave" message
 struct alignas(LINE) GangBox {
-    Line64 desc;                  // sequence << 40 | rows << 32 | queue position ; written by the leader
-    Line done;                    // workgroups of the gang that finished tiles (cumulative)
+    unsigned long long slot[GANG_RING][SLOT_ENTRIES];   // [0,64): node  [64,128): first source  [128,192): second source
+    Line done;                                          // compute workgroups that finished tiles (cumulative)
 };
-constexpr unsigned long long GANG_EXIT_ROWS = 0xffull;   // rows field of the "leave" message
 
 // One contraction: rows gathered from `SEG` source rows of length L, times packed weights.
 struct Gemm {
@@ -91,7 +98,7 @@ struct Fwd {
     Ctl *ctl;
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once
-    int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size
+    int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size compute + n_gangs scheduler workgroups
 };
 
 // ---- device-scope accesses -------------------------------------------------------------

@@ -1,7 +1,7 @@
 // The three ways internal nodes reach the fused cell (enum tl_scheduler), plus the leaf kernel.
 #pragma once
 
-#include "cell_tile.hpp"
+#include "cell_ws.hpp"
 
 namespace tl {
 
@@ -42,8 +42,7 @@ __global__ void k_leaf_copy(Fwd f)
 }
 
 // ---------------------------------------------------------------------------------------
-// Grid-wide barrier for a grid whose workgroups are all resident and whose size is a multiple
-// of N_XCD.  Two levels, so that no single word takes hundreds of back-to-back atomics: the
+// Grid-wide barrier for a grid whose workgroups are all resident.  Two levels, so that no single word takes hundreds of back-to-back atomics: the
 // workgroups of one L2 domain count on their own line, the last of each domain counts on a
 // shared line, and the very last one raises a flag line per domain, which the others poll.
 // Data visibility does not come from the barrier: callers write shared data with device-scope
@@ -57,10 +56,11 @@ __device__ inline bool grid_barrier(TileSmem &sm, const Fwd &f, unsigned &epoch)
     epoch += 1;
     if (threadIdx.x == 0) {
         const int x = blockIdx.x % N_XCD;
-        const unsigned per = gridDim.x / N_XCD;
+        const unsigned n_dom = gridDim.x < (unsigned)N_XCD ? gridDim.x : (unsigned)N_XCD;   // domains that hold workgroups
+        const unsigned per = (gridDim.x - (unsigned)x + N_XCD - 1u) / N_XCD;                  // workgroups of domain x
         if (add_dev(&ctl->bar_xcd[x].v, 1u) == per * epoch - 1u) {
-            if (add_dev(&ctl->bar_all.v, 1u) == (unsigned)N_XCD * epoch - 1u)
-                for (int i = 0; i < N_XCD; ++i) st_dev(&ctl->bar_flag[i].v, epoch);
+            if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u)
+                for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, epoch);
         }
         int ok = 1;
         int spins = 0;
@@ -83,163 +83,244 @@ __device__ inline bool grid_barrier(TileSmem &sm, const Fwd &f, unsigned &epoch)
 
 // Level frontiers on the device: heights 1, 2, ... with a grid barrier between them (the
 // depth-wise batching of Section 6.3, without a launch or a host round trip per depth).
-template <int EPI, bool VEC4>
-__global__ __launch_bounds__(WG_THREADS, 2) void k_levels_persistent(Fwd f)
+// SPW > 0 selects the weight-stationary cell (cell_ws.hpp, SPW k-steps per wave in registers,
+// one workgroup per CU, every workgroup tied to one column group); SPW == 0 the streaming cell.
+template <int EPI, bool VEC4, int SPW>
+__global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
     if (f.ctl->status != 0) return;
     const int n_levels = f.ctl->n_levels;
     const int tid = threadIdx.x;
+    const int my_cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
+    const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
+    WsWeights<EpiTraits<EPI>::NG, SPW> w;
+    if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
     for (int lvl = 1; lvl < n_levels; ++lvl) {
         const int lo = f.level_off[lvl], rows = f.level_off[lvl + 1] - lo;
         const LevelPlan plan = plan_level(rows, f.cap_tiles);
-        const int items = plan.n_tiles * f.n_cg;
-        for (int item = blockIdx.x; item < items; item += gridDim.x) {
-            const int tile = item / f.n_cg, cg = gang_cg(item % f.n_cg, f.n_cg, f.n_cg);
-            int start, count;
-            plan_tile(plan, rows, tile, &start, &count);
-            tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
-            __syncthreads();
-            cell_tile<EPI, VEC4, true>(sm, f, f.inner, f.h, count, cg);
+        if constexpr (SPW > 0) {
+            for (int tile = slot; tile < plan.n_tiles; tile += n_slots) {
+                int start, count;
+                plan_tile(plan, rows, tile, &start, &count);
+                tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
+                __syncthreads();
+                ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+            }
+        } else {
+            const int items = plan.n_tiles * f.n_cg;
+            for (int item = blockIdx.x; item < items; item += gridDim.x) {
+                const int tile = item / f.n_cg, cg = gang_cg(item % f.n_cg, f.n_cg, f.n_cg);
+                int start, count;
+                plan_tile(plan, rows, tile, &start, &count);
+                tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
+                __syncthreads();
+                cell_tile<EPI, VEC4, true>(sm, f, f.inner, f.h, count, cg);
+            }
         }
         if (lvl + 1 < n_levels && !grid_barrier(sm, f, epoch)) return;
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Ready-counter scheduler (Section 4.1): the device form of "enqueue an operation once all of
-// its inputs are resolved".  State, all in device memory:
+// Ready-counter scheduler (Section 4.1): the device form of "the master enqueues an operation
+// once all of its inputs are resolved; idle execution threads take operations off the ready
+// queue".  State, all in device memory:
 //   pending[n]   internal children of n that have not finished
 //   q_nodes[]    append-only ready queue; q_tail = entries reserved, q_head = entries consumed
 //   gangs[g]     mailbox of gang g
-// The grid is n_gangs gangs of gang_size workgroups; member j of a gang owns column group(s)
-// gang_cg(j, ..), so a gang covers all hidden units of a tile.  The leader (member 0) cuts a
-// tile of ready nodes off the queue and posts it in the gang's mailbox; every member evaluates
-// its columns of the tile and counts itself done; the leader then decrements the counter of each
-// row's parent and pushes parents that reach zero.  Gangs run independently of each other: no
-// barrier spans the grid, and a tile starts as soon as its nodes are ready and a gang is free.
-// Every wait is bounded by spin_limit and by the abort flag, so the grid always drains.
-template <int EPI, bool VEC4>
-__global__ __launch_bounds__(WG_THREADS, 2) void k_ready_persistent(Fwd f)
+// The grid is n_gangs gangs.  A gang is one scheduler workgroup (the master's role) and
+// gang_size compute workgroups (the workers); compute member j owns column group(s)
+// gang_cg(j, ..), so a gang covers all hidden units of a tile.  The scheduler cuts a tile of
+// ready nodes off the queue, resolves their child rows and posts the tile in the gang's mailbox -
+// up to GANG_RING tiles ahead of the compute workgroups, so that they find the next tile waiting
+// when they finish one.  Every compute member evaluates its columns and counts itself done; the
+// scheduler then decrements the counter of each row's parent and pushes parents that reach zero.
+// Gangs run independently of each other: no barrier spans the grid, and a tile starts as soon as
+// its nodes are ready and a gang is free.  Every wait is bounded by spin_limit and by the abort
+// flag, so the grid always drains.
+__device__ inline unsigned long long slot_entry(unsigned seq, unsigned rows, int value)
+{
+    return ((unsigned long long)((seq << 8) | rows) << 32) | (unsigned)value;
+}
+
+// Scheduler workgroup: only its first wave works, one lane per row of a tile.
+__device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
+{
+    Ctl *ctl = f.ctl;
+    const int lane = threadIdx.x;
+    if (lane >= 64) return;
+    const unsigned n_int = (unsigned)f.n_int;
+    unsigned published = 0, completed = 0;       // tiles posted / tiles whose parents have been resolved
+    int my_node[GANG_RING];                      // this lane's row of the tiles in flight (-1: none)
+#pragma unroll
+    for (int r = 0; r < GANG_RING; ++r) my_node[r] = -1;
+    int spins = 0;
+    unsigned last_head = ~0u, last_tail = ~0u;
+    bool leave = false;
+    while (!leave) {
+        bool progress = false;
+        // ---- (1) a finished tile: resolve its rows' parents -------------------------------
+        if (completed < published) {
+            unsigned d = 0;
+            if (lane == 0) d = ld_dev(&box->done.v);
+            d = __shfl(d, 0);
+            if (d >= (completed + 1) * (unsigned)f.gang_size) {
+                const int r = (int)((completed + 1) % GANG_RING);
+                int node = -1;
+#pragma unroll
+                for (int q = 0; q < GANG_RING; ++q) if (q == r) node = my_node[q];
+                int p = -1;
+                if (node >= 0) {
+                    p = f.parent[node];
+                    if (p >= 0 && add_dev(&f.pending[p], -1) != 1) p = -1;
+                }
+                // parents that became ready are pushed with one reservation on q_tail for the tile
+                const unsigned long long ready = __ballot(p >= 0);
+                const int n_ready = __popcll(ready);
+                unsigned base = 0;
+                if (lane == 0 && n_ready > 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_ready);
+                base = __shfl(base, 0);
+                if (p >= 0) {
+                    const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << lane) - 1ull));
+                    if (slot < n_int) st_dev(&f.q_nodes[slot], (unsigned)p + 1u);
+                }
+                completed += 1;
+                progress = true;
+            }
+        }
+        // ---- (2) room in the ring: cut the next tile off the ready queue --------------------
+        unsigned head = 0, tail = 0;
+        if (lane == 0) { head = ld_dev(&ctl->q_head.v); tail = ld_dev(&ctl->q_tail.v); }
+        head = __shfl(head, 0);
+        tail = __shfl(tail, 0);
+        if (tail > n_int) tail = n_int;
+        if (head != last_head || tail != last_tail) { last_head = head; last_tail = tail; spins = 0; }   // others progress
+        const unsigned in_flight = published - completed;
+        if (in_flight < (unsigned)GANG_RING && tail > head) {
+            const unsigned avail = tail - head;
+            // an idle gang takes what there is; a busy gang looks ahead only when there is plenty for all
+            if (in_flight == 0 || avail >= 16u * (unsigned)f.n_gangs) {
+                const unsigned m = (unsigned)tile_rows_for(avail, (unsigned)f.n_gangs);
+                int won = 0;
+                if (lane == 0) { unsigned expect = head; won = cas_dev(&ctl->q_head.v, &expect, head + m) ? 1 : 0; }
+                won = __shfl(won, 0);
+                if (won) {
+                    const unsigned seq = published + 1;
+                    int node = -1, s0 = -1, s1 = -1;
+                    if ((unsigned)lane < m) {
+                        unsigned v;
+                        int wait = 0;
+                        while ((v = ld_dev(&f.q_nodes[head + lane])) == 0u) {   // slot reserved, not written yet
+                            if (++wait > f.spin_limit) break;
+                            backoff();
+                        }
+                        if (v != 0u) {
+                            node = (int)v - 1;
+                            s0 = f.left[node];
+                            s1 = f.right[node];
+                        } else {
+                            st_dev(&ctl->abort.v, 1u);
+                            latch_error(ctl, TL_ESTALL);
+                        }
+                    }
+                    const int r = (int)(seq % GANG_RING);
+#pragma unroll
+                    for (int q = 0; q < GANG_RING; ++q) if (q == r) my_node[q] = node;
+                    unsigned long long *e = box->slot[r];
+                    st_dev(&e[lane], slot_entry(seq, m, node));
+                    st_dev(&e[TILE_ROWS + lane], slot_entry(seq, m, s0));
+                    st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, m, s1));
+                    published += 1;
+                    progress = true;
+                }
+            }
+        }
+        // ---- (3) leave when every node has been handed out and all own tiles are resolved -----
+        if (published == completed) {
+            unsigned ab = 0;
+            if (lane == 0) ab = ld_dev(&ctl->abort.v);
+            ab = __shfl(ab, 0);
+            if (head >= n_int || ab) leave = true;
+        }
+        if (progress) {
+            spins = 0;
+        } else if (!leave) {
+            if (++spins > f.spin_limit) {
+                st_dev(&ctl->abort.v, 1u);
+                latch_error(ctl, TL_ESTALL);
+                leave = true;           // compute workgroups stuck in a tile give up by their own budget
+            }
+            backoff();
+        }
+    }
+    // "leave" message in the next slot; statistics
+    const unsigned seq = published + 1;
+    unsigned long long *e = box->slot[seq % GANG_RING];
+    st_dev(&e[lane], slot_entry(seq, 0, VALUE_EXIT));
+    st_dev(&e[TILE_ROWS + lane], slot_entry(seq, 0, -1));
+    st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, 0, -1));
+    if (lane == 0) add_dev(&ctl->tiles.v, published);
+}
+
+template <int EPI, bool VEC4, int SPW>
+__global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
     Ctl *ctl = f.ctl;
     if (ctl->status != 0) return;
     const int tid = threadIdx.x;
+    const int n_compute = f.n_gangs * f.gang_size;
+    if ((int)blockIdx.x >= n_compute) {           // scheduler workgroups come after all compute workgroups
+        ready_scheduler(f, &f.gangs[blockIdx.x - n_compute]);
+        return;
+    }
     const int gang = blockIdx.x / f.gang_size, member = blockIdx.x % f.gang_size;
     GangBox *box = &f.gangs[gang];
-    const bool leader = member == 0;
-    const unsigned n_int = (unsigned)f.n_int;
-    unsigned seq = 0;                      // tiles this gang has been given so far
+    // weight-stationary cell (SPW > 0): gang_size == n_cg, the member's column group is fixed
+    const int my_cg = gang_cg(member, f.gang_size, f.n_cg);
+    WsWeights<EpiTraits<EPI>::NG, SPW> w;
+    if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
 
-    for (;;) {
-        seq += 1;
-        // ---- the leader cuts the next tile off the ready queue and posts it -------------
-        if (tid == 0) {
-            unsigned start = 0, rows = GANG_EXIT_ROWS;
-            int spins = 0;
-            if (leader) {
-                unsigned last_tail = ~0u;
-                for (;;) {
-                    unsigned head = ld_dev(&ctl->q_head.v);
-                    if (head >= n_int) break;                            // every node has been handed out
-                    unsigned tail = ld_dev(&ctl->q_tail.v);
-                    if (tail > n_int) tail = n_int;
-                    if (tail > head) {
-                        const unsigned m = (unsigned)tile_rows_for(tail - head, (unsigned)f.n_gangs);
-                        if (cas_dev(&ctl->q_head.v, &head, head + m)) { start = head; rows = m; break; }
-                        continue;
-                    }
-                    if (tail != last_tail) { last_tail = tail; spins = 0; }
-                    if (++spins > f.spin_limit || ((spins & 15) == 0 && ld_dev(&ctl->abort.v))) {
-                        st_dev(&ctl->abort.v, 1u);
-                        latch_error(ctl, TL_ESTALL);
-                        break;
-                    }
-                    backoff();
-                }
-                st_dev(&box->desc.v, ((unsigned long long)seq << 40) | ((unsigned long long)rows << 32) | start);
-                if (rows != GANG_EXIT_ROWS) add_dev(&ctl->tiles.v, 1u);
-            } else {
-                // the leader always posts, at the latest when its own wait gives up: the larger
-                // budget here is only a safety net
-                unsigned long long d;
-                long long polls = 0;
-                while (((d = ld_dev(&box->desc.v)) >> 40) < seq) {
-                    if (++polls > 64ll * f.spin_limit) { d = GANG_EXIT_ROWS << 32; break; }
-                    backoff();
-                }
-                start = (unsigned)d;
-                rows = (unsigned)(d >> 32) & 0xffu;
+    unsigned long long entry = 0;                 // this thread's entry of the next tile, requested ahead
+    if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[1 % GANG_RING][tid]);
+    for (unsigned seq = 1;; ++seq) {
+        // ---- rows of tile `seq`: wait until this thread's entry carries the tile's tag ----------
+        if (tid == 0) sm.cmd[2] = 1;
+        __syncthreads();
+        if (tid < SLOT_ENTRIES) {
+            long long polls = 0;
+            while ((unsigned)(entry >> 40) != seq) {
+                if (++polls > 64ll * f.spin_limit) { sm.cmd[2] = 0; break; }   // the scheduler always posts; safety net
+                backoff();
+                entry = ld_dev(&box->slot[seq % GANG_RING][tid]);
             }
-            sm.cmd[0] = (int)rows;
-            sm.cmd[1] = (int)start;
-            sm.cmd[2] = 1;
+            const int value = (int)(unsigned)entry;
+            if (tid < TILE_ROWS) sm.node[tid] = value;
+            else if (tid < 2 * TILE_ROWS) sm.src0[tid - TILE_ROWS] = value;
+            else sm.src1[tid - 2 * TILE_ROWS] = value;
+            if (tid == 0) sm.cmd[0] = (int)((entry >> 32) & 0xffu);
         }
         __syncthreads();
-        const int count = sm.cmd[0], start = sm.cmd[1];
-        if (count == (int)GANG_EXIT_ROWS) return;
+        const int count = sm.cmd[0];
+        if (sm.cmd[2] == 0 || sm.node[0] == VALUE_EXIT || count == 0) return;
+        // request the next tile's entry now; it arrives while this tile is computed
+        if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[(seq + 1) % GANG_RING][tid]);
 
-        // ---- rows of the tile: queue entries (a reserved slot may not be written yet) ----
-        {
-            int node = -1;
-            if (tid < count) {
-                unsigned v;
-                int spins = 0;
-                while ((v = ld_dev(&f.q_nodes[start + tid])) == 0u) {
-                    if (++spins > f.spin_limit) { sm.cmd[2] = 0; break; }
-                    backoff();
-                }
-                node = (int)v - 1;
-            }
-            tile_set_rows<EPI>(sm, f, tid, node);
-        }
-        __syncthreads();
-        const bool rows_ok = sm.cmd[2] != 0;
-
-        if (rows_ok)
+        if constexpr (SPW > 0) {
+            ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+        } else {
             for (int j = member; j < f.n_cg; j += f.gang_size)
                 cell_tile<EPI, VEC4, true>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
+        }
 
-        // ---- completion -------------------------------------------------------------------
-        wait_mem();            // this wave's h/c stores have reached memory
+        // ---- completion: the tile's h/c rows are in memory before the scheduler hears of it -----
+        wait_mem();
         __syncthreads();
         if (tid == 0) add_dev(&box->done.v, 1u);
-        if (!leader) continue;
-
-        if (tid == 0) {
-            const unsigned target = seq * (unsigned)f.gang_size;
-            int spins = 0, ok = rows_ok ? 1 : 0;
-            while (ld_dev(&box->done.v) < target) {
-                if (++spins > f.spin_limit) { ok = 0; break; }
-                backoff();
-            }
-            if (!ok) { st_dev(&ctl->abort.v, 1u); latch_error(ctl, TL_ESTALL); }
-            sm.cmd[3] = ok;
-        }
-        __syncthreads();
-        if (sm.cmd[3] && tid < 64) {
-            // first wave: one lane per row; parents that become ready are pushed with one
-            // reservation on q_tail for the whole tile
-            int p = -1;
-            if (tid < count) {
-                p = f.parent[sm.node[tid]];
-                if (p >= 0 && add_dev(&f.pending[p], -1) != 1) p = -1;
-            }
-            const unsigned long long ready = __ballot(p >= 0);
-            const int n_ready = __popcll(ready);
-            unsigned base = 0;
-            if (tid == 0 && n_ready > 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_ready);
-            base = __shfl(base, 0);
-            if (p >= 0) {
-                const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << tid) - 1ull));
-                if (slot < n_int) st_dev(&f.q_nodes[slot], (unsigned)p + 1u);
-            }
-        }
-        __syncthreads();
     }
 }
 

@@ -45,7 +45,9 @@ struct tl_ctx {
     Fwd last{};                       // pointers of the last forward (workspace part is reused)
     hipStream_t last_stream = nullptr;
     bool ran = false;
-    int persistent_grid = 0;          // workgroups of the persistent kernels
+    int persistent_grid = 0;          // workgroups of the persistent kernels (streaming cell)
+    int spw = 0;                      // k-steps per wave of the weight-stationary cell, 0 = not used
+    int ws_grid = 0;                  // workgroups of the persistent kernels (weight-stationary cell)
     int last_grid = 0;
     int last_levels = 0;
     // profiling
@@ -73,15 +75,40 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 typedef void (*fwd_kernel)(Fwd);
 typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
 
-fwd_kernel ready_kernel(int cell, bool vec4)
+// Steps per wave that the weight-stationary cell is instantiated for; 0 = streaming cell.
+const int WS_SIZES[] = {1, 2, 4, 5, 8, 16};
+
+template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw)
 {
-    if (cell == TL_TREELSTM) return vec4 ? k_ready_persistent<EPI_LSTM_INNER, true> : k_ready_persistent<EPI_LSTM_INNER, false>;
-    return vec4 ? k_ready_persistent<EPI_RNN_INNER, true> : k_ready_persistent<EPI_RNN_INNER, false>;
+    switch (spw) {
+    case 1: return k_ready_persistent<EPI, true, 1>;
+    case 2: return k_ready_persistent<EPI, true, 2>;
+    case 4: return k_ready_persistent<EPI, true, 4>;
+    case 5: return k_ready_persistent<EPI, true, 5>;
+    case 8: return k_ready_persistent<EPI, true, 8>;
+    case 16: return k_ready_persistent<EPI, true, 16>;
+    default: return vec4 ? k_ready_persistent<EPI, true, 0> : k_ready_persistent<EPI, false, 0>;
+    }
 }
-fwd_kernel levels_kernel(int cell, bool vec4)
+template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw)
 {
-    if (cell == TL_TREELSTM) return vec4 ? k_levels_persistent<EPI_LSTM_INNER, true> : k_levels_persistent<EPI_LSTM_INNER, false>;
-    return vec4 ? k_levels_persistent<EPI_RNN_INNER, true> : k_levels_persistent<EPI_RNN_INNER, false>;
+    switch (spw) {
+    case 1: return k_levels_persistent<EPI, true, 1>;
+    case 2: return k_levels_persistent<EPI, true, 2>;
+    case 4: return k_levels_persistent<EPI, true, 4>;
+    case 5: return k_levels_persistent<EPI, true, 5>;
+    case 8: return k_levels_persistent<EPI, true, 8>;
+    case 16: return k_levels_persistent<EPI, true, 16>;
+    default: return vec4 ? k_levels_persistent<EPI, true, 0> : k_levels_persistent<EPI, false, 0>;
+    }
+}
+fwd_kernel ready_kernel(int cell, bool vec4, int spw)
+{
+    return cell == TL_TREELSTM ? ready_kernel_epi<EPI_LSTM_INNER>(vec4, spw) : ready_kernel_epi<EPI_RNN_INNER>(vec4, spw);
+}
+fwd_kernel levels_kernel(int cell, bool vec4, int spw)
+{
+    return cell == TL_TREELSTM ? levels_kernel_epi<EPI_LSTM_INNER>(vec4, spw) : levels_kernel_epi<EPI_RNN_INNER>(vec4, spw);
 }
 tiles_kernel static_kernel(int epi, bool vec4)
 {
@@ -100,11 +127,12 @@ template <typename K> int allow_lds(K kernel)
 }
 
 // Packs one weight matrix [SEG*L x NG*H] and its bias; fills the Gemm descriptor.
-int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, Gemm *g, void **wp_out,
-              float **bp_out)
+int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, int min_steps, Gemm *g,
+              void **wp_out, float **bp_out)
 {
     const int Lp = round_up(L, 4);
-    const int Kp = round_up(SEG * Lp, KC);
+    int Kp = round_up(SEG * Lp, KC);
+    if (Kp < min_steps * STEP_K) Kp = min_steps * STEP_K;   // the weight-stationary cell wants exactly 4 * SPW k-steps
     const int n_steps = Kp / STEP_K;
     const size_t n_w = (size_t)n_cg * n_steps * NG * 64 * 4;
     float *wp = nullptr, *bp = nullptr;
@@ -197,38 +225,56 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     TL_HIP(hipMalloc(&ctx->emb, emb_bytes));
     TL_HIP(hipMemcpy(ctx->emb, cfg->emb, emb_bytes, hipMemcpyDeviceToDevice));
 
+    // Weight-stationary cell: needs 16-byte aligned rows (H % 4 == 0) and at most 16 k-steps per wave.
+    {
+        const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
+        ctx->spw = 0;
+        if (H % 4 == 0 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
+            for (int sz : WS_SIZES)
+                if (sz >= needed) { ctx->spw = sz; break; }
+    }
     int rc;
     if (cfg->cell == TL_TREELSTM) {
-        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 0, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
         if (rc != TL_OK) return rc;
-        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, 4 * ctx->spw, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     } else {
-        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, 4 * ctx->spw, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     }
     TL_HIP(hipDeviceSynchronize());
 
-    // every kernel instantiation that stages tiles needs more than the default LDS limit
+    // every kernel that stages tiles needs more than the default LDS limit
     for (int v = 0; v < 2; ++v) {
-        for (int cell = 0; cell < 2; ++cell) {
-            if ((rc = allow_lds(ready_kernel(cell, v))) != TL_OK) return rc;
-            if ((rc = allow_lds(levels_kernel(cell, v))) != TL_OK) return rc;
-        }
+        if ((rc = allow_lds(ready_kernel(cfg->cell, v, 0))) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0))) != TL_OK) return rc;
         for (int epi = 0; epi < 3; ++epi)
             if ((rc = allow_lds(static_kernel(epi, v))) != TL_OK) return rc;
     }
     int occ = 0;
-    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true)),
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, 0)),
                                                         WG_THREADS, TILE_SMEM_BYTES));
     int occ2 = 0;
-    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, false)),
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, false, 0)),
                                                         WG_THREADS, TILE_SMEM_BYTES));
     if (occ2 < occ) occ = occ2;
     if (occ < 1) return TL_EHIP;
     if (occ > 2) occ = 2;
-    ctx->persistent_grid = occ * ctx->n_cu / N_XCD * N_XCD;
-    if (ctx->persistent_grid < N_XCD) return TL_EHIP;
+    ctx->persistent_grid = occ * ctx->n_cu;
+    if (ctx->spw > 0) {
+        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw))) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw))) != TL_OK) return rc;
+        int o1 = 0, o2 = 0;
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw)),
+                                                            WG_THREADS, TILE_SMEM_BYTES));
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw)),
+                                                            WG_THREADS, TILE_SMEM_BYTES));
+        if (o2 < o1) o1 = o2;
+        if (o1 > 2) o1 = 2;
+        ctx->ws_grid = o1 * ctx->n_cu;
+        if (o1 < 1 || ctx->ws_grid < ctx->n_cg + 1) ctx->spw = 0;
+    }
 
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
     return TL_OK;
@@ -294,13 +340,16 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
     carve_workspace(ctx, &f);
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
-    const int grid_p = ctx->persistent_grid;
+    const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
+    const int spw = vec4_inner ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
+    const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
+    const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
-    f.gang_size = ctx->n_cg < grid_p ? ctx->n_cg : grid_p;
-    f.n_gangs = grid_p / f.gang_size < MAX_GANGS ? grid_p / f.gang_size : MAX_GANGS;
+    // ready scheduler: gangs of gang_size compute workgroups plus one scheduler workgroup each
+    f.gang_size = ctx->n_cg + 1 <= grid_p ? ctx->n_cg : grid_p - 1;
+    f.n_gangs = grid_p / (f.gang_size + 1) < MAX_GANGS ? grid_p / (f.gang_size + 1) : MAX_GANGS;
 
     const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
-    const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : EPI_RNN_INNER;
     const bool prof = ctx->profiling != 0;
@@ -345,12 +394,14 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     // ---- internal nodes ------------------------------------------------------------------
     if (f.n_int > 0) {
         if (cfg.scheduler == TL_SCHED_READY) {
-            const int grid_r = f.n_gangs * f.gang_size;
-            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner), dim3(grid_r), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            const int grid_r = f.n_gangs * (f.gang_size + 1);
+            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw), dim3(grid_r), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
-            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner), dim3(grid_p), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
-            ctx->last_grid = grid_p;
+            // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
+            const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
+            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw), dim3(grid_l), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists
             if ((rc = read_ctl(ctx)) != TL_OK) return rc;
