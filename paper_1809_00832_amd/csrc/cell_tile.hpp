@@ -49,8 +49,8 @@ __device__ inline float tanh_f(float x)
 }
 
 // Fills node/src0/src1 of one row.  Rows without a node are marked unused.  Caller synchronises.
-template <int EPI>
-__device__ inline void tile_set_rows(TileSmem &sm, const Fwd &f, int row, int node)
+template <int EPI, typename Smem>
+__device__ inline void tile_set_rows(Smem &sm, const Fwd &f, int row, int node)
 {
     if (row >= TILE_ROWS) return;
     int s0 = -1, s1 = -1;

@@ -5,12 +5,18 @@
 // HU hidden units for the whole forward and keeps its slice of U in registers: the K axis is
 // split between the four waves, and each wave holds SPW k-steps x NG gates of MFMA B operands
 // (up to 16 x 5 x 4 = 320 VGPRs of the 512 a wave may use when one wave per SIMD is resident).
-// Per block of 16 rows a wave then loads only its part of the gathered A rows, runs SPW x NG x 4
-// MFMAs on register operands, and the four partial sums meet in LDS, from where each wave
-// finishes four of the sixteen rows (gate functions, c update, h/c stores).  The weights are
-// read from memory once per forward instead of once per tile, which removes the L2 -> CU traffic
-// that bounds small tiles, and a 16-row block costs SPW x NG x 4 MFMAs of latency however few
-// rows are ready.
+// The weights are read from memory once per forward instead of once per tile, which removes the
+// L2 -> CU traffic that bounds small tiles, and a 16-row block costs SPW x NG x 4 MFMAs of
+// latency however few rows are ready.
+//
+// Per block of 16 rows a wave
+//   1. has requested its K range of the 16 gathered child rows one block earlier, with loads in
+//      which consecutive lanes read consecutive 16 bytes of a row (a lane-per-row gather in MFMA
+//      operand order costs one memory transaction per lane and throttles instruction issue);
+//   2. parks them in its private LDS region and reads them back in MFMA operand order;
+//   3. runs SPW x NG x 4 MFMAs on LDS-fed A and register-resident B operands;
+//   4. meets the other three waves' partial sums in LDS and finishes four of the sixteen rows
+//      (gate functions, c update, h/c stores).
 //
 // The summation order of a node is fixed (each wave walks its K range in order, the four partial
 // sums are added in wave order), so a node's result does not depend on which rows happened to
@@ -24,9 +30,19 @@
 
 namespace tl {
 
-constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;
-static_assert(2 * WS_RED_FLOATS * sizeof(float) <= sizeof(TileSmem::a) + sizeof(TileSmem::b), "reduction buffers must fit the staging area");
-static_assert(offsetof(TileSmem, b) == sizeof(TileSmem::a), "staging area must be contiguous");
+constexpr int WS_MAX_SPW = 16;
+constexpr int WS_A_LD = STEP_K * WS_MAX_SPW + 4;          // LDS row stride of a wave's A block, floats
+constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;     // one reduction buffer: [wave][gate][v][lane]
+
+// LDS of the persistent kernels that use this cell.
+struct WsSmem {
+    float a[4][16 * WS_A_LD];          // per wave: its K range of the block's 16 gathered rows
+    float red[2][WS_RED_FLOATS];       // K-split partial sums, alternating per block
+    int node[TILE_ROWS];               // same row tables as TileSmem
+    int src0[TILE_ROWS];
+    int src1[TILE_ROWS];
+    int cmd[8];
+};
 
 template <int NG, int SPW> struct WsWeights {
     floatx4 b[SPW][NG];
@@ -48,62 +64,117 @@ __device__ inline void ws_load(WsWeights<NG, SPW> &w, const Gemm &gm, int cg, in
     for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
 }
 
+// Geometry of the coalesced row loads of one wave: its K range is 16*SPW floats = LPR lanes of
+// 16 bytes; RPL rows fit into one 64-lane load; NL loads cover the 16 rows of a block.
+template <int SPW> struct WsLoadGeom {
+    static constexpr int LPR = 4 * SPW;
+    static constexpr int RPL = 64 / LPR;
+    static constexpr int NL = (16 + RPL - 1) / RPL;
+};
+
+// Requests of this wave's K range of 16 rows of the tile, with consecutive lanes on consecutive
+// 16 bytes of a row.  Lanes on the K padding read zeros (they meet zero weights, but 0 * garbage
+// could be NaN); rows that do not exist read row 0 instead: every MFMA output row depends on its
+// own A row only, and the results of such rows are never stored.  Both choices are invariant
+// per lane, so one request is a multiply-add and a load.
+template <int SEG, int SPW> struct WsRowRequest {
+    using G = WsLoadGeom<SPW>;
+    const float *base;
+    unsigned stride;
+    int seg, sub;
+    unsigned at[G::NL];
+
+    __device__ inline void init(const Fwd &f, const Gemm &gm, const float *__restrict__ table, int wave, int lane)
+    {
+        sub = lane / G::LPR;                                    // which of the RPL rows of a load
+        const int k = STEP_K * SPW * wave + (lane % G::LPR) * 4;  // position on the padded K axis
+        seg = (SEG == 2 && k >= gm.Lp) ? 1 : 0;
+        const int off = k - seg * gm.Lp;
+        const bool lane_ok = sub < G::RPL && off < gm.L;
+        base = lane_ok ? table + off : f.zeros;
+        stride = lane_ok ? (unsigned)gm.L : 0u;
+    }
+    // source rows of block [row0, row0+16): one batch of row-table reads
+    template <typename Smem> __device__ inline void prepare(const Smem &sm, int row0, bool any)
+    {
+#pragma unroll
+        for (int j = 0; j < G::NL; ++j) {
+            const int row = (row0 + j * G::RPL + sub) & (TILE_ROWS - 1);
+            const int a0 = sm.src0[row], a1 = sm.src1[row];     // -1 beyond the tile's rows
+            at[j] = any ? (unsigned)max(seg ? a1 : a0, 0) : 0u;
+        }
+    }
+    template <bool COH> __device__ inline floatx4 issue(int j) const { return ld_f4<COH>(base + (size_t)at[j] * stride); }
+};
+
+// Parks requested rows in the wave's LDS region (row-major, stride WS_A_LD).
+template <int SPW, typename Smem>
+__device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<SPW>::NL], int wave, int lane)
+{
+    using G = WsLoadGeom<SPW>;
+    const int sub = lane / G::LPR, kk = (lane % G::LPR) * 4;
+#pragma unroll
+    for (int j = 0; j < G::NL; ++j) {
+        const int r = j * G::RPL + sub;
+        if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WS_A_LD + kk]) = regs[j];
+    }
+}
+
 // Evaluates the `count` rows in sm.node/src0/src1 for column group cg.  All four waves call it
 // together; a __syncthreads() has been passed since the row tables were written.
 template <int EPI, bool COH, int SPW>
-__device__ inline void ws_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
+__device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
                                int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
+    constexpr int NL = WsLoadGeom<SPW>::NL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nrb = (count + 15) >> 4;
-    const int L = gm.L, Lp = gm.Lp, H = f.H;
+    const int H = f.H;
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
-    const int k0 = STEP_K * wave * SPW + (lane >> 4) * 4;
-    // A operands of block rb+1 are requested while block rb is being multiplied: as soon as the
-    // MFMAs of a k-step have consumed a[s], the same registers are re-loaded for the next block
-    // (the register file has no room for a second copy next to the weights).
-    floatx4 a[SPW];
-    {
-        const int row = lane & 15;
-        const int s0 = sm.src0[row], s1 = sm.src1[row];     // -1 beyond count
+    const float *a_lane = &sm.a[wave][(lane & 15) * WS_A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
+
+    WsRowRequest<SEG, SPW> req;
+    req.init(f, gm, table, wave, lane);
+    floatx4 rows[NL];
+    req.prepare(sm, 0, true);
 #pragma unroll
-        for (int s = 0; s < SPW; ++s)
-            a[s] = load_a_granule<SEG, true, COH>(table, f.zeros, L, Lp, s0, s1, k0 + s * STEP_K);
-    }
+    for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
     for (int rb = 0; rb < nrb; ++rb) {
-        // [wave][g][v][lane], 20 KB, alternating between two buffers laid over the (unused) A/B staging area
-        float *red = reinterpret_cast<float *>(&sm) + (rb & 1) * WS_RED_FLOATS;
-        // rows of the next block (none: gather zeros)
-        const int nrow = (rb + 1) * 16 + (lane & 15);
-        const bool has_next = rb + 1 < nrb;
-        const int ns0 = has_next ? sm.src0[nrow & (TILE_ROWS - 1)] : -1;
-        const int ns1 = has_next ? sm.src1[nrow & (TILE_ROWS - 1)] : -1;
-        // the row this lane finishes after the reduction, and its c operands (requested early)
+        float *red = sm.red[rb & 1];
+        ws_park_rows<SPW>(sm, rows, wave, lane);            // waits for the requested rows
+        // the next block's rows are requested between the k-steps below, one row load per step: the
+        // memory path of a CU takes a 1 KB request every ~160 cycles, a k-step lasts 640
+        req.prepare(sm, (rb + 1) * 16, rb + 1 < nrb);
+        // the row this lane finishes after the reduction, and its c operands
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
         const bool ev = enode >= 0 && hu_ok;
         float cl = 0.f, cr = 0.f;
-        if (EPI == EPI_LSTM_INNER) {
-            cl = ld_f<COH>(ev ? f.c + (size_t)sm.src0[erow] * H + hu : f.zeros);
-            cr = ld_f<COH>(ev ? f.c + (size_t)sm.src1[erow] * H + hu : f.zeros);
+        if (EPI == EPI_LSTM_INNER) {                        // unused lanes read some existing element; the value is dropped
+            const int hc = hu_ok ? hu : 0;
+            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (TILE_ROWS - 1)], 0) * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (TILE_ROWS - 1)], 0) * H + hc);
         }
+        __builtin_amdgcn_sched_barrier(0);                  // all requests are issued before the MFMAs start
         floatx4 acc[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-        __builtin_amdgcn_sched_barrier(0);
+        constexpr int LOADS_PER_STEP = (NL + SPW - 1) / SPW;
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
+            const floatx4 av = *reinterpret_cast<const floatx4 *>(a_lane + s * STEP_K);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int g = 0; g < NG; ++g)
-                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s][i], w.b[s][g][i], acc[g], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            a[s] = load_a_granule<SEG, true, COH>(table, f.zeros, L, Lp, ns0, ns1, k0 + s * STEP_K);
-            __builtin_amdgcn_sched_barrier(0);
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], w.b[s][g][i], acc[g], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < LOADS_PER_STEP; ++q)
+                if (s * LOADS_PER_STEP + q < NL) rows[s * LOADS_PER_STEP + q] = req.template issue<COH>(s * LOADS_PER_STEP + q);
+            __builtin_amdgcn_sched_barrier(0);              // keep the request where it is
         }
         // the four K-range partial sums meet in LDS; wave w finishes accumulator row w
 #pragma unroll
@@ -142,8 +213,8 @@ __device__ inline void ws_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const
                 st_f<COH>(f.h + o, tanh_f(gate[0]));
             }
         }
-        // no second barrier: the next block writes the other half of the reduction buffer, and the
-        // block after that passes the next block's barrier before it writes this half again
+        // no second barrier: the next block writes the other reduction buffer, and the block after
+        // that passes the next block's barrier before it writes this one again
     }
     __syncthreads();                                        // row tables and LDS may be rewritten after this call
 }

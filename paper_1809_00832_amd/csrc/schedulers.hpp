@@ -1,6 +1,8 @@
 // The three ways internal nodes reach the fused cell (enum tl_scheduler), plus the leaf kernel.
 #pragma once
 
+#include <type_traits>
+
 #include "cell_ws.hpp"
 
 namespace tl {
@@ -48,7 +50,7 @@ __global__ void k_leaf_copy(Fwd f)
 // Data visibility does not come from the barrier: callers write shared data with device-scope
 // stores and call wait_mem() first.  Returns false if the wait was abandoned (spin budget
 // exhausted somewhere); every workgroup then leaves the kernel.
-__device__ inline bool grid_barrier(TileSmem &sm, const Fwd &f, unsigned &epoch)
+template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch)
 {
     Ctl *ctl = f.ctl;
     wait_mem();
@@ -89,7 +91,8 @@ template <int EPI, bool VEC4, int SPW>
 __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
+    using Smem = std::conditional_t<(SPW > 0), WsSmem, TileSmem>;
+    Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     if (f.ctl->status != 0) return;
     const int n_levels = f.ctl->n_levels;
     const int tid = threadIdx.x;
@@ -269,7 +272,8 @@ template <int EPI, bool VEC4, int SPW>
 __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
+    using Smem = std::conditional_t<(SPW > 0), WsSmem, TileSmem>;
+    Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
     if (ctl->status != 0) return;
     const int tid = threadIdx.x;

@@ -119,10 +119,9 @@ tiles_kernel static_kernel(int epi, bool vec4)
     }
 }
 
-template <typename K> int allow_lds(K kernel)
+template <typename K> int allow_lds(K kernel, size_t bytes = TILE_SMEM_BYTES)
 {
-    TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)TILE_SMEM_BYTES));
+    TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
     return TL_OK;
 }
 
@@ -164,7 +163,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 256;
+    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
     TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
@@ -192,7 +191,7 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
     f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
-    f->zeros = (const float *)take(256);
+    f->zeros = (const float *)take(4096);
 }
 
 void free_all(tl_ctx *ctx)
@@ -263,13 +262,14 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     if (occ > 2) occ = 2;
     ctx->persistent_grid = occ * ctx->n_cu;
     if (ctx->spw > 0) {
-        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw))) != TL_OK) return rc;
-        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw))) != TL_OK) return rc;
+        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw), sizeof(WsSmem))) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw), sizeof(WsSmem))) != TL_OK) return rc;
         int o1 = 0, o2 = 0;
         TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw)),
-                                                            WG_THREADS, TILE_SMEM_BYTES));
+                                                            WG_THREADS, sizeof(WsSmem)));
         TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw)),
-                                                            WG_THREADS, TILE_SMEM_BYTES));
+                                                            WG_THREADS, sizeof(WsSmem)));
+        if (o1 > 1) o1 = 1;   // the cell is written for one workgroup per CU
         if (o2 < o1) o1 = o2;
         if (o1 > 2) o1 = 2;
         ctx->ws_grid = o1 * ctx->n_cu;
@@ -395,12 +395,14 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     if (f.n_int > 0) {
         if (cfg.scheduler == TL_SCHED_READY) {
             const int grid_r = f.n_gangs * (f.gang_size + 1);
-            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw), dim3(grid_r), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw), dim3(grid_r), dim3(WG_THREADS),
+                               spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw), dim3(grid_l), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f);
+            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw), dim3(grid_l), dim3(WG_THREADS),
+                               spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists
