@@ -306,15 +306,109 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
     if (active) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
 }
 
+// ---- staged path with bfloat16 operands ---------------------------------------------------
+// Same data flow as above for 1..64 rows, but the MFMA operands are bfloat16: the gathered rows
+// are rounded to nearest-even when they are stored to LDS (v_cvt_pk_bf16_f32), the weights were
+// rounded when they were packed, and one v_mfma_f32_16x16x32_bf16 per gate consumes 32 k at a
+// time.  Accumulators, gate functions, c and the stored h stay fp32.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+constexpr int A_LD_BF = KC + 8;      // LDS row stride of the bf16 A chunk, in elements (144 bytes)
+
+template <int EPI, bool VEC4, bool COH>
+__device__ inline void cell_tile_staged_bf16(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
+                                             int count, int cg)
+{
+    constexpr int NG = EpiTraits<EPI>::NG;
+    constexpr int SEG = EpiTraits<EPI>::SEG;
+    constexpr int STEPS = KC / 32;              // 2 k-steps of 32 per chunk
+    constexpr int B_UNITS = STEPS * NG * 64;    // 16-byte units of one B chunk
+    constexpr int B_PER_THREAD = (B_UNITS + WG_THREADS - 1) / WG_THREADS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nrb = (count + 15) >> 4;
+    const int rb = wave;
+    const bool active = rb < nrb;
+    const int L = gm.L, Lp = gm.Lp;
+    const int n_steps = gm.n_chunks * STEPS;
+    const floatx4 *wp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * n_steps * NG * 64;
+    __bf16 *a_lds[2] = {reinterpret_cast<__bf16 *>(&sm.a[0][0]), reinterpret_cast<__bf16 *>(&sm.a[1][0])};
+    floatx4 *b_lds[2] = {&sm.b[0][0], &sm.b[1][0]};
+
+    floatx4 acc[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    floatx4 ra[4], rbuf[B_PER_THREAD];
+    const int a_row0 = tid >> 4, a_k4 = tid & 15;
+    int s0[4], s1[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int row = a_row0 + 16 * j;
+        s0[j] = row < nrb * 16 ? sm.src0[row] : -1;
+        s1[j] = row < nrb * 16 ? sm.src1[row] : -1;
+    }
+    auto load_chunk = [&](int chunk) {
+        const int k = chunk * KC + a_k4 * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nrb) ra[j] = load_a_granule<SEG, VEC4, COH>(table, f.zeros, L, Lp, s0[j], s1[j], k);
+        const floatx4 *src = wp + (size_t)chunk * B_UNITS;
+#pragma unroll
+        for (int j = 0; j < B_PER_THREAD; ++j) {
+            const int u = tid + WG_THREADS * j;
+            rbuf[j] = src[u < B_UNITS ? u : 0];
+        }
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nrb)
+                *reinterpret_cast<bf16x4 *>(&a_lds[buf][(a_row0 + 16 * j) * A_LD_BF + a_k4 * 4]) =
+                    __builtin_convertvector(ra[j], bf16x4);
+#pragma unroll
+        for (int j = 0; j < B_PER_THREAD; ++j) {
+            const int u = tid + WG_THREADS * j;
+            if (u < B_UNITS) b_lds[buf][u] = rbuf[j];
+        }
+    };
+
+    load_chunk(0);
+    store_chunk(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < gm.n_chunks; ++chunk) {
+        const int buf = chunk & 1;
+        const bool more = chunk + 1 < gm.n_chunks;
+        if (more) load_chunk(chunk + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (active) {
+            const __bf16 *arow = &a_lds[buf][(rb * 16 + (lane & 15)) * A_LD_BF + (lane >> 4) * 8];
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const bf16x8 av = *reinterpret_cast<const bf16x8 *>(arow + s * 32);
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&b_lds[buf][(s * NG + g) * 64 + lane]);
+                    acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[g], 0, 0, 0);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) store_chunk(buf ^ 1);
+        __syncthreads();
+    }
+    if (active) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
+}
+
 // The tile.  All WG_THREADS threads of the workgroup call it together; sm.node/src0/src1 hold
 // the rows (see tile_set_rows) and a __syncthreads() has been passed since they were written.
 //   table : source rows of the gather (embedding table, or h)
 //   count : rows in use (1..TILE_ROWS);  cg : column group
-template <int EPI, bool VEC4, bool COH>
+template <int EPI, bool VEC4, bool COH, bool BF16 = false>
 __device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
                                  int count, int cg)
 {
-    if (count <= 32) cell_tile_direct<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
+    if constexpr (BF16) cell_tile_staged_bf16<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
+    else if (count <= 32) cell_tile_direct<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     else cell_tile_staged<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     __syncthreads();   // the row tables and the LDS buffers may be rewritten after this call
 }

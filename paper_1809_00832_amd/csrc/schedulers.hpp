@@ -13,7 +13,7 @@ namespace tl {
 // notes that the (N+1)/2 leaves of a tree are mutually independent) and by the host-driven
 // level scheduler, one launch per height.  Kernel boundaries order producers and consumers,
 // so plain cached loads and stores are used.
-template <int EPI, bool VEC4>
+template <int EPI, bool VEC4, bool BF16>
 __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int32_t *__restrict__ list, int total,
                                                                 LevelPlan plan)
 {
@@ -29,7 +29,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int
     __syncthreads();
     const Gemm &gm = EPI == EPI_LSTM_LEAF ? f.leaf : f.inner;
     const float *table = EPI == EPI_LSTM_LEAF ? f.emb : f.h;
-    cell_tile<EPI, VEC4, false>(sm, f, gm, table, count, cg);
+    cell_tile<EPI, VEC4, false, BF16>(sm, f, gm, table, count, cg);
 }
 
 // Leaves of TreeRNN / RNTN: h = embedding row.
@@ -87,7 +87,7 @@ template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd
 // depth-wise batching of Section 6.3, without a launch or a host round trip per depth).
 // SPW > 0 selects the weight-stationary cell (cell_ws.hpp, SPW k-steps per wave in registers,
 // one workgroup per CU, every workgroup tied to one column group); SPW == 0 the streaming cell.
-template <int EPI, bool VEC4, int SPW>
+template <int EPI, bool VEC4, int SPW, bool BF16 = false>
 __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persiste
                 plan_tile(plan, rows, tile, &start, &count);
                 tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
                 __syncthreads();
-                cell_tile<EPI, VEC4, true>(sm, f, f.inner, f.h, count, cg);
+                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, cg);
             }
         }
         if (lvl + 1 < n_levels && !grid_barrier(sm, f, epoch)) return;
@@ -268,7 +268,7 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
     if (lane == 0) add_dev(&ctl->tiles.v, published);
 }
 
-template <int EPI, bool VEC4, int SPW>
+template <int EPI, bool VEC4, int SPW, bool BF16 = false>
 __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persisten
             ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
         } else {
             for (int j = member; j < f.n_cg; j += f.gang_size)
-                cell_tile<EPI, VEC4, true>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
+                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
         }
 
         // ---- completion: the tile's h/c rows are in memory before the scheduler hears of it -----

@@ -78,8 +78,9 @@ typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
 // Steps per wave that the weight-stationary cell is instantiated for; 0 = streaming cell.
 const int WS_SIZES[] = {1, 2, 4, 5, 8, 16};
 
-template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw)
+template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw, bool bf16)
 {
+    if (bf16) return vec4 ? k_ready_persistent<EPI, true, 0, true> : k_ready_persistent<EPI, false, 0, true>;
     switch (spw) {
     case 1: return k_ready_persistent<EPI, true, 1>;
     case 2: return k_ready_persistent<EPI, true, 2>;
@@ -90,8 +91,9 @@ template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw)
     default: return vec4 ? k_ready_persistent<EPI, true, 0> : k_ready_persistent<EPI, false, 0>;
     }
 }
-template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw)
+template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw, bool bf16)
 {
+    if (bf16) return vec4 ? k_levels_persistent<EPI, true, 0, true> : k_levels_persistent<EPI, false, 0, true>;
     switch (spw) {
     case 1: return k_levels_persistent<EPI, true, 1>;
     case 2: return k_levels_persistent<EPI, true, 2>;
@@ -102,21 +104,25 @@ template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw)
     default: return vec4 ? k_levels_persistent<EPI, true, 0> : k_levels_persistent<EPI, false, 0>;
     }
 }
-fwd_kernel ready_kernel(int cell, bool vec4, int spw)
+fwd_kernel ready_kernel(int cell, bool vec4, int spw, bool bf16)
 {
-    return cell == TL_TREELSTM ? ready_kernel_epi<EPI_LSTM_INNER>(vec4, spw) : ready_kernel_epi<EPI_RNN_INNER>(vec4, spw);
+    return cell == TL_TREELSTM ? ready_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : ready_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
 }
-fwd_kernel levels_kernel(int cell, bool vec4, int spw)
+fwd_kernel levels_kernel(int cell, bool vec4, int spw, bool bf16)
 {
-    return cell == TL_TREELSTM ? levels_kernel_epi<EPI_LSTM_INNER>(vec4, spw) : levels_kernel_epi<EPI_RNN_INNER>(vec4, spw);
+    return cell == TL_TREELSTM ? levels_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : levels_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
 }
-tiles_kernel static_kernel(int epi, bool vec4)
+template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
 {
     switch (epi) {
-    case EPI_LSTM_LEAF: return vec4 ? k_tiles_static<EPI_LSTM_LEAF, true> : k_tiles_static<EPI_LSTM_LEAF, false>;
-    case EPI_LSTM_INNER: return vec4 ? k_tiles_static<EPI_LSTM_INNER, true> : k_tiles_static<EPI_LSTM_INNER, false>;
-    default: return vec4 ? k_tiles_static<EPI_RNN_INNER, true> : k_tiles_static<EPI_RNN_INNER, false>;
+    case EPI_LSTM_LEAF: return vec4 ? k_tiles_static<EPI_LSTM_LEAF, true, BF16> : k_tiles_static<EPI_LSTM_LEAF, false, BF16>;
+    case EPI_LSTM_INNER: return vec4 ? k_tiles_static<EPI_LSTM_INNER, true, BF16> : k_tiles_static<EPI_LSTM_INNER, false, BF16>;
+    default: return vec4 ? k_tiles_static<EPI_RNN_INNER, true, BF16> : k_tiles_static<EPI_RNN_INNER, false, BF16>;
     }
+}
+tiles_kernel static_kernel(int epi, bool vec4, bool bf16)
+{
+    return bf16 ? static_kernel_p<true>(epi, vec4) : static_kernel_p<false>(epi, vec4);
 }
 
 template <typename K> int allow_lds(K kernel, size_t bytes = TILE_SMEM_BYTES)
@@ -126,7 +132,7 @@ template <typename K> int allow_lds(K kernel, size_t bytes = TILE_SMEM_BYTES)
 }
 
 // Packs one weight matrix [SEG*L x NG*H] and its bias; fills the Gemm descriptor.
-int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, int min_steps, Gemm *g,
+int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, int min_steps, bool bf16, Gemm *g,
               void **wp_out, float **bp_out)
 {
     const int Lp = round_up(L, 4);
@@ -134,10 +140,14 @@ int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int
     if (Kp < min_steps * STEP_K) Kp = min_steps * STEP_K;   // the weight-stationary cell wants exactly 4 * SPW k-steps
     const int n_steps = Kp / STEP_K;
     const size_t n_w = (size_t)n_cg * n_steps * NG * 64 * 4;
-    float *wp = nullptr, *bp = nullptr;
-    TL_HIP(hipMalloc(&wp, n_w * sizeof(float)));
+    void *wp = nullptr;
+    float *bp = nullptr;
+    TL_HIP(hipMalloc(&wp, n_w * (bf16 ? sizeof(unsigned short) : sizeof(float))));
     TL_HIP(hipMalloc(&bp, (size_t)n_cg * NG * HU * sizeof(float)));
-    hipLaunchKernelGGL(k_pack_f32, dim3(1024), dim3(256), 0, 0, w, wp, NG, H, SEG, L, Lp, n_steps, n_cg);
+    if (bf16)
+        hipLaunchKernelGGL(k_pack_bf16, dim3(1024), dim3(256), 0, 0, w, (unsigned short *)wp, NG, H, SEG, L, Lp, n_steps / 2, n_cg);
+    else
+        hipLaunchKernelGGL(k_pack_f32, dim3(1024), dim3(256), 0, 0, w, (float *)wp, NG, H, SEG, L, Lp, n_steps, n_cg);
     hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, 0, b, bp, NG, H, n_cg);
     TL_HIP(hipGetLastError());
     g->wp = wp;
@@ -228,46 +238,47 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     {
         const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
         ctx->spw = 0;
-        if (H % 4 == 0 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
+        if (H % 4 == 0 && cfg->precision == TL_F32 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
             for (int sz : WS_SIZES)
                 if (sz >= needed) { ctx->spw = sz; break; }
     }
+    const bool bf16 = cfg->precision == TL_BF16_IN;
     int rc;
     if (cfg->cell == TL_TREELSTM) {
-        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 0, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 0, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
         if (rc != TL_OK) return rc;
-        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, 4 * ctx->spw, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     } else {
-        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, 4 * ctx->spw, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     }
     TL_HIP(hipDeviceSynchronize());
 
     // every kernel that stages tiles needs more than the default LDS limit
     for (int v = 0; v < 2; ++v) {
-        if ((rc = allow_lds(ready_kernel(cfg->cell, v, 0))) != TL_OK) return rc;
-        if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0))) != TL_OK) return rc;
+        if ((rc = allow_lds(ready_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
         for (int epi = 0; epi < 3; ++epi)
-            if ((rc = allow_lds(static_kernel(epi, v))) != TL_OK) return rc;
+            if ((rc = allow_lds(static_kernel(epi, v, bf16))) != TL_OK) return rc;
     }
     int occ = 0;
-    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, 0)),
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, 0, bf16)),
                                                         WG_THREADS, TILE_SMEM_BYTES));
     int occ2 = 0;
-    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, false, 0)),
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, false, 0, bf16)),
                                                         WG_THREADS, TILE_SMEM_BYTES));
     if (occ2 < occ) occ = occ2;
     if (occ < 1) return TL_EHIP;
     if (occ > 2) occ = 2;
     ctx->persistent_grid = occ * ctx->n_cu;
     if (ctx->spw > 0) {
-        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw), sizeof(WsSmem))) != TL_OK) return rc;
-        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw), sizeof(WsSmem))) != TL_OK) return rc;
+        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw, false), sizeof(WsSmem))) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw, false), sizeof(WsSmem))) != TL_OK) return rc;
         int o1 = 0, o2 = 0;
-        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw)),
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw, false)),
                                                             WG_THREADS, sizeof(WsSmem)));
-        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw)),
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw, false)),
                                                             WG_THREADS, sizeof(WsSmem)));
         if (o1 > 1) o1 = 1;   // the cell is written for one workgroup per CU
         if (o2 < o1) o1 = o2;
@@ -296,7 +307,7 @@ int tl_create(const tl_config *cfg, tl_ctx **out)
     if (!cfg || !out) return TL_EINVAL;
     *out = nullptr;
     if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN) return TL_EINVAL;   // TL_RNTN: not available yet
-    if (cfg->precision != TL_F32) return TL_EINVAL;                               // TL_BF16_IN: not available yet
+    if (cfg->precision != TL_F32 && cfg->precision != TL_BF16_IN) return TL_EINVAL;
     if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_LEVEL_HOST) return TL_EINVAL;
     if (cfg->vocab < 1 || cfg->embed_dim < 1 || cfg->hidden < 1 || cfg->spin_limit < 0) return TL_EINVAL;
     if (cfg->hidden > (1 << 14) || cfg->embed_dim > (1 << 16)) return TL_EINVAL;
@@ -335,7 +346,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.tree_off = tree_off; f.left = left; f.right = right; f.word = word;
     f.h = h; f.c = cfg.cell == TL_TREELSTM ? c : nullptr;
     f.h_root = h_root; f.c_root = c_root; f.root_out = root;
-    f.cell = cfg.cell; f.H = cfg.hidden; f.E = cfg.embed_dim; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg; f.bf16 = 0;
+    f.cell = cfg.cell; f.H = cfg.hidden; f.E = cfg.embed_dim; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg; f.bf16 = cfg.precision == TL_BF16_IN;
     f.emb = ctx->emb;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
     carve_workspace(ctx, &f);
@@ -352,6 +363,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : EPI_RNN_INNER;
+    const bool bf16 = cfg.precision == TL_BF16_IN;
     const bool prof = ctx->profiling != 0;
     const int nb_nodes = (n_nodes + 1 + 255) / 256;
 
@@ -383,7 +395,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     // ---- leaves ------------------------------------------------------------------------
     if (cfg.cell == TL_TREELSTM) {
         const LevelPlan plan = plan_level(f.n_leaf, f.cap_tiles);
-        hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+        hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
                            TILE_SMEM_BYTES, st, f, (const int32_t *)f.leaf_list, f.n_leaf, plan);
     } else {
         hipLaunchKernelGGL(k_leaf_copy, dim3(f.n_leaf), dim3(128), 0, st, f);
@@ -395,13 +407,13 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     if (f.n_int > 0) {
         if (cfg.scheduler == TL_SCHED_READY) {
             const int grid_r = f.n_gangs * (f.gang_size + 1);
-            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw), dim3(grid_r), dim3(WG_THREADS),
+            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_r), dim3(WG_THREADS),
                                spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw), dim3(grid_l), dim3(WG_THREADS),
+            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_l), dim3(WG_THREADS),
                                spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_l;
         } else {
@@ -416,7 +428,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
                     const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
                     if (rows <= 0 || lo < 0 || lo + rows > f.n_int) return TL_EHIP;
                     const LevelPlan plan = plan_level(rows, f.cap_tiles);
-                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
                                        TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, plan);
                     if (plan.n_tiles * ctx->n_cg > max_grid) max_grid = plan.n_tiles * ctx->n_cg;
                 }

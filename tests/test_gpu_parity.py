@@ -153,3 +153,46 @@ def test_repeated_forward_is_stable():
             assert_close(net.batch["c"].cpu().numpy(), ref["c"], "c iter %d" % it)
     finally:
         net.close()
+
+
+# ----------------------------------------------------------------------------- bf16-operand path
+def bf16_reference(name):
+    """Checker run on bf16-representable weights / embeddings with bf16 rounding of the gathered operand."""
+    key = name + "/bf16"
+    if key not in _ref_cache:
+        w = synth.workload(name)
+        p = w.params
+        q = synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, oracle.to_bf16(p.emb),
+                         None if p.w_leaf is None else oracle.to_bf16(p.w_leaf), p.b_leaf, oracle.to_bf16(p.u), p.b,
+                         None if p.v is None else oracle.to_bf16(p.v))
+        _ref_cache[key] = (w, oracle.forward_params(q, w.trees, n_threads=8, round_bf16=True))
+    return _ref_cache[key]
+
+
+def assert_close_bf16(got, ref, what):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = 2e-2 * np.maximum(1.0, np.abs(ref.astype(np.float64)))
+    assert (err <= bound).all(), "%s: max abs err %.3e" % (what, err.max())
+    return float(err.max())
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+@pytest.mark.parametrize("name", ["tiny", "sentence", "treernn", "throughput"])
+def test_bf16_operands_match_oracle(name, sched):
+    """bf16 weights, embeddings and gathered h as matrix operands; fp32 accumulate, gates, c and stored h."""
+    say("case bf16", name, sched)
+    w, ref = bf16_reference(name)
+    net = binding.TreeNet(w.params, scheduler=sched, precision=binding.TL_BF16_IN)
+    try:
+        got = net.run(w.trees)
+        e = assert_close_bf16(got["h"], ref["h"], "h")
+        assert_close_bf16(got["h_root"], ref["h_root"], "h_root")
+        if w.params.cell == CELL_TREELSTM:
+            assert_close_bf16(got["c"], ref["c"], "c")
+        _, root, _ = oracle.structure(w.trees.tree_off, w.trees.left, w.trees.right)
+        assert np.array_equal(got["root"], root)
+        # and the rounding really happens: the result differs from the fp32 path's reference
+        _, ref32 = reference(name)
+        say("   max abs err vs bf16 checker %.3e; distance to fp32 checker %.3e" % (e, np.abs(got["h"] - ref32["h"]).max()))
+    finally:
+        net.close()
