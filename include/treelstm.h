@@ -98,7 +98,8 @@ typedef struct {
                              0..H-1 multiply h_left, rows H..2H-1 multiply h_right.
                              TL_TREERNN / TL_RNTN: W [2d x d].                                    */
     const float *b;       /* TL_TREELSTM: [5H];  TL_TREERNN / TL_RNTN: [d]                        */
-    const float *v;       /* TL_RNTN: [d x 2d x 2d], index order (k, p, q).    Else NULL.         */
+    const float *v;       /* TL_RNTN: [d x 2d x 2d], index order (k, p, q).    Else NULL.
+                             TL_RNTN needs d <= 128 and TL_F32 (else TL_EINVAL).                  */
 } tl_config;
 
 /* Creates a context on the current HIP device.  cfg is HOST memory; *out receives the

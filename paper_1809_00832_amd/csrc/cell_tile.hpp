@@ -22,12 +22,13 @@
 
 namespace tl {
 
-enum Epi { EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2 };
+enum Epi { EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2, EPI_RNTN_INNER = 3 };
 
 template <int EPI> struct EpiTraits;
 template <> struct EpiTraits<EPI_LSTM_LEAF>  { static constexpr int NG = 3, SEG = 1; };
 template <> struct EpiTraits<EPI_LSTM_INNER> { static constexpr int NG = 5, SEG = 2; };
 template <> struct EpiTraits<EPI_RNN_INNER>  { static constexpr int NG = 1, SEG = 2; };
+template <> struct EpiTraits<EPI_RNTN_INNER> { static constexpr int NG = 1, SEG = 2; };
 
 // LDS carve-up (dynamic shared memory, 16-byte aligned).
 struct TileSmem {
@@ -403,11 +404,15 @@ __device__ inline void cell_tile_staged_bf16(TileSmem &sm, const Fwd &f, const G
 // the rows (see tile_set_rows) and a __syncthreads() has been passed since they were written.
 //   table : source rows of the gather (embedding table, or h)
 //   count : rows in use (1..TILE_ROWS);  cg : column group
+template <bool VEC4, bool COH>
+__device__ inline void rntn_tile_any(TileSmem &sm, const Fwd &f, const Gemm &gm, int count, int cg);   // cell_rntn.hpp
+
 template <int EPI, bool VEC4, bool COH, bool BF16 = false>
 __device__ inline void cell_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table,
                                  int count, int cg)
 {
-    if constexpr (BF16) cell_tile_staged_bf16<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
+    if constexpr (EPI == EPI_RNTN_INNER) rntn_tile_any<VEC4, COH>(sm, f, gm, count, cg);
+    else if constexpr (BF16) cell_tile_staged_bf16<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     else if (count <= 32) cell_tile_direct<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     else cell_tile_staged<EPI, VEC4, COH>(sm, f, gm, table, count, cg);
     __syncthreads();   // the row tables and the LDS buffers may be rewritten after this call

@@ -4,6 +4,7 @@
 #include <type_traits>
 
 #include "cell_ws.hpp"
+#include "cell_rntn.hpp"
 
 namespace tl {
 

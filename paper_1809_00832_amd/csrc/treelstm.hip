@@ -106,10 +106,12 @@ template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw, bool bf16)
 }
 fwd_kernel ready_kernel(int cell, bool vec4, int spw, bool bf16)
 {
+    if (cell == TL_RNTN) return vec4 ? k_ready_persistent<EPI_RNTN_INNER, true, 0> : k_ready_persistent<EPI_RNTN_INNER, false, 0>;
     return cell == TL_TREELSTM ? ready_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : ready_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
 }
 fwd_kernel levels_kernel(int cell, bool vec4, int spw, bool bf16)
 {
+    if (cell == TL_RNTN) return vec4 ? k_levels_persistent<EPI_RNTN_INNER, true, 0> : k_levels_persistent<EPI_RNTN_INNER, false, 0>;
     return cell == TL_TREELSTM ? levels_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : levels_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
 }
 template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
@@ -122,6 +124,7 @@ template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
 }
 tiles_kernel static_kernel(int epi, bool vec4, bool bf16)
 {
+    if (epi == EPI_RNTN_INNER) return vec4 ? k_tiles_static<EPI_RNTN_INNER, true, false> : k_tiles_static<EPI_RNTN_INNER, false, false>;
     return bf16 ? static_kernel_p<true>(epi, vec4) : static_kernel_p<false>(epi, vec4);
 }
 
@@ -238,7 +241,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     {
         const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
         ctx->spw = 0;
-        if (H % 4 == 0 && cfg->precision == TL_F32 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
+        if (H % 4 == 0 && cfg->precision == TL_F32 && cfg->cell != TL_RNTN && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
             for (int sz : WS_SIZES)
                 if (sz >= needed) { ctx->spw = sz; break; }
     }
@@ -249,9 +252,28 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if (rc != TL_OK) return rc;
         rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
-    } else {
+    } else if (cfg->cell == TL_TREERNN) {
         rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
+    } else {
+        // RNTN: tensor slices and W packed per column group and q; padded K is 64, 128 or 256
+        const int Lp = round_up(H, 4);
+        int Kp = round_up(2 * Lp, KC);
+        if (Kp > 128) Kp = 256;
+        const size_t n_v = (size_t)ctx->n_cg * (Kp + 1) * (Kp / STEP_K) * 256;
+        float *vp = nullptr, *bp = nullptr;
+        TL_HIP(hipMalloc(&vp, n_v * sizeof(float)));
+        ctx->wp_inner = vp;
+        TL_HIP(hipMalloc(&bp, (size_t)ctx->n_cg * HU * sizeof(float)));
+        ctx->bp_inner = bp;
+        hipLaunchKernelGGL(k_pack_rntn, dim3(2048), dim3(256), 0, 0, cfg->v, cfg->u, vp, H, Lp, Kp, ctx->n_cg);
+        hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, 0, cfg->b, bp, 1, H, ctx->n_cg);
+        TL_HIP(hipGetLastError());
+        ctx->g_inner.wp = vp;
+        ctx->g_inner.bp = bp;
+        ctx->g_inner.L = H;
+        ctx->g_inner.Lp = Lp;
+        ctx->g_inner.n_chunks = Kp / KC;
     }
     TL_HIP(hipDeviceSynchronize());
 
@@ -259,7 +281,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     for (int v = 0; v < 2; ++v) {
         if ((rc = allow_lds(ready_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
         if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
-        for (int epi = 0; epi < 3; ++epi)
+        for (int epi = 0; epi < 4; ++epi)
             if ((rc = allow_lds(static_kernel(epi, v, bf16))) != TL_OK) return rc;
     }
     int occ = 0;
@@ -306,7 +328,8 @@ int tl_create(const tl_config *cfg, tl_ctx **out)
 {
     if (!cfg || !out) return TL_EINVAL;
     *out = nullptr;
-    if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN) return TL_EINVAL;   // TL_RNTN: not available yet
+    if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN && cfg->cell != TL_RNTN) return TL_EINVAL;
+    if (cfg->cell == TL_RNTN && (!cfg->v || cfg->hidden > 128 || cfg->precision != TL_F32)) return TL_EINVAL;
     if (cfg->precision != TL_F32 && cfg->precision != TL_BF16_IN) return TL_EINVAL;
     if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_LEVEL_HOST) return TL_EINVAL;
     if (cfg->vocab < 1 || cfg->embed_dim < 1 || cfg->hidden < 1 || cfg->spin_limit < 0) return TL_EINVAL;
@@ -362,7 +385,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
 
     const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
-    const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : EPI_RNN_INNER;
+    const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
     const bool bf16 = cfg.precision == TL_BF16_IN;
     const bool prof = ctx->profiling != 0;
     const int nb_nodes = (n_nodes + 1 + 255) / 256;

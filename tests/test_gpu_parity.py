@@ -53,7 +53,7 @@ def reference(name):
 
 
 @pytest.mark.parametrize("sched", SCHEDULERS)
-@pytest.mark.parametrize("name", ["tiny", "sentence", "treernn", "throughput"])
+@pytest.mark.parametrize("name", ["tiny", "sentence", "treernn", "rntn", "throughput"])
 def test_workload_matches_oracle(name, sched):
     say("case", name, sched)
     w, ref = reference(name)
@@ -196,3 +196,21 @@ def test_bf16_operands_match_oracle(name, sched):
         say("   max abs err vs bf16 checker %.3e; distance to fp32 checker %.3e" % (e, np.abs(got["h"] - ref32["h"]).max()))
     finally:
         net.close()
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+def test_rntn_other_sizes(sched):
+    """RNTN at d = 20 and d = 96 (padded K of 64 and 256).  Magnitudes are raised so that tanh is not linear,
+    but kept small enough that a level does not amplify rounding differences of its inputs (with large V the
+    recursion is chaotic and no two evaluation orders agree)."""
+    say("case rntn sizes", sched)
+    for d, leaves in ((20, [3, 9, 1, 40]), (96, [5, 2, 70])):
+        p = synth.make_rnn_params(50 + d, synth.CELL_RNTN, 300, d, scale=0.05)
+        p = synth.Params(p.cell, p.vocab, d, d, p.emb * 8, None, None, p.u * 2, p.b + 0.05, p.v * (40.0 / d))
+        trees = synth.make_trees(50 + d, leaves, ["random"] * len(leaves), 300)
+        net = binding.TreeNet(p, scheduler=sched)
+        try:
+            got = net.run(trees)
+            check_against_oracle(p, trees, got, None, "rntn d=%d/%s" % (d, sched))
+        finally:
+            net.close()
