@@ -46,7 +46,26 @@ __device__ inline float tanh_f(float x)
 {
     // 1 - 2/(1+e^{2x}); the clamp keeps e^{2x} finite, beyond it tanh is 1 to fp32 precision
     float t = __expf(2.f * fminf(fmaxf(x, -15.f), 15.f));
-    return 1.f - 2.f * __frcp_rn(1.f + t);
+    return __builtin_fmaf(-2.f, __frcp_rn(1.f + t), 1.f);
+}
+
+// Gate functions of the three cells on finished pre-activations (bias included).  Every data path
+// calls these same functions, and the multiply-adds are spelled out as fused operations (left to
+// the compiler, the choice of which product to fuse differs between call sites), so that a
+// node's h and c do not depend on the path that made them.
+__device__ inline void lstm_leaf_out(float gi, float go, float gu, float *c, float *h)
+{
+    const float cc = sigmoid_f(gi) * tanh_f(gu);
+    *c = cc;
+    *h = sigmoid_f(go) * tanh_f(cc);
+}
+__device__ inline void lstm_inner_out(float gi, float gfl, float gfr, float go, float gu, float cl, float cr, float *c,
+                                      float *h)
+{
+    const float i = sigmoid_f(gi), fl = sigmoid_f(gfl), fr = sigmoid_f(gfr), og = sigmoid_f(go), u = tanh_f(gu);
+    const float cc = __builtin_fmaf(fr, cr, __builtin_fmaf(fl, cl, i * u));
+    *c = cc;
+    *h = og * tanh_f(cc);
 }
 
 // Fills node/src0/src1 of one row.  Rows without a node are marked unused.  Caller synchronises.
@@ -114,49 +133,63 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
         if (node < 0) continue;
         const size_t o = (size_t)node * H + hu;
         if (EPI == EPI_LSTM_LEAF) {
-            const float i = sigmoid_f(acc[0][v] + bias[0]);
-            const float og = sigmoid_f(acc[1][v] + bias[1]);
-            const float u = tanh_f(acc[2][v] + bias[2]);
-            const float cc = i * u;
+            float cc, hh;
+            lstm_leaf_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], &cc, &hh);
             st_f<COH>(f.c + o, cc);
-            st_f<COH>(f.h + o, og * tanh_f(cc));
+            st_f<COH>(f.h + o, hh);
         } else if (EPI == EPI_LSTM_INNER) {
             const float cl = ld_f<COH>(f.c + (size_t)sm.src0[row] * H + hu);
             const float cr = ld_f<COH>(f.c + (size_t)sm.src1[row] * H + hu);
-            const float i = sigmoid_f(acc[0][v] + bias[0]);
-            const float fl = sigmoid_f(acc[1][v] + bias[1]);
-            const float fr = sigmoid_f(acc[2][v] + bias[2]);
-            const float og = sigmoid_f(acc[3][v] + bias[3]);
-            const float u = tanh_f(acc[4][v] + bias[4]);
-            const float cc = i * u + fl * cl + fr * cr;
+            float cc, hh;
+            lstm_inner_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], acc[3][v] + bias[3],
+                           acc[4][v] + bias[4], cl, cr, &cc, &hh);
             st_f<COH>(f.c + o, cc);
-            st_f<COH>(f.h + o, og * tanh_f(cc));
+            st_f<COH>(f.h + o, hh);
         } else {
             st_f<COH>(f.h + o, tanh_f(acc[0][v] + bias[0]));
         }
     }
 }
 
-// Partial accumulators of the waves with ks > 0 go through LDS to the wave with ks == 0 of the
-// same row block.  Re-uses the A buffers; the caller guarantees nobody reads them any more.
+// Summation order of the fp32 contraction, the same on every data path: the padded K axis is cut
+// into four equal quarters of k-steps; within a quarter the k-steps are accumulated in increasing
+// order on one MFMA accumulator chain, and the four quarter sums P0..P3 are added as
+// ((P0 + P1) + P2) + P3 before the bias.  Whether a wave owns one quarter, two, or all four
+// depends on how many rows a tile has, but the bits of a node's result do not.
+//
+// The waves that hold later quarters hand them through LDS (the B buffers, which nobody reads
+// any more) to the wave that holds P0 of the same row block.  KS waves share a row block; with
+// KS == 2 a wave holds two quarters: `first` and `acc`.
 template <int NG>
-__device__ inline void ksplit_reduce(TileSmem &sm, floatx4 (&acc)[NG], int KS, int ks, bool active, int wave, int lane)
+__device__ inline void ksplit_reduce(TileSmem &sm, floatx4 (&acc)[NG], const floatx4 (&first)[NG], int KS, int ks, int rb,
+                                     int lane)
 {
-    float *red = &sm.a[0][0];               // [wave][g*4+v][lane]: 4*20*64 floats <= sizeof(a)
-    if (active && ks > 0) {
+    float *red = reinterpret_cast<float *>(&sm.b[0][0]);    // [rb 0..1][quarter][g*4+v][lane]: 2*4*20*64 floats = sizeof(b)
+    auto at = [&](int q, int g, int v) { return ((rb * 4 + q) * NG * 4 + g * 4 + v) * 64 + lane; };
+    if (ks > 0) {
 #pragma unroll
         for (int g = 0; g < NG; ++g)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) red[(wave * NG * 4 + g * 4 + v) * 64 + lane] = acc[g][v];
+            for (int v = 0; v < 4; ++v) {
+                if (KS == 4) {
+                    red[at(ks, g, v)] = acc[g][v];
+                } else {
+                    red[at(2, g, v)] = first[g][v];
+                    red[at(3, g, v)] = acc[g][v];
+                }
+            }
     }
     __syncthreads();
-    if (active && ks == 0) {
-        for (int other = 1; other < KS; ++other) {
-            const int w2 = KS == 4 ? other : wave + 2;
+    if (ks == 0) {
+        if (KS == 2) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = first[g] + acc[g];
+        }
+        for (int q = KS == 4 ? 1 : 2; q < 4; ++q) {
 #pragma unroll
             for (int g = 0; g < NG; ++g)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[g][v] += red[(w2 * NG * 4 + g * 4 + v) * 64 + lane];
+                for (int v = 0; v < 4; ++v) acc[g][v] += red[at(q, g, v)];
         }
     }
 }
@@ -171,30 +204,30 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
     constexpr int U = NG >= 5 ? (COH ? 2 : 4) : 4;   // k-steps per register group (two groups are in flight)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nrb = (count + 15) >> 4;          // 1 or 2
-    const int KS = nrb == 1 ? 4 : 2;
+    const int KS = nrb == 1 ? 4 : 2;            // waves per row block; a wave owns 4 / KS quarters of K
     const int rb = KS == 4 ? 0 : (wave & 1);
     const int ks = KS == 4 ? wave : (wave >> 1);
     const int L = gm.L, Lp = gm.Lp;
     const int n_steps = gm.n_chunks * (KC / STEP_K);
+    const int quarter = n_steps >> 2;           // n_steps is a multiple of 4
     const floatx4 *wp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * n_steps * NG * 64 + lane;
     const int row = rb * 16 + (lane & 15);
     const int s0 = sm.src0[row], s1 = sm.src1[row];   // -1 beyond count
     const int kl = (lane >> 4) * 4;
 
-    floatx4 acc[NG];
+    floatx4 acc[NG], first[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NG; ++g) acc[g] = first[g] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     floatx4 a0[U], b0[U][NG], a1[U], b1[U][NG];
-    const int my_steps = (n_steps - ks + KS - 1) / KS;      // k-steps ks, ks+KS, ... of this wave
-    const int n_groups = (my_steps + U - 1) / U;
+    int s_lo = 0, s_hi = 0;                           // k-steps of the quarter being accumulated
     auto load_group = [&](int grp, floatx4 (&a)[U], floatx4 (&b)[U][NG]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             // a k-step past the end re-reads the last one with a zeroed A operand
-            const int s_raw = ks + KS * (grp * U + u);
-            const bool real = s_raw < n_steps;
-            const int s = real ? s_raw : n_steps - 1;
+            const int s_raw = s_lo + grp * U + u;
+            const bool real = s_raw < s_hi;
+            const int s = real ? s_raw : s_hi - 1;
             a[u] = load_a_granule<SEG, VEC4, COH>(table, f.zeros, L, Lp, real ? s0 : -1, real ? s1 : -1, s * STEP_K + kl);
 #pragma unroll
             for (int g = 0; g < NG; ++g) b[u][g] = wp[(size_t)(s * NG + g) * 64];
@@ -214,18 +247,31 @@ __device__ inline void cell_tile_direct(TileSmem &sm, const Fwd &f, const Gemm &
     // MFMAs (which would expose the full memory latency once per group).  Nothing in the loop is
     // conditional: a branch around loads would make the wait counters at its join pessimistic.
     // Groups past the end multiply a zero A operand.
-    load_group(0, a0, b0);
-    for (int grp = 0; grp < n_groups; grp += 2) {
-        load_group(grp + 1, a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_group(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_group(grp + 2, a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma_group(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
+    const int n_q = 4 / KS;
+    const int n_groups = (quarter + U - 1) / U;
+    for (int qi = 0; qi < n_q; ++qi) {
+        s_lo = (ks * n_q + qi) * quarter;
+        s_hi = s_lo + quarter;
+        load_group(0, a0, b0);
+        for (int grp = 0; grp < n_groups; grp += 2) {
+            load_group(grp + 1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_group(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_group(grp + 2, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_group(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (qi + 1 < n_q) {                           // the quarter sum is complete: start the next on a fresh chain
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                first[g] = acc[g];
+                acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
     }
-    ksplit_reduce<NG>(sm, acc, KS, ks, true, wave, lane);
+    ksplit_reduce<NG>(sm, acc, first, KS, ks, rb, lane);
     if (ks == 0) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
 }
 
@@ -245,9 +291,13 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
     const int n_steps = gm.n_chunks * STEPS;
     const floatx4 *wp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * n_steps * NG * 64;
 
-    floatx4 acc[NG];
+    // a wave walks all four quarters of K here: `acc` is the chain of the current quarter, `total`
+    // the sum of the finished ones (see ksplit_reduce for the order)
+    floatx4 acc[NG], total[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NG; ++g) acc[g] = total[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int quarter = n_steps >> 2;
+    int to_boundary = quarter;
 
     // staging registers: A granules (rows tid/16 + 16 j, granule tid%16), B float4s
     floatx4 ra[4], rbuf[NG];
@@ -289,6 +339,15 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
             const float *arow = &sm.a[buf][(rb * 16 + (lane & 15)) * A_LD + (lane >> 4) * 4];
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
+                if (to_boundary == 0) {                 // uniform: a quarter of K is complete
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        total[g] += acc[g];
+                        acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    to_boundary = quarter;
+                }
+                --to_boundary;
                 const floatx4 av = *reinterpret_cast<const floatx4 *>(arow + s * STEP_K);
                 floatx4 bv[NG];
 #pragma unroll
@@ -304,7 +363,11 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
         if (more) store_chunk(buf ^ 1);
         __syncthreads();
     }
-    if (active) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
+    if (active) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) total[g] += acc[g];
+        tile_epilogue<EPI, COH, NG>(sm, f, gm, total, rb, count, cg, lane);
+    }
 }
 
 // ---- staged path with bfloat16 operands ---------------------------------------------------

@@ -18,10 +18,10 @@
 //   4. meets the other three waves' partial sums in LDS and finishes four of the sixteen rows
 //      (gate functions, c update, h/c stores).
 //
-// The summation order of a node is fixed (each wave walks its K range in order, the four partial
-// sums are added in wave order), so a node's result does not depend on which rows happened to
-// share its tile: results are bit-identical from run to run and between the two persistent
-// schedulers.
+// The summation order of a node is the one every data path uses (cell_tile.hpp, ksplit_reduce):
+// wave w walks quarter w of the K axis in order, and the four quarter sums are added in wave
+// order.  A node's result therefore does not depend on which rows happened to share its tile, on
+// the scheduler, or on whether this form or the streaming form evaluated it.
 #pragma once
 
 #include <cstddef>
@@ -194,21 +194,15 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
         if (ev) {
             const size_t o = (size_t)enode * H + hu;
             if constexpr (EPI == EPI_LSTM_INNER) {
-                const float i = sigmoid_f(gate[0]);
-                const float fl = sigmoid_f(gate[1]);
-                const float fr = sigmoid_f(gate[2]);
-                const float og = sigmoid_f(gate[3]);
-                const float u = tanh_f(gate[NG - 1]);
-                const float cc = i * u + fl * cl + fr * cr;
+                float cc, hh;
+                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
                 st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, og * tanh_f(cc));
+                st_f<COH>(f.h + o, hh);
             } else if constexpr (EPI == EPI_LSTM_LEAF) {
-                const float i = sigmoid_f(gate[0]);
-                const float og = sigmoid_f(gate[1]);
-                const float u = tanh_f(gate[NG - 1]);
-                const float cc = i * u;
+                float cc, hh;
+                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
                 st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, og * tanh_f(cc));
+                st_f<COH>(f.h + o, hh);
             } else {
                 st_f<COH>(f.h + o, tanh_f(gate[0]));
             }
