@@ -91,6 +91,20 @@ def cpu_baseline(w):
             "sample": "all %d trees of the workload, one pass, trees spread over %d threads" % (w.trees.n_trees, cores)}
 
 
+def copy_calibration(mib=1024, reps=3):
+    """A plain copy of `mib` MiB, `reps` times: it reads and writes exactly that many bytes of HBM per launch, which
+    gives the scale of the FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc."""
+    import torch
+    src = torch.ones(mib << 18, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration": True, "bytes_read_per_launch": mib << 20, "bytes_written_per_launch": mib << 20,
+                      "launches": reps}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +115,8 @@ def main():
     ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build evaluates on ONE GPU only (trees are independent; see DESIGN.md for how "
@@ -114,6 +130,9 @@ def main():
         import __graft_entry__
         __graft_entry__.build()
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        copy_calibration()
+        return
     precision = binding.TL_F32 if args.precision == "f32" else binding.TL_BF16_IN
 
     w = synth.workload(args.workload)
