@@ -137,6 +137,7 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
             lstm_leaf_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], &cc, &hh);
             st_f<COH>(f.c + o, cc);
             st_f<COH>(f.h + o, hh);
+            if (f.hb) st_h<COH>(f.hb + (size_t)node * f.hs + hu, bf16_bits(hh));
         } else if (EPI == EPI_LSTM_INNER) {
             const float cl = ld_f<COH>(f.c + (size_t)sm.src0[row] * H + hu);
             const float cr = ld_f<COH>(f.c + (size_t)sm.src1[row] * H + hu);
@@ -145,8 +146,11 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
                            acc[4][v] + bias[4], cl, cr, &cc, &hh);
             st_f<COH>(f.c + o, cc);
             st_f<COH>(f.h + o, hh);
+            if (f.hb) st_h<COH>(f.hb + (size_t)node * f.hs + hu, bf16_bits(hh));
         } else {
-            st_f<COH>(f.h + o, tanh_f(acc[0][v] + bias[0]));
+            const float hh = tanh_f(acc[0][v] + bias[0]);
+            st_f<COH>(f.h + o, hh);
+            if (f.hb) st_h<COH>(f.hb + (size_t)node * f.hs + hu, bf16_bits(hh));
         }
     }
 }
@@ -398,9 +402,13 @@ __device__ inline void cell_tile_staged_bf16(TileSmem &sm, const Fwd &f, const G
     __bf16 *a_lds[2] = {reinterpret_cast<__bf16 *>(&sm.a[0][0]), reinterpret_cast<__bf16 *>(&sm.a[1][0])};
     floatx4 *b_lds[2] = {&sm.b[0][0], &sm.b[1][0]};
 
-    floatx4 acc[NG];
+    // same order of summation as the fp32 paths, in k-steps of 32: four quarters of K, each one
+    // accumulator chain, added in quarter order (the packed K axis has a multiple of 4 such steps)
+    floatx4 acc[NG], total[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NG; ++g) acc[g] = total[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int quarter = n_steps >> 2;
+    int to_boundary = quarter;
 
     floatx4 ra[4], rbuf[B_PER_THREAD];
     const int a_row0 = tid >> 4, a_k4 = tid & 15;
@@ -448,6 +456,15 @@ __device__ inline void cell_tile_staged_bf16(TileSmem &sm, const Fwd &f, const G
             const __bf16 *arow = &a_lds[buf][(rb * 16 + (lane & 15)) * A_LD_BF + (lane >> 4) * 8];
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
+                if (to_boundary == 0) {
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) {
+                        total[g] += acc[g];
+                        acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    }
+                    to_boundary = quarter;
+                }
+                --to_boundary;
                 const bf16x8 av = *reinterpret_cast<const bf16x8 *>(arow + s * 32);
 #pragma unroll
                 for (int g = 0; g < NG; ++g) {
@@ -460,7 +477,11 @@ __device__ inline void cell_tile_staged_bf16(TileSmem &sm, const Fwd &f, const G
         if (more) store_chunk(buf ^ 1);
         __syncthreads();
     }
-    if (active) tile_epilogue<EPI, COH, NG>(sm, f, gm, acc, rb, count, cg, lane);
+    if (active) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) total[g] += acc[g];
+        tile_epilogue<EPI, COH, NG>(sm, f, gm, total, rb, count, cg, lane);
+    }
 }
 
 // The tile.  All WG_THREADS threads of the workgroup call it together; sm.node/src0/src1 hold

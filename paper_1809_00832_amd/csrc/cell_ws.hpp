@@ -73,26 +73,32 @@ template <int SPW> struct WsLoadGeom {
 };
 
 // Requests of this wave's K range of 16 rows of the tile, with consecutive lanes on consecutive
-// 16 bytes of a row.  Lanes on the K padding read zeros (they meet zero weights, but 0 * garbage
+// 16 bytes of a row.  T is the element type of the table the rows come from: float (16 elements
+// per k-step) or 16-bit (bf16 rows, 32 elements per k-step); either way a k-step is 64 bytes of a
+// row = 4 lanes.  Lanes on the K padding read zeros (they meet zero weights, but 0 * garbage
 // could be NaN); rows that do not exist read row 0 instead: every MFMA output row depends on its
 // own A row only, and the results of such rows are never stored.  Both choices are invariant
 // per lane, so one request is a multiply-add and a load.
-template <int SEG, int SPW> struct WsRowRequest {
+template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     using G = WsLoadGeom<SPW>;
-    const float *base;
+    static constexpr int EPL = 16 / (int)sizeof(T);             // elements per lane and load
+    const T *base;
     unsigned stride;
     int seg, sub;
     unsigned at[G::NL];
 
-    __device__ inline void init(const Fwd &f, const Gemm &gm, const float *__restrict__ table, int wave, int lane)
+    // rows of `table` have `stride_` elements of which the first L are data (whatever follows up to
+    // Lp, the offset of the second segment on the K axis, must read as zero or not be read: L == Lp
+    // when the table pads its rows with zeros itself)
+    __device__ inline void init(const Fwd &f, const T *__restrict__ table, int L, int Lp, int stride_, int wave, int lane)
     {
         sub = lane / G::LPR;                                    // which of the RPL rows of a load
-        const int k = STEP_K * SPW * wave + (lane % G::LPR) * 4;  // position on the padded K axis
-        seg = (SEG == 2 && k >= gm.Lp) ? 1 : 0;
-        const int off = k - seg * gm.Lp;
-        const bool lane_ok = sub < G::RPL && off < gm.L;
-        base = lane_ok ? table + off : f.zeros;
-        stride = lane_ok ? (unsigned)gm.L : 0u;
+        const int k = 4 * EPL * SPW * wave + (lane % G::LPR) * EPL;   // position on the padded K axis
+        seg = (SEG == 2 && k >= Lp) ? 1 : 0;
+        const int off = k - seg * Lp;
+        const bool lane_ok = sub < G::RPL && off < L;
+        base = lane_ok ? table + off : reinterpret_cast<const T *>(f.zeros);
+        stride = lane_ok ? (unsigned)stride_ : 0u;
     }
     // source rows of block [row0, row0+16): one batch of row-table reads
     template <typename Smem> __device__ inline void prepare(const Smem &sm, int row0, bool any)
@@ -104,7 +110,10 @@ template <int SEG, int SPW> struct WsRowRequest {
             at[j] = any ? (unsigned)max(seg ? a1 : a0, 0) : 0u;
         }
     }
-    template <bool COH> __device__ inline floatx4 issue(int j) const { return ld_f4<COH>(base + (size_t)at[j] * stride); }
+    template <bool COH> __device__ inline floatx4 issue(int j) const
+    {
+        return ld_f4<COH>(reinterpret_cast<const float *>(base + (size_t)at[j] * stride));
+    }
 };
 
 // Parks requested rows in the wave's LDS region (row-major, stride WS_A_LD).
@@ -137,7 +146,7 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
     const float *a_lane = &sm.a[wave][(lane & 15) * WS_A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
 
     WsRowRequest<SEG, SPW> req;
-    req.init(f, gm, table, wave, lane);
+    req.init(f, table, gm.L, gm.Lp, gm.L, wave, lane);
     floatx4 rows[NL];
     req.prepare(sm, 0, true);
 #pragma unroll
@@ -211,6 +220,133 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
         // that passes the next block's barrier before it writes this one again
     }
     __syncthreads();                                        // row tables and LDS may be rewritten after this call
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16-operand form (v_mfma_f32_16x16x32_bf16, fp32 accumulate, gates and state).
+//
+// A wave holds S k-steps of 32 x NG gates = S * NG * 4 registers of bf16 weights: half the fp32
+// form's, so two workgroups fit on a CU and one computes while the other waits for rows or
+// finishes gates.  The MFMAs of a block take a fraction of a microsecond here; what a block
+// costs is the gather of its child rows, so those come from a bf16 copy of h (written next to
+// the fp32 h by every epilogue, rows padded with zeros to a multiple of 8 elements): half the
+// bytes, no conversion on the way into LDS, and the rounding of the operand (once per element,
+// to nearest even) is the same as converting at gather time.
+constexpr int WSB_MAX_S = 8;
+constexpr int WSB_A_LD = 32 * WSB_MAX_S + 8;               // LDS row stride of a wave's A block, bf16 elements
+
+struct WsSmemBf {
+    unsigned short a[4][16 * WSB_A_LD];
+    float red[2][WS_RED_FLOATS];
+    int node[TILE_ROWS];
+    int src0[TILE_ROWS];
+    int src1[TILE_ROWS];
+    int cmd[8];
+};
+
+template <int NG, int S> struct WsWeightsBf {
+    bf16x8 b[S][NG];
+};
+template <int NG> struct WsWeightsBf<NG, 0> {};
+
+// k-steps (of 32) [wave*S, (wave+1)*S) of column group cg; the packed matrix has exactly 4*S of them.
+template <int NG, int S>
+__device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, int wave, int lane)
+{
+    const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(gm.wp) + ((size_t)cg * 4 * S + (size_t)wave * S) * NG * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) w.b[s][g] = wp[(size_t)(s * NG + g) * 64];
+}
+
+template <int EPI, bool COH, int S>
+__device__ inline void ws_tile(WsSmemBf &sm, const Fwd &f, const Gemm &gm, int count, int cg,
+                               const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
+{
+    constexpr int NG = EpiTraits<EPI>::NG;
+    constexpr int SEG = EpiTraits<EPI>::SEG;
+    using G = WsLoadGeom<S>;
+    constexpr int NL = G::NL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nrb = (count + 15) >> 4;
+    const int H = f.H;
+    const int hu = cg * HU + (lane & 15);
+    const bool hu_ok = hu < H;
+    const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WSB_A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
+
+    WsRowRequest<SEG, S, unsigned short> req;
+    req.init(f, f.hb, f.hs, f.hs, f.hs, wave, lane);
+    floatx4 rows[NL];
+    req.prepare(sm, 0, true);
+#pragma unroll
+    for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
+    for (int rb = 0; rb < nrb; ++rb) {
+        float *red = sm.red[rb & 1];
+        {                                                   // park the requested rows (waits for them)
+            const int sub = lane / G::LPR, kk = (lane % G::LPR) * 8;
+#pragma unroll
+            for (int j = 0; j < NL; ++j) {
+                const int r = j * G::RPL + sub;
+                if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WSB_A_LD + kk]) = rows[j];
+            }
+        }
+        req.prepare(sm, (rb + 1) * 16, rb + 1 < nrb);
+        const int erow = rb * 16 + (lane >> 4) * 4 + wave;
+        const int enode = erow < count ? sm.node[erow] : -1;
+        const bool ev = enode >= 0 && hu_ok;
+        __builtin_amdgcn_sched_barrier(0);
+        floatx4 acc[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+        constexpr int LOADS_PER_STEP = (NL + S - 1) / S;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(a_lane + s * 32);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, w.b[s][g], acc[g], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < LOADS_PER_STEP; ++q)
+                if (s * LOADS_PER_STEP + q < NL) rows[s * LOADS_PER_STEP + q] = req.template issue<COH>(s * LOADS_PER_STEP + q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // c operands of the row this lane finishes: requested now, they arrive while the partial
+        // sums cross LDS (held across the MFMA phase they would cost registers the weights need)
+        float cl = 0.f, cr = 0.f;
+        if (EPI == EPI_LSTM_INNER) {
+            const int hc = hu_ok ? hu : 0;
+            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (TILE_ROWS - 1)], 0) * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (TILE_ROWS - 1)], 0) * H + hc);
+        }
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[((wave * NG + g) * 4 + v) * 64 + lane] = acc[g][v];
+        __syncthreads();
+        float gate[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float sum = red[((0 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((1 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
+            gate[g] = sum + gm.bp[(cg * NG + g) * HU + (lane & 15)];
+        }
+        if (ev) {
+            const size_t o = (size_t)enode * H + hu;
+            float hh;
+            if constexpr (EPI == EPI_LSTM_INNER) {
+                float cc;
+                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
+                st_f<COH>(f.c + o, cc);
+            } else {
+                hh = tanh_f(gate[0]);
+            }
+            st_f<COH>(f.h + o, hh);
+            st_h<COH>(f.hb + (size_t)enode * f.hs + hu, bf16_bits(hh));
+        }
+    }
+    __syncthreads();
 }
 
 }  // namespace tl

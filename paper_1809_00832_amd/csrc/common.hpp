@@ -83,6 +83,8 @@ struct Fwd {
     int n_trees, n_nodes, n_leaf, n_int;
     const int32_t *tree_off, *left, *right, *word;
     float *h, *c;
+    unsigned short *hb;         // bf16 copy of h for the bf16 weight-stationary cell (row stride hs, pads zero); else null
+    int hs;
     float *h_root, *c_root;
     int32_t *root_out;
     // model
@@ -132,6 +134,16 @@ __device__ inline void wait_mem()
     __builtin_amdgcn_s_waitcnt(0);
 }
 
+// bf16 (round to nearest even, done by the hardware conversion) of one value, as its 16 bits
+__device__ inline unsigned short bf16_bits(float x)
+{
+    const __bf16 b = (__bf16)x;
+    return __builtin_bit_cast(unsigned short, b);
+}
+template <bool COH> __device__ inline void st_h(unsigned short *p, unsigned short v)
+{
+    if (COH) st_dev(p, v); else *p = v;
+}
 template <bool COH> __device__ inline float ld_f(const float *p) { return COH ? ld_dev(p) : *p; }
 template <bool COH> __device__ inline void st_f(float *p, float v)
 {

@@ -41,7 +41,11 @@ __global__ void k_leaf_copy(Fwd f)
     if (i >= f.n_leaf) return;
     const int n = f.leaf_list[i];
     const int w = f.word[n];
-    for (int j = threadIdx.x; j < f.H; j += blockDim.x) f.h[(size_t)n * f.H + j] = f.emb[(size_t)w * f.E + j];
+    for (int j = threadIdx.x; j < f.H; j += blockDim.x) {
+        const float x = f.emb[(size_t)w * f.E + j];
+        f.h[(size_t)n * f.H + j] = x;
+        if (f.hb) f.hb[(size_t)n * f.hs + j] = bf16_bits(x);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -87,19 +91,24 @@ template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd
 // Level frontiers on the device: heights 1, 2, ... with a grid barrier between them (the
 // depth-wise batching of Section 6.3, without a launch or a host round trip per depth).
 // SPW > 0 selects the weight-stationary cell (cell_ws.hpp, SPW k-steps per wave in registers,
-// one workgroup per CU, every workgroup tied to one column group); SPW == 0 the streaming cell.
+// every workgroup tied to one column group; one workgroup per CU in fp32, two with bf16
+// operands); SPW == 0 the streaming cell.
+template <int SPW, bool BF16>
+using PersistentSmem = std::conditional_t<(SPW > 0), std::conditional_t<BF16, WsSmemBf, WsSmem>, TileSmem>;
+template <int NG, int SPW, bool BF16>
+using PersistentWeights = std::conditional_t<(SPW > 0 && BF16), WsWeightsBf<NG, SPW>, WsWeights<NG, SPW>>;
 template <int EPI, bool VEC4, int SPW, bool BF16 = false>
-__global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persistent(Fwd f)
+__global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_levels_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    using Smem = std::conditional_t<(SPW > 0), WsSmem, TileSmem>;
+    using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     if (f.ctl->status != 0) return;
     const int n_levels = f.ctl->n_levels;
     const int tid = threadIdx.x;
     const int my_cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
-    WsWeights<EpiTraits<EPI>::NG, SPW> w;
+    PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
     for (int lvl = 1; lvl < n_levels; ++lvl) {
@@ -111,7 +120,8 @@ __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_levels_persiste
                 plan_tile(plan, rows, tile, &start, &count);
                 tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
                 __syncthreads();
-                ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
+                else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
             }
         } else {
             const int items = plan.n_tiles * f.n_cg;
@@ -270,10 +280,10 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
 }
 
 template <int EPI, bool VEC4, int SPW, bool BF16 = false>
-__global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persistent(Fwd f)
+__global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_ready_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    using Smem = std::conditional_t<(SPW > 0), WsSmem, TileSmem>;
+    using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
     if (ctl->status != 0) return;
@@ -287,7 +297,7 @@ __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persisten
     GangBox *box = &f.gangs[gang];
     // weight-stationary cell (SPW > 0): gang_size == n_cg, the member's column group is fixed
     const int my_cg = gang_cg(member, f.gang_size, f.n_cg);
-    WsWeights<EpiTraits<EPI>::NG, SPW> w;
+    PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
 
     unsigned long long entry = 0;                 // this thread's entry of the next tile, requested ahead
@@ -315,7 +325,9 @@ __global__ __launch_bounds__(WG_THREADS, SPW > 0 ? 1 : 2) void k_ready_persisten
         // request the next tile's entry now; it arrives while this tile is computed
         if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[(seq + 1) % GANG_RING][tid]);
 
-        if constexpr (SPW > 0) {
+        if constexpr (SPW > 0 && BF16) {
+            ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
+        } else if constexpr (SPW > 0) {
             ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
         } else {
             for (int j = member; j < f.n_cg; j += f.gang_size)

@@ -48,6 +48,9 @@ struct tl_ctx {
     int persistent_grid = 0;          // workgroups of the persistent kernels (streaming cell)
     int spw = 0;                      // k-steps per wave of the weight-stationary cell, 0 = not used
     int ws_grid = 0;                  // workgroups of the persistent kernels (weight-stationary cell)
+    size_t ws_lds = 0;                // their LDS bytes
+    int hs = 0;                       // row stride of the bf16 copy of h
+    unsigned short *hb = nullptr;     // bf16 copy of h, cap_nodes rows (bf16 weight-stationary cell only)
     int last_grid = 0;
     int last_levels = 0;
     // profiling
@@ -77,10 +80,22 @@ typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
 
 // Steps per wave that the weight-stationary cell is instantiated for; 0 = streaming cell.
 const int WS_SIZES[] = {1, 2, 4, 5, 8, 16};
+// Same for bf16 operands, in k-steps of 32.
+const int WSB_SIZES[] = {1, 2, 3, 4, 6, 8};
 
 template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw, bool bf16)
 {
-    if (bf16) return vec4 ? k_ready_persistent<EPI, true, 0, true> : k_ready_persistent<EPI, false, 0, true>;
+    if (bf16) {
+        switch (spw) {
+        case 1: return k_ready_persistent<EPI, true, 1, true>;
+        case 2: return k_ready_persistent<EPI, true, 2, true>;
+        case 3: return k_ready_persistent<EPI, true, 3, true>;
+        case 4: return k_ready_persistent<EPI, true, 4, true>;
+        case 6: return k_ready_persistent<EPI, true, 6, true>;
+        case 8: return k_ready_persistent<EPI, true, 8, true>;
+        default: return vec4 ? k_ready_persistent<EPI, true, 0, true> : k_ready_persistent<EPI, false, 0, true>;
+        }
+    }
     switch (spw) {
     case 1: return k_ready_persistent<EPI, true, 1>;
     case 2: return k_ready_persistent<EPI, true, 2>;
@@ -93,7 +108,17 @@ template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw, bool bf16)
 }
 template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw, bool bf16)
 {
-    if (bf16) return vec4 ? k_levels_persistent<EPI, true, 0, true> : k_levels_persistent<EPI, false, 0, true>;
+    if (bf16) {
+        switch (spw) {
+        case 1: return k_levels_persistent<EPI, true, 1, true>;
+        case 2: return k_levels_persistent<EPI, true, 2, true>;
+        case 3: return k_levels_persistent<EPI, true, 3, true>;
+        case 4: return k_levels_persistent<EPI, true, 4, true>;
+        case 6: return k_levels_persistent<EPI, true, 6, true>;
+        case 8: return k_levels_persistent<EPI, true, 8, true>;
+        default: return vec4 ? k_levels_persistent<EPI, true, 0, true> : k_levels_persistent<EPI, false, 0, true>;
+        }
+    }
     switch (spw) {
     case 1: return k_levels_persistent<EPI, true, 1>;
     case 2: return k_levels_persistent<EPI, true, 2>;
@@ -138,8 +163,10 @@ template <typename K> int allow_lds(K kernel, size_t bytes = TILE_SMEM_BYTES)
 int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, int min_steps, bool bf16, Gemm *g,
               void **wp_out, float **bp_out)
 {
-    const int Lp = round_up(L, 4);
-    int Kp = round_up(SEG * Lp, KC);
+    // bf16: segments start at multiples of 8 elements (16 bytes of a bf16 row) and the K axis is a
+    // multiple of 4 k-steps of 32, so that it splits into four quarters of whole k-steps
+    const int Lp = round_up(L, bf16 ? 8 : 4);
+    int Kp = round_up(SEG * Lp, bf16 ? 128 : KC);
     if (Kp < min_steps * STEP_K) Kp = min_steps * STEP_K;   // the weight-stationary cell wants exactly 4 * SPW k-steps
     const int n_steps = Kp / STEP_K;
     const size_t n_w = (size_t)n_cg * n_steps * NG * 64 * 4;
@@ -173,12 +200,18 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     const int N = n_nodes > ctx->cap_nodes ? n_nodes : ctx->cap_nodes;
     const int B = n_trees > ctx->cap_trees ? n_trees : ctx->cap_trees;
     if (ctx->ws) { TL_HIP(hipFree(ctx->ws)); ctx->ws = nullptr; }
+    if (ctx->hb) { TL_HIP(hipFree(ctx->hb)); ctx->hb = nullptr; }
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
     const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
+    if (ctx->spw > 0 && ctx->cfg.precision == TL_BF16_IN) {
+        const size_t hb_bytes = (size_t)N * ctx->hs * sizeof(unsigned short);
+        TL_HIP(hipMalloc(&ctx->hb, hb_bytes));
+        TL_HIP(hipMemset(ctx->hb, 0, hb_bytes));   // the padding at the end of each row stays zero for good
+    }
     TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
     ctx->ws_bytes = bytes;
     ctx->cap_nodes = N;
@@ -215,6 +248,7 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->bp_leaf);
     (void)hipFree(ctx->bp_inner);
     (void)hipFree(ctx->ws);
+    (void)hipFree(ctx->hb);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -237,23 +271,31 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     TL_HIP(hipMalloc(&ctx->emb, emb_bytes));
     TL_HIP(hipMemcpy(ctx->emb, cfg->emb, emb_bytes, hipMemcpyDeviceToDevice));
 
-    // Weight-stationary cell: needs 16-byte aligned rows (H % 4 == 0) and at most 16 k-steps per wave.
-    {
-        const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
-        ctx->spw = 0;
-        if (H % 4 == 0 && cfg->precision == TL_F32 && cfg->cell != TL_RNTN && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0))
+    // Weight-stationary cell.  fp32: needs 16-byte aligned rows (H % 4 == 0) and at most 16 k-steps of
+    // 16 per wave; bf16: at most 8 k-steps of 32 per wave (its rows come from a padded bf16 copy of h).
+    const bool bf16 = cfg->precision == TL_BF16_IN;
+    ctx->spw = 0;
+    ctx->hs = round_up(H, 8);
+    if (cfg->cell != TL_RNTN && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+        if (bf16) {
+            const int needed = round_up(2 * ctx->hs, 128) / 128;
+            for (int sz : WSB_SIZES)
+                if (sz >= needed) { ctx->spw = sz; break; }
+        } else if (H % 4 == 0) {
+            const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
             for (int sz : WS_SIZES)
                 if (sz >= needed) { ctx->spw = sz; break; }
+        }
     }
-    const bool bf16 = cfg->precision == TL_BF16_IN;
+    const int ws_steps16 = bf16 ? 8 * ctx->spw : 4 * ctx->spw;   // K axis of the weight-stationary cell in k-steps of 16
     int rc;
     if (cfg->cell == TL_TREELSTM) {
         rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 0, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
         if (rc != TL_OK) return rc;
-        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     } else if (cfg->cell == TL_TREERNN) {
-        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, 4 * ctx->spw, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
+        rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     } else {
         // RNTN: tensor slices and W packed per column group and q; padded K is 64, 128 or 256
@@ -295,16 +337,17 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     if (occ > 2) occ = 2;
     ctx->persistent_grid = occ * ctx->n_cu;
     if (ctx->spw > 0) {
-        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw, false), sizeof(WsSmem))) != TL_OK) return rc;
-        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw, false), sizeof(WsSmem))) != TL_OK) return rc;
+        ctx->ws_lds = bf16 ? sizeof(WsSmemBf) : sizeof(WsSmem);
+        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
+        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
         int o1 = 0, o2 = 0;
-        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw, false)),
-                                                            WG_THREADS, sizeof(WsSmem)));
-        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw, false)),
-                                                            WG_THREADS, sizeof(WsSmem)));
-        if (o1 > 1) o1 = 1;   // the cell is written for one workgroup per CU
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw, bf16)),
+                                                            WG_THREADS, ctx->ws_lds));
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw, bf16)),
+                                                            WG_THREADS, ctx->ws_lds));
         if (o2 < o1) o1 = o2;
-        if (o1 > 2) o1 = 2;
+        const int want = bf16 ? 2 : 1;   // fp32: the register file of a CU holds one workgroup's weights; bf16: two
+        if (o1 > want) o1 = want;
         ctx->ws_grid = o1 * ctx->n_cu;
         if (o1 < 1 || ctx->ws_grid < ctx->n_cg + 1) ctx->spw = 0;
     }
@@ -375,8 +418,10 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     carve_workspace(ctx, &f);
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
     const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
-    const int spw = vec4_inner ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
+    const bool bf16 = cfg.precision == TL_BF16_IN;
+    const int spw = (bf16 || vec4_inner) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
+    if (persistent && spw > 0 && bf16) { f.hb = ctx->hb; f.hs = ctx->hs; }
     const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
     // ready scheduler: gangs of gang_size compute workgroups plus one scheduler workgroup each
@@ -386,7 +431,6 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
-    const bool bf16 = cfg.precision == TL_BF16_IN;
     const bool prof = ctx->profiling != 0;
     const int nb_nodes = (n_nodes + 1 + 255) / 256;
 
@@ -431,13 +475,13 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
         if (cfg.scheduler == TL_SCHED_READY) {
             const int grid_r = f.n_gangs * (f.gang_size + 1);
             hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_r), dim3(WG_THREADS),
-                               spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
+                               spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
             hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_l), dim3(WG_THREADS),
-                               spw > 0 ? sizeof(WsSmem) : TILE_SMEM_BYTES, st, f);
+                               spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists

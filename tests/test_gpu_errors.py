@@ -119,17 +119,18 @@ def test_host_side_argument_checks():
         binding.tl_create(binding.TL_TREERNN, 0, 0, 8, 8, 4, z, u=z, b=z)
 
 
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
 @pytest.mark.parametrize("name", ["sentence", "throughput", "treernn"])
-def test_results_do_not_depend_on_the_schedule(name):
-    """fp32 path: every data path sums a node's contraction in the same order (four quarters of the K axis,
+def test_results_do_not_depend_on_the_schedule(name, precision):
+    """Every data path sums a node's contraction in the same order (four quarters of the K axis,
     each in k order, added in quarter order), whatever rows share its tile.  So the three schedulers agree bit
     for bit with each other and from run to run, although the ready scheduler forms different tiles every time.
     (Same recursion, different execution order, identical numbers: the claim of Section 5's numerical check.)"""
-    print("case determinism", name, flush=True)
+    print("case determinism", name, precision, flush=True)
     w = synth.workload(name)
     outs = []
     for sched in ("ready", "level_device", "level_host"):
-        net = binding.TreeNet(w.params, scheduler=sched)
+        net = binding.TreeNet(w.params, scheduler=sched, precision=binding.TL_F32 if precision == "f32" else binding.TL_BF16_IN)
         try:
             got = net.run(w.trees)
             outs.append((sched, got["h"].copy(), None if got["c"] is None else got["c"].copy()))
