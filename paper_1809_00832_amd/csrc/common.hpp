@@ -53,6 +53,7 @@ struct alignas(LINE) Ctl {
     Line bar_xcd[N_XCD];
     Line bar_all;
     Line bar_flag[N_XCD];
+    Line frontier_end[2];         // q_tail as the last arrival at barrier number e saw it, at [e & 1]
 };
 
 // Mailbox of one gang: a scheduler workgroup plus workgroups that together cover all column

@@ -55,7 +55,8 @@ __global__ void k_leaf_copy(Fwd f)
 // Data visibility does not come from the barrier: callers write shared data with device-scope
 // stores and call wait_mem() first.  Returns false if the wait was abandoned (spin budget
 // exhausted somewhere); every workgroup then leaves the kernel.
-template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch)
+template <typename Smem>
+__device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, unsigned *q_tail_seen = nullptr)
 {
     Ctl *ctl = f.ctl;
     wait_mem();
@@ -66,8 +67,13 @@ template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd
         const unsigned n_dom = gridDim.x < (unsigned)N_XCD ? gridDim.x : (unsigned)N_XCD;   // domains that hold workgroups
         const unsigned per = (gridDim.x - (unsigned)x + N_XCD - 1u) / N_XCD;                  // workgroups of domain x
         if (add_dev(&ctl->bar_xcd[x].v, 1u) == per * epoch - 1u) {
-            if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u)
+            if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u) {
+                // everybody has arrived, so every append to the ready queue made before the barrier is
+                // counted: publish the count before the flags, for all workgroups to agree on
+                st_dev(&ctl->frontier_end[epoch & 1u].v, ld_dev(&ctl->q_tail.v));
+                wait_mem();
                 for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, epoch);
+            }
         }
         int ok = 1;
         int spins = 0;
@@ -81,15 +87,25 @@ template <typename Smem> __device__ inline bool grid_barrier(Smem &sm, const Fwd
             backoff();
         }
         sm.cmd[0] = ok;
+        sm.cmd[1] = ok ? (int)ld_dev(&ctl->frontier_end[epoch & 1u].v) : 0;
     }
     __syncthreads();
     const int ok = sm.cmd[0];
+    if (q_tail_seen) *q_tail_seen = (unsigned)sm.cmd[1];
     __syncthreads();
     return ok != 0;
 }
 
-// Level frontiers on the device: heights 1, 2, ... with a grid barrier between them (the
-// depth-wise batching of Section 6.3, without a launch or a host round trip per depth).
+// Level frontiers on the device: the depth-wise batching of Section 6.3 without a launch, a host
+// round trip or a separate pass over the trees per depth.  The frontiers are built as the
+// evaluation goes, with the ready counters of Section 4.1: frontier 1 is the set of internal nodes
+// over two leaves (the structure pass left them at the head of the ready queue); while frontier k
+// is evaluated, one wave per tile decrements the counter of each row's parent and appends the
+// parents that reach zero to the queue; after a grid barrier those appended entries are frontier
+// k + 1.  A parent's counter may reach zero before its children's rows are stored: nobody reads
+// the appended entries before the barrier, which every workgroup passes only after its stores
+// have completed.  The loop ends when a frontier is empty; if nodes are left then (a cycle), the
+// batch is reported as malformed.
 // SPW > 0 selects the weight-stationary cell (cell_ws.hpp, SPW k-steps per wave in registers,
 // every workgroup tied to one column group; one workgroup per CU in fp32, two with bf16
 // operands); SPW == 0 the streaming cell.
@@ -97,44 +113,91 @@ template <int SPW, bool BF16>
 using PersistentSmem = std::conditional_t<(SPW > 0), std::conditional_t<BF16, WsSmemBf, WsSmem>, TileSmem>;
 template <int NG, int SPW, bool BF16>
 using PersistentWeights = std::conditional_t<(SPW > 0 && BF16), WsWeightsBf<NG, SPW>, WsWeights<NG, SPW>>;
+
+// Parents of a tile's rows, first half: wave 0, one lane per row, sends the decrements.  The
+// returned values are needed only in frontier_push(), after the tile has been computed.
+template <typename Smem> __device__ inline void frontier_decrement(const Smem &sm, const Fwd &f, int count, int *p, int *old)
+{
+    *p = -1;
+    *old = 0;
+    const int lane = threadIdx.x;
+    if (lane < count) {
+        const int node = sm.node[lane];
+        if (node >= 0) *p = f.parent[node];
+    }
+    if (*p >= 0) *old = add_dev(&f.pending[*p], -1);
+}
+// Second half: parents whose counter reached zero are appended with one reservation per tile.
+__device__ inline void frontier_push(const Fwd &f, int p, int old)
+{
+    const int lane = threadIdx.x;
+    const bool ready = p >= 0 && old == 1;
+    const unsigned long long mask = __ballot(ready);
+    const int n_ready = __popcll(mask);
+    if (n_ready == 0) return;
+    unsigned base = 0;
+    if (lane == 0) base = add_dev(&f.ctl->q_tail.v, (unsigned)n_ready);
+    base = __shfl(base, 0);
+    if (ready) {
+        const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+        if (slot < (unsigned)f.n_int) st_dev(&f.q_nodes[slot], (unsigned)p + 1u);
+    }
+}
+
 template <int EPI, bool VEC4, int SPW, bool BF16 = false>
 __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_levels_persistent(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
-    if (f.ctl->status != 0) return;
-    const int n_levels = f.ctl->n_levels;
+    Ctl *ctl = f.ctl;
+    if (ctl->status != 0) return;
     const int tid = threadIdx.x;
-    const int my_cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
+    const int member = blockIdx.x % f.n_cg;
+    const int my_cg = gang_cg(member, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
-    for (int lvl = 1; lvl < n_levels; ++lvl) {
-        const int lo = f.level_off[lvl], rows = f.level_off[lvl + 1] - lo;
+    unsigned begin = 0, end = (unsigned)ctl->n_seed;
+    const unsigned n_int = (unsigned)f.n_int;
+    if (end > n_int) end = n_int;
+    int frontiers = 0;
+    while (end > begin) {
+        const int rows = (int)(end - begin);
         const LevelPlan plan = plan_level(rows, f.cap_tiles);
+        // tile T of a frontier: its rows' parents are looked after by the workgroup that computes
+        // column group T % n_cg of it, so that this duty rotates over the workgroups
+        auto one_tile = [&](int tile, int cg_index, int cg) {
+            int start, count;
+            plan_tile(plan, rows, tile, &start, &count);
+            tile_set_rows<EPI>(sm, f, tid, tid < count ? (int)ld_dev(&f.q_nodes[begin + start + tid]) - 1 : -1);
+            __syncthreads();
+            const bool keeper = cg_index == tile % f.n_cg && tid < 64;
+            int p = -1, old = 0;
+            if (keeper) frontier_decrement(sm, f, count, &p, &old);
+            if constexpr (SPW > 0 && BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, cg, w);
+            else if constexpr (SPW > 0) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, cg, w);
+            else cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, cg);
+            if (keeper) frontier_push(f, p, old);
+        };
         if constexpr (SPW > 0) {
-            for (int tile = slot; tile < plan.n_tiles; tile += n_slots) {
-                int start, count;
-                plan_tile(plan, rows, tile, &start, &count);
-                tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
-                __syncthreads();
-                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
-                else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
-            }
+            for (int tile = slot; tile < plan.n_tiles; tile += n_slots) one_tile(tile, member, my_cg);
         } else {
             const int items = plan.n_tiles * f.n_cg;
-            for (int item = blockIdx.x; item < items; item += gridDim.x) {
-                const int tile = item / f.n_cg, cg = gang_cg(item % f.n_cg, f.n_cg, f.n_cg);
-                int start, count;
-                plan_tile(plan, rows, tile, &start, &count);
-                tile_set_rows<EPI>(sm, f, tid, tid < count ? f.level_nodes[lo + start + tid] : -1);
-                __syncthreads();
-                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, cg);
-            }
+            for (int item = blockIdx.x; item < items; item += gridDim.x)
+                one_tile(item / f.n_cg, item % f.n_cg, gang_cg(item % f.n_cg, f.n_cg, f.n_cg));
         }
-        if (lvl + 1 < n_levels && !grid_barrier(sm, f, epoch)) return;
+        frontiers += 1;
+        if (end >= n_int) break;                  // every internal node has been handed out
+        unsigned tail = 0;
+        if (!grid_barrier(sm, f, epoch, &tail)) return;
+        begin = end;
+        end = tail < n_int ? tail : n_int;
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        ctl->n_levels = frontiers + 1;            // heights 0 .. frontiers
+        if (end < n_int) latch_error(ctl, TL_ESTRUCT);   // nodes that never became ready: not a forest
     }
 }
 

@@ -116,6 +116,7 @@ __global__ void k_check_roots(Fwd f)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < f.n_trees && f.root_ws[t] < 0) latch_error(f.ctl, TL_ESTRUCT);
+    if (t == 0) f.ctl->n_seed = (int)f.ctl->q_tail.v;     // the first frontier: internal nodes over two leaves
 }
 
 // Heights by climbing: one thread per leaf walks towards the root; at every internal node the

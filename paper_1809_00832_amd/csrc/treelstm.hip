@@ -428,7 +428,8 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.gang_size = ctx->n_cg + 1 <= grid_p ? ctx->n_cg : grid_p - 1;
     f.n_gangs = grid_p / (f.gang_size + 1) < MAX_GANGS ? grid_p / (f.gang_size + 1) : MAX_GANGS;
 
-    const bool need_levels = cfg.scheduler != TL_SCHED_READY || cfg.validate != 0;
+    // heights and per-height node lists: for the host-driven scheduler, and as the check for cycles
+    const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
     const bool prof = ctx->profiling != 0;
