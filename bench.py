@@ -42,6 +42,30 @@ def algorithmic_work(w):
     return f_int, f_leaf, float(bytes_)
 
 
+def heights_of(trees):
+    """Height of every node (leaf 0, internal 1 + max of its children), by relaxation from the leaves."""
+    import numpy as np
+    left, right = np.asarray(trees.left), np.asarray(trees.right)
+    inner = np.nonzero(left >= 0)[0]
+    h = np.zeros(len(left), dtype=np.int64)
+    while True:
+        new = 1 + np.maximum(h[left[inner]], h[right[inner]])
+        if np.array_equal(new, h[inner]):
+            return h
+        h[inner] = new
+
+
+def span_bound_ms(w, peak_tflops, t_sync_us=2.0):
+    """Critical-path lower bound of the internal stage: heights are evaluated one after the other, each at least
+    its flops at the matrix peak or one grid-wide synchronisation (measured: about 2 us), whichever is longer."""
+    import numpy as np
+    h = heights_of(w.trees)
+    counts = np.bincount(h)[1:]
+    f_int, _, _ = algorithmic_work(w)
+    per_node = f_int / max(1, w.trees.n_internal)
+    return float(sum(max(c * per_node / (peak_tflops * 1e12) * 1e3, t_sync_us * 1e-3) for c in counts)), int(len(counts))
+
+
 def time_steps(net, steps):
     import torch
     torch.cuda.synchronize()
@@ -111,7 +135,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="throughput")
-    ap.add_argument("--scheduler", default="ready", choices=["ready", "level_device", "level_host"])
+    ap.add_argument("--scheduler", default="level_device", choices=["ready", "level_device", "level_host"])
     ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
@@ -166,6 +190,9 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "flops_per_launch": f_int, "kernel_ms": kernel_ms, "traffic": None},
     }
+    bound_ms, n_heights = span_bound_ms(w, peak)
+    out["span_bound"] = {"internal_ms": bound_ms, "heights": n_heights,
+                         "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
     if not args.no_compare:
         comp = {}
         for sched in ("ready", "level_device", "level_host"):

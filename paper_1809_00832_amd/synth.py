@@ -302,7 +302,7 @@ def _sentence_trees(seed: int, batch: int, vocab: int, lo: int = 5, hi: int = 50
 
 
 def workload(name: str) -> Workload:
-    """The five evaluation workloads (seeds 0..4); config 4 comes as two cells."""
+    """The evaluation workloads (seeds 0..4); the fourth one comes with two cells, `treernn` and `rntn`."""
     if name == "tiny":
         tr = make_trees(0, [8] * 4, ["random"] * 4, 100)
         return Workload(name, tr, make_treelstm_params(0, 100, 16, 16, "uniform0.1"))
