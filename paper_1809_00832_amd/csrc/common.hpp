@@ -52,8 +52,7 @@ struct alignas(LINE) Ctl {
     // grid barrier of the level scheduler: arrivals per L2 domain, then across domains
     Line bar_xcd[N_XCD];
     Line bar_all;
-    Line bar_flag[N_XCD];
-    Line frontier_end[2];         // q_tail as the last arrival at barrier number e saw it, at [e & 1]
+    Line64 bar_flag[N_XCD];       // barrier number in the low half; q_tail as the last arrival saw it in the high half
 };
 
 // Mailbox of one gang: a scheduler workgroup plus workgroups that together cover all column
@@ -68,6 +67,14 @@ constexpr int VALUE_EXIT = -2;            // node value of row 0 in the "leave" 
 struct alignas(LINE) GangBox {
     unsigned long long slot[GANG_RING][SLOT_ENTRIES];   // [0,64): node  [64,128): first source  [128,192): second source
     Line done;                                          // compute workgroups that finished tiles (cumulative)
+};
+
+// Record of the ready queue: a node that has become ready, with its child rows, so that whoever
+// takes it off the queue needs one memory round trip, not two.  Two 8-byte words, each written
+// by one store: {node + 1, left} and {right, node + 1}; a record whose two tags agree and are not
+// zero is complete (the queue is zeroed at the start of every forward).
+struct QRec {
+    unsigned long long lo, hi;
 };
 
 // One contraction: rows gathered from `SEG` source rows of length L, times packed weights.
@@ -95,7 +102,7 @@ struct Fwd {
     // workspace
     int32_t *parent, *pending, *leaf_list, *root_ws;
     int32_t *height, *arrive, *level_cnt, *level_off, *level_fill, *level_nodes;
-    unsigned int *q_nodes;            // ready queue: node index + 1, 0 = slot not written yet
+    QRec *q_rec;                      // ready queue, append-only: one record per internal node
     GangBox *gangs;
     const float *zeros;               // 256 bytes of zeros (stand-in source for padded operand granules)
     Ctl *ctl;
@@ -162,6 +169,23 @@ template <bool COH> __device__ inline floatx4 ld_f4(const float *p)
     v.z = __uint_as_float((unsigned)b);
     v.w = __uint_as_float((unsigned)(b >> 32));
     return v;
+}
+
+__device__ inline unsigned long long pack2(unsigned lo32, unsigned hi32) { return (unsigned long long)hi32 << 32 | lo32; }
+template <bool COH> __device__ inline void qrec_store(QRec *q, int node, int left, int right)
+{
+    const unsigned long long lo = pack2((unsigned)node + 1u, (unsigned)left), hi = pack2((unsigned)right, (unsigned)node + 1u);
+    if (COH) { st_dev(&q->lo, lo); st_dev(&q->hi, hi); } else { q->lo = lo; q->hi = hi; }
+}
+// Device-scope read; false while the record is not (completely) there.
+__device__ inline bool qrec_load(const QRec *q, int *node, int *left, int *right)
+{
+    const unsigned long long lo = ld_dev(&q->lo), hi = ld_dev(&q->hi);
+    const unsigned tag = (unsigned)lo;
+    *node = (int)tag - 1;
+    *left = (int)(unsigned)(lo >> 32);
+    *right = (int)(unsigned)hi;
+    return tag != 0u && (unsigned)(hi >> 32) == tag;
 }
 
 __device__ inline void latch_error(Ctl *ctl, int code)

@@ -69,15 +69,15 @@ __device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, uns
         if (add_dev(&ctl->bar_xcd[x].v, 1u) == per * epoch - 1u) {
             if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u) {
                 // everybody has arrived, so every append to the ready queue made before the barrier is
-                // counted: publish the count before the flags, for all workgroups to agree on
-                st_dev(&ctl->frontier_end[epoch & 1u].v, ld_dev(&ctl->q_tail.v));
-                wait_mem();
-                for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, epoch);
+                // counted: the count travels with the flag, for all workgroups to agree on it
+                const unsigned long long v = pack2(epoch, ld_dev(&ctl->q_tail.v));
+                for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, v);
             }
         }
         int ok = 1;
         int spins = 0;
-        while (ld_dev(&ctl->bar_flag[x].v) < epoch) {
+        unsigned long long flag;
+        while ((unsigned)(flag = ld_dev(&ctl->bar_flag[x].v)) < epoch) {
             if (++spins > f.spin_limit || ((spins & 63) == 0 && ld_dev(&ctl->abort.v))) {
                 st_dev(&ctl->abort.v, 1u);
                 latch_error(ctl, TL_ESTALL);
@@ -87,7 +87,7 @@ __device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, uns
             backoff();
         }
         sm.cmd[0] = ok;
-        sm.cmd[1] = ok ? (int)ld_dev(&ctl->frontier_end[epoch & 1u].v) : 0;
+        sm.cmd[1] = ok ? (int)(unsigned)(flag >> 32) : 0;
     }
     __syncthreads();
     const int ok = sm.cmd[0];
@@ -116,22 +116,29 @@ using PersistentWeights = std::conditional_t<(SPW > 0 && BF16), WsWeightsBf<NG, 
 
 // Parents of a tile's rows, first half: wave 0, one lane per row, sends the decrements.  The
 // returned values are needed only in frontier_push(), after the tile has been computed.
-template <typename Smem> __device__ inline void frontier_decrement(const Smem &sm, const Fwd &f, int count, int *p, int *old)
+struct ParentTicket {
+    int p, old, left, right;      // parent of this lane's row (-1: none), its counter before the decrement, its children
+};
+template <typename Smem> __device__ inline ParentTicket frontier_decrement(const Smem &sm, const Fwd &f, int count)
 {
-    *p = -1;
-    *old = 0;
+    ParentTicket t{-1, 0, -1, -1};
     const int lane = threadIdx.x;
     if (lane < count) {
         const int node = sm.node[lane];
-        if (node >= 0) *p = f.parent[node];
+        if (node >= 0) t.p = f.parent[node];
     }
-    if (*p >= 0) *old = add_dev(&f.pending[*p], -1);
+    if (t.p >= 0) {
+        t.old = add_dev(&f.pending[t.p], -1);
+        t.left = f.left[t.p];
+        t.right = f.right[t.p];
+    }
+    return t;
 }
 // Second half: parents whose counter reached zero are appended with one reservation per tile.
-__device__ inline void frontier_push(const Fwd &f, int p, int old)
+__device__ inline void frontier_push(const Fwd &f, const ParentTicket &t)
 {
     const int lane = threadIdx.x;
-    const bool ready = p >= 0 && old == 1;
+    const bool ready = t.p >= 0 && t.old == 1;
     const unsigned long long mask = __ballot(ready);
     const int n_ready = __popcll(mask);
     if (n_ready == 0) return;
@@ -140,7 +147,7 @@ __device__ inline void frontier_push(const Fwd &f, int p, int old)
     base = __shfl(base, 0);
     if (ready) {
         const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
-        if (slot < (unsigned)f.n_int) st_dev(&f.q_nodes[slot], (unsigned)p + 1u);
+        if (slot < (unsigned)f.n_int) qrec_store<true>(&f.q_rec[slot], t.p, t.left, t.right);
     }
 }
 
@@ -171,15 +178,21 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
         auto one_tile = [&](int tile, int cg_index, int cg) {
             int start, count;
             plan_tile(plan, rows, tile, &start, &count);
-            tile_set_rows<EPI>(sm, f, tid, tid < count ? (int)ld_dev(&f.q_nodes[begin + start + tid]) - 1 : -1);
+            if (tid < TILE_ROWS) {
+                int node = -1, s0 = -1, s1 = -1;
+                if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
+                sm.node[tid] = node;
+                sm.src0[tid] = s0;
+                sm.src1[tid] = s1;
+            }
             __syncthreads();
             const bool keeper = cg_index == tile % f.n_cg && tid < 64;
-            int p = -1, old = 0;
-            if (keeper) frontier_decrement(sm, f, count, &p, &old);
+            ParentTicket ticket{-1, 0, -1, -1};
+            if (keeper) ticket = frontier_decrement(sm, f, count);
             if constexpr (SPW > 0 && BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, cg, w);
             else if constexpr (SPW > 0) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, cg, w);
             else cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, cg);
-            if (keeper) frontier_push(f, p, old);
+            if (keeper) frontier_push(f, ticket);
         };
         if constexpr (SPW > 0) {
             for (int tile = slot; tile < plan.n_tiles; tile += n_slots) one_tile(tile, member, my_cg);
@@ -249,10 +262,15 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                 int node = -1;
 #pragma unroll
                 for (int q = 0; q < GANG_RING; ++q) if (q == r) node = my_node[q];
-                int p = -1;
+                int p = -1, pl = -1, pr = -1;
                 if (node >= 0) {
                     p = f.parent[node];
-                    if (p >= 0 && add_dev(&f.pending[p], -1) != 1) p = -1;
+                    if (p >= 0) {
+                        const int old = add_dev(&f.pending[p], -1);
+                        pl = f.left[p];                     // requested together with the decrement
+                        pr = f.right[p];
+                        if (old != 1) p = -1;
+                    }
                 }
                 // parents that became ready are pushed with one reservation on q_tail for the tile
                 const unsigned long long ready = __ballot(p >= 0);
@@ -262,7 +280,7 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                 base = __shfl(base, 0);
                 if (p >= 0) {
                     const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << lane) - 1ull));
-                    if (slot < n_int) st_dev(&f.q_nodes[slot], (unsigned)p + 1u);
+                    if (slot < n_int) qrec_store<true>(&f.q_rec[slot], p, pl, pr);
                 }
                 completed += 1;
                 progress = true;
@@ -288,17 +306,14 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                     const unsigned seq = published + 1;
                     int node = -1, s0 = -1, s1 = -1;
                     if ((unsigned)lane < m) {
-                        unsigned v;
                         int wait = 0;
-                        while ((v = ld_dev(&f.q_nodes[head + lane])) == 0u) {   // slot reserved, not written yet
+                        bool there;
+                        while (!(there = qrec_load(&f.q_rec[head + lane], &node, &s0, &s1))) {   // reserved, not written yet
                             if (++wait > f.spin_limit) break;
                             backoff();
                         }
-                        if (v != 0u) {
-                            node = (int)v - 1;
-                            s0 = f.left[node];
-                            s1 = f.right[node];
-                        } else {
+                        if (!there) {
+                            node = s0 = s1 = -1;
                             st_dev(&ctl->abort.v, 1u);
                             latch_error(ctl, TL_ESTALL);
                         }

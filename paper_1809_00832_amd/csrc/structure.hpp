@@ -54,7 +54,7 @@ __global__ void k_reset(Fwd f, int with_levels)
             if (with_levels) { f.height[i] = 0; f.arrive[i] = 0; f.level_fill[i] = 0; }
         }
         if (with_levels && i <= (size_t)N) f.level_cnt[i] = 0;
-        if (i < (size_t)f.n_int) f.q_nodes[i] = 0;
+        if (i < (size_t)f.n_int) { f.q_rec[i].lo = 0; f.q_rec[i].hi = 0; }
         if (i < (size_t)f.n_trees) f.root_ws[i] = -1;
         if (i < ctl_words) ((unsigned int *)f.ctl)[i] = 0;
         if (i < gang_words) ((unsigned int *)f.gangs)[i] = 0;
@@ -75,10 +75,12 @@ __global__ void k_scatter(Fwd f)
         if (!ok) latch_error(ctl, TL_ESTRUCT);
     }
     bool is_leaf = false, is_seed = false;
+    int l = -1, r = -1;
     if (n < f.n_nodes) {
         const int t = tree_of(f.tree_off, f.n_trees, n);
         const int lo = f.tree_off[t], hi = f.tree_off[t + 1];
-        const int l = f.left[n], r = f.right[n];
+        l = f.left[n];
+        r = f.right[n];
         if (n < lo || n >= hi) {
             latch_error(ctl, TL_ESTRUCT);
         } else if (l < 0 && r < 0) {
@@ -98,7 +100,7 @@ __global__ void k_scatter(Fwd f)
     const int leaf_slot = wave_append(&ctl->n_leaf_seen, is_leaf);
     if (is_leaf && leaf_slot < f.n_leaf) f.leaf_list[leaf_slot] = n;
     const int seed_slot = wave_append(&ctl->q_tail.v, is_seed);
-    if (is_seed && seed_slot < f.n_int) f.q_nodes[seed_slot] = (unsigned)n + 1u;
+    if (is_seed && seed_slot < f.n_int) qrec_store<false>(&f.q_rec[seed_slot], n, l, r);
 }
 
 // One thread per node: the node nobody points to is its tree's root; there must be exactly one.

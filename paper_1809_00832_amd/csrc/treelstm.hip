@@ -204,7 +204,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 10 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
+    const size_t bytes = n4 * 11 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
     if (ctx->spw > 0 && ctx->cfg.precision == TL_BF16_IN) {
@@ -233,7 +233,7 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->level_off = (int32_t *)take(n4);
     f->level_fill = (int32_t *)take(n4);
     f->level_nodes = (int32_t *)take(n4);
-    f->q_nodes = (unsigned int *)take(n4);
+    f->q_rec = (QRec *)take(2 * n4);       // n_int <= N / 2 records of 16 bytes
     f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
     f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
