@@ -33,14 +33,15 @@ namespace tl {
 constexpr int WS_MAX_SPW = 16;
 constexpr int WS_A_LD = STEP_K * WS_MAX_SPW + 4;          // LDS row stride of a wave's A block, floats
 constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;     // one reduction buffer: [wave][gate][v][lane]
+constexpr int WS_TABLE_ROWS = 256;                        // rows one call can take (a power of two)
 
 // LDS of the persistent kernels that use this cell.
 struct WsSmem {
     float a[4][16 * WS_A_LD];          // per wave: its K range of the block's 16 gathered rows
     float red[2][WS_RED_FLOATS];       // K-split partial sums, alternating per block
-    int node[TILE_ROWS];               // same row tables as TileSmem
-    int src0[TILE_ROWS];
-    int src1[TILE_ROWS];
+    int node[WS_TABLE_ROWS];           // row tables as in TileSmem, for up to WS_TABLE_ROWS rows
+    int src0[WS_TABLE_ROWS];
+    int src1[WS_TABLE_ROWS];
     int cmd[8];
 };
 
@@ -105,7 +106,7 @@ template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     {
 #pragma unroll
         for (int j = 0; j < G::NL; ++j) {
-            const int row = (row0 + j * G::RPL + sub) & (TILE_ROWS - 1);
+            const int row = (row0 + j * G::RPL + sub) & (WS_TABLE_ROWS - 1);
             const int a0 = sm.src0[row], a1 = sm.src1[row];     // -1 beyond the tile's rows
             at[j] = any ? (unsigned)max(seg ? a1 : a0, 0) : 0u;
         }
@@ -129,8 +130,9 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
     }
 }
 
-// Evaluates the `count` rows in sm.node/src0/src1 for column group cg.  All four waves call it
-// together; a __syncthreads() has been passed since the row tables were written.
+// Evaluates the `count` <= WS_TABLE_ROWS rows in sm.node/src0/src1 for column group cg, 16 at a
+// time, the requests of a block's rows always one block ahead.  All four waves call it together;
+// a __syncthreads() has been passed since the row tables were written.
 template <int EPI, bool COH, int SPW>
 __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
                                int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
@@ -164,8 +166,8 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {                        // unused lanes read some existing element; the value is dropped
             const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (TILE_ROWS - 1)], 0) * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (TILE_ROWS - 1)], 0) * H + hc);
+            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
         }
         __builtin_amdgcn_sched_barrier(0);                  // all requests are issued before the MFMAs start
         floatx4 acc[NG];
@@ -238,9 +240,9 @@ constexpr int WSB_A_LD = 32 * WSB_MAX_S + 8;               // LDS row stride of 
 struct WsSmemBf {
     unsigned short a[4][16 * WSB_A_LD];
     float red[2][WS_RED_FLOATS];
-    int node[TILE_ROWS];
-    int src0[TILE_ROWS];
-    int src1[TILE_ROWS];
+    int node[WS_TABLE_ROWS];
+    int src0[WS_TABLE_ROWS];
+    int src1[WS_TABLE_ROWS];
     int cmd[8];
 };
 
@@ -315,8 +317,8 @@ __device__ inline void ws_tile(WsSmemBf &sm, const Fwd &f, const Gemm &gm, int c
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {
             const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (TILE_ROWS - 1)], 0) * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (TILE_ROWS - 1)], 0) * H + hc);
+            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
         }
 #pragma unroll
         for (int g = 0; g < NG; ++g)

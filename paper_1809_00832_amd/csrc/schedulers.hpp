@@ -114,15 +114,16 @@ using PersistentSmem = std::conditional_t<(SPW > 0), std::conditional_t<BF16, Ws
 template <int NG, int SPW, bool BF16>
 using PersistentWeights = std::conditional_t<(SPW > 0 && BF16), WsWeightsBf<NG, SPW>, WsWeights<NG, SPW>>;
 
-// Parents of a tile's rows, first half: wave 0, one lane per row, sends the decrements.  The
-// returned values are needed only in frontier_push(), after the tile has been computed.
+// Parents of 64 rows of the row table (from row0 on), first half: wave 0, one lane per row,
+// sends the decrements.  The returned values are needed only in frontier_push(), after the rows
+// have been computed.
 struct ParentTicket {
     int p, old, left, right;      // parent of this lane's row (-1: none), its counter before the decrement, its children
 };
-template <typename Smem> __device__ inline ParentTicket frontier_decrement(const Smem &sm, const Fwd &f, int count)
+template <typename Smem> __device__ inline ParentTicket frontier_decrement(const Smem &sm, const Fwd &f, int count, int row0)
 {
     ParentTicket t{-1, 0, -1, -1};
-    const int lane = threadIdx.x;
+    const int lane = row0 + (int)threadIdx.x;
     if (lane < count) {
         const int node = sm.node[lane];
         if (node >= 0) t.p = f.parent[node];
@@ -172,34 +173,62 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     int frontiers = 0;
     while (end > begin) {
         const int rows = (int)(end - begin);
-        const LevelPlan plan = plan_level(rows, f.cap_tiles);
-        // tile T of a frontier: its rows' parents are looked after by the workgroup that computes
-        // column group T % n_cg of it, so that this duty rotates over the workgroups
-        auto one_tile = [&](int tile, int cg_index, int cg) {
-            int start, count;
-            plan_tile(plan, rows, tile, &start, &count);
-            if (tid < TILE_ROWS) {
-                int node = -1, s0 = -1, s1 = -1;
-                if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
-                sm.node[tid] = node;
-                sm.src0[tid] = s0;
-                sm.src1[tid] = s1;
-            }
-            __syncthreads();
-            const bool keeper = cg_index == tile % f.n_cg && tid < 64;
-            ParentTicket ticket{-1, 0, -1, -1};
-            if (keeper) ticket = frontier_decrement(sm, f, count);
-            if constexpr (SPW > 0 && BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, cg, w);
-            else if constexpr (SPW > 0) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, cg, w);
-            else cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, cg);
-            if (keeper) frontier_push(f, ticket);
-        };
         if constexpr (SPW > 0) {
-            for (int tile = slot; tile < plan.n_tiles; tile += n_slots) one_tile(tile, member, my_cg);
+            // Every slot (a set of workgroups that covers all column groups) takes one contiguous share of
+            // the frontier, a multiple of 16 rows, and walks it in pieces of up to WS_TABLE_ROWS rows: one
+            // fill of the row tables and one start of the row-request pipeline per piece.  The parents of
+            // rows [64 j, 64 j + 64) of a piece are looked after by wave 0 of member (frontier + slot + j) %
+            // n_cg, so that this duty rotates; the decrements are sent before the piece is computed and
+            // their results are used after it.
+            const int share = ((rows + n_slots - 1) / n_slots + 15) & ~15;
+            const int lo = slot * share, hi = min(rows, lo + share);
+            for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
+                const int count = min(hi - piece, WS_TABLE_ROWS);
+                {
+                    int node = -1, s0 = -1, s1 = -1;
+                    if (tid < count && !qrec_load(&f.q_rec[begin + piece + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
+                    sm.node[tid] = node;
+                    sm.src0[tid] = s0;
+                    sm.src1[tid] = s1;
+                }
+                __syncthreads();
+                ParentTicket ticket{-1, 0, -1, -1};
+                bool holds = false;
+                if (tid < 64) {
+                    for (int j = 0; j * 64 < count; ++j) {
+                        if ((frontiers + slot + j) % f.n_cg != member) continue;
+                        if (holds) frontier_push(f, ticket);        // only when there are fewer column groups than 64-row groups
+                        ticket = frontier_decrement(sm, f, count, j * 64);
+                        holds = true;
+                    }
+                }
+                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
+                else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+                if (holds) frontier_push(f, ticket);
+            }
         } else {
+            const LevelPlan plan = plan_level(rows, f.cap_tiles);
+            // tile T of a frontier: its rows' parents are looked after by the workgroup that computes
+            // column group T % n_cg of it
             const int items = plan.n_tiles * f.n_cg;
-            for (int item = blockIdx.x; item < items; item += gridDim.x)
-                one_tile(item / f.n_cg, item % f.n_cg, gang_cg(item % f.n_cg, f.n_cg, f.n_cg));
+            for (int item = blockIdx.x; item < items; item += gridDim.x) {
+                const int tile = item / f.n_cg, cg_index = item % f.n_cg;
+                int start, count;
+                plan_tile(plan, rows, tile, &start, &count);
+                if (tid < TILE_ROWS) {
+                    int node = -1, s0 = -1, s1 = -1;
+                    if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
+                    sm.node[tid] = node;
+                    sm.src0[tid] = s0;
+                    sm.src1[tid] = s1;
+                }
+                __syncthreads();
+                const bool keeper = cg_index == tile % f.n_cg && tid < 64;
+                ParentTicket ticket{-1, 0, -1, -1};
+                if (keeper) ticket = frontier_decrement(sm, f, count, 0);
+                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(cg_index, f.n_cg, f.n_cg));
+                if (keeper) frontier_push(f, ticket);
+            }
         }
         frontiers += 1;
         if (end >= n_int) break;                  // every internal node has been handed out
