@@ -31,13 +31,13 @@
 namespace tl {
 
 constexpr int WS_MAX_SPW = 16;
-constexpr int WS_A_LD = STEP_K * WS_MAX_SPW + 4;          // LDS row stride of a wave's A block, floats
 constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;     // one reduction buffer: [wave][gate][v][lane]
 constexpr int WS_TABLE_ROWS = 256;                        // rows one call can take (a power of two)
 
-// LDS of the persistent kernels that use this cell.
-struct WsSmem {
-    float a[4][16 * WS_A_LD];          // per wave: its K range of the block's 16 gathered rows
+// LDS of the kernels that use this cell with SPW k-steps per wave.
+template <int SPW> struct WsSmemT {
+    static constexpr int A_LD = STEP_K * SPW + 4;   // LDS row stride of a wave's A block, floats
+    float a[4][16 * A_LD];             // per wave: its K range of the block's 16 gathered rows
     float red[2][WS_RED_FLOATS];       // K-split partial sums, alternating per block
     int node[WS_TABLE_ROWS];           // row tables as in TileSmem, for up to WS_TABLE_ROWS rows
     int src0[WS_TABLE_ROWS];
@@ -117,7 +117,7 @@ template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     }
 };
 
-// Parks requested rows in the wave's LDS region (row-major, stride WS_A_LD).
+// Parks requested rows in the wave's LDS region (row-major, stride Smem::A_LD).
 template <int SPW, typename Smem>
 __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<SPW>::NL], int wave, int lane)
 {
@@ -126,7 +126,7 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 #pragma unroll
     for (int j = 0; j < G::NL; ++j) {
         const int r = j * G::RPL + sub;
-        if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WS_A_LD + kk]) = regs[j];
+        if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * Smem::A_LD + kk]) = regs[j];
     }
 }
 
@@ -134,7 +134,7 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 // time, the requests of a block's rows always one block ahead.  All four waves call it together;
 // a __syncthreads() has been passed since the row tables were written.
 template <int EPI, bool COH, int SPW>
-__device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
+__device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
                                int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
@@ -145,7 +145,7 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
     const int H = f.H;
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
-    const float *a_lane = &sm.a[wave][(lane & 15) * WS_A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
+    const float *a_lane = &sm.a[wave][(lane & 15) * WsSmemT<SPW>::A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
 
     WsRowRequest<SEG, SPW> req;
     req.init(f, table, gm.L, gm.Lp, gm.L, wave, lane);
@@ -235,10 +235,10 @@ __device__ inline void ws_tile(WsSmem &sm, const Fwd &f, const Gemm &gm, const f
 // bytes, no conversion on the way into LDS, and the rounding of the operand (once per element,
 // to nearest even) is the same as converting at gather time.
 constexpr int WSB_MAX_S = 8;
-constexpr int WSB_A_LD = 32 * WSB_MAX_S + 8;               // LDS row stride of a wave's A block, bf16 elements
 
-struct WsSmemBf {
-    unsigned short a[4][16 * WSB_A_LD];
+template <int S> struct WsSmemBfT {
+    static constexpr int A_LD = 32 * S + 8;                // LDS row stride of a wave's A block, bf16 elements
+    unsigned short a[4][16 * A_LD];
     float red[2][WS_RED_FLOATS];
     int node[WS_TABLE_ROWS];
     int src0[WS_TABLE_ROWS];
@@ -263,7 +263,7 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
 }
 
 template <int EPI, bool COH, int S>
-__device__ inline void ws_tile(WsSmemBf &sm, const Fwd &f, const Gemm &gm, int count, int cg,
+__device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, int count, int cg,
                                const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
@@ -275,7 +275,7 @@ __device__ inline void ws_tile(WsSmemBf &sm, const Fwd &f, const Gemm &gm, int c
     const int H = f.H;
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
-    const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WSB_A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
+    const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
 
     WsRowRequest<SEG, S, unsigned short> req;
     req.init(f, f.hb, f.hs, f.hs, f.hs, wave, lane);
@@ -290,7 +290,7 @@ __device__ inline void ws_tile(WsSmemBf &sm, const Fwd &f, const Gemm &gm, int c
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
                 const int r = j * G::RPL + sub;
-                if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WSB_A_LD + kk]) = rows[j];
+                if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WsSmemBfT<S>::A_LD + kk]) = rows[j];
             }
         }
         req.prepare(sm, (rb + 1) * 16, rb + 1 < nrb);

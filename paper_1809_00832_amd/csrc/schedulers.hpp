@@ -33,6 +33,33 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int
     cell_tile<EPI, VEC4, false, BF16>(sm, f, gm, table, count, cg);
 }
 
+// Leaves with the weight-stationary cell (fp32): the leaf matrix is small (E x 3H), so a column
+// group's slice takes few registers, two workgroups fit on a CU, and every workgroup keeps its
+// slice while it walks a contiguous share of the leaf list in pieces of up to WS_TABLE_ROWS rows.
+template <int SPW>
+__global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    WsSmemT<SPW> &sm = *reinterpret_cast<WsSmemT<SPW> *>(smem_raw);
+    if (f.ctl->status != 0) return;
+    const int tid = threadIdx.x;
+    const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
+    const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
+    WsWeights<EpiTraits<EPI_LSTM_LEAF>::NG, SPW> w;
+    ws_load(w, f.leaf, cg, tid >> 6, tid & 63);
+    const int share = ((f.n_leaf + n_slots - 1) / n_slots + 15) & ~15;
+    const int lo = slot * share, hi = min(f.n_leaf, lo + share);
+    for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
+        const int count = min(hi - piece, WS_TABLE_ROWS);
+        const int node = tid < count ? f.leaf_list[piece + tid] : -1;
+        sm.node[tid] = node;
+        sm.src0[tid] = node >= 0 ? f.word[node] : -1;
+        sm.src1[tid] = -1;
+        __syncthreads();
+        ws_tile<EPI_LSTM_LEAF, false, SPW>(sm, f, f.leaf, f.emb, count, cg, w);
+    }
+}
+
 // Leaves of TreeRNN / RNTN: h = embedding row.
 __global__ void k_leaf_copy(Fwd f)
 {
@@ -110,7 +137,7 @@ __device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, uns
 // every workgroup tied to one column group; one workgroup per CU in fp32, two with bf16
 // operands); SPW == 0 the streaming cell.
 template <int SPW, bool BF16>
-using PersistentSmem = std::conditional_t<(SPW > 0), std::conditional_t<BF16, WsSmemBf, WsSmem>, TileSmem>;
+using PersistentSmem = std::conditional_t<(SPW > 0), std::conditional_t<BF16, WsSmemBfT<(SPW > 0 ? SPW : 1)>, WsSmemT<(SPW > 0 ? SPW : 1)>>, TileSmem>;
 template <int NG, int SPW, bool BF16>
 using PersistentWeights = std::conditional_t<(SPW > 0 && BF16), WsWeightsBf<NG, SPW>, WsWeights<NG, SPW>>;
 

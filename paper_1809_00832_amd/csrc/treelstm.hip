@@ -49,6 +49,8 @@ struct tl_ctx {
     int spw = 0;                      // k-steps per wave of the weight-stationary cell, 0 = not used
     int ws_grid = 0;                  // workgroups of the persistent kernels (weight-stationary cell)
     size_t ws_lds = 0;                // their LDS bytes
+    int spw_leaf = 0;                 // k-steps per wave of the weight-stationary leaf kernel, 0 = streaming tiles
+    int leaf_grid = 0;
     int hs = 0;                       // row stride of the bf16 copy of h
     unsigned short *hb = nullptr;     // bf16 copy of h, cap_nodes rows (bf16 weight-stationary cell only)
     int last_grid = 0;
@@ -138,6 +140,40 @@ fwd_kernel levels_kernel(int cell, bool vec4, int spw, bool bf16)
 {
     if (cell == TL_RNTN) return vec4 ? k_levels_persistent<EPI_RNTN_INNER, true, 0> : k_levels_persistent<EPI_RNTN_INNER, false, 0>;
     return cell == TL_TREELSTM ? levels_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : levels_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
+}
+fwd_kernel leaf_ws_kernel(int spw)
+{
+    switch (spw) {
+    case 1: return k_leaf_ws<1>;
+    case 2: return k_leaf_ws<2>;
+    case 4: return k_leaf_ws<4>;
+    case 5: return k_leaf_ws<5>;
+    case 8: return k_leaf_ws<8>;
+    case 16: return k_leaf_ws<16>;
+    default: return nullptr;
+    }
+}
+// LDS bytes of the weight-stationary kernels
+size_t ws_lds_bytes(int spw, bool bf16)
+{
+    if (bf16) {
+        switch (spw) {
+        case 1: return sizeof(WsSmemBfT<1>);
+        case 2: return sizeof(WsSmemBfT<2>);
+        case 3: return sizeof(WsSmemBfT<3>);
+        case 4: return sizeof(WsSmemBfT<4>);
+        case 6: return sizeof(WsSmemBfT<6>);
+        default: return sizeof(WsSmemBfT<8>);
+        }
+    }
+    switch (spw) {
+    case 1: return sizeof(WsSmemT<1>);
+    case 2: return sizeof(WsSmemT<2>);
+    case 4: return sizeof(WsSmemT<4>);
+    case 5: return sizeof(WsSmemT<5>);
+    case 8: return sizeof(WsSmemT<8>);
+    default: return sizeof(WsSmemT<16>);
+    }
 }
 template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
 {
@@ -288,9 +324,15 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         }
     }
     const int ws_steps16 = bf16 ? 8 * ctx->spw : 4 * ctx->spw;   // K axis of the weight-stationary cell in k-steps of 16
+    ctx->spw_leaf = 0;
+    if (cfg->cell == TL_TREELSTM && !bf16 && E % 4 == 0 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+        const int needed = round_up(E, KC) / STEP_K / 4;
+        for (int sz : WS_SIZES)
+            if (sz >= needed) { ctx->spw_leaf = sz; break; }
+    }
     int rc;
     if (cfg->cell == TL_TREELSTM) {
-        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 0, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 4 * ctx->spw_leaf, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
         if (rc != TL_OK) return rc;
         rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
@@ -337,7 +379,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     if (occ > 2) occ = 2;
     ctx->persistent_grid = occ * ctx->n_cu;
     if (ctx->spw > 0) {
-        ctx->ws_lds = bf16 ? sizeof(WsSmemBf) : sizeof(WsSmem);
+        ctx->ws_lds = ws_lds_bytes(ctx->spw, bf16);
         if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
         if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
         int o1 = 0, o2 = 0;
@@ -350,6 +392,16 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if (o1 > want) o1 = want;
         ctx->ws_grid = o1 * ctx->n_cu;
         if (o1 < 1 || ctx->ws_grid < ctx->n_cg + 1) ctx->spw = 0;
+    }
+
+    if (ctx->spw_leaf > 0) {
+        const size_t lds = ws_lds_bytes(ctx->spw_leaf, false);
+        if ((rc = allow_lds(leaf_ws_kernel(ctx->spw_leaf), lds)) != TL_OK) return rc;
+        int o = 0;
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(leaf_ws_kernel(ctx->spw_leaf)), WG_THREADS, lds));
+        if (o > 2) o = 2;
+        ctx->leaf_grid = o * ctx->n_cu / ctx->n_cg * ctx->n_cg;
+        if (ctx->leaf_grid < ctx->n_cg) ctx->spw_leaf = 0;
     }
 
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
@@ -461,7 +513,10 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     if (prof) TL_HIP(hipEventRecord(ev[1], st));
 
     // ---- leaves ------------------------------------------------------------------------
-    if (cfg.cell == TL_TREELSTM) {
+    if (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) {
+        hipLaunchKernelGGL(leaf_ws_kernel(ctx->spw_leaf), dim3(ctx->leaf_grid), dim3(WG_THREADS),
+                           ws_lds_bytes(ctx->spw_leaf, false), st, f);
+    } else if (cfg.cell == TL_TREELSTM) {
         const LevelPlan plan = plan_level(f.n_leaf, f.cap_tiles);
         hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
                            TILE_SMEM_BYTES, st, f, (const int32_t *)f.leaf_list, f.n_leaf, plan);
