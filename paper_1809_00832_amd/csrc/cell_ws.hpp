@@ -263,8 +263,8 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
 }
 
 template <int EPI, bool COH, int S>
-__device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, int count, int cg,
-                               const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
+__device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
+                               int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
@@ -278,7 +278,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, i
     const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
 
     WsRowRequest<SEG, S, unsigned short> req;
-    req.init(f, f.hb, f.hs, f.hs, f.hs, wave, lane);
+    req.init(f, table, stride, stride, stride, wave, lane);   // rows of `stride` elements, zero beyond their data
     floatx4 rows[NL];
     req.prepare(sm, 0, true);
 #pragma unroll
@@ -341,11 +341,15 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, i
                 float cc;
                 lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
                 st_f<COH>(f.c + o, cc);
+            } else if constexpr (EPI == EPI_LSTM_LEAF) {
+                float cc;
+                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
+                st_f<COH>(f.c + o, cc);
             } else {
                 hh = tanh_f(gate[0]);
             }
             st_f<COH>(f.h + o, hh);
-            st_h<COH>(f.hb + (size_t)enode * f.hs + hu, bf16_bits(hh));
+            if (f.hb) st_h<COH>(f.hb + (size_t)enode * f.hs + hu, bf16_bits(hh));
         }
     }
     __syncthreads();

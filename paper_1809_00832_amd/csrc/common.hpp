@@ -98,6 +98,8 @@ struct Fwd {
     // model
     int cell, H, E, vocab, n_cg, bf16;
     const float *emb;           // fp32 embedding table (as given)
+    const unsigned short *embb; // bf16 copy, rows of es elements (zero padded), for the bf16 weight-stationary leaf kernel
+    int es;
     Gemm leaf, inner;
     // workspace
     int32_t *parent, *pending, *leaf_list, *root_ws;

@@ -74,6 +74,17 @@ __global__ void k_pack_bias(const float *__restrict__ b, float *__restrict__ bp,
     }
 }
 
+// bf16 copy of a row-major table with rows padded to Ls elements (pads zero)
+__global__ void k_pad_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, size_t rows, int L, int Ls)
+{
+    const size_t total = rows * (size_t)Ls;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / Ls;
+        const int j = (int)(e - r * Ls);
+        dst[e] = j < L ? f32_to_bf16_rne(src[r * L + j]) : (unsigned short)0;
+    }
+}
+
 __global__ void k_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, size_t n)
 {
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x)

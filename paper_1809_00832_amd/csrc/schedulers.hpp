@@ -60,6 +60,32 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
     }
 }
 
+// The same with bf16 operands: rows come from a bf16 copy of the embedding table (rows padded with
+// zeros to a multiple of 8 elements).
+template <int S>
+__global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    WsSmemBfT<S> &sm = *reinterpret_cast<WsSmemBfT<S> *>(smem_raw);
+    if (f.ctl->status != 0) return;
+    const int tid = threadIdx.x;
+    const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
+    const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
+    WsWeightsBf<EpiTraits<EPI_LSTM_LEAF>::NG, S> w;
+    ws_load(w, f.leaf, cg, tid >> 6, tid & 63);
+    const int share = ((f.n_leaf + n_slots - 1) / n_slots + 15) & ~15;
+    const int lo = slot * share, hi = min(f.n_leaf, lo + share);
+    for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
+        const int count = min(hi - piece, WS_TABLE_ROWS);
+        const int node = tid < count ? f.leaf_list[piece + tid] : -1;
+        sm.node[tid] = node;
+        sm.src0[tid] = node >= 0 ? f.word[node] : -1;
+        sm.src1[tid] = -1;
+        __syncthreads();
+        ws_tile<EPI_LSTM_LEAF, false, S>(sm, f, f.leaf, f.embb, f.es, count, cg, w);
+    }
+}
+
 // Leaves of TreeRNN / RNTN: h = embedding row.
 __global__ void k_leaf_copy(Fwd f)
 {
@@ -229,7 +255,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                         holds = true;
                     }
                 }
-                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
+                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
                 else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
                 if (holds) frontier_push(f, ticket);
             }
@@ -460,7 +486,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[(seq + 1) % GANG_RING][tid]);
 
         if constexpr (SPW > 0 && BF16) {
-            ws_tile<EPI, true, SPW>(sm, f, f.inner, count, my_cg, w);
+            ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
         } else if constexpr (SPW > 0) {
             ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
         } else {

@@ -51,6 +51,8 @@ struct tl_ctx {
     size_t ws_lds = 0;                // their LDS bytes
     int spw_leaf = 0;                 // k-steps per wave of the weight-stationary leaf kernel, 0 = streaming tiles
     int leaf_grid = 0;
+    int es = 0;                       // row stride of the bf16 copy of the embedding table
+    unsigned short *embb = nullptr;
     int hs = 0;                       // row stride of the bf16 copy of h
     unsigned short *hb = nullptr;     // bf16 copy of h, cap_nodes rows (bf16 weight-stationary cell only)
     int last_grid = 0;
@@ -150,6 +152,18 @@ fwd_kernel leaf_ws_kernel(int spw)
     case 5: return k_leaf_ws<5>;
     case 8: return k_leaf_ws<8>;
     case 16: return k_leaf_ws<16>;
+    default: return nullptr;
+    }
+}
+fwd_kernel leaf_ws_bf_kernel(int s)
+{
+    switch (s) {
+    case 1: return k_leaf_ws_bf<1>;
+    case 2: return k_leaf_ws_bf<2>;
+    case 3: return k_leaf_ws_bf<3>;
+    case 4: return k_leaf_ws_bf<4>;
+    case 6: return k_leaf_ws_bf<6>;
+    case 8: return k_leaf_ws_bf<8>;
     default: return nullptr;
     }
 }
@@ -285,6 +299,7 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->bp_inner);
     (void)hipFree(ctx->ws);
     (void)hipFree(ctx->hb);
+    (void)hipFree(ctx->embb);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -325,14 +340,26 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     }
     const int ws_steps16 = bf16 ? 8 * ctx->spw : 4 * ctx->spw;   // K axis of the weight-stationary cell in k-steps of 16
     ctx->spw_leaf = 0;
-    if (cfg->cell == TL_TREELSTM && !bf16 && E % 4 == 0 && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
-        const int needed = round_up(E, KC) / STEP_K / 4;
-        for (int sz : WS_SIZES)
-            if (sz >= needed) { ctx->spw_leaf = sz; break; }
+    ctx->es = round_up(E, 8);
+    if (cfg->cell == TL_TREELSTM && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+        if (bf16) {
+            const int needed = round_up(ctx->es, 128) / 128;
+            for (int sz : WSB_SIZES)
+                if (sz >= needed) { ctx->spw_leaf = sz; break; }
+        } else if (E % 4 == 0) {
+            const int needed = round_up(E, KC) / STEP_K / 4;
+            for (int sz : WS_SIZES)
+                if (sz >= needed) { ctx->spw_leaf = sz; break; }
+        }
+    }
+    if (bf16 && ctx->spw_leaf > 0) {
+        TL_HIP(hipMalloc(&ctx->embb, (size_t)cfg->vocab * ctx->es * sizeof(unsigned short)));
+        hipLaunchKernelGGL(k_pad_bf16, dim3(1024), dim3(256), 0, 0, cfg->emb, ctx->embb, (size_t)cfg->vocab, E, ctx->es);
+        TL_HIP(hipGetLastError());
     }
     int rc;
     if (cfg->cell == TL_TREELSTM) {
-        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 4 * ctx->spw_leaf, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, (bf16 ? 8 : 4) * ctx->spw_leaf, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
         if (rc != TL_OK) return rc;
         rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
@@ -395,10 +422,11 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     }
 
     if (ctx->spw_leaf > 0) {
-        const size_t lds = ws_lds_bytes(ctx->spw_leaf, false);
-        if ((rc = allow_lds(leaf_ws_kernel(ctx->spw_leaf), lds)) != TL_OK) return rc;
+        const size_t lds = ws_lds_bytes(ctx->spw_leaf, bf16);
+        const fwd_kernel lk = bf16 ? leaf_ws_bf_kernel(ctx->spw_leaf) : leaf_ws_kernel(ctx->spw_leaf);
+        if ((rc = allow_lds(lk, lds)) != TL_OK) return rc;
         int o = 0;
-        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(leaf_ws_kernel(ctx->spw_leaf)), WG_THREADS, lds));
+        TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(lk), WG_THREADS, lds));
         if (o > 2) o = 2;
         ctx->leaf_grid = o * ctx->n_cu / ctx->n_cg * ctx->n_cg;
         if (ctx->leaf_grid < ctx->n_cg) ctx->spw_leaf = 0;
@@ -465,7 +493,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.h = h; f.c = cfg.cell == TL_TREELSTM ? c : nullptr;
     f.h_root = h_root; f.c_root = c_root; f.root_out = root;
     f.cell = cfg.cell; f.H = cfg.hidden; f.E = cfg.embed_dim; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg; f.bf16 = cfg.precision == TL_BF16_IN;
-    f.emb = ctx->emb;
+    f.emb = ctx->emb; f.embb = ctx->embb; f.es = ctx->es;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
     carve_workspace(ctx, &f);
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
@@ -514,8 +542,8 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
 
     // ---- leaves ------------------------------------------------------------------------
     if (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) {
-        hipLaunchKernelGGL(leaf_ws_kernel(ctx->spw_leaf), dim3(ctx->leaf_grid), dim3(WG_THREADS),
-                           ws_lds_bytes(ctx->spw_leaf, false), st, f);
+        hipLaunchKernelGGL(bf16 ? leaf_ws_bf_kernel(ctx->spw_leaf) : leaf_ws_kernel(ctx->spw_leaf), dim3(ctx->leaf_grid),
+                           dim3(WG_THREADS), ws_lds_bytes(ctx->spw_leaf, bf16), st, f);
     } else if (cfg.cell == TL_TREELSTM) {
         const LevelPlan plan = plan_level(f.n_leaf, f.cap_tiles);
         hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
