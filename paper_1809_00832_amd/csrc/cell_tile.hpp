@@ -41,12 +41,13 @@ struct TileSmem {
 };
 constexpr size_t TILE_SMEM_BYTES = sizeof(TileSmem);
 
-__device__ inline float sigmoid_f(float x) { return __frcp_rn(1.f + __expf(-x)); }
+// v_rcp_f32 (1 ulp) rather than a correctly rounded division, which costs ten instructions
+__device__ inline float sigmoid_f(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 __device__ inline float tanh_f(float x)
 {
     // 1 - 2/(1+e^{2x}); the clamp keeps e^{2x} finite, beyond it tanh is 1 to fp32 precision
     float t = __expf(2.f * fminf(fmaxf(x, -15.f), 15.f));
-    return __builtin_fmaf(-2.f, __frcp_rn(1.f + t), 1.f);
+    return __builtin_fmaf(-2.f, __builtin_amdgcn_rcpf(1.f + t), 1.f);
 }
 
 // Gate functions of the three cells on finished pre-activations (bias included).  Every data path

@@ -76,44 +76,47 @@ template <int SPW> struct WsLoadGeom {
 // Requests of this wave's K range of 16 rows of the tile, with consecutive lanes on consecutive
 // 16 bytes of a row.  T is the element type of the table the rows come from: float (16 elements
 // per k-step) or 16-bit (bf16 rows, 32 elements per k-step); either way a k-step is 64 bytes of a
-// row = 4 lanes.  Lanes on the K padding read zeros (they meet zero weights, but 0 * garbage
-// could be NaN); rows that do not exist read row 0 instead: every MFMA output row depends on its
-// own A row only, and the results of such rows are never stored.  Both choices are invariant
-// per lane, so one request is a multiply-add and a load.
+// row = 4 lanes.  A request is one 32-bit multiply-add (row * row bytes + this lane's offset in
+// the row) and a load from a uniform base.  Lanes on the K padding meet zero weights; they
+// re-read the last 16 bytes of the same row, which hold finite values (0 * garbage could be
+// NaN).  Rows that do not exist (-1 in the row table) read row 0 instead: every MFMA output row
+// depends on its own A row only, and the results of such rows are never stored.
+// The caller guarantees rows < 2^24 and table bytes < 2^32.
 template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     using G = WsLoadGeom<SPW>;
     static constexpr int EPL = 16 / (int)sizeof(T);             // elements per lane and load
-    const T *base;
-    unsigned stride;
-    int seg, sub;
-    unsigned at[G::NL];
+    const char *table;
+    const int *src;                                             // row table of this lane's segment (LDS)
+    unsigned lane_off, row_bytes;
+    int sub;
+    unsigned off[G::NL];
 
-    // rows of `table` have `stride_` elements of which the first L are data (whatever follows up to
-    // Lp, the offset of the second segment on the K axis, must read as zero or not be read: L == Lp
-    // when the table pads its rows with zeros itself)
-    __device__ inline void init(const Fwd &f, const T *__restrict__ table, int L, int Lp, int stride_, int wave, int lane)
+    // rows of `table` are `stride` elements apart; what a row holds between its data and `stride`
+    // elements reads as zero
+    template <typename Smem>
+    __device__ inline void init(const Smem &sm, const T *__restrict__ table_, int Lp, int stride, int wave, int lane)
     {
+        table = reinterpret_cast<const char *>(table_);
         sub = lane / G::LPR;                                    // which of the RPL rows of a load
         const int k = 4 * EPL * SPW * wave + (lane % G::LPR) * EPL;   // position on the padded K axis
-        seg = (SEG == 2 && k >= Lp) ? 1 : 0;
-        const int off = k - seg * Lp;
-        const bool lane_ok = sub < G::RPL && off < L;
-        base = lane_ok ? table + off : reinterpret_cast<const T *>(f.zeros);
-        stride = lane_ok ? (unsigned)stride_ : 0u;
+        const int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
+        const int o = min(k - seg * Lp, stride - EPL);
+        src = seg ? sm.src1 : sm.src0;
+        lane_off = (unsigned)o * (unsigned)sizeof(T);
+        row_bytes = (unsigned)stride * (unsigned)sizeof(T);
     }
-    // source rows of block [row0, row0+16): one batch of row-table reads
-    template <typename Smem> __device__ inline void prepare(const Smem &sm, int row0, bool any)
+    // byte offsets of the requests of block [row0, row0 + 16): one batch of row-table reads
+    __device__ inline void prepare(int row0)
     {
 #pragma unroll
         for (int j = 0; j < G::NL; ++j) {
             const int row = (row0 + j * G::RPL + sub) & (WS_TABLE_ROWS - 1);
-            const int a0 = sm.src0[row], a1 = sm.src1[row];     // -1 beyond the tile's rows
-            at[j] = any ? (unsigned)max(seg ? a1 : a0, 0) : 0u;
+            off[j] = __umul24((unsigned)max(src[row], 0), row_bytes) + lane_off;
         }
     }
     template <bool COH> __device__ inline floatx4 issue(int j) const
     {
-        return ld_f4<COH>(reinterpret_cast<const float *>(base + (size_t)at[j] * stride));
+        return ld_f4<COH>(reinterpret_cast<const float *>(table + off[j]));
     }
 };
 
@@ -148,9 +151,9 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     const float *a_lane = &sm.a[wave][(lane & 15) * WsSmemT<SPW>::A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
 
     WsRowRequest<SEG, SPW> req;
-    req.init(f, table, gm.L, gm.Lp, gm.L, wave, lane);
+    req.init(sm, table, gm.Lp, gm.L, wave, lane);
     floatx4 rows[NL];
-    req.prepare(sm, 0, true);
+    req.prepare(0);
 #pragma unroll
     for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
     for (int rb = 0; rb < nrb; ++rb) {
@@ -158,7 +161,7 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         ws_park_rows<SPW>(sm, rows, wave, lane);            // waits for the requested rows
         // the next block's rows are requested between the k-steps below, one row load per step: the
         // memory path of a CU takes a 1 KB request every ~160 cycles, a k-step lasts 640
-        req.prepare(sm, (rb + 1) * 16, rb + 1 < nrb);
+        req.prepare((rb + 1) * 16);
         // the row this lane finishes after the reduction, and its c operands
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
@@ -278,9 +281,9 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
 
     WsRowRequest<SEG, S, unsigned short> req;
-    req.init(f, table, stride, stride, stride, wave, lane);   // rows of `stride` elements, zero beyond their data
+    req.init(sm, table, stride, stride, wave, lane);
     floatx4 rows[NL];
-    req.prepare(sm, 0, true);
+    req.prepare(0);
 #pragma unroll
     for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
     for (int rb = 0; rb < nrb; ++rb) {
@@ -293,7 +296,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
                 if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WsSmemBfT<S>::A_LD + kk]) = rows[j];
             }
         }
-        req.prepare(sm, (rb + 1) * 16, rb + 1 < nrb);
+        req.prepare((rb + 1) * 16);
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
         const bool ev = enode >= 0 && hu_ok;

@@ -458,7 +458,13 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
     // weight-stationary cell (SPW > 0): gang_size == n_cg, the member's column group is fixed
     const int my_cg = gang_cg(member, f.gang_size, f.n_cg);
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
-    if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+    if constexpr (SPW > 0) {
+        ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+        // tiles have at most TILE_ROWS rows here; the rest of the cell's row tables reads "no row"
+        sm.node[tid] = -1;
+        sm.src0[tid] = -1;
+        sm.src1[tid] = -1;
+    }
 
     unsigned long long entry = 0;                 // this thread's entry of the next tile, requested ahead
     if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[1 % GANG_RING][tid]);

@@ -341,7 +341,8 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     const int ws_steps16 = bf16 ? 8 * ctx->spw : 4 * ctx->spw;   // K axis of the weight-stationary cell in k-steps of 16
     ctx->spw_leaf = 0;
     ctx->es = round_up(E, 8);
-    if (cfg->cell == TL_TREELSTM && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+    const bool leaf_range = cfg->vocab < (1 << 24) && (unsigned long long)cfg->vocab * ctx->es * 4ull < (1ull << 32);
+    if (cfg->cell == TL_TREELSTM && leaf_range && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
         if (bf16) {
             const int needed = round_up(ctx->es, 128) / 128;
             for (int sz : WSB_SIZES)
@@ -499,7 +500,9 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
     const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
     const bool bf16 = cfg.precision == TL_BF16_IN;
-    const int spw = (bf16 || vec4_inner) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
+    // the weight-stationary cell addresses rows with 24-bit row numbers and 32-bit byte offsets
+    const bool ws_range = n_nodes < (1 << 24) && (unsigned long long)n_nodes * cfg.hidden * 4ull < (1ull << 32);
+    const int spw = ((bf16 || vec4_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
     if (persistent && spw > 0 && bf16) { f.hb = ctx->hb; f.hs = ctx->hs; }
     const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
