@@ -49,10 +49,13 @@ struct alignas(LINE) Ctl {
     Line q_head;                  // ready-queue entries consumed into tiles
     Line q_tail;                  // ready-queue entries reserved by producers
     Line tiles;                   // tiles formed (statistics only)
-    // grid barrier of the level scheduler: arrivals per L2 domain, then across domains
-    Line bar_xcd[N_XCD];
+    // grid barrier of the level scheduler, one word per L2 domain: arrivals of the domain's workgroups in
+    // the low half, ready-queue records they have appended (cumulative) in the high half
+    Line64 bar_xcd[N_XCD];
+    // large grids add a second level: arrivals of whole domains, and a flag per domain that the last
+    // arrival raises (barrier number in the low half, length of the ready queue in the high half)
     Line bar_all;
-    Line64 bar_flag[N_XCD];       // barrier number in the low half; q_tail as the last arrival saw it in the high half
+    Line64 bar_flag[N_XCD];
 };
 
 // Mailbox of one gang: a scheduler workgroup plus workgroups that together cover all column

@@ -102,49 +102,89 @@ __global__ void k_leaf_copy(Fwd f)
 }
 
 // ---------------------------------------------------------------------------------------
-// Grid-wide barrier for a grid whose workgroups are all resident.  Two levels, so that no single word takes hundreds of back-to-back atomics: the
-// workgroups of one L2 domain count on their own line, the last of each domain counts on a
-// shared line, and the very last one raises a flag line per domain, which the others poll.
+// Grid-wide barrier for a grid whose workgroups are all resident; it also tells every workgroup
+// how long the ready queue has become (`queue_len`), the same figure for all.
+//
+// Up to FLAT_BARRIER_MAX workgroups: every workgroup adds itself to the word of its L2 domain (no
+// single word takes hundreds of back-to-back atomics, and nobody waits for the result of its own
+// arrival), then one lane per domain polls the domains' words until all of them show the arrivals
+// of this barrier.  The same atomic carries the number of ready-queue records the workgroup has
+// appended since the last barrier, in the high half of the word, so that the poll which sees
+// everybody arrived also sees the length of the queue, without another round trip.
+//
+// Larger grids (two workgroups per CU): that many pollers on the words the arrivals are counted
+// on delay the arrivals themselves (accesses to one address are served one after the other), so
+// a second level is used: the last arrival of a domain counts the domain on a shared word, the
+// very last one reads the queue length and raises one flag per domain, and a workgroup polls only
+// the flag of its own domain.
+//
 // Data visibility does not come from the barrier: callers write shared data with device-scope
-// stores and call wait_mem() first.  Returns false if the wait was abandoned (spin budget
-// exhausted somewhere); every workgroup then leaves the kernel.
+// stores, and wait_mem() here lets them complete first.  Returns false if the wait was abandoned
+// (spin budget exhausted somewhere); every workgroup then leaves the kernel.
+constexpr unsigned FLAT_BARRIER_MAX = 256;
+
 template <typename Smem>
-__device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, unsigned *q_tail_seen = nullptr)
+__device__ inline bool grid_barrier(Smem &sm, const Fwd &f, unsigned &epoch, unsigned appended, unsigned n_seed,
+                                    unsigned *queue_len)
 {
     Ctl *ctl = f.ctl;
     wait_mem();
     __syncthreads();
     epoch += 1;
-    if (threadIdx.x == 0) {
-        const int x = blockIdx.x % N_XCD;
+    if (threadIdx.x < 64) {
+        const unsigned lane = threadIdx.x;
         const unsigned n_dom = gridDim.x < (unsigned)N_XCD ? gridDim.x : (unsigned)N_XCD;   // domains that hold workgroups
-        const unsigned per = (gridDim.x - (unsigned)x + N_XCD - 1u) / N_XCD;                  // workgroups of domain x
-        if (add_dev(&ctl->bar_xcd[x].v, 1u) == per * epoch - 1u) {
-            if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u) {
-                // everybody has arrived, so every append to the ready queue made before the barrier is
-                // counted: the count travels with the flag, for all workgroups to agree on it
-                const unsigned long long v = pack2(epoch, ld_dev(&ctl->q_tail.v));
-                for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, v);
+        const unsigned x = blockIdx.x % N_XCD;
+        int ok = 1, spins = 0;
+        unsigned len = 0;
+        auto give_up = [&]() {
+            st_dev(&ctl->abort.v, 1u);
+            latch_error(ctl, TL_ESTALL);
+            ok = 0;
+        };
+        auto aborted = [&]() { return __ballot(lane == 0 && ld_dev(&ctl->abort.v) != 0u) != 0ull; };
+        if (gridDim.x <= FLAT_BARRIER_MAX) {
+            if (lane == 0) add_dev(&ctl->bar_xcd[x].v, 1ull | (unsigned long long)appended << 32);
+            const unsigned per = (gridDim.x - lane + N_XCD - 1u) / N_XCD;                     // workgroups of domain `lane`
+            const unsigned long long all_domains = (1ull << n_dom) - 1ull;
+            unsigned long long v = 0;
+            for (;;) {
+                if (lane < n_dom) v = ld_dev(&ctl->bar_xcd[lane].v);      // one lane per domain, nobody else loads
+                if (__ballot(lane < n_dom && (unsigned)v >= per * epoch) == all_domains) break;
+                if (++spins > f.spin_limit || ((spins & 63) == 0 && aborted())) { give_up(); break; }
+                backoff();
             }
-        }
-        int ok = 1;
-        int spins = 0;
-        unsigned long long flag;
-        while ((unsigned)(flag = ld_dev(&ctl->bar_flag[x].v)) < epoch) {
-            if (++spins > f.spin_limit || ((spins & 63) == 0 && ld_dev(&ctl->abort.v))) {
-                st_dev(&ctl->abort.v, 1u);
-                latch_error(ctl, TL_ESTALL);
-                ok = 0;
-                break;
+            len = lane < n_dom ? (unsigned)(v >> 32) : 0u;
+            for (int o = N_XCD / 2; o >= 1; o >>= 1) len += __shfl_xor(len, o);
+            len += n_seed;
+        } else {
+            unsigned long long flag = 0;
+            if (lane == 0) {
+                const unsigned per = (gridDim.x - x + N_XCD - 1u) / N_XCD;                    // workgroups of this domain
+                if ((unsigned)add_dev(&ctl->bar_xcd[x].v, 1ull) == per * epoch - 1u) {
+                    if (add_dev(&ctl->bar_all.v, 1u) == n_dom * epoch - 1u) {
+                        // everybody has arrived, so every append made before the barrier is counted
+                        const unsigned long long v = pack2(epoch, ld_dev(&ctl->q_tail.v));
+                        for (unsigned i = 0; i < n_dom; ++i) st_dev(&ctl->bar_flag[i].v, v);
+                    }
+                }
             }
-            backoff();
+            for (;;) {
+                if (lane == 0) flag = ld_dev(&ctl->bar_flag[x].v);
+                if (__ballot(lane == 0 && (unsigned)flag >= epoch) != 0ull) break;
+                if (++spins > f.spin_limit || ((spins & 63) == 0 && aborted())) { give_up(); break; }
+                backoff();
+            }
+            len = (unsigned)(flag >> 32);
         }
-        sm.cmd[0] = ok;
-        sm.cmd[1] = ok ? (int)(unsigned)(flag >> 32) : 0;
+        if (lane == 0) {
+            sm.cmd[0] = ok;
+            sm.cmd[1] = (int)len;
+        }
     }
     __syncthreads();
     const int ok = sm.cmd[0];
-    if (q_tail_seen) *q_tail_seen = (unsigned)sm.cmd[1];
+    *queue_len = (unsigned)sm.cmd[1];
     __syncthreads();
     return ok != 0;
 }
@@ -189,13 +229,13 @@ template <typename Smem> __device__ inline ParentTicket frontier_decrement(const
     return t;
 }
 // Second half: parents whose counter reached zero are appended with one reservation per tile.
-__device__ inline void frontier_push(const Fwd &f, const ParentTicket &t)
+__device__ inline unsigned frontier_push(const Fwd &f, const ParentTicket &t)
 {
     const int lane = threadIdx.x;
     const bool ready = t.p >= 0 && t.old == 1;
     const unsigned long long mask = __ballot(ready);
     const int n_ready = __popcll(mask);
-    if (n_ready == 0) return;
+    if (n_ready == 0) return 0u;
     unsigned base = 0;
     if (lane == 0) base = add_dev(&f.ctl->q_tail.v, (unsigned)n_ready);
     base = __shfl(base, 0);
@@ -203,6 +243,7 @@ __device__ inline void frontier_push(const Fwd &f, const ParentTicket &t)
         const unsigned slot = base + (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
         if (slot < (unsigned)f.n_int) qrec_store<true>(&f.q_rec[slot], t.p, t.left, t.right);
     }
+    return (unsigned)n_ready;
 }
 
 template <int EPI, bool VEC4, int SPW, bool BF16 = false>
@@ -220,7 +261,9 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
-    unsigned begin = 0, end = (unsigned)ctl->n_seed;
+    const unsigned n_seed = (unsigned)ctl->n_seed;
+    unsigned begin = 0, end = n_seed;
+    unsigned appended = 0;                        // records this workgroup has appended since the last barrier (wave 0 counts)
     const unsigned n_int = (unsigned)f.n_int;
     if (end > n_int) end = n_int;
     int frontiers = 0;
@@ -250,14 +293,14 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                 if (tid < 64) {
                     for (int j = 0; j * 64 < count; ++j) {
                         if ((frontiers + slot + j) % f.n_cg != member) continue;
-                        if (holds) frontier_push(f, ticket);        // only when there are fewer column groups than 64-row groups
+                        if (holds) appended += frontier_push(f, ticket);        // only when there are fewer column groups than 64-row groups
                         ticket = frontier_decrement(sm, f, count, j * 64);
                         holds = true;
                     }
                 }
                 if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
                 else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
-                if (holds) frontier_push(f, ticket);
+                if (holds) appended += frontier_push(f, ticket);
             }
         } else {
             const LevelPlan plan = plan_level(rows, f.cap_tiles);
@@ -280,15 +323,16 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                 ParentTicket ticket{-1, 0, -1, -1};
                 if (keeper) ticket = frontier_decrement(sm, f, count, 0);
                 cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(cg_index, f.n_cg, f.n_cg));
-                if (keeper) frontier_push(f, ticket);
+                if (keeper) appended += frontier_push(f, ticket);
             }
         }
         frontiers += 1;
         if (end >= n_int) break;                  // every internal node has been handed out
-        unsigned tail = 0;
-        if (!grid_barrier(sm, f, epoch, &tail)) return;
+        unsigned queue_len = 0;
+        if (!grid_barrier(sm, f, epoch, appended, n_seed, &queue_len)) return;
+        appended = 0;
         begin = end;
-        end = tail < n_int ? tail : n_int;
+        end = queue_len < n_int ? queue_len : n_int;
     }
     if (blockIdx.x == 0 && tid == 0) {
         ctl->n_levels = frontiers + 1;            // heights 0 .. frontiers
