@@ -59,10 +59,15 @@ enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
  *                        children; the workgroup that finishes the last child pushes the
  *                        parent on a device ready queue, from which tiles of ready nodes
  *                        are formed.  Needs no heights and no per-level barrier.
- *  TL_SCHED_LEVEL_DEVICE node heights and per-height node lists are built on the device;
- *                        one persistent kernel walks the heights with a grid-wide barrier.
- *  TL_SCHED_LEVEL_HOST   same lists, one kernel launch per height from the host (the host
- *                        reads the number of heights back first).  Comparison baseline. */
+ *  TL_SCHED_LEVEL_DEVICE one persistent kernel walks the heights 1, 2, ... with a grid-wide
+ *                        barrier between them; the frontier of the next height is built
+ *                        from the same counters while the current one is evaluated (no
+ *                        separate pass over the trees).
+ *  TL_SCHED_LEVEL_HOST   node heights and per-height node lists are built on the device,
+ *                        then one kernel launch per height from the host (which reads the
+ *                        number of heights back first).  Comparison baseline.
+ * Results do not depend on the scheduler: all paths of one precision sum a node's
+ * contraction in the same order, so the three agree bit for bit. */
 enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2 };
 
 enum tl_error {
@@ -73,8 +78,9 @@ enum tl_error {
     TL_ESTRUCT = -4,   /* malformed batch: offsets not ascending / child outside its tree /
                           node with two parents / tree without exactly one root / leaf word id
                           outside the vocabulary / node count inconsistent with full binary trees */
-    TL_ESTALL = -5     /* the scheduler made no progress within its spin budget (nodes that are
-                          unreachable from any leaf, e.g. a cycle); outputs are incomplete      */
+    TL_ESTALL = -5     /* TL_SCHED_READY made no progress within its spin budget (nodes that are
+                          unreachable from any leaf, e.g. a cycle); outputs are incomplete.  The
+                          level schedulers report such a batch as TL_ESTRUCT.                   */
 };
 
 typedef struct {

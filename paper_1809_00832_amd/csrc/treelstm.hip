@@ -327,7 +327,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     const bool bf16 = cfg->precision == TL_BF16_IN;
     ctx->spw = 0;
     ctx->hs = round_up(H, 8);
-    if (cfg->cell != TL_RNTN && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+    if (cfg->cell != TL_RNTN) {
         if (bf16) {
             const int needed = round_up(2 * ctx->hs, 128) / 128;
             for (int sz : WSB_SIZES)
@@ -342,7 +342,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     ctx->spw_leaf = 0;
     ctx->es = round_up(E, 8);
     const bool leaf_range = cfg->vocab < (1 << 24) && (unsigned long long)cfg->vocab * ctx->es * 4ull < (1ull << 32);
-    if (cfg->cell == TL_TREELSTM && leaf_range && !(getenv("TL_WS") && atoi(getenv("TL_WS")) == 0)) {
+    if (cfg->cell == TL_TREELSTM && leaf_range) {
         if (bf16) {
             const int needed = round_up(ctx->es, 128) / 128;
             for (int sz : WSB_SIZES)

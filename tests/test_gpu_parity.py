@@ -198,6 +198,41 @@ def test_bf16_operands_match_oracle(name, sched):
         net.close()
 
 
+def round_params_bf16(p):
+    return synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, oracle.to_bf16(p.emb),
+                        None if p.w_leaf is None else oracle.to_bf16(p.w_leaf), p.b_leaf, oracle.to_bf16(p.u), p.b,
+                        None if p.v is None else oracle.to_bf16(p.v))
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+def test_bf16_ragged_and_degenerate_batches(sched):
+    """bf16 operands with sizes that are not multiples of anything: H and E below and across the 8-element
+    padding of the bf16 row copies, single-node trees, ragged tiles, a second smaller batch on the same context."""
+    say("case bf16 ragged", sched)
+    cases = [
+        (dict(vocab=50, E=7, H=5), [1]),
+        (dict(vocab=50, E=7, H=5), [1, 1, 2]),
+        (dict(vocab=50, E=9, H=33), [1, 2, 3, 1, 70, 5]),
+        (dict(vocab=50, E=64, H=64), [17] * 9 + [1] + [130]),
+        (dict(vocab=60, E=20, H=136), [300, 2, 45]),
+    ]
+    for i, (dims, leaves) in enumerate(cases):
+        params = synth.make_treelstm_params(70 + i, dims["vocab"], dims["E"], dims["H"], "xavier")
+        trees = synth.make_trees(70 + i, leaves, ["random"] * len(leaves), dims["vocab"])
+        net = binding.TreeNet(params, scheduler=sched, precision=binding.TL_BF16_IN)
+        try:
+            for batch in (trees, synth.make_trees(95 + i, leaves[:1], ["random"], dims["vocab"])):
+                got = net.run(batch)
+                ref = oracle.forward_params(round_params_bf16(params), batch, n_threads=4, round_bf16=True)
+                assert_close_bf16(got["h"], ref["h"], "bf16 ragged%d h" % i)
+                assert_close_bf16(got["c"], ref["c"], "bf16 ragged%d c" % i)
+                assert_close_bf16(got["h_root"], ref["h_root"], "bf16 ragged%d h_root" % i)
+                _, root, _ = oracle.structure(batch.tree_off, batch.left, batch.right)
+                assert np.array_equal(got["root"], root)
+        finally:
+            net.close()
+
+
 @pytest.mark.parametrize("sched", SCHEDULERS)
 def test_rntn_other_sizes(sched):
     """RNTN at d = 20 and d = 96 (padded K of 64 and 256).  Magnitudes are raised so that tanh is not linear,
