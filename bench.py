@@ -19,6 +19,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}      # MI355X dense matrix peaks
 HBM_GBS = 8000.0
+# HBM bytes per launch of the internal-node kernel from rocprofv3 counter passes (FETCH_SIZE + WRITE_SIZE, scaled by a
+# copy of known size; profiles/levels_persistent_throughput_f32_counters.md).  Only for the configuration the counters
+# were taken on; to be cleared when that kernel changes.
+MEASURED_TRAFFIC = {("throughput", "level_device", "f32"): {"read": 250.2 * 2 ** 20, "write": 26.4 * 2 ** 20}}
 
 
 def algorithmic_work(w):
@@ -190,6 +194,11 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "flops_per_launch": f_int, "kernel_ms": kernel_ms, "traffic": None},
     }
+    traffic = MEASURED_TRAFFIC.get((args.workload, args.scheduler, args.precision))
+    if traffic:
+        out["roofline"]["traffic"] = traffic["read"] + traffic["write"]
+        out["roofline"]["traffic_read"] = traffic["read"]
+        out["roofline"]["traffic_write"] = traffic["write"]
     bound_ms, n_heights = span_bound_ms(w, peak)
     out["span_bound"] = {"internal_ms": bound_ms, "heights": n_heights,
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
