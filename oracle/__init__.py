@@ -27,6 +27,8 @@ def _load():
         lib = ctypes.CDLL(LIB)
         lib.oracle_structure.restype = ctypes.c_int
         lib.oracle_structure.argtypes = [ctypes.c_int, ctypes.c_int, _I, _I, _I, _I, _I, _I]
+        lib.oracle_classify.restype = ctypes.c_int
+        lib.oracle_classify.argtypes = [ctypes.c_int] * 3 + [_F] * 4
         lib.oracle_forward.restype = ctypes.c_int
         lib.oracle_forward.argtypes = ([ctypes.c_int] * 5 + [_F] * 6 + [ctypes.c_int, ctypes.c_int] + [_I] * 4
                                        + [ctypes.c_int, ctypes.c_int] + [_F] * 4)
@@ -87,6 +89,21 @@ def forward(cell, vocab, embed_dim, hidden, emb, w_leaf, b_leaf, u, b, v,
     if rc != 0:
         raise ValueError("malformed tree batch")
     return {"h": h, "c": c, "h_root": h_root, "c_root": c_root}
+
+
+def classify(h, w_s, b_s):
+    """Per-node class probabilities softmax(h W_s + b_s): h [N x H], w_s [H x C], b_s [C] -> [N x C] fp32."""
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    w_s = np.ascontiguousarray(w_s, dtype=np.float32)
+    b_s = np.ascontiguousarray(b_s, dtype=np.float32)
+    n, H = h.shape
+    C = w_s.shape[1]
+    assert w_s.shape[0] == H and b_s.shape == (C,)
+    probs = np.zeros((n, C), dtype=np.float32)
+    if lib.oracle_classify(n, H, C, _f(h), _f(w_s), _f(b_s), _f(probs)) != 0:
+        raise ValueError("bad classifier dimensions")
+    return probs
 
 
 def forward_params(params, trees, **kw):

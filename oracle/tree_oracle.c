@@ -249,3 +249,32 @@ int oracle_forward(int cell, int vocab, int E, int H, int round_bf16,
     free(parent); free(height); free(root);
     return rc;
 }
+
+/*
+ * Per-node classifier head.  Section 6.1 states that a trained network labels all nodes of the
+ * parse trees; the paper does not print the head.  The reading taken is the usual one of the
+ * cited models: probs[n] = softmax(h[n] W_s + b_s), W_s is [H x C] row-major.  Logits are
+ * accumulated in double (bias first, then k ascending), the softmax subtracts the row maximum
+ * and is evaluated in double; each probability is rounded to fp32 once.
+ * Pinned by tests against closed forms (zero weights, two classes = logistic function),
+ * scipy.special.softmax on a double matmul, shift invariance and a brute-force loop.
+ */
+int oracle_classify(int n_rows, int H, int C, const float *h, const float *w_s, const float *b_s, float *probs)
+{
+    if (n_rows < 0 || H < 1 || C < 1) return -1;
+    double *z = malloc(sizeof(double) * (size_t)C);
+    for (int n = 0; n < n_rows; ++n) {
+        for (int c = 0; c < C; ++c) {
+            double s = b_s[c];
+            for (int k = 0; k < H; ++k) s += (double)h[(size_t)n * H + k] * (double)w_s[(size_t)k * C + c];
+            z[c] = s;
+        }
+        double m = z[0];
+        for (int c = 1; c < C; ++c) if (z[c] > m) m = z[c];
+        double sum = 0.0;
+        for (int c = 0; c < C; ++c) { z[c] = exp(z[c] - m); sum += z[c]; }
+        for (int c = 0; c < C; ++c) probs[(size_t)n * C + c] = (float)(z[c] / sum);
+    }
+    free(z);
+    return 0;
+}

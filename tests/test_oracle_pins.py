@@ -490,3 +490,46 @@ def test_bf16_operand_rounding_is_ties_to_even_inside_the_checker():
         t, _ = parse_bracketing(expr)
         r = run(p, t, round_bf16=True)
         np.testing.assert_allclose(r["h"][0], np.tanh(np.array(want)), rtol=0, atol=1e-7)
+
+
+# ----------------------------------------------------------------------------- classifier head
+def test_classifier_zero_weights_gives_softmax_of_bias():
+    """W_s = 0: every node gets softmax(b_s); with b_s = 0 that is 1/C; with two classes it is the logistic
+    function of the bias difference."""
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((9, 13)).astype(np.float32)
+    for C in (1, 2, 5):
+        p = oracle.classify(h, np.zeros((13, C), np.float32), np.zeros(C, np.float32))
+        assert np.allclose(p, 1.0 / C, atol=1e-7)
+    b = np.array([0.3, -1.1], np.float32)
+    p = oracle.classify(h, np.zeros((13, 2), np.float32), b)
+    assert np.allclose(p[:, 0], 1.0 / (1.0 + math.exp(-(float(b[0]) - float(b[1])))), atol=1e-7)
+
+
+def test_classifier_matches_library_softmax_and_brute_force():
+    from scipy.special import softmax
+    rng = np.random.default_rng(4)
+    h = rng.standard_normal((17, 11)).astype(np.float32)
+    w = rng.standard_normal((11, 4)).astype(np.float32)        # not square: a transposed operand cannot pass
+    b = rng.standard_normal(4).astype(np.float32)
+    p = oracle.classify(h, w, b)
+    ref = softmax(h.astype(np.float64) @ w.astype(np.float64) + b.astype(np.float64), axis=1)
+    assert np.allclose(p, ref, atol=1e-7)
+    # brute force, pure Python
+    for n in (0, 16):
+        z = [float(b[c]) + sum(float(h[n, k]) * float(w[k, c]) for k in range(11)) for c in range(4)]
+        e = [math.exp(v) for v in z]
+        assert np.allclose(p[n], [v / sum(e) for v in e], atol=1e-7)
+    assert np.allclose(p.sum(axis=1), 1.0, atol=1e-6)
+    assert np.array_equal(p.argmax(axis=1), ref.argmax(axis=1))
+
+
+def test_classifier_shift_invariance_and_large_logits():
+    rng = np.random.default_rng(5)
+    h = rng.standard_normal((6, 8)).astype(np.float32)
+    w = rng.standard_normal((8, 3)).astype(np.float32)
+    b = rng.standard_normal(3).astype(np.float32)
+    p0 = oracle.classify(h, w, b)
+    assert np.allclose(oracle.classify(h, w, b + np.float32(7.5)), p0, atol=1e-6)
+    big = oracle.classify(h * np.float32(300.0), w, b)          # logits of several hundred: no overflow
+    assert np.isfinite(big).all() and np.allclose(big.sum(axis=1), 1.0, atol=1e-6)
