@@ -107,6 +107,37 @@ def run_scheduler(w, sched, precision, steps, warmup):
         net.close()
 
 
+def head_stage(w, n_classes, reps=50):
+    """The per-node classifier head on the h rows of one forward: mean kernel time from events on the launch stream
+    (tl_classify is launched on torch's current stream), against the memory roofline (h read once, probabilities
+    written once)."""
+    import torch
+    from paper_1809_00832_amd import binding
+    net = binding.TreeNet(w.params, scheduler="level_device")
+    try:
+        net.load(w.trees)
+        net.forward()
+        H, N = w.params.hidden, w.trees.n_nodes
+        g = torch.Generator(device="cuda").manual_seed(1)
+        ws = torch.randn((H, n_classes), device="cuda", generator=g) * (H ** -0.5)
+        bs = torch.zeros(n_classes, device="cuda")
+        probs = torch.empty((N, n_classes), device="cuda")
+        for _ in range(5):
+            binding.tl_classify(net.ctx, net.batch["h"], ws, bs, probs)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            binding.tl_classify(net.ctx, net.batch["h"], ws, bs, probs)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ms = sum(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) / reps
+        bytes_ = (N * H + N * n_classes + H * n_classes + n_classes) * 4.0
+        return {"classes": n_classes, "ms": ms, "bound": "hbm", "achieved": bytes_ / (ms * 1e-3) / 1e9, "peak": HBM_GBS,
+                "unit": "GB/s", "frac": bytes_ / (ms * 1e-3) / 1e9 / HBM_GBS, "bytes_per_launch": bytes_}
+    finally:
+        net.close()
+
+
 def cpu_baseline(w):
     """The CPU checker as it stands, all trees once, one thread per host core (at most 16)."""
     import oracle
@@ -143,6 +174,7 @@ def main():
     ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--head", type=int, default=5, help="classes of the per-node classifier head timed as an extra stage (0: skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
@@ -202,6 +234,8 @@ def main():
     bound_ms, n_heights = span_bound_ms(w, peak)
     out["span_bound"] = {"internal_ms": bound_ms, "heights": n_heights,
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
+    if args.head > 0:
+        out["head"] = head_stage(w, args.head)
     if not args.no_compare:
         comp = {}
         for sched in ("ready", "level_device", "level_host"):

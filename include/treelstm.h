@@ -161,6 +161,22 @@ int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
  * internal-node kernel.  Waits for the stream. */
 int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
 
+/*
+ * Per-node classifier head (Section 6.1: the evaluated networks label all nodes of a parse
+ * tree; the paper does not print the head, the usual form is taken):
+ *     probs[n] = softmax(h[n] W_s + b_s)          for n = 0 .. n_rows-1
+ * Asynchronous on hip_stream; call it after tl_forward on the same stream to label a batch.
+ *   h     [n_rows x H] fp32, H = cfg.hidden of ctx       DEVICE, read-only
+ *   w_s   [H x n_classes] fp32, row-major                 DEVICE, read-only
+ *   b_s   [n_classes] fp32                                DEVICE, read-only
+ *   probs [n_rows x n_classes] fp32 out                   DEVICE
+ * fp32 arithmetic throughout (one pass over h; bound by memory bandwidth).
+ * 1 <= n_classes <= 32 and n_classes * H <= 24576, else TL_EINVAL.  Nothing is allocated and
+ * nothing of the context changes.
+ */
+int tl_classify(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const float *b_s, int n_classes,
+                float *probs, void *hip_stream);
+
 const char *tl_strerror(int code);
 
 /* Frees the context and everything it owns.  Waits for the device. */

@@ -20,7 +20,7 @@ TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4,
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats",
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_classify",
            "tl_strerror", "tl_destroy")
 
 
@@ -57,6 +57,8 @@ def lib():
         L.tl_last_stats.restype = ci
         L.tl_last_stats.argtypes = [vp] + [ctypes.POINTER(ci)] * 3
         L.tl_strerror.restype = ctypes.c_char_p
+        L.tl_classify.restype = ci
+        L.tl_classify.argtypes = [vp, ci, vp, vp, vp, ci, vp, vp]
         L.tl_strerror.argtypes = [ci]
         L.tl_destroy.restype = ci
         L.tl_destroy.argtypes = [vp]
@@ -120,6 +122,20 @@ def tl_last_stats(ctx):
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().tl_last_stats(ctx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "tl_last_stats")
     return {"n_levels": a.value, "n_tiles": b.value, "n_workgroups": c.value}
+
+
+def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):
+    """probs = softmax(h @ w_s + b_s) row by row; all arguments are float32 CUDA tensors.  Returns probs."""
+    import torch
+    n_rows, n_classes = int(h.shape[0]), int(w_s.shape[1])
+    for t in (h, w_s, b_s):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    if probs is None:
+        probs = torch.empty((n_rows, n_classes), dtype=torch.float32, device=h.device)
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_classify(ctx, n_rows, h.data_ptr(), w_s.data_ptr(), b_s.data_ptr(), n_classes, probs.data_ptr(), st),
+           "tl_classify")
+    return probs
 
 
 def tl_strerror(code: int) -> str:

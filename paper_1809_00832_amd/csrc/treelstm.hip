@@ -12,6 +12,7 @@
 #include "structure.hpp"
 #include "cell_tile.hpp"
 #include "schedulers.hpp"
+#include "classify.hpp"
 
 using namespace tl;
 
@@ -644,6 +645,26 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups)
     if (n_levels) *n_levels = ctx->host_ctl->n_levels;
     if (n_tiles) *n_tiles = (int)ctx->host_ctl->tiles.v;
     if (n_workgroups) *n_workgroups = ctx->last_grid;
+    return TL_OK;
+}
+
+int tl_classify(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const float *b_s, int n_classes, float *probs,
+                void *hip_stream)
+{
+    if (!ctx || !h || !w_s || !b_s || !probs) return TL_EINVAL;
+    if (n_rows < 0 || n_classes < 1 || n_classes > CLS_MAX_CLASSES) return TL_EINVAL;
+    if (n_rows == 0) return TL_OK;
+    const int H = ctx->cfg.hidden, Hp = (H + 3) & ~3;
+    const size_t lds = (size_t)n_classes * Hp * sizeof(float);
+    if (lds > 96 * 1024) return TL_EINVAL;
+    typedef void (*cls_kernel)(const float *, const float *, const float *, float *, int, int, int);
+    const cls_kernel k = n_classes <= 2 ? k_classify<2> : n_classes <= 8 ? k_classify<8> : n_classes <= 16 ? k_classify<16> : k_classify<32>;
+    TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    long long blocks = ((long long)n_rows + 15) / 16;
+    const long long cap = (long long)ctx->n_cu * 8;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(256), lds, (hipStream_t)hip_stream, h, w_s, b_s, probs, n_rows, H, n_classes);
+    TL_HIP(hipGetLastError());
     return TL_OK;
 }
 
