@@ -138,6 +138,33 @@ def head_stage(w, n_classes, reps=50):
         net.close()
 
 
+def length_sweep(steps, warmup):
+    """Latency of ONE tree (no batching) against its number of leaves, parameters of the `sentence` workload: the
+    experiment of Figure 11 (time per instance by sentence length; with enough parallel units a tree of N words takes
+    O(log N) steps when it is balanced, O(N) when it is a chain)."""
+    from paper_1809_00832_amd import binding, synth
+    base = synth.workload("sentence")
+    rows = []
+    for shape in ("balanced", "random", "chain"):
+        for leaves in (2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
+            trees = synth.make_trees(100 + leaves, [leaves], [shape], base.params.vocab)
+            row = {"shape": shape, "leaves": leaves, "height": int(heights_of(trees).max())}
+            for sched in ("level_device", "ready"):
+                net = binding.TreeNet(base.params, scheduler=sched)
+                try:
+                    net.load(trees)
+                    for _ in range(warmup):
+                        net.forward()
+                    row[sched + "_ms"] = time_steps(net, steps) * 1e3
+                    if binding.tl_status(net.ctx) != 0:
+                        raise RuntimeError("forward failed")
+                finally:
+                    net.close()
+            rows.append(row)
+    print(json.dumps({"length_sweep": rows, "hidden": base.params.hidden, "embed_dim": base.params.embed_dim, "dtype": "f32",
+                      "note": "one tree per forward, whole tl_forward (structure pass, leaves, internal nodes, roots)"}))
+
+
 def cpu_baseline(w):
     """The CPU checker as it stands, all trees once, one thread per host core (at most 16)."""
     import oracle
@@ -175,6 +202,8 @@ def main():
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--head", type=int, default=5, help="classes of the per-node classifier head timed as an extra stage (0: skip)")
+    ap.add_argument("--length-sweep", action="store_true",
+                    help="print only the latency of single trees of 2..1024 leaves (balanced, random, chain)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
@@ -192,6 +221,9 @@ def main():
     torch.cuda.set_device(0)
     if args.copy_calibration:
         copy_calibration()
+        return
+    if args.length_sweep:
+        length_sweep(min(args.steps, 30), min(args.warmup, 5))
         return
     precision = binding.TL_F32 if args.precision == "f32" else binding.TL_BF16_IN
 
