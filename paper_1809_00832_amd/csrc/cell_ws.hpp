@@ -82,7 +82,11 @@ template <int SPW> struct WsLoadGeom {
 // NaN).  Rows that do not exist (-1 in the row table) read row 0 instead: every MFMA output row
 // depends on its own A row only, and the results of such rows are never stored.
 // The caller guarantees rows < 2^24 and table bytes < 2^32.
-template <int SEG, int SPW, typename T = float> struct WsRowRequest {
+// TAIL: fp32 rows whose length is even but not a multiple of 4 (so rows are 8-byte, not 16-byte
+// aligned, which the two 8-byte loads of a device-scope request tolerate).  The last request of
+// a row then covers two elements of the row and two of whatever follows it in memory; the lanes
+// concerned take their second 8 bytes from a block of zeros instead.
+template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowRequest {
     using G = WsLoadGeom<SPW>;
     static constexpr int EPL = 16 / (int)sizeof(T);             // elements per lane and load
     const char *table;
@@ -90,20 +94,25 @@ template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     unsigned lane_off, row_bytes;
     int sub;
     unsigned off[G::NL];
+    const char *hi_base;                                        // TAIL only: where the second 8 bytes come from
+    unsigned hi_mask;
 
     // rows of `table` are `stride` elements apart; what a row holds between its data and `stride`
     // elements reads as zero
     template <typename Smem>
-    __device__ inline void init(const Smem &sm, const T *__restrict__ table_, int Lp, int stride, int wave, int lane)
+    __device__ inline void init(const Smem &sm, const Fwd &f, const T *__restrict__ table_, int Lp, int stride, int wave, int lane)
     {
         table = reinterpret_cast<const char *>(table_);
         sub = lane / G::LPR;                                    // which of the RPL rows of a load
         const int k = 4 * EPL * SPW * wave + (lane % G::LPR) * EPL;   // position on the padded K axis
         const int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
-        const int o = min(k - seg * Lp, stride - EPL);
+        const int o = min(k - seg * Lp, (stride - EPL + 3) & ~3);
         src = seg ? sm.src1 : sm.src0;
         lane_off = (unsigned)o * (unsigned)sizeof(T);
         row_bytes = (unsigned)stride * (unsigned)sizeof(T);
+        const bool tail = TAIL && o + EPL > stride;
+        hi_base = tail ? reinterpret_cast<const char *>(f.zeros) : table + 8;
+        hi_mask = tail ? 0u : ~0u;
     }
     // byte offsets of the requests of block [row0, row0 + 16): one batch of row-table reads
     __device__ inline void prepare(int row0)
@@ -116,7 +125,19 @@ template <int SEG, int SPW, typename T = float> struct WsRowRequest {
     }
     template <bool COH> __device__ inline floatx4 issue(int j) const
     {
-        return ld_f4<COH>(reinterpret_cast<const float *>(table + off[j]));
+        if constexpr (!TAIL) {
+            return ld_f4<COH>(reinterpret_cast<const float *>(table + off[j]));
+        } else {
+            static_assert(sizeof(T) == 4, "tail handling is for fp32 rows");
+            const unsigned long long a = ld_dev(reinterpret_cast<const unsigned long long *>(table + off[j]));
+            const unsigned long long b = ld_dev(reinterpret_cast<const unsigned long long *>(hi_base + (off[j] & hi_mask)));
+            floatx4 v;
+            v.x = __uint_as_float((unsigned)a);
+            v.y = __uint_as_float((unsigned)(a >> 32));
+            v.z = __uint_as_float((unsigned)b);
+            v.w = __uint_as_float((unsigned)(b >> 32));
+            return v;
+        }
     }
 };
 
@@ -136,7 +157,7 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 // Evaluates the `count` <= WS_TABLE_ROWS rows in sm.node/src0/src1 for column group cg, 16 at a
 // time, the requests of a block's rows always one block ahead.  All four waves call it together;
 // a __syncthreads() has been passed since the row tables were written.
-template <int EPI, bool COH, int SPW>
+template <int EPI, bool COH, int SPW, bool TAIL = false>
 __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
                                int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
 {
@@ -150,8 +171,8 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     const bool hu_ok = hu < H;
     const float *a_lane = &sm.a[wave][(lane & 15) * WsSmemT<SPW>::A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
 
-    WsRowRequest<SEG, SPW> req;
-    req.init(sm, table, gm.Lp, gm.L, wave, lane);
+    WsRowRequest<SEG, SPW, float, TAIL> req;
+    req.init(sm, f, table, gm.Lp, gm.L, wave, lane);
     floatx4 rows[NL];
     req.prepare(0);
 #pragma unroll
@@ -281,7 +302,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
 
     WsRowRequest<SEG, S, unsigned short> req;
-    req.init(sm, table, stride, stride, wave, lane);
+    req.init(sm, f, table, stride, stride, wave, lane);
     floatx4 rows[NL];
     req.prepare(0);
 #pragma unroll

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                     }
                 }
                 if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
-                else ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+                else ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, count, my_cg, w);
                 if (holds) appended += frontier_push(f, ticket);
             }
         } else {
@@ -538,7 +538,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         if constexpr (SPW > 0 && BF16) {
             ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
         } else if constexpr (SPW > 0) {
-            ws_tile<EPI, true, SPW>(sm, f, f.inner, f.h, count, my_cg, w);
+            ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, count, my_cg, w);
         } else {
             for (int j = member; j < f.n_cg; j += f.gang_size)
                 cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));

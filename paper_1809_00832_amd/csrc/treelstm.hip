@@ -102,12 +102,12 @@ template <int EPI> fwd_kernel ready_kernel_epi(bool vec4, int spw, bool bf16)
         }
     }
     switch (spw) {
-    case 1: return k_ready_persistent<EPI, true, 1>;
-    case 2: return k_ready_persistent<EPI, true, 2>;
-    case 4: return k_ready_persistent<EPI, true, 4>;
-    case 5: return k_ready_persistent<EPI, true, 5>;
-    case 8: return k_ready_persistent<EPI, true, 8>;
-    case 16: return k_ready_persistent<EPI, true, 16>;
+    case 1: return vec4 ? k_ready_persistent<EPI, true, 1> : k_ready_persistent<EPI, false, 1>;
+    case 2: return vec4 ? k_ready_persistent<EPI, true, 2> : k_ready_persistent<EPI, false, 2>;
+    case 4: return vec4 ? k_ready_persistent<EPI, true, 4> : k_ready_persistent<EPI, false, 4>;
+    case 5: return vec4 ? k_ready_persistent<EPI, true, 5> : k_ready_persistent<EPI, false, 5>;
+    case 8: return vec4 ? k_ready_persistent<EPI, true, 8> : k_ready_persistent<EPI, false, 8>;
+    case 16: return vec4 ? k_ready_persistent<EPI, true, 16> : k_ready_persistent<EPI, false, 16>;
     default: return vec4 ? k_ready_persistent<EPI, true, 0> : k_ready_persistent<EPI, false, 0>;
     }
 }
@@ -125,12 +125,12 @@ template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw, bool bf16)
         }
     }
     switch (spw) {
-    case 1: return k_levels_persistent<EPI, true, 1>;
-    case 2: return k_levels_persistent<EPI, true, 2>;
-    case 4: return k_levels_persistent<EPI, true, 4>;
-    case 5: return k_levels_persistent<EPI, true, 5>;
-    case 8: return k_levels_persistent<EPI, true, 8>;
-    case 16: return k_levels_persistent<EPI, true, 16>;
+    case 1: return vec4 ? k_levels_persistent<EPI, true, 1> : k_levels_persistent<EPI, false, 1>;
+    case 2: return vec4 ? k_levels_persistent<EPI, true, 2> : k_levels_persistent<EPI, false, 2>;
+    case 4: return vec4 ? k_levels_persistent<EPI, true, 4> : k_levels_persistent<EPI, false, 4>;
+    case 5: return vec4 ? k_levels_persistent<EPI, true, 5> : k_levels_persistent<EPI, false, 5>;
+    case 8: return vec4 ? k_levels_persistent<EPI, true, 8> : k_levels_persistent<EPI, false, 8>;
+    case 16: return vec4 ? k_levels_persistent<EPI, true, 16> : k_levels_persistent<EPI, false, 16>;
     default: return vec4 ? k_levels_persistent<EPI, true, 0> : k_levels_persistent<EPI, false, 0>;
     }
 }
@@ -333,7 +333,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
             const int needed = round_up(2 * ctx->hs, 128) / 128;
             for (int sz : WSB_SIZES)
                 if (sz >= needed) { ctx->spw = sz; break; }
-        } else if (H % 4 == 0) {
+        } else if (H % 2 == 0) {      // rows of h must be 8-byte aligned at least
             const int needed = round_up(2 * round_up(H, 4), KC) / STEP_K / 4;
             for (int sz : WS_SIZES)
                 if (sz >= needed) { ctx->spw = sz; break; }
@@ -409,8 +409,10 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     ctx->persistent_grid = occ * ctx->n_cu;
     if (ctx->spw > 0) {
         ctx->ws_lds = ws_lds_bytes(ctx->spw, bf16);
-        if ((rc = allow_lds(ready_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
-        if ((rc = allow_lds(levels_kernel(cfg->cell, true, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
+        for (int v = 0; v < 2; ++v) {   // fp32: rows 16-byte aligned / 8-byte aligned
+            if ((rc = allow_lds(ready_kernel(cfg->cell, v != 0, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
+            if ((rc = allow_lds(levels_kernel(cfg->cell, v != 0, ctx->spw, bf16), ctx->ws_lds)) != TL_OK) return rc;
+        }
         int o1 = 0, o2 = 0;
         TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o1, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, ctx->spw, bf16)),
                                                             WG_THREADS, ctx->ws_lds));
@@ -503,7 +505,8 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     const bool bf16 = cfg.precision == TL_BF16_IN;
     // the weight-stationary cell addresses rows with 24-bit row numbers and 32-bit byte offsets
     const bool ws_range = n_nodes < (1 << 24) && (unsigned long long)n_nodes * cfg.hidden * 4ull < (1ull << 32);
-    const int spw = ((bf16 || vec4_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
+    const bool pair_inner = (cfg.hidden % 2 == 0) && (((uintptr_t)h & 7) == 0);      // rows 8-byte aligned
+    const int spw = ((bf16 || pair_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
     if (persistent && spw > 0 && bf16) { f.hb = ctx->hb; f.hs = ctx->hs; }
     const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;

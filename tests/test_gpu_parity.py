@@ -118,6 +118,7 @@ def test_ragged_and_degenerate_batches(sched):
         (dict(vocab=50, E=7, H=5), [1]),
         (dict(vocab=50, E=7, H=5), [1, 1, 1]),
         (dict(vocab=50, E=12, H=20), [2]),
+        (dict(vocab=50, E=10, H=6), [3, 1, 20]),          # rows 8-byte but not 16-byte aligned
         (dict(vocab=50, E=9, H=33), [1, 2, 3, 1, 70, 5]),
         (dict(vocab=50, E=64, H=64), [17] * 9 + [1] + [130]),
     ]
