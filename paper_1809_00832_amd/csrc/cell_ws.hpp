@@ -171,12 +171,49 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     const bool hu_ok = hu < H;
     const float *a_lane = &sm.a[wave][(lane & 15) * WsSmemT<SPW>::A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
 
+    // Second half of a block: the four K-range partial sums have met in LDS (a barrier has been
+    // passed since they were written); wave w finishes accumulator row w of the block.
+    auto finish = [&](const float *red, int enode, bool ev, float cl, float cr) {
+        float gate[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            float sum = red[((0 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((1 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
+            sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
+            gate[g] = sum + w.bias[g];
+        }
+        if (ev) {
+            const size_t o = (size_t)enode * H + hu;
+            if constexpr (EPI == EPI_LSTM_INNER) {
+                float cc, hh;
+                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
+                st_f<COH>(f.c + o, cc);
+                st_f<COH>(f.h + o, hh);
+            } else if constexpr (EPI == EPI_LSTM_LEAF) {
+                float cc, hh;
+                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
+                st_f<COH>(f.c + o, cc);
+                st_f<COH>(f.h + o, hh);
+            } else {
+                st_f<COH>(f.h + o, tanh_f(gate[0]));
+            }
+        }
+    };
+
     WsRowRequest<SEG, SPW, float, TAIL> req;
     req.init(sm, f, table, gm.Lp, gm.L, wave, lane);
     floatx4 rows[NL];
     req.prepare(0);
 #pragma unroll
     for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
+    // The second half of block rb - 1 is done inside the MFMA phase of block rb (after its first
+    // k-step): what it waits for (the barrier, LDS round trips, the c rows) has then had a k-step
+    // of MFMAs to arrive, instead of leaving the matrix pipe idle between two blocks.
+    int p_enode = -1;
+    bool p_ev = false;
+    float p_cl = 0.f, p_cr = 0.f;
+    constexpr int FINISH_AFTER = SPW > 1 ? 1 : 0;               // k-step after which the previous block is finished
     for (int rb = 0; rb < nrb; ++rb) {
         float *red = sm.red[rb & 1];
         ws_park_rows<SPW>(sm, rows, wave, lane);            // waits for the requested rows
@@ -210,41 +247,27 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             for (int q = 0; q < LOADS_PER_STEP; ++q)
                 if (s * LOADS_PER_STEP + q < NL) rows[s * LOADS_PER_STEP + q] = req.template issue<COH>(s * LOADS_PER_STEP + q);
             __builtin_amdgcn_sched_barrier(0);              // keep the request where it is
+            if (s == FINISH_AFTER && rb > 0) {
+                __syncthreads();                            // every wave has written its partial sums of block rb - 1
+                finish(sm.red[(rb - 1) & 1], p_enode, p_ev, p_cl, p_cr);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        // the four K-range partial sums meet in LDS; wave w finishes accumulator row w
+        // this block's partial sums go to LDS; they are picked up one block later (or after the loop)
 #pragma unroll
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < 4; ++v) red[((wave * NG + g) * 4 + v) * 64 + lane] = acc[g][v];
-        __syncthreads();
-        float gate[NG];
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            float sum = red[((0 * NG + g) * 4 + wave) * 64 + lane];
-            sum += red[((1 * NG + g) * 4 + wave) * 64 + lane];
-            sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
-            sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
-            gate[g] = sum + w.bias[g];
-        }
-        if (ev) {
-            const size_t o = (size_t)enode * H + hu;
-            if constexpr (EPI == EPI_LSTM_INNER) {
-                float cc, hh;
-                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
-                st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, hh);
-            } else if constexpr (EPI == EPI_LSTM_LEAF) {
-                float cc, hh;
-                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
-                st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, hh);
-            } else {
-                st_f<COH>(f.h + o, tanh_f(gate[0]));
-            }
-        }
-        // no second barrier: the next block writes the other reduction buffer, and the block after
-        // that passes the next block's barrier before it writes this one again
+        p_enode = enode;
+        p_ev = ev;
+        p_cl = cl;
+        p_cr = cr;
+        // the two reduction buffers alternate: buffer rb & 1 is written again at the end of block
+        // rb + 2, after every wave has passed the barrier inside block rb + 2, hence after it has
+        // read this buffer (inside block rb + 1)
     }
+    __syncthreads();
+    if (nrb > 0) finish(sm.red[(nrb - 1) & 1], p_enode, p_ev, p_cl, p_cr);
     __syncthreads();                                        // row tables and LDS may be rewritten after this call
 }
 
