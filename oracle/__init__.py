@@ -27,6 +27,9 @@ def _load():
         lib = ctypes.CDLL(LIB)
         lib.oracle_structure.restype = ctypes.c_int
         lib.oracle_structure.argtypes = [ctypes.c_int, ctypes.c_int, _I, _I, _I, _I, _I, _I]
+        lib.oracle_backward.restype = ctypes.c_int
+        lib.oracle_backward.argtypes = ([ctypes.c_int] * 3 + [_F] * 5 + [ctypes.c_int, ctypes.c_int] + [_I] * 4 + [_F] * 3
+                                        + [_F] * 5)
         lib.oracle_classify.restype = ctypes.c_int
         lib.oracle_classify.argtypes = [ctypes.c_int] * 3 + [_F] * 4
         lib.oracle_forward.restype = ctypes.c_int
@@ -89,6 +92,25 @@ def forward(cell, vocab, embed_dim, hidden, emb, w_leaf, b_leaf, u, b, v,
     if rc != 0:
         raise ValueError("malformed tree batch")
     return {"h": h, "c": c, "h_root": h_root, "c_root": c_root}
+
+
+def backward(params, trees, h, c, g_h):
+    """Gradients of a loss with dL/dh[n] = g_h[n] (TreeLSTM): dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x [N x E])."""
+    lib = _load()
+    assert params.cell == 0
+    H, E = params.hidden, params.embed_dim
+    n_trees, n_nodes = len(trees.tree_off) - 1, len(trees.left)
+    out = {"d_u": np.zeros((2 * H, 5 * H), np.float32), "d_b": np.zeros(5 * H, np.float32),
+           "d_w_leaf": np.zeros((E, 3 * H), np.float32), "d_b_leaf": np.zeros(3 * H, np.float32),
+           "d_x": np.zeros((n_nodes, E), np.float32)}
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    rc = lib.oracle_backward(params.vocab, E, H, _f(params.emb), _f(params.w_leaf), _f(params.b_leaf), _f(params.u),
+                             _f(params.b), n_trees, n_nodes, _i(trees.tree_off), _i(trees.left), _i(trees.right),
+                             _i(trees.word), _f(f32(h)), _f(f32(c)), _f(f32(g_h)),
+                             _f(out["d_u"]), _f(out["d_b"]), _f(out["d_w_leaf"]), _f(out["d_b_leaf"]), _f(out["d_x"]))
+    if rc != 0:
+        raise ValueError("malformed tree batch")
+    return out
 
 
 def classify(h, w_s, b_s):

@@ -278,3 +278,137 @@ int oracle_classify(int n_rows, int H, int C, const float *h, const float *w_s, 
     free(z);
     return 0;
 }
+
+/*
+ * Backward pass of the TreeLSTM forward above (Section 4.2.2, "Recursive Backpropagation": the
+ * gradient of a recursive call is the recursive application of the gradient of its body, with
+ * the forward values of each call instance kept for it - here the stored h / c rows, found by
+ * node index).
+ *
+ * The loss is any function of the node states; the caller passes g_h[n] = dL/dh[n] for every
+ * node (zero rows where a node's state does not enter the loss directly).  With the forward
+ * definitions above, going from a node to its children (dh_n = g_h[n] + what the parent sent,
+ * dc_n = what the parent sent, zero at roots):
+ *   t = tanh(c_n)      do = dh_n * t        dct = dc_n + dh_n * o * (1 - t^2)
+ *   internal:  dgi = dct*u*i(1-i)   dgfl = dct*c_l*fl(1-fl)   dgfr = dct*c_r*fr(1-fr)
+ *              dgo = do*o(1-o)      dgu = dct*i*(1-u^2)
+ *              dc_l = dct*fl        dc_r = dct*fr
+ *              [dh_l ; dh_r] (sent to the children) = dG U^T      dU += a^T dG     db += dG
+ *   leaf:      dgi = dct*u*i(1-i)   dgo = do*o(1-o)   dgu = dct*i*(1-u^2)
+ *              dx = dG W_x^T        dW_x += x^T dG    db_x += dG
+ * Gates are recomputed in double from the stored fp32 child states (the same values the forward
+ * cell consumed); all sums are accumulated in double and rounded to fp32 once at the end.
+ * d_x is [n_nodes x E]: row n is dL/d(embedding row used by leaf n); rows of internal nodes are zero.
+ * TreeLSTM only.  Returns 0, or -1 on a malformed batch.
+ * Pinned by tests against torch autograd on an independent float64 evaluation, finite
+ * differences, and closed forms.
+ */
+typedef struct {
+    int E, H;
+    const float *emb, *w_leaf, *b_leaf, *u, *b, *h, *c, *g_h;
+    const int32_t *left, *right, *word;
+    double *d_u, *d_b, *d_w_leaf, *d_b_leaf;   /* accumulators */
+    float *d_x;
+} bwd_t;
+
+static void backward_node(const bwd_t *m, int n, const double *dh, const double *dc, double *scratch)
+{
+    const int H = m->H, E = m->E;
+    const float *c = m->c + (size_t)n * H;
+    if (m->left[n] < 0) {
+        double *x = scratch, *g = x + E, *dg = g + 3 * H;
+        const float *xr = m->emb + (size_t)m->word[n] * E;
+        for (int k = 0; k < E; ++k) x[k] = xr[k];
+        affine(x, E, m->w_leaf, m->b_leaf, 3 * H, g);
+        for (int j = 0; j < H; ++j) {
+            const double i = sigm(g[j]), o = sigm(g[H + j]), u = tanh(g[2 * H + j]);
+            const double t = tanh((double)c[j]);
+            const double d_o = dh[j] * t, dct = dc[j] + dh[j] * o * (1.0 - t * t);
+            dg[j] = dct * u * i * (1.0 - i);
+            dg[H + j] = d_o * o * (1.0 - o);
+            dg[2 * H + j] = dct * i * (1.0 - u * u);
+        }
+        for (int k = 0; k < E; ++k) {
+            const float *row = m->w_leaf + (size_t)k * 3 * H;
+            double s = 0.0;
+            for (int j = 0; j < 3 * H; ++j) {
+                s += dg[j] * (double)row[j];
+                m->d_w_leaf[(size_t)k * 3 * H + j] += x[k] * dg[j];
+            }
+            m->d_x[(size_t)n * E + k] = (float)s;
+        }
+        for (int j = 0; j < 3 * H; ++j) m->d_b_leaf[j] += dg[j];
+        return;
+    }
+    const int l = m->left[n], r = m->right[n];
+    double *a = scratch, *g = a + 2 * H, *dg = g + 5 * H, *dhl = dg + 5 * H, *dhr = dhl + H, *dcl = dhr + H, *dcr = dcl + H;
+    double *next = dcr + H;
+    const float *cl = m->c + (size_t)l * H, *cr = m->c + (size_t)r * H;
+    for (int k = 0; k < H; ++k) { a[k] = m->h[(size_t)l * H + k]; a[H + k] = m->h[(size_t)r * H + k]; }
+    affine(a, 2 * H, m->u, m->b, 5 * H, g);
+    for (int j = 0; j < H; ++j) {
+        const double i = sigm(g[j]), fl = sigm(g[H + j]), fr = sigm(g[2 * H + j]);
+        const double o = sigm(g[3 * H + j]), u = tanh(g[4 * H + j]);
+        const double t = tanh((double)c[j]);
+        const double d_o = dh[j] * t, dct = dc[j] + dh[j] * o * (1.0 - t * t);
+        dg[j] = dct * u * i * (1.0 - i);
+        dg[H + j] = dct * (double)cl[j] * fl * (1.0 - fl);
+        dg[2 * H + j] = dct * (double)cr[j] * fr * (1.0 - fr);
+        dg[3 * H + j] = d_o * o * (1.0 - o);
+        dg[4 * H + j] = dct * i * (1.0 - u * u);
+        dcl[j] = dct * fl;
+        dcr[j] = dct * fr;
+    }
+    for (int k = 0; k < 2 * H; ++k) {
+        const float *row = m->u + (size_t)k * 5 * H;
+        double s = 0.0;
+        for (int j = 0; j < 5 * H; ++j) {
+            s += dg[j] * (double)row[j];
+            m->d_u[(size_t)k * 5 * H + j] += a[k] * dg[j];
+        }
+        if (k < H) dhl[k] = s + (double)m->g_h[(size_t)l * H + k];
+        else dhr[k - H] = s + (double)m->g_h[(size_t)r * H + (k - H)];
+    }
+    for (int j = 0; j < 5 * H; ++j) m->d_b[j] += dg[j];
+    backward_node(m, l, dhl, dcl, next);
+    backward_node(m, r, dhr, dcr, next);
+}
+
+int oracle_backward(int vocab, int E, int H,
+                    const float *emb, const float *w_leaf, const float *b_leaf, const float *u, const float *b,
+                    int n_trees, int n_nodes, const int32_t *tree_off,
+                    const int32_t *left, const int32_t *right, const int32_t *word,
+                    const float *h, const float *c, const float *g_h,
+                    float *d_u, float *d_b, float *d_w_leaf, float *d_b_leaf, float *d_x)
+{
+    int32_t *parent = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *height = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *root = malloc(sizeof(int32_t) * (size_t)(n_trees > 0 ? n_trees : 1));
+    int rc = oracle_structure(n_trees, n_nodes, tree_off, left, right, parent, root, height);
+    for (int n = 0; rc == 0 && n < n_nodes; ++n)
+        if (left[n] < 0 && (word[n] < 0 || word[n] >= vocab)) rc = -1;
+    if (rc == 0) {
+        const size_t nu = (size_t)2 * H * 5 * H, nw = (size_t)E * 3 * H;
+        bwd_t m = { E, H, emb, w_leaf, b_leaf, u, b, h, c, g_h, left, right, word,
+                    calloc(nu, sizeof(double)), calloc((size_t)5 * H, sizeof(double)),
+                    calloc(nw, sizeof(double)), calloc((size_t)3 * H, sizeof(double)), d_x };
+        memset(d_x, 0, sizeof(float) * (size_t)n_nodes * E);
+        int max_h = 0;
+        for (int t = 0; t < n_trees; ++t) if (height[root[t]] > max_h) max_h = height[root[t]];
+        /* scratch of one node: 2H + 5H + 5H + 4H doubles (or E + 6H at a leaf); one such frame per level of the recursion */
+        const size_t frame = (size_t)(16 * H > E + 6 * H ? 16 * H : E + 6 * H);
+        double *scratch = malloc(sizeof(double) * frame * (size_t)(max_h + 2));
+        double *dh = malloc(sizeof(double) * (size_t)H), *dc = calloc((size_t)H, sizeof(double));
+        for (int t = 0; t < n_trees; ++t) {
+            for (int j = 0; j < H; ++j) dh[j] = (double)g_h[(size_t)root[t] * H + j];
+            backward_node(&m, root[t], dh, dc, scratch);
+        }
+        for (size_t i = 0; i < nu; ++i) d_u[i] = (float)m.d_u[i];
+        for (int j = 0; j < 5 * H; ++j) d_b[j] = (float)m.d_b[j];
+        for (size_t i = 0; i < nw; ++i) d_w_leaf[i] = (float)m.d_w_leaf[i];
+        for (int j = 0; j < 3 * H; ++j) d_b_leaf[j] = (float)m.d_b_leaf[j];
+        free(m.d_u); free(m.d_b); free(m.d_w_leaf); free(m.d_b_leaf); free(scratch); free(dh); free(dc);
+    }
+    free(parent); free(height); free(root);
+    return rc;
+}

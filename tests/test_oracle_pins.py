@@ -533,3 +533,121 @@ def test_classifier_shift_invariance_and_large_logits():
     assert np.allclose(oracle.classify(h, w, b + np.float32(7.5)), p0, atol=1e-6)
     big = oracle.classify(h * np.float32(300.0), w, b)          # logits of several hundred: no overflow
     assert np.isfinite(big).all() and np.allclose(big.sum(axis=1), 1.0, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------- backward pass
+def _torch_loss(p, trees, g_h, dtype=torch.float64):
+    """Independent evaluation in plain PyTorch (float64, recursion per tree): loss = sum_n <g_h[n], h[n]>.
+    Returns (loss, dict of leaf tensors that require grad)."""
+    t = {k: torch.tensor(np.asarray(getattr(p, k)), dtype=dtype, requires_grad=True)
+         for k in ("emb", "w_leaf", "b_leaf", "u", "b")}
+    H = p.hidden
+    g = torch.tensor(g_h, dtype=dtype)
+    left, right, word = trees.left, trees.right, trees.word
+    loss = torch.zeros((), dtype=dtype)
+
+    def ev(n):
+        nonlocal loss
+        if left[n] < 0:
+            z = t["emb"][int(word[n])] @ t["w_leaf"] + t["b_leaf"]
+            i, o, u = torch.sigmoid(z[:H]), torch.sigmoid(z[H:2 * H]), torch.tanh(z[2 * H:])
+            c = i * u
+        else:
+            hl, cl = ev(int(left[n]))
+            hr, cr = ev(int(right[n]))
+            z = torch.cat([hl, hr]) @ t["u"] + t["b"]
+            i, fl, fr = torch.sigmoid(z[:H]), torch.sigmoid(z[H:2 * H]), torch.sigmoid(z[2 * H:3 * H])
+            o, u = torch.sigmoid(z[3 * H:4 * H]), torch.tanh(z[4 * H:])
+            c = i * u + fl * cl + fr * cr
+        h = o * torch.tanh(c)
+        loss = loss + (g[n] * h).sum()
+        return h, c
+
+    _, root, _ = oracle.structure(trees.tree_off, trees.left, trees.right)
+    for r in root:
+        ev(int(r))
+    return loss, t
+
+
+def _backward_case(seed, E, H, leaves, shapes):
+    p = synth.make_treelstm_params(seed, 23, E, H, "xavier")
+    p = Params(p.cell, p.vocab, E, H, p.emb * 3, p.w_leaf * 2, p.b_leaf + 0.1, p.u * 2, p.b, None)
+    trees = synth.make_trees(seed, leaves, shapes, 23)
+    fwd = oracle.forward_params(p, trees)
+    rng = np.random.default_rng(seed)
+    g_h = rng.standard_normal(fwd["h"].shape).astype(np.float32)
+    g_h[rng.random(len(g_h)) < 0.3] = 0.0           # some nodes do not enter the loss directly
+    return p, trees, fwd, g_h
+
+
+def test_backward_matches_autograd_of_an_independent_evaluation():
+    """All five gradients against torch autograd through a float64 PyTorch recursion that shares nothing with the
+    checker (the checker recomputes gates from the stored fp32 states, hence the tolerance)."""
+    for seed, E, H, leaves, shapes in ((1, 5, 4, [1, 2, 7], ["random"] * 3), (2, 3, 6, [9, 4], ["chain", "balanced"]),
+                                       (3, 8, 3, [12], ["random"])):
+        p, trees, fwd, g_h = _backward_case(seed, E, H, leaves, shapes)
+        got = oracle.backward(p, trees, fwd["h"], fwd["c"], g_h)
+        loss, t = _torch_loss(p, trees, g_h)
+        loss.backward()
+        ref = {"d_u": t["u"].grad, "d_b": t["b"].grad, "d_w_leaf": t["w_leaf"].grad, "d_b_leaf": t["b_leaf"].grad}
+        for k, v in ref.items():
+            assert np.allclose(got[k], v.numpy(), rtol=2e-4, atol=2e-6), (seed, k, np.abs(got[k] - v.numpy()).max())
+        d_emb = np.zeros_like(p.emb, dtype=np.float64)
+        for n in np.nonzero(trees.left < 0)[0]:
+            d_emb[trees.word[n]] += got["d_x"][n]
+        assert np.allclose(d_emb, t["emb"].grad.numpy(), rtol=2e-4, atol=2e-6)
+        assert not got["d_x"][trees.left >= 0].any()             # rows of internal nodes stay zero
+
+
+def test_backward_matches_finite_differences():
+    """Central differences of the float64 evaluation, entry by entry, on a tiny case (no autograd involved)."""
+    p, trees, fwd, g_h = _backward_case(7, 3, 2, [3, 2], ["random", "random"])
+    got = oracle.backward(p, trees, fwd["h"], fwd["c"], g_h)
+    eps = 1e-6
+    for name, key in (("u", "d_u"), ("b", "d_b"), ("w_leaf", "d_w_leaf"), ("b_leaf", "d_b_leaf")):
+        base = np.asarray(getattr(p, name), dtype=np.float64)
+        for idx in list(np.ndindex(base.shape))[::3]:
+            vals = []
+            for s in (+eps, -eps):
+                w = base.copy()
+                w[idx] += s
+                q = Params(p.cell, p.vocab, p.embed_dim, p.hidden, p.emb, p.w_leaf, p.b_leaf, p.u, p.b, None)
+                q = q._replace(**{name: w}) if hasattr(q, "_replace") else _with(q, name, w)
+                with torch.no_grad():
+                    vals.append(float(_torch_loss(q, trees, g_h)[0]))
+            fd = (vals[0] - vals[1]) / (2 * eps)
+            assert abs(fd - got[key][idx]) <= 1e-5 + 1e-4 * abs(fd), (name, idx, fd, got[key][idx])
+
+
+def _with(p, name, value):
+    d = {k: getattr(p, k) for k in ("cell", "vocab", "embed_dim", "hidden", "emb", "w_leaf", "b_leaf", "u", "b", "v")}
+    d[name] = value
+    return Params(**d)
+
+
+def test_backward_closed_forms():
+    """Zero upstream gradient gives zero gradients; gradients are linear in g_h; a single-leaf tree has the
+    hand-derived leaf gradient."""
+    p, trees, fwd, g_h = _backward_case(11, 4, 3, [5, 1], ["random", "random"])
+    zero = oracle.backward(p, trees, fwd["h"], fwd["c"], np.zeros_like(g_h))
+    assert all(not v.any() for v in zero.values())
+    one = oracle.backward(p, trees, fwd["h"], fwd["c"], g_h)
+    two = oracle.backward(p, trees, fwd["h"], fwd["c"], 2 * g_h)
+    for k in one:
+        assert np.allclose(two[k], 2 * one[k], rtol=1e-6, atol=1e-9)
+    # the single-leaf tree alone: dL/db_leaf by hand
+    single, _ = synth.subset(trees, [1])
+    f1 = oracle.forward_params(p, single)
+    g1 = np.array([[0.7, -0.2, 0.4]], np.float32)
+    got = oracle.backward(p, single, f1["h"], f1["c"], g1)
+    x = p.emb[single.word[0]].astype(np.float64)
+    z = x @ p.w_leaf.astype(np.float64) + p.b_leaf
+    H = 3
+    i, o, u = 1 / (1 + np.exp(-z[:H])), 1 / (1 + np.exp(-z[H:2 * H])), np.tanh(z[2 * H:])
+    c = i * u
+    t = np.tanh(c)
+    dct = g1[0] * o * (1 - t * t)
+    ref = np.concatenate([dct * u * i * (1 - i), g1[0] * t * o * (1 - o), dct * i * (1 - u * u)])
+    assert np.allclose(got["d_b_leaf"], ref, rtol=1e-5, atol=1e-7)
+    assert np.allclose(got["d_w_leaf"], np.outer(x, ref), rtol=1e-5, atol=1e-7)
+    assert np.allclose(got["d_x"][0], p.w_leaf.astype(np.float64) @ ref, rtol=1e-5, atol=1e-7)
