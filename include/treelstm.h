@@ -162,6 +162,27 @@ int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
 int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
 
 /*
+ * Backward pass of a TL_TREELSTM / TL_F32 forward (Section 4.2.2, recursive backpropagation: the
+ * gradient of a node's cell is applied from the roots down, each node finding its forward values
+ * by node index).  The loss may depend on every node's h: g_h[n] = dL/dh[n] (zero rows where it
+ * does not).  h and c are the rows tl_forward wrote for the same batch.
+ *   tree_off, left, right, word, h, c   as in tl_forward (h, c read-only)          DEVICE
+ *   g_h       [n_nodes x H] fp32                                                  DEVICE, read-only
+ *   d_u       [2H x 5H], d_b [5H], d_w_leaf [E x 3H], d_b_leaf [3H]  fp32 out,
+ *             sums over all nodes of the batch, same layouts as the parameters    DEVICE
+ *   d_x       [n_nodes x E] fp32 out: row n = dL/d(embedding row used by leaf n);
+ *             rows of internal nodes are zero (the caller scatter-adds by word)    DEVICE
+ * fp32 arithmetic; the gate activations are recomputed from h / c, not stored by the forward.
+ * Work is enqueued on hip_stream, but the call waits for the structure pass (it needs the
+ * number of heights) and returns the deferred structure status: TL_OK, TL_ESTRUCT, ...
+ * The first call for a larger batch than any before allocates workspace.  Other cells or
+ * TL_BF16_IN: TL_EINVAL.
+ */
+int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+                const int32_t *right, const int32_t *word, const float *h, const float *c, const float *g_h,
+                float *d_u, float *d_b, float *d_w_leaf, float *d_b_leaf, float *d_x, void *hip_stream);
+
+/*
  * Per-node classifier head (Section 6.1: the evaluated networks label all nodes of a parse
  * tree; the paper does not print the head, the usual form is taken):
  *     probs[n] = softmax(h[n] W_s + b_s)          for n = 0 .. n_rows-1

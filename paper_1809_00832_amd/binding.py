@@ -20,7 +20,7 @@ TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4,
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_classify",
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_classify",
            "tl_strerror", "tl_destroy")
 
 
@@ -57,6 +57,8 @@ def lib():
         L.tl_last_stats.restype = ci
         L.tl_last_stats.argtypes = [vp] + [ctypes.POINTER(ci)] * 3
         L.tl_strerror.restype = ctypes.c_char_p
+        L.tl_backward.restype = ci
+        L.tl_backward.argtypes = [vp, ci, ci] + [vp] * 13
         L.tl_classify.restype = ci
         L.tl_classify.argtypes = [vp, ci, vp, vp, vp, ci, vp, vp]
         L.tl_strerror.argtypes = [ci]
@@ -122,6 +124,24 @@ def tl_last_stats(ctx):
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().tl_last_stats(ctx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)), "tl_last_stats")
     return {"n_levels": a.value, "n_tiles": b.value, "n_workgroups": c.value}
+
+
+def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
+    """Gradients for a batch that tl_forward has evaluated (`batch` is the dict TreeNet.load returns, holding h and
+    c); g_h [N x H] float32 CUDA tensor.  Returns dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x) of CUDA tensors."""
+    import torch
+    N, H, E = batch["N"], int(batch["h"].shape[1]), int(embed_dim)
+    assert g_h.is_cuda and g_h.dtype == torch.float32 and g_h.is_contiguous() and tuple(g_h.shape) == (N, H)
+    dev = g_h.device
+    out = {"d_u": torch.empty((2 * H, 5 * H), device=dev), "d_b": torch.empty(5 * H, device=dev),
+           "d_w_leaf": torch.empty((E, 3 * H), device=dev), "d_b_leaf": torch.empty(3 * H, device=dev),
+           "d_x": torch.empty((N, E), device=dev)}
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_backward(ctx, batch["B"], N, batch["tree_off"].data_ptr(), batch["left"].data_ptr(),
+                             batch["right"].data_ptr(), batch["word"].data_ptr(), batch["h"].data_ptr(),
+                             batch["c"].data_ptr(), g_h.data_ptr(), out["d_u"].data_ptr(), out["d_b"].data_ptr(),
+                             out["d_w_leaf"].data_ptr(), out["d_b_leaf"].data_ptr(), out["d_x"].data_ptr(), st), "tl_backward")
+    return out
 
 
 def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):

@@ -1,0 +1,193 @@
+// Backward pass of the TreeLSTM forward (Section 4.2.2, recursive backpropagation): the gradient
+// of a node's cell is applied to the node, then to its children, with the forward values of each
+// node found by node index in the h / c rows.  Heights are walked from the roots down (a parent
+// is always higher than its children), one pair of launches per height:
+//   1. gate gradients: the forward contraction G = [h_l ; h_r] U + b is recomputed with the
+//      streaming cell, and its epilogue turns (dh, dc, c, c_l, c_r, gates) into the gradient of
+//      the five gate pre-activations (a row of 5H values per node, kept by list position) and
+//      sends dc to the children;
+//   2. operand gradient: [dh_l ; dh_r] += dG U^T, the same streaming cell with the rows of dG as
+//      the gathered operand and U^T as the packed weights; its epilogue adds the result to the
+//      children's dh rows (every node has one parent, so plain read-modify-write).
+// Leaves likewise (dG W_x^T gives the gradient of each leaf's embedding row).  The weight
+// gradients dU = sum_n a_n^T dG_n, dW_x = sum_n x_n^T dG_n are two contractions over all nodes at
+// the end (k_weight_grad), the bias gradients column sums of the dG rows.
+#pragma once
+
+#include "cell_tile.hpp"
+
+namespace tl {
+
+template <int EPI, int NG>
+__device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG], int rb,
+                                    int count, int cg, int lane)
+{
+    const int col = cg * HU + (lane & 15);
+    const int H = f.H;
+    if constexpr (EPI == EPI_BWD_INNER_GATES || EPI == EPI_BWD_LEAF_GATES) {
+        if (col >= H) return;
+        float bias[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = rb * 16 + (lane >> 4) * 4 + v;
+            if (row >= count) continue;
+            const int node = sm.node[row];
+            if (node < 0) continue;
+            const size_t o = (size_t)node * H + col;
+            const float t = tanh_f(f.c[o]);
+            const float dh = f.dh[o], dc = f.dc[o];
+            float *dg = f.dg + (size_t)(sm.cmd[3] + row) * (NG * H) + col;
+            if constexpr (EPI == EPI_BWD_INNER_GATES) {
+                const int l = sm.src0[row], r = sm.src1[row];
+                const float cl = f.c[(size_t)l * H + col], cr = f.c[(size_t)r * H + col];
+                const float i = sigmoid_f(acc[0][v] + bias[0]), fl = sigmoid_f(acc[1][v] + bias[1]);
+                const float fr = sigmoid_f(acc[2][v] + bias[2]), og = sigmoid_f(acc[3][v] + bias[3]);
+                const float u = tanh_f(acc[4][v] + bias[4]);
+                const float dct = dc + dh * og * (1.f - t * t);
+                dg[0] = dct * u * i * (1.f - i);
+                dg[H] = dct * cl * fl * (1.f - fl);
+                dg[2 * H] = dct * cr * fr * (1.f - fr);
+                dg[3 * H] = dh * t * og * (1.f - og);
+                dg[4 * H] = dct * i * (1.f - u * u);
+                f.dc[(size_t)l * H + col] = dct * fl;
+                f.dc[(size_t)r * H + col] = dct * fr;
+            } else {
+                const float i = sigmoid_f(acc[0][v] + bias[0]), og = sigmoid_f(acc[1][v] + bias[1]);
+                const float u = tanh_f(acc[2][v] + bias[2]);
+                const float dct = dc + dh * og * (1.f - t * t);
+                dg[0] = dct * u * i * (1.f - i);
+                dg[H] = dh * t * og * (1.f - og);
+                dg[2 * H] = dct * i * (1.f - u * u);
+            }
+        }
+    } else {
+        if (col >= f.out_cols) return;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = rb * 16 + (lane >> 4) * 4 + v;
+            if (row >= count) continue;
+            const int node = sm.node[row];
+            if (node < 0) continue;
+            if constexpr (EPI == EPI_BWD_INNER_OPERAND) {
+                const int child = col < H ? f.left[node] : f.right[node];
+                float *p = f.dh + (size_t)child * H + (col < H ? col : col - H);
+                *p += acc[0][v];
+            } else {
+                f.d_x[(size_t)node * f.E + col] = acc[0][v];
+            }
+        }
+    }
+}
+
+// out[r][c] = in[c][r] for a row-major [rows x cols] input
+__global__ void k_transpose(const float *__restrict__ in, float *__restrict__ out, int rows, int cols)
+{
+    const size_t total = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t c = e / rows, r = e - c * rows;          // e indexes the output [cols x rows]
+        out[e] = in[r * cols + c];
+    }
+}
+
+__global__ void k_fill(float *__restrict__ p, size_t n, float v)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) p[e] = v;
+}
+
+// Weight gradient: out[k][j] = sum_q a_q[k] * dg[q][j] over the n_rows nodes of `list` (dg rows by
+// list position), a_q = [h[left]; h[right]] (SEG 2, L = H) or the embedding row of the leaf's
+// word (SEG 1, L = E).  K_out = SEG * L rows, n_cols columns, row-major.
+// One workgroup per 64 x 64 tile of the output, wave w on the 32 x 32 quarter (w / 2, w % 2);
+// the contraction runs over the nodes, 16 at a time through LDS, on v_mfma_f32_16x16x4_f32 with
+// the node index as the k of the instruction.
+constexpr int WG_TILE = 64, WG_Q = 16, WG_LD = WG_TILE + 4;
+
+template <int SEG>
+__global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__restrict__ list, int n_rows,
+                                                     const float *__restrict__ table, int L, const float *__restrict__ dg,
+                                                     int n_cols, float *__restrict__ out)
+{
+    __shared__ float as[WG_Q][WG_LD];
+    __shared__ float bs[WG_Q][WG_LD];
+    __shared__ int s_src[WG_Q][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int k0 = blockIdx.x * WG_TILE, j0 = blockIdx.y * WG_TILE;
+    const int K_out = SEG * L;
+    const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
+    floatx4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const int lq = tid >> 4, lk = (tid & 15) * 4;             // this thread stages 4 consecutive columns of row lq
+    for (int q0 = 0; q0 < n_rows; q0 += WG_Q) {
+        if (tid < WG_Q) {
+            const int q = q0 + tid;
+            int s0 = -1, s1 = -1;
+            if (q < n_rows) {
+                const int node = list[q];
+                if (SEG == 2) { s0 = f.left[node]; s1 = f.right[node]; } else { s0 = f.word[node]; }
+            }
+            s_src[tid][0] = s0;
+            s_src[tid][1] = s1;
+        }
+        __syncthreads();
+        {
+            const int q = q0 + lq;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = k0 + lk + e;
+                float a = 0.f;
+                if (q < n_rows && k < K_out) {
+                    const int seg = (SEG == 2 && k >= L) ? 1 : 0;
+                    a = table[(size_t)s_src[lq][seg] * L + (k - seg * L)];
+                }
+                as[lq][lk + e] = a;
+                const int j = j0 + lk + e;
+                bs[lq][lk + e] = (q < n_rows && j < n_cols) ? dg[(size_t)q * n_cols + j] : 0.f;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < WG_Q / 4; ++kk) {
+            const int qq = kk * 4 + (lane >> 4);
+            float a[2], b[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[t] = as[qq][wr + t * 16 + (lane & 15)];
+                b[t] = bs[qq][wc + t * 16 + (lane & 15)];
+            }
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int k = k0 + wr + ta * 16 + (lane >> 4) * 4 + v, j = j0 + wc + tb * 16 + (lane & 15);
+                if (k < K_out && j < n_cols) out[(size_t)k * n_cols + j] = acc[ta][tb][v];
+            }
+}
+
+// out[j] = sum_q dg[q][j]: blockIdx.x covers 64 columns, blockIdx.y a slice of the rows; `out` is zero beforehand.
+__global__ void k_column_sums(const float *__restrict__ dg, int n_rows, int n_cols, float *__restrict__ out)
+{
+    const int j = blockIdx.x * 64 + threadIdx.x;
+    if (j >= n_cols) return;
+    const int per = (n_rows + gridDim.y - 1) / gridDim.y;
+    const int lo = blockIdx.y * per, hi = min(n_rows, lo + per);
+    float s = 0.f;
+    for (int q = lo; q < hi; ++q) s += dg[(size_t)q * n_cols + j];
+    if (hi > lo) atomicAdd(&out[j], s);
+}
+
+}  // namespace tl

@@ -22,13 +22,22 @@
 
 namespace tl {
 
-enum Epi { EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2, EPI_RNTN_INNER = 3 };
+enum Epi {
+    EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2, EPI_RNTN_INNER = 3,
+    // backward pass (backward.hpp): gate gradients of internal nodes / leaves (the forward contraction is
+    // recomputed), and the gradient sent to the operand rows (gate gradients times transposed weights)
+    EPI_BWD_INNER_GATES = 4, EPI_BWD_INNER_OPERAND = 5, EPI_BWD_LEAF_GATES = 6, EPI_BWD_LEAF_OPERAND = 7
+};
 
 template <int EPI> struct EpiTraits;
 template <> struct EpiTraits<EPI_LSTM_LEAF>  { static constexpr int NG = 3, SEG = 1; };
 template <> struct EpiTraits<EPI_LSTM_INNER> { static constexpr int NG = 5, SEG = 2; };
 template <> struct EpiTraits<EPI_RNN_INNER>  { static constexpr int NG = 1, SEG = 2; };
 template <> struct EpiTraits<EPI_RNTN_INNER> { static constexpr int NG = 1, SEG = 2; };
+template <> struct EpiTraits<EPI_BWD_INNER_GATES>   { static constexpr int NG = 5, SEG = 2; };
+template <> struct EpiTraits<EPI_BWD_INNER_OPERAND> { static constexpr int NG = 1, SEG = 1; };
+template <> struct EpiTraits<EPI_BWD_LEAF_GATES>    { static constexpr int NG = 3, SEG = 1; };
+template <> struct EpiTraits<EPI_BWD_LEAF_OPERAND>  { static constexpr int NG = 1, SEG = 1; };
 
 // LDS carve-up (dynamic shared memory, 16-byte aligned).
 struct TileSmem {
@@ -70,14 +79,18 @@ __device__ inline void lstm_inner_out(float gi, float gfl, float gfr, float go, 
 }
 
 // Fills node/src0/src1 of one row.  Rows without a node are marked unused.  Caller synchronises.
+// `pos` is the row's position in the list the tile was cut from: the backward kernels that
+// gather rows of gate gradients find them by that position.
 template <int EPI, typename Smem>
-__device__ inline void tile_set_rows(Smem &sm, const Fwd &f, int row, int node)
+__device__ inline void tile_set_rows(Smem &sm, const Fwd &f, int row, int node, int pos = 0)
 {
     if (row >= TILE_ROWS) return;
     int s0 = -1, s1 = -1;
     if (node >= 0) {
-        if (EPI == EPI_LSTM_LEAF) {
+        if (EPI == EPI_LSTM_LEAF || EPI == EPI_BWD_LEAF_GATES) {
             s0 = f.word[node];
+        } else if (EPI == EPI_BWD_INNER_OPERAND || EPI == EPI_BWD_LEAF_OPERAND) {
+            s0 = pos;
         } else {
             s0 = f.left[node];
             s1 = f.right[node];
@@ -115,11 +128,19 @@ __device__ inline floatx4 load_a_granule(const float *__restrict__ table, const 
     return v;
 }
 
+template <int EPI, int NG>
+__device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG], int rb,
+                                    int count, int cg, int lane);   // backward.hpp
+
 // Gate functions and h/c stores for the 4 accumulator rows a lane holds.
 template <int EPI, bool COH, int NG>
 __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG],
                                      int rb, int count, int cg, int lane)
 {
+    if constexpr (EPI >= EPI_BWD_INNER_GATES) {
+        bwd_epilogue<EPI, NG>(sm, f, gm, acc, rb, count, cg, lane);
+        return;
+    }
     const int hu = cg * HU + (lane & 15);
     const int H = f.H;
     if (hu >= H) return;

@@ -111,6 +111,13 @@ struct Fwd {
     GangBox *gangs;
     const float *zeros;               // 256 bytes of zeros (stand-in source for padded operand granules)
     Ctl *ctl;
+    // backward pass only (null / zero in a forward)
+    float *dh, *dc;                   // [n_nodes x H]: gradient arriving at each node's h and c
+    float *dg;                        // rows of gate-pre-activation gradients: [n_int x 5H] or [n_leaf x 3H], by list position
+    float *d_x;                       // [n_nodes x E] out: gradient of the embedding row each leaf used
+    Gemm bwd;                         // packed transposed weights of the "gradient to the operand" contraction
+    int pos0;                         // list position of the first node of the list a static launch works on
+    int out_cols;                     // columns of the contraction a backward kernel produces (2H or E)
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once
     int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size compute + n_gangs scheduler workgroups

@@ -13,6 +13,7 @@
 #include "cell_tile.hpp"
 #include "schedulers.hpp"
 #include "classify.hpp"
+#include "backward.hpp"
 
 using namespace tl;
 
@@ -56,6 +57,12 @@ struct tl_ctx {
     unsigned short *embb = nullptr;
     int hs = 0;                       // row stride of the bf16 copy of h
     unsigned short *hb = nullptr;     // bf16 copy of h, cap_nodes rows (bf16 weight-stationary cell only)
+    // backward pass (TreeLSTM, fp32): transposed weights packed like the forward ones, workspace
+    void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr;
+    float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr;
+    Gemm g_bwd_inner{}, g_bwd_leaf{};
+    float *bw = nullptr;              // dh | dc | gate gradients of internal nodes | of leaves
+    int bw_nodes = 0;
     int last_grid = 0;
     int last_levels = 0;
     // profiling
@@ -198,6 +205,15 @@ template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
     default: return vec4 ? k_tiles_static<EPI_RNN_INNER, true, BF16> : k_tiles_static<EPI_RNN_INNER, false, BF16>;
     }
 }
+tiles_kernel backward_kernel(int epi, bool vec4)
+{
+    switch (epi) {
+    case EPI_BWD_INNER_GATES: return vec4 ? k_tiles_static<EPI_BWD_INNER_GATES, true, false> : k_tiles_static<EPI_BWD_INNER_GATES, false, false>;
+    case EPI_BWD_INNER_OPERAND: return vec4 ? k_tiles_static<EPI_BWD_INNER_OPERAND, true, false> : k_tiles_static<EPI_BWD_INNER_OPERAND, false, false>;
+    case EPI_BWD_LEAF_GATES: return vec4 ? k_tiles_static<EPI_BWD_LEAF_GATES, true, false> : k_tiles_static<EPI_BWD_LEAF_GATES, false, false>;
+    default: return vec4 ? k_tiles_static<EPI_BWD_LEAF_OPERAND, true, false> : k_tiles_static<EPI_BWD_LEAF_OPERAND, false, false>;
+    }
+}
 tiles_kernel static_kernel(int epi, bool vec4, bool bf16)
 {
     if (epi == EPI_RNTN_INNER) return vec4 ? k_tiles_static<EPI_RNTN_INNER, true, false> : k_tiles_static<EPI_RNTN_INNER, false, false>;
@@ -301,6 +317,11 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->ws);
     (void)hipFree(ctx->hb);
     (void)hipFree(ctx->embb);
+    (void)hipFree(ctx->wp_bwd_inner);
+    (void)hipFree(ctx->wp_bwd_leaf);
+    (void)hipFree(ctx->bp_bwd_inner);
+    (void)hipFree(ctx->bp_bwd_leaf);
+    (void)hipFree(ctx->bw);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -365,6 +386,28 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if (rc != TL_OK) return rc;
         rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
+        if (!bf16) {
+            // backward pass: U^T [5H x 2H] and W_leaf^T [3H x E] packed as single-gate contractions, zero bias
+            const int rows_u = 2 * H, cols_u = 5 * H, rows_w = E, cols_w = 3 * H;
+            const size_t n_t = (size_t)(rows_u * (size_t)cols_u > (size_t)rows_w * cols_w ? (size_t)rows_u * cols_u : (size_t)rows_w * cols_w);
+            float *t = nullptr, *zb = nullptr;
+            TL_HIP(hipMalloc(&t, n_t * sizeof(float)));
+            const size_t n_zb = (size_t)(2 * H > E ? 2 * H : E) + HU;
+            TL_HIP(hipMalloc(&zb, n_zb * sizeof(float)));
+            TL_HIP(hipMemset(zb, 0, n_zb * sizeof(float)));
+            hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->u, t, rows_u, cols_u);
+            rc = pack_gemm(t, zb, 1, 2 * H, 1, 5 * H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner, &ctx->wp_bwd_inner,
+                           &ctx->bp_bwd_inner);
+            if (rc == TL_OK) {
+                TL_HIP(hipDeviceSynchronize());
+                hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->w_leaf, t, rows_w, cols_w);
+                rc = pack_gemm(t, zb, 1, E, 1, 3 * H, (E + HU - 1) / HU, 0, false, &ctx->g_bwd_leaf, &ctx->wp_bwd_leaf, &ctx->bp_bwd_leaf);
+            }
+            TL_HIP(hipDeviceSynchronize());
+            (void)hipFree(t);
+            (void)hipFree(zb);
+            if (rc != TL_OK) return rc;
+        }
     } else if (cfg->cell == TL_TREERNN) {
         rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
@@ -396,6 +439,8 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
         for (int epi = 0; epi < 4; ++epi)
             if ((rc = allow_lds(static_kernel(epi, v, bf16))) != TL_OK) return rc;
+        for (int epi = EPI_BWD_INNER_GATES; epi <= EPI_BWD_LEAF_OPERAND; ++epi)
+            if ((rc = allow_lds(backward_kernel(epi, v))) != TL_OK) return rc;
     }
     int occ = 0;
     TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, 0, bf16)),
@@ -648,6 +693,116 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups)
     if (n_levels) *n_levels = ctx->host_ctl->n_levels;
     if (n_tiles) *n_tiles = (int)ctx->host_ctl->tiles.v;
     if (n_workgroups) *n_workgroups = ctx->last_grid;
+    return TL_OK;
+}
+
+int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left, const int32_t *right,
+                const int32_t *word, const float *h, const float *c, const float *g_h, float *d_u, float *d_b,
+                float *d_w_leaf, float *d_b_leaf, float *d_x, void *hip_stream)
+{
+    if (!ctx || !tree_off || !left || !right || !word || !h || !c || !g_h) return TL_EINVAL;
+    if (!d_u || !d_b || !d_w_leaf || !d_b_leaf || !d_x) return TL_EINVAL;
+    const tl_config &cfg = ctx->cfg;
+    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    if (n_trees < 1 || n_nodes < n_trees) return TL_EINVAL;
+    if (((long long)n_nodes + n_trees) % 2 != 0) return TL_ESTRUCT;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = ensure_workspace(ctx, n_nodes, n_trees);
+    if (rc != TL_OK) return rc;
+    const int H = cfg.hidden, E = cfg.embed_dim;
+    const int n_leaf = (int)(((long long)n_nodes + n_trees) / 2), n_int = n_nodes - n_leaf;
+    // workspace of the backward pass: dh, dc [N x H], gate gradients [n_int x 5H] and [n_leaf x 3H]
+    if (n_nodes > ctx->bw_nodes) {
+        TL_HIP(hipDeviceSynchronize());
+        if (ctx->bw) { TL_HIP(hipFree(ctx->bw)); ctx->bw = nullptr; }
+        ctx->bw_nodes = 0;
+        const size_t cap = (size_t)ctx->cap_nodes;
+        TL_HIP(hipMalloc(&ctx->bw, (2 * cap * H + cap * 5 * H) * sizeof(float)));   // n_int*5H + n_leaf*3H <= N*5H
+        ctx->bw_nodes = ctx->cap_nodes;
+    }
+    Fwd f{};
+    f.n_trees = n_trees; f.n_nodes = n_nodes; f.n_leaf = n_leaf; f.n_int = n_int;
+    f.tree_off = tree_off; f.left = left; f.right = right; f.word = word;
+    f.h = const_cast<float *>(h); f.c = const_cast<float *>(c);
+    f.cell = cfg.cell; f.H = H; f.E = E; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg;
+    f.emb = ctx->emb;
+    f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
+    carve_workspace(ctx, &f);
+    f.spin_limit = DEFAULT_SPIN_LIMIT;
+    f.cap_tiles = ctx->persistent_grid / ctx->n_cg > 0 ? ctx->persistent_grid / ctx->n_cg : 1;
+    const size_t cap = (size_t)ctx->bw_nodes;
+    f.dh = ctx->bw;
+    f.dc = f.dh + cap * H;
+    float *dg_int = f.dc + cap * H, *dg_leaf = dg_int + (size_t)n_int * 5 * H;
+    f.d_x = d_x;
+    ctx->last = f;
+    ctx->last_stream = st;
+    ctx->ran = true;
+    const int nb_nodes = (n_nodes + 1 + 255) / 256;
+    // structure pass with heights and per-height lists (as for the host-driven level scheduler)
+    hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, 1);
+    hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_check_roots, dim3((n_trees + 255) / 256), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_climb, dim3((n_leaf + 255) / 256), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
+    hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
+    // dh starts as the upstream gradient of every node, dc as zero; d_x rows of internal nodes stay zero
+    TL_HIP(hipMemcpyAsync(f.dh, g_h, (size_t)n_nodes * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, f.dc, (size_t)n_nodes * H, 0.f);
+    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_x, (size_t)n_nodes * E, 0.f);
+    hipLaunchKernelGGL(k_fill, dim3(8), dim3(256), 0, st, d_b, (size_t)5 * H, 0.f);
+    hipLaunchKernelGGL(k_fill, dim3(8), dim3(256), 0, st, d_b_leaf, (size_t)3 * H, 0.f);
+    TL_HIP(hipGetLastError());
+    if ((rc = read_ctl(ctx)) != TL_OK) return rc;
+    if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
+    const int n_levels = ctx->host_ctl->n_levels;
+    const bool vec4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
+    if (n_levels > 1) {
+        TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
+        TL_HIP(hipStreamSynchronize(st));
+        for (int lvl = n_levels - 1; lvl >= 1; --lvl) {     // roots first: a parent is always higher than its children
+            const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
+            if (rows <= 0 || lo < 0 || lo + rows > n_int) return TL_EHIP;
+            const LevelPlan plan = plan_level(rows, f.cap_tiles);
+            Fwd g = f;
+            g.dg = dg_int;
+            g.pos0 = lo;
+            hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_GATES, vec4), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                               TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
+            g.bwd = ctx->g_bwd_inner;
+            g.out_cols = 2 * H;
+            g.n_cg = (2 * H + HU - 1) / HU;
+            hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_OPERAND, vec4), dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
+                               TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
+        }
+    }
+    {
+        const LevelPlan plan = plan_level(n_leaf, f.cap_tiles);
+        Fwd g = f;
+        g.dg = dg_leaf;
+        g.pos0 = 0;
+        hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_GATES, E % 4 == 0), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                           TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
+        g.bwd = ctx->g_bwd_leaf;
+        g.out_cols = E;
+        g.n_cg = (E + HU - 1) / HU;
+        hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_OPERAND, H % 4 == 0), dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
+                           TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
+    }
+    // weight and bias gradients: contractions over all nodes
+    if (n_int > 0) {
+        hipLaunchKernelGGL(k_weight_grad<2>, dim3((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE), dim3(256), 0, st, f,
+                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u);
+        hipLaunchKernelGGL(k_column_sums, dim3((5 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_int, n_int, 5 * H, d_b);
+    } else {
+        hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_u, (size_t)2 * H * 5 * H, 0.f);
+    }
+    hipLaunchKernelGGL(k_weight_grad<1>, dim3((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE), dim3(256), 0, st, f,
+                       (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf);
+    hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
+    TL_HIP(hipGetLastError());
     return TL_OK;
 }
 
