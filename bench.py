@@ -165,6 +165,32 @@ def length_sweep(steps, warmup):
                       "note": "one tree per forward, whole tl_forward (structure pass, leaves, internal nodes, roots)"}))
 
 
+def backward_stage(w, reps=10):
+    """tl_backward on the states of one forward (TreeLSTM, fp32): mean wall time per call (the call waits for the
+    structure pass itself), with its algorithmic flops: 60 H^2 per internal node (gates recomputed, operand
+    gradient, weight gradient: 20 H^2 each) and 18 E H per leaf."""
+    import torch
+    from paper_1809_00832_amd import binding
+    net = binding.TreeNet(w.params, scheduler="level_device")
+    try:
+        b = net.load(w.trees)
+        net.forward()
+        g_h = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda")
+        for _ in range(2):
+            binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        H, E = w.params.hidden, w.params.embed_dim
+        flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
+        return {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
+    finally:
+        net.close()
+
+
 def cpu_baseline(w):
     """The CPU checker as it stands, all trees once, one thread per host core (at most 16)."""
     import oracle
@@ -202,6 +228,7 @@ def main():
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--head", type=int, default=5, help="classes of the per-node classifier head timed as an extra stage (0: skip)")
+    ap.add_argument("--backward", action="store_true", help="also time tl_backward on the same batch (TreeLSTM, fp32)")
     ap.add_argument("--length-sweep", action="store_true",
                     help="print only the latency of single trees of 2..1024 leaves (balanced, random, chain)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -268,6 +295,8 @@ def main():
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
     if args.head > 0:
         out["head"] = head_stage(w, args.head)
+    if args.backward and w.params.cell == 0 and args.precision == "f32":
+        out["backward"] = backward_stage(w)
     if not args.no_compare:
         comp = {}
         for sched in ("ready", "level_device", "level_host"):

@@ -96,12 +96,15 @@ __global__ void k_fill(float *__restrict__ p, size_t n, float v)
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) p[e] = v;
 }
 
-// Weight gradient: out[k][j] = sum_q a_q[k] * dg[q][j] over the n_rows nodes of `list` (dg rows by
+// Weight gradient: out[k][j] += sum_q a_q[k] * dg[q][j] over the n_rows nodes of `list` (dg rows by
 // list position), a_q = [h[left]; h[right]] (SEG 2, L = H) or the embedding row of the leaf's
-// word (SEG 1, L = E).  K_out = SEG * L rows, n_cols columns, row-major.
-// One workgroup per 64 x 64 tile of the output, wave w on the 32 x 32 quarter (w / 2, w % 2);
-// the contraction runs over the nodes, 16 at a time through LDS, on v_mfma_f32_16x16x4_f32 with
-// the node index as the k of the instruction.
+// word (SEG 1, L = E).  K_out = SEG * L rows, n_cols columns, row-major; `out` is zero beforehand.
+// One workgroup per 64 x 64 tile of the output and slice of the nodes (blockIdx.z; the slices'
+// partial tiles are added with atomics: the node axis is long and the output small, so without
+// slices there are too few workgroups to hide the latency of the gathers), wave w on the
+// 32 x 32 quarter (w / 2, w % 2).  The contraction runs over the nodes, 16 at a time through LDS,
+// on v_mfma_f32_16x16x4_f32 with the node index as the k of the instruction; the next 16 nodes'
+// operands are requested into registers before the current ones are multiplied.
 constexpr int WG_TILE = 64, WG_Q = 16, WG_LD = WG_TILE + 4;
 
 template <int SEG>
@@ -111,45 +114,45 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
 {
     __shared__ float as[WG_Q][WG_LD];
     __shared__ float bs[WG_Q][WG_LD];
-    __shared__ int s_src[WG_Q][2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k0 = blockIdx.x * WG_TILE, j0 = blockIdx.y * WG_TILE;
     const int K_out = SEG * L;
     const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
+    const int per = ((n_rows + (int)gridDim.z - 1) / (int)gridDim.z + WG_Q - 1) / WG_Q * WG_Q;
+    const int q_lo = blockIdx.z * per, q_hi = min(n_rows, q_lo + per);
+    if (q_lo >= q_hi) return;
     floatx4 acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
     const int lq = tid >> 4, lk = (tid & 15) * 4;             // this thread stages 4 consecutive columns of row lq
-    for (int q0 = 0; q0 < n_rows; q0 += WG_Q) {
-        if (tid < WG_Q) {
-            const int q = q0 + tid;
-            int s0 = -1, s1 = -1;
-            if (q < n_rows) {
-                const int node = list[q];
-                if (SEG == 2) { s0 = f.left[node]; s1 = f.right[node]; } else { s0 = f.word[node]; }
-            }
-            s_src[tid][0] = s0;
-            s_src[tid][1] = s1;
+    float ra[4], rb[4];
+    auto request = [&](int q0) {                              // operands of nodes q0 .. q0 + 15 into registers
+        const int q = q0 + lq;
+        int s0 = 0, s1 = 0;
+        const bool live = q < q_hi;
+        if (live) {
+            const int node = list[q];
+            if (SEG == 2) { s0 = f.left[node]; s1 = f.right[node]; } else { s0 = f.word[node]; }
         }
-        __syncthreads();
-        {
-            const int q = q0 + lq;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int k = k0 + lk + e;
-                float a = 0.f;
-                if (q < n_rows && k < K_out) {
-                    const int seg = (SEG == 2 && k >= L) ? 1 : 0;
-                    a = table[(size_t)s_src[lq][seg] * L + (k - seg * L)];
-                }
-                as[lq][lk + e] = a;
-                const int j = j0 + lk + e;
-                bs[lq][lk + e] = (q < n_rows && j < n_cols) ? dg[(size_t)q * n_cols + j] : 0.f;
-            }
+        for (int e = 0; e < 4; ++e) {
+            const int k = k0 + lk + e, j = j0 + lk + e;
+            const int seg = (SEG == 2 && k >= L) ? 1 : 0;
+            ra[e] = (live && k < K_out) ? table[(size_t)(seg ? s1 : s0) * L + (k - seg * L)] : 0.f;
+            rb[e] = (live && j < n_cols) ? dg[(size_t)q * n_cols + j] : 0.f;
+        }
+    };
+    request(q_lo);
+    for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            as[lq][lk + e] = ra[e];
+            bs[lq][lk + e] = rb[e];
         }
         __syncthreads();
+        if (q0 + WG_Q < q_hi) request(q0 + WG_Q);
 #pragma unroll
         for (int kk = 0; kk < WG_Q / 4; ++kk) {
             const int qq = kk * 4 + (lane >> 4);
@@ -174,7 +177,7 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int k = k0 + wr + ta * 16 + (lane >> 4) * 4 + v, j = j0 + wc + tb * 16 + (lane & 15);
-                if (k < K_out && j < n_cols) out[(size_t)k * n_cols + j] = acc[ta][tb][v];
+                if (k < K_out && j < n_cols) atomicAdd(&out[(size_t)k * n_cols + j], acc[ta][tb][v]);
             }
 }
 

@@ -791,17 +791,28 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_OPERAND, H % 4 == 0), dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
                            TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
     }
-    // weight and bias gradients: contractions over all nodes
+    // weight and bias gradients: contractions over all nodes, the node axis cut into slices so that a few
+    // thousand workgroups are in flight
+    auto slices = [&](int tiles, int rows) {
+        int z = (8 * ctx->n_cu + tiles - 1) / tiles;
+        const int max_z = (rows + 4 * WG_Q - 1) / (4 * WG_Q);
+        if (z > max_z) z = max_z;
+        return z < 1 ? 1 : z;
+    };
+    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_u, (size_t)2 * H * 5 * H, 0.f);
+    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_w_leaf, (size_t)E * 3 * H, 0.f);
     if (n_int > 0) {
-        hipLaunchKernelGGL(k_weight_grad<2>, dim3((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE), dim3(256), 0, st, f,
+        const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE, 1);
+        hipLaunchKernelGGL(k_weight_grad<2>, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
                            (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u);
         hipLaunchKernelGGL(k_column_sums, dim3((5 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_int, n_int, 5 * H, d_b);
-    } else {
-        hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_u, (size_t)2 * H * 5 * H, 0.f);
     }
-    hipLaunchKernelGGL(k_weight_grad<1>, dim3((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE), dim3(256), 0, st, f,
-                       (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf);
-    hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
+    {
+        const dim3 grid((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE, 1);
+        hipLaunchKernelGGL(k_weight_grad<1>, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_leaf)), dim3(256), 0, st, f,
+                           (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf);
+        hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
+    }
     TL_HIP(hipGetLastError());
     return TL_OK;
 }
