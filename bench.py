@@ -235,8 +235,8 @@ def main():
                     help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build evaluates on ONE GPU only (trees are independent; see DESIGN.md for how "
-                 "a batch would be sharded); run with --gpus 1")
+        sys.exit("bench.py: the forward pass is evaluated on ONE GPU only (trees are independent: a batch shards by tree, "
+                 "with no exchange between GPUs); run with --gpus 1")
 
     import torch
     from paper_1809_00832_amd import binding, synth

@@ -119,6 +119,10 @@ int tl_create(const tl_config *cfg, tl_ctx **out);
  * and that the first call with a larger batch than any before (re)allocates the
  * context's workspace, which synchronises the device.
  *
+ * With TL_SCHED_READY or TL_SCHED_LEVEL_DEVICE, profiling off, and after one ordinary call
+ * with a batch at least as large (so that nothing is allocated), the call makes no host round
+ * trip and may be captured in a HIP graph and replayed.
+ *
  *   n_trees >= 1, n_nodes >= n_trees                          HOST scalars
  *   tree_off [n_trees+1]  int32, tree_off[0]=0, ascending,
  *                         tree_off[n_trees]=n_nodes            DEVICE, read-only

@@ -148,3 +148,37 @@ def test_results_do_not_depend_on_the_schedule(name, precision):
         diff = int((h != outs[0][1]).sum())
         assert diff == 0, "%s vs ready: %d h elements differ, max %.3e" % (sched, diff, np.abs(h - outs[0][1]).max())
         assert c is None or np.array_equal(c, outs[0][2]), "%s vs ready: c differs" % sched
+
+
+@pytest.mark.parametrize("sched", ["ready", "level_device"])
+def test_forward_replayed_from_a_hip_graph(sched):
+    """tl_forward of the two device-scheduled variants makes no host round trip and clears its state with fill
+    kernels, so it can be captured in a HIP graph.  Every replay, with eager work and synchronisation between
+    replays and with new child states poisoned each time, must reproduce the eager result bit for bit."""
+    print("case graph", sched, flush=True)
+    w = synth.workload("sentence")
+    net = binding.TreeNet(w.params, scheduler=sched)
+    try:
+        net.load(w.trees)
+        net.forward()                                   # eager: also sizes the workspace, nothing is allocated later
+        torch.cuda.synchronize()
+        assert binding.tl_status(net.ctx) == 0
+        eager_h = net.batch["h"].clone()
+        eager_c = net.batch["c"].clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            net.forward()
+        for it in range(4):
+            net.batch["h"].fill_(float("nan"))
+            net.batch["c"].fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(net.batch["h"], eager_h) and torch.equal(net.batch["c"], eager_c), "replay %d differs" % it
+            scratch = torch.randn(1 << 16, device="cuda").sum().item()      # unrelated eager work between replays
+            assert scratch == scratch
+        assert binding.tl_status(net.ctx) == 0
+    finally:
+        net.close()
