@@ -96,13 +96,18 @@ template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowR
     unsigned off[G::NL];
     const char *hi_base;                                        // TAIL only: where the second 8 bytes come from
     unsigned hi_mask;
+    __amdgpu_buffer_rsrc_t rsrc;                                // the table as a raw buffer (device-scope requests)
 
     // rows of `table` are `stride` elements apart; what a row holds between its data and `stride`
     // elements reads as zero
     template <typename Smem>
-    __device__ inline void init(const Smem &sm, const Fwd &f, const T *__restrict__ table_, int Lp, int stride, int wave, int lane)
+    __device__ inline void init(const Smem &sm, const Fwd &f, const T *__restrict__ table_, int table_rows, int Lp, int stride,
+                                int wave, int lane)
     {
         table = reinterpret_cast<const char *>(table_);
+        // the whole table; the caller guarantees that it is smaller than 4 GiB
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(table_), 0, (unsigned)table_rows * (unsigned)stride * (unsigned)sizeof(T),
+                                                 0x00020000);
         sub = lane / G::LPR;                                    // which of the RPL rows of a load
         const int k = 4 * EPL * SPW * wave + (lane % G::LPR) * EPL;   // position on the padded K axis
         const int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
@@ -120,12 +125,22 @@ template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowR
 #pragma unroll
         for (int j = 0; j < G::NL; ++j) {
             const int row = (row0 + j * G::RPL + sub) & (WS_TABLE_ROWS - 1);
-            off[j] = __umul24((unsigned)max(src[row], 0), row_bytes) + lane_off;
+            off[j] = __umul24((unsigned)src[row], row_bytes) + lane_off;     // the tables hold row 0 for rows that do not exist
         }
     }
     template <bool COH> __device__ inline floatx4 issue(int j) const
     {
-        if constexpr (!TAIL) {
+        if constexpr (!TAIL && COH) {
+            // one 16-byte device-scope load (buffer_load_dwordx4 ... sc1)
+            typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+            const uintx4 u = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off[j], 0, 16);
+            floatx4 v;
+            v.x = __uint_as_float(u.x);
+            v.y = __uint_as_float(u.y);
+            v.z = __uint_as_float(u.z);
+            v.w = __uint_as_float(u.w);
+            return v;
+        } else if constexpr (!TAIL) {
             return ld_f4<COH>(reinterpret_cast<const float *>(table + off[j]));
         } else {
             static_assert(sizeof(T) == 4, "tail handling is for fp32 rows");
@@ -154,12 +169,14 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
     }
 }
 
+// The row tables of this cell: sm.node holds -1 for rows that do not exist, sm.src0 / sm.src1 hold
+// row 0 for them (so that a request needs no test).
 // Evaluates the `count` <= WS_TABLE_ROWS rows in sm.node/src0/src1 for column group cg, 16 at a
 // time, the requests of a block's rows always one block ahead.  All four waves call it together;
 // a __syncthreads() has been passed since the row tables were written.
 template <int EPI, bool COH, int SPW, bool TAIL = false>
-__device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int count,
-                               int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
+__device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int table_rows,
+                               int count, int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
@@ -202,7 +219,7 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     };
 
     WsRowRequest<SEG, SPW, float, TAIL> req;
-    req.init(sm, f, table, gm.Lp, gm.L, wave, lane);
+    req.init(sm, f, table, table_rows, gm.Lp, gm.L, wave, lane);
     floatx4 rows[NL];
     req.prepare(0);
 #pragma unroll
@@ -227,8 +244,8 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {                        // unused lanes read some existing element; the value is dropped
             const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
+            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
         }
         __builtin_amdgcn_sched_barrier(0);                  // all requests are issued before the MFMAs start
         floatx4 acc[NG];
@@ -311,7 +328,7 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
 
 template <int EPI, bool COH, int S>
 __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
-                               int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
+                               int table_rows, int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
@@ -325,7 +342,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
 
     WsRowRequest<SEG, S, unsigned short> req;
-    req.init(sm, f, table, stride, stride, wave, lane);
+    req.init(sm, f, table, table_rows, stride, stride, wave, lane);
     floatx4 rows[NL];
     req.prepare(0);
 #pragma unroll
@@ -364,8 +381,8 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {
             const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)max(sm.src0[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)max(sm.src1[erow & (WS_TABLE_ROWS - 1)], 0) * H + hc);
+            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
         }
 #pragma unroll
         for (int g = 0; g < NG; ++g)

@@ -56,10 +56,10 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
         const int count = min(hi - piece, WS_TABLE_ROWS);
         const int node = tid < count ? f.leaf_list[piece + tid] : -1;
         sm.node[tid] = node;
-        sm.src0[tid] = node >= 0 ? f.word[node] : -1;
-        sm.src1[tid] = -1;
+        sm.src0[tid] = node >= 0 ? f.word[node] : 0;
+        sm.src1[tid] = 0;
         __syncthreads();
-        ws_tile<EPI_LSTM_LEAF, false, SPW>(sm, f, f.leaf, f.emb, count, cg, w);
+        ws_tile<EPI_LSTM_LEAF, false, SPW>(sm, f, f.leaf, f.emb, f.vocab, count, cg, w);
     }
 }
 
@@ -82,10 +82,10 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
         const int count = min(hi - piece, WS_TABLE_ROWS);
         const int node = tid < count ? f.leaf_list[piece + tid] : -1;
         sm.node[tid] = node;
-        sm.src0[tid] = node >= 0 ? f.word[node] : -1;
-        sm.src1[tid] = -1;
+        sm.src0[tid] = node >= 0 ? f.word[node] : 0;
+        sm.src1[tid] = 0;
         __syncthreads();
-        ws_tile<EPI_LSTM_LEAF, false, S>(sm, f, f.leaf, f.embb, f.es, count, cg, w);
+        ws_tile<EPI_LSTM_LEAF, false, S>(sm, f, f.leaf, f.embb, f.vocab, f.es, count, cg, w);
     }
 }
 
@@ -287,8 +287,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                     int node = -1, s0 = -1, s1 = -1;
                     if (tid < count && !qrec_load(&f.q_rec[begin + piece + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
                     sm.node[tid] = node;
-                    sm.src0[tid] = s0;
-                    sm.src1[tid] = s1;
+                    sm.src0[tid] = max(s0, 0);
+                    sm.src1[tid] = max(s1, 0);
                 }
                 __syncthreads();
                 ParentTicket ticket{-1, 0, -1, -1};
@@ -301,8 +301,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                         holds = true;
                     }
                 }
-                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
-                else ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, count, my_cg, w);
+                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.n_nodes, f.hs, count, my_cg, w);
+                else ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w);
                 if (holds) appended += frontier_push(f, ticket);
             }
         } else {
@@ -509,8 +509,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
         // tiles have at most TILE_ROWS rows here; the rest of the cell's row tables reads "no row"
         sm.node[tid] = -1;
-        sm.src0[tid] = -1;
-        sm.src1[tid] = -1;
+        sm.src0[tid] = 0;
+        sm.src1[tid] = 0;
     }
 
     unsigned long long entry = 0;                 // this thread's entry of the next tile, requested ahead
@@ -528,8 +528,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
             }
             const int value = (int)(unsigned)entry;
             if (tid < TILE_ROWS) sm.node[tid] = value;
-            else if (tid < 2 * TILE_ROWS) sm.src0[tid - TILE_ROWS] = value;
-            else sm.src1[tid - 2 * TILE_ROWS] = value;
+            else if (tid < 2 * TILE_ROWS) sm.src0[tid - TILE_ROWS] = SPW > 0 ? max(value, 0) : value;
+            else sm.src1[tid - 2 * TILE_ROWS] = SPW > 0 ? max(value, 0) : value;
             if (tid == 0) sm.cmd[0] = (int)((entry >> 32) & 0xffu);
         }
         __syncthreads();
@@ -539,9 +539,9 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         if (tid < SLOT_ENTRIES) entry = ld_dev(&box->slot[(seq + 1) % GANG_RING][tid]);
 
         if constexpr (SPW > 0 && BF16) {
-            ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.hs, count, my_cg, w);
+            ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.n_nodes, f.hs, count, my_cg, w);
         } else if constexpr (SPW > 0) {
-            ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, count, my_cg, w);
+            ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w);
         } else {
             for (int j = member; j < f.n_cg; j += f.gang_size)
                 cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
