@@ -33,6 +33,13 @@
  * A single-node tree (the root is a leaf) is legal.
  *
  * Threading: a context is not thread safe; one forward may be in flight per context.
+ * TL_SCHED_READY and TL_SCHED_LEVEL_DEVICE evaluate the internal nodes in one kernel whose
+ * workgroups wait for each other, so all of them must be resident together: they are sized to
+ * fill the device, and while such a forward runs nothing else that holds compute units for long
+ * (another context's forward on a second stream, say) may run on the same device.  Breaking
+ * this does not hang - every wait is bounded by spin_limit - but the forward may then end with
+ * TL_ESTALL.  Forwards of several contexts are therefore put on one stream or ordered with
+ * events; TL_SCHED_LEVEL_HOST has no such requirement.
  * Errors: functions return TL_OK (0) or a negative tl_error.
  */
 #ifndef TREELSTM_H
