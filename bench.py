@@ -196,7 +196,7 @@ def cpu_baseline(w):
     import oracle
     cores = min(16, os.cpu_count() or 1)
     passes, dt_all = 0, 0.0
-    while passes < 3 or (dt_all < 1.5 and passes < 20):      # about 20 to 30 core-seconds on this workload
+    while passes < 1 or (dt_all < 1.5 and passes < 20):      # about 25 core-seconds on the default workload
         t0 = time.perf_counter()
         oracle.forward_params(w.params, w.trees, n_threads=cores)
         dt_all += time.perf_counter() - t0
