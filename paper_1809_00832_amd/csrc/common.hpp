@@ -49,6 +49,7 @@ struct alignas(LINE) Ctl {
     Line q_head;                  // ready-queue entries consumed into tiles
     Line q_tail;                  // ready-queue entries reserved by producers
     Line tiles;                   // tiles formed (statistics only)
+    Line direct;                  // nodes that a scheduler handed to its own gang without passing the queue
     // grid barrier of the level scheduler, one word per L2 domain: arrivals of the domain's workgroups in
     // the low half, ready-queue records they have appended (cumulative) in the high half
     Line64 bar_xcd[N_XCD];
@@ -69,7 +70,10 @@ constexpr int SLOT_ENTRIES = 3 * TILE_ROWS;
 constexpr int VALUE_EXIT = -2;            // node value of row 0 in the "leave" message
 struct alignas(LINE) GangBox {
     unsigned long long slot[GANG_RING][SLOT_ENTRIES];   // [0,64): node  [64,128): first source  [128,192): second source
-    Line done;                                          // compute workgroups that finished tiles (cumulative)
+    // compute workgroups that have finished the tiles of each ring slot (cumulative per slot).  One counter
+    // for the whole ring would not do: a fast member's count for the tile after would stand in for a
+    // slow member's count for this one.
+    Line done[GANG_RING];
 };
 
 // Record of the ready queue: a node that has become ready, with its child rows, so that whoever

@@ -377,17 +377,19 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
 #pragma unroll
     for (int r = 0; r < GANG_RING; ++r) my_node[r] = -1;
     int spins = 0;
-    unsigned last_head = ~0u, last_tail = ~0u;
+    unsigned last_head = 0u, last_tail = 0u, last_direct = ~0u;
     bool leave = false;
     while (!leave) {
         bool progress = false;
         // ---- (1) a finished tile: resolve its rows' parents -------------------------------
         if (completed < published) {
+            // tile number t = completed + 1 is the ceil(t / GANG_RING)-th tile of ring slot t % GANG_RING
+            const unsigned t = completed + 1;
+            const int r = (int)(t % GANG_RING);
             unsigned d = 0;
-            if (lane == 0) d = ld_dev(&box->done.v);
+            if (lane == 0) d = ld_dev(&box->done[r].v);
             d = __shfl(d, 0);
-            if (d >= (completed + 1) * (unsigned)f.gang_size) {
-                const int r = (int)((completed + 1) % GANG_RING);
+            if (d >= (t + GANG_RING - 1) / GANG_RING * (unsigned)f.gang_size) {
                 int node = -1;
 #pragma unroll
                 for (int q = 0; q < GANG_RING; ++q) if (q == r) node = my_node[q];
@@ -401,27 +403,60 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                         if (old != 1) p = -1;
                     }
                 }
-                // parents that became ready are pushed with one reservation on q_tail for the tile
                 const unsigned long long ready = __ballot(p >= 0);
                 const int n_ready = __popcll(ready);
-                unsigned base = 0;
-                if (lane == 0 && n_ready > 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_ready);
-                base = __shfl(base, 0);
-                if (p >= 0) {
-                    const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << lane) - 1ull));
-                    if (slot < n_int) qrec_store<true>(&f.q_rec[slot], p, pl, pr);
+                // Parents that became ready.  While ready work is scarce (the regime in which the next
+                // dependent step waits for this one: chains, the top of a tree) they go straight back to
+                // this gang as its next tile: no queue round trip between a node and its parent.
+                // Otherwise they are pushed on the queue with one reservation on q_tail for the tile.
+                const bool scarce = last_tail - last_head < 16u * (unsigned)f.n_gangs;
+                if (n_ready > 0 && scarce) {
+                    // lane j < n_ready takes the j-th ready lane's node (position of the j-th set bit)
+                    int pos = 0, rem = lane;
+#pragma unroll
+                    for (int b = 32; b >= 1; b >>= 1) {
+                        const int cnt = __popcll(ready & (((1ull << b) - 1ull) << pos));
+                        if (cnt <= rem) { pos += b; rem -= cnt; }
+                    }
+                    pos &= 63;
+                    int node2 = __shfl(p, pos), s0 = __shfl(pl, pos), s1 = __shfl(pr, pos);
+                    if (lane >= n_ready) node2 = s0 = s1 = -1;
+                    if (lane == 0) add_dev(&ctl->direct.v, (unsigned)n_ready);
+                    const unsigned seq = published + 1;
+                    const int r2 = (int)(seq % GANG_RING);
+#pragma unroll
+                    for (int q = 0; q < GANG_RING; ++q) if (q == r2) my_node[q] = node2;
+                    unsigned long long *e = box->slot[r2];
+                    st_dev(&e[lane], slot_entry(seq, (unsigned)n_ready, node2));
+                    st_dev(&e[TILE_ROWS + lane], slot_entry(seq, (unsigned)n_ready, s0));
+                    st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, (unsigned)n_ready, s1));
+                    published += 1;
+                } else if (n_ready > 0) {
+                    unsigned base = 0;
+                    if (lane == 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_ready);
+                    base = __shfl(base, 0);
+                    if (p >= 0) {
+                        const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << lane) - 1ull));
+                        if (slot < n_int) qrec_store<true>(&f.q_rec[slot], p, pl, pr);
+                    }
                 }
                 completed += 1;
                 progress = true;
             }
         }
         // ---- (2) room in the ring: cut the next tile off the ready queue --------------------
-        unsigned head = 0, tail = 0;
-        if (lane == 0) { head = ld_dev(&ctl->q_head.v); tail = ld_dev(&ctl->q_tail.v); }
+        unsigned head = 0, tail = 0, direct = 0;
+        if (lane == 0) { head = ld_dev(&ctl->q_head.v); tail = ld_dev(&ctl->q_tail.v); direct = ld_dev(&ctl->direct.v); }
         head = __shfl(head, 0);
         tail = __shfl(tail, 0);
+        direct = __shfl(direct, 0);
         if (tail > n_int) tail = n_int;
-        if (head != last_head || tail != last_tail) { last_head = head; last_tail = tail; spins = 0; }   // others progress
+        if (head != last_head || tail != last_tail || direct != last_direct) {   // others progress
+            last_head = head;
+            last_tail = tail;
+            last_direct = direct;
+            spins = 0;
+        }
         const unsigned in_flight = published - completed;
         if (in_flight < (unsigned)GANG_RING && tail > head) {
             const unsigned avail = tail - head;
@@ -464,7 +499,7 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
             unsigned ab = 0;
             if (lane == 0) ab = ld_dev(&ctl->abort.v);
             ab = __shfl(ab, 0);
-            if (head >= n_int || ab) leave = true;
+            if (head + direct >= n_int || ab) leave = true;     // every node has been handed out, by the queue or directly
         }
         if (progress) {
             spins = 0;
@@ -550,7 +585,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         // ---- completion: the tile's h/c rows are in memory before the scheduler hears of it -----
         wait_mem();
         __syncthreads();
-        if (tid == 0) add_dev(&box->done.v, 1u);
+        if (tid == 0) add_dev(&box->done[seq % GANG_RING].v, 1u);
     }
 }
 
