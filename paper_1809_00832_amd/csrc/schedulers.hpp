@@ -405,11 +405,13 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                 }
                 const unsigned long long ready = __ballot(p >= 0);
                 const int n_ready = __popcll(ready);
-                // Parents that became ready.  While ready work is scarce (the regime in which the next
-                // dependent step waits for this one: chains, the top of a tree) they go straight back to
-                // this gang as its next tile: no queue round trip between a node and its parent.
-                // Otherwise they are pushed on the queue with one reservation on q_tail for the tile.
-                const bool scarce = last_tail - last_head < 16u * (unsigned)f.n_gangs;
+                // Parents that became ready.  While the queue holds less than one row per gang (the regime
+                // in which the next dependent step waits for this one: chains, the top of a tree) they go
+                // straight back to this gang as its next tile: no queue round trip between a node and its
+                // parent.  Otherwise they are pushed on the queue with one reservation on q_tail for the
+                // tile (handing them back while the queue is well filled only cuts the work into many
+                // small tiles: measured).
+                const bool scarce = last_tail - last_head < (unsigned)f.n_gangs;
                 if (n_ready > 0 && scarce) {
                     // lane j < n_ready takes the j-th ready lane's node (position of the j-th set bit)
                     int pos = 0, rem = lane;
