@@ -361,6 +361,13 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
         const bool ev = enode >= 0 && hu_ok;
+        // c operands of the row this lane finishes: requested before the MFMAs, used after them
+        float cl = 0.f, cr = 0.f;
+        if (EPI == EPI_LSTM_INNER) {
+            const int hc = hu_ok ? hu : 0;
+            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+        }
         __builtin_amdgcn_sched_barrier(0);
         floatx4 acc[NG];
 #pragma unroll
@@ -375,14 +382,6 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
             for (int q = 0; q < LOADS_PER_STEP; ++q)
                 if (s * LOADS_PER_STEP + q < NL) rows[s * LOADS_PER_STEP + q] = req.template issue<COH>(s * LOADS_PER_STEP + q);
             __builtin_amdgcn_sched_barrier(0);
-        }
-        // c operands of the row this lane finishes: requested now, they arrive while the partial
-        // sums cross LDS (held across the MFMA phase they would cost registers the weights need)
-        float cl = 0.f, cr = 0.f;
-        if (EPI == EPI_LSTM_INNER) {
-            const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
         }
 #pragma unroll
         for (int g = 0; g < NG; ++g)
