@@ -107,13 +107,13 @@ __global__ void k_fill(float *__restrict__ p, size_t n, float v)
 // operands are requested into registers before the current ones are multiplied.
 constexpr int WG_TILE = 64, WG_Q = 16, WG_LD = WG_TILE + 4;
 
-template <int SEG>
+template <int SEG, bool VEC4>
 __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__restrict__ list, int n_rows,
                                                      const float *__restrict__ table, int L, const float *__restrict__ dg,
                                                      int n_cols, float *__restrict__ out)
 {
-    __shared__ float as[WG_Q][WG_LD];
-    __shared__ float bs[WG_Q][WG_LD];
+    __shared__ __align__(16) float as[WG_Q][WG_LD];
+    __shared__ __align__(16) float bs[WG_Q][WG_LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k0 = blockIdx.x * WG_TILE, j0 = blockIdx.y * WG_TILE;
     const int K_out = SEG * L;
@@ -136,21 +136,28 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
             const int node = list[q];
             if (SEG == 2) { s0 = f.left[node]; s1 = f.right[node]; } else { s0 = f.word[node]; }
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int k = k0 + lk + e, j = j0 + lk + e;
+        if constexpr (VEC4) {      // L and n_cols multiples of 4, rows 16-byte aligned: 4 consecutive columns never leave a segment
+            const int k = k0 + lk, j = j0 + lk;
             const int seg = (SEG == 2 && k >= L) ? 1 : 0;
-            ra[e] = (live && k < K_out) ? table[(size_t)(seg ? s1 : s0) * L + (k - seg * L)] : 0.f;
-            rb[e] = (live && j < n_cols) ? dg[(size_t)q * n_cols + j] : 0.f;
+            floatx4 a = floatx4{0.f, 0.f, 0.f, 0.f}, b = a;
+            if (live && k < K_out) a = *reinterpret_cast<const floatx4 *>(table + (size_t)(seg ? s1 : s0) * L + (k - seg * L));
+            if (live && j < n_cols) b = *reinterpret_cast<const floatx4 *>(dg + (size_t)q * n_cols + j);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { ra[e] = a[e]; rb[e] = b[e]; }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = k0 + lk + e, j = j0 + lk + e;
+                const int seg = (SEG == 2 && k >= L) ? 1 : 0;
+                ra[e] = (live && k < K_out) ? table[(size_t)(seg ? s1 : s0) * L + (k - seg * L)] : 0.f;
+                rb[e] = (live && j < n_cols) ? dg[(size_t)q * n_cols + j] : 0.f;
+            }
         }
     };
     request(q_lo);
     for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            as[lq][lk + e] = ra[e];
-            bs[lq][lk + e] = rb[e];
-        }
+        *reinterpret_cast<floatx4 *>(&as[lq][lk]) = floatx4{ra[0], ra[1], ra[2], ra[3]};
+        *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{rb[0], rb[1], rb[2], rb[3]};
         __syncthreads();
         if (q0 + WG_Q < q_hi) request(q0 + WG_Q);
 #pragma unroll

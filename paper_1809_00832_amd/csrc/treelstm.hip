@@ -89,6 +89,7 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 typedef void (*fwd_kernel)(Fwd);
 typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
+typedef void (*wgrad_kernel)(Fwd, const int32_t *, int, const float *, int, const float *, int, float *);
 
 // Steps per wave that the weight-stationary cell is instantiated for; 0 = streaming cell.
 const int WS_SIZES[] = {1, 2, 4, 5, 8, 16};
@@ -803,13 +804,17 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_w_leaf, (size_t)E * 3 * H, 0.f);
     if (n_int > 0) {
         const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE, 1);
-        hipLaunchKernelGGL(k_weight_grad<2>, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
+        const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
+        const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<2, true>) : wgrad_kernel(k_weight_grad<2, false>);
+        hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
                            (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u);
         hipLaunchKernelGGL(k_column_sums, dim3((5 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_int, n_int, 5 * H, d_b);
     }
     {
         const dim3 grid((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE, 1);
-        hipLaunchKernelGGL(k_weight_grad<1>, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_leaf)), dim3(256), 0, st, f,
+        const bool v4 = E % 4 == 0 && H % 4 == 0;
+        const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<1, true>) : wgrad_kernel(k_weight_grad<1, false>);
+        hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_leaf)), dim3(256), 0, st, f,
                            (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf);
         hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
     }
