@@ -44,7 +44,8 @@ struct alignas(LINE) Ctl {
     int n_levels;
     int reached;                  // nodes reached bottom-up from the leaves
     int tiles_formed;             // ready scheduler: tiles of ready nodes formed
-    int pad0[LINE / 4 - 7];
+    int n_roots;                  // nodes without a parent found by the structure pass (one per tree in a valid batch)
+    int pad0[LINE / 4 - 8];
     Line abort;                   // set when a waiting workgroup gives up; everybody leaves
     Line q_head;                  // ready-queue entries consumed into tiles
     Line q_tail;                  // ready-queue entries reserved by producers
@@ -209,6 +210,10 @@ __device__ inline void latch_error(Ctl *ctl, int code)
     int expected = 0;
     cas_dev(&ctl->status, &expected, code);
 }
+
+// After the structure pass: has it found anything wrong?  (A tree without a root shows as a root count
+// below the number of trees; every other defect has been latched in status.)
+__device__ inline bool batch_rejected(const Fwd &f) { return f.ctl->status != 0 || f.ctl->n_roots != f.n_trees; }
 
 __device__ inline void backoff() { __builtin_amdgcn_s_sleep(2); }
 

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int tile = blockIdx.x / f.n_cg, cg = blockIdx.x % f.n_cg;
     int start, count;
     plan_tile(plan, total, tile, &start, &count);
@@ -44,7 +44,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     WsSmemT<SPW> &sm = *reinterpret_cast<WsSmemT<SPW> *>(smem_raw);
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     WsSmemBfT<S> &sm = *reinterpret_cast<WsSmemBfT<S> *>(smem_raw);
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
 // Leaves of TreeRNN / RNTN: h = embedding row.
 __global__ void k_leaf_copy(Fwd f)
 {
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int i = blockIdx.x;
     if (i >= f.n_leaf) return;
     const int n = f.leaf_list[i];
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
-    if (ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int member = blockIdx.x % f.n_cg;
     const int my_cg = gang_cg(member, f.n_cg, f.n_cg);
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
-    if (ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int n_compute = f.n_gangs * f.gang_size;
     if ((int)blockIdx.x >= n_compute) {           // scheduler workgroups come after all compute workgroups

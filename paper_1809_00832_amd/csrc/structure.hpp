@@ -108,17 +108,18 @@ __global__ void k_roots(Fwd f)
 {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     Ctl *ctl = f.ctl;
-    if (n == 0 && ctl->n_leaf_seen != f.n_leaf) latch_error(ctl, TL_ESTRUCT);
-    if (n >= f.n_nodes || f.parent[n] != -1) return;
-    const int t = tree_of(f.tree_off, f.n_trees, n);
-    if (atomicCAS(&f.root_ws[t], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);
-}
-
-__global__ void k_check_roots(Fwd f)
-{
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < f.n_trees && f.root_ws[t] < 0) latch_error(f.ctl, TL_ESTRUCT);
-    if (t == 0) f.ctl->n_seed = (int)f.ctl->q_tail.v;     // the first frontier: internal nodes over two leaves
+    if (n == 0) {
+        if (ctl->n_leaf_seen != f.n_leaf) latch_error(ctl, TL_ESTRUCT);
+        ctl->n_seed = (int)ctl->q_tail.v;                // the first frontier: internal nodes over two leaves
+    }
+    const bool is_root = n < f.n_nodes && f.parent[n] == -1;
+    if (is_root) {
+        const int t = tree_of(f.tree_off, f.n_trees, n);
+        if (atomicCAS(&f.root_ws[t], -1, n) != -1) latch_error(ctl, TL_ESTRUCT);     // a second root of the same tree
+    }
+    // no tree has two roots, so "as many roots as trees" means one each; later kernels compare the two
+    // numbers (batch_rejected) and the root gather reports a mismatch
+    wave_append(&ctl->n_roots, is_root);
 }
 
 // Heights by climbing: one thread per leaf walks towards the root; at every internal node the
@@ -127,7 +128,7 @@ __global__ void k_check_roots(Fwd f)
 __global__ void k_climb(Fwd f)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f.ctl->status != 0 || i >= f.n_leaf) return;
+    if (batch_rejected(f) || i >= f.n_leaf) return;
     int n = f.leaf_list[i];
     int hcur = 0;
     for (int guard = 0; guard < f.n_nodes; ++guard) {
@@ -151,7 +152,7 @@ __global__ void k_level_hist(Fwd f)
     __shared__ int s_hist[HIST_BINS];
     __shared__ int s_max;
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x) s_hist[b] = 0;
     if (threadIdx.x == 0) s_max = 0;
     __syncthreads();
@@ -174,8 +175,11 @@ __global__ void k_scan_levels(Fwd f)
     __shared__ int s_carry;
     Ctl *ctl = f.ctl;
     const int tid = threadIdx.x;
-    if (ctl->status != 0) {
-        if (tid == 0) ctl->n_levels = 0;
+    if (batch_rejected(f)) {
+        if (tid == 0) {
+            ctl->n_levels = 0;
+            latch_error(ctl, TL_ESTRUCT);
+        }
         return;
     }
     const int n_levels = ctl->max_height + 1;
@@ -212,7 +216,7 @@ __global__ void k_fill_levels(Fwd f)
     __shared__ int s_hist[HIST_BINS];
     __shared__ int s_base[HIST_BINS];
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) return;
     for (int b = threadIdx.x; b < HIST_BINS; b += blockDim.x) s_hist[b] = 0;
     __syncthreads();
     const bool mine = n < f.n_nodes && f.left[n] >= 0 && f.arrive[n] == 2;
@@ -234,7 +238,10 @@ __global__ void k_fill_levels(Fwd f)
 // h_root / c_root / root outputs.
 __global__ void k_root_gather(Fwd f)
 {
-    if (f.ctl->status != 0) return;
+    if (batch_rejected(f)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) latch_error(f.ctl, TL_ESTRUCT);    // a tree without a root
+        return;
+    }
     const int t = blockIdx.x;
     const int r = f.root_ws[t];
     if (r < 0) return;

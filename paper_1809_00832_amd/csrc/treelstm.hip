@@ -490,6 +490,8 @@ int read_ctl(tl_ctx *ctx)
 {
     TL_HIP(hipMemcpyAsync(ctx->host_ctl, ctx->last.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, ctx->last_stream));
     TL_HIP(hipStreamSynchronize(ctx->last_stream));
+    // a tree without a root shows as a root count below the number of trees
+    if (ctx->host_ctl->status == 0 && ctx->host_ctl->n_roots != ctx->last.n_trees) ctx->host_ctl->status = TL_ESTRUCT;
     return TL_OK;
 }
 
@@ -583,7 +585,6 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
     hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
-    hipLaunchKernelGGL(k_check_roots, dim3((n_trees + 255) / 256), dim3(256), 0, st, f);
     if (need_levels) {
         hipLaunchKernelGGL(k_climb, dim3((f.n_leaf + 255) / 256), dim3(256), 0, st, f);
         hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
@@ -744,7 +745,6 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, 1);
     hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
-    hipLaunchKernelGGL(k_check_roots, dim3((n_trees + 255) / 256), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_climb, dim3((n_leaf + 255) / 256), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
