@@ -30,6 +30,8 @@ def _load():
         lib.oracle_backward.restype = ctypes.c_int
         lib.oracle_backward.argtypes = ([ctypes.c_int] * 3 + [_F] * 5 + [ctypes.c_int, ctypes.c_int] + [_I] * 4 + [_F] * 3
                                         + [_F] * 5)
+        lib.oracle_classify_backward.restype = ctypes.c_int
+        lib.oracle_classify_backward.argtypes = ([ctypes.c_int] * 3 + [_F] * 3 + [_I] + [_F] * 3 + [ctypes.POINTER(ctypes.c_double)])
         lib.oracle_classify.restype = ctypes.c_int
         lib.oracle_classify.argtypes = [ctypes.c_int] * 3 + [_F] * 4
         lib.oracle_forward.restype = ctypes.c_int
@@ -126,6 +128,24 @@ def classify(h, w_s, b_s):
     if lib.oracle_classify(n, H, C, _f(h), _f(w_s), _f(b_s), _f(probs)) != 0:
         raise ValueError("bad classifier dimensions")
     return probs
+
+
+def classify_backward(h, w_s, b_s, label):
+    """Cross-entropy (summed over nodes with label >= 0) on top of classify(): dict(loss, g_h, d_w_s, d_b_s)."""
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    w_s = np.ascontiguousarray(w_s, dtype=np.float32)
+    b_s = np.ascontiguousarray(b_s, dtype=np.float32)
+    label = np.ascontiguousarray(label, dtype=np.int32)
+    n, H = h.shape
+    C = w_s.shape[1]
+    out = {"g_h": np.zeros((n, H), np.float32), "d_w_s": np.zeros((H, C), np.float32), "d_b_s": np.zeros(C, np.float32)}
+    loss = ctypes.c_double(0.0)
+    if lib.oracle_classify_backward(n, H, C, _f(h), _f(w_s), _f(b_s), _i(label), _f(out["g_h"]), _f(out["d_w_s"]),
+                                    _f(out["d_b_s"]), ctypes.byref(loss)) != 0:
+        raise ValueError("bad classifier dimensions or labels")
+    out["loss"] = loss.value
+    return out
 
 
 def forward_params(params, trees, **kw):

@@ -412,3 +412,53 @@ int oracle_backward(int vocab, int E, int H,
     free(parent); free(height); free(root);
     return rc;
 }
+
+/*
+ * Backward pass of the classifier head with a cross-entropy loss summed over the labelled nodes:
+ *   L = - sum_{n : label[n] >= 0} log probs[n][label[n]],   probs as in oracle_classify.
+ * With g[n] = probs[n] - onehot(label[n]) (zero for unlabelled nodes):
+ *   g_h[n] = g[n] W_s^T     d_w_s = sum_n h[n]^T g[n]     d_b_s = sum_n g[n]
+ * All sums in double, rounded to fp32 once.  g_h is what the tree backward pass takes as the
+ * upstream gradient of every node.  Returns 0, or -1 on bad dimensions / labels.
+ * Pinned by tests against torch's cross_entropy autograd in float64 and closed forms.
+ */
+int oracle_classify_backward(int n_rows, int H, int C, const float *h, const float *w_s, const float *b_s,
+                             const int32_t *label, float *g_h, float *d_w_s, float *d_b_s, double *loss)
+{
+    if (n_rows < 0 || H < 1 || C < 1) return -1;
+    double *z = malloc(sizeof(double) * (size_t)C);
+    double *dw = calloc((size_t)H * C, sizeof(double)), *db = calloc((size_t)C, sizeof(double));
+    double total = 0.0;
+    int rc = 0;
+    for (int n = 0; n < n_rows && rc == 0; ++n) {
+        float *gr = g_h + (size_t)n * H;
+        if (label[n] < 0) { for (int k = 0; k < H; ++k) gr[k] = 0.f; continue; }
+        if (label[n] >= C) { rc = -1; break; }
+        for (int c = 0; c < C; ++c) {
+            double s = b_s[c];
+            for (int k = 0; k < H; ++k) s += (double)h[(size_t)n * H + k] * (double)w_s[(size_t)k * C + c];
+            z[c] = s;
+        }
+        double m = z[0];
+        for (int c = 1; c < C; ++c) if (z[c] > m) m = z[c];
+        double sum = 0.0;
+        for (int c = 0; c < C; ++c) sum += exp(z[c] - m);
+        total += -(z[label[n]] - m - log(sum));
+        for (int c = 0; c < C; ++c) z[c] = exp(z[c] - m) / sum - (c == label[n] ? 1.0 : 0.0);
+        for (int k = 0; k < H; ++k) {
+            double s = 0.0;
+            const double hk = h[(size_t)n * H + k];
+            for (int c = 0; c < C; ++c) {
+                s += z[c] * (double)w_s[(size_t)k * C + c];
+                dw[(size_t)k * C + c] += hk * z[c];
+            }
+            gr[k] = (float)s;
+        }
+        for (int c = 0; c < C; ++c) db[c] += z[c];
+    }
+    for (size_t i = 0; i < (size_t)H * C; ++i) d_w_s[i] = (float)dw[i];
+    for (int c = 0; c < C; ++c) d_b_s[c] = (float)db[c];
+    *loss = total;
+    free(z); free(dw); free(db);
+    return rc;
+}

@@ -651,3 +651,36 @@ def test_backward_closed_forms():
     assert np.allclose(got["d_b_leaf"], ref, rtol=1e-5, atol=1e-7)
     assert np.allclose(got["d_w_leaf"], np.outer(x, ref), rtol=1e-5, atol=1e-7)
     assert np.allclose(got["d_x"][0], p.w_leaf.astype(np.float64) @ ref, rtol=1e-5, atol=1e-7)
+
+
+def test_classifier_backward_matches_torch_cross_entropy():
+    """Loss and all three gradients against torch.nn.functional.cross_entropy (float64, reduction sum) with some
+    nodes unlabelled; closed form for zero weights (probabilities 1/C)."""
+    rng = np.random.default_rng(9)
+    N, H, C = 23, 7, 4
+    h = np.tanh(rng.standard_normal((N, H))).astype(np.float32)
+    w = rng.standard_normal((H, C)).astype(np.float32)
+    b = rng.standard_normal(C).astype(np.float32)
+    label = rng.integers(0, C, N).astype(np.int32)
+    label[rng.random(N) < 0.25] = -1
+    got = oracle.classify_backward(h, w, b, label)
+    th = torch.tensor(h, dtype=torch.float64, requires_grad=True)
+    tw = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    tb = torch.tensor(b, dtype=torch.float64, requires_grad=True)
+    keep = torch.tensor(label >= 0)
+    loss = torch.nn.functional.cross_entropy((th @ tw + tb)[keep], torch.tensor(label[label >= 0], dtype=torch.long),
+                                             reduction="sum")
+    loss.backward()
+    assert abs(got["loss"] - float(loss)) < 1e-9 * max(1.0, abs(float(loss)))
+    assert np.allclose(got["g_h"], th.grad.numpy(), rtol=1e-6, atol=1e-7)
+    assert np.allclose(got["d_w_s"], tw.grad.numpy(), rtol=1e-6, atol=1e-6)
+    assert np.allclose(got["d_b_s"], tb.grad.numpy(), rtol=1e-6, atol=1e-6)
+    assert not got["g_h"][label < 0].any()
+    zero = oracle.classify_backward(h, np.zeros_like(w), np.zeros_like(b), label)
+    n_lab = int((label >= 0).sum())
+    assert abs(zero["loss"] - n_lab * math.log(C)) < 1e-9
+    counts = np.bincount(label[label >= 0], minlength=C)
+    assert np.allclose(zero["d_b_s"], n_lab / C - counts, atol=1e-6)
+    assert not zero["g_h"].any()
+    with pytest.raises(ValueError):
+        oracle.classify_backward(h, w, b, np.full(N, C, np.int32))
