@@ -165,28 +165,52 @@ def length_sweep(steps, warmup):
                       "note": "one tree per forward, whole tl_forward (structure pass, leaves, internal nodes, roots)"}))
 
 
-def backward_stage(w, reps=10):
+def backward_stage(w, n_classes, reps=10):
     """tl_backward on the states of one forward (TreeLSTM, fp32): mean wall time per call (the call waits for the
     structure pass itself), with its algorithmic flops: 60 H^2 per internal node (gates recomputed, operand
-    gradient, weight gradient: 20 H^2 each) and 18 E H per leaf."""
+    gradient, weight gradient: 20 H^2 each) and 18 E H per leaf.  With a head (n_classes > 0) also the head's
+    backward on its own and one training step without the parameter update: forward, head backward (which
+    recomputes the head's forward), tree backward, back to back on one stream."""
     import torch
     from paper_1809_00832_amd import binding
     net = binding.TreeNet(w.params, scheduler="level_device")
     try:
         b = net.load(w.trees)
         net.forward()
-        g_h = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda")
-        for _ in range(2):
-            binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) / reps * 1e3
-        H, E = w.params.hidden, w.params.embed_dim
+        H, E, N = w.params.hidden, w.params.embed_dim, w.trees.n_nodes
+        g_h = torch.randn((N, H), device="cuda")
+
+        def wall(fn, reps):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps * 1e3
+
+        ms = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
         flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
-        return {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
+        out = {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12,
+               "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
+        if n_classes > 0:
+            g = torch.Generator(device="cuda").manual_seed(2)
+            ws = torch.randn((H, n_classes), device="cuda", generator=g) * (H ** -0.5)
+            bs = torch.zeros(n_classes, device="cuda")
+            label = torch.randint(0, n_classes, (N,), device="cuda", generator=g, dtype=torch.int32)
+            out["head_backward_ms"] = wall(lambda: binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label), 50)
+
+            def train_step():
+                net.forward()
+                hb = binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label)
+                binding.tl_backward(net.ctx, b, hb["g_h"], E)
+
+            step_ms = wall(train_step, reps)
+            out["train_step_ms"] = step_ms
+            out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
+            out["train_step_note"] = "forward + head backward + tree backward, no parameter update"
+        return out
     finally:
         net.close()
 
@@ -301,7 +325,7 @@ def main():
     if args.head > 0:
         out["head"] = head_stage(w, args.head)
     if args.backward and w.params.cell == 0 and args.precision == "f32":
-        out["backward"] = backward_stage(w)
+        out["backward"] = backward_stage(w, args.head)
     if not args.no_compare:
         comp = {}
         for sched in ("ready", "level_device", "level_host"):

@@ -209,6 +209,29 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
 int tl_classify(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const float *b_s, int n_classes,
                 float *probs, void *hip_stream);
 
+/*
+ * Backward pass of the classifier head under a cross-entropy loss summed over the labelled
+ * rows (the training objective of the sentiment networks of Section 6.1, where every node of a
+ * parse tree carries a label; the paper does not print it, the usual form is taken):
+ *     loss      = - sum_n log probs[n][label[n]]            probs as in tl_classify
+ *     d_logits[n] = probs[n] - onehot(label[n])
+ *     g_h[n]    = d_logits[n] W_s^T          (the g_h argument of tl_backward)
+ *     d_w_s     = sum_n h[n]^T d_logits[n]       d_b_s = sum_n d_logits[n]
+ * A row whose label is outside [0, n_classes) has no label: its d_logits and g_h rows are
+ * zero and it adds nothing to the sums.
+ *   h, w_s, b_s   as in tl_classify                                   DEVICE, read-only
+ *   label     [n_rows] int32                                           DEVICE, read-only
+ *   d_logits  [n_rows x n_classes] fp32 out                            DEVICE
+ *   g_h       [n_rows x H] fp32 out                                    DEVICE
+ *   d_w_s     [H x n_classes], d_b_s [n_classes], loss [1]  fp32 out   DEVICE
+ * fp32 arithmetic; the sums over rows are accumulated with atomics, so their last bits can
+ * differ from run to run.  Asynchronous on hip_stream, allocates nothing, same limits on
+ * n_classes as tl_classify.  n_rows = 0 zeroes the three sums.
+ */
+int tl_classify_backward(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const float *b_s, int n_classes,
+                         const int32_t *label, float *d_logits, float *g_h, float *d_w_s, float *d_b_s, float *loss,
+                         void *hip_stream);
+
 const char *tl_strerror(int code);
 
 /* Frees the context and everything it owns.  Waits for the device. */

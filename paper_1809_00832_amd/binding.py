@@ -21,7 +21,7 @@ TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
 EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_classify",
-           "tl_strerror", "tl_destroy")
+           "tl_classify_backward", "tl_strerror", "tl_destroy")
 
 
 class tl_config(ctypes.Structure):
@@ -61,6 +61,8 @@ def lib():
         L.tl_backward.argtypes = [vp, ci, ci] + [vp] * 13
         L.tl_classify.restype = ci
         L.tl_classify.argtypes = [vp, ci, vp, vp, vp, ci, vp, vp]
+        L.tl_classify_backward.restype = ci
+        L.tl_classify_backward.argtypes = [vp, ci, vp, vp, vp, ci] + [vp] * 7
         L.tl_strerror.argtypes = [ci]
         L.tl_destroy.restype = ci
         L.tl_destroy.argtypes = [vp]
@@ -156,6 +158,25 @@ def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):
     _check(lib().tl_classify(ctx, n_rows, h.data_ptr(), w_s.data_ptr(), b_s.data_ptr(), n_classes, probs.data_ptr(), st),
            "tl_classify")
     return probs
+
+
+def tl_classify_backward(ctx, h, w_s, b_s, label, stream=None):
+    """Cross-entropy over the rows with a label in [0, C) on top of tl_classify.  h, w_s, b_s float32 and label
+    int32 CUDA tensors.  Returns dict(loss [1], d_logits, g_h, d_w_s, d_b_s) of new float32 CUDA tensors."""
+    import torch
+    n_rows, n_classes = int(h.shape[0]), int(w_s.shape[1])
+    for t in (h, w_s, b_s):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert label.is_cuda and label.dtype == torch.int32 and label.is_contiguous() and label.numel() == n_rows
+    new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=h.device)
+    out = {"loss": new(1), "d_logits": new(n_rows, n_classes), "g_h": new(n_rows, int(h.shape[1])),
+           "d_w_s": new(int(h.shape[1]), n_classes), "d_b_s": new(n_classes)}
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_classify_backward(ctx, n_rows, h.data_ptr(), w_s.data_ptr(), b_s.data_ptr(), n_classes,
+                                      label.data_ptr(), out["d_logits"].data_ptr(), out["g_h"].data_ptr(),
+                                      out["d_w_s"].data_ptr(), out["d_b_s"].data_ptr(), out["loss"].data_ptr(), st),
+           "tl_classify_backward")
+    return out
 
 
 def tl_strerror(code: int) -> str:

@@ -842,6 +842,39 @@ int tl_classify(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const
     return TL_OK;
 }
 
+int tl_classify_backward(tl_ctx *ctx, int n_rows, const float *h, const float *w_s, const float *b_s, int n_classes,
+                         const int32_t *label, float *d_logits, float *g_h, float *d_w_s, float *d_b_s, float *loss,
+                         void *hip_stream)
+{
+    if (!ctx || !h || !w_s || !b_s || !label || !d_logits || !g_h || !d_w_s || !d_b_s || !loss) return TL_EINVAL;
+    if (n_rows < 0 || n_classes < 1 || n_classes > CLS_MAX_CLASSES) return TL_EINVAL;
+    const int H = ctx->cfg.hidden, Hp = (H + 3) & ~3, C = n_classes;
+    const size_t lds = (size_t)C * Hp * sizeof(float);
+    if (lds > 96 * 1024) return TL_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipLaunchKernelGGL(k_head_zero, dim3(16), dim3(256), 0, st, d_w_s, H * C, d_b_s, C, loss);
+    TL_HIP(hipGetLastError());
+    if (n_rows == 0) return TL_OK;
+    typedef void (*bwd_kernel)(const float *, const float *, const float *, const int32_t *, float *, float *, float *, int, int, int);
+    typedef void (*wg_kernel)(const float *, const float *, float *, float *, int, int, int);
+    const bwd_kernel kb = C <= 2 ? k_classify_backward<2> : C <= 8 ? k_classify_backward<8> : C <= 16 ? k_classify_backward<16>
+                                                                                                     : k_classify_backward<32>;
+    const wg_kernel kw = C <= 2 ? k_head_weight_grad<2> : C <= 8 ? k_head_weight_grad<8> : C <= 16 ? k_head_weight_grad<16>
+                                                                                                  : k_head_weight_grad<32>;
+    TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kb), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    long long blocks = ((long long)n_rows + 15) / 16;
+    const long long cap = (long long)ctx->n_cu * 4;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(kb, dim3((unsigned)blocks), dim3(256), lds, st, h, w_s, b_s, label, d_logits, g_h, loss, n_rows, H, C);
+    const int col_blocks = (H + 63) / 64;
+    long long slices = ((long long)n_rows + 4 * HW_ROWS - 1) / (4 * HW_ROWS);
+    const long long slice_cap = (2LL * ctx->n_cu + col_blocks - 1) / col_blocks;
+    if (slices > slice_cap) slices = slice_cap;
+    hipLaunchKernelGGL(kw, dim3((unsigned)col_blocks, (unsigned)slices), dim3(256), 0, st, h, d_logits, d_w_s, d_b_s, n_rows, H, C);
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
 const char *tl_strerror(int code)
 {
     switch (code) {

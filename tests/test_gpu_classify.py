@@ -90,3 +90,70 @@ def test_classifier_argument_checks():
         torch.cuda.synchronize()
     finally:
         big.close()
+
+
+@pytest.mark.parametrize("H,C,N", [(512, 5, 13572), (512, 2, 1), (150, 32, 777), (5, 3, 37), (33, 1, 16), (64, 8, 4097)])
+def test_classifier_backward_matches_oracle(H, C, N):
+    """tl_classify_backward against the CPU checker: logits gradient and g_h element by element, the three sums
+    (fp32 atomics over up to 13572 rows) relative to the scale of the sum."""
+    print("case classify backward", H, C, N, flush=True)
+    rng = np.random.default_rng(H * 1000 + C + 1)
+    h = np.tanh(rng.standard_normal((N, H))).astype(np.float32)
+    w = (rng.standard_normal((H, C)) * (2.0 / np.sqrt(H))).astype(np.float32)
+    b = rng.standard_normal(C).astype(np.float32)
+    label = rng.integers(0, C, N).astype(np.int32)
+    label[rng.random(N) < 0.2] = -1
+    ref = oracle.classify_backward(h, w, b, label)
+    ref_probs = oracle.classify(h, w, b)
+    net = make_net(H)
+    try:
+        dev = torch.device("cuda")
+        got = binding.tl_classify_backward(net.ctx, *(torch.from_numpy(a).to(dev) for a in (h, w, b, label)))
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy().astype(np.float64) for k, v in got.items()}
+    finally:
+        net.close()
+    onehot = np.zeros((N, C))
+    onehot[label >= 0, label[label >= 0]] = 1.0
+    ref_dl = np.where((label >= 0)[:, None], ref_probs - onehot, 0.0)
+    assert (np.abs(got["d_logits"] - ref_dl) <= 1e-5 + 1e-4 * np.abs(ref_dl)).all()
+    assert (np.abs(got["g_h"] - ref["g_h"]) <= 1e-5 + 1e-4 * np.abs(ref["g_h"])).all()
+    assert not got["g_h"][label < 0].any()
+    for key in ("d_w_s", "d_b_s"):
+        scale = max(1.0, float(np.abs(ref[key]).max()))
+        err = float(np.abs(got[key] - ref[key]).max())
+        assert err <= 1e-4 * scale, "%s: max abs err %.3e at scale %.3e" % (key, err, scale)
+    assert abs(got["loss"][0] - ref["loss"]) <= 1e-4 * max(1.0, abs(ref["loss"]))
+    print("   loss %.4f (ref %.4f)" % (got["loss"][0], ref["loss"]), flush=True)
+
+
+def test_head_gradient_feeds_the_tree_backward():
+    """A whole training step without the parameter update: forward, head, head backward, tree backward, each on
+    the device, against the same chain in the CPU checker."""
+    print("case training step", flush=True)
+    w_ = synth.workload("tiny")
+    p, t = w_.params, w_.trees
+    rng = np.random.default_rng(21)
+    H, C = p.hidden, 5
+    ws = (rng.standard_normal((H, C)) * 0.5).astype(np.float32)
+    bs = rng.standard_normal(C).astype(np.float32)
+    label = rng.integers(0, C, t.n_nodes).astype(np.int32)
+    fwd = oracle.forward_params(p, t)
+    head = oracle.classify_backward(fwd["h"], ws, bs, label)
+    ref = oracle.backward(p, t, fwd["h"], fwd["c"], head["g_h"])
+    net = binding.TreeNet(p, scheduler="level_device")
+    try:
+        net.load(t)
+        net.forward()
+        hb = binding.tl_classify_backward(net.ctx, net.batch["h"], torch.from_numpy(ws).cuda(), torch.from_numpy(bs).cuda(),
+                                          torch.from_numpy(label).cuda())
+        got = binding.tl_backward(net.ctx, net.batch, hb["g_h"], p.embed_dim)
+        torch.cuda.synchronize()
+        assert abs(float(hb["loss"][0]) - head["loss"]) <= 1e-4 * abs(head["loss"])
+        for key in ("d_u", "d_b", "d_w_leaf", "d_b_leaf"):
+            g = got[key].cpu().numpy().astype(np.float64)
+            scale = max(1.0, float(np.abs(ref[key]).max()))
+            err = float(np.abs(g - ref[key]).max())
+            assert err <= 2e-4 * scale, "%s: max abs err %.3e at scale %.3e" % (key, err, scale)
+    finally:
+        net.close()
