@@ -194,6 +194,12 @@ def backward_stage(w, n_classes, reps=10):
         flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
         out = {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12,
                "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
+        # training mode: the forward keeps the gate activations, the backward does not recompute the contraction
+        # (40 H^2 flops per internal node and 12 E H per leaf are left)
+        binding.tl_set_keep_gates(net.ctx, True)
+        net.forward()
+        out["ms_kept_gates"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
+        out["forward_ms_keeping_gates"] = wall(net.forward, 50)
         if n_classes > 0:
             g = torch.Generator(device="cuda").manual_seed(2)
             ws = torch.randn((H, n_classes), device="cuda", generator=g) * (H ** -0.5)
@@ -209,7 +215,7 @@ def backward_stage(w, n_classes, reps=10):
             step_ms = wall(train_step, reps)
             out["train_step_ms"] = step_ms
             out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
-            out["train_step_note"] = "forward + head backward + tree backward, no parameter update"
+            out["train_step_note"] = "forward keeping the gate activations + head backward + tree backward, no parameter update"
         return out
     finally:
         net.close()

@@ -194,6 +194,19 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                 float *d_u, float *d_b, float *d_w_leaf, float *d_b_leaf, float *d_x, void *hip_stream);
 
 /*
+ * Training mode of tl_forward (Section 4.2.2: the backward pass of a recursive call looks up the
+ * forward values of the same call instance).  With on != 0, every later tl_forward of a TreeLSTM /
+ * TL_F32 context also keeps the gate activations of every node (5H floats per node, in a
+ * workspace the context owns and grows like its others), and a tl_backward whose h argument and
+ * n_nodes are those of that forward takes them from there instead of recomputing the forward
+ * contraction.  The caller must not change h, c or the batch between the two calls.  Results of
+ * tl_forward are unchanged bit for bit; those of tl_backward agree with the recomputing path to
+ * rounding (the same activations, computed once instead of twice).  Other cells / precisions:
+ * accepted, no effect.  Off by default.
+ */
+int tl_set_keep_gates(tl_ctx *ctx, int on);
+
+/*
  * Per-node classifier head (Section 6.1: the evaluated networks label all nodes of a parse
  * tree; the paper does not print the head, the usual form is taken):
  *     probs[n] = softmax(h[n] W_s + b_s)          for n = 0 .. n_rows-1

@@ -20,7 +20,7 @@ TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4,
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_classify",
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_set_keep_gates", "tl_classify",
            "tl_classify_backward", "tl_strerror", "tl_destroy")
 
 
@@ -59,6 +59,8 @@ def lib():
         L.tl_strerror.restype = ctypes.c_char_p
         L.tl_backward.restype = ci
         L.tl_backward.argtypes = [vp, ci, ci] + [vp] * 13
+        L.tl_set_keep_gates.restype = ci
+        L.tl_set_keep_gates.argtypes = [vp, ci]
         L.tl_classify.restype = ci
         L.tl_classify.argtypes = [vp, ci, vp, vp, vp, ci, vp, vp]
         L.tl_classify_backward.restype = ci
@@ -144,6 +146,10 @@ def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
                              batch["c"].data_ptr(), g_h.data_ptr(), out["d_u"].data_ptr(), out["d_b"].data_ptr(),
                              out["d_w_leaf"].data_ptr(), out["d_b_leaf"].data_ptr(), out["d_x"].data_ptr(), st), "tl_backward")
     return out
+
+
+def tl_set_keep_gates(ctx, on: bool) -> None:
+    _check(lib().tl_set_keep_gates(ctx, 1 if on else 0), "tl_set_keep_gates")
 
 
 def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):

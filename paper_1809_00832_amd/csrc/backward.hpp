@@ -81,6 +81,64 @@ __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm
     }
 }
 
+// Gate gradients from gate activations that the forward kept (Fwd::gates): the elementwise part
+// of bwd_epilogue without the contraction in front of it.  One thread per (row of `list`, group of
+// V hidden units); same outputs as the EPI_BWD_*_GATES epilogues (dg rows by list position from
+// pos0 on, dc of the children).
+template <bool INNER, int V>
+__global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+{
+    const int H = f.H, per_row = H / V;
+    const int NG = INNER ? 5 : 3;
+    const long long total = (long long)n_rows * per_row;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int row = (int)(e / per_row), col = (int)(e - (long long)row * per_row) * V;
+        const int node = list[row];
+        const size_t o = (size_t)node * H + col;
+        const float *kept = f.gates + (size_t)node * (5 * H) + col;
+        float *dg = f.dg + (size_t)(pos0 + row) * (NG * H) + col;
+        int l = 0, r = 0;
+        if (INNER) { l = f.left[node]; r = f.right[node]; }
+        float cn[V], dh[V], dc[V], g[5][V], cl[V], cr[V], out[5][V], dcl[V], dcr[V];
+        auto load = [&](float (&dst)[V], const float *src) {
+            if constexpr (V == 4) { const floatx4 t = *reinterpret_cast<const floatx4 *>(src); dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w; }
+            else dst[0] = *src;
+        };
+        auto store = [&](float *dst, const float (&src)[V]) {
+            if constexpr (V == 4) *reinterpret_cast<floatx4 *>(dst) = floatx4{src[0], src[1], src[2], src[3]};
+            else *dst = src[0];
+        };
+        load(cn, f.c + o); load(dh, f.dh + o); load(dc, f.dc + o);
+#pragma unroll
+        for (int q = 0; q < NG; ++q) load(g[q], kept + (size_t)q * H);
+        if (INNER) { load(cl, f.c + (size_t)l * H + col); load(cr, f.c + (size_t)r * H + col); }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float t = tanh_f(cn[v]);
+            if (INNER) {
+                const float i = g[0][v], fl = g[1][v], fr = g[2][v], og = g[3][v], u = g[4][v];
+                const float dct = dc[v] + dh[v] * og * (1.f - t * t);
+                out[0][v] = dct * u * i * (1.f - i);
+                out[1][v] = dct * cl[v] * fl * (1.f - fl);
+                out[2][v] = dct * cr[v] * fr * (1.f - fr);
+                out[3][v] = dh[v] * t * og * (1.f - og);
+                out[4][v] = dct * i * (1.f - u * u);
+                dcl[v] = dct * fl;
+                dcr[v] = dct * fr;
+            } else {
+                const float i = g[0][v], og = g[1][v], u = g[2][v];
+                const float dct = dc[v] + dh[v] * og * (1.f - t * t);
+                out[0][v] = dct * u * i * (1.f - i);
+                out[1][v] = dh[v] * t * og * (1.f - og);
+                out[2][v] = dct * i * (1.f - u * u);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NG; ++q) store(dg + (size_t)q * H, out[q]);
+        if (INNER) { store(f.dc + (size_t)l * H + col, dcl); store(f.dc + (size_t)r * H + col, dcr); }
+    }
+}
+
 // out[r][c] = in[c][r] for a row-major [rows x cols] input
 __global__ void k_transpose(const float *__restrict__ in, float *__restrict__ out, int rows, int cols)
 {

@@ -63,19 +63,40 @@ __device__ inline float tanh_f(float x)
 // calls these same functions, and the multiply-adds are spelled out as fused operations (left to
 // the compiler, the choice of which product to fuse differs between call sites), so that a
 // node's h and c do not depend on the path that made them.
-__device__ inline void lstm_leaf_out(float gi, float go, float gu, float *c, float *h)
+// `keep`, when not null, receives the gate activations for the backward pass (Section 4.2.2:
+// forward values are kept per call instance): i, o, u of a leaf at keep[0], keep[H], keep[2H];
+// i, f_l, f_r, o, u of an internal node at keep[0] .. keep[4H].
+__device__ inline void lstm_leaf_out(float gi, float go, float gu, float *c, float *h, float *keep = nullptr, int H = 0)
 {
-    const float cc = sigmoid_f(gi) * tanh_f(gu);
+    const float i = sigmoid_f(gi), og = sigmoid_f(go), u = tanh_f(gu);
+    const float cc = i * u;
     *c = cc;
-    *h = sigmoid_f(go) * tanh_f(cc);
+    *h = og * tanh_f(cc);
+    if (keep) {
+        keep[0] = i;
+        keep[H] = og;
+        keep[2 * H] = u;
+    }
 }
 __device__ inline void lstm_inner_out(float gi, float gfl, float gfr, float go, float gu, float cl, float cr, float *c,
-                                      float *h)
+                                      float *h, float *keep = nullptr, int H = 0)
 {
     const float i = sigmoid_f(gi), fl = sigmoid_f(gfl), fr = sigmoid_f(gfr), og = sigmoid_f(go), u = tanh_f(gu);
     const float cc = __builtin_fmaf(fr, cr, __builtin_fmaf(fl, cl, i * u));
     *c = cc;
     *h = og * tanh_f(cc);
+    if (keep) {
+        keep[0] = i;
+        keep[H] = fl;
+        keep[2 * H] = fr;
+        keep[3 * H] = og;
+        keep[4 * H] = u;
+    }
+}
+// Where a node's kept gate activations start for hidden unit hu; null when they are not kept.
+__device__ inline float *kept_gates(const Fwd &f, int node, int hu)
+{
+    return f.gates ? f.gates + (size_t)node * (5 * f.H) + hu : nullptr;
 }
 
 // Fills node/src0/src1 of one row.  Rows without a node are marked unused.  Caller synchronises.
@@ -156,7 +177,7 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
         const size_t o = (size_t)node * H + hu;
         if (EPI == EPI_LSTM_LEAF) {
             float cc, hh;
-            lstm_leaf_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], &cc, &hh);
+            lstm_leaf_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], &cc, &hh, kept_gates(f, node, hu), H);
             st_f<COH>(f.c + o, cc);
             st_f<COH>(f.h + o, hh);
             if (f.hb) st_h<COH>(f.hb + (size_t)node * f.hs + hu, bf16_bits(hh));
@@ -165,7 +186,7 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
             const float cr = ld_f<COH>(f.c + (size_t)sm.src1[row] * H + hu);
             float cc, hh;
             lstm_inner_out(acc[0][v] + bias[0], acc[1][v] + bias[1], acc[2][v] + bias[2], acc[3][v] + bias[3],
-                           acc[4][v] + bias[4], cl, cr, &cc, &hh);
+                           acc[4][v] + bias[4], cl, cr, &cc, &hh, kept_gates(f, node, hu), H);
             st_f<COH>(f.c + o, cc);
             st_f<COH>(f.h + o, hh);
             if (f.hb) st_h<COH>(f.hb + (size_t)node * f.hs + hu, bf16_bits(hh));

@@ -204,12 +204,12 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             const size_t o = (size_t)enode * H + hu;
             if constexpr (EPI == EPI_LSTM_INNER) {
                 float cc, hh;
-                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
+                lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh, kept_gates(f, enode, hu), H);
                 st_f<COH>(f.c + o, cc);
                 st_f<COH>(f.h + o, hh);
             } else if constexpr (EPI == EPI_LSTM_LEAF) {
                 float cc, hh;
-                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
+                lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh, kept_gates(f, enode, hu), H);
                 st_f<COH>(f.c + o, cc);
                 st_f<COH>(f.h + o, hh);
             } else {

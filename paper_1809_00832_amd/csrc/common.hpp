@@ -117,6 +117,7 @@ struct Fwd {
     const float *zeros;               // 256 bytes of zeros (stand-in source for padded operand granules)
     Ctl *ctl;
     // backward pass only (null / zero in a forward)
+    float *gates;                     // null, or [n_nodes x 5H]: gate activations kept by the forward for the backward pass
     float *dh, *dc;                   // [n_nodes x H]: gradient arriving at each node's h and c
     float *dg;                        // rows of gate-pre-activation gradients: [n_int x 5H] or [n_leaf x 3H], by list position
     float *d_x;                       // [n_nodes x E] out: gradient of the embedding row each leaf used

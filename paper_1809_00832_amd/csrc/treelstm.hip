@@ -63,6 +63,11 @@ struct tl_ctx {
     Gemm g_bwd_inner{}, g_bwd_leaf{};
     float *bw = nullptr;              // dh | dc | gate gradients of internal nodes | of leaves
     int bw_nodes = 0;
+    bool keep_gates = false;          // tl_set_keep_gates
+    float *gates = nullptr;           // [gates_cap x 5H] gate activations of the last forward that kept them
+    int gates_cap = 0;
+    int gates_nodes = 0;              // nodes of that forward, 0: nothing kept
+    const float *gates_h = nullptr;   // its h argument: identifies the batch the activations belong to
     int last_grid = 0;
     int last_levels = 0;
     // profiling
@@ -323,6 +328,7 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->bp_bwd_inner);
     (void)hipFree(ctx->bp_bwd_leaf);
     (void)hipFree(ctx->bw);
+    (void)hipFree(ctx->gates);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -548,6 +554,19 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.emb = ctx->emb; f.embb = ctx->embb; f.es = ctx->es;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
     carve_workspace(ctx, &f);
+    ctx->gates_nodes = 0;
+    if (ctx->keep_gates && cfg.cell == TL_TREELSTM && cfg.precision == TL_F32) {
+        if (n_nodes > ctx->gates_cap) {
+            TL_HIP(hipDeviceSynchronize());
+            if (ctx->gates) { TL_HIP(hipFree(ctx->gates)); ctx->gates = nullptr; }
+            ctx->gates_cap = 0;
+            TL_HIP(hipMalloc(&ctx->gates, (size_t)ctx->cap_nodes * 5 * cfg.hidden * sizeof(float)));
+            ctx->gates_cap = ctx->cap_nodes;
+        }
+        f.gates = ctx->gates;
+        ctx->gates_nodes = n_nodes;
+        ctx->gates_h = h;
+    }
     f.spin_limit = cfg.spin_limit > 0 ? cfg.spin_limit : DEFAULT_SPIN_LIMIT;
     const bool vec4_inner = (cfg.hidden % 4 == 0) && (((uintptr_t)h & 15) == 0);
     const bool bf16 = cfg.precision == TL_BF16_IN;
@@ -760,6 +779,18 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
     const int n_levels = ctx->host_ctl->n_levels;
     const bool vec4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
+    // gate activations of the forward that wrote these h rows, if it kept them: no contraction to recompute
+    const bool kept = ctx->gates_nodes == n_nodes && ctx->gates_h == h && ctx->gates != nullptr;
+    const bool kept_v4 = H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
+    f.gates = kept ? ctx->gates : nullptr;
+    auto gate_grad_kept = [&](bool inner, const Fwd &g, const int32_t *list, int rows) {
+        typedef void (*kept_kernel)(Fwd, const int32_t *, int, int);
+        const kept_kernel k = inner ? (kept_v4 ? kept_kernel(k_gate_grad_kept<true, 4>) : kept_kernel(k_gate_grad_kept<true, 1>))
+                                    : (kept_v4 ? kept_kernel(k_gate_grad_kept<false, 4>) : kept_kernel(k_gate_grad_kept<false, 1>));
+        long long blocks = ((long long)rows * (kept_v4 ? H / 4 : H) + 255) / 256;
+        if (blocks > 8LL * ctx->n_cu) blocks = 8LL * ctx->n_cu;
+        hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(256), 0, st, g, list, rows, g.pos0);
+    };
     if (n_levels > 1) {
         TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
         TL_HIP(hipStreamSynchronize(st));
@@ -770,8 +801,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
             Fwd g = f;
             g.dg = dg_int;
             g.pos0 = lo;
-            hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_GATES, vec4), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
-                               TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
+            if (kept)
+                gate_grad_kept(true, g, (const int32_t *)(f.level_nodes + lo), rows);
+            else
+                hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_GATES, vec4), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                                   TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
             g.bwd = ctx->g_bwd_inner;
             g.out_cols = 2 * H;
             g.n_cg = (2 * H + HU - 1) / HU;
@@ -784,8 +818,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         Fwd g = f;
         g.dg = dg_leaf;
         g.pos0 = 0;
-        hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_GATES, E % 4 == 0), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
-                           TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
+        if (kept)
+            gate_grad_kept(false, g, (const int32_t *)f.leaf_list, n_leaf);
+        else
+            hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_GATES, E % 4 == 0), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                               TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
         g.bwd = ctx->g_bwd_leaf;
         g.out_cols = E;
         g.n_cg = (E + HU - 1) / HU;
@@ -819,6 +856,14 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
     }
     TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
+int tl_set_keep_gates(tl_ctx *ctx, int on)
+{
+    if (!ctx) return TL_EINVAL;
+    ctx->keep_gates = on != 0;
+    if (!ctx->keep_gates) ctx->gates_nodes = 0;
     return TL_OK;
 }
 

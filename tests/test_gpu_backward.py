@@ -23,11 +23,12 @@ def assert_grad_close(got, ref, what):
     return float(err.max() / max(np.abs(ref).max(), 1e-30))
 
 
-def run_case(params, trees, seed, what):
+def run_case(params, trees, seed, what, keep=False, scheduler="level_device"):
     rng = np.random.default_rng(seed)
-    net = binding.TreeNet(params, scheduler="level_device")
+    net = binding.TreeNet(params, scheduler=scheduler)
     try:
         b = net.load(trees)
+        binding.tl_set_keep_gates(net.ctx, keep)
         net.forward()
         assert binding.tl_status(net.ctx) == 0
         g_h = rng.standard_normal((trees.n_nodes, params.hidden)).astype(np.float32)
@@ -76,6 +77,57 @@ def test_backward_full_size_subset_of_trees():
     w = synth.workload("throughput")
     sub, _ = synth.subset(w.trees, list(range(24)))
     run_case(w.params, sub, 5, "throughput[:24]")
+
+
+@pytest.mark.parametrize("scheduler", ["level_device", "ready", "level_host"])
+def test_backward_from_kept_gate_activations(scheduler):
+    """Training mode: the forward keeps every node's gate activations and the backward takes them instead of
+    recomputing the contraction.  Same bar against the checker, for every forward data path (weight-stationary cell
+    under the two device schedulers, streaming cell under host-driven levels and for sizes the former does not
+    take), plus: the forward's own results do not change, and a forward of another batch in between (which
+    invalidates what was kept) sends the backward down the recomputing path again."""
+    print("case backward kept gates", scheduler, flush=True)
+    for name in ("tiny", "sentence"):
+        w = synth.workload(name)
+        run_case(w.params, w.trees, 7, name + " kept", keep=True, scheduler=scheduler)
+    for i, (dims, leaves) in enumerate([(dict(vocab=50, E=7, H=5), [1, 1, 2]), (dict(vocab=50, E=10, H=6), [3, 1, 20]),
+                                        (dict(vocab=50, E=9, H=33), [1, 2, 3, 1, 70, 5]),
+                                        (dict(vocab=50, E=64, H=64), [17] * 9 + [1] + [130])]):
+        params = synth.make_treelstm_params(80 + i, dims["vocab"], dims["E"], dims["H"], "xavier")
+        trees = synth.make_trees(80 + i, leaves, ["random"] * len(leaves), dims["vocab"])
+        run_case(params, trees, 80 + i, "ragged%d kept" % i, keep=True, scheduler=scheduler)
+    w = synth.workload("sentence")
+    net = binding.TreeNet(w.params, scheduler=scheduler)
+    try:
+        b = net.load(w.trees)
+        net.forward()
+        h_plain = b["h"].clone()
+        g_h = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda")
+        recomputed = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+        binding.tl_set_keep_gates(net.ctx, True)
+        net.forward()
+        assert torch.equal(b["h"], h_plain), "keeping the gates changed the forward"
+        kept = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+        for k in kept:
+            scale = float(recomputed[k].abs().max())
+            assert float((kept[k] - recomputed[k]).abs().max()) <= 1e-4 * max(scale, 1e-6), k
+        # another batch through the same context: what was kept no longer belongs to b
+        other = binding.TreeNet(w.params, scheduler=scheduler)
+        try:
+            ob = other.load(synth.make_trees(5, [4, 9], ["random"] * 2, w.params.vocab))
+            L = binding.lib()
+            st = torch.cuda.current_stream().cuda_stream
+            args = [ob[k].data_ptr() for k in ("tree_off", "left", "right", "word", "h", "c", "h_root", "c_root", "root")]
+            assert L.tl_forward(net.ctx, ob["B"], ob["N"], *args, st) == binding.TL_OK
+            again = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+            torch.cuda.synchronize()
+            for k in again:
+                scale = float(recomputed[k].abs().max())
+                assert float((again[k] - recomputed[k]).abs().max()) <= 1e-4 * max(scale, 1e-6), k
+        finally:
+            other.close()
+    finally:
+        net.close()
 
 
 def test_backward_argument_checks():
