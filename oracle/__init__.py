@@ -32,6 +32,11 @@ def _load():
                                         + [_F] * 5)
         lib.oracle_classify_backward.restype = ctypes.c_int
         lib.oracle_classify_backward.argtypes = ([ctypes.c_int] * 3 + [_F] * 3 + [_I] + [_F] * 3 + [ctypes.POINTER(ctypes.c_double)])
+        lib.oracle_td_step.restype = None
+        lib.oracle_td_step.argtypes = [ctypes.c_int] + [_F] * 3 + [ctypes.c_float] + [_F] * 5
+        lib.oracle_td_generate.restype = ctypes.c_int
+        lib.oracle_td_generate.argtypes = ([ctypes.c_int] + [_F] * 3 + [ctypes.c_float, ctypes.c_int] + [_F] * 2
+                                           + [ctypes.c_int, ctypes.c_int] + [_I] * 4 + [_F] * 3 + [_I])
         lib.oracle_classify.restype = ctypes.c_int
         lib.oracle_classify.argtypes = [ctypes.c_int] * 3 + [_F] * 4
         lib.oracle_forward.restype = ctypes.c_int
@@ -146,6 +151,37 @@ def classify_backward(h, w_s, b_s, label):
         raise ValueError("bad classifier dimensions or labels")
     out["loss"] = loss.value
     return out
+
+
+def td_step(u_td, b_td, w_stop, b_stop, h, c):
+    """One node of the top-down generator: (child_h [2 x H], child_c [2 x H], score) from the node's stored state."""
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    c = np.ascontiguousarray(c, dtype=np.float32)
+    H = h.shape[0]
+    kh, kc = np.zeros((2, H), np.float32), np.zeros((2, H), np.float32)
+    score = np.zeros(1, np.float32)
+    lib.oracle_td_step(H, _f(u_td), _f(b_td), _f(w_stop), float(b_stop), _f(h), _f(c), _f(kh), _f(kc), _f(score))
+    return kh, kc, float(score[0])
+
+
+def td_generate(u_td, b_td, w_stop, b_stop, h_root, c_root, max_depth, max_nodes):
+    """Top-down generation from the root states; dict(n_nodes, truncated, parent, left, right, depth, score, h, c),
+    arrays cut to n_nodes rows, nodes in breadth-first order."""
+    lib = _load()
+    h_root = np.ascontiguousarray(h_root, dtype=np.float32)
+    c_root = np.ascontiguousarray(c_root, dtype=np.float32)
+    B, H = h_root.shape
+    ints = [np.full(max_nodes, -1, np.int32) for _ in range(4)]
+    score = np.zeros(max_nodes, np.float32)
+    h, c = np.zeros((max_nodes, H), np.float32), np.zeros((max_nodes, H), np.float32)
+    trunc = np.zeros(1, np.int32)
+    n = lib.oracle_td_generate(H, _f(u_td), _f(b_td), _f(w_stop), float(b_stop), B, _f(h_root), _f(c_root), int(max_depth),
+                               int(max_nodes), *[_i(a) for a in ints], _f(score), _f(h), _f(c), _i(trunc))
+    if n < 0:
+        raise ValueError("bad arguments")
+    return {"n_nodes": n, "truncated": int(trunc[0]), "parent": ints[0][:n], "left": ints[1][:n], "right": ints[2][:n],
+            "depth": ints[3][:n], "score": score[:n], "h": h[:n], "c": c[:n]}
 
 
 def forward_params(params, trees, **kw):

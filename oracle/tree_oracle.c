@@ -462,3 +462,86 @@ int oracle_classify_backward(int n_rows, int H, int C, const float *h, const flo
     free(z); free(dw); free(db);
     return rc;
 }
+
+/*
+ * Top-down generation of trees whose shape is decided by values computed on the way (Section 6.3,
+ * "Dynamically Structured Models": whether a node gets children depends on the node's own
+ * computed value, so the tree is not known before it is evaluated).  The paper names such models
+ * (TD-TreeLSTM and others) and prints no equations; the form used here is an LSTM step along
+ * every parent -> child edge with weights per side, and a linear stopping rule:
+ *
+ *    score(n) = w_stop . h_n + b_stop                     n expands iff score(n) > 0 and depth(n) < max_depth
+ *    child on side s in {L, R}:  g = h_n U_s + b_s,  g = [gi|gf|go|gu] each H wide
+ *                                c_s = s(gf)*c_n + s(gi)*tanh(gu);   h_s = s(go)*tanh(c_s)
+ *
+ * u_td is [H x 8H] row-major with columns [iL|fL|oL|uL|iR|fR|oR|uR], b_td [8H].  Sums in double in
+ * ascending index order, stored states rounded to fp32 once; a child consumes the stored fp32
+ * state of its parent.  The score is rounded to fp32 before it is compared with zero.
+ *
+ * oracle_td_step: both children and the score of one node from its stored state.
+ *   child_h, child_c: [2 x H] (left, right).
+ */
+void oracle_td_step(int H, const float *u_td, const float *b_td, const float *w_stop, float b_stop,
+                    const float *h, const float *c, float *child_h, float *child_c, float *score)
+{
+    double s = b_stop;
+    for (int k = 0; k < H; ++k) s += (double)w_stop[k] * (double)h[k];
+    *score = (float)s;
+    for (int side = 0; side < 2; ++side) {
+        for (int j = 0; j < H; ++j) {
+            double g[4];
+            for (int q = 0; q < 4; ++q) {
+                const int col = side * 4 * H + q * H + j;
+                double acc = b_td[col];
+                for (int k = 0; k < H; ++k) acc += (double)h[k] * (double)u_td[(size_t)k * 8 * H + col];
+                g[q] = acc;
+            }
+            const double cc = sigm(g[1]) * (double)c[j] + sigm(g[0]) * tanh(g[3]);
+            child_c[side * H + j] = (float)cc;
+            child_h[side * H + j] = (float)(sigm(g[2]) * tanh(cc));
+        }
+    }
+}
+
+/*
+ * oracle_td_generate: grows n_trees trees breadth first.  Node t < n_trees is the root of tree t with
+ * the given state (rows of h_root / c_root); children get the next two free indices, left first, in the
+ * order in which their parents are visited (index order).  A node that would expand when fewer than two
+ * of the max_nodes rows are free stays a leaf and is counted in *truncated.
+ * Outputs, max_nodes rows each: parent (-1 for roots), left / right (-1 for nodes without children),
+ * depth, score, h, c.  Returns the number of nodes, or -1 on bad arguments.
+ */
+int oracle_td_generate(int H, const float *u_td, const float *b_td, const float *w_stop, float b_stop,
+                       int n_trees, const float *h_root, const float *c_root, int max_depth, int max_nodes,
+                       int32_t *parent, int32_t *left, int32_t *right, int32_t *depth, float *score,
+                       float *h, float *c, int32_t *truncated)
+{
+    if (H < 1 || n_trees < 1 || max_nodes < n_trees || max_depth < 0) return -1;
+    float *kid_h = malloc(sizeof(float) * 2 * (size_t)H), *kid_c = malloc(sizeof(float) * 2 * (size_t)H);
+    int n = n_trees;
+    *truncated = 0;
+    for (int t = 0; t < n_trees; ++t) {
+        parent[t] = -1;
+        depth[t] = 0;
+        memcpy(h + (size_t)t * H, h_root + (size_t)t * H, sizeof(float) * (size_t)H);
+        memcpy(c + (size_t)t * H, c_root + (size_t)t * H, sizeof(float) * (size_t)H);
+    }
+    for (int v = 0; v < n; ++v) {                 /* index order is breadth-first order */
+        oracle_td_step(H, u_td, b_td, w_stop, b_stop, h + (size_t)v * H, c + (size_t)v * H, kid_h, kid_c, &score[v]);
+        left[v] = right[v] = -1;
+        if (!(score[v] > 0.0f) || depth[v] >= max_depth) continue;
+        if (n + 2 > max_nodes) { *truncated += 1; continue; }
+        for (int side = 0; side < 2; ++side) {
+            const int k = n + side;
+            parent[k] = v;
+            depth[k] = depth[v] + 1;
+            memcpy(h + (size_t)k * H, kid_h + (size_t)side * H, sizeof(float) * (size_t)H);
+            memcpy(c + (size_t)k * H, kid_c + (size_t)side * H, sizeof(float) * (size_t)H);
+        }
+        left[v] = n;
+        right[v] = n + 1;
+        n += 2;
+    }
+    free(kid_h); free(kid_c);
+    return n;
+}

@@ -327,6 +327,55 @@ def workload(name: str) -> Workload:
 WORKLOADS = ("tiny", "sentence", "throughput", "treernn", "rntn", "stress")
 
 
+@dataclass
+class TopDown:
+    """Inputs of a top-down generation: parameters, root states and the two limits."""
+    name: str
+    hidden: int
+    u_td: np.ndarray       # [H x 8H], columns [iL|fL|oL|uL|iR|fR|oR|uR]
+    b_td: np.ndarray       # [8H]
+    w_stop: np.ndarray     # [H]
+    b_stop: float
+    h_root: np.ndarray     # [B x H]
+    c_root: np.ndarray     # [B x H]
+    max_depth: int
+    max_nodes: int
+
+
+def make_topdown(seed: int, name: str, batch: int, hidden: int, max_depth: int, max_nodes: int, stop_scale: float,
+                 b_stop: float) -> TopDown:
+    """Xavier-uniform edge weights (forget biases 1), a stopping direction of N(0, (stop_scale / sqrt(H))^2) entries,
+    root states h ~ U(-0.8, 0.8), c ~ N(0, 0.5^2)."""
+    H = hidden
+    u_td = _xavier(Stream(seed, "u_td"), H, 8 * H)
+    b_td = np.zeros(8 * H, dtype=np.float32)
+    b_td[H:2 * H] = 1.0
+    b_td[5 * H:6 * H] = 1.0
+    w_stop = Stream(seed, "w_stop").normal(stop_scale / float(np.sqrt(H)), (H,))
+    h_root = Stream(seed, "h_root").uniform(-0.8, 0.8, (batch, H))
+    c_root = Stream(seed, "c_root").normal(0.5, (batch, H))
+    return TopDown(name, H, u_td, b_td, w_stop, float(b_stop), h_root, c_root, max_depth, max_nodes)
+
+
+def topdown_workload(name: str) -> TopDown:
+    """Dynamic-structure workloads: `td64` / `td1` are the two batch sizes of the paper's top-down experiment (64 and 1
+    instances) at the hidden size of the `throughput` workload; the others are small parity cases."""
+    if name == "td64":        # 2 038 nodes, depths 0..9, trees of 1 to 409 nodes
+        return make_topdown(10, name, 64, 512, 12, 8192, 6.0, -0.3)
+    if name == "td1":         # tree 7 of td64 on its own: 409 nodes
+        w = make_topdown(10, name, 64, 512, 12, 8192, 6.0, -0.3)
+        w.h_root, w.c_root, w.max_nodes = w.h_root[7:8].copy(), w.c_root[7:8].copy(), 1024
+        return w
+    if name == "td_small":    # 231 nodes, depths 0..6
+        return make_topdown(18, name, 5, 33, 6, 700, 6.0, 0.3)
+    if name == "td_mid":      # 1 781 nodes, depths 0..10
+        return make_topdown(12, name, 25, 150, 10, 4096, 6.0, -0.3)
+    raise ValueError(name)
+
+
+TOPDOWN_WORKLOADS = ("td_small", "td_mid", "td64", "td1")
+
+
 def subset(batch: TreeBatch, trees: Sequence[int]) -> tuple:
     """The given trees as a batch of their own (indices rebased); also returns, for
     every node of the new batch, its global index in the original batch."""

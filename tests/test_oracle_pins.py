@@ -684,3 +684,98 @@ def test_classifier_backward_matches_torch_cross_entropy():
     assert not zero["g_h"].any()
     with pytest.raises(ValueError):
         oracle.classify_backward(h, w, b, np.full(N, C, np.int32))
+
+
+# ---- top-down generation (dynamic structure) -------------------------------------------------
+
+def _td_case(seed, B, H, D, cap, b_stop):
+    return synth.make_topdown(seed, "case", B, H, D, cap, 6.0, b_stop)
+
+
+def _td_run(w, **chg):
+    a = dict(u_td=w.u_td, b_td=w.b_td, w_stop=w.w_stop, b_stop=w.b_stop, h_root=w.h_root, c_root=w.c_root,
+             max_depth=w.max_depth, max_nodes=w.max_nodes)
+    a.update(chg)
+    return oracle.td_generate(**a)
+
+
+def test_topdown_states_follow_lstm_cells_along_every_path():
+    """A node's state is what torch.nn.LSTMCell (float64, zero input, recurrent weights = this side's block of u_td
+    in torch's gate order i, f, g, o) gives when it is applied edge by edge from the root down."""
+    w = synth.topdown_workload("td_small")
+    r = _td_run(w)
+    H = w.hidden
+    assert r["n_nodes"] > 100 and (r["left"] >= 0).any() and (r["left"][r["depth"] < w.max_depth] < 0).any()
+    cells = []
+    for side in range(2):
+        cell = torch.nn.LSTMCell(1, H, dtype=torch.float64)
+        blk = lambda q: w.u_td[:, side * 4 * H + q * H: side * 4 * H + (q + 1) * H].astype(np.float64)
+        bias = lambda q: w.b_td[side * 4 * H + q * H: side * 4 * H + (q + 1) * H].astype(np.float64)
+        order = (0, 1, 3, 2)                          # ours: i f o u;  torch: i f g(=u) o
+        with torch.no_grad():
+            cell.weight_hh.copy_(torch.tensor(np.concatenate([blk(q).T for q in order], axis=0)))
+            cell.bias_hh.copy_(torch.tensor(np.concatenate([bias(q) for q in order])))
+            cell.weight_ih.zero_()
+            cell.bias_ih.zero_()
+        cells.append(cell)
+    zero_in = torch.zeros(1, 1, dtype=torch.float64)
+    checked = 0
+    for v in range(r["n_nodes"]):
+        p = int(r["parent"][v])
+        if p < 0:
+            assert np.array_equal(r["h"][v], w.h_root[v]) and np.array_equal(r["c"][v], w.c_root[v])
+            continue
+        side = 0 if int(r["left"][p]) == v else 1
+        assert int(r["right"][p]) == v or side == 0
+        with torch.no_grad():
+            hh, cc = cells[side](zero_in, (torch.tensor(r["h"][p], dtype=torch.float64)[None],
+                                           torch.tensor(r["c"][p], dtype=torch.float64)[None]))
+        assert np.allclose(r["h"][v], hh[0].numpy(), rtol=1e-6, atol=1e-7), v
+        assert np.allclose(r["c"][v], cc[0].numpy(), rtol=1e-6, atol=1e-7), v
+        assert r["depth"][v] == r["depth"][p] + 1
+        checked += 1
+    assert checked == r["n_nodes"] - w.h_root.shape[0]
+
+
+def test_topdown_decisions_and_structure():
+    """The stopping rule against a numpy evaluation of the score on the generated states, breadth-first numbering,
+    and closed forms: a positive constant score grows full trees to the depth limit, a negative one leaves the
+    roots alone, a small capacity truncates."""
+    w = synth.topdown_workload("td_small")
+    r = _td_run(w)
+    B, n = w.h_root.shape[0], r["n_nodes"]
+    score = r["h"].astype(np.float64) @ w.w_stop.astype(np.float64) + w.b_stop
+    assert np.allclose(r["score"], score, rtol=1e-6, atol=1e-6)
+    expands = (score > 0) & (r["depth"] < w.max_depth)
+    assert np.array_equal(r["left"] >= 0, expands) and np.array_equal(r["right"] >= 0, expands)
+    assert r["truncated"] == 0
+    kids = np.flatnonzero(expands)
+    assert np.array_equal(r["left"][kids], B + 2 * np.arange(len(kids)))          # breadth first, left before right
+    assert np.array_equal(r["right"][kids], r["left"][kids] + 1)
+    assert np.array_equal(np.sort(np.concatenate([r["left"][kids], r["right"][kids]])), np.arange(B, n))
+    assert (np.diff(r["depth"]) >= 0).all()
+    zero = np.zeros_like(w.w_stop)
+    full = _td_run(w, w_stop=zero, b_stop=1.0, max_depth=4)
+    assert full["n_nodes"] == B * (2 ** 5 - 1) and np.array_equal(np.bincount(full["depth"]), B * 2 ** np.arange(5))
+    none = _td_run(w, w_stop=zero, b_stop=-1.0)
+    assert none["n_nodes"] == B and (none["left"] < 0).all()
+    edge = _td_run(w, w_stop=zero, b_stop=0.0)                  # score == 0 does not expand
+    assert edge["n_nodes"] == B
+    flat = _td_run(w, w_stop=zero, b_stop=1.0, max_depth=0)
+    assert flat["n_nodes"] == B
+    small = _td_run(w, w_stop=zero, b_stop=1.0, max_depth=4, max_nodes=B + 7)
+    assert small["n_nodes"] == B + 6 and small["truncated"] == (B + 6) - 3       # three nodes expanded, the rest wanted to
+    with pytest.raises(ValueError):
+        _td_run(w, max_nodes=B - 1)
+
+
+def test_topdown_step_is_the_generators_step():
+    """td_step on a node's stored state reproduces the stored children (what the GPU tests lean on node by node) and
+    distinguishes the sides."""
+    w = synth.topdown_workload("td_small")
+    r = _td_run(w)
+    v = int(np.flatnonzero(r["left"] >= 0)[3])
+    kh, kc, score = oracle.td_step(w.u_td, w.b_td, w.w_stop, w.b_stop, r["h"][v], r["c"][v])
+    assert np.array_equal(kh[0], r["h"][r["left"][v]]) and np.array_equal(kh[1], r["h"][r["right"][v]])
+    assert np.array_equal(kc[0], r["c"][r["left"][v]]) and np.array_equal(kc[1], r["c"][r["right"][v]])
+    assert score == r["score"][v] and not np.allclose(kh[0], kh[1])
