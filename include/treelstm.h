@@ -245,6 +245,49 @@ int tl_classify_backward(tl_ctx *ctx, int n_rows, const float *h, const float *w
                          const int32_t *label, float *d_logits, float *g_h, float *d_w_s, float *d_b_s, float *loss,
                          void *hip_stream);
 
+/*
+ * Top-down generation of dynamically structured trees (Section 6.3, "Dynamically Structured
+ * Models": whether a node gets children is decided from the value computed for that node, so the
+ * trees are not known before they are evaluated).  The paper names such models and prints no
+ * equations; the form taken is an LSTM step along every parent -> child edge with weights per
+ * side and a linear stopping rule:
+ *     score(n) = w_stop . h[n] + b_stop        n gets two children iff score(n) > 0,
+ *                                               depth(n) < max_depth and two rows are free
+ *     child on side s:  g = h[n] U_s + b_s = [gi|gf|go|gu]
+ *                       c_s = sigmoid(gf) c[n] + sigmoid(gi) tanh(gu),  h_s = sigmoid(go) tanh(c_s)
+ *
+ * tl_td_create: copies and re-packs the parameters.
+ *   u_td   [H x 8H] fp32 row-major, columns [iL|fL|oL|uL|iR|fR|oR|uR]   DEVICE, read during the call
+ *   b_td   [8H], w_stop [H] fp32                                         DEVICE, read during the call
+ *   b_stop, spin_limit (0: default; bound of every wait inside the kernel)
+ * TL_OK, TL_EINVAL (null pointer, hidden < 1 or > 16384), TL_ENOMEM, TL_EHIP.
+ */
+typedef struct tl_td_ctx tl_td_ctx;
+int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *w_stop, float b_stop, int spin_limit,
+                 tl_td_ctx **out);
+
+/*
+ * Grows n_trees trees breadth first in one persistent kernel, asynchronously on hip_stream.
+ *   h, c     [max_nodes x H] fp32: rows 0 .. n_trees-1 hold the root states on entry (node t is
+ *            the root of tree t); every other used row is written                       DEVICE
+ *   parent, left, right, depth  [max_nodes] int32 out: links (-1: none) and depth       DEVICE
+ *   score    [max_nodes] fp32 out                                                       DEVICE
+ *   counts   [4] int32 out: nodes, nodes that would have expanded but found no two free
+ *            rows, frontiers walked, 0                                                  DEVICE
+ * Rows beyond counts[0] are not written.  The two children of a node are consecutive rows, left
+ * first; which rows they are depends on timing and differs from run to run, the trees (and each
+ * node's state, bit for bit) do not.  Nothing is allocated.  fp32 arithmetic on the matrix units.
+ * The kernel needs the device to itself (all its workgroups resident), like the persistent
+ * schedulers of tl_forward; calls on one context must not overlap.
+ * TL_OK, TL_EINVAL (null pointer, n_trees < 1, max_nodes < n_trees, max_depth < 0), TL_EHIP.
+ * tl_td_status waits for the stream and returns what the kernel latched: TL_OK, or TL_ESTALL if
+ * a wait inside the kernel ran out of spins.
+ */
+int tl_td_generate(tl_td_ctx *ctx, int n_trees, int max_nodes, int max_depth, float *h, float *c, int32_t *parent,
+                   int32_t *left, int32_t *right, int32_t *depth, float *score, int32_t *counts, void *hip_stream);
+int tl_td_status(tl_td_ctx *ctx);
+int tl_td_destroy(tl_td_ctx *ctx);
+
 const char *tl_strerror(int code);
 
 /* Frees the context and everything it owns.  Waits for the device. */

@@ -21,7 +21,7 @@ TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
 
 EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_set_keep_gates", "tl_classify",
-           "tl_classify_backward", "tl_strerror", "tl_destroy")
+           "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
 
 
 class tl_config(ctypes.Structure):
@@ -61,6 +61,14 @@ def lib():
         L.tl_backward.argtypes = [vp, ci, ci] + [vp] * 13
         L.tl_set_keep_gates.restype = ci
         L.tl_set_keep_gates.argtypes = [vp, ci]
+        L.tl_td_create.restype = ci
+        L.tl_td_create.argtypes = [ci, vp, vp, vp, ctypes.c_float, ci, ctypes.POINTER(vp)]
+        L.tl_td_generate.restype = ci
+        L.tl_td_generate.argtypes = [vp, ci, ci, ci] + [vp] * 9
+        L.tl_td_status.restype = ci
+        L.tl_td_status.argtypes = [vp]
+        L.tl_td_destroy.restype = ci
+        L.tl_td_destroy.argtypes = [vp]
         L.tl_classify.restype = ci
         L.tl_classify.argtypes = [vp, ci, vp, vp, vp, ci, vp, vp]
         L.tl_classify_backward.restype = ci
@@ -183,6 +191,52 @@ def tl_classify_backward(ctx, h, w_s, b_s, label, stream=None):
                                       out["d_w_s"].data_ptr(), out["d_b_s"].data_ptr(), out["loss"].data_ptr(), st),
            "tl_classify_backward")
     return out
+
+
+def tl_td_create(hidden, u_td, b_td, w_stop, b_stop, spin_limit=0):
+    """Context of the top-down generator; u_td [H x 8H], b_td [8H], w_stop [H] float32 CUDA tensors."""
+    import torch
+    for t in (u_td, b_td, w_stop):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+    assert tuple(u_td.shape) == (hidden, 8 * hidden) and b_td.numel() == 8 * hidden and w_stop.numel() == hidden
+    ctx = ctypes.c_void_p()
+    _check(lib().tl_td_create(int(hidden), u_td.data_ptr(), b_td.data_ptr(), w_stop.data_ptr(), float(b_stop), int(spin_limit),
+                              ctypes.byref(ctx)), "tl_td_create")
+    return ctx
+
+
+def tl_td_generate(ctx, h_root, c_root, max_nodes, max_depth, stream=None):
+    """Grows one tree per row of h_root / c_root (float32 CUDA tensors [B x H]).  Returns a dict of new CUDA tensors
+    with max_nodes rows each (h, c, parent, left, right, depth, score) and counts [4]; asynchronous."""
+    import torch
+    B, H = int(h_root.shape[0]), int(h_root.shape[1])
+    assert h_root.is_cuda and c_root.is_cuda and h_root.dtype == torch.float32 and tuple(c_root.shape) == (B, H)
+    dev = h_root.device
+    out = {"h": torch.empty((max_nodes, H), device=dev), "c": torch.empty((max_nodes, H), device=dev),
+           "score": torch.empty(max_nodes, device=dev), "counts": torch.zeros(4, dtype=torch.int32, device=dev)}
+    for k in ("parent", "left", "right", "depth"):
+        out[k] = torch.empty(max_nodes, dtype=torch.int32, device=dev)
+    out["h"][:B].copy_(h_root)
+    out["c"][:B].copy_(c_root)
+    tl_td_generate_into(ctx, B, max_depth, out, stream)
+    return out
+
+
+def tl_td_generate_into(ctx, n_trees, max_depth, out, stream=None):
+    """The call itself on buffers that tl_td_generate allocated (root rows in place)."""
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_td_generate(ctx, int(n_trees), int(out["h"].shape[0]), int(max_depth), out["h"].data_ptr(), out["c"].data_ptr(),
+                                out["parent"].data_ptr(), out["left"].data_ptr(), out["right"].data_ptr(),
+                                out["depth"].data_ptr(), out["score"].data_ptr(), out["counts"].data_ptr(), st), "tl_td_generate")
+
+
+def tl_td_status(ctx) -> int:
+    return lib().tl_td_status(ctx)
+
+
+def tl_td_destroy(ctx) -> None:
+    _check(lib().tl_td_destroy(ctx), "tl_td_destroy")
 
 
 def tl_strerror(code: int) -> str:

@@ -26,7 +26,9 @@ enum Epi {
     EPI_LSTM_LEAF = 0, EPI_LSTM_INNER = 1, EPI_RNN_INNER = 2, EPI_RNTN_INNER = 3,
     // backward pass (backward.hpp): gate gradients of internal nodes / leaves (the forward contraction is
     // recomputed), and the gradient sent to the operand rows (gate gradients times transposed weights)
-    EPI_BWD_INNER_GATES = 4, EPI_BWD_INNER_OPERAND = 5, EPI_BWD_LEAF_GATES = 6, EPI_BWD_LEAF_OPERAND = 7
+    EPI_BWD_INNER_GATES = 4, EPI_BWD_INNER_OPERAND = 5, EPI_BWD_LEAF_GATES = 6, EPI_BWD_LEAF_OPERAND = 7,
+    // top-down generation (topdown.hpp): the child on one side of a node from the node's own state
+    EPI_TD_CHILD = 8
 };
 
 template <int EPI> struct EpiTraits;
@@ -38,6 +40,7 @@ template <> struct EpiTraits<EPI_BWD_INNER_GATES>   { static constexpr int NG = 
 template <> struct EpiTraits<EPI_BWD_INNER_OPERAND> { static constexpr int NG = 1, SEG = 1; };
 template <> struct EpiTraits<EPI_BWD_LEAF_GATES>    { static constexpr int NG = 3, SEG = 1; };
 template <> struct EpiTraits<EPI_BWD_LEAF_OPERAND>  { static constexpr int NG = 1, SEG = 1; };
+template <> struct EpiTraits<EPI_TD_CHILD>          { static constexpr int NG = 4, SEG = 1; };
 
 // LDS carve-up (dynamic shared memory, 16-byte aligned).
 struct TileSmem {
@@ -158,13 +161,33 @@ template <int EPI, bool COH, int NG>
 __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG],
                                      int rb, int count, int cg, int lane)
 {
-    if constexpr (EPI >= EPI_BWD_INNER_GATES) {
+    if constexpr (EPI >= EPI_BWD_INNER_GATES && EPI <= EPI_BWD_LEAF_OPERAND) {
         bwd_epilogue<EPI, NG>(sm, f, gm, acc, rb, count, cg, lane);
         return;
     }
     const int hu = cg * HU + (lane & 15);
     const int H = f.H;
     if (hu >= H) return;
+    if constexpr (EPI == EPI_TD_CHILD) {
+        // rows: node = the child to write, src0 = its parent; gates i, f, o, u of an LSTM step along the edge
+        float bias[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = rb * 16 + (lane >> 4) * 4 + v;
+            if (row >= count) continue;
+            const int node = sm.node[row];
+            if (node < 0) continue;
+            const float cp = ld_f<COH>(f.c + (size_t)sm.src0[row] * H + hu);
+            const float i = sigmoid_f(acc[0][v] + bias[0]), fg = sigmoid_f(acc[1][v] + bias[1]);
+            const float og = sigmoid_f(acc[2][v] + bias[2]), u = tanh_f(acc[3][v] + bias[3]);
+            const float cc = __builtin_fmaf(fg, cp, i * u);
+            st_f<COH>(f.c + (size_t)node * H + hu, cc);
+            st_f<COH>(f.h + (size_t)node * H + hu, og * tanh_f(cc));
+        }
+        return;
+    }
     float bias[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];

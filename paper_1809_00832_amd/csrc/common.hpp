@@ -51,6 +51,7 @@ struct alignas(LINE) Ctl {
     Line q_tail;                  // ready-queue entries reserved by producers
     Line tiles;                   // tiles formed (statistics only)
     Line direct;                  // nodes that a scheduler handed to its own gang without passing the queue
+    Line truncated;               // top-down generation: nodes that would have expanded but found no free rows
     // grid barrier of the level scheduler, one word per L2 domain: arrivals of the domain's workgroups in
     // the low half, ready-queue records they have appended (cumulative) in the high half
     Line64 bar_xcd[N_XCD];

@@ -14,6 +14,7 @@
 #include "schedulers.hpp"
 #include "classify.hpp"
 #include "backward.hpp"
+#include "topdown.hpp"
 
 using namespace tl;
 
@@ -74,6 +75,21 @@ struct tl_ctx {
     int profiling = 0;
     hipEvent_t ev[TL_PROFILE_RING][TL_N_STAGES]{};   // created on first use
     long long n_recorded = 0;                        // forwards recorded since profiling was switched on
+};
+
+// Context of the top-down generator (tl_td_*).
+struct tl_td_ctx {
+    int device = 0, n_cu = 0, H = 0, n_cg = 0, spin_limit = 0;
+    tl::Gemm side[2]{};
+    void *wp[2] = {nullptr, nullptr};
+    float *bp[2] = {nullptr, nullptr};
+    float *w_stop = nullptr;
+    float b_stop = 0.f;
+    float *zeros = nullptr;
+    tl::Ctl *ctl = nullptr;
+    tl::Ctl *host_ctl = nullptr;      // pinned
+    hipStream_t last_stream = nullptr;
+    bool ran = false;
 };
 
 namespace {
@@ -490,6 +506,19 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
 
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
     return TL_OK;
+}
+
+void td_free(tl_td_ctx *ctx)
+{
+    for (int sd = 0; sd < 2; ++sd) {
+        (void)hipFree(ctx->wp[sd]);
+        (void)hipFree(ctx->bp[sd]);
+    }
+    (void)hipFree(ctx->w_stop);
+    (void)hipFree(ctx->zeros);
+    (void)hipFree(ctx->ctl);
+    if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
+    delete ctx;
 }
 
 int read_ctl(tl_ctx *ctx)
@@ -917,6 +946,106 @@ int tl_classify_backward(tl_ctx *ctx, int n_rows, const float *h, const float *w
     if (slices > slice_cap) slices = slice_cap;
     hipLaunchKernelGGL(kw, dim3((unsigned)col_blocks, (unsigned)slices), dim3(256), 0, st, h, d_logits, d_w_s, d_b_s, n_rows, H, C);
     TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
+int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *w_stop, float b_stop, int spin_limit,
+                 tl_td_ctx **out)
+{
+    if (!out) return TL_EINVAL;
+    *out = nullptr;
+    if (!u_td || !b_td || !w_stop || hidden < 1 || hidden > (1 << 14) || spin_limit < 0) return TL_EINVAL;
+    tl_td_ctx *ctx = new (std::nothrow) tl_td_ctx();
+    if (!ctx) return TL_ENOMEM;
+    const int H = hidden;
+    int rc = [&]() -> int {
+        TL_HIP(hipGetDevice(&ctx->device));
+        hipDeviceProp_t prop;
+        TL_HIP(hipGetDeviceProperties(&prop, ctx->device));
+        ctx->n_cu = prop.multiProcessorCount;
+        ctx->H = H;
+        ctx->n_cg = (H + HU - 1) / HU;
+        ctx->b_stop = b_stop;
+        ctx->spin_limit = spin_limit > 0 ? spin_limit : DEFAULT_SPIN_LIMIT;
+        // one side's [H x 4H] block of u_td, made contiguous for the packer
+        float *block = nullptr;
+        TL_HIP(hipMalloc(&block, (size_t)H * 4 * H * sizeof(float)));
+        for (int sd = 0; sd < 2; ++sd) {
+            const hipError_t e = hipMemcpy2D(block, (size_t)4 * H * sizeof(float), u_td + (size_t)sd * 4 * H, (size_t)8 * H * sizeof(float),
+                                             (size_t)4 * H * sizeof(float), (size_t)H, hipMemcpyDeviceToDevice);
+            if (e != hipSuccess) { (void)hipFree(block); return TL_EHIP; }
+            const int prc = pack_gemm(block, b_td + (size_t)sd * 4 * H, 4, H, 1, H, ctx->n_cg, 0, false, &ctx->side[sd], &ctx->wp[sd], &ctx->bp[sd]);
+            if (prc != TL_OK) { (void)hipFree(block); return prc; }
+            if (hipDeviceSynchronize() != hipSuccess) { (void)hipFree(block); return TL_EHIP; }
+        }
+        TL_HIP(hipFree(block));
+        TL_HIP(hipMalloc(&ctx->w_stop, (size_t)round_up(H, 4) * sizeof(float)));
+        TL_HIP(hipMemset(ctx->w_stop, 0, (size_t)round_up(H, 4) * sizeof(float)));
+        TL_HIP(hipMemcpy(ctx->w_stop, w_stop, (size_t)H * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMalloc(&ctx->zeros, 4096));
+        TL_HIP(hipMemset(ctx->zeros, 0, 4096));
+        TL_HIP(hipMalloc(&ctx->ctl, sizeof(Ctl)));
+        TL_HIP(hipMemset(ctx->ctl, 0, sizeof(Ctl)));
+        TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
+        TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_td_generate<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)TILE_SMEM_BYTES));
+        TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_td_generate<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)TILE_SMEM_BYTES));
+        TL_HIP(hipDeviceSynchronize());
+        return TL_OK;
+    }();
+    if (rc != TL_OK) {
+        td_free(ctx);
+        return rc;
+    }
+    *out = ctx;
+    return TL_OK;
+}
+
+int tl_td_generate(tl_td_ctx *ctx, int n_trees, int max_nodes, int max_depth, float *h, float *c, int32_t *parent,
+                   int32_t *left, int32_t *right, int32_t *depth, float *score, int32_t *counts, void *hip_stream)
+{
+    if (!ctx || !h || !c || !parent || !left || !right || !depth || !score || !counts) return TL_EINVAL;
+    if (n_trees < 1 || max_nodes < n_trees || max_depth < 0) return TL_EINVAL;
+    if ((unsigned long long)max_nodes * (unsigned long long)ctx->H >= (1ull << 40)) return TL_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    TopDown a{};
+    a.f.h = h; a.f.c = c; a.f.H = ctx->H; a.f.n_cg = ctx->n_cg;
+    a.f.zeros = ctx->zeros; a.f.ctl = ctx->ctl; a.f.spin_limit = ctx->spin_limit;
+    a.f.n_trees = n_trees; a.f.n_nodes = max_nodes;
+    a.side[0] = ctx->side[0]; a.side[1] = ctx->side[1];
+    a.w_stop = ctx->w_stop; a.b_stop = ctx->b_stop;
+    a.n_trees = n_trees; a.max_depth = max_depth; a.max_nodes = max_nodes;
+    a.parent = parent; a.left = left; a.right = right; a.depth = depth; a.score = score; a.counts = counts;
+    // the grid barrier in its one-level form: at most FLAT_BARRIER_MAX workgroups, all resident (one per CU)
+    int grid = ctx->n_cu < (int)FLAT_BARRIER_MAX ? ctx->n_cu : (int)FLAT_BARRIER_MAX;
+    if (grid < 1) grid = 1;
+    const bool vec4 = ctx->H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
+    hipLaunchKernelGGL(k_td_reset, dim3(4), dim3(256), 0, st, a);
+    if (vec4)
+        hipLaunchKernelGGL(k_td_generate<true>, dim3(grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, a);
+    else
+        hipLaunchKernelGGL(k_td_generate<false>, dim3(grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, a);
+    TL_HIP(hipGetLastError());
+    ctx->last_stream = st;
+    ctx->ran = true;
+    return TL_OK;
+}
+
+int tl_td_status(tl_td_ctx *ctx)
+{
+    if (!ctx) return TL_EINVAL;
+    if (!ctx->ran) return TL_OK;
+    TL_HIP(hipMemcpyAsync(ctx->host_ctl, ctx->ctl, sizeof(Ctl), hipMemcpyDeviceToHost, ctx->last_stream));
+    TL_HIP(hipStreamSynchronize(ctx->last_stream));
+    return ctx->host_ctl->status;
+}
+
+int tl_td_destroy(tl_td_ctx *ctx)
+{
+    if (!ctx) return TL_EINVAL;
+    (void)hipDeviceSynchronize();
+    td_free(ctx);
     return TL_OK;
 }
 
