@@ -221,6 +221,55 @@ def backward_stage(w, n_classes, reps=10):
         net.close()
 
 
+def topdown_bench(steps, warmup, with_cpu):
+    """Top-down generation of dynamically structured trees (the experiment of Table 3: batch sizes 1 and 64): instances
+    per second of tl_td_generate with the root states resident, kernel time from events on the launch stream, the
+    algorithmic flops (8 H^2 per generated child plus 2 H per scored node) and the dependent frontiers that bound it."""
+    import torch
+    from paper_1809_00832_amd import binding, synth
+    rows = []
+    for name in ("td64", "td1"):
+        w = synth.topdown_workload(name)
+        dev = lambda x: torch.from_numpy(x).cuda().contiguous()
+        ctx = binding.tl_td_create(w.hidden, dev(w.u_td), dev(w.b_td), dev(w.w_stop), w.b_stop)
+        try:
+            out = binding.tl_td_generate(ctx, dev(w.h_root), dev(w.c_root), w.max_nodes, w.max_depth)
+            B = w.h_root.shape[0]
+            for _ in range(warmup):
+                binding.tl_td_generate_into(ctx, B, w.max_depth, out)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev[0].record()
+            for i in range(steps):
+                binding.tl_td_generate_into(ctx, B, w.max_depth, out)
+                ev[i + 1].record()
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / steps
+            if binding.tl_td_status(ctx) != 0:
+                raise RuntimeError("generation failed")
+            counts = out["counts"].cpu().numpy()
+            n, fronts = int(counts[0]), int(counts[2])
+            kernel_ms = sum(ev[i].elapsed_time(ev[i + 1]) for i in range(steps)) / steps
+            flops = 8.0 * w.hidden ** 2 * (n - B) + 2.0 * w.hidden * n
+            row = {"workload": name, "instances": B, "hidden": w.hidden, "nodes": n, "frontiers": fronts,
+                   "ms_per_batch": sec * 1e3, "instances_per_s": B / sec, "nodes_per_s": n / sec, "launch_ms": kernel_ms,
+                   "tflops": flops / (kernel_ms * 1e-3) / 1e12, "frac_mfma_peak": flops / (kernel_ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"],
+                   "us_per_frontier": kernel_ms * 1e3 / max(fronts, 1)}
+            if with_cpu and name == "td1":
+                import oracle
+                t0 = time.perf_counter()
+                r = oracle.td_generate(w.u_td, w.b_td, w.w_stop, w.b_stop, w.h_root, w.c_root, w.max_depth, w.max_nodes)
+                dt = time.perf_counter() - t0
+                row["cpu_baseline"] = {"value": 1.0 / dt, "unit": "instances/s", "cores": 1, "kind": "oracle",
+                                       "sample": "the one tree of td1 (%d nodes)" % r["n_nodes"], "nodes_per_s": r["n_nodes"] / dt}
+            rows.append(row)
+        finally:
+            binding.tl_td_destroy(ctx)
+    print(json.dumps({"topdown": rows, "dtype": "f32", "data": "synthetic",
+                      "note": "tl_td_generate, root states resident; trees are grown breadth first, two grid barriers per depth"}))
+
+
 def cpu_baseline(w):
     """The CPU checker as it stands, all trees once, one thread per host core (at most 16)."""
     import oracle
@@ -266,6 +315,8 @@ def main():
     ap.add_argument("--backward", action="store_true", help="also time tl_backward on the same batch (TreeLSTM, fp32)")
     ap.add_argument("--length-sweep", action="store_true",
                     help="print only the latency of single trees of 2..1024 leaves (balanced, random, chain)")
+    ap.add_argument("--topdown", action="store_true",
+                    help="print only the throughput of top-down generation of dynamically structured trees (batches of 64 and 1)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
@@ -286,6 +337,9 @@ def main():
         return
     if args.length_sweep:
         length_sweep(min(args.steps, 30), min(args.warmup, 5))
+        return
+    if args.topdown:
+        topdown_bench(args.steps, args.warmup, not args.no_cpu)
         return
     precision = binding.TL_F32 if args.precision == "f32" else binding.TL_BF16_IN
 
