@@ -73,9 +73,22 @@ enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
  *  TL_SCHED_LEVEL_HOST   node heights and per-height node lists are built on the device,
  *                        then one kernel launch per height from the host (which reads the
  *                        number of heights back first).  Comparison baseline.
+ *  TL_SCHED_READY_PRIORITY  TL_SCHED_READY with the critical path first (what Section 4.1
+ *                        leaves as future work: operations that many later ones wait for
+ *                        should run before others that are ready).  The structure pass also
+ *                        computes every node's distance from its root, i.e. the number of
+ *                        dependent steps still above it (counted up to 128; two more small
+ *                        launches).  A node is critical when that distance is at least 32
+ *                        and at least four times the batch's mean.  Critical nodes that start ready go to the front of
+ *                        the ready queue, and a critical parent that becomes ready is handed
+ *                        straight back to the gang that finished its last child, as a small
+ *                        tile of its own, instead of queueing behind the bulk of the batch;
+ *                        that gang takes no other work while it holds such a chain.  Pays
+ *                        when a few deep trees share a batch with much shallow work, costs
+ *                        the extra launches otherwise.
  * Results do not depend on the scheduler: all paths of one precision sum a node's
- * contraction in the same order, so the three agree bit for bit. */
-enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2 };
+ * contraction in the same order, so all of them agree bit for bit. */
+enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2, TL_SCHED_READY_PRIORITY = 3 };
 
 enum tl_error {
     TL_OK = 0,

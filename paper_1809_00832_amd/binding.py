@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(HERE, "libtreelstm.so")
 
 TL_TREELSTM, TL_TREERNN, TL_RNTN = 0, 1, 2
 TL_F32, TL_BF16_IN = 0, 1
-TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST = 0, 1, 2
+TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST, TL_SCHED_READY_PRIORITY = 0, 1, 2, 3
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4, -5
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
-SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST}
+SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST,
+              "ready_priority": TL_SCHED_READY_PRIORITY}
 
 EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_set_keep_gates", "tl_classify",
            "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")

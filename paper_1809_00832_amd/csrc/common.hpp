@@ -52,6 +52,11 @@ struct alignas(LINE) Ctl {
     Line tiles;                   // tiles formed (statistics only)
     Line direct;                  // nodes that a scheduler handed to its own gang without passing the queue
     Line truncated;               // top-down generation: nodes that would have expanded but found no free rows
+    // priority variant of the ready scheduler: sum of all nodes' (capped) distances from their roots, and the
+    // critical / other seeds placed so far
+    Line64 depth_sum;
+    Line seed_front;
+    Line seed_back;
     // grid barrier of the level scheduler, one word per L2 domain: arrivals of the domain's workgroups in
     // the low half, ready-queue records they have appended (cumulative) in the high half
     Line64 bar_xcd[N_XCD];
@@ -113,6 +118,8 @@ struct Fwd {
     // workspace
     int32_t *parent, *pending, *leaf_list, *root_ws;
     int32_t *height, *arrive, *level_cnt, *level_off, *level_fill, *level_nodes;
+    int32_t *depth_root;              // priority scheduling: distance of every node from its root, capped
+    int priority;                     // ready scheduler: critical path first
     QRec *q_rec;                      // ready queue, append-only: one record per internal node
     GangBox *gangs;
     const float *zeros;               // 256 bytes of zeros (stand-in source for padded operand granules)

@@ -3,6 +3,7 @@
 
 #include <type_traits>
 
+#include "structure.hpp"
 #include "cell_ws.hpp"
 #include "cell_rntn.hpp"
 
@@ -379,6 +380,10 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
     int spins = 0;
     unsigned last_head = 0u, last_tail = 0u, last_direct = ~0u;
     bool leave = false;
+    // priorities: a parent with at least crit_thr dependent steps above it is critical; while this gang holds
+    // critical nodes (handed back to it tile after tile) it takes nothing else off the queue
+    const int crit_thr = f.priority ? critical_threshold(f) : 0x7fffffff;
+    bool holding = false;
     while (!leave) {
         bool progress = false;
         // ---- (1) a finished tile: resolve its rows' parents -------------------------------
@@ -393,52 +398,58 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                 int node = -1;
 #pragma unroll
                 for (int q = 0; q < GANG_RING; ++q) if (q == r) node = my_node[q];
-                int p = -1, pl = -1, pr = -1;
+                int p = -1, pl = -1, pr = -1, pd = 0;
                 if (node >= 0) {
                     p = f.parent[node];
                     if (p >= 0) {
                         const int old = add_dev(&f.pending[p], -1);
                         pl = f.left[p];                     // requested together with the decrement
                         pr = f.right[p];
+                        if (f.priority) pd = f.depth_root[p];
                         if (old != 1) p = -1;
                     }
                 }
                 const unsigned long long ready = __ballot(p >= 0);
-                const int n_ready = __popcll(ready);
                 // Parents that became ready.  While the queue holds less than one row per gang (the regime
                 // in which the next dependent step waits for this one: chains, the top of a tree) they go
                 // straight back to this gang as its next tile: no queue round trip between a node and its
                 // parent.  Otherwise they are pushed on the queue with one reservation on q_tail for the
                 // tile (handing them back while the queue is well filled only cuts the work into many
-                // small tiles: measured).
+                // small tiles: measured).  With priorities, critical parents are handed back in any case.
                 const bool scarce = last_tail - last_head < (unsigned)f.n_gangs;
-                if (n_ready > 0 && scarce) {
-                    // lane j < n_ready takes the j-th ready lane's node (position of the j-th set bit)
+                const unsigned long long critical = f.priority ? __ballot(p >= 0 && pd >= crit_thr) : 0ull;
+                const unsigned long long direct_set = scarce ? ready : critical;
+                const unsigned long long queue_set = ready & ~direct_set;
+                const int n_direct = __popcll(direct_set), n_queue = __popcll(queue_set);
+                holding = critical != 0ull;
+                if (n_direct > 0) {
+                    // lane j < n_direct takes the j-th chosen lane's node (position of the j-th set bit)
                     int pos = 0, rem = lane;
 #pragma unroll
                     for (int b = 32; b >= 1; b >>= 1) {
-                        const int cnt = __popcll(ready & (((1ull << b) - 1ull) << pos));
+                        const int cnt = __popcll(direct_set & (((1ull << b) - 1ull) << pos));
                         if (cnt <= rem) { pos += b; rem -= cnt; }
                     }
                     pos &= 63;
                     int node2 = __shfl(p, pos), s0 = __shfl(pl, pos), s1 = __shfl(pr, pos);
-                    if (lane >= n_ready) node2 = s0 = s1 = -1;
-                    if (lane == 0) add_dev(&ctl->direct.v, (unsigned)n_ready);
+                    if (lane >= n_direct) node2 = s0 = s1 = -1;
+                    if (lane == 0) add_dev(&ctl->direct.v, (unsigned)n_direct);
                     const unsigned seq = published + 1;
                     const int r2 = (int)(seq % GANG_RING);
 #pragma unroll
                     for (int q = 0; q < GANG_RING; ++q) if (q == r2) my_node[q] = node2;
                     unsigned long long *e = box->slot[r2];
-                    st_dev(&e[lane], slot_entry(seq, (unsigned)n_ready, node2));
-                    st_dev(&e[TILE_ROWS + lane], slot_entry(seq, (unsigned)n_ready, s0));
-                    st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, (unsigned)n_ready, s1));
+                    st_dev(&e[lane], slot_entry(seq, (unsigned)n_direct, node2));
+                    st_dev(&e[TILE_ROWS + lane], slot_entry(seq, (unsigned)n_direct, s0));
+                    st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, (unsigned)n_direct, s1));
                     published += 1;
-                } else if (n_ready > 0) {
+                }
+                if (n_queue > 0) {
                     unsigned base = 0;
-                    if (lane == 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_ready);
+                    if (lane == 0) base = add_dev(&ctl->q_tail.v, (unsigned)n_queue);
                     base = __shfl(base, 0);
-                    if (p >= 0) {
-                        const unsigned slot = base + (unsigned)__popcll(ready & ((1ull << lane) - 1ull));
+                    if ((queue_set >> lane) & 1ull) {
+                        const unsigned slot = base + (unsigned)__popcll(queue_set & ((1ull << lane) - 1ull));
                         if (slot < n_int) qrec_store<true>(&f.q_rec[slot], p, pl, pr);
                     }
                 }
@@ -460,7 +471,7 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
             spins = 0;
         }
         const unsigned in_flight = published - completed;
-        if (in_flight < (unsigned)GANG_RING && tail > head) {
+        if (!holding && in_flight < (unsigned)GANG_RING && tail > head) {
             const unsigned avail = tail - head;
             // an idle gang takes what there is; a busy gang looks ahead only when there is plenty for all
             if (in_flight == 0 || avail >= 16u * (unsigned)f.n_gangs) {

@@ -3,8 +3,8 @@
 // ready queue or a waiting list by their number of unresolved inputs (Section 4.1, Figure 4
 // step 2) and of the parent pointers that stand in for a call stack ("Graph execution stack").
 //
-// Counters that many threads bump at once are bumped once per wave (ballot + popcount) or once
-// per workgroup (LDS histogram): atomics on one address are served one after the other.
+// Counters that many threads bump at once are bumped once per workgroup (ballot + popcount per
+// wave, combined in LDS; LDS histograms): atomics on one address are served one after the other.
 #pragma once
 
 #include "common.hpp"
@@ -23,19 +23,33 @@ __device__ inline int tree_of(const int32_t *tree_off, int n_trees, int n)
     return lo;
 }
 
-// Slot in an append-only list for every lane with pred set: one atomic per wave.  Must be
-// called by all lanes of the wave.  Returns -1 for lanes without pred.
-template <typename T> __device__ inline int wave_append(T *counter, bool pred)
+// Slot in an append-only list for every thread with pred set (-1 for the others): one atomic per
+// workgroup of up to 1024 threads.  Must be called by
+// all threads of the workgroup; s_cnt is shared scratch of APPEND_SCRATCH ints.
+constexpr int APPEND_SCRATCH = 17;
+template <typename T> __device__ inline int block_append(T *counter, bool pred, int *s_cnt)
 {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = (blockDim.x + 63) >> 6;
     const unsigned long long mask = __ballot(pred);
-    if (mask == 0) return -1;
-    const int lane = threadIdx.x & 63;
-    const int first = __ffsll((long long)mask) - 1;
-    T base = 0;
-    if (lane == first) base = atomicAdd(counter, (T)__popcll(mask));
-    base = __shfl(base, first);
-    return pred ? (int)base + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
+    if (lane == 0) s_cnt[wave] = __popcll(mask);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < n_waves; ++w) {
+            const int c = s_cnt[w];
+            s_cnt[w] = total;
+            total += c;
+        }
+        s_cnt[16] = total ? (int)atomicAdd(counter, (T)total) : 0;
+    }
+    __syncthreads();
+    const int slot = pred ? s_cnt[16] + s_cnt[wave] + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
+    __syncthreads();
+    return slot;
 }
+
+// Threads per workgroup of the per-node kernels that append to lists.
+constexpr int NODE_BLOCK = 1024;
 
 // Resets the per-forward scheduler state.  A fill kernel rather than memsets so that a caller
 // may capture the forward in a HIP graph.
@@ -64,8 +78,9 @@ __global__ void k_reset(Fwd f, int with_levels)
 // One thread per node: checks, parent scatter, leaf list, counters of unfinished children.
 // Leaves are evaluated by a kernel of their own before any internal node, so pending[] counts
 // internal children only, and an internal node whose children are both leaves starts ready.
-__global__ void k_scatter(Fwd f)
+__global__ __launch_bounds__(NODE_BLOCK) void k_scatter(Fwd f)
 {
+    __shared__ int s_cnt[APPEND_SCRATCH];
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     Ctl *ctl = f.ctl;
     if (n <= f.n_trees) {   // offsets: 0 = off[0] < off[1] < ... < off[B] = N
@@ -97,15 +112,16 @@ __global__ void k_scatter(Fwd f)
             latch_error(ctl, TL_ESTRUCT);
         }
     }
-    const int leaf_slot = wave_append(&ctl->n_leaf_seen, is_leaf);
+    const int leaf_slot = block_append(&ctl->n_leaf_seen, is_leaf, s_cnt);
     if (is_leaf && leaf_slot < f.n_leaf) f.leaf_list[leaf_slot] = n;
-    const int seed_slot = wave_append(&ctl->q_tail.v, is_seed);
+    const int seed_slot = block_append(&ctl->q_tail.v, is_seed, s_cnt);
     if (is_seed && seed_slot < f.n_int) qrec_store<false>(&f.q_rec[seed_slot], n, l, r);
 }
 
 // One thread per node: the node nobody points to is its tree's root; there must be exactly one.
-__global__ void k_roots(Fwd f)
+__global__ __launch_bounds__(NODE_BLOCK) void k_roots(Fwd f)
 {
+    __shared__ int s_cnt[APPEND_SCRATCH];
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     Ctl *ctl = f.ctl;
     if (n == 0) {
@@ -119,7 +135,72 @@ __global__ void k_roots(Fwd f)
     }
     // no tree has two roots, so "as many roots as trees" means one each; later kernels compare the two
     // numbers (batch_rejected) and the root gather reports a mismatch
-    wave_append(&ctl->n_roots, is_root);
+    block_append(&ctl->n_roots, is_root, s_cnt);
+}
+
+// ---- distance from the root (priority scheduling) -----------------------------------------
+// One thread per node walks up the parent links and counts, giving up after DEPTH_CAP steps: the
+// priority rule only asks whether a node is far from its root compared with the rest of the
+// batch, so a distance of "DEPTH_CAP or more" is as good as the exact one, and the longest walk
+// (which sets the duration of the kernel) stays short however deep a tree is.  The parent array
+// of a batch fits the L2, so a step costs a cache hit.
+constexpr int DEPTH_CAP = 128;
+
+__global__ __launch_bounds__(NODE_BLOCK) void k_depth_walk(Fwd f)
+{
+    __shared__ unsigned s_sum[16];
+    if (batch_rejected(f)) return;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned d = 0;
+    if (n < f.n_nodes) {
+        int p = f.parent[n];
+        while (p >= 0 && d < (unsigned)DEPTH_CAP) {
+            d += 1;
+            p = f.parent[p];
+        }
+        f.depth_root[n] = (int)d;
+    }
+    unsigned sum = d;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long total = 0;
+        for (int w = 0; w < (int)((blockDim.x + 63) >> 6); ++w) total += s_sum[w];
+        if (total) atomicAdd(&f.ctl->depth_sum.v, total);
+    }
+}
+
+// A node is critical when at least this many dependent steps are still above it: 32, or four times the
+// batch's mean if that is more (then nothing is critical in a batch whose mean exceeds DEPTH_CAP / 4).
+__device__ inline int critical_threshold(const Fwd &f)
+{
+    const unsigned long long mean4 = 4ull * f.ctl->depth_sum.v / (unsigned long long)f.n_nodes;
+    return mean4 > 32ull ? (mean4 > 0x7fffffffull ? 0x7fffffff : (int)mean4) : 32;
+}
+
+// Rewrites the first n_seed records of the ready queue (the internal nodes over two leaves) with the
+// critical ones at the front, the others filled in from the back.
+__global__ __launch_bounds__(NODE_BLOCK) void k_seed_place(Fwd f)
+{
+    __shared__ int s_cnt[APPEND_SCRATCH];
+    if (batch_rejected(f)) return;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    Ctl *ctl = f.ctl;
+    const int thr = critical_threshold(f);
+    bool seed = false, crit = false;
+    int l = -1, r = -1;
+    if (n < f.n_nodes) {
+        l = f.left[n];
+        r = f.right[n];
+        seed = l >= 0 && f.pending[n] == 0;
+        crit = seed && f.depth_root[n] >= thr;
+    }
+    const int front = block_append(&ctl->seed_front.v, crit, s_cnt);
+    const int back = block_append(&ctl->seed_back.v, seed && !crit, s_cnt);
+    const int slot = crit ? front : ctl->n_seed - 1 - back;
+    if (seed && slot >= 0 && slot < f.n_int) qrec_store<false>(&f.q_rec[slot], n, l, r);
 }
 
 // Heights by climbing: one thread per leaf walks towards the root; at every internal node the

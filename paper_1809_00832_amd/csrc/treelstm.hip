@@ -293,7 +293,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 11 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
+    const size_t bytes = n4 * 12 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
     if (ctx->spw > 0 && ctx->cfg.precision == TL_BF16_IN) {
@@ -323,6 +323,7 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->level_fill = (int32_t *)take(n4);
     f->level_nodes = (int32_t *)take(n4);
     f->q_rec = (QRec *)take(2 * n4);       // n_int <= N / 2 records of 16 bytes
+    f->depth_root = (int32_t *)take(n4);
     f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
     f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
@@ -541,7 +542,7 @@ int tl_create(const tl_config *cfg, tl_ctx **out)
     if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN && cfg->cell != TL_RNTN) return TL_EINVAL;
     if (cfg->cell == TL_RNTN && (!cfg->v || cfg->hidden > 128 || cfg->precision != TL_F32)) return TL_EINVAL;
     if (cfg->precision != TL_F32 && cfg->precision != TL_BF16_IN) return TL_EINVAL;
-    if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_LEVEL_HOST) return TL_EINVAL;
+    if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_READY_PRIORITY) return TL_EINVAL;
     if (cfg->vocab < 1 || cfg->embed_dim < 1 || cfg->hidden < 1 || cfg->spin_limit < 0) return TL_EINVAL;
     if (cfg->hidden > (1 << 14) || cfg->embed_dim > (1 << 16)) return TL_EINVAL;
     if (!cfg->emb || !cfg->u || !cfg->b) return TL_EINVAL;
@@ -613,10 +614,13 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
 
     // heights and per-height node lists: for the host-driven scheduler, and as the check for cycles
     const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;
+    const bool ready_sched = cfg.scheduler == TL_SCHED_READY || cfg.scheduler == TL_SCHED_READY_PRIORITY;
+    f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
     const bool prof = ctx->profiling != 0;
     const int nb_nodes = (n_nodes + 1 + 255) / 256;
+    const int nb_big = (n_nodes + 1 + NODE_BLOCK - 1) / NODE_BLOCK;
 
     ctx->last = f;
     ctx->last_stream = st;
@@ -631,13 +635,17 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     }
     // ---- structure pass ----------------------------------------------------------------
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
-    hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
-    hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_scatter, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
+    hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     if (need_levels) {
         hipLaunchKernelGGL(k_climb, dim3((f.n_leaf + 255) / 256), dim3(256), 0, st, f);
         hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
         hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
         hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
+    }
+    if (f.priority && f.n_int > 0) {
+        hipLaunchKernelGGL(k_depth_walk, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
+        hipLaunchKernelGGL(k_seed_place, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     }
     TL_HIP(hipGetLastError());
     if (prof) TL_HIP(hipEventRecord(ev[1], st));
@@ -658,7 +666,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
 
     // ---- internal nodes ------------------------------------------------------------------
     if (f.n_int > 0) {
-        if (cfg.scheduler == TL_SCHED_READY) {
+        if (ready_sched) {
             const int grid_r = f.n_gangs * (f.gang_size + 1);
             hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_r), dim3(WG_THREADS),
                                spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
@@ -789,10 +797,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     ctx->last_stream = st;
     ctx->ran = true;
     const int nb_nodes = (n_nodes + 1 + 255) / 256;
+    const int nb_big = (n_nodes + 1 + NODE_BLOCK - 1) / NODE_BLOCK;
     // structure pass with heights and per-height lists (as for the host-driven level scheduler)
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, 1);
-    hipLaunchKernelGGL(k_scatter, dim3(nb_nodes), dim3(256), 0, st, f);
-    hipLaunchKernelGGL(k_roots, dim3(nb_nodes), dim3(256), 0, st, f);
+    hipLaunchKernelGGL(k_scatter, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
+    hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     hipLaunchKernelGGL(k_climb, dim3((n_leaf + 255) / 256), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
     hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);

@@ -321,6 +321,16 @@ def workload(name: str) -> Workload:
     if name == "stress":
         tr = make_trees(4, [1024] * 64, ["chain", "balanced"] * 32, 50000)
         return Workload(name, tr, make_treelstm_params(4, 50000, 256, 256, "xavier"))
+    if name == "mixed":
+        # a few very deep trees in a batch of much shallow work (the case for critical-path-first scheduling):
+        # 8 192 sentence trees followed by 8 left-branching chains of 1 024 leaves
+        counts = list(Stream(5, "leaves").integers(5, 50, 8192)) + [1024] * 8
+        tr = make_trees(5, counts, ["random"] * 8192 + ["chain"] * 8, 20000)
+        return Workload(name, tr, make_treelstm_params(5, 20000, 256, 256, "xavier"))
+    if name == "mixed_small":
+        counts = list(Stream(6, "leaves").integers(5, 50, 512)) + [256] * 4
+        tr = make_trees(6, counts, ["random"] * 512 + ["chain"] * 4, 1000)
+        return Workload(name, tr, make_treelstm_params(6, 1000, 48, 64, "xavier"))
     raise ValueError(name)
 
 

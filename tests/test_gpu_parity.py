@@ -11,7 +11,7 @@ from paper_1809_00832_amd.synth import CELL_TREELSTM
 
 pytestmark = pytest.mark.gpu
 
-SCHEDULERS = ["level_host", "level_device", "ready"]
+SCHEDULERS = ["level_host", "level_device", "ready", "ready_priority"]
 ATOL, RTOL = 1e-4, 1e-3
 
 
@@ -86,10 +86,48 @@ def test_stress_shapes_sampled_trees(sched):
         assert np.isfinite(got["h"]).all() and np.isfinite(got["c"]).all()
         stats = binding.tl_last_stats(net.ctx)
         say("   ", stats)
-        if sched != "ready":
+        if not sched.startswith("ready"):
             assert stats["n_levels"] == 1024
     finally:
         net.close()
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_critical_path_first_on_a_mixed_batch(precision):
+    """A few deep chains at the end of a batch of shallow trees: the priority variant of the ready scheduler moves
+    the chains' first nodes to the front of the queue and hands each chain back to one gang step by step.  Same
+    numbers as every other scheduler, bit for bit; chains and a sample of the shallow trees against the checker."""
+    say("case mixed batch", precision)
+    w = synth.workload("mixed_small")
+    prec = binding.TL_F32 if precision == "f32" else binding.TL_BF16_IN
+    outs = {}
+    for sched in ("ready_priority", "level_device", "ready"):
+        net = binding.TreeNet(w.params, scheduler=sched, precision=prec)
+        try:
+            outs[sched] = net.run(w.trees)
+            if sched == "ready_priority":
+                for _ in range(5):                       # tile composition differs from run to run, the bits do not
+                    net.batch["h"].fill_(float("nan"))
+                    net.forward()
+                    assert binding.tl_status(net.ctx) == 0
+                    assert np.array_equal(net.batch["h"].cpu().numpy(), outs[sched]["h"])
+        finally:
+            net.close()
+    for sched in ("level_device", "ready"):
+        assert np.array_equal(outs[sched]["h"], outs["ready_priority"]["h"]), sched
+        assert np.array_equal(outs[sched]["c"], outs["ready_priority"]["c"]), sched
+    B = w.trees.n_trees
+    pick = [B - 1, B - 3, 0, 17, 200, 511]
+    sub, orig = synth.subset(w.trees, pick)
+    p = w.params
+    if precision == "bf16":          # the checker takes weights that are already bf16-representable
+        p = synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, oracle.to_bf16(p.emb), oracle.to_bf16(p.w_leaf), p.b_leaf,
+                         oracle.to_bf16(p.u), p.b, None)
+    ref = oracle.forward_params(p, sub, round_bf16=precision == "bf16", n_threads=4)
+    got = outs["ready_priority"]
+    tol = dict(atol=1e-4, rtol=1e-3) if precision == "f32" else dict(atol=2e-2, rtol=2e-2)
+    assert np.allclose(got["h"][orig], ref["h"], **tol) and np.allclose(got["c"][orig], ref["c"], **tol)
+    assert np.allclose(got["h_root"][pick], ref["h_root"], **tol)
 
 
 @pytest.mark.parametrize("sched", SCHEDULERS)
