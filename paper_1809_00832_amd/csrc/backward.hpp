@@ -63,19 +63,26 @@ __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm
             }
         }
     } else {
-        if (col >= f.out_cols) return;
+        // operand gradient: the NG blocks of output columns of this column group start at g * (out_cols / NG)
+        constexpr bool INNER = EPI == EPI_BWD_INNER_OPERAND || EPI == EPI_BWD_INNER_OPERAND4;
+        const int block = f.out_cols / NG;
+        if (col >= block) return;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = rb * 16 + (lane >> 4) * 4 + v;
             if (row >= count) continue;
             const int node = sm.node[row];
             if (node < 0) continue;
-            if constexpr (EPI == EPI_BWD_INNER_OPERAND) {
-                const int child = col < H ? f.left[node] : f.right[node];
-                float *p = f.dh + (size_t)child * H + (col < H ? col : col - H);
-                *p += acc[0][v];
-            } else {
-                f.d_x[(size_t)node * f.E + col] = acc[0][v];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const int oc = g * block + col;
+                if constexpr (INNER) {
+                    const int child = oc < H ? f.left[node] : f.right[node];
+                    float *p = f.dh + (size_t)child * H + (oc < H ? oc : oc - H);
+                    *p += acc[g][v];
+                } else {
+                    f.d_x[(size_t)node * f.E + oc] = acc[g][v];
+                }
             }
         }
     }
@@ -168,7 +175,7 @@ constexpr int WG_TILE = 64, WG_Q = 16, WG_LD = WG_TILE + 4;
 template <int SEG, bool VEC4>
 __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__restrict__ list, int n_rows,
                                                      const float *__restrict__ table, int L, const float *__restrict__ dg,
-                                                     int n_cols, float *__restrict__ out)
+                                                     int n_cols, float *__restrict__ out, float *__restrict__ bias_out)
 {
     __shared__ __align__(16) float as[WG_Q][WG_LD];
     __shared__ __align__(16) float bs[WG_Q][WG_LD];
@@ -186,6 +193,9 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
         for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
     const int lq = tid >> 4, lk = (tid & 15) * 4;             // this thread stages 4 consecutive columns of row lq
     float ra[4], rb[4];
+    // the workgroups of the first row of output tiles also sum the columns of dg they pass over (bias gradient)
+    const bool with_bias = bias_out != nullptr && blockIdx.x == 0;
+    float bsum[4] = {0.f, 0.f, 0.f, 0.f};
     auto request = [&](int q0) {                              // operands of nodes q0 .. q0 + 15 into registers
         const int q = q0 + lq;
         int s0 = 0, s1 = 0;
@@ -216,6 +226,10 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
     for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
         *reinterpret_cast<floatx4 *>(&as[lq][lk]) = floatx4{ra[0], ra[1], ra[2], ra[3]};
         *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{rb[0], rb[1], rb[2], rb[3]};
+        if (with_bias) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bsum[e] += rb[e];
+        }
         __syncthreads();
         if (q0 + WG_Q < q_hi) request(q0 + WG_Q);
 #pragma unroll
@@ -244,18 +258,29 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
                 const int k = k0 + wr + ta * 16 + (lane >> 4) * 4 + v, j = j0 + wc + tb * 16 + (lane & 15);
                 if (k < K_out && j < n_cols) atomicAdd(&out[(size_t)k * n_cols + j], acc[ta][tb][v]);
             }
+    if (with_bias) {                                          // uniform per workgroup; the loop ended with a barrier
+        *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{bsum[0], bsum[1], bsum[2], bsum[3]};
+        __syncthreads();
+        if (tid < WG_TILE && j0 + tid < n_cols) {
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < WG_Q; ++q) t += bs[q][tid];
+            atomicAdd(&bias_out[j0 + tid], t);
+        }
+    }
 }
 
-// out[j] = sum_q dg[q][j]: blockIdx.x covers 64 columns, blockIdx.y a slice of the rows; `out` is zero beforehand.
-__global__ void k_column_sums(const float *__restrict__ dg, int n_rows, int n_cols, float *__restrict__ out)
+// Zeroes up to six arrays in one launch (outputs and workspace of the backward pass).
+struct ZeroList {
+    float *p[6];
+    size_t n[6];
+};
+__global__ void k_zero_many(ZeroList z)
 {
-    const int j = blockIdx.x * 64 + threadIdx.x;
-    if (j >= n_cols) return;
-    const int per = (n_rows + gridDim.y - 1) / gridDim.y;
-    const int lo = blockIdx.y * per, hi = min(n_rows, lo + per);
-    float s = 0.f;
-    for (int q = lo; q < hi; ++q) s += dg[(size_t)q * n_cols + j];
-    if (hi > lo) atomicAdd(&out[j], s);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+#pragma unroll
+    for (int a = 0; a < 6; ++a)
+        for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < z.n[a]; e += stride) z.p[a][e] = 0.f;
 }
 
 }  // namespace tl

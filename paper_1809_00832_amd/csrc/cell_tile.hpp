@@ -28,8 +28,19 @@ enum Epi {
     // recomputed), and the gradient sent to the operand rows (gate gradients times transposed weights)
     EPI_BWD_INNER_GATES = 4, EPI_BWD_INNER_OPERAND = 5, EPI_BWD_LEAF_GATES = 6, EPI_BWD_LEAF_OPERAND = 7,
     // top-down generation (topdown.hpp): the child on one side of a node from the node's own state
-    EPI_TD_CHILD = 8
+    EPI_TD_CHILD = 8,
+    // the two operand-gradient contractions with four blocks of output columns per column group instead of
+    // one (output widths that are multiples of 4): every gathered row is reused four times as often
+    EPI_BWD_INNER_OPERAND4 = 9, EPI_BWD_LEAF_OPERAND4 = 10
 };
+constexpr bool epi_is_backward(int epi)
+{
+    return (epi >= EPI_BWD_INNER_GATES && epi <= EPI_BWD_LEAF_OPERAND) || epi == EPI_BWD_INNER_OPERAND4 || epi == EPI_BWD_LEAF_OPERAND4;
+}
+constexpr bool epi_is_operand_gradient(int epi)
+{
+    return epi == EPI_BWD_INNER_OPERAND || epi == EPI_BWD_LEAF_OPERAND || epi == EPI_BWD_INNER_OPERAND4 || epi == EPI_BWD_LEAF_OPERAND4;
+}
 
 template <int EPI> struct EpiTraits;
 template <> struct EpiTraits<EPI_LSTM_LEAF>  { static constexpr int NG = 3, SEG = 1; };
@@ -41,6 +52,8 @@ template <> struct EpiTraits<EPI_BWD_INNER_OPERAND> { static constexpr int NG = 
 template <> struct EpiTraits<EPI_BWD_LEAF_GATES>    { static constexpr int NG = 3, SEG = 1; };
 template <> struct EpiTraits<EPI_BWD_LEAF_OPERAND>  { static constexpr int NG = 1, SEG = 1; };
 template <> struct EpiTraits<EPI_TD_CHILD>          { static constexpr int NG = 4, SEG = 1; };
+template <> struct EpiTraits<EPI_BWD_INNER_OPERAND4> { static constexpr int NG = 4, SEG = 1; };
+template <> struct EpiTraits<EPI_BWD_LEAF_OPERAND4>  { static constexpr int NG = 4, SEG = 1; };
 
 // LDS carve-up (dynamic shared memory, 16-byte aligned).
 struct TileSmem {
@@ -113,7 +126,7 @@ __device__ inline void tile_set_rows(Smem &sm, const Fwd &f, int row, int node, 
     if (node >= 0) {
         if (EPI == EPI_LSTM_LEAF || EPI == EPI_BWD_LEAF_GATES) {
             s0 = f.word[node];
-        } else if (EPI == EPI_BWD_INNER_OPERAND || EPI == EPI_BWD_LEAF_OPERAND) {
+        } else if (epi_is_operand_gradient(EPI)) {
             s0 = pos;
         } else {
             s0 = f.left[node];
@@ -161,7 +174,7 @@ template <int EPI, bool COH, int NG>
 __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG],
                                      int rb, int count, int cg, int lane)
 {
-    if constexpr (EPI >= EPI_BWD_INNER_GATES && EPI <= EPI_BWD_LEAF_OPERAND) {
+    if constexpr (epi_is_backward(EPI)) {
         bwd_epilogue<EPI, NG>(sm, f, gm, acc, rb, count, cg, lane);
         return;
     }

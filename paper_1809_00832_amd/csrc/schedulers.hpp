@@ -31,7 +31,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int
     if (tid == 0) sm.cmd[3] = f.pos0 + start;               // list position of row 0 (backward kernels)
     __syncthreads();
     constexpr bool LEAF_ROWS = EPI == EPI_LSTM_LEAF || EPI == EPI_BWD_LEAF_GATES;
-    constexpr bool GRAD_ROWS = EPI == EPI_BWD_INNER_OPERAND || EPI == EPI_BWD_LEAF_OPERAND;
+    constexpr bool GRAD_ROWS = epi_is_operand_gradient(EPI);
     const Gemm &gm = LEAF_ROWS ? f.leaf : (GRAD_ROWS ? f.bwd : f.inner);
     const float *table = LEAF_ROWS ? f.emb : (GRAD_ROWS ? f.dg : f.h);
     cell_tile<EPI, VEC4, false, BF16>(sm, f, gm, table, count, cg);

@@ -62,6 +62,7 @@ struct tl_ctx {
     void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr;
     float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr;
     Gemm g_bwd_inner{}, g_bwd_leaf{};
+    int ng_bwd_inner = 1, ng_bwd_leaf = 1;    // blocks of output columns per column group of the operand-gradient contractions
     float *bw = nullptr;              // dh | dc | gate gradients of internal nodes | of leaves
     int bw_nodes = 0;
     bool keep_gates = false;          // tl_set_keep_gates
@@ -110,7 +111,7 @@ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
 typedef void (*fwd_kernel)(Fwd);
 typedef void (*tiles_kernel)(Fwd, const int32_t *, int, LevelPlan);
-typedef void (*wgrad_kernel)(Fwd, const int32_t *, int, const float *, int, const float *, int, float *);
+typedef void (*wgrad_kernel)(Fwd, const int32_t *, int, const float *, int, const float *, int, float *, float *);
 
 // Steps per wave that the weight-stationary cell is instantiated for; 0 = streaming cell.
 const int WS_SIZES[] = {1, 2, 4, 5, 8, 16};
@@ -233,6 +234,8 @@ tiles_kernel backward_kernel(int epi, bool vec4)
     case EPI_BWD_INNER_GATES: return vec4 ? k_tiles_static<EPI_BWD_INNER_GATES, true, false> : k_tiles_static<EPI_BWD_INNER_GATES, false, false>;
     case EPI_BWD_INNER_OPERAND: return vec4 ? k_tiles_static<EPI_BWD_INNER_OPERAND, true, false> : k_tiles_static<EPI_BWD_INNER_OPERAND, false, false>;
     case EPI_BWD_LEAF_GATES: return vec4 ? k_tiles_static<EPI_BWD_LEAF_GATES, true, false> : k_tiles_static<EPI_BWD_LEAF_GATES, false, false>;
+    case EPI_BWD_INNER_OPERAND4: return vec4 ? k_tiles_static<EPI_BWD_INNER_OPERAND4, true, false> : k_tiles_static<EPI_BWD_INNER_OPERAND4, false, false>;
+    case EPI_BWD_LEAF_OPERAND4: return vec4 ? k_tiles_static<EPI_BWD_LEAF_OPERAND4, true, false> : k_tiles_static<EPI_BWD_LEAF_OPERAND4, false, false>;
     default: return vec4 ? k_tiles_static<EPI_BWD_LEAF_OPERAND, true, false> : k_tiles_static<EPI_BWD_LEAF_OPERAND, false, false>;
     }
 }
@@ -420,12 +423,16 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
             TL_HIP(hipMalloc(&zb, n_zb * sizeof(float)));
             TL_HIP(hipMemset(zb, 0, n_zb * sizeof(float)));
             hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->u, t, rows_u, cols_u);
-            rc = pack_gemm(t, zb, 1, 2 * H, 1, 5 * H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner, &ctx->wp_bwd_inner,
-                           &ctx->bp_bwd_inner);
+            // output columns in four blocks per column group where the width allows it (see EPI_BWD_INNER_OPERAND4)
+            ctx->ng_bwd_inner = (2 * H) % 4 == 0 ? 4 : 1;
+            ctx->ng_bwd_leaf = E % 4 == 0 ? 4 : 1;
+            rc = pack_gemm(t, zb, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1, 5 * H, (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, 0, false,
+                           &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner);
             if (rc == TL_OK) {
                 TL_HIP(hipDeviceSynchronize());
                 hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->w_leaf, t, rows_w, cols_w);
-                rc = pack_gemm(t, zb, 1, E, 1, 3 * H, (E + HU - 1) / HU, 0, false, &ctx->g_bwd_leaf, &ctx->wp_bwd_leaf, &ctx->bp_bwd_leaf);
+                rc = pack_gemm(t, zb, ctx->ng_bwd_leaf, E / ctx->ng_bwd_leaf, 1, 3 * H, (E / ctx->ng_bwd_leaf + HU - 1) / HU, 0, false,
+                               &ctx->g_bwd_leaf, &ctx->wp_bwd_leaf, &ctx->bp_bwd_leaf);
             }
             TL_HIP(hipDeviceSynchronize());
             (void)hipFree(t);
@@ -463,8 +470,8 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if ((rc = allow_lds(levels_kernel(cfg->cell, v, 0, bf16))) != TL_OK) return rc;
         for (int epi = 0; epi < 4; ++epi)
             if ((rc = allow_lds(static_kernel(epi, v, bf16))) != TL_OK) return rc;
-        for (int epi = EPI_BWD_INNER_GATES; epi <= EPI_BWD_LEAF_OPERAND; ++epi)
-            if ((rc = allow_lds(backward_kernel(epi, v))) != TL_OK) return rc;
+        for (int epi = EPI_BWD_INNER_GATES; epi <= EPI_BWD_LEAF_OPERAND4; ++epi)
+            if (epi_is_backward(epi) && (rc = allow_lds(backward_kernel(epi, v))) != TL_OK) return rc;
     }
     int occ = 0;
     TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(ready_kernel(cfg->cell, true, 0, bf16)),
@@ -808,10 +815,16 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
     // dh starts as the upstream gradient of every node, dc as zero; d_x rows of internal nodes stay zero
     TL_HIP(hipMemcpyAsync(f.dh, g_h, (size_t)n_nodes * H * sizeof(float), hipMemcpyDeviceToDevice, st));
-    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, f.dc, (size_t)n_nodes * H, 0.f);
-    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_x, (size_t)n_nodes * E, 0.f);
-    hipLaunchKernelGGL(k_fill, dim3(8), dim3(256), 0, st, d_b, (size_t)5 * H, 0.f);
-    hipLaunchKernelGGL(k_fill, dim3(8), dim3(256), 0, st, d_b_leaf, (size_t)3 * H, 0.f);
+    {
+        ZeroList z{};
+        z.p[0] = f.dc;     z.n[0] = (size_t)n_nodes * H;
+        z.p[1] = d_x;      z.n[1] = (size_t)n_nodes * E;
+        z.p[2] = d_b;      z.n[2] = (size_t)5 * H;
+        z.p[3] = d_b_leaf; z.n[3] = (size_t)3 * H;
+        z.p[4] = d_u;      z.n[4] = (size_t)2 * H * 5 * H;
+        z.p[5] = d_w_leaf; z.n[5] = (size_t)E * 3 * H;
+        hipLaunchKernelGGL(k_zero_many, dim3(1024), dim3(256), 0, st, z);
+    }
     TL_HIP(hipGetLastError());
     if ((rc = read_ctl(ctx)) != TL_OK) return rc;
     if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
@@ -846,8 +859,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                                    TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
             g.bwd = ctx->g_bwd_inner;
             g.out_cols = 2 * H;
-            g.n_cg = (2 * H + HU - 1) / HU;
-            hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_OPERAND, vec4), dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
+            g.n_cg = (2 * H / ctx->ng_bwd_inner + HU - 1) / HU;
+            hipLaunchKernelGGL(backward_kernel(ctx->ng_bwd_inner == 4 ? EPI_BWD_INNER_OPERAND4 : EPI_BWD_INNER_OPERAND, vec4),
+                               dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
                                TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
         }
     }
@@ -863,8 +877,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                                TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
         g.bwd = ctx->g_bwd_leaf;
         g.out_cols = E;
-        g.n_cg = (E + HU - 1) / HU;
-        hipLaunchKernelGGL(backward_kernel(EPI_BWD_LEAF_OPERAND, H % 4 == 0), dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
+        g.n_cg = (E / ctx->ng_bwd_leaf + HU - 1) / HU;
+        hipLaunchKernelGGL(backward_kernel(ctx->ng_bwd_leaf == 4 ? EPI_BWD_LEAF_OPERAND4 : EPI_BWD_LEAF_OPERAND, H % 4 == 0),
+                           dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
                            TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
     }
     // weight and bias gradients: contractions over all nodes, the node axis cut into slices so that a few
@@ -875,23 +890,20 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         if (z > max_z) z = max_z;
         return z < 1 ? 1 : z;
     };
-    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_u, (size_t)2 * H * 5 * H, 0.f);
-    hipLaunchKernelGGL(k_fill, dim3(512), dim3(256), 0, st, d_w_leaf, (size_t)E * 3 * H, 0.f);
     if (n_int > 0) {
         const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE, 1);
         const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
         const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<2, true>) : wgrad_kernel(k_weight_grad<2, false>);
         hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
-                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u);
-        hipLaunchKernelGGL(k_column_sums, dim3((5 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_int, n_int, 5 * H, d_b);
+                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u, d_b);
     }
     {
         const dim3 grid((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE, 1);
         const bool v4 = E % 4 == 0 && H % 4 == 0;
         const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<1, true>) : wgrad_kernel(k_weight_grad<1, false>);
         hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_leaf)), dim3(256), 0, st, f,
-                           (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf);
-        hipLaunchKernelGGL(k_column_sums, dim3((3 * H + 63) / 64, 32), dim3(64), 0, st, (const float *)dg_leaf, n_leaf, 3 * H, d_b_leaf);
+                           (const int32_t *)f.leaf_list, n_leaf, (const float *)ctx->emb, E, (const float *)dg_leaf, 3 * H, d_w_leaf,
+                           d_b_leaf);
     }
     TL_HIP(hipGetLastError());
     return TL_OK;
