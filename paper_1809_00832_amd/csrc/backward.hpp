@@ -5,13 +5,15 @@
 //   1. gate gradients: the forward contraction G = [h_l ; h_r] U + b is recomputed with the
 //      streaming cell, and its epilogue turns (dh, dc, c, c_l, c_r, gates) into the gradient of
 //      the five gate pre-activations (a row of 5H values per node, kept by list position) and
-//      sends dc to the children;
+//      sends dc to the children; if the forward kept its gate activations, an elementwise
+//      kernel does the same from those, without the contraction;
 //   2. operand gradient: [dh_l ; dh_r] += dG U^T, the same streaming cell with the rows of dG as
 //      the gathered operand and U^T as the packed weights; its epilogue adds the result to the
 //      children's dh rows (every node has one parent, so plain read-modify-write).
 // Leaves likewise (dG W_x^T gives the gradient of each leaf's embedding row).  The weight
 // gradients dU = sum_n a_n^T dG_n, dW_x = sum_n x_n^T dG_n are two contractions over all nodes at
-// the end (k_weight_grad), the bias gradients column sums of the dG rows.
+// the end (k_weight_grad), which also sums the columns of the dG rows it passes over (bias
+// gradients).
 #pragma once
 
 #include "cell_tile.hpp"
@@ -154,11 +156,6 @@ __global__ void k_transpose(const float *__restrict__ in, float *__restrict__ ou
         const size_t c = e / rows, r = e - c * rows;          // e indexes the output [cols x rows]
         out[e] = in[r * cols + c];
     }
-}
-
-__global__ void k_fill(float *__restrict__ p, size_t n, float v)
-{
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) p[e] = v;
 }
 
 // Weight gradient: out[k][j] += sum_q a_q[k] * dg[q][j] over the n_rows nodes of `list` (dg rows by

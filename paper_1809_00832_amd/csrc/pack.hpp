@@ -85,10 +85,4 @@ __global__ void k_pad_bf16(const float *__restrict__ src, unsigned short *__rest
     }
 }
 
-__global__ void k_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, size_t n)
-{
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x)
-        dst[e] = f32_to_bf16_rne(src[e]);
-}
-
 }  // namespace tl
