@@ -98,11 +98,13 @@ def run_scheduler(w, sched, precision, steps, warmup):
         stages = [binding.tl_stage_ms(net.ctx, back) for back in range(k)]
         binding.tl_set_profiling(net.ctx, False)
         avg = {key: sum(s[key] for s in stages) / k for key in stages[0]}
+        totals = sorted(s["total"] for s in stages)          # one forward each, first to last event on the stream
+        latency = {"median": totals[len(totals) // 2], "min": totals[0], "max": totals[-1], "forwards": k}
         stats = binding.tl_last_stats(net.ctx)
         code = binding.tl_status(net.ctx)
         if code != 0:
             raise binding.TLError(code, "timed forward")
-        return dict(sec=sec, sec_profiled=sec_prof, stage_ms=avg, stats=stats)
+        return dict(sec=sec, sec_profiled=sec_prof, stage_ms=avg, stats=stats, latency_ms=latency)
     finally:
         net.close()
 
@@ -369,6 +371,7 @@ def main():
         "step_algorithmic_gbs": bytes_ / sec / 1e9,
         "stage_ms": main_run["stage_ms"],
         "ms_per_step_with_stage_events": main_run["sec_profiled"] * 1e3,
+        "forward_latency_ms": main_run["latency_ms"],
         "tiles_formed": main_run["stats"]["n_tiles"],
         "roofline": {"bound": "mfma", "kernel": "internal-node kernel (%s scheduler)" % args.scheduler,
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
@@ -393,7 +396,7 @@ def main():
                 continue
             r = run_scheduler(w, sched, precision, args.steps, args.warmup)
             comp[sched] = {"trees_per_sec": t.n_trees / r["sec"], "ms_per_step": r["sec"] * 1e3,
-                           "stage_ms": r["stage_ms"], "n_levels": r["stats"]["n_levels"]}
+                           "stage_ms": r["stage_ms"], "forward_latency_ms": r["latency_ms"], "n_levels": r["stats"]["n_levels"]}
         out["comparison"] = comp
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
