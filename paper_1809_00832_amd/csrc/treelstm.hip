@@ -59,8 +59,9 @@ struct tl_ctx {
     int hs = 0;                       // row stride of the bf16 copy of h
     unsigned short *hb = nullptr;     // bf16 copy of h, cap_nodes rows (bf16 weight-stationary cell only)
     // backward pass (TreeLSTM, fp32): transposed weights packed like the forward ones, workspace
-    void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr;
-    float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr;
+    void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr, *wp_bwd_inner1 = nullptr;
+    float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr, *bp_bwd_inner1 = nullptr;
+    Gemm g_bwd_inner1{};              // U^T once more with one column block per group: more workgroups for heights of few rows
     Gemm g_bwd_inner{}, g_bwd_leaf{};
     int ng_bwd_inner = 1, ng_bwd_leaf = 1;    // blocks of output columns per column group of the operand-gradient contractions
     float *bw = nullptr;              // dh | dc | gate gradients of internal nodes | of leaves
@@ -344,6 +345,8 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->hb);
     (void)hipFree(ctx->embb);
     (void)hipFree(ctx->wp_bwd_inner);
+    (void)hipFree(ctx->wp_bwd_inner1);
+    (void)hipFree(ctx->bp_bwd_inner1);
     (void)hipFree(ctx->wp_bwd_leaf);
     (void)hipFree(ctx->bp_bwd_inner);
     (void)hipFree(ctx->bp_bwd_leaf);
@@ -428,6 +431,9 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
             ctx->ng_bwd_leaf = E % 4 == 0 ? 4 : 1;
             rc = pack_gemm(t, zb, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1, 5 * H, (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, 0, false,
                            &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner);
+            if (rc == TL_OK && ctx->ng_bwd_inner == 4)
+                rc = pack_gemm(t, zb, 1, 2 * H, 1, 5 * H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner1, &ctx->wp_bwd_inner1,
+                               &ctx->bp_bwd_inner1);
             if (rc == TL_OK) {
                 TL_HIP(hipDeviceSynchronize());
                 hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->w_leaf, t, rows_w, cols_w);
@@ -857,10 +863,13 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
             else
                 hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_GATES, vec4), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
                                    TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
-            g.bwd = ctx->g_bwd_inner;
+            // heights of few rows: one column block per group, so that four times as many workgroups share the
+            // long K axis (5H) of the few tiles; otherwise four blocks per group, which reuse each gathered row more
+            const int ng = (ctx->ng_bwd_inner == 4 && rows > 64) ? 4 : 1;
+            g.bwd = (ctx->ng_bwd_inner == 4 && ng == 1) ? ctx->g_bwd_inner1 : ctx->g_bwd_inner;
             g.out_cols = 2 * H;
-            g.n_cg = (2 * H / ctx->ng_bwd_inner + HU - 1) / HU;
-            hipLaunchKernelGGL(backward_kernel(ctx->ng_bwd_inner == 4 ? EPI_BWD_INNER_OPERAND4 : EPI_BWD_INNER_OPERAND, vec4),
+            g.n_cg = (2 * H / ng + HU - 1) / HU;
+            hipLaunchKernelGGL(backward_kernel(ng == 4 ? EPI_BWD_INNER_OPERAND4 : EPI_BWD_INNER_OPERAND, vec4),
                                dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
                                TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
         }
