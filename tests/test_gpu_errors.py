@@ -186,7 +186,7 @@ def test_forward_replayed_from_a_hip_graph(sched):
 
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
 @pytest.mark.parametrize("sched", ["ready", "level_device", "ready_priority"])
-@pytest.mark.parametrize("name,iters", [("throughput", 300), ("sentence", 300), ("stress", 20)])
+@pytest.mark.parametrize("name,iters", [("throughput", 300), ("sentence", 300), ("stress", 20), ("mixed_small", 200)])
 def test_many_forwards_give_the_same_bits(name, iters, sched, precision):
     """Many forwards of one batch through one context: every one ends without error and with exactly the bits of
     the first (tile composition, arrival order at the barriers and queue order differ from run to run).  The state
