@@ -209,15 +209,19 @@ def backward_stage(w, n_classes, reps=10):
             label = torch.randint(0, n_classes, (N,), device="cuda", generator=g, dtype=torch.int32)
             out["head_backward_ms"] = wall(lambda: binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label), 50)
 
-            def train_step():
+            def train_step(lr=0.0):
                 net.forward()
                 hb = binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label)
-                binding.tl_backward(net.ctx, b, hb["g_h"], E)
+                grads = binding.tl_backward(net.ctx, b, hb["g_h"], E)
+                binding.tl_sgd_update(net.ctx, lr, b, grads)           # lr = 0: all the work, parameters unchanged
 
+            grads0 = binding.tl_backward(net.ctx, b, g_h, E)
+            out["sgd_update_ms"] = wall(lambda: binding.tl_sgd_update(net.ctx, 0.0, b, grads0), reps)
             step_ms = wall(train_step, reps)
             out["train_step_ms"] = step_ms
             out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
-            out["train_step_note"] = "forward keeping the gate activations + head backward + tree backward, no parameter update"
+            out["train_step_note"] = ("forward keeping the gate activations + head backward + tree backward + SGD update of "
+                                      "all parameters (embedding rows included) and re-packing of the weights")
         return out
     finally:
         net.close()

@@ -207,6 +207,29 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                 float *d_u, float *d_b, float *d_w_leaf, float *d_b_leaf, float *d_x, void *hip_stream);
 
 /*
+ * One step of plain stochastic gradient descent on the parameters the context holds (the
+ * training runs of Section 6 update the model after every batch; the paper does not print its
+ * optimiser, the plainest one is taken): theta <- theta - lr * gradient for U, b, W_leaf,
+ * b_leaf, and emb[word[n]] <- emb[word[n]] - lr * d_x[n] for every leaf n.  The gradient arrays
+ * are those tl_backward wrote (DEVICE, read-only); left / word / n_nodes are the batch's arrays.
+ * d_x may be NULL: the embedding table then stays as it is.  Afterwards everything derived from
+ * the parameters (packed weights of the forward and backward kernels) is rebuilt; all of it is
+ * enqueued on hip_stream and nothing is allocated.  Dense parameters change exactly as the
+ * formula says in fp32 (product rounded, then difference); embedding rows shared by several
+ * leaves are updated with atomics.  Calls on one context must be ordered with its forwards
+ * and backwards (same stream, or synchronised).  TreeLSTM / TL_F32 only, else TL_EINVAL.
+ */
+int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const int32_t *word, const float *d_u,
+                  const float *d_b, const float *d_w_leaf, const float *d_b_leaf, const float *d_x, void *hip_stream);
+
+/*
+ * Copies the context's current parameters to the caller's DEVICE buffers (any of them may be
+ * NULL): u [2H x 5H], b [5H], w_leaf [E x 3H], b_leaf [3H], emb [vocab x E], fp32, the layouts
+ * tl_create takes.  Asynchronous on hip_stream.  TreeLSTM / TL_F32 only, else TL_EINVAL.
+ */
+int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream);
+
+/*
  * Training mode of tl_forward (Section 4.2.2: the backward pass of a recursive call looks up the
  * forward values of the same call instance).  With on != 0, every later tl_forward of a TreeLSTM /
  * TL_F32 context also keeps the gate activations of every node (5H floats per node, in a

@@ -21,8 +21,8 @@ TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST,
               "ready_priority": TL_SCHED_READY_PRIORITY}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward", "tl_set_keep_gates", "tl_classify",
-           "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
+EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward",
+           "tl_set_keep_gates", "tl_sgd_update", "tl_get_params", "tl_classify", "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
 
 
 class tl_config(ctypes.Structure):
@@ -60,6 +60,10 @@ def lib():
         L.tl_strerror.restype = ctypes.c_char_p
         L.tl_backward.restype = ci
         L.tl_backward.argtypes = [vp, ci, ci] + [vp] * 13
+        L.tl_sgd_update.restype = ci
+        L.tl_sgd_update.argtypes = [vp, ctypes.c_float, ci] + [vp] * 8
+        L.tl_get_params.restype = ci
+        L.tl_get_params.argtypes = [vp] * 7
         L.tl_set_keep_gates.restype = ci
         L.tl_set_keep_gates.argtypes = [vp, ci]
         L.tl_td_create.restype = ci
@@ -154,6 +158,29 @@ def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
                              batch["right"].data_ptr(), batch["word"].data_ptr(), batch["h"].data_ptr(),
                              batch["c"].data_ptr(), g_h.data_ptr(), out["d_u"].data_ptr(), out["d_b"].data_ptr(),
                              out["d_w_leaf"].data_ptr(), out["d_b_leaf"].data_ptr(), out["d_x"].data_ptr(), st), "tl_backward")
+    return out
+
+
+def tl_sgd_update(ctx, lr, batch, grads, with_embedding=True, stream=None) -> None:
+    """theta -= lr * gradient for the parameters the context holds; `grads` is what tl_backward returned, `batch`
+    the dict TreeNet.load returned."""
+    import torch
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_sgd_update(ctx, float(lr), batch["N"], batch["left"].data_ptr(), batch["word"].data_ptr(),
+                               grads["d_u"].data_ptr(), grads["d_b"].data_ptr(), grads["d_w_leaf"].data_ptr(),
+                               grads["d_b_leaf"].data_ptr(), grads["d_x"].data_ptr() if with_embedding else None, st),
+           "tl_sgd_update")
+
+
+def tl_get_params(ctx, vocab, embed_dim, hidden, stream=None):
+    """The context's current parameters as new CUDA tensors: dict(u, b, w_leaf, b_leaf, emb)."""
+    import torch
+    H, E = int(hidden), int(embed_dim)
+    new = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
+    out = {"u": new(2 * H, 5 * H), "b": new(5 * H), "w_leaf": new(E, 3 * H), "b_leaf": new(3 * H), "emb": new(int(vocab), E)}
+    st = (stream or torch.cuda.current_stream()).cuda_stream
+    _check(lib().tl_get_params(ctx, out["u"].data_ptr(), out["b"].data_ptr(), out["w_leaf"].data_ptr(), out["b_leaf"].data_ptr(),
+                               out["emb"].data_ptr(), st), "tl_get_params")
     return out
 
 

@@ -267,6 +267,40 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
     }
 }
 
+// Plain stochastic gradient descent, theta <- theta - lr * g (the product rounded, then the difference: the two
+// roundings of the definition written as two operations), for up to four dense arrays in one launch.
+struct SgdList {
+    float *theta[4];
+    const float *grad[4];
+    size_t n[4];
+};
+__global__ void k_sgd_dense(SgdList z, float lr)
+{
+#pragma clang fp contract(off)          // two roundings, as the definition says: no fused multiply-add here
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+        for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < z.n[a]; e += stride) {
+            const float step = lr * z.grad[a][e];
+            z.theta[a][e] = z.theta[a][e] - step;
+        }
+}
+
+// The embedding table: row word[n] -= lr * d_x[n] for every leaf n.  Several leaves may share a word, so the
+// rows are updated with atomics (the order of those additions is not fixed).
+__global__ void k_sgd_embedding(float *__restrict__ emb, const float *__restrict__ d_x, const int32_t *__restrict__ left,
+                                const int32_t *__restrict__ word, int n_nodes, int E, int vocab, float lr)
+{
+    const size_t total = (size_t)n_nodes * E;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const int n = (int)(e / E), j = (int)(e - (size_t)n * E);
+        if (left[n] >= 0) continue;
+        const int w = word[n];
+        if (w < 0 || w >= vocab) continue;
+        atomicAdd(&emb[(size_t)w * E + j], -(lr * d_x[e]));
+    }
+}
+
 // Zeroes up to six arrays in one launch (outputs and workspace of the backward pass).
 struct ZeroList {
     float *p[6];

@@ -66,6 +66,9 @@ struct tl_ctx {
     int ng_bwd_inner = 1, ng_bwd_leaf = 1;    // blocks of output columns per column group of the operand-gradient contractions
     float *bw = nullptr;              // dh | dc | gate gradients of internal nodes | of leaves
     int bw_nodes = 0;
+    float *m_u = nullptr, *m_b = nullptr, *m_w_leaf = nullptr, *m_b_leaf = nullptr;   // fp32 TreeLSTM: the parameters themselves
+    float *t_scratch = nullptr, *zero_bias = nullptr;
+    int ws_steps16 = 0;
     bool keep_gates = false;          // tl_set_keep_gates
     float *gates = nullptr;           // [gates_cap x 5H] gate activations of the last forward that kept them
     int gates_cap = 0;
@@ -253,8 +256,9 @@ template <typename K> int allow_lds(K kernel, size_t bytes = TILE_SMEM_BYTES)
 }
 
 // Packs one weight matrix [SEG*L x NG*H] and its bias; fills the Gemm descriptor.
+// If *wp_out / *bp_out are set they are packed over (the sizes depend only on the shapes), else allocated.
 int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int n_cg, int min_steps, bool bf16, Gemm *g,
-              void **wp_out, float **bp_out)
+              void **wp_out, float **bp_out, hipStream_t st = nullptr)
 {
     // bf16: segments start at multiples of 8 elements (16 bytes of a bf16 row) and the K axis is a
     // multiple of 4 k-steps of 32, so that it splits into four quarters of whole k-steps
@@ -263,23 +267,52 @@ int pack_gemm(const float *w, const float *b, int NG, int H, int SEG, int L, int
     if (Kp < min_steps * STEP_K) Kp = min_steps * STEP_K;   // the weight-stationary cell wants exactly 4 * SPW k-steps
     const int n_steps = Kp / STEP_K;
     const size_t n_w = (size_t)n_cg * n_steps * NG * 64 * 4;
-    void *wp = nullptr;
-    float *bp = nullptr;
-    TL_HIP(hipMalloc(&wp, n_w * (bf16 ? sizeof(unsigned short) : sizeof(float))));
-    TL_HIP(hipMalloc(&bp, (size_t)n_cg * NG * HU * sizeof(float)));
+    void *wp = *wp_out;
+    float *bp = *bp_out;
+    if (!wp) TL_HIP(hipMalloc(&wp, n_w * (bf16 ? sizeof(unsigned short) : sizeof(float))));
+    *wp_out = wp;
+    if (!bp) TL_HIP(hipMalloc(&bp, (size_t)n_cg * NG * HU * sizeof(float)));
+    *bp_out = bp;
     if (bf16)
-        hipLaunchKernelGGL(k_pack_bf16, dim3(1024), dim3(256), 0, 0, w, (unsigned short *)wp, NG, H, SEG, L, Lp, n_steps / 2, n_cg);
+        hipLaunchKernelGGL(k_pack_bf16, dim3(1024), dim3(256), 0, st, w, (unsigned short *)wp, NG, H, SEG, L, Lp, n_steps / 2, n_cg);
     else
-        hipLaunchKernelGGL(k_pack_f32, dim3(1024), dim3(256), 0, 0, w, (float *)wp, NG, H, SEG, L, Lp, n_steps, n_cg);
-    hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, 0, b, bp, NG, H, n_cg);
+        hipLaunchKernelGGL(k_pack_f32, dim3(1024), dim3(256), 0, st, w, (float *)wp, NG, H, SEG, L, Lp, n_steps, n_cg);
+    hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, st, b, bp, NG, H, n_cg);
     TL_HIP(hipGetLastError());
     g->wp = wp;
     g->bp = bp;
     g->L = L;
     g->Lp = Lp;
     g->n_chunks = Kp / KC;
-    *wp_out = wp;
-    *bp_out = bp;
+    return TL_OK;
+}
+
+// (Re-)packs everything that is derived from the fp32 TreeLSTM parameters kept in the context: forward weights of
+// leaves and internal nodes, and the transposed weights of the backward pass.  Enqueued on st.
+int pack_treelstm_f32(tl_ctx *ctx, hipStream_t st)
+{
+    const int H = ctx->cfg.hidden, E = ctx->cfg.embed_dim;
+    int rc = pack_gemm(ctx->m_w_leaf, ctx->m_b_leaf, 3, H, 1, E, ctx->n_cg, 4 * ctx->spw_leaf, false, &ctx->g_leaf, &ctx->wp_leaf,
+                       &ctx->bp_leaf, st);
+    if (rc != TL_OK) return rc;
+    rc = pack_gemm(ctx->m_u, ctx->m_b, 5, H, 2, H, ctx->n_cg, ctx->ws_steps16, false, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner, st);
+    if (rc != TL_OK) return rc;
+    // backward pass: U^T [5H x 2H] and W_leaf^T [3H x E] as contractions with a zero bias
+    float *t = ctx->t_scratch, *zb = ctx->zero_bias;
+    hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, st, (const float *)ctx->m_u, t, 2 * H, 5 * H);
+    rc = pack_gemm(t, zb, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1, 5 * H, (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, 0, false,
+                   &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner, st);
+    if (rc != TL_OK) return rc;
+    if (ctx->ng_bwd_inner == 4) {
+        rc = pack_gemm(t, zb, 1, 2 * H, 1, 5 * H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner1, &ctx->wp_bwd_inner1,
+                       &ctx->bp_bwd_inner1, st);
+        if (rc != TL_OK) return rc;
+    }
+    hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, st, (const float *)ctx->m_w_leaf, t, E, 3 * H);   // in stream order after the packs above
+    rc = pack_gemm(t, zb, ctx->ng_bwd_leaf, E / ctx->ng_bwd_leaf, 1, 3 * H, (E / ctx->ng_bwd_leaf + HU - 1) / HU, 0, false,
+                   &ctx->g_bwd_leaf, &ctx->wp_bwd_leaf, &ctx->bp_bwd_leaf, st);
+    if (rc != TL_OK) return rc;
+    TL_HIP(hipGetLastError());
     return TL_OK;
 }
 
@@ -352,6 +385,12 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->bp_bwd_leaf);
     (void)hipFree(ctx->bw);
     (void)hipFree(ctx->gates);
+    (void)hipFree(ctx->m_u);
+    (void)hipFree(ctx->m_b);
+    (void)hipFree(ctx->m_w_leaf);
+    (void)hipFree(ctx->m_b_leaf);
+    (void)hipFree(ctx->t_scratch);
+    (void)hipFree(ctx->zero_bias);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -412,37 +451,33 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     }
     int rc;
     if (cfg->cell == TL_TREELSTM) {
-        rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, (bf16 ? 8 : 4) * ctx->spw_leaf, bf16, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
-        if (rc != TL_OK) return rc;
-        rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
-        if (rc != TL_OK) return rc;
         if (!bf16) {
-            // backward pass: U^T [5H x 2H] and W_leaf^T [3H x E] packed as single-gate contractions, zero bias
-            const int rows_u = 2 * H, cols_u = 5 * H, rows_w = E, cols_w = 3 * H;
-            const size_t n_t = (size_t)(rows_u * (size_t)cols_u > (size_t)rows_w * cols_w ? (size_t)rows_u * cols_u : (size_t)rows_w * cols_w);
-            float *t = nullptr, *zb = nullptr;
-            TL_HIP(hipMalloc(&t, n_t * sizeof(float)));
+            // fp32 TreeLSTM contexts keep the parameters as given (tl_backward / tl_sgd_update / tl_get_params), a
+            // scratch matrix for the transposes and a zero bias for the operand-gradient contractions
+            const size_t n_u = (size_t)2 * H * 5 * H, n_w = (size_t)E * 3 * H;
+            TL_HIP(hipMalloc(&ctx->m_u, n_u * sizeof(float)));
+            TL_HIP(hipMalloc(&ctx->m_b, (size_t)5 * H * sizeof(float)));
+            TL_HIP(hipMalloc(&ctx->m_w_leaf, n_w * sizeof(float)));
+            TL_HIP(hipMalloc(&ctx->m_b_leaf, (size_t)3 * H * sizeof(float)));
+            TL_HIP(hipMemcpy(ctx->m_u, cfg->u, n_u * sizeof(float), hipMemcpyDeviceToDevice));
+            TL_HIP(hipMemcpy(ctx->m_b, cfg->b, (size_t)5 * H * sizeof(float), hipMemcpyDeviceToDevice));
+            TL_HIP(hipMemcpy(ctx->m_w_leaf, cfg->w_leaf, n_w * sizeof(float), hipMemcpyDeviceToDevice));
+            TL_HIP(hipMemcpy(ctx->m_b_leaf, cfg->b_leaf, (size_t)3 * H * sizeof(float), hipMemcpyDeviceToDevice));
+            TL_HIP(hipMalloc(&ctx->t_scratch, (n_u > n_w ? n_u : n_w) * sizeof(float)));
             const size_t n_zb = (size_t)(2 * H > E ? 2 * H : E) + HU;
-            TL_HIP(hipMalloc(&zb, n_zb * sizeof(float)));
-            TL_HIP(hipMemset(zb, 0, n_zb * sizeof(float)));
-            hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->u, t, rows_u, cols_u);
+            TL_HIP(hipMalloc(&ctx->zero_bias, n_zb * sizeof(float)));
+            TL_HIP(hipMemset(ctx->zero_bias, 0, n_zb * sizeof(float)));
             // output columns in four blocks per column group where the width allows it (see EPI_BWD_INNER_OPERAND4)
             ctx->ng_bwd_inner = (2 * H) % 4 == 0 ? 4 : 1;
             ctx->ng_bwd_leaf = E % 4 == 0 ? 4 : 1;
-            rc = pack_gemm(t, zb, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1, 5 * H, (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, 0, false,
-                           &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner);
-            if (rc == TL_OK && ctx->ng_bwd_inner == 4)
-                rc = pack_gemm(t, zb, 1, 2 * H, 1, 5 * H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner1, &ctx->wp_bwd_inner1,
-                               &ctx->bp_bwd_inner1);
-            if (rc == TL_OK) {
-                TL_HIP(hipDeviceSynchronize());
-                hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, 0, cfg->w_leaf, t, rows_w, cols_w);
-                rc = pack_gemm(t, zb, ctx->ng_bwd_leaf, E / ctx->ng_bwd_leaf, 1, 3 * H, (E / ctx->ng_bwd_leaf + HU - 1) / HU, 0, false,
-                               &ctx->g_bwd_leaf, &ctx->wp_bwd_leaf, &ctx->bp_bwd_leaf);
-            }
+            ctx->ws_steps16 = ws_steps16;
+            rc = pack_treelstm_f32(ctx, nullptr);
             TL_HIP(hipDeviceSynchronize());
-            (void)hipFree(t);
-            (void)hipFree(zb);
+            if (rc != TL_OK) return rc;
+        } else {
+            rc = pack_gemm(cfg->w_leaf, cfg->b_leaf, 3, H, 1, E, ctx->n_cg, 8 * ctx->spw_leaf, true, &ctx->g_leaf, &ctx->wp_leaf, &ctx->bp_leaf);
+            if (rc != TL_OK) return rc;
+            rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, true, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
             if (rc != TL_OK) return rc;
         }
     } else if (cfg->cell == TL_TREERNN) {
@@ -915,6 +950,42 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                            d_b_leaf);
     }
     TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
+int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const int32_t *word, const float *d_u,
+                  const float *d_b, const float *d_w_leaf, const float *d_b_leaf, const float *d_x, void *hip_stream)
+{
+    if (!ctx || !d_u || !d_b || !d_w_leaf || !d_b_leaf) return TL_EINVAL;
+    const tl_config &cfg = ctx->cfg;
+    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    if (d_x && (!left || !word || n_nodes < 1)) return TL_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int H = cfg.hidden, E = cfg.embed_dim;
+    SgdList z{};
+    z.theta[0] = ctx->m_u;      z.grad[0] = d_u;      z.n[0] = (size_t)2 * H * 5 * H;
+    z.theta[1] = ctx->m_b;      z.grad[1] = d_b;      z.n[1] = (size_t)5 * H;
+    z.theta[2] = ctx->m_w_leaf; z.grad[2] = d_w_leaf; z.n[2] = (size_t)E * 3 * H;
+    z.theta[3] = ctx->m_b_leaf; z.grad[3] = d_b_leaf; z.n[3] = (size_t)3 * H;
+    hipLaunchKernelGGL(k_sgd_dense, dim3(1024), dim3(256), 0, st, z, lr);
+    if (d_x) hipLaunchKernelGGL(k_sgd_embedding, dim3(1024), dim3(256), 0, st, ctx->emb, d_x, left, word, n_nodes, E, cfg.vocab, lr);
+    TL_HIP(hipGetLastError());
+    ctx->gates_nodes = 0;             // what a forward kept belongs to the old parameters
+    return pack_treelstm_f32(ctx, st);
+}
+
+int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream)
+{
+    if (!ctx) return TL_EINVAL;
+    const tl_config &cfg = ctx->cfg;
+    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t H = cfg.hidden, E = cfg.embed_dim;
+    if (u) TL_HIP(hipMemcpyAsync(u, ctx->m_u, 2 * H * 5 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (b) TL_HIP(hipMemcpyAsync(b, ctx->m_b, 5 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (w_leaf) TL_HIP(hipMemcpyAsync(w_leaf, ctx->m_w_leaf, E * 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (b_leaf) TL_HIP(hipMemcpyAsync(b_leaf, ctx->m_b_leaf, 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (emb) TL_HIP(hipMemcpyAsync(emb, ctx->emb, (size_t)cfg.vocab * E * sizeof(float), hipMemcpyDeviceToDevice, st));
     return TL_OK;
 }
 

@@ -150,3 +150,80 @@ def test_backward_argument_checks():
         assert L.tl_backward(net.ctx, b["B"], b["N"], *([p] * 13), None) == binding.TL_EINVAL      # not a TreeLSTM
     finally:
         net.close()
+
+
+def test_sgd_update_changes_the_context_as_the_formula_says():
+    """tl_sgd_update against the definition written out in numpy float32 (theta - lr * g, product rounded, then
+    difference): dense parameters bit for bit, the embedding rows (atomics over leaves that share a word) to 1e-6;
+    and a forward through the updated context equals the forward of a fresh context created from those
+    parameters: everything derived from them was rebuilt."""
+    print("case sgd update", flush=True)
+    w = synth.workload("sentence")
+    p, t = w.params, w.trees
+    lr = np.float32(0.05)
+    net = binding.TreeNet(p, scheduler="level_device")
+    try:
+        b = net.load(t)
+        binding.tl_set_keep_gates(net.ctx, True)
+        net.forward()
+        g_h = torch.randn((t.n_nodes, p.hidden), device="cuda")
+        grads = binding.tl_backward(net.ctx, b, g_h, p.embed_dim)
+        binding.tl_sgd_update(net.ctx, float(lr), b, grads)
+        new = {k: v.cpu().numpy() for k, v in binding.tl_get_params(net.ctx, p.vocab, p.embed_dim, p.hidden).items()}
+        g = {k: v.cpu().numpy() for k, v in grads.items()}
+        for key, old, grad in (("u", p.u, g["d_u"]), ("b", p.b, g["d_b"]), ("w_leaf", p.w_leaf, g["d_w_leaf"]),
+                               ("b_leaf", p.b_leaf, g["d_b_leaf"])):
+            want = (old.astype(np.float32) - (lr * grad.astype(np.float32)).astype(np.float32)).astype(np.float32)
+            assert np.array_equal(new[key], want.reshape(new[key].shape)), key
+        emb = p.emb.astype(np.float64).copy()
+        leaves = np.flatnonzero(t.left < 0)
+        np.add.at(emb, t.word[leaves], -float(lr) * g["d_x"][leaves].astype(np.float64))
+        assert np.abs(new["emb"] - emb).max() <= 1e-6
+        assert np.abs(new["emb"] - p.emb).max() > 0
+        net.forward()
+        torch.cuda.synchronize()
+        assert binding.tl_status(net.ctx) == 0
+        h_after = b["h"].cpu().numpy().copy()
+    finally:
+        net.close()
+    q = synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, new["emb"], new["w_leaf"], new["b_leaf"], new["u"], new["b"], None)
+    fresh = binding.TreeNet(q, scheduler="level_device")
+    try:
+        got = fresh.run(t)
+        assert np.array_equal(got["h"], h_after), "max diff %.3e" % np.abs(got["h"] - h_after).max()
+        gb = binding.tl_backward(fresh.ctx, fresh.batch, g_h, p.embed_dim)       # the backward's packed weights too
+    finally:
+        fresh.close()
+    ref = oracle.forward_params(q, t, n_threads=4)
+    assert np.allclose(h_after, ref["h"], atol=1e-4, rtol=1e-3)
+
+
+def test_a_few_training_steps_reduce_the_loss():
+    """Forward, head backward, tree backward, update, five times over one batch with fixed labels: the summed
+    cross-entropy goes down step after step (head parameters updated with the same rule by torch)."""
+    print("case training loop", flush=True)
+    w = synth.workload("tiny")
+    p, t = w.params, w.trees
+    rng = np.random.default_rng(4)
+    C = 3
+    ws = torch.from_numpy((rng.standard_normal((p.hidden, C)) * 0.3).astype(np.float32)).cuda()
+    bs = torch.zeros(C, device="cuda")
+    label = torch.from_numpy(rng.integers(0, C, t.n_nodes).astype(np.int32)).cuda()
+    net = binding.TreeNet(p, scheduler="ready")
+    losses = []
+    try:
+        b = net.load(t)
+        binding.tl_set_keep_gates(net.ctx, True)
+        for step in range(6):
+            net.forward()
+            hb = binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label)
+            grads = binding.tl_backward(net.ctx, b, hb["g_h"], p.embed_dim)
+            losses.append(float(hb["loss"][0]))
+            binding.tl_sgd_update(net.ctx, 0.02, b, grads)
+            ws -= 0.02 * hb["d_w_s"]
+            bs -= 0.02 * hb["d_b_s"]
+        assert binding.tl_status(net.ctx) == 0
+    finally:
+        net.close()
+    print("    losses", ["%.4f" % x for x in losses], flush=True)
+    assert all(b_ < a_ for a_, b_ in zip(losses, losses[1:])), losses
