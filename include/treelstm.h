@@ -33,7 +33,8 @@
  * A single-node tree (the root is a leaf) is legal.
  *
  * Threading: a context is not thread safe; one forward may be in flight per context.
- * TL_SCHED_READY and TL_SCHED_LEVEL_DEVICE evaluate the internal nodes in one kernel whose
+ * TL_SCHED_READY (also in its _PRIORITY variant, which is meant wherever TL_SCHED_READY is
+ * named below) and TL_SCHED_LEVEL_DEVICE evaluate the internal nodes in one kernel whose
  * workgroups wait for each other, so all of them must be resident together: they are sized to
  * fill the device, and while such a forward runs nothing else that holds compute units for long
  * (another context's forward on a second stream, say) may run on the same device.  Breaking

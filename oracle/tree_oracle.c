@@ -545,3 +545,78 @@ int oracle_td_generate(int H, const float *u_td, const float *b_td, const float 
     free(kid_h); free(kid_c);
     return n;
 }
+
+/*
+ * Backward pass of the TreeRNN forward (leaf h = x, internal h = tanh([h_l ; h_r] W + b)) for a loss
+ * that may touch every node: g_h[n] = dL/dh[n] from outside; a node's total dh is g_h[n] plus what its
+ * parent sends down.  With a = [h_l ; h_r]:
+ *   internal:  dpre = dh * (1 - h^2)      [dh_l ; dh_r] (sent down) = dpre W^T      dW += a^T dpre      db += dpre
+ *   leaf:      d_x[n] = dh                (the embedding row is the state itself)
+ * h is the stored fp32 forward state; sums in double, rounded to fp32 once.  d_x is [n_nodes x H], rows of
+ * internal nodes zero.  Returns 0, or -1 on a malformed batch.
+ * Pinned by tests against torch autograd on an independent float64 evaluation and finite differences.
+ */
+typedef struct {
+    int H;
+    const float *w, *h, *g_h;
+    const int32_t *left, *right;
+    double *d_w, *d_b;
+    float *d_x;
+} bwd_rnn_t;
+
+static void backward_rnn_node(const bwd_rnn_t *m, int n, const double *dh, double *scratch)
+{
+    const int H = m->H;
+    if (m->left[n] < 0) {
+        for (int j = 0; j < H; ++j) m->d_x[(size_t)n * H + j] = (float)dh[j];
+        return;
+    }
+    const int l = m->left[n], r = m->right[n];
+    double *dpre = scratch, *dhl = dpre + H, *dhr = dhl + H, *next = dhr + H;
+    for (int j = 0; j < H; ++j) {
+        const double hv = m->h[(size_t)n * H + j];
+        dpre[j] = dh[j] * (1.0 - hv * hv);
+        m->d_b[j] += dpre[j];
+    }
+    for (int k = 0; k < 2 * H; ++k) {
+        const double ak = k < H ? m->h[(size_t)l * H + k] : m->h[(size_t)r * H + (k - H)];
+        const float *row = m->w + (size_t)k * H;
+        double s = 0.0;
+        for (int j = 0; j < H; ++j) {
+            s += dpre[j] * (double)row[j];
+            m->d_w[(size_t)k * H + j] += ak * dpre[j];
+        }
+        if (k < H) dhl[k] = s + (double)m->g_h[(size_t)l * H + k];
+        else dhr[k - H] = s + (double)m->g_h[(size_t)r * H + (k - H)];
+    }
+    backward_rnn_node(m, l, dhl, next);
+    backward_rnn_node(m, r, dhr, next);
+}
+
+int oracle_backward_rnn(int H, const float *w, int n_trees, int n_nodes, const int32_t *tree_off,
+                        const int32_t *left, const int32_t *right, const float *h, const float *g_h,
+                        float *d_w, float *d_b, float *d_x)
+{
+    int32_t *parent = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *height = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *root = malloc(sizeof(int32_t) * (size_t)(n_trees > 0 ? n_trees : 1));
+    int rc = oracle_structure(n_trees, n_nodes, tree_off, left, right, parent, root, height);
+    if (rc == 0) {
+        const size_t nw = (size_t)2 * H * H;
+        bwd_rnn_t m = { H, w, h, g_h, left, right, calloc(nw, sizeof(double)), calloc((size_t)H, sizeof(double)), d_x };
+        memset(d_x, 0, sizeof(float) * (size_t)n_nodes * H);
+        int max_h = 0;
+        for (int t = 0; t < n_trees; ++t) if (height[root[t]] > max_h) max_h = height[root[t]];
+        double *scratch = malloc(sizeof(double) * (size_t)3 * H * (size_t)(max_h + 2));
+        double *dh = malloc(sizeof(double) * (size_t)H);
+        for (int t = 0; t < n_trees; ++t) {
+            for (int j = 0; j < H; ++j) dh[j] = (double)g_h[(size_t)root[t] * H + j];
+            backward_rnn_node(&m, root[t], dh, scratch);
+        }
+        for (size_t i = 0; i < nw; ++i) d_w[i] = (float)m.d_w[i];
+        for (int j = 0; j < H; ++j) d_b[j] = (float)m.d_b[j];
+        free(m.d_w); free(m.d_b); free(scratch); free(dh);
+    }
+    free(parent); free(height); free(root);
+    return rc;
+}

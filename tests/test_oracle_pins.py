@@ -779,3 +779,73 @@ def test_topdown_step_is_the_generators_step():
     assert np.array_equal(kh[0], r["h"][r["left"][v]]) and np.array_equal(kh[1], r["h"][r["right"][v]])
     assert np.array_equal(kc[0], r["c"][r["left"][v]]) and np.array_equal(kc[1], r["c"][r["right"][v]])
     assert score == r["score"][v] and not np.allclose(kh[0], kh[1])
+
+
+# ---- TreeRNN backward -----------------------------------------------------------------------
+
+def _rnn_case(seed, d, leaves, shapes):
+    p = synth.make_rnn_params(seed, CELL_TREERNN, 19, d, scale=0.6)
+    p = Params(p.cell, p.vocab, d, d, p.emb, None, None, p.u, p.b + 0.05, None)
+    trees = synth.make_trees(seed, leaves, shapes, 19)
+    fwd = oracle.forward_params(p, trees)
+    rng = np.random.default_rng(seed)
+    g_h = rng.standard_normal(fwd["h"].shape).astype(np.float32)
+    g_h[rng.random(len(g_h)) < 0.3] = 0.0
+    return p, trees, fwd, g_h
+
+
+def _torch_rnn_loss(p, trees, g_h, w=None, b=None):
+    t = {"emb": torch.tensor(p.emb, dtype=torch.float64, requires_grad=True),
+         "u": torch.tensor(p.u if w is None else w, dtype=torch.float64, requires_grad=True),
+         "b": torch.tensor(p.b if b is None else b, dtype=torch.float64, requires_grad=True)}
+    g = torch.tensor(g_h, dtype=torch.float64)
+    loss = torch.zeros((), dtype=torch.float64)
+
+    def ev(n):
+        nonlocal loss
+        if trees.left[n] < 0:
+            h = t["emb"][int(trees.word[n])] * 1.0
+        else:
+            h = torch.tanh(torch.cat([ev(int(trees.left[n])), ev(int(trees.right[n]))]) @ t["u"] + t["b"])
+        loss = loss + (g[n] * h).sum()
+        return h
+
+    _, root, _ = oracle.structure(trees.tree_off, trees.left, trees.right)
+    for r in root:
+        ev(int(r))
+    return loss, t
+
+
+def test_treernn_backward_matches_autograd_and_finite_differences():
+    """d_u, d_b and the per-leaf embedding gradients against torch autograd through an independent float64
+    recursion; a sample of entries against central differences of that evaluation; zero and doubled g_h."""
+    for seed, d, leaves, shapes in ((1, 4, [1, 2, 7], ["random"] * 3), (2, 6, [9, 4], ["chain", "balanced"]), (3, 3, [12], ["random"])):
+        p, trees, fwd, g_h = _rnn_case(seed, d, leaves, shapes)
+        got = oracle.backward(p, trees, fwd["h"], None, g_h)
+        loss, t = _torch_rnn_loss(p, trees, g_h)
+        loss.backward()
+        assert np.allclose(got["d_u"], t["u"].grad.numpy(), rtol=2e-4, atol=2e-6), seed
+        assert np.allclose(got["d_b"], t["b"].grad.numpy(), rtol=2e-4, atol=2e-6), seed
+        d_emb = np.zeros_like(p.emb, dtype=np.float64)
+        for n in np.nonzero(trees.left < 0)[0]:
+            d_emb[trees.word[n]] += got["d_x"][n]
+        assert np.allclose(d_emb, t["emb"].grad.numpy(), rtol=2e-4, atol=2e-6)
+        assert not got["d_x"][trees.left >= 0].any()
+    p, trees, fwd, g_h = _rnn_case(7, 3, [3, 2], ["random", "random"])
+    got = oracle.backward(p, trees, fwd["h"], None, g_h)
+    eps = 1e-6
+    base = p.u.astype(np.float64)
+    for idx in list(np.ndindex(base.shape))[::2]:
+        vals = []
+        for s in (+eps, -eps):
+            w = base.copy()
+            w[idx] += s
+            with torch.no_grad():
+                vals.append(float(_torch_rnn_loss(p, trees, g_h, w=w)[0]))
+        fd = (vals[0] - vals[1]) / (2 * eps)
+        assert abs(fd - got["d_u"][idx]) <= 1e-5 + 1e-4 * abs(fd), (idx, fd, got["d_u"][idx])
+    zero = oracle.backward(p, trees, fwd["h"], None, np.zeros_like(g_h))
+    assert all(not v.any() for v in zero.values())
+    two = oracle.backward(p, trees, fwd["h"], None, 2 * g_h)
+    for k in got:
+        assert np.allclose(two[k], 2 * got[k], rtol=1e-6, atol=1e-9)
