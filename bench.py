@@ -193,15 +193,19 @@ def backward_stage(w, n_classes, reps=10):
             return (time.perf_counter() - t0) / reps * 1e3
 
         ms = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
-        flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
+        if w.params.cell == 0:
+            flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
+        else:                       # TreeRNN: operand gradient and weight gradient, 4 H^2 each per internal node
+            flops = 8.0 * H * H * w.trees.n_internal
         out = {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12,
                "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
         # training mode: the forward keeps the gate activations, the backward does not recompute the contraction
         # (40 H^2 flops per internal node and 12 E H per leaf are left)
-        binding.tl_set_keep_gates(net.ctx, True)
-        net.forward()
-        out["ms_kept_gates"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
-        out["forward_ms_keeping_gates"] = wall(net.forward, 50)
+        if w.params.cell == 0:
+            binding.tl_set_keep_gates(net.ctx, True)
+            net.forward()
+            out["ms_kept_gates"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
+            out["forward_ms_keeping_gates"] = wall(net.forward, 50)
         if n_classes > 0:
             g = torch.Generator(device="cuda").manual_seed(2)
             ws = torch.randn((H, n_classes), device="cuda", generator=g) * (H ** -0.5)
@@ -220,8 +224,8 @@ def backward_stage(w, n_classes, reps=10):
             step_ms = wall(train_step, reps)
             out["train_step_ms"] = step_ms
             out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
-            out["train_step_note"] = ("forward keeping the gate activations + head backward + tree backward + SGD update of "
-                                      "all parameters (embedding rows included) and re-packing of the weights")
+            out["train_step_note"] = ("forward (a TreeLSTM keeps its gate activations) + head backward + tree backward + SGD update "
+                                      "of all parameters (embedding rows included) and re-packing of the weights")
         return out
     finally:
         net.close()
@@ -398,7 +402,7 @@ def main():
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
     if args.head > 0:
         out["head"] = head_stage(w, args.head)
-    if args.backward and w.params.cell == 0 and args.precision == "f32":
+    if args.backward and w.params.cell in (0, 1) and args.precision == "f32":
         out["backward"] = backward_stage(w, args.head)
     if not args.no_compare:
         comp = {}

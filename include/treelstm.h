@@ -187,20 +187,24 @@ int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
 int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
 
 /*
- * Backward pass of a TL_TREELSTM / TL_F32 forward (Section 4.2.2, recursive backpropagation: the
- * gradient of a node's cell is applied from the roots down, each node finding its forward values
- * by node index).  The loss may depend on every node's h: g_h[n] = dL/dh[n] (zero rows where it
- * does not).  h and c are the rows tl_forward wrote for the same batch.
- *   tree_off, left, right, word, h, c   as in tl_forward (h, c read-only)          DEVICE
+ * Backward pass of a TL_TREELSTM or TL_TREERNN forward in TL_F32 (Section 4.2.2, recursive
+ * backpropagation: the gradient of a node's cell is applied from the roots down, each node
+ * finding its forward values by node index).  The loss may depend on every node's h:
+ * g_h[n] = dL/dh[n] (zero rows where it does not).  h and c are the rows tl_forward wrote for
+ * the same batch.
+ *   tree_off, left, right, word, h, c   as in tl_forward (h, c read-only; c NULL for
+ *             TL_TREERNN)                                                         DEVICE
  *   g_h       [n_nodes x H] fp32                                                  DEVICE, read-only
  *   d_u       [2H x 5H], d_b [5H], d_w_leaf [E x 3H], d_b_leaf [3H]  fp32 out,
  *             sums over all nodes of the batch, same layouts as the parameters    DEVICE
+ *             (TL_TREERNN: d_u [2H x H], d_b [H]; d_w_leaf, d_b_leaf unused, may be NULL)
  *   d_x       [n_nodes x E] fp32 out: row n = dL/d(embedding row used by leaf n);
  *             rows of internal nodes are zero (the caller scatter-adds by word)    DEVICE
- * fp32 arithmetic; the gate activations are recomputed from h / c, not stored by the forward.
+ * fp32 arithmetic; the TreeLSTM gate activations are recomputed from h / c unless the forward
+ * kept them (tl_set_keep_gates); the TreeRNN needs nothing but h.
  * Work is enqueued on hip_stream, but the call waits for the structure pass (it needs the
  * number of heights) and returns the deferred structure status: TL_OK, TL_ESTRUCT, ...
- * The first call for a larger batch than any before allocates workspace.  Other cells or
+ * The first call for a larger batch than any before allocates workspace.  TL_RNTN or
  * TL_BF16_IN: TL_EINVAL.
  */
 int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
@@ -218,7 +222,8 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
  * enqueued on hip_stream and nothing is allocated.  Dense parameters change exactly as the
  * formula says in fp32 (product rounded, then difference); embedding rows shared by several
  * leaves are updated with atomics.  Calls on one context must be ordered with its forwards
- * and backwards (same stream, or synchronised).  TreeLSTM / TL_F32 only, else TL_EINVAL.
+ * and backwards (same stream, or synchronised).  TL_TREELSTM or TL_TREERNN (u, b and the
+ * embedding only; d_w_leaf, d_b_leaf may be NULL) in TL_F32, else TL_EINVAL.
  */
 int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const int32_t *word, const float *d_u,
                   const float *d_b, const float *d_w_leaf, const float *d_b_leaf, const float *d_x, void *hip_stream);
@@ -226,7 +231,8 @@ int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const
 /*
  * Copies the context's current parameters to the caller's DEVICE buffers (any of them may be
  * NULL): u [2H x 5H], b [5H], w_leaf [E x 3H], b_leaf [3H], emb [vocab x E], fp32, the layouts
- * tl_create takes.  Asynchronous on hip_stream.  TreeLSTM / TL_F32 only, else TL_EINVAL.
+ * tl_create takes (TL_TREERNN: u [2H x H], b [H]; w_leaf and b_leaf must be NULL).
+ * Asynchronous on hip_stream.  TL_TREELSTM or TL_TREERNN in TL_F32, else TL_EINVAL.
  */
 int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream);
 

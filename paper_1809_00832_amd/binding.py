@@ -145,19 +145,24 @@ def tl_last_stats(ctx):
 
 def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
     """Gradients for a batch that tl_forward has evaluated (`batch` is the dict TreeNet.load returns, holding h and
-    c); g_h [N x H] float32 CUDA tensor.  Returns dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x) of CUDA tensors."""
+    c); g_h [N x H] float32 CUDA tensor.  Returns dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x) of CUDA tensors for a
+    TreeLSTM, dict(d_u [2H x H], d_b [H], d_x) for a TreeRNN (batch["c"] is None there)."""
     import torch
     N, H, E = batch["N"], int(batch["h"].shape[1]), int(embed_dim)
     assert g_h.is_cuda and g_h.dtype == torch.float32 and g_h.is_contiguous() and tuple(g_h.shape) == (N, H)
     dev = g_h.device
-    out = {"d_u": torch.empty((2 * H, 5 * H), device=dev), "d_b": torch.empty(5 * H, device=dev),
-           "d_w_leaf": torch.empty((E, 3 * H), device=dev), "d_b_leaf": torch.empty(3 * H, device=dev),
+    lstm = batch.get("c") is not None
+    ng = 5 if lstm else 1
+    out = {"d_u": torch.empty((2 * H, ng * H), device=dev), "d_b": torch.empty(ng * H, device=dev),
            "d_x": torch.empty((N, E), device=dev)}
+    if lstm:
+        out["d_w_leaf"] = torch.empty((E, 3 * H), device=dev)
+        out["d_b_leaf"] = torch.empty(3 * H, device=dev)
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib().tl_backward(ctx, batch["B"], N, batch["tree_off"].data_ptr(), batch["left"].data_ptr(),
                              batch["right"].data_ptr(), batch["word"].data_ptr(), batch["h"].data_ptr(),
-                             batch["c"].data_ptr(), g_h.data_ptr(), out["d_u"].data_ptr(), out["d_b"].data_ptr(),
-                             out["d_w_leaf"].data_ptr(), out["d_b_leaf"].data_ptr(), out["d_x"].data_ptr(), st), "tl_backward")
+                             _ptr(batch.get("c")), g_h.data_ptr(), out["d_u"].data_ptr(), out["d_b"].data_ptr(),
+                             _ptr(out.get("d_w_leaf")), _ptr(out.get("d_b_leaf")), out["d_x"].data_ptr(), st), "tl_backward")
     return out
 
 
@@ -167,19 +172,23 @@ def tl_sgd_update(ctx, lr, batch, grads, with_embedding=True, stream=None) -> No
     import torch
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib().tl_sgd_update(ctx, float(lr), batch["N"], batch["left"].data_ptr(), batch["word"].data_ptr(),
-                               grads["d_u"].data_ptr(), grads["d_b"].data_ptr(), grads["d_w_leaf"].data_ptr(),
-                               grads["d_b_leaf"].data_ptr(), grads["d_x"].data_ptr() if with_embedding else None, st),
+                               grads["d_u"].data_ptr(), grads["d_b"].data_ptr(), _ptr(grads.get("d_w_leaf")),
+                               _ptr(grads.get("d_b_leaf")), grads["d_x"].data_ptr() if with_embedding else None, st),
            "tl_sgd_update")
 
 
-def tl_get_params(ctx, vocab, embed_dim, hidden, stream=None):
-    """The context's current parameters as new CUDA tensors: dict(u, b, w_leaf, b_leaf, emb)."""
+def tl_get_params(ctx, vocab, embed_dim, hidden, cell=TL_TREELSTM, stream=None):
+    """The context's current parameters as new CUDA tensors: dict(u, b, w_leaf, b_leaf, emb); dict(u, b, emb) for a
+    TreeRNN."""
     import torch
     H, E = int(hidden), int(embed_dim)
+    ng = 5 if cell == TL_TREELSTM else 1
     new = lambda *shape: torch.empty(shape, dtype=torch.float32, device="cuda")
-    out = {"u": new(2 * H, 5 * H), "b": new(5 * H), "w_leaf": new(E, 3 * H), "b_leaf": new(3 * H), "emb": new(int(vocab), E)}
+    out = {"u": new(2 * H, ng * H), "b": new(ng * H), "emb": new(int(vocab), E)}
+    if cell == TL_TREELSTM:
+        out["w_leaf"], out["b_leaf"] = new(E, 3 * H), new(3 * H)
     st = (stream or torch.cuda.current_stream()).cuda_stream
-    _check(lib().tl_get_params(ctx, out["u"].data_ptr(), out["b"].data_ptr(), out["w_leaf"].data_ptr(), out["b_leaf"].data_ptr(),
+    _check(lib().tl_get_params(ctx, out["u"].data_ptr(), out["b"].data_ptr(), _ptr(out.get("w_leaf")), _ptr(out.get("b_leaf")),
                                out["emb"].data_ptr(), st), "tl_get_params")
     return out
 

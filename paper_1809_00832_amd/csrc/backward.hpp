@@ -148,6 +148,39 @@ __global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__
     }
 }
 
+// TreeRNN (h = tanh(a W + b), leaves h = x): the gradient of the pre-activation needs only the stored h,
+// dpre = dh (1 - h^2), one row of H values per listed node (by list position from pos0 on).
+template <int V>
+__global__ __launch_bounds__(256) void k_rnn_gate_grad(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+{
+    const int H = f.H, per_row = H / V;
+    const long long total = (long long)n_rows * per_row;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int row = (int)(e / per_row), col = (int)(e - (long long)row * per_row) * V;
+        const size_t o = (size_t)list[row] * H + col;
+        float *dg = f.dg + (size_t)(pos0 + row) * H + col;
+        if constexpr (V == 4) {
+            const floatx4 hv = *reinterpret_cast<const floatx4 *>(f.h + o), dh = *reinterpret_cast<const floatx4 *>(f.dh + o);
+            *reinterpret_cast<floatx4 *>(dg) = floatx4{dh.x * (1.f - hv.x * hv.x), dh.y * (1.f - hv.y * hv.y),
+                                                      dh.z * (1.f - hv.z * hv.z), dh.w * (1.f - hv.w * hv.w)};
+        } else {
+            const float hv = f.h[o];
+            *dg = f.dh[o] * (1.f - hv * hv);
+        }
+    }
+}
+
+// TreeRNN leaves: the embedding row is the state itself, so its gradient is the row of dh.
+__global__ void k_rnn_leaf_grad(Fwd f)
+{
+    const size_t total = (size_t)f.n_leaf * f.H;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / f.H), j = (int)(e - (size_t)i * f.H);
+        const size_t o = (size_t)f.leaf_list[i] * f.H + j;
+        f.d_x[o] = f.dh[o];
+    }
+}
+
 // out[r][c] = in[c][r] for a row-major [rows x cols] input
 __global__ void k_transpose(const float *__restrict__ in, float *__restrict__ out, int rows, int cols)
 {

@@ -316,6 +316,26 @@ int pack_treelstm_f32(tl_ctx *ctx, hipStream_t st)
     return TL_OK;
 }
 
+// The same for an fp32 TreeRNN context: forward weights and W^T of the backward pass.
+int pack_treernn_f32(tl_ctx *ctx, hipStream_t st)
+{
+    const int H = ctx->cfg.hidden;
+    int rc = pack_gemm(ctx->m_u, ctx->m_b, 1, H, 2, H, ctx->n_cg, ctx->ws_steps16, false, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner, st);
+    if (rc != TL_OK) return rc;
+    float *t = ctx->t_scratch, *zb = ctx->zero_bias;
+    hipLaunchKernelGGL(k_transpose, dim3(1024), dim3(256), 0, st, (const float *)ctx->m_u, t, 2 * H, H);
+    rc = pack_gemm(t, zb, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1, H, (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, 0, false,
+                   &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner, st);
+    if (rc != TL_OK) return rc;
+    if (ctx->ng_bwd_inner == 4) {
+        rc = pack_gemm(t, zb, 1, 2 * H, 1, H, (2 * H + HU - 1) / HU, 0, false, &ctx->g_bwd_inner1, &ctx->wp_bwd_inner1,
+                       &ctx->bp_bwd_inner1, st);
+        if (rc != TL_OK) return rc;
+    }
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace for batches of up to n_nodes nodes / n_trees trees.
@@ -480,6 +500,20 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
             rc = pack_gemm(cfg->u, cfg->b, 5, H, 2, H, ctx->n_cg, ws_steps16, true, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
             if (rc != TL_OK) return rc;
         }
+    } else if (cfg->cell == TL_TREERNN && !bf16) {
+        const size_t n_u = (size_t)2 * H * H;
+        TL_HIP(hipMalloc(&ctx->m_u, n_u * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->m_b, (size_t)H * sizeof(float)));
+        TL_HIP(hipMemcpy(ctx->m_u, cfg->u, n_u * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMemcpy(ctx->m_b, cfg->b, (size_t)H * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMalloc(&ctx->t_scratch, n_u * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->zero_bias, ((size_t)2 * H + HU) * sizeof(float)));
+        TL_HIP(hipMemset(ctx->zero_bias, 0, ((size_t)2 * H + HU) * sizeof(float)));
+        ctx->ng_bwd_inner = (2 * H) % 4 == 0 ? 4 : 1;
+        ctx->ws_steps16 = ws_steps16;
+        rc = pack_treernn_f32(ctx, nullptr);
+        TL_HIP(hipDeviceSynchronize());
+        if (rc != TL_OK) return rc;
     } else if (cfg->cell == TL_TREERNN) {
         rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
@@ -806,10 +840,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                 const int32_t *word, const float *h, const float *c, const float *g_h, float *d_u, float *d_b,
                 float *d_w_leaf, float *d_b_leaf, float *d_x, void *hip_stream)
 {
-    if (!ctx || !tree_off || !left || !right || !word || !h || !c || !g_h) return TL_EINVAL;
-    if (!d_u || !d_b || !d_w_leaf || !d_b_leaf || !d_x) return TL_EINVAL;
+    if (!ctx || !tree_off || !left || !right || !word || !h || !g_h || !d_u || !d_b || !d_x) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM;
+    if (lstm && (!c || !d_w_leaf || !d_b_leaf)) return TL_EINVAL;
     if (n_trees < 1 || n_nodes < n_trees) return TL_EINVAL;
     if (((long long)n_nodes + n_trees) % 2 != 0) return TL_ESTRUCT;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -829,7 +864,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     Fwd f{};
     f.n_trees = n_trees; f.n_nodes = n_nodes; f.n_leaf = n_leaf; f.n_int = n_int;
     f.tree_off = tree_off; f.left = left; f.right = right; f.word = word;
-    f.h = const_cast<float *>(h); f.c = const_cast<float *>(c);
+    f.h = const_cast<float *>(h); f.c = lstm ? const_cast<float *>(c) : nullptr;
     f.cell = cfg.cell; f.H = H; f.E = E; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg;
     f.emb = ctx->emb;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
@@ -839,7 +874,8 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     const size_t cap = (size_t)ctx->bw_nodes;
     f.dh = ctx->bw;
     f.dc = f.dh + cap * H;
-    float *dg_int = f.dc + cap * H, *dg_leaf = dg_int + (size_t)n_int * 5 * H;
+    const int ng_cell = lstm ? 5 : 1;                         // gate blocks of an internal node
+    float *dg_int = f.dc + cap * H, *dg_leaf = dg_int + (size_t)n_int * ng_cell * H;
     f.d_x = d_x;
     ctx->last = f;
     ctx->last_stream = st;
@@ -858,12 +894,12 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     TL_HIP(hipMemcpyAsync(f.dh, g_h, (size_t)n_nodes * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     {
         ZeroList z{};
-        z.p[0] = f.dc;     z.n[0] = (size_t)n_nodes * H;
+        z.p[0] = f.dc;     z.n[0] = lstm ? (size_t)n_nodes * H : 0;
         z.p[1] = d_x;      z.n[1] = (size_t)n_nodes * E;
-        z.p[2] = d_b;      z.n[2] = (size_t)5 * H;
-        z.p[3] = d_b_leaf; z.n[3] = (size_t)3 * H;
-        z.p[4] = d_u;      z.n[4] = (size_t)2 * H * 5 * H;
-        z.p[5] = d_w_leaf; z.n[5] = (size_t)E * 3 * H;
+        z.p[2] = d_b;      z.n[2] = (size_t)ng_cell * H;
+        z.p[3] = d_b_leaf; z.n[3] = lstm ? (size_t)3 * H : 0;
+        z.p[4] = d_u;      z.n[4] = (size_t)2 * H * ng_cell * H;
+        z.p[5] = d_w_leaf; z.n[5] = lstm ? (size_t)E * 3 * H : 0;
         hipLaunchKernelGGL(k_zero_many, dim3(1024), dim3(256), 0, st, z);
     }
     TL_HIP(hipGetLastError());
@@ -872,7 +908,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     const int n_levels = ctx->host_ctl->n_levels;
     const bool vec4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
     // gate activations of the forward that wrote these h rows, if it kept them: no contraction to recompute
-    const bool kept = ctx->gates_nodes == n_nodes && ctx->gates_h == h && ctx->gates != nullptr;
+    const bool kept = lstm && ctx->gates_nodes == n_nodes && ctx->gates_h == h && ctx->gates != nullptr;
     const bool kept_v4 = H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
     f.gates = kept ? ctx->gates : nullptr;
     auto gate_grad_kept = [&](bool inner, const Fwd &g, const int32_t *list, int rows) {
@@ -893,7 +929,14 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
             Fwd g = f;
             g.dg = dg_int;
             g.pos0 = lo;
-            if (kept)
+            if (!lstm) {
+                typedef void (*rnn_kernel)(Fwd, const int32_t *, int, int);
+                const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
+                long long blocks = ((long long)rows * (v4 ? H / 4 : H) + 255) / 256;
+                if (blocks > 8LL * ctx->n_cu) blocks = 8LL * ctx->n_cu;
+                hipLaunchKernelGGL(v4 ? rnn_kernel(k_rnn_gate_grad<4>) : rnn_kernel(k_rnn_gate_grad<1>), dim3((unsigned)blocks), dim3(256),
+                                   0, st, g, (const int32_t *)(f.level_nodes + lo), rows, lo);
+            } else if (kept)
                 gate_grad_kept(true, g, (const int32_t *)(f.level_nodes + lo), rows);
             else
                 hipLaunchKernelGGL(backward_kernel(EPI_BWD_INNER_GATES, vec4), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
@@ -909,7 +952,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                                TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
         }
     }
-    {
+    if (!lstm) {
+        hipLaunchKernelGGL(k_rnn_leaf_grad, dim3(1024), dim3(256), 0, st, f);       // leaves: d_x = dh
+    } else {
         const LevelPlan plan = plan_level(n_leaf, f.cap_tiles);
         Fwd g = f;
         g.dg = dg_leaf;
@@ -935,13 +980,13 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         return z < 1 ? 1 : z;
     };
     if (n_int > 0) {
-        const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (5 * H + WG_TILE - 1) / WG_TILE, 1);
+        const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (ng_cell * H + WG_TILE - 1) / WG_TILE, 1);
         const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
         const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<2, true>) : wgrad_kernel(k_weight_grad<2, false>);
         hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
-                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, 5 * H, d_u, d_b);
+                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, ng_cell * H, d_u, d_b);
     }
-    {
+    if (lstm) {
         const dim3 grid((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE, 1);
         const bool v4 = E % 4 == 0 && H % 4 == 0;
         const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<1, true>) : wgrad_kernel(k_weight_grad<1, false>);
@@ -956,33 +1001,37 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
 int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const int32_t *word, const float *d_u,
                   const float *d_b, const float *d_w_leaf, const float *d_b_leaf, const float *d_x, void *hip_stream)
 {
-    if (!ctx || !d_u || !d_b || !d_w_leaf || !d_b_leaf) return TL_EINVAL;
+    if (!ctx || !d_u || !d_b) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM;
+    if (lstm && (!d_w_leaf || !d_b_leaf)) return TL_EINVAL;
     if (d_x && (!left || !word || n_nodes < 1)) return TL_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    const int H = cfg.hidden, E = cfg.embed_dim;
+    const int H = cfg.hidden, E = cfg.embed_dim, ng_cell = lstm ? 5 : 1;
     SgdList z{};
-    z.theta[0] = ctx->m_u;      z.grad[0] = d_u;      z.n[0] = (size_t)2 * H * 5 * H;
-    z.theta[1] = ctx->m_b;      z.grad[1] = d_b;      z.n[1] = (size_t)5 * H;
-    z.theta[2] = ctx->m_w_leaf; z.grad[2] = d_w_leaf; z.n[2] = (size_t)E * 3 * H;
-    z.theta[3] = ctx->m_b_leaf; z.grad[3] = d_b_leaf; z.n[3] = (size_t)3 * H;
+    z.theta[0] = ctx->m_u;      z.grad[0] = d_u;      z.n[0] = (size_t)2 * H * ng_cell * H;
+    z.theta[1] = ctx->m_b;      z.grad[1] = d_b;      z.n[1] = (size_t)ng_cell * H;
+    z.theta[2] = ctx->m_w_leaf; z.grad[2] = d_w_leaf; z.n[2] = lstm ? (size_t)E * 3 * H : 0;
+    z.theta[3] = ctx->m_b_leaf; z.grad[3] = d_b_leaf; z.n[3] = lstm ? (size_t)3 * H : 0;
     hipLaunchKernelGGL(k_sgd_dense, dim3(1024), dim3(256), 0, st, z, lr);
     if (d_x) hipLaunchKernelGGL(k_sgd_embedding, dim3(1024), dim3(256), 0, st, ctx->emb, d_x, left, word, n_nodes, E, cfg.vocab, lr);
     TL_HIP(hipGetLastError());
     ctx->gates_nodes = 0;             // what a forward kept belongs to the old parameters
-    return pack_treelstm_f32(ctx, st);
+    return lstm ? pack_treelstm_f32(ctx, st) : pack_treernn_f32(ctx, st);
 }
 
 int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream)
 {
     if (!ctx) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if (cfg.cell != TL_TREELSTM || cfg.precision != TL_F32) return TL_EINVAL;
+    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM;
+    if (!lstm && (w_leaf || b_leaf)) return TL_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
-    const size_t H = cfg.hidden, E = cfg.embed_dim;
-    if (u) TL_HIP(hipMemcpyAsync(u, ctx->m_u, 2 * H * 5 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
-    if (b) TL_HIP(hipMemcpyAsync(b, ctx->m_b, 5 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    const size_t H = cfg.hidden, E = cfg.embed_dim, ng_cell = lstm ? 5 : 1;
+    if (u) TL_HIP(hipMemcpyAsync(u, ctx->m_u, 2 * H * ng_cell * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (b) TL_HIP(hipMemcpyAsync(b, ctx->m_b, ng_cell * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (w_leaf) TL_HIP(hipMemcpyAsync(w_leaf, ctx->m_w_leaf, E * 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (b_leaf) TL_HIP(hipMemcpyAsync(b_leaf, ctx->m_b_leaf, 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (emb) TL_HIP(hipMemcpyAsync(emb, ctx->emb, (size_t)cfg.vocab * E * sizeof(float), hipMemcpyDeviceToDevice, st));
