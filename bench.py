@@ -80,7 +80,26 @@ def time_steps(net, steps):
     return (time.perf_counter() - t0) / steps
 
 
-def run_scheduler(w, sched, precision, steps, warmup):
+def time_graph_replays(net, steps):
+    """The forward captured once in a HIP graph and replayed `steps` times (no host work per forward but the replay
+    call): seconds per replay.  Device schedulers only: the host-driven one reads the number of heights back."""
+    import torch
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        net.forward()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def run_scheduler(w, sched, precision, steps, warmup, graph=False):
     from paper_1809_00832_amd import binding
     net = binding.TreeNet(w.params, scheduler=sched, precision=precision)
     try:
@@ -104,7 +123,12 @@ def run_scheduler(w, sched, precision, steps, warmup):
         code = binding.tl_status(net.ctx)
         if code != 0:
             raise binding.TLError(code, "timed forward")
-        return dict(sec=sec, sec_profiled=sec_prof, stage_ms=avg, stats=stats, latency_ms=latency)
+        out = dict(sec=sec, sec_profiled=sec_prof, stage_ms=avg, stats=stats, latency_ms=latency)
+        if graph and sched != "level_host":
+            out["sec_graph"] = time_graph_replays(net, steps)
+            if binding.tl_status(net.ctx) != 0:
+                raise binding.TLError(binding.tl_status(net.ctx), "graph replay")
+        return out
     finally:
         net.close()
 
@@ -332,6 +356,8 @@ def main():
     ap.add_argument("--backward", action="store_true", help="also time tl_backward on the same batch (TreeLSTM, fp32)")
     ap.add_argument("--length-sweep", action="store_true",
                     help="print only the latency of single trees of 2..1024 leaves (balanced, random, chain)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the forward replayed from a HIP graph (device schedulers)")
     ap.add_argument("--topdown", action="store_true",
                     help="print only the throughput of top-down generation of dynamically structured trees (batches of 64 and 1)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -364,7 +390,7 @@ def main():
     t = w.trees
     f_int, f_leaf, bytes_ = algorithmic_work(w)
 
-    main_run = run_scheduler(w, args.scheduler, precision, args.steps, args.warmup)
+    main_run = run_scheduler(w, args.scheduler, precision, args.steps, args.warmup, graph=args.graph)
     sec = main_run["sec"]
     peak = PEAK_TFLOPS[args.precision]
     kernel_ms = main_run["stage_ms"]["internal"]
@@ -387,6 +413,7 @@ def main():
         "stage_ms": main_run["stage_ms"],
         "ms_per_step_with_stage_events": main_run["sec_profiled"] * 1e3,
         "forward_latency_ms": main_run["latency_ms"],
+        **({"ms_per_step_graph_replay": main_run["sec_graph"] * 1e3} if "sec_graph" in main_run else {}),
         "tiles_formed": main_run["stats"]["n_tiles"],
         "roofline": {"bound": "mfma", "kernel": "internal-node kernel (%s scheduler)" % args.scheduler,
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
@@ -409,9 +436,11 @@ def main():
         for sched in ("ready", "ready_priority", "level_device", "level_host"):
             if sched == args.scheduler:
                 continue
-            r = run_scheduler(w, sched, precision, args.steps, args.warmup)
+            r = run_scheduler(w, sched, precision, args.steps, args.warmup, graph=args.graph)
             comp[sched] = {"trees_per_sec": t.n_trees / r["sec"], "ms_per_step": r["sec"] * 1e3,
                            "stage_ms": r["stage_ms"], "forward_latency_ms": r["latency_ms"], "n_levels": r["stats"]["n_levels"]}
+            if "sec_graph" in r:
+                comp[sched]["ms_per_step_graph_replay"] = r["sec_graph"] * 1e3
         out["comparison"] = comp
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
