@@ -30,6 +30,8 @@ def _load():
         lib.oracle_backward.restype = ctypes.c_int
         lib.oracle_backward.argtypes = ([ctypes.c_int] * 3 + [_F] * 5 + [ctypes.c_int, ctypes.c_int] + [_I] * 4 + [_F] * 3
                                         + [_F] * 5)
+        lib.oracle_backward_rntn.restype = ctypes.c_int
+        lib.oracle_backward_rntn.argtypes = [ctypes.c_int, _F, _F, ctypes.c_int, ctypes.c_int] + [_I] * 3 + [_F] * 6
         lib.oracle_backward_rnn.restype = ctypes.c_int
         lib.oracle_backward_rnn.argtypes = [ctypes.c_int, _F, ctypes.c_int, ctypes.c_int] + [_I] * 3 + [_F] * 5
         lib.oracle_classify_backward.restype = ctypes.c_int
@@ -105,7 +107,7 @@ def forward(cell, vocab, embed_dim, hidden, emb, w_leaf, b_leaf, u, b, v,
 
 def backward(params, trees, h, c, g_h):
     """Gradients of a loss with dL/dh[n] = g_h[n].  TreeLSTM: dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x [N x E]);
-    TreeRNN (c is ignored): dict(d_u [2H x H], d_b [H], d_x [N x H])."""
+    TreeRNN (c is ignored): dict(d_u [2H x H], d_b [H], d_x [N x H]); RNTN: the same plus d_v [H x 2H x 2H]."""
     lib = _load()
     if params.cell == 1:
         H = params.hidden
@@ -114,6 +116,18 @@ def backward(params, trees, h, c, g_h):
         f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
         rc = lib.oracle_backward_rnn(H, _f(params.u), n_trees, n_nodes, _i(trees.tree_off), _i(trees.left), _i(trees.right),
                                      _f(f32(h)), _f(f32(g_h)), _f(out["d_u"]), _f(out["d_b"]), _f(out["d_x"]))
+        if rc != 0:
+            raise ValueError("malformed tree batch")
+        return out
+    if params.cell == 2:
+        H = params.hidden
+        n_trees, n_nodes = len(trees.tree_off) - 1, len(trees.left)
+        out = {"d_u": np.zeros((2 * H, H), np.float32), "d_b": np.zeros(H, np.float32),
+               "d_v": np.zeros((H, 2 * H, 2 * H), np.float32), "d_x": np.zeros((n_nodes, H), np.float32)}
+        f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+        rc = lib.oracle_backward_rntn(H, _f(params.u), _f(params.v), n_trees, n_nodes, _i(trees.tree_off), _i(trees.left),
+                                      _i(trees.right), _f(f32(h)), _f(f32(g_h)), _f(out["d_u"]), _f(out["d_b"]), _f(out["d_v"]),
+                                      _f(out["d_x"]))
         if rc != 0:
             raise ValueError("malformed tree batch")
         return out

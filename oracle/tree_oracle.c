@@ -620,3 +620,95 @@ int oracle_backward_rnn(int H, const float *w, int n_trees, int n_nodes, const i
     free(parent); free(height); free(root);
     return rc;
 }
+
+/*
+ * Backward pass of the RNTN forward (leaf h = x, internal h_k = tanh(a^T V_k a + (a W)_k + b_k), a = [h_l ; h_r],
+ * V of shape d x 2d x 2d) for a loss that may touch every node (g_h[n] = dL/dh[n] from outside):
+ *   internal:  dz = dh * (1 - h^2)
+ *              da_p = sum_k dz_k ( sum_q (V[k][p][q] + V[k][q][p]) a_q + W[p][k] )      sent down to the children
+ *              dV[k][p][q] += dz_k a_p a_q       dW[p][k] += a_p dz_k       db_k += dz_k
+ *   leaf:      d_x[n] = dh
+ * h is the stored fp32 forward state; sums in double, rounded to fp32 once.  d_x is [n_nodes x d], rows of internal
+ * nodes zero.  Returns 0, or -1 on a malformed batch.
+ * Pinned by tests against torch autograd on an independent float64 evaluation and finite differences.
+ */
+typedef struct {
+    int H;
+    const float *w, *v, *h, *g_h;
+    const int32_t *left, *right;
+    double *d_w, *d_b, *d_v;
+    float *d_x;
+} bwd_rntn_t;
+
+static void backward_rntn_node(const bwd_rntn_t *m, int n, const double *dh, double *scratch)
+{
+    const int H = m->H, D2 = 2 * H;
+    if (m->left[n] < 0) {
+        for (int j = 0; j < H; ++j) m->d_x[(size_t)n * H + j] = (float)dh[j];
+        return;
+    }
+    const int l = m->left[n], r = m->right[n];
+    double *dz = scratch, *a = dz + H, *da = a + D2, *next = da + D2;
+    for (int k = 0; k < H; ++k) {
+        const double hv = m->h[(size_t)n * H + k];
+        dz[k] = dh[k] * (1.0 - hv * hv);
+        m->d_b[k] += dz[k];
+    }
+    for (int p = 0; p < D2; ++p) a[p] = p < H ? m->h[(size_t)l * H + p] : m->h[(size_t)r * H + (p - H)];
+    for (int p = 0; p < D2; ++p) {
+        double s = 0.0;
+        for (int k = 0; k < H; ++k) {
+            s += dz[k] * (double)m->w[(size_t)p * H + k];
+            m->d_w[(size_t)p * H + k] += a[p] * dz[k];
+        }
+        da[p] = s;
+    }
+    for (int k = 0; k < H; ++k) {
+        const float *Vk = m->v + (size_t)k * D2 * D2;
+        double *dVk = m->d_v + (size_t)k * D2 * D2;
+        for (int p = 0; p < D2; ++p)
+            for (int q = 0; q < D2; ++q) {
+                const double vpq = Vk[(size_t)p * D2 + q];
+                da[p] += dz[k] * vpq * a[q];
+                da[q] += dz[k] * vpq * a[p];
+                dVk[(size_t)p * D2 + q] += dz[k] * a[p] * a[q];
+            }
+    }
+    double *dhl = next, *dhr = dhl + H, *deeper = dhr + H;
+    for (int j = 0; j < H; ++j) {
+        dhl[j] = da[j] + (double)m->g_h[(size_t)l * H + j];
+        dhr[j] = da[H + j] + (double)m->g_h[(size_t)r * H + j];
+    }
+    backward_rntn_node(m, l, dhl, deeper);
+    backward_rntn_node(m, r, dhr, deeper);
+}
+
+int oracle_backward_rntn(int H, const float *w, const float *v, int n_trees, int n_nodes, const int32_t *tree_off,
+                         const int32_t *left, const int32_t *right, const float *h, const float *g_h,
+                         float *d_w, float *d_b, float *d_v, float *d_x)
+{
+    int32_t *parent = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *height = malloc(sizeof(int32_t) * (size_t)(n_nodes > 0 ? n_nodes : 1));
+    int32_t *root = malloc(sizeof(int32_t) * (size_t)(n_trees > 0 ? n_trees : 1));
+    int rc = oracle_structure(n_trees, n_nodes, tree_off, left, right, parent, root, height);
+    if (rc == 0) {
+        const size_t nw = (size_t)2 * H * H, nv = (size_t)H * 2 * H * 2 * H;
+        bwd_rntn_t m = { H, w, v, h, g_h, left, right, calloc(nw, sizeof(double)), calloc((size_t)H, sizeof(double)),
+                         calloc(nv, sizeof(double)), d_x };
+        memset(d_x, 0, sizeof(float) * (size_t)n_nodes * H);
+        int max_h = 0;
+        for (int t = 0; t < n_trees; ++t) if (height[root[t]] > max_h) max_h = height[root[t]];
+        double *scratch = malloc(sizeof(double) * (size_t)7 * H * (size_t)(max_h + 2));     /* dz, a, da, dhl, dhr per level */
+        double *dh = malloc(sizeof(double) * (size_t)H);
+        for (int t = 0; t < n_trees; ++t) {
+            for (int j = 0; j < H; ++j) dh[j] = (double)g_h[(size_t)root[t] * H + j];
+            backward_rntn_node(&m, root[t], dh, scratch);
+        }
+        for (size_t i = 0; i < nw; ++i) d_w[i] = (float)m.d_w[i];
+        for (int j = 0; j < H; ++j) d_b[j] = (float)m.d_b[j];
+        for (size_t i = 0; i < nv; ++i) d_v[i] = (float)m.d_v[i];
+        free(m.d_w); free(m.d_b); free(m.d_v); free(scratch); free(dh);
+    }
+    free(parent); free(height); free(root);
+    return rc;
+}

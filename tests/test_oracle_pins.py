@@ -849,3 +849,69 @@ def test_treernn_backward_matches_autograd_and_finite_differences():
     two = oracle.backward(p, trees, fwd["h"], None, 2 * g_h)
     for k in got:
         assert np.allclose(two[k], 2 * got[k], rtol=1e-6, atol=1e-9)
+
+
+# ---- RNTN backward ----------------------------------------------------------------------------
+
+def _rntn_case(seed, d, leaves, shapes):
+    p = synth.make_rnn_params(seed, CELL_RNTN, 19, d, scale=0.5)
+    p = Params(p.cell, p.vocab, d, d, p.emb, None, None, p.u, p.b + 0.05, p.v)
+    trees = synth.make_trees(seed, leaves, shapes, 19)
+    fwd = oracle.forward_params(p, trees)
+    rng = np.random.default_rng(seed)
+    g_h = rng.standard_normal(fwd["h"].shape).astype(np.float32)
+    g_h[rng.random(len(g_h)) < 0.3] = 0.0
+    return p, trees, fwd, g_h
+
+
+def _torch_rntn_loss(p, trees, g_h, **override):
+    t = {k: torch.tensor(override.get(k, getattr(p, k)), dtype=torch.float64, requires_grad=True) for k in ("emb", "u", "b", "v")}
+    g = torch.tensor(g_h, dtype=torch.float64)
+    loss = torch.zeros((), dtype=torch.float64)
+
+    def ev(n):
+        nonlocal loss
+        if trees.left[n] < 0:
+            h = t["emb"][int(trees.word[n])] * 1.0
+        else:
+            a = torch.cat([ev(int(trees.left[n])), ev(int(trees.right[n]))])
+            h = torch.tanh(torch.einsum("p,kpq,q->k", a, t["v"], a) + a @ t["u"] + t["b"])
+        loss = loss + (g[n] * h).sum()
+        return h
+
+    _, root, _ = oracle.structure(trees.tree_off, trees.left, trees.right)
+    for r in root:
+        ev(int(r))
+    return loss, t
+
+
+def test_rntn_backward_matches_autograd_and_finite_differences():
+    """d_v, d_u (= dW), d_b and the per-leaf embedding gradients against torch autograd through an independent
+    float64 evaluation (einsum for the bilinear form); a sample of tensor entries against central differences."""
+    for seed, d, leaves, shapes in ((1, 3, [1, 2, 6], ["random"] * 3), (2, 4, [7, 4], ["chain", "balanced"]), (3, 2, [10], ["random"])):
+        p, trees, fwd, g_h = _rntn_case(seed, d, leaves, shapes)
+        got = oracle.backward(p, trees, fwd["h"], None, g_h)
+        loss, t = _torch_rntn_loss(p, trees, g_h)
+        loss.backward()
+        for key, name in (("d_u", "u"), ("d_b", "b"), ("d_v", "v")):
+            assert np.allclose(got[key], t[name].grad.numpy(), rtol=2e-4, atol=2e-6), (seed, key)
+        d_emb = np.zeros_like(p.emb, dtype=np.float64)
+        for n in np.nonzero(trees.left < 0)[0]:
+            d_emb[trees.word[n]] += got["d_x"][n]
+        assert np.allclose(d_emb, t["emb"].grad.numpy(), rtol=2e-4, atol=2e-6)
+        assert not got["d_x"][trees.left >= 0].any()
+    p, trees, fwd, g_h = _rntn_case(7, 2, [3, 2], ["random", "random"])
+    got = oracle.backward(p, trees, fwd["h"], None, g_h)
+    eps = 1e-6
+    base = p.v.astype(np.float64)
+    for idx in list(np.ndindex(base.shape))[::3]:
+        vals = []
+        for s in (+eps, -eps):
+            v = base.copy()
+            v[idx] += s
+            with torch.no_grad():
+                vals.append(float(_torch_rntn_loss(p, trees, g_h, v=v)[0]))
+        fd = (vals[0] - vals[1]) / (2 * eps)
+        assert abs(fd - got["d_v"][idx]) <= 1e-5 + 1e-4 * abs(fd), (idx, fd, got["d_v"][idx])
+    zero = oracle.backward(p, trees, fwd["h"], None, np.zeros_like(g_h))
+    assert all(not x.any() for x in zero.values())
