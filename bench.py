@@ -216,11 +216,14 @@ def backward_stage(w, n_classes, reps=10):
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) / reps * 1e3
 
-        ms = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
+        rntn = w.params.cell == 2
+        ms = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E, rntn=rntn), reps)
         if w.params.cell == 0:
             flops = 60.0 * H * H * w.trees.n_internal + 18.0 * E * H * w.trees.n_leaves
-        else:                       # TreeRNN: operand gradient and weight gradient, 4 H^2 each per internal node
+        elif w.params.cell == 1:    # TreeRNN: operand gradient and weight gradient, 4 H^2 each per internal node
             flops = 8.0 * H * H * w.trees.n_internal
+        else:                       # RNTN: both contractions run over rows of d * 2d + d values, 2d outputs
+            flops = 2.0 * 2.0 * (H * 2 * H + H) * 2 * H * w.trees.n_internal
         out = {"ms": ms, "flops": flops, "tflops": flops / (ms * 1e-3) / 1e12,
                "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_TFLOPS["f32"]}
         # training mode: the forward keeps the gate activations, the backward does not recompute the contraction
@@ -240,10 +243,10 @@ def backward_stage(w, n_classes, reps=10):
             def train_step(lr=0.0):
                 net.forward()
                 hb = binding.tl_classify_backward(net.ctx, b["h"], ws, bs, label)
-                grads = binding.tl_backward(net.ctx, b, hb["g_h"], E)
+                grads = binding.tl_backward(net.ctx, b, hb["g_h"], E, rntn=rntn)
                 binding.tl_sgd_update(net.ctx, lr, b, grads)           # lr = 0: all the work, parameters unchanged
 
-            grads0 = binding.tl_backward(net.ctx, b, g_h, E)
+            grads0 = binding.tl_backward(net.ctx, b, g_h, E, rntn=rntn)
             out["sgd_update_ms"] = wall(lambda: binding.tl_sgd_update(net.ctx, 0.0, b, grads0), reps)
             step_ms = wall(train_step, reps)
             out["train_step_ms"] = step_ms
@@ -429,7 +432,7 @@ def main():
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
     if args.head > 0:
         out["head"] = head_stage(w, args.head)
-    if args.backward and w.params.cell in (0, 1) and args.precision == "f32":
+    if args.backward and args.precision == "f32":
         out["backward"] = backward_stage(w, args.head)
     if not args.no_compare:
         comp = {}

@@ -187,7 +187,7 @@ int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
 int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
 
 /*
- * Backward pass of a TL_TREELSTM or TL_TREERNN forward in TL_F32 (Section 4.2.2, recursive
+ * Backward pass of a forward in TL_F32, for all three cells (Section 4.2.2, recursive
  * backpropagation: the gradient of a node's cell is applied from the roots down, each node
  * finding its forward values by node index).  The loss may depend on every node's h:
  * g_h[n] = dL/dh[n] (zero rows where it does not).  h and c are the rows tl_forward wrote for
@@ -197,15 +197,18 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
  *   g_h       [n_nodes x H] fp32                                                  DEVICE, read-only
  *   d_u       [2H x 5H], d_b [5H], d_w_leaf [E x 3H], d_b_leaf [3H]  fp32 out,
  *             sums over all nodes of the batch, same layouts as the parameters    DEVICE
- *             (TL_TREERNN: d_u [2H x H], d_b [H]; d_w_leaf, d_b_leaf unused, may be NULL)
+ *             (TL_TREERNN: d_u [2H x H], d_b [H]; d_w_leaf, d_b_leaf unused, may be NULL.
+ *             TL_RNTN: d_u [2d x d] for W, d_b [d], and d_w_leaf receives the gradient of the
+ *             tensor V, [d x 2d x 2d]; d_b_leaf unused.)
  *   d_x       [n_nodes x E] fp32 out: row n = dL/d(embedding row used by leaf n);
  *             rows of internal nodes are zero (the caller scatter-adds by word)    DEVICE
  * fp32 arithmetic; the TreeLSTM gate activations are recomputed from h / c unless the forward
- * kept them (tl_set_keep_gates); the TreeRNN needs nothing but h.
+ * kept them (tl_set_keep_gates); TreeRNN and RNTN need nothing but h.  The RNTN path is a first
+ * version: it materialises a row of d * 2d + d values per internal node (workspace of that size).
  * Work is enqueued on hip_stream, but the call waits for the structure pass (it needs the
  * number of heights) and returns the deferred structure status: TL_OK, TL_ESTRUCT, ...
- * The first call for a larger batch than any before allocates workspace.  TL_RNTN or
- * TL_BF16_IN: TL_EINVAL.
+ * The first call for a larger batch than any before allocates workspace (TL_ENOMEM if the RNTN
+ * rows would take more than 64 GiB).  TL_BF16_IN: TL_EINVAL.
  */
 int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
                 const int32_t *right, const int32_t *word, const float *h, const float *c, const float *g_h,
@@ -222,8 +225,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
  * enqueued on hip_stream and nothing is allocated.  Dense parameters change exactly as the
  * formula says in fp32 (product rounded, then difference); embedding rows shared by several
  * leaves are updated with atomics.  Calls on one context must be ordered with its forwards
- * and backwards (same stream, or synchronised).  TL_TREELSTM or TL_TREERNN (u, b and the
- * embedding only; d_w_leaf, d_b_leaf may be NULL) in TL_F32, else TL_EINVAL.
+ * and backwards (same stream, or synchronised).  TL_F32 only, else TL_EINVAL; TL_TREERNN has
+ * u, b and the embedding only (d_w_leaf, d_b_leaf may be NULL), TL_RNTN takes the gradient of
+ * V in d_w_leaf, as tl_backward writes it.
  */
 int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const int32_t *word, const float *d_u,
                   const float *d_b, const float *d_w_leaf, const float *d_b_leaf, const float *d_x, void *hip_stream);
@@ -231,8 +235,9 @@ int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const
 /*
  * Copies the context's current parameters to the caller's DEVICE buffers (any of them may be
  * NULL): u [2H x 5H], b [5H], w_leaf [E x 3H], b_leaf [3H], emb [vocab x E], fp32, the layouts
- * tl_create takes (TL_TREERNN: u [2H x H], b [H]; w_leaf and b_leaf must be NULL).
- * Asynchronous on hip_stream.  TL_TREELSTM or TL_TREERNN in TL_F32, else TL_EINVAL.
+ * tl_create takes (TL_TREERNN: u [2H x H], b [H]; w_leaf and b_leaf must be NULL.  TL_RNTN:
+ * u = W [2d x d], b [d], w_leaf receives V [d x 2d x 2d], b_leaf must be NULL).
+ * Asynchronous on hip_stream.  TL_F32 only, else TL_EINVAL.
  */
 int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream);
 

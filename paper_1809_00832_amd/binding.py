@@ -143,10 +143,11 @@ def tl_last_stats(ctx):
     return {"n_levels": a.value, "n_tiles": b.value, "n_workgroups": c.value}
 
 
-def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
+def tl_backward(ctx, batch, g_h, embed_dim, rntn=False, stream=None):
     """Gradients for a batch that tl_forward has evaluated (`batch` is the dict TreeNet.load returns, holding h and
     c); g_h [N x H] float32 CUDA tensor.  Returns dict(d_u, d_b, d_w_leaf, d_b_leaf, d_x) of CUDA tensors for a
-    TreeLSTM, dict(d_u [2H x H], d_b [H], d_x) for a TreeRNN (batch["c"] is None there)."""
+    TreeLSTM, dict(d_u [2H x H], d_b [H], d_x) for a TreeRNN (batch["c"] is None there), and with rntn=True also
+    d_w_leaf [d x 2d x 2d], the gradient of the tensor V."""
     import torch
     N, H, E = batch["N"], int(batch["h"].shape[1]), int(embed_dim)
     assert g_h.is_cuda and g_h.dtype == torch.float32 and g_h.is_contiguous() and tuple(g_h.shape) == (N, H)
@@ -158,6 +159,8 @@ def tl_backward(ctx, batch, g_h, embed_dim, stream=None):
     if lstm:
         out["d_w_leaf"] = torch.empty((E, 3 * H), device=dev)
         out["d_b_leaf"] = torch.empty(3 * H, device=dev)
+    elif rntn:
+        out["d_w_leaf"] = torch.empty((H, 2 * H, 2 * H), device=dev)        # gradient of the tensor V
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib().tl_backward(ctx, batch["B"], N, batch["tree_off"].data_ptr(), batch["left"].data_ptr(),
                              batch["right"].data_ptr(), batch["word"].data_ptr(), batch["h"].data_ptr(),
@@ -179,7 +182,7 @@ def tl_sgd_update(ctx, lr, batch, grads, with_embedding=True, stream=None) -> No
 
 def tl_get_params(ctx, vocab, embed_dim, hidden, cell=TL_TREELSTM, stream=None):
     """The context's current parameters as new CUDA tensors: dict(u, b, w_leaf, b_leaf, emb); dict(u, b, emb) for a
-    TreeRNN."""
+    TreeRNN; dict(u, b, w_leaf = V [d x 2d x 2d], emb) for an RNTN."""
     import torch
     H, E = int(hidden), int(embed_dim)
     ng = 5 if cell == TL_TREELSTM else 1
@@ -187,6 +190,8 @@ def tl_get_params(ctx, vocab, embed_dim, hidden, cell=TL_TREELSTM, stream=None):
     out = {"u": new(2 * H, ng * H), "b": new(ng * H), "emb": new(int(vocab), E)}
     if cell == TL_TREELSTM:
         out["w_leaf"], out["b_leaf"] = new(E, 3 * H), new(3 * H)
+    elif cell == TL_RNTN:
+        out["w_leaf"] = new(H, 2 * H, 2 * H)
     st = (stream or torch.cuda.current_stream()).cuda_stream
     _check(lib().tl_get_params(ctx, out["u"].data_ptr(), out["b"].data_ptr(), _ptr(out.get("w_leaf")), _ptr(out.get("b_leaf")),
                                out["emb"].data_ptr(), st), "tl_get_params")

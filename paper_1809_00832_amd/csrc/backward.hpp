@@ -181,6 +181,72 @@ __global__ void k_rnn_leaf_grad(Fwd f)
     }
 }
 
+// ---- RNTN (h_k = tanh(a^T V_k a + (a W)_k + b_k)) -----------------------------------------------
+// With dz = dh (1 - h^2) and the row y = [ dz_k a_q for all (k, q) | dz ] of length d * 2d + d per node, both
+// gradients are ordinary contractions that the kernels above already do:
+//   da = y S          S[(k, q)][p] = V[k][p][q] + V[k][q][p],  S[d * 2d + k][p] = W[p][k]       (operand gradient)
+//   sum_n a_n^T y_n   gives dV (as [p][(k, q)]) and dW (the last d columns), its column sums db   (weight gradient)
+// k_rntn_build_s makes S from the parameters, k_rntn_rows the rows y of the listed nodes, k_rntn_unpack puts the
+// weight-gradient contraction back into the layouts of V, W and b.
+__global__ void k_rntn_build_s(const float *__restrict__ v, const float *__restrict__ w, float *__restrict__ s, int d)
+{
+    const int D2 = 2 * d;
+    const size_t total = ((size_t)d * D2 + d) * D2;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const int p = (int)(e % D2);
+        const size_t r = e / D2;
+        if (r < (size_t)d * D2) {
+            const int k = (int)(r / D2), q = (int)(r - (size_t)k * D2);
+            s[e] = v[((size_t)k * D2 + p) * D2 + q] + v[((size_t)k * D2 + q) * D2 + p];
+        } else {
+            const int k = (int)(r - (size_t)d * D2);
+            s[e] = w[(size_t)p * d + k];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_rntn_rows(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+{
+    const int d = f.H, D2 = 2 * d;
+    const int L = d * D2 + d;
+    const long long total = (long long)n_rows * L;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+        const int row = (int)(e / L), j = (int)(e - (long long)row * L);
+        const int node = list[row];
+        const int k = j < d * D2 ? j / D2 : j - d * D2;
+        const float hv = f.h[(size_t)node * d + k];
+        const float dz = f.dh[(size_t)node * d + k] * (1.f - hv * hv);
+        float y = dz;
+        if (j < d * D2) {
+            const int q = j - k * D2;
+            const int child = q < d ? f.left[node] : f.right[node];
+            y = dz * f.h[(size_t)child * d + (q < d ? q : q - d)];
+        }
+        f.dg[(size_t)(pos0 + row) * L + j] = y;
+    }
+}
+
+// acc [2d x (d * 2d + d)] = sum_n a_n^T y_n, colsum [d * 2d + d] = sum_n y_n  ->  d_v [d][2d][2d], d_w [2d][d], d_b [d]
+__global__ void k_rntn_unpack(const float *__restrict__ acc, const float *__restrict__ colsum, float *__restrict__ d_v,
+                              float *__restrict__ d_w, float *__restrict__ d_b, int d)
+{
+    const int D2 = 2 * d, L = d * D2 + d;
+    const size_t n_v = (size_t)d * D2 * D2, total = n_v + (size_t)D2 * d + d;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        if (e < n_v) {
+            const int q = (int)(e % D2), p = (int)((e / D2) % D2), k = (int)(e / ((size_t)D2 * D2));
+            d_v[e] = acc[(size_t)p * L + (size_t)k * D2 + q];
+        } else if (e < n_v + (size_t)D2 * d) {
+            const size_t r = e - n_v;
+            const int k = (int)(r % d), p = (int)(r / d);
+            d_w[r] = acc[(size_t)p * L + (size_t)d * D2 + k];
+        } else {
+            const int k = (int)(e - n_v - (size_t)D2 * d);
+            d_b[k] = colsum[(size_t)d * D2 + k];
+        }
+    }
+}
+
 // out[r][c] = in[c][r] for a row-major [rows x cols] input
 __global__ void k_transpose(const float *__restrict__ in, float *__restrict__ out, int rows, int cols)
 {

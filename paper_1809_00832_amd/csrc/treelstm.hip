@@ -68,6 +68,8 @@ struct tl_ctx {
     int bw_nodes = 0;
     float *m_u = nullptr, *m_b = nullptr, *m_w_leaf = nullptr, *m_b_leaf = nullptr;   // fp32 TreeLSTM: the parameters themselves
     float *t_scratch = nullptr, *zero_bias = nullptr;
+    float *m_v = nullptr;             // fp32 RNTN: the tensor V as given
+    float *rntn_acc = nullptr;        // RNTN backward: [2d x (d * 2d + d)] weight-gradient contraction and its column sums
     int ws_steps16 = 0;
     bool keep_gates = false;          // tl_set_keep_gates
     float *gates = nullptr;           // [gates_cap x 5H] gate activations of the last forward that kept them
@@ -336,6 +338,39 @@ int pack_treernn_f32(tl_ctx *ctx, hipStream_t st)
     return TL_OK;
 }
 
+// The same for an fp32 RNTN context: the forward's packed tensor slices, and the matrix S of the operand gradient
+// (see backward.hpp) packed like transposed weights.
+int pack_rntn_f32(tl_ctx *ctx, hipStream_t st)
+{
+    const int H = ctx->cfg.hidden, D2 = 2 * H, L = H * D2 + H;
+    const int Lp = round_up(H, 4);
+    int Kp = round_up(2 * Lp, KC);
+    if (Kp > 128) Kp = 256;
+    const size_t n_v = (size_t)ctx->n_cg * (Kp + 1) * (Kp / STEP_K) * 256;
+    if (!ctx->wp_inner) TL_HIP(hipMalloc(&ctx->wp_inner, n_v * sizeof(float)));
+    if (!ctx->bp_inner) TL_HIP(hipMalloc(&ctx->bp_inner, (size_t)ctx->n_cg * HU * sizeof(float)));
+    hipLaunchKernelGGL(k_pack_rntn, dim3(2048), dim3(256), 0, st, (const float *)ctx->m_v, (const float *)ctx->m_u, (float *)ctx->wp_inner,
+                       H, Lp, Kp, ctx->n_cg);
+    hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, st, (const float *)ctx->m_b, ctx->bp_inner, 1, H, ctx->n_cg);
+    TL_HIP(hipGetLastError());
+    ctx->g_inner.wp = ctx->wp_inner;
+    ctx->g_inner.bp = ctx->bp_inner;
+    ctx->g_inner.L = H;
+    ctx->g_inner.Lp = Lp;
+    ctx->g_inner.n_chunks = Kp / KC;
+    hipLaunchKernelGGL(k_rntn_build_s, dim3(2048), dim3(256), 0, st, (const float *)ctx->m_v, (const float *)ctx->m_u, ctx->t_scratch, H);
+    int rc = pack_gemm(ctx->t_scratch, ctx->zero_bias, ctx->ng_bwd_inner, D2 / ctx->ng_bwd_inner, 1, L,
+                       (D2 / ctx->ng_bwd_inner + HU - 1) / HU, 0, false, &ctx->g_bwd_inner, &ctx->wp_bwd_inner, &ctx->bp_bwd_inner, st);
+    if (rc != TL_OK) return rc;
+    if (ctx->ng_bwd_inner == 4) {
+        rc = pack_gemm(ctx->t_scratch, ctx->zero_bias, 1, D2, 1, L, (D2 + HU - 1) / HU, 0, false, &ctx->g_bwd_inner1, &ctx->wp_bwd_inner1,
+                       &ctx->bp_bwd_inner1, st);
+        if (rc != TL_OK) return rc;
+    }
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Workspace for batches of up to n_nodes nodes / n_trees trees.
@@ -411,6 +446,8 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->m_b_leaf);
     (void)hipFree(ctx->t_scratch);
     (void)hipFree(ctx->zero_bias);
+    (void)hipFree(ctx->m_v);
+    (void)hipFree(ctx->rntn_acc);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -518,24 +555,22 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         rc = pack_gemm(cfg->u, cfg->b, 1, H, 2, H, ctx->n_cg, ws_steps16, bf16, &ctx->g_inner, &ctx->wp_inner, &ctx->bp_inner);
         if (rc != TL_OK) return rc;
     } else {
-        // RNTN: tensor slices and W packed per column group and q; padded K is 64, 128 or 256
-        const int Lp = round_up(H, 4);
-        int Kp = round_up(2 * Lp, KC);
-        if (Kp > 128) Kp = 256;
-        const size_t n_v = (size_t)ctx->n_cg * (Kp + 1) * (Kp / STEP_K) * 256;
-        float *vp = nullptr, *bp = nullptr;
-        TL_HIP(hipMalloc(&vp, n_v * sizeof(float)));
-        ctx->wp_inner = vp;
-        TL_HIP(hipMalloc(&bp, (size_t)ctx->n_cg * HU * sizeof(float)));
-        ctx->bp_inner = bp;
-        hipLaunchKernelGGL(k_pack_rntn, dim3(2048), dim3(256), 0, 0, cfg->v, cfg->u, vp, H, Lp, Kp, ctx->n_cg);
-        hipLaunchKernelGGL(k_pack_bias, dim3(64), dim3(256), 0, 0, cfg->b, bp, 1, H, ctx->n_cg);
-        TL_HIP(hipGetLastError());
-        ctx->g_inner.wp = vp;
-        ctx->g_inner.bp = bp;
-        ctx->g_inner.L = H;
-        ctx->g_inner.Lp = Lp;
-        ctx->g_inner.n_chunks = Kp / KC;
+        // RNTN (fp32 only): the parameters as given, tensor slices and W packed per column group and q (padded K is
+        // 64, 128 or 256), and what the backward pass derives from them
+        const size_t D2 = (size_t)2 * H, L = (size_t)H * D2 + H;
+        TL_HIP(hipMalloc(&ctx->m_v, (size_t)H * D2 * D2 * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->m_u, D2 * H * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->m_b, (size_t)H * sizeof(float)));
+        TL_HIP(hipMemcpy(ctx->m_v, cfg->v, (size_t)H * D2 * D2 * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMemcpy(ctx->m_u, cfg->u, D2 * H * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMemcpy(ctx->m_b, cfg->b, (size_t)H * sizeof(float), hipMemcpyDeviceToDevice));
+        TL_HIP(hipMalloc(&ctx->t_scratch, L * D2 * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->rntn_acc, (D2 * L + L) * sizeof(float)));
+        TL_HIP(hipMalloc(&ctx->zero_bias, (D2 + HU) * sizeof(float)));
+        TL_HIP(hipMemset(ctx->zero_bias, 0, (D2 + HU) * sizeof(float)));
+        ctx->ng_bwd_inner = D2 % 4 == 0 ? 4 : 1;
+        rc = pack_rntn_f32(ctx, nullptr);
+        if (rc != TL_OK) return rc;
     }
     TL_HIP(hipDeviceSynchronize());
 
@@ -842,9 +877,10 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
 {
     if (!ctx || !tree_off || !left || !right || !word || !h || !g_h || !d_u || !d_b || !d_x) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
-    const bool lstm = cfg.cell == TL_TREELSTM;
+    if (cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM, rntn = cfg.cell == TL_RNTN;
     if (lstm && (!c || !d_w_leaf || !d_b_leaf)) return TL_EINVAL;
+    if (rntn && !d_w_leaf) return TL_EINVAL;                  // dV
     if (n_trees < 1 || n_nodes < n_trees) return TL_EINVAL;
     if (((long long)n_nodes + n_trees) % 2 != 0) return TL_ESTRUCT;
     hipStream_t st = (hipStream_t)hip_stream;
@@ -853,12 +889,17 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     const int H = cfg.hidden, E = cfg.embed_dim;
     const int n_leaf = (int)(((long long)n_nodes + n_trees) / 2), n_int = n_nodes - n_leaf;
     // workspace of the backward pass: dh, dc [N x H], gate gradients [n_int x 5H] and [n_leaf x 3H]
+    // (RNTN: rows of d * 2d + d values per internal node, see backward.hpp)
+    const size_t rntn_row = (size_t)H * 2 * H + H;
     if (n_nodes > ctx->bw_nodes) {
         TL_HIP(hipDeviceSynchronize());
         if (ctx->bw) { TL_HIP(hipFree(ctx->bw)); ctx->bw = nullptr; }
         ctx->bw_nodes = 0;
         const size_t cap = (size_t)ctx->cap_nodes;
-        TL_HIP(hipMalloc(&ctx->bw, (2 * cap * H + cap * 5 * H) * sizeof(float)));   // n_int*5H + n_leaf*3H <= N*5H
+        size_t floats = 2 * cap * H + cap * 5 * H;                                   // n_int*5H + n_leaf*3H <= N*5H
+        if (rntn) floats = 2 * cap * H + (cap / 2 + 1) * rntn_row;
+        if (floats * sizeof(float) > ((size_t)64 << 30)) return TL_ENOMEM;
+        TL_HIP(hipMalloc(&ctx->bw, floats * sizeof(float)));
         ctx->bw_nodes = ctx->cap_nodes;
     }
     Fwd f{};
@@ -876,6 +917,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     f.dc = f.dh + cap * H;
     const int ng_cell = lstm ? 5 : 1;                         // gate blocks of an internal node
     float *dg_int = f.dc + cap * H, *dg_leaf = dg_int + (size_t)n_int * ng_cell * H;
+    const int dg_cols = rntn ? (int)rntn_row : ng_cell * H;   // length of a row of dg_int
     f.d_x = d_x;
     ctx->last = f;
     ctx->last_stream = st;
@@ -898,7 +940,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         z.p[1] = d_x;      z.n[1] = (size_t)n_nodes * E;
         z.p[2] = d_b;      z.n[2] = (size_t)ng_cell * H;
         z.p[3] = d_b_leaf; z.n[3] = lstm ? (size_t)3 * H : 0;
-        z.p[4] = d_u;      z.n[4] = (size_t)2 * H * ng_cell * H;
+        z.p[4] = rntn ? ctx->rntn_acc : d_u;   z.n[4] = rntn ? (size_t)2 * H * rntn_row + rntn_row : (size_t)2 * H * ng_cell * H;
         z.p[5] = d_w_leaf; z.n[5] = lstm ? (size_t)E * 3 * H : 0;
         hipLaunchKernelGGL(k_zero_many, dim3(1024), dim3(256), 0, st, z);
     }
@@ -929,7 +971,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
             Fwd g = f;
             g.dg = dg_int;
             g.pos0 = lo;
-            if (!lstm) {
+            if (rntn) {
+                long long blocks = ((long long)rows * dg_cols + 255) / 256;
+                if (blocks > 16LL * ctx->n_cu) blocks = 16LL * ctx->n_cu;
+                hipLaunchKernelGGL(k_rntn_rows, dim3((unsigned)blocks), dim3(256), 0, st, g, (const int32_t *)(f.level_nodes + lo), rows, lo);
+            } else if (!lstm) {
                 typedef void (*rnn_kernel)(Fwd, const int32_t *, int, int);
                 const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
                 long long blocks = ((long long)rows * (v4 ? H / 4 : H) + 255) / 256;
@@ -947,7 +993,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
             g.bwd = (ctx->ng_bwd_inner == 4 && ng == 1) ? ctx->g_bwd_inner1 : ctx->g_bwd_inner;
             g.out_cols = 2 * H;
             g.n_cg = (2 * H / ng + HU - 1) / HU;
-            hipLaunchKernelGGL(backward_kernel(ng == 4 ? EPI_BWD_INNER_OPERAND4 : EPI_BWD_INNER_OPERAND, vec4),
+            hipLaunchKernelGGL(backward_kernel(ng == 4 ? EPI_BWD_INNER_OPERAND4 : EPI_BWD_INNER_OPERAND, vec4 && dg_cols % 4 == 0),
                                dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
                                TILE_SMEM_BYTES, st, g, (const int32_t *)(f.level_nodes + lo), rows, plan);
         }
@@ -980,12 +1026,16 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         return z < 1 ? 1 : z;
     };
     if (n_int > 0) {
-        const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (ng_cell * H + WG_TILE - 1) / WG_TILE, 1);
-        const bool v4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
+        const dim3 grid((2 * H + WG_TILE - 1) / WG_TILE, (dg_cols + WG_TILE - 1) / WG_TILE, 1);
+        const bool v4 = H % 4 == 0 && dg_cols % 4 == 0 && (((uintptr_t)h & 15) == 0);
         const wgrad_kernel wk = v4 ? wgrad_kernel(k_weight_grad<2, true>) : wgrad_kernel(k_weight_grad<2, false>);
+        float *acc = rntn ? ctx->rntn_acc : d_u, *colsum = rntn ? ctx->rntn_acc + (size_t)2 * H * rntn_row : d_b;
         hipLaunchKernelGGL(wk, dim3(grid.x, grid.y, slices(grid.x * grid.y, n_int)), dim3(256), 0, st, f,
-                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, ng_cell * H, d_u, d_b);
+                           (const int32_t *)f.level_nodes, n_int, (const float *)h, H, (const float *)dg_int, dg_cols, acc, colsum);
     }
+    if (rntn)      // back into the layouts of V, W and b (all zero when the batch has no internal node)
+        hipLaunchKernelGGL(k_rntn_unpack, dim3(1024), dim3(256), 0, st, (const float *)ctx->rntn_acc,
+                           (const float *)(ctx->rntn_acc + (size_t)2 * H * rntn_row), d_w_leaf, d_u, d_b, H);
     if (lstm) {
         const dim3 grid((E + WG_TILE - 1) / WG_TILE, (3 * H + WG_TILE - 1) / WG_TILE, 1);
         const bool v4 = E % 4 == 0 && H % 4 == 0;
@@ -1003,36 +1053,39 @@ int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const
 {
     if (!ctx || !d_u || !d_b) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
-    const bool lstm = cfg.cell == TL_TREELSTM;
+    if (cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM, rntn = cfg.cell == TL_RNTN;
     if (lstm && (!d_w_leaf || !d_b_leaf)) return TL_EINVAL;
+    if (rntn && !d_w_leaf) return TL_EINVAL;
     if (d_x && (!left || !word || n_nodes < 1)) return TL_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     const int H = cfg.hidden, E = cfg.embed_dim, ng_cell = lstm ? 5 : 1;
     SgdList z{};
     z.theta[0] = ctx->m_u;      z.grad[0] = d_u;      z.n[0] = (size_t)2 * H * ng_cell * H;
     z.theta[1] = ctx->m_b;      z.grad[1] = d_b;      z.n[1] = (size_t)ng_cell * H;
-    z.theta[2] = ctx->m_w_leaf; z.grad[2] = d_w_leaf; z.n[2] = lstm ? (size_t)E * 3 * H : 0;
+    z.theta[2] = lstm ? ctx->m_w_leaf : ctx->m_v; z.grad[2] = d_w_leaf; z.n[2] = lstm ? (size_t)E * 3 * H : rntn ? (size_t)H * 4 * H * H : 0;
     z.theta[3] = ctx->m_b_leaf; z.grad[3] = d_b_leaf; z.n[3] = lstm ? (size_t)3 * H : 0;
     hipLaunchKernelGGL(k_sgd_dense, dim3(1024), dim3(256), 0, st, z, lr);
     if (d_x) hipLaunchKernelGGL(k_sgd_embedding, dim3(1024), dim3(256), 0, st, ctx->emb, d_x, left, word, n_nodes, E, cfg.vocab, lr);
     TL_HIP(hipGetLastError());
     ctx->gates_nodes = 0;             // what a forward kept belongs to the old parameters
-    return lstm ? pack_treelstm_f32(ctx, st) : pack_treernn_f32(ctx, st);
+    return lstm ? pack_treelstm_f32(ctx, st) : rntn ? pack_rntn_f32(ctx, st) : pack_treernn_f32(ctx, st);
 }
 
 int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream)
 {
     if (!ctx) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
-    if ((cfg.cell != TL_TREELSTM && cfg.cell != TL_TREERNN) || cfg.precision != TL_F32) return TL_EINVAL;
-    const bool lstm = cfg.cell == TL_TREELSTM;
-    if (!lstm && (w_leaf || b_leaf)) return TL_EINVAL;
+    if (cfg.precision != TL_F32) return TL_EINVAL;
+    const bool lstm = cfg.cell == TL_TREELSTM, rntn = cfg.cell == TL_RNTN;
+    if (!lstm && b_leaf) return TL_EINVAL;
+    if (!lstm && !rntn && w_leaf) return TL_EINVAL;
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t H = cfg.hidden, E = cfg.embed_dim, ng_cell = lstm ? 5 : 1;
     if (u) TL_HIP(hipMemcpyAsync(u, ctx->m_u, 2 * H * ng_cell * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (b) TL_HIP(hipMemcpyAsync(b, ctx->m_b, ng_cell * H * sizeof(float), hipMemcpyDeviceToDevice, st));
-    if (w_leaf) TL_HIP(hipMemcpyAsync(w_leaf, ctx->m_w_leaf, E * 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (w_leaf && rntn) TL_HIP(hipMemcpyAsync(w_leaf, ctx->m_v, H * 4 * H * H * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (w_leaf && lstm) TL_HIP(hipMemcpyAsync(w_leaf, ctx->m_w_leaf, E * 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (b_leaf) TL_HIP(hipMemcpyAsync(b_leaf, ctx->m_b_leaf, 3 * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     if (emb) TL_HIP(hipMemcpyAsync(emb, ctx->emb, (size_t)cfg.vocab * E * sizeof(float), hipMemcpyDeviceToDevice, st));
     return TL_OK;

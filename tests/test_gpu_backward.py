@@ -141,13 +141,13 @@ def test_backward_argument_checks():
             binding.tl_backward(net.ctx, b, torch.zeros((w.trees.n_nodes, w.params.hidden), device="cuda"), w.params.embed_dim)
     finally:
         net.close()
-    w4 = synth.workload("rntn")
+    w4 = synth.workload("treernn")
     net = binding.TreeNet(w4.params, scheduler="level_device")
     try:
         b = net.load(w4.trees)
         L = binding.lib()
         p = b["h"].data_ptr()
-        assert L.tl_backward(net.ctx, b["B"], b["N"], *([p] * 13), None) == binding.TL_EINVAL      # no backward for the RNTN
+        assert L.tl_backward(net.ctx, b["B"], b["N"], *([p] * 6), None, *([p] * 6), None) == binding.TL_EINVAL      # g_h missing
     finally:
         net.close()
 
@@ -281,6 +281,65 @@ def test_treernn_backward_matches_oracle():
     finally:
         net.close()
     q = synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, new["emb"], None, None, new["u"], new["b"], None)
+    fresh = binding.TreeNet(q, scheduler="level_device")
+    try:
+        assert np.array_equal(fresh.run(sub)["h"], h_after)
+    finally:
+        fresh.close()
+
+
+def run_rntn_case(params, trees, seed, what):
+    rng = np.random.default_rng(seed)
+    net = binding.TreeNet(params, scheduler="level_device")
+    try:
+        b = net.load(trees)
+        net.forward()
+        assert binding.tl_status(net.ctx) == 0
+        g_h = rng.standard_normal((trees.n_nodes, params.hidden)).astype(np.float32)
+        g_h[rng.random(trees.n_nodes) < 0.3] = 0.0
+        got = binding.tl_backward(net.ctx, b, torch.from_numpy(g_h).cuda(), params.embed_dim, rntn=True)
+        torch.cuda.synchronize()
+        assert binding.tl_status(net.ctx) == 0
+        got = {k: v.cpu().numpy() for k, v in got.items()}
+        h = b["h"].cpu().numpy()
+    finally:
+        net.close()
+    ref = oracle.backward(params, trees, h, None, g_h)
+    rel = {k: assert_grad_close(got["d_w_leaf" if k == "d_v" else k], ref[k], "%s %s" % (what, k)) for k in ref}
+    print("   ", what, {k: "%.1e" % v for k, v in rel.items()}, flush=True)
+    assert not got["d_x"][trees.left >= 0].any()
+
+
+def test_rntn_backward_matches_oracle():
+    """RNTN: gradients of V, W, b and of every leaf's embedding row against the checker, on ragged sizes and on the
+    first trees of the `rntn` workload (d = 64); then an SGD step: parameters as the formula says, and the next
+    forward equals that of a fresh context."""
+    print("case rntn backward", flush=True)
+    for i, (d, leaves) in enumerate([(3, [1]), (5, [1, 1, 2]), (8, [2, 9]), (12, [1, 2, 3, 1, 40, 5]), (32, [17] * 5 + [1] + [70])]):
+        params = synth.make_rnn_params(95 + i, synth.CELL_RNTN, 50, d, scale=0.4)
+        trees = synth.make_trees(95 + i, leaves, ["random"] * len(leaves), 50)
+        run_rntn_case(params, trees, 95 + i, "rntn ragged%d" % i)
+    w = synth.workload("rntn")
+    sub, _ = synth.subset(w.trees, list(range(12)))
+    run_rntn_case(w.params, sub, 8, "rntn[:12]")
+    p = w.params
+    lr = np.float32(0.1)
+    net = binding.TreeNet(p, scheduler="level_device")
+    try:
+        b = net.load(sub)
+        net.forward()
+        grads = binding.tl_backward(net.ctx, b, torch.randn((sub.n_nodes, p.hidden), device="cuda"), p.embed_dim, rntn=True)
+        binding.tl_sgd_update(net.ctx, float(lr), b, grads)
+        new = {k: v.cpu().numpy() for k, v in binding.tl_get_params(net.ctx, p.vocab, p.embed_dim, p.hidden, cell=p.cell).items()}
+        g = {k: v.cpu().numpy() for k, v in grads.items()}
+        assert np.array_equal(new["u"], p.u - (lr * g["d_u"]).astype(np.float32))
+        assert np.array_equal(new["b"], p.b - (lr * g["d_b"]).astype(np.float32))
+        assert np.array_equal(new["w_leaf"], p.v - (lr * g["d_w_leaf"]).astype(np.float32))
+        net.forward()
+        h_after = b["h"].cpu().numpy().copy()
+    finally:
+        net.close()
+    q = synth.Params(p.cell, p.vocab, p.embed_dim, p.hidden, new["emb"], None, None, new["u"], new["b"], new["w_leaf"])
     fresh = binding.TreeNet(q, scheduler="level_device")
     try:
         assert np.array_equal(fresh.run(sub)["h"], h_after)
