@@ -46,15 +46,31 @@ __global__ void k_pack_rntn(const float *__restrict__ v, const float *__restrict
     }
 }
 
+// Order of summation over q, the same however the work is spread: the slices fall into 16 classes by
+// q mod 16; a class is added up in ascending q on one accumulator; part p (p = 0..3) is the sum of the classes
+// p, p + 4, p + 8, p + 12 in that order; the result is ((part 0 + part 1) + part 2) + part 3, then the bias.
+// A workgroup evaluates one part of a tile and column group (sm.cmd[5] = p; its four waves take one class each),
+// or all four parts one after the other (sm.cmd[5] = -1).  With one part per workgroup, four workgroups share a
+// tile and column group: each leaves its part in a scratch area (unit sm.cmd[6] of it), counts itself done, and
+// the one that completes the count adds the parts up and writes h.  A height of a few rows thus spreads over
+// four times as many workgroups, each with a quarter of the slices: with d = 64 there are only four column
+// groups, and a block of 16 rows costs 129 slices x 32 MFMAs whatever the number of rows.
+constexpr int RNTN_PARTS = 4;
+constexpr int RNTN_PART_FLOATS = TILE_ROWS * HU;            // one part of one tile and column group in the scratch area
+
 template <int NS, bool VEC4, bool COH>
 __device__ inline void rntn_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, int count, int cg)
 {
     constexpr int Kp = NS * STEP_K;
     constexpr int LD = Kp + 4;                              // LDS row stride of the A tile, floats
-    static_assert(TILE_ROWS * LD * sizeof(float) <= sizeof(TileSmem::a) + sizeof(TileSmem::b), "A tile must fit the staging area");
+    constexpr int RED_FLOATS = 4 * 2 * 4 * 64;              // [wave][2 row blocks x 4 values][lane]
+    static_assert((TILE_ROWS * LD + RED_FLOATS) * sizeof(float) <= sizeof(TileSmem::a) + sizeof(TileSmem::b),
+                  "A tile and the exchange area must fit the staging area");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nrb = (count + 15) >> 4;
+    const int part = sm.cmd[5], unit = sm.cmd[6];           // written by the caller before its barrier
     float *a_lds = reinterpret_cast<float *>(&sm);
+    float *red = a_lds + TILE_ROWS * LD;
     // ---- the tile's gathered rows, once, into LDS ----------------------------------------
     for (int g = tid; g < nrb * 16 * (Kp / 4); g += WG_THREADS) {
         const int row = g / (Kp / 4), k4 = g - row * (Kp / 4);
@@ -65,8 +81,6 @@ __device__ inline void rntn_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, int
 
     const floatx4 *vp = reinterpret_cast<const floatx4 *>(gm.wp) + (size_t)cg * (Kp + 1) * NS * 64 + lane;
     floatx4 out[4];
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) out[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
     floatx4 b0[NS], b1[NS];
     auto load_slice = [&](int q, floatx4 (&b)[NS]) {
         const int qq = q <= Kp ? q : Kp;                    // past the end: re-read the last slice, never used
@@ -95,39 +109,87 @@ __device__ inline void rntn_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, int
             }
         }
     };
-    load_slice(wave, b0);
-    for (int q = wave; q <= Kp; q += 8) {
-        load_slice(q + 4, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        use_slice(q, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_slice(q + 8, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        use_slice(q + 4, b1);
-        __builtin_amdgcn_sched_barrier(0);
+    float mine[4] = {0.f, 0.f, 0.f, 0.f};                   // wave w: row block w, parts added up so far
+    const int p_lo = part < 0 ? 0 : part, p_hi = part < 0 ? RNTN_PARTS - 1 : part;
+    for (int pp = p_lo; pp <= p_hi; ++pp) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) out[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const int cls = pp + RNTN_PARTS * wave;             // this wave's class of the part
+        load_slice(cls, b0);
+        for (int q = cls; q <= Kp; q += 32) {
+            load_slice(q + 16, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            use_slice(q, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_slice(q + 32, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            use_slice(q + 16, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the part: the four waves' class sums in wave order; wave w takes row block w, two row blocks per round
+        float ppart[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r0 = 0; r0 < nrb; r0 += 2) {
+            __syncthreads();                                // the exchange area is free again
+#pragma unroll
+            for (int rbi = 0; rbi < 2; ++rbi)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float x = 0.f;
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb) if (rb == r0 + rbi) x = out[rb][v];
+                    red[(wave * 8 + rbi * 4 + v) * 64 + lane] = x;
+                }
+            __syncthreads();
+            if (wave >= r0 && wave < r0 + 2) {
+                const int rbi = wave - r0;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    ppart[v] = ((red[(0 * 8 + rbi * 4 + v) * 64 + lane] + red[(1 * 8 + rbi * 4 + v) * 64 + lane]) +
+                                red[(2 * 8 + rbi * 4 + v) * 64 + lane]) + red[(3 * 8 + rbi * 4 + v) * 64 + lane];
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mine[v] = pp == p_lo ? ppart[v] : mine[v] + ppart[v];
     }
-    __syncthreads();                                        // everybody is done with the A tile
-    // ---- partial sums of the four waves meet in LDS; wave w finishes row block w ---------
-    float *red = a_lds;                                     // [wave][rb*4+v][lane]
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[(wave * 16 + rb * 4 + v) * 64 + lane] = out[rb][v];
-    __syncthreads();
     const int rb = wave;
     const int hu = cg * HU + (lane & 15);
+    const float bias = gm.bp[cg * HU + (lane & 15)];
+    if (part < 0) {
+        if (rb < nrb && hu < f.H) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = rb * 16 + (lane >> 4) * 4 + v;
+                const int node = row < count ? sm.node[row] : -1;
+                if (node >= 0) st_f<COH>(f.h + (size_t)node * f.H + hu, tanh_f(mine[v] + bias));
+            }
+        }
+        return;
+    }
+    // ---- one part per workgroup: parts meet in the scratch area, the last one to arrive finishes ----
+    float *sc = f.rntn_part + (size_t)(unit * f.n_cg + cg) * RNTN_PARTS * RNTN_PART_FLOATS;
+    unsigned int *done = f.rntn_done + (size_t)unit * f.n_cg + cg;
+    if (rb < nrb) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = rb * 16 + (lane >> 4) * 4 + v;
+            st_dev(sc + part * RNTN_PART_FLOATS + row * HU + (lane & 15), mine[v]);
+        }
+    }
+    wait_mem();
+    __syncthreads();
+    if (tid == 0) sm.cmd[7] = (int)add_dev(done, 1u);
+    __syncthreads();
+    if (sm.cmd[7] != RNTN_PARTS - 1) return;                // uniform: not the last part of this tile and column group
+    if (tid == 0) st_dev(done, 0u);                         // the counter is ready for its next use
     if (rb < nrb && hu < f.H) {
-        const float bias = gm.bp[cg * HU + (lane & 15)];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int row = rb * 16 + (lane >> 4) * 4 + v;
             const int node = row < count ? sm.node[row] : -1;
-            if (node < 0) continue;
-            float sum = red[(0 * 16 + rb * 4 + v) * 64 + lane];
-            sum += red[(1 * 16 + rb * 4 + v) * 64 + lane];
-            sum += red[(2 * 16 + rb * 4 + v) * 64 + lane];
-            sum += red[(3 * 16 + rb * 4 + v) * 64 + lane];
-            st_f<COH>(f.h + (size_t)node * f.H + hu, tanh_f(sum + bias));
+            const float *e = sc + row * HU + (lane & 15);
+            const float sum = ((ld_dev(e) + ld_dev(e + RNTN_PART_FLOATS)) + ld_dev(e + 2 * RNTN_PART_FLOATS)) +
+                              ld_dev(e + 3 * RNTN_PART_FLOATS);
+            if (node >= 0) st_f<COH>(f.h + (size_t)node * f.H + hu, tanh_f(sum + bias));
         }
     }
 }

@@ -119,6 +119,9 @@ struct Fwd {
     int32_t *parent, *pending, *leaf_list, *root_ws;
     int32_t *height, *arrive, *level_cnt, *level_off, *level_fill, *level_nodes;
     int32_t *depth_root;              // priority scheduling: distance of every node from its root, capped
+    float *rntn_part;                 // RNTN: parts of the sums over q, [unit][column group][part][64 rows x 16], see cell_rntn.hpp
+    unsigned int *rntn_done;          // RNTN: parts finished per unit and column group (back at zero after every tile)
+    int rntn_units;                   // units the two arrays have room for
     int priority;                     // ready scheduler: critical path first
     QRec *q_rec;                      // ready queue, append-only: one record per internal node
     GangBox *gangs;

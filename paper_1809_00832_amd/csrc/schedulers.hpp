@@ -22,13 +22,20 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_tiles_static(Fwd f, const int
     extern __shared__ __align__(16) unsigned char smem_raw[];
     TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
     if (batch_rejected(f)) return;
-    const int tile = blockIdx.x / f.n_cg, cg = blockIdx.x % f.n_cg;
+    // RNTN cell, frontier of few tiles: RNTN_PARTS workgroups per tile and column group, one part of the sums each
+    const int parts = (EPI == EPI_RNTN_INNER && plan.n_tiles <= f.rntn_units) ? RNTN_PARTS : 1;
+    const int tile = blockIdx.x / (f.n_cg * parts), rem = blockIdx.x % (f.n_cg * parts);
+    const int cg = rem % f.n_cg, part = rem / f.n_cg;
     int start, count;
     plan_tile(plan, total, tile, &start, &count);
     if (count <= 0) return;
     const int tid = threadIdx.x;
     tile_set_rows<EPI>(sm, f, tid, tid < count ? list[start + tid] : -1, f.pos0 + start + tid);
-    if (tid == 0) sm.cmd[3] = f.pos0 + start;               // list position of row 0 (backward kernels)
+    if (tid == 0) {
+        sm.cmd[3] = f.pos0 + start;                         // list position of row 0 (backward kernels)
+        sm.cmd[5] = parts > 1 ? part : -1;
+        sm.cmd[6] = tile;                                   // unit of the scratch area
+    }
     __syncthreads();
     constexpr bool LEAF_ROWS = EPI == EPI_LSTM_LEAF || EPI == EPI_BWD_LEAF_GATES;
     constexpr bool GRAD_ROWS = epi_is_operand_gradient(EPI);
@@ -310,11 +317,17 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
             const LevelPlan plan = plan_level(rows, f.cap_tiles);
             // tile T of a frontier: its rows' parents are looked after by the workgroup that computes
             // column group T % n_cg of it
-            const int items = plan.n_tiles * f.n_cg;
+            const int parts = (EPI == EPI_RNTN_INNER && plan.n_tiles <= f.rntn_units) ? RNTN_PARTS : 1;
+            const int items = plan.n_tiles * f.n_cg * parts;
             for (int item = blockIdx.x; item < items; item += gridDim.x) {
-                const int tile = item / f.n_cg, cg_index = item % f.n_cg;
+                const int tile = item / (f.n_cg * parts), rem = item % (f.n_cg * parts);
+                const int cg_index = rem % f.n_cg, part = rem / f.n_cg;
                 int start, count;
                 plan_tile(plan, rows, tile, &start, &count);
+                if (tid == 0) {
+                    sm.cmd[5] = parts > 1 ? part : -1;
+                    sm.cmd[6] = tile;                       // unit of the scratch area
+                }
                 if (tid < TILE_ROWS) {
                     int node = -1, s0 = -1, s1 = -1;
                     if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
@@ -323,7 +336,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                     sm.src1[tid] = s1;
                 }
                 __syncthreads();
-                const bool keeper = cg_index == tile % f.n_cg && tid < 64;
+                const bool keeper = cg_index == tile % f.n_cg && part == 0 && tid < 64;
                 ParentTicket ticket{-1, 0, -1, -1};
                 if (keeper) ticket = frontier_decrement(sm, f, count, 0);
                 cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(cg_index, f.n_cg, f.n_cg));
@@ -578,7 +591,10 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
             if (tid < TILE_ROWS) sm.node[tid] = value;
             else if (tid < 2 * TILE_ROWS) sm.src0[tid - TILE_ROWS] = SPW > 0 ? max(value, 0) : value;
             else sm.src1[tid - 2 * TILE_ROWS] = SPW > 0 ? max(value, 0) : value;
-            if (tid == 0) sm.cmd[0] = (int)((entry >> 32) & 0xffu);
+            if (tid == 0) {
+                sm.cmd[0] = (int)((entry >> 32) & 0xffu);
+                sm.cmd[5] = -1;                             // RNTN cell: this workgroup adds up all parts itself
+            }
         }
         __syncthreads();
         const int count = sm.cmd[0];

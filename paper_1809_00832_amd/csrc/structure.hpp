@@ -70,6 +70,7 @@ __global__ void k_reset(Fwd f, int with_levels)
         if (with_levels && i <= (size_t)N) f.level_cnt[i] = 0;
         if (i < (size_t)f.n_int) { f.q_rec[i].lo = 0; f.q_rec[i].hi = 0; }
         if (i < (size_t)f.n_trees) f.root_ws[i] = -1;
+        if (f.rntn_done && i < (size_t)f.rntn_units * f.n_cg) f.rntn_done[i] = 0u;   // (a forward that gave up may have left counts)
         if (i < ctl_words) ((unsigned int *)f.ctl)[i] = 0;
         if (i < gang_words) ((unsigned int *)f.gangs)[i] = 0;
     }

@@ -69,6 +69,9 @@ struct tl_ctx {
     float *m_u = nullptr, *m_b = nullptr, *m_w_leaf = nullptr, *m_b_leaf = nullptr;   // fp32 TreeLSTM: the parameters themselves
     float *t_scratch = nullptr, *zero_bias = nullptr;
     float *m_v = nullptr;             // fp32 RNTN: the tensor V as given
+    float *rntn_part = nullptr;       // RNTN forward: scratch area of the parts of a tile's sums, see cell_rntn.hpp
+    unsigned int *rntn_done = nullptr;
+    int rntn_units = 0;
     float *rntn_acc = nullptr;        // RNTN backward: [2d x (d * 2d + d)] weight-gradient contraction and its column sums
     int ws_steps16 = 0;
     bool keep_gates = false;          // tl_set_keep_gates
@@ -448,6 +451,8 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->zero_bias);
     (void)hipFree(ctx->m_v);
     (void)hipFree(ctx->rntn_acc);
+    (void)hipFree(ctx->rntn_part);
+    (void)hipFree(ctx->rntn_done);
     if (ctx->host_levels) (void)hipHostFree(ctx->host_levels);
     if (ctx->host_ctl) (void)hipHostFree(ctx->host_ctl);
     for (auto &set : ctx->ev)
@@ -622,6 +627,19 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         if (ctx->leaf_grid < ctx->n_cg) ctx->spw_leaf = 0;
     }
 
+    if (cfg->cell == TL_RNTN) {
+        // frontiers of so few tiles that half the workgroups would idle are cut into parts (cell_rntn.hpp);
+        // one unit of the scratch area per tile of such a frontier
+        const int grid = ctx->persistent_grid > ctx->ws_grid ? ctx->persistent_grid : ctx->ws_grid;
+        const int units = grid / (2 * ctx->n_cg);
+        if (units > 0) {
+            const size_t per_unit = (size_t)ctx->n_cg * RNTN_PARTS * RNTN_PART_FLOATS * sizeof(float);
+            TL_HIP(hipMalloc(&ctx->rntn_part, units * per_unit));
+            TL_HIP(hipMalloc(&ctx->rntn_done, (size_t)units * ctx->n_cg * sizeof(unsigned int)));
+            TL_HIP(hipMemset(ctx->rntn_done, 0, (size_t)units * ctx->n_cg * sizeof(unsigned int)));
+        }
+        ctx->rntn_units = units;
+    }
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
     return TL_OK;
 }
@@ -725,6 +743,9 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     if (persistent && spw > 0 && bf16) { f.hb = ctx->hb; f.hs = ctx->hs; }
     const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
+    // RNTN: a frontier of at most rntn_units tiles is cut into RNTN_PARTS workgroups per tile and column group
+    f.rntn_part = ctx->rntn_part; f.rntn_done = ctx->rntn_done;
+    f.rntn_units = cfg.cell == TL_RNTN ? (grid_p / (2 * ctx->n_cg) < ctx->rntn_units ? grid_p / (2 * ctx->n_cg) : ctx->rntn_units) : 0;
     // ready scheduler: gangs of gang_size compute workgroups plus one scheduler workgroup each
     f.gang_size = ctx->n_cg + 1 <= grid_p ? ctx->n_cg : grid_p - 1;
     f.n_gangs = grid_p / (f.gang_size + 1) < MAX_GANGS ? grid_p / (f.gang_size + 1) : MAX_GANGS;
@@ -806,9 +827,10 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
                     const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
                     if (rows <= 0 || lo < 0 || lo + rows > f.n_int) return TL_EHIP;
                     const LevelPlan plan = plan_level(rows, f.cap_tiles);
-                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
+                    const int parts = plan.n_tiles <= f.rntn_units ? RNTN_PARTS : 1;
+                    hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner, bf16), dim3(plan.n_tiles * ctx->n_cg * parts), dim3(WG_THREADS),
                                        TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, plan);
-                    if (plan.n_tiles * ctx->n_cg > max_grid) max_grid = plan.n_tiles * ctx->n_cg;
+                    if (plan.n_tiles * ctx->n_cg * parts > max_grid) max_grid = plan.n_tiles * ctx->n_cg * parts;
                 }
                 ctx->last_grid = max_grid;
             }

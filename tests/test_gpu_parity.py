@@ -194,6 +194,30 @@ def test_repeated_forward_is_stable():
         net.close()
 
 
+def test_rntn_schedulers_agree_bit_for_bit():
+    """RNTN: the level schedulers cut a frontier of few tiles into four workgroups per tile and column group (each
+    adds up a quarter of the slices, the last one to finish adds the quarters); the ready schedulers and the large
+    frontiers do not.  The order of summation is the same either way, so all four give the same bits, run after run."""
+    say("case rntn bits")
+    w, ref = reference("rntn")
+    first = None
+    for sched in SCHEDULERS:
+        net = binding.TreeNet(w.params, scheduler=sched)
+        try:
+            net.load(w.trees)
+            for it in range(3):
+                net.batch["h"].fill_(float("nan"))
+                net.forward()
+                assert binding.tl_status(net.ctx) == 0
+                h = net.batch["h"].cpu().numpy()
+                if first is None:
+                    first = h
+                    assert_close(h, ref["h"], "rntn h")
+                assert np.array_equal(h, first), "rntn %s run %d differs in bits" % (sched, it)
+        finally:
+            net.close()
+
+
 # ----------------------------------------------------------------------------- bf16-operand path
 def bf16_reference(name):
     """Checker run on bf16-representable weights / embeddings with bf16 rounding of the gathered operand."""
