@@ -194,6 +194,43 @@ def test_repeated_forward_is_stable():
         net.close()
 
 
+_large_cache = {}
+
+
+@pytest.mark.parametrize("sched", SCHEDULERS)
+def test_large_batch_and_wide_hidden(sched):
+    """Sizes at the other end: a batch of 6 000 trees (about 320 000 nodes, H=32: queue, counters, frontier lists
+    and workspace far beyond one tile per workgroup, frontiers of tens of thousands of rows) and a hidden size
+    above what the weight-stationary cell holds (H=576: the persistent kernels fall back to the streaming cell).
+    Every node is compared."""
+    say("case large", sched)
+    if "big" not in _large_cache:
+        sizes = synth.Stream(77, "sizes").integers(5, 50, 6000)
+        params = synth.make_treelstm_params(77, 500, 16, 32, "xavier")
+        trees = synth.make_trees(77, [int(v) for v in sizes], ["random"] * len(sizes), 500)
+        wide_p = synth.make_treelstm_params(78, 200, 40, 576, "xavier")
+        wide_t = synth.make_trees(78, [9, 1, 30, 2, 70], ["random"] * 5, 200)
+        _large_cache["big"] = (params, trees, oracle.forward_params(params, trees, n_threads=8))
+        _large_cache["wide"] = (wide_p, wide_t, oracle.forward_params(wide_p, wide_t, n_threads=8))
+    for key in ("big", "wide"):
+        params, trees, ref = _large_cache[key]
+        for prec in (binding.TL_F32, binding.TL_BF16_IN):
+            net = binding.TreeNet(params, scheduler=sched, precision=prec)
+            try:
+                got = net.run(trees)
+                if prec == binding.TL_F32:
+                    check_against_oracle(params, trees, got, ref, "%s/%s" % (key, sched))
+                else:
+                    q = round_params_bf16(params)
+                    refb = oracle.forward_params(q, trees, n_threads=8, round_bf16=True)
+                    assert_close_bf16(got["h"], refb["h"], "%s bf16 h" % key)
+                    assert_close_bf16(got["c"], refb["c"], "%s bf16 c" % key)
+                say("   %s %s nodes %d" % (key, "f32" if prec == binding.TL_F32 else "bf16", len(trees.left)),
+                    binding.tl_last_stats(net.ctx))
+            finally:
+                net.close()
+
+
 def test_rntn_schedulers_agree_bit_for_bit():
     """RNTN: the level schedulers cut a frontier of few tiles into four workgroups per tile and column group (each
     adds up a quarter of the slices, the last one to finish adds the quarters); the ready schedulers and the large
