@@ -326,9 +326,16 @@ def cpu_baseline(w, max_nodes=40000):
         dt_all += time.perf_counter() - t0
         passes += 1
     dt = dt_all / passes
+    # and on one thread, on every eighth tree of that sample
+    one, _ = synth.subset(trees, list(range(0, trees.n_trees, 8)))
+    t0 = time.perf_counter()
+    oracle.forward_params(w.params, one, n_threads=1)
+    dt_one = time.perf_counter() - t0
     return {"value": trees.n_trees / dt, "unit": "trees/s", "cores": cores, "kind": "oracle",
-            "nodes_per_sec": trees.n_nodes / dt, "seconds": dt_all,
-            "sample": "%s, %d passes (mean), trees spread over %d threads" % (what, passes, cores)}
+            "nodes_per_sec": trees.n_nodes / dt, "seconds": dt_all + dt_one,
+            "sample": "%s, %d passes (mean), trees spread over %d threads" % (what, passes, cores),
+            "one_thread": {"value": one.n_trees / dt_one, "unit": "trees/s", "nodes_per_sec": one.n_nodes / dt_one,
+                           "sample": "%d trees (%d nodes) of that sample, one pass" % (one.n_trees, one.n_nodes)}}
 
 
 def copy_calibration(mib=1024, reps=3):
