@@ -145,6 +145,9 @@ int tl_create(const tl_config *cfg, tl_ctx **out);
  * trip and may be captured in a HIP graph and replayed.
  *
  *   n_trees >= 1, n_nodes >= n_trees                          HOST scalars
+ *                         (n_trees = n_nodes = 0, an empty batch, is accepted: nothing is
+ *                         launched, read or written, the pointers may be NULL, and
+ *                         tl_status reports TL_OK afterwards)
  *   tree_off [n_trees+1]  int32, tree_off[0]=0, ascending,
  *                         tree_off[n_trees]=n_nodes            DEVICE, read-only
  *   left, right, word [n_nodes] int32                          DEVICE, read-only

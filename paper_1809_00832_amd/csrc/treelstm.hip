@@ -698,7 +698,13 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
                const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
                int32_t *root, void *hip_stream)
 {
-    if (!ctx || !tree_off || !left || !right || !word || !h) return TL_EINVAL;
+    if (!ctx) return TL_EINVAL;
+    if (n_trees == 0 && n_nodes == 0) {     // an empty batch: nothing to evaluate, nothing is launched or written
+        ctx->ran = false;
+        ctx->gates_nodes = 0;
+        return TL_OK;
+    }
+    if (!tree_off || !left || !right || !word || !h) return TL_EINVAL;
     if (n_trees < 1 || n_nodes < n_trees) return TL_EINVAL;
     const tl_config &cfg = ctx->cfg;
     if (cfg.cell == TL_TREELSTM && !c) return TL_EINVAL;

@@ -103,6 +103,9 @@ def test_host_side_argument_checks():
         ptr = [x.data_ptr() for x in args]
         st = torch.cuda.current_stream().cuda_stream
         assert L.tl_forward(net.ctx, 0, b["N"], *ptr, st) == binding.TL_EINVAL
+        assert L.tl_forward(net.ctx, 0, 0, *([None] * 9), st) == binding.TL_OK                      # an empty batch is a no-op
+        assert binding.tl_status(net.ctx) == binding.TL_OK
+        assert binding.tl_last_stats(net.ctx)["n_workgroups"] == 0
         assert L.tl_forward(net.ctx, b["B"], b["B"] - 1, *ptr, st) == binding.TL_EINVAL
         assert L.tl_forward(net.ctx, b["B"], b["N"], None, *ptr[1:], st) == binding.TL_EINVAL
         assert L.tl_forward(net.ctx, b["B"], b["N"], *ptr[:5], None, *ptr[6:], st) == binding.TL_EINVAL   # c missing
