@@ -45,6 +45,7 @@ template <int SPW> struct WsSmemT {
     int cmd[8];
 };
 
+constexpr int WS_VGPR_STEPS = 5;   // k-steps whose weights stay in the vector registers when not all fit (see ws_load)
 template <int NG, int SPW> struct WsWeights {
     floatx4 b[SPW][NG];
     float bias[NG];
@@ -63,6 +64,22 @@ __device__ inline void ws_load(WsWeights<NG, SPW> &w, const Gemm &gm, int cg, in
         for (int g = 0; g < NG; ++g) w.b[s][g] = wp[(size_t)(s * NG + g) * 64];
 #pragma unroll
     for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+    // A wave has 256 vector registers and 256 accumulation registers; an MFMA takes its B operand from either
+    // file.  With more weights than fit beside everything else in the first file, say which of them live in the
+    // second: left to itself the compiler parks them there as well, but copies each back before its MFMA,
+    // one vector instruction per MFMA operand and block.
+    if constexpr (SPW * NG * 4 > 256) {
+#pragma unroll
+        for (int s = WS_VGPR_STEPS; s < SPW; ++s)
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = w.b[s][g][i];
+                    asm volatile("" : "+a"(x));             // no instruction: a register-class constraint only
+                    w.b[s][g][i] = x;
+                }
+    }
 }
 
 // Geometry of the coalesced row loads of one wave: its K range is 16*SPW floats = LPR lanes of
