@@ -269,9 +269,12 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
         constexpr int LOADS_PER_STEP = (NL + SPW - 1) / SPW;
+        // the A operand of a k-step is read from LDS one k-step ahead, so that its latency runs under MFMAs
+        floatx4 av_next = *reinterpret_cast<const floatx4 *>(a_lane);
 #pragma unroll
         for (int s = 0; s < SPW; ++s) {
-            const floatx4 av = *reinterpret_cast<const floatx4 *>(a_lane + s * STEP_K);
+            const floatx4 av = av_next;
+            if (s + 1 < SPW) av_next = *reinterpret_cast<const floatx4 *>(a_lane + (s + 1) * STEP_K);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -390,9 +393,11 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
 #pragma unroll
         for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
         constexpr int LOADS_PER_STEP = (NL + S - 1) / S;
+        bf16x8 av_next = *reinterpret_cast<const bf16x8 *>(a_lane);      // read one k-step ahead, as in the fp32 form
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            const bf16x8 av = *reinterpret_cast<const bf16x8 *>(a_lane + s * 32);
+            const bf16x8 av = av_next;
+            if (s + 1 < S) av_next = *reinterpret_cast<const bf16x8 *>(a_lane + (s + 1) * 32);
 #pragma unroll
             for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, w.b[s][g], acc[g], 0, 0, 0);
 #pragma unroll
