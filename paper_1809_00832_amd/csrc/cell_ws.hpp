@@ -332,6 +332,7 @@ template <int S> struct WsSmemBfT {
 
 template <int NG, int S> struct WsWeightsBf {
     bf16x8 b[S][NG];
+    float bias[NG];     // in registers too: a load of it after the barrier would have to wait for the row requests issued before it
 };
 template <int NG> struct WsWeightsBf<NG, 0> {};
 
@@ -344,6 +345,8 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
     for (int s = 0; s < S; ++s)
 #pragma unroll
         for (int g = 0; g < NG; ++g) w.b[s][g] = wp[(size_t)(s * NG + g) * 64];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
 }
 
 template <int EPI, bool COH, int S>
@@ -417,7 +420,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
             sum += red[((1 * NG + g) * 4 + wave) * 64 + lane];
             sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
             sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
-            gate[g] = sum + gm.bp[(cg * NG + g) * HU + (lane & 15)];
+            gate[g] = sum + w.bias[g];
         }
         if (ev) {
             const size_t o = (size_t)enode * H + hu;
