@@ -191,9 +191,14 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 // Evaluates the `count` <= WS_TABLE_ROWS rows in sm.node/src0/src1 for column group cg, 16 at a
 // time, the requests of a block's rows always one block ahead.  All four waves call it together;
 // a __syncthreads() has been passed since the row tables were written.
-template <int EPI, bool COH, int SPW, bool TAIL = false>
+// `hook` lets the caller start memory work of its own beside the cell's: it is called (with -1) once the first row
+// requests are out.
+struct WsNoHook {
+    __device__ inline void operator()(int) const {}
+};
+template <int EPI, bool COH, int SPW, bool TAIL = false, typename Hook = WsNoHook>
 __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int table_rows,
-                               int count, int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w)
+                               int count, int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w, Hook hook = Hook())
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
@@ -241,6 +246,7 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     req.prepare(0);
 #pragma unroll
     for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
+    hook(-1);
     // The second half of block rb - 1 is done inside the MFMA phase of block rb (after its first
     // k-step): what it waits for (the barrier, LDS round trips, the c rows) has then had a k-step
     // of MFMAs to arrive, instead of leaving the matrix pipe idle between two blocks.
@@ -349,9 +355,10 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
     for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
 }
 
-template <int EPI, bool COH, int S>
+template <int EPI, bool COH, int S, typename Hook = WsNoHook>
 __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
-                               int table_rows, int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w)
+                               int table_rows, int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w,
+                               Hook hook = Hook())
 {
     constexpr int NG = EpiTraits<EPI>::NG;
     constexpr int SEG = EpiTraits<EPI>::SEG;
@@ -370,6 +377,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     req.prepare(0);
 #pragma unroll
     for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
+    hook(-1);
     for (int rb = 0; rb < nrb; ++rb) {
         float *red = sm.red[rb & 1];
         {                                                   // park the requested rows (waits for them)

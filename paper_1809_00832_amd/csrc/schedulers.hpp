@@ -285,8 +285,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
             // the frontier, a multiple of 16 rows, and walks it in pieces of up to WS_TABLE_ROWS rows: one
             // fill of the row tables and one start of the row-request pipeline per piece.  The parents of
             // rows [64 j, 64 j + 64) of a piece are looked after by wave 0 of member (frontier + slot + j) %
-            // n_cg, so that this duty rotates; the decrements are sent before the piece is computed and
-            // their results are used after it.
+            // n_cg, so that this duty rotates; the decrements are sent while the piece's first rows are on their
+            // way and their results are used after the piece.
             const int share = ((rows + n_slots - 1) / n_slots + 15) & ~15;
             const int lo = slot * share, hi = min(rows, lo + share);
             for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
@@ -299,19 +299,25 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                     sm.src1[tid] = max(s1, 0);
                 }
                 __syncthreads();
-                ParentTicket ticket{-1, 0, -1, -1};
-                bool holds = false;
+                // this wave's 64-row group of parents, if any.  The decrements of the last one are sent from inside the
+                // cell, once its first row requests are out: looking up the parents is a memory round trip of its own,
+                // which then runs beside that of the rows instead of in front of it.  (Earlier groups - fewer column
+                // groups than 64-row groups - are dealt with at once.)
+                int j_mine = -1;
                 if (tid < 64) {
                     for (int j = 0; j * 64 < count; ++j) {
                         if ((frontiers + slot + j) % f.n_cg != member) continue;
-                        if (holds) appended += frontier_push(f, ticket);        // only when there are fewer column groups than 64-row groups
-                        ticket = frontier_decrement(sm, f, count, j * 64);
-                        holds = true;
+                        if (j_mine >= 0) appended += frontier_push(f, frontier_decrement(sm, f, count, j_mine * 64));
+                        j_mine = j;
                     }
                 }
-                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.n_nodes, f.hs, count, my_cg, w);
-                else ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w);
-                if (holds) appended += frontier_push(f, ticket);
+                ParentTicket ticket{-1, 0, -1, -1};
+                auto hook = [&](int where) {            // -1: the first row requests are out
+                    if (where == -1 && j_mine >= 0) ticket = frontier_decrement(sm, f, count, j_mine * 64);
+                };
+                if constexpr (BF16) ws_tile<EPI, true, SPW>(sm, f, f.inner, f.hb, f.n_nodes, f.hs, count, my_cg, w, hook);
+                else ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w, hook);
+                if (j_mine >= 0) appended += frontier_push(f, ticket);
             }
         } else {
             const LevelPlan plan = plan_level(rows, f.cap_tiles);
