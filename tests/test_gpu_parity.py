@@ -231,6 +231,31 @@ def test_large_batch_and_wide_hidden(sched):
                 net.close()
 
 
+@pytest.mark.parametrize("sched", ["level_device", "ready"])
+def test_hidden_sizes_between_the_register_layouts(sched):
+    """Hidden sizes that fall between the sizes the weight-stationary cell is built for (its K axis is padded up to the
+    next of 1, 2, 4, 5, 8, 16 k-steps per wave): H = 96, 200, 448 with E = 36, 50, 64, both precisions, a batch whose
+    frontiers span several blocks and a ragged tail."""
+    say("case hidden sizes", sched)
+    for i, (H, E) in enumerate(((96, 36), (200, 50), (448, 64))):
+        params = synth.make_treelstm_params(60 + i, 300, E, H, "xavier")
+        leaves = [int(v) for v in synth.Stream(60 + i, "sizes").integers(2, 40, 24)] + [1, 90]
+        trees = synth.make_trees(60 + i, leaves, ["random"] * len(leaves), 300)
+        ref = oracle.forward_params(params, trees, n_threads=8)
+        refb = oracle.forward_params(round_params_bf16(params), trees, n_threads=8, round_bf16=True)
+        for prec in (binding.TL_F32, binding.TL_BF16_IN):
+            net = binding.TreeNet(params, scheduler=sched, precision=prec)
+            try:
+                got = net.run(trees)
+                if prec == binding.TL_F32:
+                    check_against_oracle(params, trees, got, ref, "H=%d/%s" % (H, sched))
+                else:
+                    assert_close_bf16(got["h"], refb["h"], "H=%d bf16 h" % H)
+                    assert_close_bf16(got["c"], refb["c"], "H=%d bf16 c" % H)
+            finally:
+                net.close()
+
+
 def test_rntn_schedulers_agree_bit_for_bit():
     """RNTN: the level schedulers cut a frontier of few tiles into four workgroups per tile and column group (each
     adds up a quarter of the slices, the last one to finish adds the quarters); the ready schedulers and the large
