@@ -184,9 +184,11 @@ int tl_set_profiling(tl_ctx *ctx, int on);
 int tl_stage_ms(tl_ctx *ctx, int back, float *ms);
 
 /* Facts about the last forward, for reports and tests (HOST out-parameters, any may be
- * NULL): number of heights seen by a level scheduler (0 for TL_SCHED_READY), number of
- * tiles of ready nodes formed by TL_SCHED_READY (0 otherwise), workgroups launched for the
- * internal-node kernel.  Waits for the stream. */
+ * NULL): number of heights seen by a level scheduler (0 for TL_SCHED_READY; with
+ * TL_SCHED_LEVEL_DEVICE the number of frontiers it evaluated plus one for the leaves, which
+ * exceeds the number of heights by a few when it left the last rows of large frontiers to
+ * the next one), number of tiles of ready nodes formed by TL_SCHED_READY (0 otherwise),
+ * workgroups launched for the internal-node kernel.  Waits for the stream. */
 int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
 
 /*
