@@ -283,14 +283,14 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
         if constexpr (SPW > 0) {
             // The slots advance together, 16 rows each per step, so a frontier costs ceil(rows / (16 n_slots)) steps of
             // the whole machine, and a few rows beyond a multiple cost a whole step.  Such a remainder of a large
-            // frontier (at most 32 rows of at least two steps' worth) is left in the queue: it becomes the head of
-            // the next frontier, whose last step usually has room (on the H=512 evaluation batch: 58 steps
+            // frontier (at most 32 rows beyond one or more full steps) is left in the queue: it becomes the head of
+            // the next frontier, whose last step usually has room (on the H=512 evaluation batch: 57 steps
             // instead of 60).  Every row of the queue is still taken exactly once.  Only where a step is long (fp32,
             // 16 k-steps per wave: about 6 us): a node left behind may cost its tree one more frontier, which is
             // worth a step there and not where steps are short.
             constexpr bool LEAVE_REMAINDER = !BF16 && SPW >= 16;
             const int step_rows = 16 * n_slots, rem = rows % step_rows;
-            if (LEAVE_REMAINDER && rows >= 2 * step_rows && rem > 0 && rem <= 32) rows -= rem;
+            if (LEAVE_REMAINDER && rows > step_rows && rem > 0 && rem <= 32) rows -= rem;
             // Every slot (a set of workgroups that covers all column groups) takes one contiguous share of
             // the frontier, a multiple of 16 rows, and walks it in pieces of up to WS_TABLE_ROWS rows: one
             // fill of the row tables and one start of the row-request pipeline per piece.  The parents of
