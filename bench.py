@@ -22,7 +22,7 @@ HBM_GBS = 8000.0
 # HBM bytes per launch of the internal-node kernel from rocprofv3 counter passes (FETCH_SIZE + WRITE_SIZE, scaled by a
 # copy of known size; profiles/levels_persistent_throughput_f32_counters.md).  Only for the configuration the counters
 # were taken on; to be cleared when that kernel changes.
-MEASURED_TRAFFIC = {("throughput", "level_device", "f32"): {"read": 250.1 * 2 ** 20, "write": 26.4 * 2 ** 20}}
+MEASURED_TRAFFIC = {("throughput", "level_device", "f32"): {"read": 250.5 * 2 ** 20, "write": 26.4 * 2 ** 20}}
 
 
 def algorithmic_work(w):
