@@ -256,6 +256,29 @@ def test_hidden_sizes_between_the_register_layouts(sched):
                 net.close()
 
 
+def test_wide_frontiers_at_a_hidden_size_with_uneven_slots():
+    """H = 440: 28 column groups, so the 256 workgroups of the level scheduler form 9 slots and 4 stay idle; 100 trees give
+    frontiers of several steps of those slots, whose remainders the scheduler leaves to the next frontier.  Every
+    node against the checker, all schedulers bit for bit."""
+    say("case wide frontiers, H=440")
+    params = synth.make_treelstm_params(71, 400, 52, 440, "xavier")
+    leaves = [int(v) for v in synth.Stream(71, "sizes").integers(5, 50, 100)]
+    trees = synth.make_trees(71, leaves, ["random"] * len(leaves), 400)
+    ref = oracle.forward_params(params, trees, n_threads=8)
+    first = None
+    for sched in SCHEDULERS:
+        net = binding.TreeNet(params, scheduler=sched)
+        try:
+            got = net.run(trees)
+            check_against_oracle(params, trees, got, ref, "H=440/%s" % sched)
+            if first is None:
+                first = got
+            assert np.array_equal(got["h"], first["h"]) and np.array_equal(got["c"], first["c"]), sched
+            say("   ", sched, binding.tl_last_stats(net.ctx))
+        finally:
+            net.close()
+
+
 def test_rntn_schedulers_agree_bit_for_bit():
     """RNTN: the level schedulers cut a frontier of few tiles into four workgroups per tile and column group (each
     adds up a quarter of the slices, the last one to finish adds the quarters); the ready schedulers and the large
