@@ -206,7 +206,11 @@ __global__ __launch_bounds__(NODE_BLOCK) void k_seed_place(Fwd f)
 
 // Heights by climbing: one thread per leaf walks towards the root; at every internal node the
 // first child to arrive stops, the second continues with height 1 + max.  The walk passes each
-// node once, so a thread's loop is bounded by the tree height.
+// node once, so a thread's loop is bounded by the tree height.  The two children meet through one
+// exchange on height[p] (zero before the pass): the first leaves 1 + its own height there and
+// finds zero, the second finds the first one's value - the data travels in the word that is
+// exchanged, so a step costs two memory round trips (the parent, the exchange) and no fence.
+// arrive[p] = 2 marks the nodes whose height is final.
 __global__ void k_climb(Fwd f)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -216,11 +220,11 @@ __global__ void k_climb(Fwd f)
     for (int guard = 0; guard < f.n_nodes; ++guard) {
         const int p = f.parent[n];
         if (p < 0) break;
-        atomicMax(&f.height[p], hcur + 1);
-        __threadfence();
-        if (atomicAdd(&f.arrive[p], 1) == 0) break;
-        __threadfence();
-        hcur = ld_dev(&f.height[p]);
+        const int other = atomicExch(&f.height[p], hcur + 1);
+        if (other == 0) break;                   // the sibling's subtree is not done yet: its thread will carry on
+        hcur = other > hcur + 1 ? other : hcur + 1;
+        f.height[p] = hcur;
+        f.arrive[p] = 2;
         n = p;
     }
 }
