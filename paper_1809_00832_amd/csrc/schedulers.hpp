@@ -403,9 +403,26 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
     if (lane >= 64) return;
     const unsigned n_int = (unsigned)f.n_int;
     unsigned published = 0, completed = 0;       // tiles posted / tiles whose parents have been resolved
-    int my_node[GANG_RING];                      // this lane's row of the tiles in flight (-1: none)
+    // this lane's row of the tiles in flight: its parent (-1: none) and the parent's children and distance from the
+    // root.  They are looked up when the tile is posted, while the compute workgroups are busy with it, so that a
+    // finished tile costs one round trip (the decrement) before its parents can be handed on, not three.
+    int my_p[GANG_RING], my_pl[GANG_RING], my_pr[GANG_RING], my_pd[GANG_RING];
 #pragma unroll
-    for (int r = 0; r < GANG_RING; ++r) my_node[r] = -1;
+    for (int r = 0; r < GANG_RING; ++r) { my_p[r] = -1; my_pl[r] = -1; my_pr[r] = -1; my_pd[r] = 0; }
+    auto remember = [&](int r, int node) {
+        int p = -1, pl = -1, pr = -1, pd = 0;
+        if (node >= 0) {
+            p = f.parent[node];
+            if (p >= 0) {
+                pl = f.left[p];
+                pr = f.right[p];
+                if (f.priority) pd = f.depth_root[p];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < GANG_RING; ++q)
+            if (q == r) { my_p[q] = p; my_pl[q] = pl; my_pr[q] = pr; my_pd[q] = pd; }
+    };
     int spins = 0;
     unsigned last_head = 0u, last_tail = 0u, last_direct = ~0u;
     bool leave = false;
@@ -424,20 +441,11 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
             if (lane == 0) d = ld_dev(&box->done[r].v);
             d = __shfl(d, 0);
             if (d >= (t + GANG_RING - 1) / GANG_RING * (unsigned)f.gang_size) {
-                int node = -1;
-#pragma unroll
-                for (int q = 0; q < GANG_RING; ++q) if (q == r) node = my_node[q];
                 int p = -1, pl = -1, pr = -1, pd = 0;
-                if (node >= 0) {
-                    p = f.parent[node];
-                    if (p >= 0) {
-                        const int old = add_dev(&f.pending[p], -1);
-                        pl = f.left[p];                     // requested together with the decrement
-                        pr = f.right[p];
-                        if (f.priority) pd = f.depth_root[p];
-                        if (old != 1) p = -1;
-                    }
-                }
+#pragma unroll
+                for (int q = 0; q < GANG_RING; ++q)
+                    if (q == r) { p = my_p[q]; pl = my_pl[q]; pr = my_pr[q]; pd = my_pd[q]; }
+                if (p >= 0 && add_dev(&f.pending[p], -1) != 1) p = -1;
                 const unsigned long long ready = __ballot(p >= 0);
                 // Parents that became ready.  While the queue holds less than one row per gang (the regime
                 // in which the next dependent step waits for this one: chains, the top of a tree) they go
@@ -465,12 +473,11 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                     if (lane == 0) add_dev(&ctl->direct.v, (unsigned)n_direct);
                     const unsigned seq = published + 1;
                     const int r2 = (int)(seq % GANG_RING);
-#pragma unroll
-                    for (int q = 0; q < GANG_RING; ++q) if (q == r2) my_node[q] = node2;
                     unsigned long long *e = box->slot[r2];
                     st_dev(&e[lane], slot_entry(seq, (unsigned)n_direct, node2));
                     st_dev(&e[TILE_ROWS + lane], slot_entry(seq, (unsigned)n_direct, s0));
                     st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, (unsigned)n_direct, s1));
+                    remember(r2, node2);
                     published += 1;
                 }
                 if (n_queue > 0) {
@@ -525,12 +532,11 @@ __device__ inline void ready_scheduler(const Fwd &f, GangBox *box)
                         }
                     }
                     const int r = (int)(seq % GANG_RING);
-#pragma unroll
-                    for (int q = 0; q < GANG_RING; ++q) if (q == r) my_node[q] = node;
                     unsigned long long *e = box->slot[r];
                     st_dev(&e[lane], slot_entry(seq, m, node));
                     st_dev(&e[TILE_ROWS + lane], slot_entry(seq, m, s0));
                     st_dev(&e[2 * TILE_ROWS + lane], slot_entry(seq, m, s1));
+                    remember(r, node);
                     published += 1;
                     progress = true;
                 }
