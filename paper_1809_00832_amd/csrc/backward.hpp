@@ -292,14 +292,23 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
     // the workgroups of the first row of output tiles also sum the columns of dg they pass over (bias gradient)
     const bool with_bias = bias_out != nullptr && blockIdx.x == 0;
     float bsum[4] = {0.f, 0.f, 0.f, 0.f};
-    auto request = [&](int q0) {                              // operands of nodes q0 .. q0 + 15 into registers
+    // The operands of a step (16 nodes) hang on a chain of three loads: the node from the list, its source rows from
+    // the child (or word) arrays, the data from those rows.  A step has only 16 MFMAs per wave to hide it, so the chain
+    // is spread over three steps: step i requests the data of step i + 1, the source rows of step i + 2 and the node
+    // of step i + 3, each from what the step before has requested.
+    auto node_of = [&](int q0) {                              // stage 1
         const int q = q0 + lq;
-        int s0 = 0, s1 = 0;
-        const bool live = q < q_hi;
-        if (live) {
-            const int node = list[q];
-            if (SEG == 2) { s0 = f.left[node]; s1 = f.right[node]; } else { s0 = f.word[node]; }
+        return q < q_hi ? list[q] : -1;
+    };
+    auto sources_of = [&](int node, int *s0, int *s1) {       // stage 2
+        *s0 = *s1 = 0;
+        if (node >= 0) {
+            if (SEG == 2) { *s0 = f.left[node]; *s1 = f.right[node]; } else { *s0 = f.word[node]; }
         }
+    };
+    auto request = [&](int q0, int node, int s0, int s1) {    // stage 3: operands of nodes q0 .. q0 + 15 into registers
+        const int q = q0 + lq;
+        const bool live = node >= 0;
         if constexpr (VEC4) {      // L and n_cols multiples of 4, rows 16-byte aligned: 4 consecutive columns never leave a segment
             const int k = k0 + lk, j = j0 + lk;
             const int seg = (SEG == 2 && k >= L) ? 1 : 0;
@@ -318,7 +327,12 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
             }
         }
     };
-    request(q_lo);
+    int node1 = node_of(q_lo), s0_1, s1_1;                    // step q_lo: all three stages at once
+    sources_of(node1, &s0_1, &s1_1);
+    request(q_lo, node1, s0_1, s1_1);
+    node1 = node_of(q_lo + WG_Q);                             // step q_lo + 16: node and source rows
+    sources_of(node1, &s0_1, &s1_1);
+    int node2 = node_of(q_lo + 2 * WG_Q);                     // step q_lo + 32: node
     for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
         *reinterpret_cast<floatx4 *>(&as[lq][lk]) = floatx4{ra[0], ra[1], ra[2], ra[3]};
         *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{rb[0], rb[1], rb[2], rb[3]};
@@ -327,7 +341,10 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
             for (int e = 0; e < 4; ++e) bsum[e] += rb[e];
         }
         __syncthreads();
-        if (q0 + WG_Q < q_hi) request(q0 + WG_Q);
+        request(q0 + WG_Q, node1, s0_1, s1_1);                // (beyond the end: node -1, nothing is loaded)
+        node1 = node2;
+        sources_of(node1, &s0_1, &s1_1);
+        node2 = node_of(q0 + 3 * WG_Q);
 #pragma unroll
         for (int kk = 0; kk < WG_Q / 4; ++kk) {
             const int qq = kk * 4 + (lane >> 4);
