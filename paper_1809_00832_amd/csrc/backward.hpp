@@ -273,8 +273,8 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
                                                      const float *__restrict__ table, int L, const float *__restrict__ dg,
                                                      int n_cols, float *__restrict__ out, float *__restrict__ bias_out)
 {
-    __shared__ __align__(16) float as[WG_Q][WG_LD];
-    __shared__ __align__(16) float bs[WG_Q][WG_LD];
+    __shared__ __align__(16) float as[2][WG_Q][WG_LD];         // two buffers each: a step's operands are parked while the
+    __shared__ __align__(16) float bs[2][WG_Q][WG_LD];         // step before is still being multiplied (one barrier per step)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k0 = blockIdx.x * WG_TILE, j0 = blockIdx.y * WG_TILE;
     const int K_out = SEG * L;
@@ -333,14 +333,18 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
     node1 = node_of(q_lo + WG_Q);                             // step q_lo + 16: node and source rows
     sources_of(node1, &s0_1, &s1_1);
     int node2 = node_of(q_lo + 2 * WG_Q);                     // step q_lo + 32: node
-    for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
-        *reinterpret_cast<floatx4 *>(&as[lq][lk]) = floatx4{ra[0], ra[1], ra[2], ra[3]};
-        *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{rb[0], rb[1], rb[2], rb[3]};
+    auto park = [&](int buf) {
+        *reinterpret_cast<floatx4 *>(&as[buf][lq][lk]) = floatx4{ra[0], ra[1], ra[2], ra[3]};
+        *reinterpret_cast<floatx4 *>(&bs[buf][lq][lk]) = floatx4{rb[0], rb[1], rb[2], rb[3]};
         if (with_bias) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) bsum[e] += rb[e];
         }
-        __syncthreads();
+    };
+    park(0);
+    __syncthreads();
+    int buf = 0;
+    for (int q0 = q_lo; q0 < q_hi; q0 += WG_Q) {
         request(q0 + WG_Q, node1, s0_1, s1_1);                // (beyond the end: node -1, nothing is loaded)
         node1 = node2;
         sources_of(node1, &s0_1, &s1_1);
@@ -351,8 +355,8 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
             float a[2], b[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                a[t] = as[qq][wr + t * 16 + (lane & 15)];
-                b[t] = bs[qq][wc + t * 16 + (lane & 15)];
+                a[t] = as[buf][qq][wr + t * 16 + (lane & 15)];
+                b[t] = bs[buf][qq][wc + t * 16 + (lane & 15)];
             }
 #pragma unroll
             for (int ta = 0; ta < 2; ++ta)
@@ -360,7 +364,10 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
                 for (int tb = 0; tb < 2; ++tb)
                     acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
         }
+        // the other buffer was read in the step before this one, and every wave has passed the barrier since
+        if (q0 + WG_Q < q_hi) park(buf ^ 1);
         __syncthreads();
+        buf ^= 1;
     }
 #pragma unroll
     for (int ta = 0; ta < 2; ++ta)
@@ -372,12 +379,12 @@ __global__ __launch_bounds__(256) void k_weight_grad(Fwd f, const int32_t *__res
                 if (k < K_out && j < n_cols) atomicAdd(&out[(size_t)k * n_cols + j], acc[ta][tb][v]);
             }
     if (with_bias) {                                          // uniform per workgroup; the loop ended with a barrier
-        *reinterpret_cast<floatx4 *>(&bs[lq][lk]) = floatx4{bsum[0], bsum[1], bsum[2], bsum[3]};
+        *reinterpret_cast<floatx4 *>(&bs[0][lq][lk]) = floatx4{bsum[0], bsum[1], bsum[2], bsum[3]};
         __syncthreads();
         if (tid < WG_TILE && j0 + tid < n_cols) {
             float t = 0.f;
 #pragma unroll
-            for (int q = 0; q < WG_Q; ++q) t += bs[q][tid];
+            for (int q = 0; q < WG_Q; ++q) t += bs[0][q][tid];
             atomicAdd(&bias_out[j0 + tid], t);
         }
     }
