@@ -420,6 +420,11 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
         __builtin_amdgcn_sched_barrier(0);   // keep the global loads ahead of the MFMAs that hide them
         if (active) {
             const float *arow = &sm.a[buf][(rb * 16 + (lane & 15)) * A_LD + (lane >> 4) * 4];
+            // the operands of a k-step are read from LDS one k-step ahead, so that the read runs under MFMAs
+            floatx4 av_next = *reinterpret_cast<const floatx4 *>(arow);
+            floatx4 bv_next[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) bv_next[g] = sm.b[buf][g * 64 + lane];
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 if (to_boundary == 0) {                 // uniform: a quarter of K is complete
@@ -431,10 +436,15 @@ __device__ inline void cell_tile_staged(TileSmem &sm, const Fwd &f, const Gemm &
                     to_boundary = quarter;
                 }
                 --to_boundary;
-                const floatx4 av = *reinterpret_cast<const floatx4 *>(arow + s * STEP_K);
+                const floatx4 av = av_next;
                 floatx4 bv[NG];
 #pragma unroll
-                for (int g = 0; g < NG; ++g) bv[g] = sm.b[buf][(s * NG + g) * 64 + lane];
+                for (int g = 0; g < NG; ++g) bv[g] = bv_next[g];
+                if (s + 1 < STEPS) {
+                    av_next = *reinterpret_cast<const floatx4 *>(arow + (s + 1) * STEP_K);
+#pragma unroll
+                    for (int g = 0; g < NG; ++g) bv_next[g] = sm.b[buf][((s + 1) * NG + g) * 64 + lane];
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
