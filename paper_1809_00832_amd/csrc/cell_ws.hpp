@@ -234,6 +234,11 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
                 lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh, kept_gates(f, enode, hu), H);
                 st_f<COH>(f.c + o, cc);
                 st_f<COH>(f.h + o, hh);
+            } else if constexpr (EPI == EPI_TD_CHILD) {     // gates i, f, o, u of an LSTM step along the edge (as in cell_tile.hpp)
+                const float i = sigmoid_f(gate[0]), fg = sigmoid_f(gate[1]), og = sigmoid_f(gate[2]), u = tanh_f(gate[3]);
+                const float cc = __builtin_fmaf(fg, cl, i * u);
+                st_f<COH>(f.c + o, cc);
+                st_f<COH>(f.h + o, og * tanh_f(cc));
             } else {
                 st_f<COH>(f.h + o, tanh_f(gate[0]));
             }
@@ -269,6 +274,9 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             const int hc = hu_ok ? hu : 0;
             cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
             cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+        } else if (EPI == EPI_TD_CHILD) {                   // the parent's c (src0 = the parent's row)
+            const int hc = hu_ok ? hu : 0;
+            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
         }
         __builtin_amdgcn_sched_barrier(0);                  // all requests are issued before the MFMAs start
         floatx4 acc[NG];

@@ -50,16 +50,29 @@ __global__ void k_td_reset(TopDown a)
     }
 }
 
-template <bool VEC4>
+// SPW > 0: the expansion step runs on the weight-stationary cell (cell_ws.hpp): every workgroup is tied to one side
+// and one column group for the whole call and keeps that slice of the step's matrix in registers (SPW k-steps per
+// wave), instead of streaming 4 H^2 weights per side and frontier through LDS.  Needs H % 4 == 0, 16-byte aligned
+// rows, at least 2 n_cg workgroups, fewer than 2^24 rows and less than 4 GiB of h (the host checks).
+template <bool VEC4, int SPW = 0>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_td_generate(TopDown a)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
+    using Smem = std::conditional_t<(SPW > 0), WsSmemT<(SPW > 0 ? SPW : 1)>, TileSmem>;
+    Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     const Fwd &f = a.f;
     Ctl *ctl = f.ctl;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int H = f.H, B = a.n_trees;
     const int last_row = B + 2 * ((a.max_nodes - B) / 2);       // rows that whole pairs can fill
+    // weight-stationary form: this workgroup's side, column group and share of the rows
+    const int combos = 2 * f.n_cg;
+    const int my_sd = ((int)blockIdx.x % combos) / f.n_cg, my_cg = ((int)blockIdx.x % combos) % f.n_cg;
+    const int slot = (int)blockIdx.x / combos, n_slots = (int)gridDim.x / combos;
+    WsWeights<EpiTraits<EPI_TD_CHILD>::NG, SPW> w;
+    if constexpr (SPW > 0) {
+        if (slot < n_slots) ws_load(w, a.side[my_sd], my_cg, wave, lane);
+    }
     unsigned epoch = 0;
     int begin = 0, end = B, d = 0;
     for (;; ++d) {
@@ -132,6 +145,33 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_td_generate(TopDown a)
         const int pairs = (new_end - end) / 2;
         if (pairs <= 0) break;
         // ---- expand --------------------------------------------------------------------------
+        if constexpr (SPW > 0) {
+            if (slot < n_slots) {
+                // every slot takes a contiguous share of the pairs, a multiple of 16 rows, in pieces of the row tables' size
+                const int share = ((pairs + n_slots - 1) / n_slots + 15) & ~15;
+                const int lo = slot * share, hi = pairs < lo + share ? pairs : lo + share;
+                for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
+                    const int count = hi - piece < WS_TABLE_ROWS ? hi - piece : WS_TABLE_ROWS;
+                    {
+                        int child = -1, par = 0;
+                        if (tid < count) {
+                            child = end + 2 * (piece + tid) + my_sd;
+                            par = ld_dev(&a.parent[child]);
+                        }
+                        sm.node[tid] = child;
+                        sm.src0[tid] = par > 0 ? par : 0;       // (rows that do not exist read row 0; nothing of them is stored)
+                        sm.src1[tid] = 0;
+                    }
+                    __syncthreads();
+                    ws_tile<EPI_TD_CHILD, true, SPW>(sm, f, a.side[my_sd], f.h, a.max_nodes, count, my_cg, w);
+                }
+            }
+            unsigned unused_ws = 0;
+            if (!grid_barrier(sm, f, epoch, 0u, (unsigned)B, &unused_ws)) return;
+            begin = end;
+            end = new_end;
+            continue;
+        }
         const int n_cg = f.n_cg;
         int conc = (int)gridDim.x / (2 * n_cg);               // tiles the grid works on at once
         if (conc < 1) conc = 1;
@@ -154,7 +194,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_td_generate(TopDown a)
                 sm.src1[tid] = -1;
             }
             __syncthreads();
-            cell_tile<EPI_TD_CHILD, VEC4, true>(sm, f, a.side[sd], f.h, count, cg);
+            if constexpr (SPW == 0) cell_tile<EPI_TD_CHILD, VEC4, true>(sm, f, a.side[sd], f.h, count, cg);
         }
         unsigned unused = 0;
         if (!grid_barrier(sm, f, epoch, 0u, (unsigned)B, &unused)) return;

@@ -90,6 +90,7 @@ struct tl_ctx {
 // Context of the top-down generator (tl_td_*).
 struct tl_td_ctx {
     int device = 0, n_cu = 0, H = 0, n_cg = 0, spin_limit = 0;
+    int spw = 0;                      // k-steps per wave of the weight-stationary expansion step (0: streaming cell only)
     tl::Gemm side[2]{};
     void *wp[2] = {nullptr, nullptr};
     float *bp[2] = {nullptr, nullptr};
@@ -1180,6 +1181,21 @@ int tl_classify_backward(tl_ctx *ctx, int n_rows, const float *h, const float *w
     return TL_OK;
 }
 
+namespace {
+typedef void (*td_kernel)(tl::TopDown);
+td_kernel td_ws_kernel(int spw)
+{
+    switch (spw) {
+    case 1: return tl::k_td_generate<true, 1>;
+    case 2: return tl::k_td_generate<true, 2>;
+    case 4: return tl::k_td_generate<true, 4>;
+    case 5: return tl::k_td_generate<true, 5>;
+    case 8: return tl::k_td_generate<true, 8>;
+    default: return tl::k_td_generate<true, 16>;
+    }
+}
+}  // namespace
+
 int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *w_stop, float b_stop, int spin_limit,
                  tl_td_ctx **out)
 {
@@ -1198,6 +1214,14 @@ int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *
         ctx->n_cg = (H + HU - 1) / HU;
         ctx->b_stop = b_stop;
         ctx->spin_limit = spin_limit > 0 ? spin_limit : DEFAULT_SPIN_LIMIT;
+        // weight-stationary expansion step: H a multiple of 4, the K axis (H) within 16 k-steps of 16 per wave, and a grid
+        // that holds every (side, column group) pair at least once
+        ctx->spw = 0;
+        if (H % 4 == 0 && ctx->n_cu >= 2 * ctx->n_cg) {
+            const int needed = round_up(H, KC) / STEP_K / 4;
+            for (int sz : WS_SIZES)
+                if (sz >= needed) { ctx->spw = sz; break; }
+        }
         // one side's [H x 4H] block of u_td, made contiguous for the packer
         float *block = nullptr;
         TL_HIP(hipMalloc(&block, (size_t)H * 4 * H * sizeof(float)));
@@ -1205,7 +1229,7 @@ int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *
             const hipError_t e = hipMemcpy2D(block, (size_t)4 * H * sizeof(float), u_td + (size_t)sd * 4 * H, (size_t)8 * H * sizeof(float),
                                              (size_t)4 * H * sizeof(float), (size_t)H, hipMemcpyDeviceToDevice);
             if (e != hipSuccess) { (void)hipFree(block); return TL_EHIP; }
-            const int prc = pack_gemm(block, b_td + (size_t)sd * 4 * H, 4, H, 1, H, ctx->n_cg, 0, false, &ctx->side[sd], &ctx->wp[sd], &ctx->bp[sd]);
+            const int prc = pack_gemm(block, b_td + (size_t)sd * 4 * H, 4, H, 1, H, ctx->n_cg, 4 * ctx->spw, false, &ctx->side[sd], &ctx->wp[sd], &ctx->bp[sd]);
             if (prc != TL_OK) { (void)hipFree(block); return prc; }
             if (hipDeviceSynchronize() != hipSuccess) { (void)hipFree(block); return TL_EHIP; }
         }
@@ -1222,6 +1246,9 @@ int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *
                                    (int)TILE_SMEM_BYTES));
         TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_td_generate<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)TILE_SMEM_BYTES));
+        if (ctx->spw > 0)
+            TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(td_ws_kernel(ctx->spw)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)ws_lds_bytes(ctx->spw, false)));
         TL_HIP(hipDeviceSynchronize());
         return TL_OK;
     }();
@@ -1253,7 +1280,11 @@ int tl_td_generate(tl_td_ctx *ctx, int n_trees, int max_nodes, int max_depth, fl
     if (grid < 1) grid = 1;
     const bool vec4 = ctx->H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
     hipLaunchKernelGGL(k_td_reset, dim3(4), dim3(256), 0, st, a);
-    if (vec4)
+    // the weight-stationary cell addresses rows with 24-bit row numbers and 32-bit byte offsets
+    const bool ws_range = max_nodes < (1 << 24) && (unsigned long long)max_nodes * ctx->H * 4ull < (1ull << 32);
+    if (vec4 && ctx->spw > 0 && ws_range && grid >= 2 * ctx->n_cg)
+        hipLaunchKernelGGL(td_ws_kernel(ctx->spw), dim3(grid), dim3(WG_THREADS), ws_lds_bytes(ctx->spw, false), st, a);
+    else if (vec4)
         hipLaunchKernelGGL(k_td_generate<true>, dim3(grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, a);
     else
         hipLaunchKernelGGL(k_td_generate<false>, dim3(grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, a);

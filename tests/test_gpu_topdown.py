@@ -156,7 +156,8 @@ def test_full_size_batch_of_64():
 
 def test_closed_forms_limits_and_ragged_sizes():
     print("case topdown closed forms", flush=True)
-    for i, (B, H, D) in enumerate([(5, 33, 4), (1, 6, 5), (3, 150, 3), (70, 64, 2)]):
+    # (H = 64, 100, 320: the expansion step on the weight-stationary cell, the last two with a padded K axis)
+    for i, (B, H, D) in enumerate([(5, 33, 4), (1, 6, 5), (3, 150, 3), (70, 64, 2), (9, 100, 4), (4, 320, 3)]):
         w = synth.make_topdown(40 + i, "case", B, H, D, B * (2 ** (D + 1) - 1) + 3, 6.0, 0.0)
         zero = np.zeros_like(w.w_stop)
         full = generate(w, w_stop=zero, b_stop=1.0)
