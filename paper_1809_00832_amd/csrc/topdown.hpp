@@ -81,30 +81,51 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_td_generate(TopDown a)
         const int n_front = end - begin;
         for (int chunk = blockIdx.x; chunk * TD_DECIDE < n_front; chunk += gridDim.x) {
             const int first = begin + chunk * TD_DECIDE;
+            // the wave's four nodes side by side: their rows are requested together, one round trip per 256 (64) elements
+            // of H instead of one per node and piece (every lane still adds up its elements of a row in ascending order)
+            const float *hr[4];
+            bool valid[4];
+            float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int n = first + wave * 4 + j;
-                const bool valid = n < end;
-                const float *hr = f.h + (size_t)(valid ? n : 0) * H;
-                float part = 0.f;
-                if (VEC4) {
-                    for (int k = lane * 4; k < H; k += 256) {
-                        const floatx4 x = ld_f4<true>(hr + k);
-                        const floatx4 w = *reinterpret_cast<const floatx4 *>(a.w_stop + k);
-                        part = __builtin_fmaf(x.x, w.x, part);
-                        part = __builtin_fmaf(x.y, w.y, part);
-                        part = __builtin_fmaf(x.z, w.z, part);
-                        part = __builtin_fmaf(x.w, w.w, part);
-                    }
-                } else {
-                    for (int k = lane; k < H; k += 64) part = __builtin_fmaf(ld_f<true>(hr + k), a.w_stop[k], part);
-                }
+                valid[j] = n < end;
+                hr[j] = f.h + (size_t)(valid[j] ? n : 0) * H;
+            }
+            if (VEC4) {
+                for (int k = lane * 4; k < H; k += 256) {
+                    floatx4 x[4];
 #pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o);
-                const float score = part + a.b_stop;
+                    for (int j = 0; j < 4; ++j) x[j] = ld_f4<true>(hr[j] + k);
+                    const floatx4 wv = *reinterpret_cast<const floatx4 *>(a.w_stop + k);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        part[j] = __builtin_fmaf(x[j].x, wv.x, part[j]);
+                        part[j] = __builtin_fmaf(x[j].y, wv.y, part[j]);
+                        part[j] = __builtin_fmaf(x[j].z, wv.z, part[j]);
+                        part[j] = __builtin_fmaf(x[j].w, wv.w, part[j]);
+                    }
+                }
+            } else {
+                for (int k = lane; k < H; k += 64) {
+                    float x[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x[j] = ld_f<true>(hr[j] + k);
+                    const float wv = a.w_stop[k];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) part[j] = __builtin_fmaf(x[j], wv, part[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = first + wave * 4 + j;
+                float p = part[j];
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) p += __shfl_xor(p, o);
+                const float score = p + a.b_stop;
                 if (lane == 0) {
-                    sm.src0[wave * 4 + j] = (valid && score > 0.f && d < a.max_depth) ? 1 : 0;
-                    if (valid) a.score[n] = score;
+                    sm.src0[wave * 4 + j] = (valid[j] && score > 0.f && d < a.max_depth) ? 1 : 0;
+                    if (valid[j]) a.score[n] = score;
                 }
             }
             __syncthreads();
