@@ -303,7 +303,10 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                 const int count = min(hi - piece, WS_TABLE_ROWS);
                 {
                     int node = -1, s0 = -1, s1 = -1;
-                    if (tid < count && !qrec_load(&f.q_rec[begin + piece + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
+                    if (tid < count && !qrec_load(&f.q_rec[begin + piece + tid], &node, &s0, &s1)) {
+                        node = s0 = s1 = -1;
+                        latch_error(ctl, TL_ESTALL);          // a record inside the frontier that is not there: never skipped silently
+                    }
                     sm.node[tid] = node;
                     sm.src0[tid] = max(s0, 0);
                     sm.src1[tid] = max(s1, 0);
@@ -346,7 +349,10 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                 }
                 if (tid < TILE_ROWS) {
                     int node = -1, s0 = -1, s1 = -1;
-                    if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) node = s0 = s1 = -1;
+                    if (tid < count && !qrec_load(&f.q_rec[begin + start + tid], &node, &s0, &s1)) {
+                        node = s0 = s1 = -1;
+                        latch_error(ctl, TL_ESTALL);
+                    }
                     sm.node[tid] = node;
                     sm.src0[tid] = s0;
                     sm.src1[tid] = s1;

@@ -23,7 +23,37 @@ def assert_grad_close(got, ref, what):
     return float(err.max() / max(np.abs(ref).max(), 1e-30))
 
 
-def run_case(params, trees, seed, what, keep=False, scheduler="level_device"):
+def oracle_backward_whole_batch(params, trees, h, c, g_h, n_parts=16):
+    """The checker's (single-threaded) backward on n_parts disjoint sets of trees, side by side from Python threads (a
+    ctypes call releases the interpreter lock); the sets' weight gradients are added in float64 here, since a gradient
+    with respect to a shared parameter is the sum over the trees, and every node's d_x row belongs to one tree."""
+    from concurrent.futures import ThreadPoolExecutor
+    B = trees.n_trees
+    sizes = np.diff(trees.tree_off)
+    parts = [[] for _ in range(min(n_parts, B))]
+    load = np.zeros(len(parts))
+    for t in np.argsort(-sizes, kind="stable"):            # largest first onto the lightest set
+        k = int(np.argmin(load))
+        parts[k].append(int(t))
+        load[k] += sizes[t]
+
+    def one(pick):
+        sub, orig = synth.subset(trees, sorted(pick))
+        return orig, oracle.backward(params, sub, h[orig], None if c is None else c[orig], g_h[orig])
+
+    with ThreadPoolExecutor(len(parts)) as pool:
+        results = list(pool.map(one, parts))
+    total = {}
+    for orig, r in results:
+        for k, v in r.items():
+            if k == "d_x":
+                total.setdefault(k, np.zeros((trees.n_nodes, v.shape[1]), np.float64))[orig] = v
+            else:
+                total[k] = total.get(k, 0.0) + v.astype(np.float64)
+    return total
+
+
+def run_case(params, trees, seed, what, keep=False, scheduler="level_device", whole_batch=False):
     rng = np.random.default_rng(seed)
     net = binding.TreeNet(params, scheduler=scheduler)
     try:
@@ -40,7 +70,8 @@ def run_case(params, trees, seed, what, keep=False, scheduler="level_device"):
         h, c = b["h"].cpu().numpy(), b["c"].cpu().numpy()
     finally:
         net.close()
-    ref = oracle.backward(params, trees, h, c, g_h)          # same forward states as the GPU used
+    # same forward states as the GPU used
+    ref = oracle_backward_whole_batch(params, trees, h, c, g_h) if whole_batch else oracle.backward(params, trees, h, c, g_h)
     rel = {k: assert_grad_close(got[k], ref[k], "%s %s" % (what, k)) for k in ref}
     print("   ", what, {k: "%.1e" % v for k, v in rel.items()}, flush=True)
     assert not got["d_x"][trees.left >= 0].any()
@@ -70,13 +101,27 @@ def test_backward_ragged_and_degenerate():
         run_case(params, trees, 60 + i, "ragged%d" % i)
 
 
-def test_backward_full_size_subset_of_trees():
-    """H = 512, E = 300 (the sizes of the `throughput` workload) on its first 24 trees: the checker's backward is a
-    single-threaded double-precision evaluation, so the whole batch would take minutes."""
-    print("case backward throughput subset", flush=True)
+@pytest.mark.parametrize("keep", [False, True])
+def test_backward_full_size_whole_batch(keep):
+    """The `throughput` workload as it is (256 trees, 13 572 nodes, H = 512, E = 300), gates recomputed and kept:
+    every gradient array of the whole batch against the checker, so that every slice of the node axis of the
+    weight-gradient contraction is covered."""
+    print("case backward throughput, whole batch, kept gates:", keep, flush=True)
     w = synth.workload("throughput")
-    sub, _ = synth.subset(w.trees, list(range(24)))
-    run_case(w.params, sub, 5, "throughput[:24]")
+    run_case(w.params, w.trees, 5, "throughput", keep=keep, whole_batch=True)
+
+
+def test_whole_batch_reference_equals_the_checker_in_one_piece():
+    """The split of the checker's backward over sets of trees (used for the full-size batches) against the checker
+    run on the same batch in one piece."""
+    w = synth.workload("sentence")
+    rng = np.random.default_rng(11)
+    fw = oracle.forward_params(w.params, w.trees, n_threads=4)
+    g_h = rng.standard_normal(fw["h"].shape).astype(np.float32)
+    one = oracle.backward(w.params, w.trees, fw["h"], fw["c"], g_h)
+    many = oracle_backward_whole_batch(w.params, w.trees, fw["h"], fw["c"], g_h, n_parts=7)
+    for k in one:
+        assert np.abs(many[k] - one[k]).max() <= 1e-6 * max(np.abs(one[k]).max(), 1e-30), k
 
 
 @pytest.mark.parametrize("scheduler", ["level_device", "ready", "level_host"])
@@ -229,7 +274,7 @@ def test_a_few_training_steps_reduce_the_loss():
     assert all(b_ < a_ for a_, b_ in zip(losses, losses[1:])), losses
 
 
-def run_rnn_case(params, trees, seed, what):
+def run_rnn_case(params, trees, seed, what, whole_batch=False):
     rng = np.random.default_rng(seed)
     net = binding.TreeNet(params, scheduler="level_device")
     try:
@@ -245,7 +290,7 @@ def run_rnn_case(params, trees, seed, what):
         h = b["h"].cpu().numpy()
     finally:
         net.close()
-    ref = oracle.backward(params, trees, h, None, g_h)
+    ref = oracle_backward_whole_batch(params, trees, h, None, g_h) if whole_batch else oracle.backward(params, trees, h, None, g_h)
     rel = {k: assert_grad_close(got[k], ref[k], "%s %s" % (what, k)) for k in ref}
     print("   ", what, {k: "%.1e" % v for k, v in rel.items()}, flush=True)
     assert not got["d_x"][trees.left >= 0].any()
@@ -253,15 +298,15 @@ def run_rnn_case(params, trees, seed, what):
 
 def test_treernn_backward_matches_oracle():
     """TreeRNN: gradients of W, b and of every leaf's embedding row against the checker, on ragged sizes, on the
-    first trees of the `treernn` workload (d = 256), and after an SGD step through the context."""
+    whole `treernn` workload (d = 256, 256 trees), and after an SGD step through the context."""
     print("case treernn backward", flush=True)
     for i, (d, leaves) in enumerate([(5, [1]), (6, [1, 1, 2]), (20, [2, 9]), (33, [1, 2, 3, 1, 70, 5]), (64, [17] * 9 + [1] + [130])]):
         params = synth.make_rnn_params(90 + i, synth.CELL_TREERNN, 50, d, scale=0.4)
         trees = synth.make_trees(90 + i, leaves, ["random"] * len(leaves), 50)
         run_rnn_case(params, trees, 90 + i, "rnn ragged%d" % i)
     w = synth.workload("treernn")
+    run_rnn_case(w.params, w.trees, 6, "treernn, whole batch", whole_batch=True)
     sub, _ = synth.subset(w.trees, list(range(40)))
-    run_rnn_case(w.params, sub, 6, "treernn[:40]")
     # update: parameters as the formula says, and the next forward equals that of a fresh context
     p = w.params
     lr = np.float32(0.1)
@@ -288,7 +333,7 @@ def test_treernn_backward_matches_oracle():
         fresh.close()
 
 
-def run_rntn_case(params, trees, seed, what):
+def run_rntn_case(params, trees, seed, what, whole_batch=False):
     rng = np.random.default_rng(seed)
     net = binding.TreeNet(params, scheduler="level_device")
     try:
@@ -304,7 +349,7 @@ def run_rntn_case(params, trees, seed, what):
         h = b["h"].cpu().numpy()
     finally:
         net.close()
-    ref = oracle.backward(params, trees, h, None, g_h)
+    ref = oracle_backward_whole_batch(params, trees, h, None, g_h) if whole_batch else oracle.backward(params, trees, h, None, g_h)
     rel = {k: assert_grad_close(got["d_w_leaf" if k == "d_v" else k], ref[k], "%s %s" % (what, k)) for k in ref}
     print("   ", what, {k: "%.1e" % v for k, v in rel.items()}, flush=True)
     assert not got["d_x"][trees.left >= 0].any()
@@ -312,7 +357,7 @@ def run_rntn_case(params, trees, seed, what):
 
 def test_rntn_backward_matches_oracle():
     """RNTN: gradients of V, W, b and of every leaf's embedding row against the checker, on ragged sizes and on the
-    first trees of the `rntn` workload (d = 64); then an SGD step: parameters as the formula says, and the next
+    whole `rntn` workload (d = 64, 256 trees); then an SGD step: parameters as the formula says, and the next
     forward equals that of a fresh context."""
     print("case rntn backward", flush=True)
     for i, (d, leaves) in enumerate([(3, [1]), (5, [1, 1, 2]), (8, [2, 9]), (12, [1, 2, 3, 1, 40, 5]), (32, [17] * 5 + [1] + [70])]):
@@ -320,8 +365,8 @@ def test_rntn_backward_matches_oracle():
         trees = synth.make_trees(95 + i, leaves, ["random"] * len(leaves), 50)
         run_rntn_case(params, trees, 95 + i, "rntn ragged%d" % i)
     w = synth.workload("rntn")
+    run_rntn_case(w.params, w.trees, 8, "rntn, whole batch", whole_batch=True)
     sub, _ = synth.subset(w.trees, list(range(12)))
-    run_rntn_case(w.params, sub, 8, "rntn[:12]")
     p = w.params
     lr = np.float32(0.1)
     net = binding.TreeNet(p, scheduler="level_device")
