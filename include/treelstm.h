@@ -99,9 +99,10 @@ enum tl_error {
     TL_ESTRUCT = -4,   /* malformed batch: offsets not ascending / child outside its tree /
                           node with two parents / tree without exactly one root / leaf word id
                           outside the vocabulary / node count inconsistent with full binary trees */
-    TL_ESTALL = -5     /* TL_SCHED_READY made no progress within its spin budget (nodes that are
+    TL_ESTALL = -5,    /* TL_SCHED_READY made no progress within its spin budget (nodes that are
                           unreachable from any leaf, e.g. a cycle); outputs are incomplete.  The
                           level schedulers report such a batch as TL_ESTRUCT.                   */
+    TL_ELIMIT = -6     /* tl_forward_noalloc: the batch does not fit the fixed workspace         */
 };
 
 typedef struct {
@@ -167,6 +168,33 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes,
                const int32_t *tree_off, const int32_t *left, const int32_t *right,
                const int32_t *word, float *h, float *c, float *h_root, float *c_root,
                int32_t *root, void *hip_stream);
+
+/*
+ * tl_forward for callers that cannot allocate device memory while they run: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same results bit for bit as tl_forward, but the scheduler state (parent links, ready
+ * counters, ready queue, mailboxes, control block, and the bf16 copy of h that TL_BF16_IN gathers
+ * from) lives in one fixed array that is part of the library's device code - about 17.2 MiB of
+ * every GPU the library is used on, held until the process ends - instead of a workspace that the
+ * context allocates and grows.  The call allocates, creates and frees nothing (no hipMalloc,
+ * hipHostMalloc, hipFree, event creation), never synchronises, and only enqueues kernels on
+ * hip_stream.  Limits:
+ *   n_nodes <= TL_NOALLOC_MAX_NODES, and with TL_BF16_IN also
+ *   n_nodes * roundup(H, 8) <= TL_NOALLOC_MAX_NODES * 512     else TL_ELIMIT (nothing is enqueued)
+ *   TL_SCHED_LEVEL_HOST contexts                               TL_EINVAL (that scheduler reads
+ *                                                              level offsets back to the host)
+ * Stage timing (tl_set_profiling) is not recorded and gate activations (tl_set_keep_gates) are not
+ * kept by this call.  tl_status and tl_last_stats afterwards report on this call like on a
+ * tl_forward.  All contexts of a process share the one array of their GPU, which holds whatever
+ * the last call left there (every call resets what it needs): two such calls that overlap in time
+ * on one GPU - from two contexts or two streams - race and give wrong results; order them on one
+ * stream or with events.  tl_forward calls are not affected (they use the context's own workspace).
+ */
+enum { TL_NOALLOC_MAX_NODES = 16384 };
+int tl_forward_noalloc(tl_ctx *ctx, int n_trees, int n_nodes,
+                       const int32_t *tree_off, const int32_t *left, const int32_t *right,
+                       const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+                       int32_t *root, void *hip_stream);
 
 /* Waits for the stream of the last tl_forward and returns its latched device-side
  * error (TL_OK if none). */

@@ -16,12 +16,13 @@ LIB_PATH = os.path.join(HERE, "libtreelstm.so")
 TL_TREELSTM, TL_TREERNN, TL_RNTN = 0, 1, 2
 TL_F32, TL_BF16_IN = 0, 1
 TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST, TL_SCHED_READY_PRIORITY = 0, 1, 2, 3
-TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL = 0, -1, -2, -3, -4, -5
+TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL, TL_ELIMIT = 0, -1, -2, -3, -4, -5, -6
+TL_NOALLOC_MAX_NODES = 16384
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST,
               "ready_priority": TL_SCHED_READY_PRIORITY}
 
-EXPORTS = ("tl_create", "tl_forward", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward",
+EXPORTS = ("tl_create", "tl_forward", "tl_forward_noalloc", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward",
            "tl_set_keep_gates", "tl_sgd_update", "tl_get_params", "tl_classify", "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
 
 
@@ -49,6 +50,8 @@ def lib():
         L.tl_create.argtypes = [ctypes.POINTER(tl_config), ctypes.POINTER(vp)]
         L.tl_forward.restype = ci
         L.tl_forward.argtypes = [vp, ci, ci] + [vp] * 10
+        L.tl_forward_noalloc.restype = ci
+        L.tl_forward_noalloc.argtypes = [vp, ci, ci] + [vp] * 10
         L.tl_status.restype = ci
         L.tl_status.argtypes = [vp]
         L.tl_set_profiling.restype = ci
@@ -121,6 +124,16 @@ def tl_forward(ctx, n_trees, n_nodes, tree_off, left, right, word, h, c=None, h_
         stream = torch.cuda.current_stream().cuda_stream
     _check(lib().tl_forward(ctx, n_trees, n_nodes, _ptr(tree_off), _ptr(left), _ptr(right), _ptr(word), _ptr(h),
                             _ptr(c), _ptr(h_root), _ptr(c_root), _ptr(root), stream), "tl_forward")
+
+
+def tl_forward_noalloc(ctx, n_trees, n_nodes, tree_off, left, right, word, h, c=None, h_root=None, c_root=None, root=None,
+                       stream=None) -> None:
+    """Same arguments as tl_forward; the library allocates nothing during the call (fixed per-GPU workspace)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    _check(lib().tl_forward_noalloc(ctx, n_trees, n_nodes, _ptr(tree_off), _ptr(left), _ptr(right), _ptr(word), _ptr(h),
+                                    _ptr(c), _ptr(h_root), _ptr(c_root), _ptr(root), stream), "tl_forward_noalloc")
 
 
 def tl_status(ctx) -> int:

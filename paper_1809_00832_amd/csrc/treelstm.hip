@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "treelstm.h"
@@ -42,6 +43,7 @@ struct tl_ctx {
     // workspace
     unsigned char *ws = nullptr;
     size_t ws_bytes = 0;
+    unsigned char *scratch = nullptr;  // this device's copy of the fixed workspace of tl_forward_noalloc (not owned)
     int cap_nodes = 0, cap_trees = 0;
     int32_t *host_levels = nullptr;   // pinned, cap_nodes + 2
     Ctl *host_ctl = nullptr;          // pinned
@@ -375,7 +377,41 @@ int pack_rntn_f32(tl_ctx *ctx, hipStream_t st)
     return TL_OK;
 }
 
-size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+constexpr size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Bytes of the workspace for batches of up to N nodes / B trees (carve_workspace cuts it up).
+constexpr size_t workspace_bytes(size_t N, size_t B)
+{
+    return align256((N + 2) * 4) * 12 + align256(B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
+}
+
+// Workspace of tl_forward_noalloc: one array per device, part of the loaded code object, so that the call has
+// nothing to allocate.  First the workspace proper for TL_NOALLOC_MAX_NODES nodes (and as many trees), then room
+// for the bf16 copy of h that the bf16 weight-stationary cell gathers from.  Host code must not use the name
+// `scratch` as an address: tl_create asks the runtime for the array's address on its device (scratch_address).
+constexpr size_t NOALLOC_WS_BYTES = workspace_bytes(TL_NOALLOC_MAX_NODES, TL_NOALLOC_MAX_NODES);
+constexpr size_t NOALLOC_HB_BYTES = (size_t)TL_NOALLOC_MAX_NODES * 512 * sizeof(unsigned short);
+static __device__ __align__(256) unsigned char scratch[NOALLOC_WS_BYTES + NOALLOC_HB_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+unsigned char *scratch_of_device[MAX_DEVICES];
+
+// Address of `scratch` on the current device (which must be `device`); looked up once per device.
+int scratch_address(int device, unsigned char **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= MAX_DEVICES) return TL_EINVAL;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_of_device[device]) {
+        void *p = nullptr;
+        TL_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return TL_EHIP;
+        scratch_of_device[device] = static_cast<unsigned char *>(p);
+    }
+    *out = scratch_of_device[device];
+    return TL_OK;
+}
 
 // Workspace for batches of up to n_nodes nodes / n_trees trees.
 int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
@@ -388,8 +424,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     if (ctx->hb) { TL_HIP(hipFree(ctx->hb)); ctx->hb = nullptr; }
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
-    const size_t n4 = align256((size_t)(N + 2) * 4);
-    const size_t bytes = n4 * 12 + align256((size_t)B * 4) + align256(sizeof(Ctl)) + align256(sizeof(GangBox) * MAX_GANGS) + 4096;
+    const size_t bytes = workspace_bytes((size_t)N, (size_t)B);
     TL_HIP(hipMalloc(&ctx->ws, bytes));
     TL_HIP(hipMemset(ctx->ws, 0, bytes));   // includes the block of zeros at the end, which is never written again
     if (ctx->spw > 0 && ctx->cfg.precision == TL_BF16_IN) {
@@ -404,10 +439,11 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     return TL_OK;
 }
 
-void carve_workspace(const tl_ctx *ctx, Fwd *f)
+// Cuts a workspace of workspace_bytes(cap_nodes, cap_trees) bytes at `base` into the arrays of a forward.
+void carve_workspace(unsigned char *base, int cap_nodes, int cap_trees, Fwd *f)
 {
-    const size_t n4 = align256((size_t)(ctx->cap_nodes + 2) * 4);
-    unsigned char *p = ctx->ws;
+    const size_t n4 = align256((size_t)(cap_nodes + 2) * 4);
+    unsigned char *p = base;
     auto take = [&](size_t b) { unsigned char *r = p; p += b; return r; };
     f->parent = (int32_t *)take(n4);
     f->pending = (int32_t *)take(n4);
@@ -420,7 +456,7 @@ void carve_workspace(const tl_ctx *ctx, Fwd *f)
     f->level_nodes = (int32_t *)take(n4);
     f->q_rec = (QRec *)take(2 * n4);       // n_int <= N / 2 records of 16 bytes
     f->depth_root = (int32_t *)take(n4);
-    f->root_ws = (int32_t *)take(align256((size_t)ctx->cap_trees * 4));
+    f->root_ws = (int32_t *)take(align256((size_t)cap_trees * 4));
     f->ctl = (Ctl *)take(align256(sizeof(Ctl)));
     f->gangs = (GangBox *)take(align256(sizeof(GangBox) * MAX_GANGS));
     f->zeros = (const float *)take(4096);
@@ -642,6 +678,7 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         ctx->rntn_units = units;
     }
     TL_HIP(hipHostMalloc(&ctx->host_ctl, sizeof(Ctl), hipHostMallocDefault));
+    if ((rc = scratch_address(ctx->device, &ctx->scratch)) != TL_OK) return rc;
     return TL_OK;
 }
 
@@ -695,9 +732,15 @@ int tl_create(const tl_config *cfg, tl_ctx **out)
     return TL_OK;
 }
 
-int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
-               const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
-               int32_t *root, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// tl_forward (static_ws false: workspace owned by the context, grown on demand) and tl_forward_noalloc (static_ws
+// true: the fixed per-device array; nothing is allocated, created or freed on this path).
+int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+                 const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+                 int32_t *root, void *hip_stream)
 {
     if (!ctx) return TL_EINVAL;
     if (n_trees == 0 && n_nodes == 0) {     // an empty batch: nothing to evaluate, nothing is launched or written
@@ -711,8 +754,15 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     if (cfg.cell == TL_TREELSTM && !c) return TL_EINVAL;
     if (((long long)n_nodes + n_trees) % 2 != 0) return TL_ESTRUCT;   // full binary trees: N = 2 leaves - trees
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = ensure_workspace(ctx, n_nodes, n_trees);
-    if (rc != TL_OK) return rc;
+    int rc = TL_OK;
+    if (static_ws) {
+        if (cfg.scheduler == TL_SCHED_LEVEL_HOST) return TL_EINVAL;      // reads level offsets back through a pinned buffer it would have to allocate
+        if (n_nodes > TL_NOALLOC_MAX_NODES) return TL_ELIMIT;
+        if (cfg.precision == TL_BF16_IN && (size_t)n_nodes * ctx->hs * sizeof(unsigned short) > NOALLOC_HB_BYTES) return TL_ELIMIT;   // bf16 copy of h
+        if (!ctx->scratch) return TL_EHIP;
+    } else if ((rc = ensure_workspace(ctx, n_nodes, n_trees)) != TL_OK) {
+        return rc;
+    }
 
     Fwd f{};
     f.n_trees = n_trees;
@@ -725,9 +775,10 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.cell = cfg.cell; f.H = cfg.hidden; f.E = cfg.embed_dim; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg; f.bf16 = cfg.precision == TL_BF16_IN;
     f.emb = ctx->emb; f.embb = ctx->embb; f.es = ctx->es;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
-    carve_workspace(ctx, &f);
+    if (static_ws) carve_workspace(ctx->scratch, TL_NOALLOC_MAX_NODES, TL_NOALLOC_MAX_NODES, &f);
+    else carve_workspace(ctx->ws, ctx->cap_nodes, ctx->cap_trees, &f);
     ctx->gates_nodes = 0;
-    if (ctx->keep_gates && cfg.cell == TL_TREELSTM && cfg.precision == TL_F32) {
+    if (!static_ws && ctx->keep_gates && cfg.cell == TL_TREELSTM && cfg.precision == TL_F32) {
         if (n_nodes > ctx->gates_cap) {
             TL_HIP(hipDeviceSynchronize());
             if (ctx->gates) { TL_HIP(hipFree(ctx->gates)); ctx->gates = nullptr; }
@@ -747,7 +798,10 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     const bool pair_inner = (cfg.hidden % 2 == 0) && (((uintptr_t)h & 7) == 0);      // rows 8-byte aligned
     const int spw = ((bf16 || pair_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
-    if (persistent && spw > 0 && bf16) { f.hb = ctx->hb; f.hs = ctx->hs; }
+    if (persistent && spw > 0 && bf16) {
+        f.hb = static_ws ? reinterpret_cast<unsigned short *>(ctx->scratch + NOALLOC_WS_BYTES) : ctx->hb;
+        f.hs = ctx->hs;
+    }
     const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
     // RNTN: a frontier of at most rntn_units tiles is cut into RNTN_PARTS workgroups per tile and column group
@@ -763,7 +817,7 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
-    const bool prof = ctx->profiling != 0;
+    const bool prof = ctx->profiling != 0 && !static_ws;      // (recording may have to create events)
     const int nb_nodes = (n_nodes + 1 + 255) / 256;
     const int nb_big = (n_nodes + 1 + NODE_BLOCK - 1) / NODE_BLOCK;
 
@@ -779,6 +833,14 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
         TL_HIP(hipEventRecord(ev[0], st));
     }
     // ---- structure pass ----------------------------------------------------------------
+    if (static_ws && f.hb && ctx->hs != cfg.hidden) {
+        // the padding at the end of each row of the bf16 copy of h must read as zero, and the shared array may hold
+        // what a context of another hidden size left there
+        ZeroList z{};
+        z.p[0] = reinterpret_cast<float *>(f.hb);
+        z.n[0] = (size_t)n_nodes * ctx->hs * sizeof(unsigned short) / sizeof(float);      // hs is a multiple of 8
+        hipLaunchKernelGGL(k_zero_many, dim3(256), dim3(256), 0, st, z);
+    }
     hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
     hipLaunchKernelGGL(k_scatter, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
@@ -855,6 +917,24 @@ int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, c
         ctx->n_recorded += 1;
     }
     return TL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tl_forward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+               const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+               int32_t *root, void *hip_stream)
+{
+    return forward_impl(ctx, false, n_trees, n_nodes, tree_off, left, right, word, h, c, h_root, c_root, root, hip_stream);
+}
+
+int tl_forward_noalloc(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, const int32_t *left,
+                       const int32_t *right, const int32_t *word, float *h, float *c, float *h_root, float *c_root,
+                       int32_t *root, void *hip_stream)
+{
+    return forward_impl(ctx, true, n_trees, n_nodes, tree_off, left, right, word, h, c, h_root, c_root, root, hip_stream);
 }
 
 int tl_status(tl_ctx *ctx)
@@ -938,7 +1018,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     f.cell = cfg.cell; f.H = H; f.E = E; f.vocab = cfg.vocab; f.n_cg = ctx->n_cg;
     f.emb = ctx->emb;
     f.leaf = ctx->g_leaf; f.inner = ctx->g_inner;
-    carve_workspace(ctx, &f);
+    carve_workspace(ctx->ws, ctx->cap_nodes, ctx->cap_trees, &f);
     f.spin_limit = DEFAULT_SPIN_LIMIT;
     f.cap_tiles = ctx->persistent_grid / ctx->n_cg > 0 ? ctx->persistent_grid / ctx->n_cg : 1;
     const size_t cap = (size_t)ctx->bw_nodes;
@@ -1320,6 +1400,7 @@ const char *tl_strerror(int code)
     case TL_EHIP: return "HIP runtime error";
     case TL_ESTRUCT: return "malformed tree batch";
     case TL_ESTALL: return "scheduler made no progress (unreachable nodes)";
+    case TL_ELIMIT: return "batch larger than the fixed workspace of tl_forward_noalloc";
     default: return "unknown error";
     }
 }
