@@ -358,7 +358,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="throughput")
-    ap.add_argument("--scheduler", default="level_device", choices=["ready", "level_device", "level_host", "ready_priority"])
+    ap.add_argument("--scheduler", default="level_device", choices=["ready", "level_device", "level_host", "ready_priority", "dataflow"])
     ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
@@ -443,7 +443,7 @@ def main():
         out["backward"] = backward_stage(w, args.head)
     if not args.no_compare:
         comp = {}
-        for sched in ("ready", "ready_priority", "level_device", "level_host"):
+        for sched in ("dataflow", "ready", "ready_priority", "level_device", "level_host"):
             if sched == args.scheduler:
                 continue
             r = run_scheduler(w, sched, precision, args.steps, args.warmup, graph=args.graph)

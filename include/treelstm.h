@@ -34,7 +34,7 @@
  *
  * Threading: a context is not thread safe; one forward may be in flight per context.
  * TL_SCHED_READY (also in its _PRIORITY variant, which is meant wherever TL_SCHED_READY is
- * named below) and TL_SCHED_LEVEL_DEVICE evaluate the internal nodes in one kernel whose
+ * named below), TL_SCHED_LEVEL_DEVICE and TL_SCHED_DATAFLOW evaluate the internal nodes in one kernel whose
  * workgroups wait for each other, so all of them must be resident together: they are sized to
  * fill the device, and while such a forward runs nothing else that holds compute units for long
  * (another context's forward on a second stream, say) may run on the same device.  Breaking
@@ -87,9 +87,27 @@ enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
  *                        that gang takes no other work while it holds such a chain.  Pays
  *                        when a few deep trees share a batch with much shallow work, costs
  *                        the extra launches otherwise.
+ *  TL_SCHED_DATAFLOW     the ready counters of Section 4.1 with nothing shared between the
+ *                        workers.  The trees are dealt to sets of workgroups (one workgroup per 16
+ *                        hidden units) in contiguous ranges of about equal node count; every
+ *                        workgroup keeps, for the trees of its set, its own counters of handed-out
+ *                        children and its own list of ready nodes, so no queue, record, mailbox or
+ *                        grid-wide barrier is exchanged about the schedule.  Whether a child's row
+ *                        has been written is read off the row itself: the rows that internal nodes
+ *                        will produce are filled with a bit pattern that no cell stores (all ones, a
+ *                        NaN) before the kernel starts, and a consumer repeats its request while a
+ *                        piece of the row still shows it.  A dependent step costs about one memory
+ *                        round trip instead of an acknowledgement, a barrier and a queue read, so
+ *                        this is the fastest choice for deep or narrow batches and as fast as
+ *                        TL_SCHED_LEVEL_DEVICE on wide ones.  Consequence: if the parameters or
+ *                        embeddings hold NaNs whose bits are all ones, a forward ends with
+ *                        TL_ESTALL instead of NaN results.  Where the weight-stationary cell is not
+ *                        used (TL_RNTN, hidden > 512, odd hidden in TL_F32, tl_forward_noalloc)
+ *                        TL_SCHED_LEVEL_DEVICE stands in.  Unreachable nodes: TL_ESTRUCT.
  * Results do not depend on the scheduler: all paths of one precision sum a node's
  * contraction in the same order, so all of them agree bit for bit. */
-enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2, TL_SCHED_READY_PRIORITY = 3 };
+enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2, TL_SCHED_READY_PRIORITY = 3,
+                    TL_SCHED_DATAFLOW = 4 };
 
 enum tl_error {
     TL_OK = 0,

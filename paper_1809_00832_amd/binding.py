@@ -15,12 +15,12 @@ LIB_PATH = os.path.join(HERE, "libtreelstm.so")
 
 TL_TREELSTM, TL_TREERNN, TL_RNTN = 0, 1, 2
 TL_F32, TL_BF16_IN = 0, 1
-TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST, TL_SCHED_READY_PRIORITY = 0, 1, 2, 3
+TL_SCHED_READY, TL_SCHED_LEVEL_DEVICE, TL_SCHED_LEVEL_HOST, TL_SCHED_READY_PRIORITY, TL_SCHED_DATAFLOW = 0, 1, 2, 3, 4
 TL_OK, TL_EINVAL, TL_ENOMEM, TL_EHIP, TL_ESTRUCT, TL_ESTALL, TL_ELIMIT = 0, -1, -2, -3, -4, -5, -6
 TL_NOALLOC_MAX_NODES = 16384
 TL_N_STAGES, TL_PROFILE_RING = 5, 128
 SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "level_host": TL_SCHED_LEVEL_HOST,
-              "ready_priority": TL_SCHED_READY_PRIORITY}
+              "ready_priority": TL_SCHED_READY_PRIORITY, "dataflow": TL_SCHED_DATAFLOW}
 
 EXPORTS = ("tl_create", "tl_forward", "tl_forward_noalloc", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward",
            "tl_set_keep_gates", "tl_sgd_update", "tl_get_params", "tl_classify", "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")

@@ -33,6 +33,7 @@ namespace tl {
 constexpr int WS_MAX_SPW = 16;
 constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;     // one reduction buffer: [wave][gate][v][lane]
 constexpr int WS_TABLE_ROWS = 256;                        // rows one call can take (a power of two)
+constexpr int FLOW_NXT_ROWS = 64;                         // rows of the next piece that the data-flow scheduler keeps in LDS
 
 // LDS of the kernels that use this cell with SPW k-steps per wave.
 template <int SPW> struct WsSmemT {
@@ -42,6 +43,8 @@ template <int SPW> struct WsSmemT {
     int node[WS_TABLE_ROWS];           // row tables as in TileSmem, for up to WS_TABLE_ROWS rows
     int src0[WS_TABLE_ROWS];
     int src1[WS_TABLE_ROWS];
+    int par[WS_TABLE_ROWS];            // data-flow scheduler: parent of each row's node (-1: none)
+    int nxt[4][FLOW_NXT_ROWS];         // ... and the four tables of the piece after the current one, when that is a small one
     int cmd[8];
 };
 
@@ -173,6 +176,80 @@ template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowR
     }
 };
 
+// ---- validity carried by the data itself (data-flow scheduler) -----------------------------
+// Before the kernel starts, every row that an internal node will produce (its c row and the h row
+// its parent gathers) is filled with a bit pattern that no cell ever stores: all ones, a NaN (h
+// and c are finite whenever the parameters and embeddings are).  A consumer requests a child's
+// row whenever it likes and looks at what arrives: a 16-byte piece that still shows the pattern in
+// any of its elements has not been written (completely) yet, and the request is repeated.  No
+// flag, counter or barrier stands between the producer's store and the consumer's load, and the
+// producer does not wait for its stores to be acknowledged.  A row is written in pieces by the
+// workgroups of several column groups and an element by one store, so every element is checked.
+constexpr unsigned FLOW_SENTINEL = 0xFFFFFFFFu;             // fp32; a bf16 element shows 0xFFFF
+
+template <typename T> __device__ inline unsigned flow_fold(unsigned m, const floatx4 &v)
+{
+    const unsigned a = __float_as_uint(v.x), b = __float_as_uint(v.y), c = __float_as_uint(v.z), d = __float_as_uint(v.w);
+    if constexpr (sizeof(T) == 4) {
+        return max(max(m, a), max(max(b, c), d));
+    } else {
+        typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+        ushort2_t mm = __builtin_bit_cast(ushort2_t, m);
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(ushort2_t, a));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(ushort2_t, b));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(ushort2_t, c));
+        mm = __builtin_elementwise_max(mm, __builtin_bit_cast(ushort2_t, d));
+        return __builtin_bit_cast(unsigned, mm);
+    }
+}
+template <typename T> __device__ inline bool flow_shows_sentinel(unsigned m)
+{
+    if constexpr (sizeof(T) == 4) return m == FLOW_SENTINEL;
+    else return (m & 0xFFFFu) == 0xFFFFu || (m >> 16) == 0xFFFFu;
+}
+__device__ inline void flow_give_up(const Fwd &f)
+{
+    st_dev(&f.ctl->abort.v, 1u);
+    latch_error(f.ctl, TL_ESTALL);
+}
+// The rows of one block (requested earlier, `req` still holds their offsets): repeats the requests until no piece
+// this wave uses shows the pattern.  Bounded by the spin budget and the abort flag; returns false when it gave up.
+template <typename T, bool COH, typename Req, int NL, int RPL>
+__device__ inline bool flow_wait_rows(const Fwd &f, const Req &req, floatx4 (&rows)[NL], int sub)
+{
+    int spins = 0;
+    unsigned aborted = 0u;
+    for (;;) {
+        unsigned m = 0u;
+#pragma unroll
+        for (int j = 0; j < NL; ++j)
+            if (sub < RPL && j * RPL + sub < 16) m = flow_fold<T>(m, rows[j]);
+        if (__ballot(flow_shows_sentinel<T>(m)) == 0ull) return true;
+        if (++spins > f.spin_limit || aborted != 0u) {
+            flow_give_up(f);
+            return false;
+        }
+        backoff();
+#pragma unroll
+        for (int j = 0; j < NL; ++j) rows[j] = req.template issue<COH>(j);
+        aborted = ld_dev(&f.ctl->abort.v);                  // arrives with the rows
+    }
+}
+// One element of a child's c row.
+template <bool COH> __device__ inline float flow_wait_c(const Fwd &f, const float *p, float v)
+{
+    int spins = 0;
+    while (__float_as_uint(v) == FLOW_SENTINEL) {
+        if (++spins > f.spin_limit || ((spins & 63) == 0 && ld_dev(&f.ctl->abort.v) != 0u)) {
+            flow_give_up(f);
+            break;
+        }
+        backoff();
+        v = ld_f<COH>(p);
+    }
+    return v;
+}
+
 // Parks requested rows in the wave's LDS region (row-major, stride Smem::A_LD).
 template <int SPW, typename Smem>
 __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<SPW>::NL], int wave, int lane)
@@ -191,12 +268,13 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 // Evaluates the `count` <= WS_TABLE_ROWS rows in sm.node/src0/src1 for column group cg, 16 at a
 // time, the requests of a block's rows always one block ahead.  All four waves call it together;
 // a __syncthreads() has been passed since the row tables were written.
-// `hook` lets the caller start memory work of its own beside the cell's: it is called (with -1) once the first row
-// requests are out.
+// `hook` lets the caller do memory work of its own beside the cell's, at points where waiting for what it requested
+// earlier costs nothing: it is called with -1 once the first row requests are out, with rb when the rows of block rb
+// have arrived and been parked, and with -2 after the last block's matrix instructions, before its rows are finished.
 struct WsNoHook {
     __device__ inline void operator()(int) const {}
 };
-template <int EPI, bool COH, int SPW, bool TAIL = false, typename Hook = WsNoHook>
+template <int EPI, bool COH, int SPW, bool TAIL = false, bool FLOW = false, typename Hook = WsNoHook>
 __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int table_rows,
                                int count, int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w, Hook hook = Hook())
 {
@@ -212,7 +290,7 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
 
     // Second half of a block: the four K-range partial sums have met in LDS (a barrier has been
     // passed since they were written); wave w finishes accumulator row w of the block.
-    auto finish = [&](const float *red, int enode, bool ev, float cl, float cr) {
+    auto finish = [&](const float *red, int enode, bool ev, float cl, float cr, int erow) {
         float gate[NG];
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
@@ -224,6 +302,10 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         }
         if (ev) {
             const size_t o = (size_t)enode * H + hu;
+            if constexpr (FLOW && EPI == EPI_LSTM_INNER) {      // a child's c element may arrive after its h row
+                cl = flow_wait_c<COH>(f, f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hu, cl);
+                cr = flow_wait_c<COH>(f, f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hu, cr);
+            }
             if constexpr (EPI == EPI_LSTM_INNER) {
                 float cc, hh;
                 lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh, kept_gates(f, enode, hu), H);
@@ -258,13 +340,19 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     int p_enode = -1;
     bool p_ev = false;
     float p_cl = 0.f, p_cr = 0.f;
+    int p_erow = 0;
     constexpr int FINISH_AFTER = SPW > 1 ? 1 : 0;               // k-step after which the previous block is finished
     for (int rb = 0; rb < nrb; ++rb) {
         float *red = sm.red[rb & 1];
+        if constexpr (FLOW) {                               // the rows are there only when their producers have stored them
+            if (!flow_wait_rows<float, COH, WsRowRequest<SEG, SPW, float, TAIL>, NL, WsLoadGeom<SPW>::RPL>(f, req, rows, req.sub))
+                sm.cmd[7] = 1;
+        }
         ws_park_rows<SPW>(sm, rows, wave, lane);            // waits for the requested rows
         // the next block's rows are requested between the k-steps below, one row load per step: the
         // memory path of a CU takes a 1 KB request every ~160 cycles, a k-step lasts 640
         req.prepare((rb + 1) * 16);
+        hook(rb);
         // the row this lane finishes after the reduction, and its c operands
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
@@ -300,7 +388,7 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             __builtin_amdgcn_sched_barrier(0);              // keep the request where it is
             if (s == FINISH_AFTER && rb > 0) {
                 __syncthreads();                            // every wave has written its partial sums of block rb - 1
-                finish(sm.red[(rb - 1) & 1], p_enode, p_ev, p_cl, p_cr);
+                finish(sm.red[(rb - 1) & 1], p_enode, p_ev, p_cl, p_cr, p_erow);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -313,12 +401,14 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         p_ev = ev;
         p_cl = cl;
         p_cr = cr;
+        p_erow = erow;
         // the two reduction buffers alternate: buffer rb & 1 is written again at the end of block
         // rb + 2, after every wave has passed the barrier inside block rb + 2, hence after it has
         // read this buffer (inside block rb + 1)
     }
+    hook(-2);
     __syncthreads();
-    if (nrb > 0) finish(sm.red[(nrb - 1) & 1], p_enode, p_ev, p_cl, p_cr);
+    if (nrb > 0) finish(sm.red[(nrb - 1) & 1], p_enode, p_ev, p_cl, p_cr, p_erow);
     __syncthreads();                                        // row tables and LDS may be rewritten after this call
 }
 
@@ -341,6 +431,8 @@ template <int S> struct WsSmemBfT {
     int node[WS_TABLE_ROWS];
     int src0[WS_TABLE_ROWS];
     int src1[WS_TABLE_ROWS];
+    int par[WS_TABLE_ROWS];
+    int nxt[4][FLOW_NXT_ROWS];
     int cmd[8];
 };
 
@@ -363,7 +455,7 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, in
     for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
 }
 
-template <int EPI, bool COH, int S, typename Hook = WsNoHook>
+template <int EPI, bool COH, int S, bool FLOW = false, typename Hook = WsNoHook>
 __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
                                int table_rows, int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w,
                                Hook hook = Hook())
@@ -388,6 +480,10 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     hook(-1);
     for (int rb = 0; rb < nrb; ++rb) {
         float *red = sm.red[rb & 1];
+        if constexpr (FLOW) {                               // the rows are there only when their producers have stored them
+            if (!flow_wait_rows<unsigned short, COH, WsRowRequest<SEG, S, unsigned short>, NL, G::RPL>(f, req, rows, req.sub))
+                sm.cmd[7] = 1;
+        }
         {                                                   // park the requested rows (waits for them)
             const int sub = lane / G::LPR, kk = (lane % G::LPR) * 8;
 #pragma unroll
@@ -397,6 +493,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
             }
         }
         req.prepare((rb + 1) * 16);
+        hook(rb);
         const int erow = rb * 16 + (lane >> 4) * 4 + wave;
         const int enode = erow < count ? sm.node[erow] : -1;
         const bool ev = enode >= 0 && hu_ok;
@@ -428,6 +525,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         for (int g = 0; g < NG; ++g)
 #pragma unroll
             for (int v = 0; v < 4; ++v) red[((wave * NG + g) * 4 + v) * 64 + lane] = acc[g][v];
+        if (rb == nrb - 1) hook(-2);
         __syncthreads();
         float gate[NG];
 #pragma unroll
@@ -441,6 +539,10 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         if (ev) {
             const size_t o = (size_t)enode * H + hu;
             float hh;
+            if constexpr (FLOW && EPI == EPI_LSTM_INNER) {      // a child's c element may arrive after its h row
+                cl = flow_wait_c<COH>(f, f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hu, cl);
+                cr = flow_wait_c<COH>(f, f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hu, cr);
+            }
             if constexpr (EPI == EPI_LSTM_INNER) {
                 float cc;
                 lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);

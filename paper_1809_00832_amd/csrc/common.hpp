@@ -138,6 +138,12 @@ struct Fwd {
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once
     int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size compute + n_gangs scheduler workgroups
+    int xcd_slots;                    // level / data-flow scheduler: every slot on one L2 domain (the slots divide evenly over the domains)
+    // data-flow scheduler: per column group a counter of handed-out children per node [n_cg x n_nodes] and a list of
+    // ready nodes {node, left, right, 0} [n_cg x n_int]; a workgroup uses the part that belongs to its slot's trees
+    int32_t *flow_seen;
+    int4 *flow_list;
+    int flow;                         // data-flow scheduler: who fills the rows of internal nodes with the "not written" pattern: 1 the reset kernel, 2 the leaf kernel
 };
 
 // ---- device-scope accesses -------------------------------------------------------------

@@ -54,6 +54,8 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
     WsSmemT<SPW> &sm = *reinterpret_cast<WsSmemT<SPW> *>(smem_raw);
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
+    // (data-flow scheduler: the stores that mark the internal nodes' rows go out first and complete beside the cells)
+    if (f.flow == 2) flow_fill(f, (size_t)blockIdx.x * 4 + (tid >> 6), (size_t)gridDim.x * 4);
     const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
     WsWeights<EpiTraits<EPI_LSTM_LEAF>::NG, SPW> w;
@@ -80,6 +82,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
     WsSmemBfT<S> &sm = *reinterpret_cast<WsSmemBfT<S> *>(smem_raw);
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
+    if (f.flow == 2) flow_fill(f, (size_t)blockIdx.x * 4 + (tid >> 6), (size_t)gridDim.x * 4);
     const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
     WsWeightsBf<EpiTraits<EPI_LSTM_LEAF>::NG, S> w;
@@ -266,9 +269,22 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     Ctl *ctl = f.ctl;
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
-    const int member = blockIdx.x % f.n_cg;
-    const int my_cg = gang_cg(member, f.n_cg, f.n_cg);
-    const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
+    // A slot is a set of workgroups that covers all column groups; the workgroups of a slot gather the same child rows.
+    // Workgroups are dealt to the L2 domains round-robin, so when the slots divide evenly over the domains every slot is
+    // put on one domain: its rows then cross the fabric once instead of once per domain that holds some of its column
+    // groups, and a row's pieces are written from one L2.
+    const int n_slots = gridDim.x / f.n_cg;
+    int member, slot, my_cg;
+    if (f.xcd_slots) {
+        const int q = blockIdx.x / N_XCD;
+        slot = (int)(blockIdx.x % N_XCD) + N_XCD * (q / f.n_cg);
+        member = q % f.n_cg;
+        my_cg = member;
+    } else {
+        member = blockIdx.x % f.n_cg;
+        slot = blockIdx.x / f.n_cg;
+        my_cg = gang_cg(member, f.n_cg, f.n_cg);
+    }
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
@@ -376,6 +392,244 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     if (blockIdx.x == 0 && tid == 0) {
         ctl->n_levels = frontiers + 1;            // the leaves and the frontiers (= the heights, unless rows were left over)
         if (end < n_int) latch_error(ctl, TL_ESTRUCT);   // nodes that never became ready: not a forest
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Data-flow scheduler: the ready counters of Section 4.1 with nothing shared between the workers.
+//
+// The trees of the batch are dealt to the slots in contiguous ranges of about equal node count (a
+// slot is a set of workgroups that covers all column groups, see above), and every workgroup of a
+// slot evaluates, for its own column group, all internal nodes of the slot's trees.  It keeps the
+// whole scheduling state to itself: a counter of handed-out children per node and an append-only
+// list of the nodes that have become ready (both in a part of the workspace that no other
+// workgroup touches).  It starts with the nodes over two leaves, found by scanning the slot's node
+// range; handing out a node counts it at its parent, and a parent whose internal children have all
+// been handed out goes to the end of the list, so the list is filled ahead of the evaluation and a
+// node always comes after its children.  Nothing is exchanged about the schedule: no shared
+// queue, no records, no grid barrier, no mailbox.
+//
+// What a node does need from the other workgroups of its slot are the children's rows, of which
+// every workgroup produces 16 hidden units.  Their completion is read off the rows themselves
+// (cell_ws.hpp, "validity carried by the data"): the rows of all internal nodes are filled with a
+// pattern no cell produces before the kernel starts, a consumer requests a child row as early as
+// it likes and repeats the request while a piece of it still shows the pattern.  A dependent step
+// then costs the producer's store, its way through the memory system and the consumer's load -
+// about one round trip - where the level scheduler pays the stores' acknowledgement, a grid
+// barrier of two round trips, the records of the next frontier and then the rows.  Slots do not
+// wait for each other at all.
+//
+// All workgroups of a slot build the same list and take it in the same pieces, and a piece depends on
+// earlier pieces only, so the workgroup that is furthest behind never waits for anything unfinished:
+// the waits always end (and each is bounded by the spin budget and the abort flag).
+// Nodes that never become ready (a cycle) are never listed; the workgroup then finishes with fewer
+// nodes than its slot has and reports the batch as malformed.
+struct FlowTicket {
+    int p, key, left, right, up;  // parent that became ready with this lane's row (-1: none), its place among the group's parents, its children and its own parent
+};
+// One lane per row of rows [row0, row0 + 64) of the row table: counts the row at its parent.  All workgroups of a
+// slot must build the same list in the same order (they take its entries in pieces, and a piece must hold the same
+// nodes everywhere), so the order in which a group's parents are listed must not depend on which of two siblings in
+// the group happened to be counted second: the first child to arrive leaves its lane and the group's stamp in the
+// counter word, and the parent is listed under the larger of its children's lanes when both are in the group.
+// p: the parent of the lane's row (-1: none), which the row's list entry carries.
+__device__ inline FlowTicket flow_count_at_parent(const Fwd &f, unsigned *seen, int p, unsigned stamp)
+{
+    FlowTicket t{-1, 0, -1, -1, -1};
+    const int lane = threadIdx.x;
+    if (p >= 0) {
+        // counter word: children counted (2 bits) | lane of the first one (6 bits) | stamp of its group (24 bits)
+        const unsigned old = __hip_atomic_fetch_add(&seen[p], 1u | (unsigned)lane << 2 | stamp << 8, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int need = f.pending[p];                // internal children, as the structure pass left it
+        t.left = f.left[p];
+        t.right = f.right[p];
+        t.up = f.parent[p];
+        if ((int)(old & 3u) + 1 == need) {
+            t.p = p;
+            const int other = (int)(old >> 2 & 63u);
+            t.key = (need == 2 && old >> 8 == (stamp & 0xFFFFFFu) && other > lane) ? other : lane;
+        }
+    }
+    return t;
+}
+// Parents that have become ready go to the end of this workgroup's list (its length is kept in LDS), in key order.
+// `scratch`: two words of LDS that only this wave uses (the set of keys is put together there: LDS operations of one
+// wave are executed in the order in which they are issued).
+// Entries that fall into the window of FLOW_NXT_ROWS list positions from `win0` on also go to the LDS tables `nxt`
+// (node, first and second source, parent): the next piece is taken from there when it lies in that window entirely.
+__device__ inline void flow_append(int4 *list, int capacity, int *len, volatile unsigned *scratch, const FlowTicket &t,
+                                   int (*nxt)[FLOW_NXT_ROWS], int win0)
+{
+    const int lane = threadIdx.x;
+    const bool ready = t.p >= 0;
+    const unsigned long long own = __ballot(ready && t.key == lane);
+    unsigned long long keys = own;
+    if (__ballot(ready && t.key != lane) != 0ull) {           // a parent listed under its other child's lane: rare
+        if (lane == 0) {
+            scratch[0] = 0u;
+            scratch[1] = 0u;
+        }
+        if (ready) __hip_atomic_fetch_or(const_cast<unsigned *>(&scratch[t.key >> 5]), 1u << (t.key & 31), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        keys = (unsigned long long)scratch[1] << 32 | scratch[0];
+    }
+    if (keys == 0ull) return;
+    int base = 0;
+    if (lane == 0) {
+        base = *len;
+        *len = base + __popcll(keys);
+    }
+    base = __shfl(base, 0);
+    if (ready) {
+        const int pos = base + __popcll(keys & ((1ull << t.key) - 1ull));
+        if (pos < capacity) list[pos] = int4{t.p, t.left, t.right, t.up};
+        const unsigned at = (unsigned)(pos - win0);
+        if (at < (unsigned)FLOW_NXT_ROWS) {
+            nxt[0][at] = t.p;
+            nxt[1][at] = t.left;
+            nxt[2][at] = t.right;
+            nxt[3][at] = t.up;
+        }
+    }
+}
+
+template <int EPI, bool VEC4, int SPW, bool BF16 = false>
+__global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fwd f)
+{
+    static_assert(SPW > 0, "the data-flow scheduler uses the weight-stationary cell");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    using Smem = PersistentSmem<SPW, BF16>;
+    Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
+    Ctl *ctl = f.ctl;
+    if (batch_rejected(f)) return;
+    const int tid = threadIdx.x;
+    const int n_slots = gridDim.x / f.n_cg;
+    int member, slot;
+    if (f.xcd_slots) {                                // every slot on one L2 domain, as in the level scheduler
+        const int q = blockIdx.x / N_XCD;
+        slot = (int)(blockIdx.x % N_XCD) + N_XCD * (q / f.n_cg);
+        member = q % f.n_cg;
+    } else {
+        member = blockIdx.x % f.n_cg;
+        slot = blockIdx.x / f.n_cg;
+    }
+    const int my_cg = member;
+    PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
+    ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+
+    // the slot's trees: [t_lo, t_hi), cut where the node count passes slot / n_slots of the batch
+    auto first_tree_at = [&](int s) {
+        const long long bound = ((long long)s * f.n_nodes + n_slots - 1) / n_slots;
+        int lo = 0, hi = f.n_trees;                   // smallest t with tree_off[t] >= bound; tree_off[n_trees] = n_nodes
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (f.tree_off[mid] >= bound) hi = mid; else lo = mid + 1;
+        }
+        return lo;
+    };
+    const int t_lo = first_tree_at(slot), t_hi = first_tree_at(slot + 1);
+    const int nb = f.tree_off[t_lo], ne = f.tree_off[t_hi];
+    const int slot_internal = ((ne - nb) - (t_hi - t_lo)) / 2;      // full binary trees
+    if (slot_internal <= 0) return;
+    unsigned *seen = reinterpret_cast<unsigned *>(f.flow_seen) + (size_t)member * f.n_nodes;   // this workgroup's own: [nb, ne) of it
+    int4 *list = f.flow_list + (size_t)member * f.n_int + (nb - t_lo) / 2;
+    int *len = &sm.cmd[4];
+    if (tid == 0) sm.cmd[7] = 0;
+    for (int n = nb + tid; n < ne; n += WG_THREADS) seen[n] = 0u;
+    // the list starts with the slot's nodes over two leaves, in node order
+    int n_listed = 0;
+    for (int base = nb; base < ne; base += WG_THREADS) {
+        const int n = base + tid;
+        int l = -1, r = -1;
+        bool seed = false;
+        if (n < ne) {
+            l = f.left[n];
+            r = f.right[n];
+            seed = l >= 0 && f.pending[n] == 0;
+        }
+        const unsigned long long mask = __ballot(seed);
+        __syncthreads();                              // (the counts of the previous round have been read)
+        if ((tid & 63) == 0) sm.cmd[tid >> 6] = __popcll(mask);
+        __syncthreads();
+        int at = n_listed;
+        for (int wv = 0; wv < (tid >> 6); ++wv) at += sm.cmd[wv];
+        if (seed) {
+            const int pos = at + __popcll(mask & ((1ull << (tid & 63)) - 1ull));
+            if (pos < slot_internal) list[pos] = int4{n, l, r, f.parent[n]};
+        }
+        n_listed += sm.cmd[0] + sm.cmd[1] + sm.cmd[2] + sm.cmd[3];
+    }
+    __syncthreads();
+    if (tid == 0) *len = n_listed;
+    wait_mem();
+    __syncthreads();
+    // The list is taken in pieces of whole 16-row blocks as long as it holds that many: what is left over waits for
+    // the entries that the piece itself brings (a node is listed when its last child is handed out, so everything
+    // listed so far depends on earlier pieces only, and the rows of a piece never wait for each other).
+    // A piece that takes everything the list holds is followed by a piece of entries that it lists itself: those
+    // are also kept in LDS (sm.nxt), so that in the narrow part of a tree - where every step waits for the one
+    // before - the next piece's rows are known without a trip to the list in memory.
+    int begin = 0, pieces = 0;
+    bool from_lds = false;
+    for (;;) {
+        const int avail = min(*len, slot_internal) - begin;
+        if (avail <= 0) break;                        // every listed node has been handed out, so nothing more will be listed
+        int count = min(avail, WS_TABLE_ROWS);
+        if (count > 16) count &= ~15;
+        {
+            // rows beyond the piece stand in with the sources of its first row: they are requested like the others
+            // (a request needs no test), so they must be rows that do become valid
+            const int i = tid < count ? tid : 0;
+            int4 rec;
+            if (from_lds) rec = int4{sm.nxt[0][i], sm.nxt[1][i], sm.nxt[2][i], sm.nxt[3][i]};
+            else rec = list[begin + i];
+            sm.node[tid] = tid < count ? rec.x : -1;
+            sm.src0[tid] = rec.y;
+            sm.src1[tid] = rec.z;
+            sm.par[tid] = tid < count ? rec.w : -1;
+        }
+        const bool takes_all = avail == count;
+        const int win0 = takes_all ? begin + count : -(1 << 30);
+        __syncthreads();
+        // Wave 0 counts the piece's rows at their parents, 64 rows (four blocks) at a time; the parent of a row comes with
+        // its list entry.  The count (a chain of two memory round trips) is sent when the group's first block starts -
+        // for the first group: as soon as the first row requests are out - and what it brings back is used with the
+        // group's last block, or after the last matrix instructions of the piece, to list the parents that have
+        // become ready: the cell never waits for it.
+        FlowTicket ticket{-1, 0, -1, -1, -1};
+        const unsigned stamp0 = (unsigned)pieces * (WS_TABLE_ROWS / 64) + 1u;
+        volatile unsigned *scratch = reinterpret_cast<volatile unsigned *>(&sm.cmd[5]);
+        auto hook = [&](int where) {
+            if (tid >= 64) return;
+            if (where == -1) {
+                ticket = flow_count_at_parent(f, seen, sm.par[tid], stamp0);
+            } else if (where == -2) {
+                flow_append(list, slot_internal, len, scratch, ticket, sm.nxt, win0);
+                ticket.p = -1;
+            } else if (where > 0 && (where & 3) == 0) {
+                ticket = flow_count_at_parent(f, seen, where * 16 + tid < count ? sm.par[where * 16 + tid] : -1, stamp0 + (unsigned)(where >> 2));
+            } else if ((where & 3) == 3) {
+                flow_append(list, slot_internal, len, scratch, ticket, sm.nxt, win0);
+                ticket.p = -1;
+            }
+        };
+        if constexpr (BF16) ws_tile<EPI, true, SPW, true>(sm, f, f.inner, f.hb, f.n_nodes, f.hs, count, my_cg, w, hook);
+        else ws_tile<EPI, true, SPW, !VEC4, true>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w, hook);
+        if (sm.cmd[7] != 0) return;                   // a wait was abandoned: everybody leaves
+        pieces += 1;
+        begin += count;
+        __syncthreads();
+        from_lds = takes_all && *len - begin <= FLOW_NXT_ROWS;      // (everything listed since is in the LDS tables)
+        if (!from_lds) {
+            wait_mem();                               // the next piece is read from the list in memory: wave 0's entries have arrived there
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        __hip_atomic_fetch_max(&ctl->n_levels, pieces + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (begin < slot_internal) latch_error(ctl, TL_ESTRUCT);     // nodes that never became ready: not a forest
     }
 }
 

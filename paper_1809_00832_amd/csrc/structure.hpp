@@ -51,6 +51,39 @@ template <typename T> __device__ inline int block_append(T *counter, bool pred, 
 // Threads per workgroup of the per-node kernels that append to lists.
 constexpr int NODE_BLOCK = 1024;
 
+// Data-flow scheduler: the rows that internal nodes will produce - c, and the h row their parents gather (the bf16
+// copy when there is one) - show "not written" (all ones) in every element until they are.  One wave per row; called
+// by all lanes of wave number `wave` of `n_waves`.
+__device__ inline void flow_fill(const Fwd &f, size_t wave, size_t n_waves)
+{
+    const int H = f.H, lane = threadIdx.x & 63;
+    const bool quad = (H & 3) == 0 && (((uintptr_t)f.h | (uintptr_t)f.c) & 15) == 0;
+    const float ones = __uint_as_float(0xFFFFFFFFu);
+    const floatx4 ones4 = floatx4{ones, ones, ones, ones};
+    for (size_t n = wave; n < (size_t)f.n_nodes; n += n_waves) {
+        if (f.left[n] < 0) continue;
+        float *c = f.c ? f.c + n * H : nullptr, *h = f.hb ? nullptr : f.h + n * H;
+        if (quad) {
+            for (int e = lane * 4; e < H; e += 256) {
+                if (c) *reinterpret_cast<floatx4 *>(c + e) = ones4;
+                if (h) *reinterpret_cast<floatx4 *>(h + e) = ones4;
+            }
+        } else {
+            for (int e = lane; e < H; e += 64) {
+                if (c) c[e] = ones;
+                if (h) h[e] = ones;
+            }
+        }
+        if (f.hb) {
+            unsigned short *hb = f.hb + n * f.hs;             // rows 16-byte aligned; what lies beyond H stays zero
+            for (int e = lane * 8; e < H; e += 512) {
+                if (e + 8 <= H) *reinterpret_cast<floatx4 *>(hb + e) = ones4;
+                else for (int k = e; k < H; ++k) hb[k] = (unsigned short)0xFFFFu;
+            }
+        }
+    }
+}
+
 // Resets the per-forward scheduler state.  A fill kernel rather than memsets so that a caller
 // may capture the forward in a HIP graph.
 __global__ void k_reset(Fwd f, int with_levels)
@@ -74,6 +107,7 @@ __global__ void k_reset(Fwd f, int with_levels)
         if (i < ctl_words) ((unsigned int *)f.ctl)[i] = 0;
         if (i < gang_words) ((unsigned int *)f.gangs)[i] = 0;
     }
+    if (f.flow == 1) flow_fill(f, ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, stride >> 6);
 }
 
 // One thread per node: checks, parent scatter, leaf list, counters of unfinished children.

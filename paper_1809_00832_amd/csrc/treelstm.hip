@@ -43,6 +43,7 @@ struct tl_ctx {
     // workspace
     unsigned char *ws = nullptr;
     size_t ws_bytes = 0;
+    unsigned char *flow_ws = nullptr;  // data-flow scheduler: per-column-group counters and lists, for cap_nodes nodes
     unsigned char *scratch = nullptr;  // this device's copy of the fixed workspace of tl_forward_noalloc (not owned)
     int cap_nodes = 0, cap_trees = 0;
     int32_t *host_levels = nullptr;   // pinned, cap_nodes + 2
@@ -175,6 +176,32 @@ template <int EPI> fwd_kernel levels_kernel_epi(bool vec4, int spw, bool bf16)
     case 16: return vec4 ? k_levels_persistent<EPI, true, 16> : k_levels_persistent<EPI, false, 16>;
     default: return vec4 ? k_levels_persistent<EPI, true, 0> : k_levels_persistent<EPI, false, 0>;
     }
+}
+template <int EPI> fwd_kernel flow_kernel_epi(bool vec4, int spw, bool bf16)
+{
+    if (bf16) {
+        switch (spw) {
+        case 1: return k_flow_persistent<EPI, true, 1, true>;
+        case 2: return k_flow_persistent<EPI, true, 2, true>;
+        case 3: return k_flow_persistent<EPI, true, 3, true>;
+        case 4: return k_flow_persistent<EPI, true, 4, true>;
+        case 6: return k_flow_persistent<EPI, true, 6, true>;
+        default: return k_flow_persistent<EPI, true, 8, true>;
+        }
+    }
+    switch (spw) {
+    case 1: return vec4 ? k_flow_persistent<EPI, true, 1> : k_flow_persistent<EPI, false, 1>;
+    case 2: return vec4 ? k_flow_persistent<EPI, true, 2> : k_flow_persistent<EPI, false, 2>;
+    case 4: return vec4 ? k_flow_persistent<EPI, true, 4> : k_flow_persistent<EPI, false, 4>;
+    case 5: return vec4 ? k_flow_persistent<EPI, true, 5> : k_flow_persistent<EPI, false, 5>;
+    case 8: return vec4 ? k_flow_persistent<EPI, true, 8> : k_flow_persistent<EPI, false, 8>;
+    default: return vec4 ? k_flow_persistent<EPI, true, 16> : k_flow_persistent<EPI, false, 16>;
+    }
+}
+// spw > 0 and not the RNTN cell
+fwd_kernel flow_kernel(int cell, bool vec4, int spw, bool bf16)
+{
+    return cell == TL_TREELSTM ? flow_kernel_epi<EPI_LSTM_INNER>(vec4, spw, bf16) : flow_kernel_epi<EPI_RNN_INNER>(vec4, spw, bf16);
 }
 fwd_kernel ready_kernel(int cell, bool vec4, int spw, bool bf16)
 {
@@ -413,6 +440,9 @@ int scratch_address(int device, unsigned char **out)
     return TL_OK;
 }
 
+// Data-flow scheduler: counters [n_cg x N] (int32) followed by lists [n_cg x N / 2] of 16-byte entries.
+size_t flow_bytes(size_t n_cg, size_t N) { return align256(n_cg * N * sizeof(int32_t)) + n_cg * (N / 2 + 1) * sizeof(int4); }
+
 // Workspace for batches of up to n_nodes nodes / n_trees trees.
 int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
 {
@@ -422,6 +452,7 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
     const int B = n_trees > ctx->cap_trees ? n_trees : ctx->cap_trees;
     if (ctx->ws) { TL_HIP(hipFree(ctx->ws)); ctx->ws = nullptr; }
     if (ctx->hb) { TL_HIP(hipFree(ctx->hb)); ctx->hb = nullptr; }
+    if (ctx->flow_ws) { TL_HIP(hipFree(ctx->flow_ws)); ctx->flow_ws = nullptr; }
     if (ctx->host_levels) { TL_HIP(hipHostFree(ctx->host_levels)); ctx->host_levels = nullptr; }
     ctx->cap_nodes = ctx->cap_trees = 0;
     const size_t bytes = workspace_bytes((size_t)N, (size_t)B);
@@ -432,6 +463,8 @@ int ensure_workspace(tl_ctx *ctx, int n_nodes, int n_trees)
         TL_HIP(hipMalloc(&ctx->hb, hb_bytes));
         TL_HIP(hipMemset(ctx->hb, 0, hb_bytes));   // the padding at the end of each row stays zero for good
     }
+    if (ctx->spw > 0 && ctx->cfg.scheduler == TL_SCHED_DATAFLOW)
+        TL_HIP(hipMalloc(&ctx->flow_ws, flow_bytes(ctx->n_cg, (size_t)N)));
     TL_HIP(hipHostMalloc(&ctx->host_levels, (size_t)(N + 2) * 4, hipHostMallocDefault));
     ctx->ws_bytes = bytes;
     ctx->cap_nodes = N;
@@ -471,6 +504,7 @@ void free_all(tl_ctx *ctx)
     (void)hipFree(ctx->bp_inner);
     (void)hipFree(ctx->ws);
     (void)hipFree(ctx->hb);
+    (void)hipFree(ctx->flow_ws);
     (void)hipFree(ctx->embb);
     (void)hipFree(ctx->wp_bwd_inner);
     (void)hipFree(ctx->wp_bwd_inner1);
@@ -647,6 +681,12 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(levels_kernel(cfg->cell, true, ctx->spw, bf16)),
                                                             WG_THREADS, ctx->ws_lds));
         if (o2 < o1) o1 = o2;
+        for (int v = 0; v < 2; ++v) {
+            const fwd_kernel fk = flow_kernel(cfg->cell, v != 0, ctx->spw, bf16);
+            if ((rc = allow_lds(fk, ctx->ws_lds)) != TL_OK) return rc;
+            TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o2, reinterpret_cast<const void *>(fk), WG_THREADS, ctx->ws_lds));
+            if (o2 < o1) o1 = o2;
+        }
         const int want = bf16 ? 2 : 1;   // fp32: the register file of a CU holds one workgroup's weights; bf16: two
         if (o1 > want) o1 = want;
         ctx->ws_grid = o1 * ctx->n_cu;
@@ -715,7 +755,7 @@ int tl_create(const tl_config *cfg, tl_ctx **out)
     if (cfg->cell != TL_TREELSTM && cfg->cell != TL_TREERNN && cfg->cell != TL_RNTN) return TL_EINVAL;
     if (cfg->cell == TL_RNTN && (!cfg->v || cfg->hidden > 128 || cfg->precision != TL_F32)) return TL_EINVAL;
     if (cfg->precision != TL_F32 && cfg->precision != TL_BF16_IN) return TL_EINVAL;
-    if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_READY_PRIORITY) return TL_EINVAL;
+    if (cfg->scheduler < TL_SCHED_READY || cfg->scheduler > TL_SCHED_DATAFLOW) return TL_EINVAL;
     if (cfg->vocab < 1 || cfg->embed_dim < 1 || cfg->hidden < 1 || cfg->spin_limit < 0) return TL_EINVAL;
     if (cfg->hidden > (1 << 14) || cfg->embed_dim > (1 << 16)) return TL_EINVAL;
     if (!cfg->emb || !cfg->u || !cfg->b) return TL_EINVAL;
@@ -798,6 +838,9 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     const bool pair_inner = (cfg.hidden % 2 == 0) && (((uintptr_t)h & 7) == 0);      // rows 8-byte aligned
     const int spw = ((bf16 || pair_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
+    // the data-flow scheduler needs the weight-stationary cell and its private lists; without them (RNTN, sizes the
+    // cell does not take, the fixed workspace) the level scheduler on the device stands in
+    const bool flow = cfg.scheduler == TL_SCHED_DATAFLOW && spw > 0 && !static_ws && ctx->flow_ws != nullptr;
     if (persistent && spw > 0 && bf16) {
         f.hb = static_ws ? reinterpret_cast<unsigned short *>(ctx->scratch + NOALLOC_WS_BYTES) : ctx->hb;
         f.hs = ctx->hs;
@@ -815,6 +858,11 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;
     const bool ready_sched = cfg.scheduler == TL_SCHED_READY || cfg.scheduler == TL_SCHED_READY_PRIORITY;
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
+    if (flow) {
+        f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) ? 2 : 1;
+        f.flow_seen = reinterpret_cast<int32_t *>(ctx->flow_ws);
+        f.flow_list = reinterpret_cast<int4 *>(ctx->flow_ws + align256((size_t)ctx->n_cg * ctx->cap_nodes * sizeof(int32_t)));
+    }
     const bool vec4_leaf = cfg.embed_dim % 4 == 0;
     const int inner_epi = cfg.cell == TL_TREELSTM ? EPI_LSTM_INNER : (cfg.cell == TL_TREERNN ? EPI_RNN_INNER : EPI_RNTN_INNER);
     const bool prof = ctx->profiling != 0 && !static_ws;      // (recording may have to create events)
@@ -841,7 +889,9 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
         z.n[0] = (size_t)n_nodes * ctx->hs * sizeof(unsigned short) / sizeof(float);      // hs is a multiple of 8
         hipLaunchKernelGGL(k_zero_many, dim3(256), dim3(256), 0, st, z);
     }
-    hipLaunchKernelGGL(k_reset, dim3(256), dim3(256), 0, st, f, need_levels ? 1 : 0);
+    // (the data-flow scheduler's fill of the rows of internal nodes takes one wave per node)
+    const int nb_reset = f.flow == 1 ? (n_nodes / 4 + 1 < 256 ? 256 : (n_nodes / 4 + 1 > 4096 ? 4096 : n_nodes / 4 + 1)) : 256;
+    hipLaunchKernelGGL(k_reset, dim3(nb_reset), dim3(256), 0, st, f, need_levels ? 1 : 0);
     hipLaunchKernelGGL(k_scatter, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     if (need_levels) {
@@ -878,11 +928,12 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
             hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_r), dim3(WG_THREADS),
                                spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_r;
-        } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE) {
+        } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE || cfg.scheduler == TL_SCHED_DATAFLOW) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_l), dim3(WG_THREADS),
-                               spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
+            f.xcd_slots = (spw > 0 && (grid_l / ctx->n_cg) % N_XCD == 0 && !getenv("TL_NO_XCD_SLOTS")) ? 1 : 0;
+            hipLaunchKernelGGL(flow ? flow_kernel(cfg.cell, vec4_inner, spw, bf16) : levels_kernel(cfg.cell, vec4_inner, spw, bf16),
+                               dim3(grid_l), dim3(WG_THREADS), spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists

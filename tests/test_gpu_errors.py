@@ -8,7 +8,7 @@ from paper_1809_00832_amd import binding, synth
 from paper_1809_00832_amd.synth import TreeBatch
 
 pytestmark = pytest.mark.gpu
-SCHEDULERS = ["level_host", "level_device", "ready", "ready_priority"]
+SCHEDULERS = ["level_host", "level_device", "ready", "ready_priority", "dataflow"]
 
 
 def run_expect(params, trees, sched, expect, **kw):
@@ -132,7 +132,7 @@ def test_results_do_not_depend_on_the_schedule(name, precision):
     print("case determinism", name, precision, flush=True)
     w = synth.workload(name)
     outs = []
-    for sched in ("ready", "level_device", "level_host", "ready_priority"):
+    for sched in ("ready", "level_device", "level_host", "ready_priority", "dataflow"):
         net = binding.TreeNet(w.params, scheduler=sched, precision=binding.TL_F32 if precision == "f32" else binding.TL_BF16_IN)
         try:
             got = net.run(w.trees)
@@ -153,7 +153,7 @@ def test_results_do_not_depend_on_the_schedule(name, precision):
         assert c is None or np.array_equal(c, outs[0][2]), "%s vs ready: c differs" % sched
 
 
-@pytest.mark.parametrize("sched", ["ready", "level_device", "ready_priority"])
+@pytest.mark.parametrize("sched", ["ready", "level_device", "ready_priority", "dataflow"])
 def test_forward_replayed_from_a_hip_graph(sched):
     """tl_forward of the two device-scheduled variants makes no host round trip and clears its state with fill
     kernels, so it can be captured in a HIP graph.  Every replay, with eager work and synchronisation between
@@ -188,7 +188,7 @@ def test_forward_replayed_from_a_hip_graph(sched):
 
 
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
-@pytest.mark.parametrize("sched", ["ready", "level_device", "ready_priority"])
+@pytest.mark.parametrize("sched", ["ready", "level_device", "ready_priority", "dataflow"])
 @pytest.mark.parametrize("name,iters", [("throughput", 300), ("sentence", 300), ("stress", 20), ("mixed_small", 200)])
 def test_many_forwards_give_the_same_bits(name, iters, sched, precision):
     """Many forwards of one batch through one context: every one ends without error and with exactly the bits of
