@@ -33,6 +33,7 @@ namespace tl {
 constexpr int WS_MAX_SPW = 16;
 constexpr int WS_RED_FLOATS = 4 * MAX_GATES * 4 * 64;     // one reduction buffer: [wave][gate][v][lane]
 constexpr int WS_TABLE_ROWS = 256;                        // rows one call can take (a power of two)
+constexpr int FLOW_ROOTS_KEPT = 192;                      // roots of a slot's trees that are remembered in LDS (more: found again by a second pass)
 constexpr int FLOW_NXT_ROWS = 64;                         // rows of the next piece that the data-flow scheduler keeps in LDS
 
 // LDS of the kernels that use this cell with SPW k-steps per wave.
@@ -45,6 +46,7 @@ template <int SPW> struct WsSmemT {
     int src1[WS_TABLE_ROWS];
     int par[WS_TABLE_ROWS];            // data-flow scheduler: parent of each row's node (-1: none)
     int nxt[4][FLOW_NXT_ROWS];         // ... and the four tables of the piece after the current one, when that is a small one
+    int roots[FLOW_ROOTS_KEPT];        // ... and the roots among the slot's nodes
     int cmd[8];
 };
 
@@ -433,6 +435,7 @@ template <int S> struct WsSmemBfT {
     int src1[WS_TABLE_ROWS];
     int par[WS_TABLE_ROWS];
     int nxt[4][FLOW_NXT_ROWS];
+    int roots[FLOW_ROOTS_KEPT];
     int cmd[8];
 };
 

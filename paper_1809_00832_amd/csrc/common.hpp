@@ -138,11 +138,11 @@ struct Fwd {
     int spin_limit;
     int cap_tiles;                    // tiles the launched grid can work on at once
     int n_gangs, gang_size;           // ready scheduler: grid = n_gangs * gang_size compute + n_gangs scheduler workgroups
-    int xcd_slots;                    // level / data-flow scheduler: every slot on one L2 domain (the slots divide evenly over the domains)
     // data-flow scheduler: per column group a counter of handed-out children per node [n_cg x n_nodes] and a list of
     // ready nodes {node, left, right, 0} [n_cg x n_int]; a workgroup uses the part that belongs to its slot's trees
     int32_t *flow_seen;
     int4 *flow_list;
+    int flow_roots;                   // data-flow scheduler: roots are found and their states copied out by the cell kernels (no separate passes)
     int flow;                         // data-flow scheduler: who fills the rows of internal nodes with the "not written" pattern: 1 the reset kernel, 2 the leaf kernel
 };
 
@@ -231,7 +231,12 @@ __device__ inline void latch_error(Ctl *ctl, int code)
 
 // After the structure pass: has it found anything wrong?  (A tree without a root shows as a root count
 // below the number of trees; every other defect has been latched in status.)
-__device__ inline bool batch_rejected(const Fwd &f) { return f.ctl->status != 0 || f.ctl->n_roots != f.n_trees; }
+// (Where the cell kernels look after the roots themselves, the root count is not taken beforehand; what must hold
+// before any cell runs is that the leaf list is complete.)
+__device__ inline bool batch_rejected(const Fwd &f)
+{
+    return f.ctl->status != 0 || (f.flow_roots ? f.ctl->n_leaf_seen != f.n_leaf : f.ctl->n_roots != f.n_trees);
+}
 
 __device__ inline void backoff() { __builtin_amdgcn_s_sleep(2); }
 

@@ -270,21 +270,12 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     // A slot is a set of workgroups that covers all column groups; the workgroups of a slot gather the same child rows.
-    // Workgroups are dealt to the L2 domains round-robin, so when the slots divide evenly over the domains every slot is
-    // put on one domain: its rows then cross the fabric once instead of once per domain that holds some of its column
-    // groups, and a row's pieces are written from one L2.
+    // (Putting every slot on one L2 domain, so that its rows cross the fabric once instead of once per domain that
+    // holds some of its column groups, was measured and is not done: no faster on the H=512 batch, whose fabric
+    // reads are far from any limit, and up to 7 % slower on narrow batches.)
     const int n_slots = gridDim.x / f.n_cg;
-    int member, slot, my_cg;
-    if (f.xcd_slots) {
-        const int q = blockIdx.x / N_XCD;
-        slot = (int)(blockIdx.x % N_XCD) + N_XCD * (q / f.n_cg);
-        member = q % f.n_cg;
-        my_cg = member;
-    } else {
-        member = blockIdx.x % f.n_cg;
-        slot = blockIdx.x / f.n_cg;
-        my_cg = gang_cg(member, f.n_cg, f.n_cg);
-    }
+    const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;
+    const int my_cg = gang_cg(member, f.n_cg, f.n_cg);
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
@@ -424,6 +415,44 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
 // the waits always end (and each is bounded by the spin budget and the abort flag).
 // Nodes that never become ready (a cycle) are never listed; the workgroup then finishes with fewer
 // nodes than its slot has and reports the batch as malformed.
+// The state of root n goes to the per-tree outputs: one lane copies the 16 hidden units of column group cg.  An
+// internal root's units have been stored by the lane's own workgroup (and those stores have arrived), a leaf's by
+// the leaf kernel, so ordinary loads see them.  The tree is one of [t_lo, t_hi).
+__device__ inline void flow_copy_root(const Fwd &f, int n, int cg, int t_lo, int t_hi)
+{
+    int lo = t_lo, hi = t_hi - 1;                             // largest t with tree_off[t] <= n
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (f.tree_off[mid] <= n) lo = mid; else hi = mid - 1;
+    }
+    const int t = lo, H = f.H, u0 = cg * HU;
+    const size_t src = (size_t)n * H + u0, dst = (size_t)t * H + u0;
+    const bool quad = (H & 3) == 0 && u0 + HU <= H &&
+                      (((uintptr_t)f.h | (uintptr_t)f.c | (uintptr_t)f.h_root | (uintptr_t)f.c_root) & 15) == 0;
+    if (quad) {
+        floatx4 vh[4], vc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            vh[j] = *reinterpret_cast<const floatx4 *>(f.h + src + 4 * j);
+            if (f.c) vc[j] = *reinterpret_cast<const floatx4 *>(f.c + src + 4 * j);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (f.h_root) *reinterpret_cast<floatx4 *>(f.h_root + dst + 4 * j) = vh[j];
+            if (f.c_root && f.c) *reinterpret_cast<floatx4 *>(f.c_root + dst + 4 * j) = vc[j];
+        }
+    } else {
+        for (int j = 0; j < HU && u0 + j < H; ++j) {
+            if (f.h_root) f.h_root[dst + j] = f.h[src + j];
+            if (f.c_root && f.c) f.c_root[dst + j] = f.c[src + j];
+        }
+    }
+    if (cg == 0) {                                            // once per root
+        if (f.root_out) f.root_out[t] = n;
+        if (atomicCAS(&f.root_ws[t], -1, n) != -1) latch_error(f.ctl, TL_ESTRUCT);      // a second root of the same tree
+    }
+}
+
 struct FlowTicket {
     int p, key, left, right, up;  // parent that became ready with this lane's row (-1: none), its place among the group's parents, its children and its own parent
 };
@@ -506,15 +535,7 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int n_slots = gridDim.x / f.n_cg;
-    int member, slot;
-    if (f.xcd_slots) {                                // every slot on one L2 domain, as in the level scheduler
-        const int q = blockIdx.x / N_XCD;
-        slot = (int)(blockIdx.x % N_XCD) + N_XCD * (q / f.n_cg);
-        member = q % f.n_cg;
-    } else {
-        member = blockIdx.x % f.n_cg;
-        slot = blockIdx.x / f.n_cg;
-    }
+    const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;
     const int my_cg = member;
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
@@ -532,22 +553,37 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     const int t_lo = first_tree_at(slot), t_hi = first_tree_at(slot + 1);
     const int nb = f.tree_off[t_lo], ne = f.tree_off[t_hi];
     const int slot_internal = ((ne - nb) - (t_hi - t_lo)) / 2;      // full binary trees
-    if (slot_internal <= 0) return;
+    if (ne <= nb) return;
     unsigned *seen = reinterpret_cast<unsigned *>(f.flow_seen) + (size_t)member * f.n_nodes;   // this workgroup's own: [nb, ne) of it
     int4 *list = f.flow_list + (size_t)member * f.n_int + (nb - t_lo) / 2;
     int *len = &sm.cmd[4];
-    if (tid == 0) sm.cmd[7] = 0;
+    if (tid == 0) {
+        sm.cmd[6] = 0;                                // roots found
+        sm.cmd[7] = 0;                                // a wait was abandoned
+    }
+    __syncthreads();
     for (int n = nb + tid; n < ne; n += WG_THREADS) seen[n] = 0u;
-    // the list starts with the slot's nodes over two leaves, in node order
-    int n_listed = 0;
+    // the list starts with the slot's nodes over two leaves, in node order.  The same pass over the slot's nodes counts
+    // the roots (nodes without a parent): there must be one per tree (a second one in a tree is caught where the roots
+    // are copied out, after the last piece).
+    int n_listed = 0, n_roots = 0;
     for (int base = nb; base < ne; base += WG_THREADS) {
         const int n = base + tid;
-        int l = -1, r = -1;
+        int l = -1, r = -1, up = 0;
         bool seed = false;
         if (n < ne) {
             l = f.left[n];
             r = f.right[n];
+            up = f.parent[n];
             seed = l >= 0 && f.pending[n] == 0;
+        }
+        if (f.flow_roots) {
+            const bool is_root = n < ne && up < 0;
+            n_roots += __popcll(__ballot(is_root));           // (every wave counts its own; added up below)
+            if (is_root) {
+                const int at = atomicAdd(&sm.cmd[6], 1);
+                if (at < FLOW_ROOTS_KEPT) sm.roots[at] = n;
+            }
         }
         const unsigned long long mask = __ballot(seed);
         __syncthreads();                              // (the counts of the previous round have been read)
@@ -557,11 +593,17 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
         for (int wv = 0; wv < (tid >> 6); ++wv) at += sm.cmd[wv];
         if (seed) {
             const int pos = at + __popcll(mask & ((1ull << (tid & 63)) - 1ull));
-            if (pos < slot_internal) list[pos] = int4{n, l, r, f.parent[n]};
+            if (pos < slot_internal) list[pos] = int4{n, l, r, up};
         }
         n_listed += sm.cmd[0] + sm.cmd[1] + sm.cmd[2] + sm.cmd[3];
     }
     __syncthreads();
+    if (f.flow_roots) {
+        if ((tid & 63) == 0) sm.cmd[tid >> 6] = n_roots;
+        __syncthreads();
+        if (tid == 0 && member == 0 && sm.cmd[0] + sm.cmd[1] + sm.cmd[2] + sm.cmd[3] != t_hi - t_lo) latch_error(ctl, TL_ESTRUCT);
+    }
+    const int roots_found = sm.cmd[6];
     if (tid == 0) *len = n_listed;
     wait_mem();
     __syncthreads();
@@ -630,6 +672,18 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     if (tid == 0) {
         __hip_atomic_fetch_max(&ctl->n_levels, pieces + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (begin < slot_internal) latch_error(ctl, TL_ESTRUCT);     // nodes that never became ready: not a forest
+    }
+    if (f.flow_roots) {
+        // the roots' states, every workgroup the hidden units it has computed itself (or, for a tree of one node,
+        // that the leaf kernel has left), once its own stores have arrived
+        wait_mem();
+        __syncthreads();
+        if (roots_found <= FLOW_ROOTS_KEPT) {
+            for (int i = tid; i < roots_found; i += WG_THREADS) flow_copy_root(f, sm.roots[i], my_cg, t_lo, t_hi);
+        } else {
+            for (int n = nb + tid; n < ne; n += WG_THREADS)
+                if (f.parent[n] < 0) flow_copy_root(f, n, my_cg, t_lo, t_hi);
+        }
     }
 }
 

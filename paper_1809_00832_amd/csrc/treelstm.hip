@@ -740,7 +740,7 @@ int read_ctl(tl_ctx *ctx)
     TL_HIP(hipMemcpyAsync(ctx->host_ctl, ctx->last.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, ctx->last_stream));
     TL_HIP(hipStreamSynchronize(ctx->last_stream));
     // a tree without a root shows as a root count below the number of trees
-    if (ctx->host_ctl->status == 0 && ctx->host_ctl->n_roots != ctx->last.n_trees) ctx->host_ctl->status = TL_ESTRUCT;
+    if (ctx->host_ctl->status == 0 && !ctx->last.flow_roots && ctx->host_ctl->n_roots != ctx->last.n_trees) ctx->host_ctl->status = TL_ESTRUCT;
     return TL_OK;
 }
 
@@ -860,6 +860,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     if (flow) {
         f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) ? 2 : 1;
+        f.flow_roots = f.n_int > 0 && !need_levels ? 1 : 0;      // (with no internal node the data-flow kernel is not launched)
         f.flow_seen = reinterpret_cast<int32_t *>(ctx->flow_ws);
         f.flow_list = reinterpret_cast<int4 *>(ctx->flow_ws + align256((size_t)ctx->n_cg * ctx->cap_nodes * sizeof(int32_t)));
     }
@@ -893,7 +894,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     const int nb_reset = f.flow == 1 ? (n_nodes / 4 + 1 < 256 ? 256 : (n_nodes / 4 + 1 > 4096 ? 4096 : n_nodes / 4 + 1)) : 256;
     hipLaunchKernelGGL(k_reset, dim3(nb_reset), dim3(256), 0, st, f, need_levels ? 1 : 0);
     hipLaunchKernelGGL(k_scatter, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
-    hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
+    if (!f.flow_roots) hipLaunchKernelGGL(k_roots, dim3(nb_big), dim3(NODE_BLOCK), 0, st, f);
     if (need_levels) {
         hipLaunchKernelGGL(k_climb, dim3((f.n_leaf + 255) / 256), dim3(256), 0, st, f);
         hipLaunchKernelGGL(k_level_hist, dim3(nb_nodes), dim3(256), 0, st, f);
@@ -931,7 +932,6 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE || cfg.scheduler == TL_SCHED_DATAFLOW) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            f.xcd_slots = (spw > 0 && (grid_l / ctx->n_cg) % N_XCD == 0 && !getenv("TL_NO_XCD_SLOTS")) ? 1 : 0;
             hipLaunchKernelGGL(flow ? flow_kernel(cfg.cell, vec4_inner, spw, bf16) : levels_kernel(cfg.cell, vec4_inner, spw, bf16),
                                dim3(grid_l), dim3(WG_THREADS), spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
             ctx->last_grid = grid_l;
@@ -961,7 +961,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     if (prof) TL_HIP(hipEventRecord(ev[3], st));
 
     // ---- roots ---------------------------------------------------------------------------
-    hipLaunchKernelGGL(k_root_gather, dim3(n_trees), dim3(128), 0, st, f);
+    if (!f.flow_roots) hipLaunchKernelGGL(k_root_gather, dim3(n_trees), dim3(128), 0, st, f);
     TL_HIP(hipGetLastError());
     if (prof) {
         TL_HIP(hipEventRecord(ev[4], st));
