@@ -19,10 +19,19 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}      # MI355X dense matrix peaks
 HBM_GBS = 8000.0
-# HBM bytes per launch of the internal-node kernel from rocprofv3 counter passes (FETCH_SIZE + WRITE_SIZE, scaled by a
-# copy of known size; profiles/levels_persistent_throughput_f32_counters.md).  Only for the configuration the counters
-# were taken on; to be cleared when that kernel changes.
-MEASURED_TRAFFIC = {("throughput", "level_device", "f32"): {"read": 250.5 * 2 ** 20, "write": 26.4 * 2 ** 20}}
+DEFAULT_SCHEDULER = "dataflow"
+
+
+def measured_traffic(workload, scheduler, dtype):
+    """HBM bytes per launch of the internal-node kernel from rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE, each
+    scaled by a copy of known size), as written into profiles/traffic.json together with the counter summaries under
+    profiles/.  A configuration whose counters have not been taken (or whose kernel has changed since) has no entry."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
+            table = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    return table.get("%s/%s/%s" % (workload, scheduler, dtype))
 
 
 def algorithmic_work(w):
@@ -139,7 +148,7 @@ def head_stage(w, n_classes, reps=50):
     written once)."""
     import torch
     from paper_1809_00832_amd import binding
-    net = binding.TreeNet(w.params, scheduler="level_device")
+    net = binding.TreeNet(w.params, scheduler=DEFAULT_SCHEDULER)
     try:
         net.load(w.trees)
         net.forward()
@@ -307,6 +316,37 @@ def topdown_bench(steps, warmup, with_cpu):
                       "note": "tl_td_generate, root states resident; trees are grown breadth first, two grid barriers per depth"}))
 
 
+def other_configs(steps, warmup):
+    """The evaluation workloads other than the headline one, a few steps each: ms per step, trees/s, nodes/s and the
+    internal-node kernel's fraction of the matrix peak of its precision (algorithmic flops over its mean duration from
+    the library's stage events), for the default scheduler; on `sentence`, `throughput` and `stress` also for the
+    ready-queue scheduler and the two level-wise ones (Section 4.1 against the depth-wise batching of Section 6.3)."""
+    from paper_1809_00832_amd import binding, synth
+    rows = []
+    cases = [("tiny", "f32"), ("sentence", "f32"), ("throughput", "bf16"), ("treernn", "f32"), ("rntn", "f32"), ("stress", "f32"),
+             ("sentence", "bf16"), ("stress", "bf16")]
+    for name, dtype in cases:
+        w = synth.workload(name)
+        t = w.trees
+        f_int, f_leaf, _ = algorithmic_work(w)
+        prec = binding.TL_F32 if dtype == "f32" else binding.TL_BF16_IN
+        heavy = name == "stress"
+        k, wu = (min(steps, 5), min(warmup, 2)) if heavy else (min(steps, 20), min(warmup, 5))
+        scheds = [DEFAULT_SCHEDULER]
+        if name in ("sentence", "throughput", "stress"):
+            scheds += ["ready", "level_device", "level_host"]
+        row = {"workload": name, "dtype": dtype, "trees": t.n_trees, "nodes": t.n_nodes, "hidden": w.params.hidden, "schedulers": {}}
+        for sched in scheds:
+            r = run_scheduler(w, sched, prec, k, wu)
+            kernel_ms = r["stage_ms"]["internal"]
+            row["schedulers"][sched] = {
+                "ms_per_step": r["sec"] * 1e3, "trees_per_sec": t.n_trees / r["sec"], "nodes_per_sec": t.n_nodes / r["sec"],
+                "internal_ms": kernel_ms, "internal_frac_mfma_peak": f_int / (kernel_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
+                "step_frac_mfma_peak": (f_int + f_leaf) / r["sec"] / 1e12 / PEAK_TFLOPS[dtype], "stage_ms": r["stage_ms"]}
+        rows.append(row)
+    return rows
+
+
 def cpu_baseline(w, max_nodes=40000):
     """The CPU checker as it stands, one thread per host core (at most 16), on all trees of the workload, or, when
     the workload is large, on a sample of whole trees of about max_nodes nodes taken at even spacing over the batch."""
@@ -358,10 +398,11 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="throughput")
-    ap.add_argument("--scheduler", default="level_device", choices=["ready", "level_device", "level_host", "ready_priority", "dataflow"])
+    ap.add_argument("--scheduler", default=DEFAULT_SCHEDULER, choices=["ready", "level_device", "level_host", "ready_priority", "dataflow"])
     ap.add_argument("--precision", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads / precisions")
     ap.add_argument("--head", type=int, default=5, help="classes of the per-node classifier head timed as an extra stage (0: skip)")
     ap.add_argument("--backward", action="store_true", help="also time tl_backward on the same batch (TreeLSTM, fp32)")
     ap.add_argument("--length-sweep", action="store_true",
@@ -429,11 +470,12 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "flops_per_launch": f_int, "kernel_ms": kernel_ms, "traffic": None},
     }
-    traffic = MEASURED_TRAFFIC.get((args.workload, args.scheduler, args.precision))
+    traffic = measured_traffic(args.workload, args.scheduler, args.precision)
     if traffic:
-        out["roofline"]["traffic"] = traffic["read"] + traffic["write"]
-        out["roofline"]["traffic_read"] = traffic["read"]
-        out["roofline"]["traffic_write"] = traffic["write"]
+        out["roofline"]["traffic"] = traffic["read_bytes"] + traffic["write_bytes"]
+        out["roofline"]["traffic_read"] = traffic["read_bytes"]
+        out["roofline"]["traffic_write"] = traffic["write_bytes"]
+        out["roofline"]["traffic_source"] = traffic.get("source")
     bound_ms, n_heights = span_bound_ms(w, peak)
     out["span_bound"] = {"internal_ms": bound_ms, "heights": n_heights,
                          "note": "sum over heights of max(flops at matrix peak, 2 us grid synchronisation)"}
@@ -452,6 +494,8 @@ def main():
             if "sec_graph" in r:
                 comp[sched]["ms_per_step_graph_replay"] = r["sec_graph"] * 1e3
         out["comparison"] = comp
+    if not args.no_others and args.workload == "throughput" and args.precision == "f32":
+        out["other_configs"] = other_configs(args.steps, args.warmup)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

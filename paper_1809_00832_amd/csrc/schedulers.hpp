@@ -662,8 +662,8 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
         if (sm.cmd[7] != 0) return;                   // a wait was abandoned: everybody leaves
         pieces += 1;
         begin += count;
-        __syncthreads();
-        from_lds = takes_all && *len - begin <= FLOW_NXT_ROWS;      // (everything listed since is in the LDS tables)
+        // (wave 0 has listed the piece's last parents before the last barrier inside the cell, so *len and sm.nxt are final)
+        from_lds = takes_all && *len - begin <= FLOW_NXT_ROWS;      // everything listed since is in the LDS tables
         if (!from_lds) {
             wait_mem();                               // the next piece is read from the list in memory: wave 0's entries have arrived there
             __syncthreads();
