@@ -34,13 +34,19 @@
  *
  * Threading: a context is not thread safe; one forward may be in flight per context.
  * TL_SCHED_READY (also in its _PRIORITY variant, which is meant wherever TL_SCHED_READY is
- * named below), TL_SCHED_LEVEL_DEVICE and TL_SCHED_DATAFLOW evaluate the internal nodes in one kernel whose
- * workgroups wait for each other, so all of them must be resident together: they are sized to
- * fill the device, and while such a forward runs nothing else that holds compute units for long
- * (another context's forward on a second stream, say) may run on the same device.  Breaking
- * this does not hang - every wait is bounded by spin_limit - but the forward may then end with
- * TL_ESTALL.  Forwards of several contexts are therefore put on one stream or ordered with
- * events; TL_SCHED_LEVEL_HOST has no such requirement.
+ * named below), TL_SCHED_LEVEL_DEVICE and TL_SCHED_DATAFLOW evaluate the internal nodes in one
+ * kernel whose workgroups wait for each other, so all of them must be resident together.
+ * tl_forward sizes the grid to what the device holds of the very kernel it launches (asked of
+ * the runtime per kernel variant) and returns TL_EHIP at once if not even one set of workgroups
+ * fits; with the device to itself such a forward therefore always completes.  What the library
+ * cannot see is other work on the device: while such a forward runs, nothing else that holds
+ * compute units for long (another context's forward on a second stream, say) may run beside it.
+ * Forwards of several contexts are therefore put on one stream or ordered with events (tested
+ * with two contexts on two streams); breaking this does not hang - every wait is bounded by
+ * spin_limit - but the forward may then end with TL_ESTALL.  TL_SCHED_LEVEL_HOST has no such
+ * requirement.  The default of the ABI (scheduler = 0) is TL_SCHED_READY, the plainest device
+ * form of the paper's mechanism; TL_SCHED_DATAFLOW is the fastest on every workload measured in
+ * fp32, TL_SCHED_LEVEL_DEVICE on wide batches with bf16 operands.
  * Errors: functions return TL_OK (0) or a negative tl_error.
  */
 #ifndef TREELSTM_H

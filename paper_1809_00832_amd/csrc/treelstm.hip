@@ -6,6 +6,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "treelstm.h"
 #include "common.hpp"
@@ -43,6 +44,8 @@ struct tl_ctx {
     // workspace
     unsigned char *ws = nullptr;
     size_t ws_bytes = 0;
+    struct Resident { const void *kernel; size_t lds; int per_cu; };
+    std::vector<Resident> resident;    // workgroups per compute unit of the persistent kernel variants launched so far
     unsigned char *flow_ws = nullptr;  // data-flow scheduler: per-column-group counters and lists, for cap_nodes nodes
     unsigned char *scratch = nullptr;  // this device's copy of the fixed workspace of tl_forward_noalloc (not owned)
     int cap_nodes = 0, cap_trees = 0;
@@ -401,6 +404,19 @@ int pack_rntn_f32(tl_ctx *ctx, hipStream_t st)
         if (rc != TL_OK) return rc;
     }
     TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
+// Workgroups of `kernel` (with `lds` bytes of dynamic LDS) that one compute unit holds at a time; asked of the runtime
+// once per kernel variant.
+int resident_per_cu(tl_ctx *ctx, fwd_kernel kernel, size_t lds, int *out)
+{
+    for (const auto &r : ctx->resident)
+        if (r.kernel == reinterpret_cast<const void *>(kernel) && r.lds == lds) { *out = r.per_cu; return TL_OK; }
+    int n = 0;
+    TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void *>(kernel), WG_THREADS, lds));
+    ctx->resident.push_back({reinterpret_cast<const void *>(kernel), lds, n});
+    *out = n;
     return TL_OK;
 }
 
@@ -845,7 +861,21 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
         f.hb = static_ws ? reinterpret_cast<unsigned short *>(ctx->scratch + NOALLOC_WS_BYTES) : ctx->hb;
         f.hs = ctx->hs;
     }
-    const int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
+    // The persistent kernels' workgroups wait for each other, so all of them must be resident at once: the grid is
+    // cut to what the device holds of the very kernel that is launched (the figure taken at tl_create is that of one
+    // variant), and a kernel of which not even one set of workgroups fits is refused here, not found out by a stall.
+    const bool ready_sched = cfg.scheduler == TL_SCHED_READY || cfg.scheduler == TL_SCHED_READY_PRIORITY;
+    const fwd_kernel kern = !persistent ? nullptr
+                            : ready_sched ? ready_kernel(cfg.cell, vec4_inner, spw, bf16)
+                            : flow ? flow_kernel(cfg.cell, vec4_inner, spw, bf16) : levels_kernel(cfg.cell, vec4_inner, spw, bf16);
+    const size_t kern_lds = spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES;
+    int grid_p = (persistent && spw > 0) ? ctx->ws_grid : ctx->persistent_grid;
+    if (kern) {
+        int per_cu = 0;
+        if ((rc = resident_per_cu(ctx, kern, kern_lds, &per_cu)) != TL_OK) return rc;
+        if (per_cu * ctx->n_cu < grid_p) grid_p = per_cu * ctx->n_cu;
+        if (grid_p < (spw > 0 ? ctx->n_cg : 1) + (ready_sched ? 1 : 0)) return TL_EHIP;
+    }
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
     // RNTN: a frontier of at most rntn_units tiles is cut into RNTN_PARTS workgroups per tile and column group
     f.rntn_part = ctx->rntn_part; f.rntn_done = ctx->rntn_done;
@@ -856,7 +886,6 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
 
     // heights and per-height node lists: for the host-driven scheduler, and as the check for cycles
     const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;
-    const bool ready_sched = cfg.scheduler == TL_SCHED_READY || cfg.scheduler == TL_SCHED_READY_PRIORITY;
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     if (flow) {
         f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) ? 2 : 1;
@@ -926,14 +955,12 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     if (f.n_int > 0) {
         if (ready_sched) {
             const int grid_r = f.n_gangs * (f.gang_size + 1);
-            hipLaunchKernelGGL(ready_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_r), dim3(WG_THREADS),
-                               spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
+            hipLaunchKernelGGL(kern, dim3(grid_r), dim3(WG_THREADS), kern_lds, st, f);
             ctx->last_grid = grid_r;
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE || cfg.scheduler == TL_SCHED_DATAFLOW) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            hipLaunchKernelGGL(flow ? flow_kernel(cfg.cell, vec4_inner, spw, bf16) : levels_kernel(cfg.cell, vec4_inner, spw, bf16),
-                               dim3(grid_l), dim3(WG_THREADS), spw > 0 ? ctx->ws_lds : TILE_SMEM_BYTES, st, f);
+            hipLaunchKernelGGL(kern, dim3(grid_l), dim3(WG_THREADS), kern_lds, st, f);
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists

@@ -393,3 +393,40 @@ def test_rntn_other_sizes(sched):
             check_against_oracle(p, trees, got, None, "rntn d=%d/%s" % (d, sched))
         finally:
             net.close()
+
+
+@pytest.mark.parametrize("sched", ["dataflow", "level_device", "ready"])
+def test_two_contexts_on_two_streams_ordered_by_events(sched):
+    """The documented way to use several contexts on one device: their forwards (persistent kernels that need the
+    device to themselves) go to different streams but are ordered with events, here four forwards alternating
+    between a TreeLSTM and a TreeRNN context.  Both results against the checker."""
+    import torch
+    say("case two contexts", sched)
+    wa, ra = reference("sentence")
+    wb, rb = reference("treernn")
+    a = binding.TreeNet(wa.params, scheduler=sched)
+    b = binding.TreeNet(wb.params, scheduler=sched)
+    try:
+        a.load(wa.trees)
+        b.load(wb.trees)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        last = None
+        for it in range(4):
+            for net, stream in ((a, sa), (b, sb)):
+                if last is not None:
+                    stream.wait_event(last)
+                with torch.cuda.stream(stream):
+                    if it == 3:
+                        net.batch["h"].fill_(float("nan"))
+                    net.forward(stream.cuda_stream)
+                    last = torch.cuda.Event()
+                    last.record(stream)
+        torch.cuda.synchronize()
+        assert binding.tl_status(a.ctx) == 0 and binding.tl_status(b.ctx) == 0
+        assert_close(a.batch["h"].cpu().numpy(), ra["h"], "context A h")
+        assert_close(a.batch["c"].cpu().numpy(), ra["c"], "context A c")
+        assert_close(b.batch["h"].cpu().numpy(), rb["h"], "context B h")
+    finally:
+        a.close()
+        b.close()
