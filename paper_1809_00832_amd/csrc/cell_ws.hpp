@@ -238,7 +238,7 @@ __device__ inline bool flow_wait_rows(const Fwd &f, const Req &req, floatx4 (&ro
     }
 }
 // One element of a child's c row.
-template <bool COH> __device__ inline float flow_wait_c(const Fwd &f, const float *p, float v)
+template <bool COH> __device__ inline float flow_wait_c(const Fwd &f, __amdgpu_buffer_rsrc_t rs_c, unsigned off, float v)
 {
     int spins = 0;
     while (__float_as_uint(v) == FLOW_SENTINEL) {
@@ -247,7 +247,7 @@ template <bool COH> __device__ inline float flow_wait_c(const Fwd &f, const floa
             break;
         }
         backoff();
-        v = ld_f<COH>(p);
+        v = buf_ld_f<COH>(rs_c, off);
     }
     return v;
 }
@@ -289,6 +289,9 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
     const float *a_lane = &sm.a[wave][(lane & 15) * WsSmemT<SPW>::A_LD + (lane >> 4) * 4];   // + 16 s: this lane's operand of k-step s
+    // h and c rows as raw buffers (the caller guarantees that they are smaller than 4 GiB)
+    const __amdgpu_buffer_rsrc_t rs_h = buf_of(f.h, (unsigned long long)f.n_nodes * H * 4), rs_c = buf_of(f.c, (unsigned long long)f.n_nodes * H * 4);
+    const unsigned row_b = (unsigned)H * 4u, hu_b = (unsigned)(hu_ok ? hu : 0) * 4u;
 
     // Second half of a block: the four K-range partial sums have met in LDS (a barrier has been
     // passed since they were written); wave w finishes accumulator row w of the block.
@@ -303,28 +306,28 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             gate[g] = sum + w.bias[g];
         }
         if (ev) {
-            const size_t o = (size_t)enode * H + hu;
+            const unsigned o = (unsigned)enode * row_b + hu_b;
             if constexpr (FLOW && EPI == EPI_LSTM_INNER) {      // a child's c element may arrive after its h row
-                cl = flow_wait_c<COH>(f, f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hu, cl);
-                cr = flow_wait_c<COH>(f, f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hu, cr);
+                cl = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b, cl);
+                cr = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b, cr);
             }
             if constexpr (EPI == EPI_LSTM_INNER) {
                 float cc, hh;
                 lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh, kept_gates(f, enode, hu), H);
-                st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, hh);
+                buf_st_f<COH>(rs_c, o, cc);
+                buf_st_f<COH>(rs_h, o, hh);
             } else if constexpr (EPI == EPI_LSTM_LEAF) {
                 float cc, hh;
                 lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh, kept_gates(f, enode, hu), H);
-                st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, hh);
+                buf_st_f<COH>(rs_c, o, cc);
+                buf_st_f<COH>(rs_h, o, hh);
             } else if constexpr (EPI == EPI_TD_CHILD) {     // gates i, f, o, u of an LSTM step along the edge (as in cell_tile.hpp)
                 const float i = sigmoid_f(gate[0]), fg = sigmoid_f(gate[1]), og = sigmoid_f(gate[2]), u = tanh_f(gate[3]);
                 const float cc = __builtin_fmaf(fg, cl, i * u);
-                st_f<COH>(f.c + o, cc);
-                st_f<COH>(f.h + o, og * tanh_f(cc));
+                buf_st_f<COH>(rs_c, o, cc);
+                buf_st_f<COH>(rs_h, o, og * tanh_f(cc));
             } else {
-                st_f<COH>(f.h + o, tanh_f(gate[0]));
+                buf_st_f<COH>(rs_h, o, tanh_f(gate[0]));
             }
         }
     };
@@ -361,12 +364,10 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         const bool ev = enode >= 0 && hu_ok;
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {                        // unused lanes read some existing element; the value is dropped
-            const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
+            cr = buf_ld_f<COH>(rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
         } else if (EPI == EPI_TD_CHILD) {                   // the parent's c (src0 = the parent's row)
-            const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
         }
         __builtin_amdgcn_sched_barrier(0);                  // all requests are issued before the MFMAs start
         floatx4 acc[NG];
@@ -436,26 +437,29 @@ template <int S> struct WsSmemBfT {
     int par[WS_TABLE_ROWS];
     int nxt[4][FLOW_NXT_ROWS];
     int roots[FLOW_ROOTS_KEPT];
+    float bias[MAX_GATES * HU];        // the column group's bias (ws_load puts it here: a load of it from memory after the barrier would
+                                       // have to wait for the row requests issued before it, and registers are short in this form)
     int cmd[8];
 };
 
 template <int NG, int S> struct WsWeightsBf {
     bf16x8 b[S][NG];
-    float bias[NG];     // in registers too: a load of it after the barrier would have to wait for the row requests issued before it
 };
 template <int NG> struct WsWeightsBf<NG, 0> {};
 
 // k-steps (of 32) [wave*S, (wave+1)*S) of column group cg; the packed matrix has exactly 4*S of them.
+// Called by all threads of the workgroup; a barrier must be passed before the first ws_tile (its own first barrier
+// comes before the bias is read).
 template <int NG, int S>
-__device__ inline void ws_load(WsWeightsBf<NG, S> &w, const Gemm &gm, int cg, int wave, int lane)
+__device__ inline void ws_load(WsWeightsBf<NG, S> &w, WsSmemBfT<S> &sm, const Gemm &gm, int cg, int wave, int lane)
 {
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(gm.wp) + ((size_t)cg * 4 * S + (size_t)wave * S) * NG * 64 + lane;
 #pragma unroll
     for (int s = 0; s < S; ++s)
 #pragma unroll
         for (int g = 0; g < NG; ++g) w.b[s][g] = wp[(size_t)(s * NG + g) * 64];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) w.bias[g] = gm.bp[(cg * NG + g) * HU + (lane & 15)];
+    const int t = wave * 64 + lane;
+    if (t < NG * HU) sm.bias[t] = gm.bp[cg * NG * HU + t];
 }
 
 template <int EPI, bool COH, int S, bool FLOW = false, typename Hook = WsNoHook>
@@ -473,6 +477,10 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
     const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
+    // h, c and the bf16 copy of h as raw buffers (the caller guarantees that they are smaller than 4 GiB)
+    const __amdgpu_buffer_rsrc_t rs_h = buf_of(f.h, (unsigned long long)f.n_nodes * H * 4), rs_c = buf_of(f.c, (unsigned long long)f.n_nodes * H * 4),
+                                 rs_hb = buf_of(f.hb, (unsigned long long)f.n_nodes * f.hs * 2);
+    const unsigned row_b = (unsigned)H * 4u, hu_b = (unsigned)(hu_ok ? hu : 0) * 4u;
 
     WsRowRequest<SEG, S, unsigned short> req;
     req.init(sm, f, table, table_rows, stride, stride, wave, lane);
@@ -503,9 +511,8 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         // c operands of the row this lane finishes: requested before the MFMAs, used after them
         float cl = 0.f, cr = 0.f;
         if (EPI == EPI_LSTM_INNER) {
-            const int hc = hu_ok ? hu : 0;
-            cl = ld_f<COH>(f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hc);
-            cr = ld_f<COH>(f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hc);
+            cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
+            cr = buf_ld_f<COH>(rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
         }
         __builtin_amdgcn_sched_barrier(0);
         floatx4 acc[NG];
@@ -537,28 +544,28 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
             sum += red[((1 * NG + g) * 4 + wave) * 64 + lane];
             sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
             sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
-            gate[g] = sum + w.bias[g];
+            gate[g] = sum + sm.bias[g * HU + (lane & 15)];
         }
         if (ev) {
-            const size_t o = (size_t)enode * H + hu;
+            const unsigned o = (unsigned)enode * row_b + hu_b;
             float hh;
             if constexpr (FLOW && EPI == EPI_LSTM_INNER) {      // a child's c element may arrive after its h row
-                cl = flow_wait_c<COH>(f, f.c + (size_t)sm.src0[erow & (WS_TABLE_ROWS - 1)] * H + hu, cl);
-                cr = flow_wait_c<COH>(f, f.c + (size_t)sm.src1[erow & (WS_TABLE_ROWS - 1)] * H + hu, cr);
+                cl = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b, cl);
+                cr = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b, cr);
             }
             if constexpr (EPI == EPI_LSTM_INNER) {
                 float cc;
                 lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh);
-                st_f<COH>(f.c + o, cc);
+                buf_st_f<COH>(rs_c, o, cc);
             } else if constexpr (EPI == EPI_LSTM_LEAF) {
                 float cc;
                 lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh);
-                st_f<COH>(f.c + o, cc);
+                buf_st_f<COH>(rs_c, o, cc);
             } else {
                 hh = tanh_f(gate[0]);
             }
-            st_f<COH>(f.h + o, hh);
-            if (f.hb) st_h<COH>(f.hb + (size_t)enode * f.hs + hu, bf16_bits(hh));
+            buf_st_f<COH>(rs_h, o, hh);
+            if (f.hb) buf_st_h<COH>(rs_hb, ((unsigned)enode * (unsigned)f.hs + (unsigned)hu) * 2u, bf16_bits(hh));
         }
     }
     __syncthreads();

@@ -206,6 +206,26 @@ template <bool COH> __device__ inline floatx4 ld_f4(const float *p)
     return v;
 }
 
+// Rows of a table smaller than 4 GiB addressed as a raw buffer: a 32-bit byte offset per lane and the base in scalar
+// registers, where a pointer per lane costs two vector registers and 64-bit arithmetic.  COH: device scope (the
+// cache-policy bit that the device-scope loads and stores above carry as well).
+__device__ inline __amdgpu_buffer_rsrc_t buf_of(const void *p, unsigned long long bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, p ? (unsigned)bytes : 0u, 0x00020000);
+}
+template <bool COH> __device__ inline float buf_ld_f(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, COH ? 16 : 0));
+}
+template <bool COH> __device__ inline void buf_st_f(__amdgpu_buffer_rsrc_t r, unsigned off, float v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, (int)off, 0, COH ? 16 : 0);
+}
+template <bool COH> __device__ inline void buf_st_h(__amdgpu_buffer_rsrc_t r, unsigned off, unsigned short v)
+{
+    __builtin_amdgcn_raw_buffer_store_b16(v, r, (int)off, 0, COH ? 16 : 0);
+}
+
 __device__ inline unsigned long long pack2(unsigned lo32, unsigned hi32) { return (unsigned long long)hi32 << 32 | lo32; }
 template <bool COH> __device__ inline void qrec_store(QRec *q, int node, int left, int right)
 {

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
     const int cg = gang_cg(blockIdx.x % f.n_cg, f.n_cg, f.n_cg);
     const int slot = blockIdx.x / f.n_cg, n_slots = gridDim.x / f.n_cg;
     WsWeightsBf<EpiTraits<EPI_LSTM_LEAF>::NG, S> w;
-    ws_load(w, f.leaf, cg, tid >> 6, tid & 63);
+    ws_load(w, sm, f.leaf, cg, tid >> 6, tid & 63);
     const int share = ((f.n_leaf + n_slots - 1) / n_slots + 15) & ~15;
     const int lo = slot * share, hi = min(f.n_leaf, lo + share);
     for (int piece = lo; piece < hi; piece += WS_TABLE_ROWS) {
@@ -277,7 +277,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;
     const int my_cg = gang_cg(member, f.n_cg, f.n_cg);
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
-    if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+    if constexpr (SPW > 0 && BF16) ws_load(w, sm, f.inner, my_cg, tid >> 6, tid & 63);
+    else if constexpr (SPW > 0) ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
     unsigned epoch = 0;
     const unsigned n_seed = (unsigned)ctl->n_seed;
     unsigned begin = 0, end = n_seed;
@@ -510,7 +511,7 @@ __device__ inline void flow_append(int4 *list, int capacity, int *len, volatile 
         base = *len;
         *len = base + __popcll(keys);
     }
-    base = __shfl(base, 0);
+    base = __builtin_amdgcn_readfirstlane(base);
     if (ready) {
         const int pos = base + __popcll(keys & ((1ull << t.key) - 1ull));
         if (pos < capacity) list[pos] = int4{t.p, t.left, t.right, t.up};
@@ -538,7 +539,8 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;
     const int my_cg = member;
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
-    ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+    if constexpr (BF16) ws_load(w, sm, f.inner, my_cg, tid >> 6, tid & 63);
+    else ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
 
     // the slot's trees: [t_lo, t_hi), cut where the node count passes slot / n_slots of the batch
     auto first_tree_at = [&](int s) {
@@ -903,7 +905,8 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
     const int my_cg = gang_cg(member, f.gang_size, f.n_cg);
     PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
     if constexpr (SPW > 0) {
-        ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+        if constexpr (BF16) ws_load(w, sm, f.inner, my_cg, tid >> 6, tid & 63);
+        else ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
         // tiles have at most TILE_ROWS rows here; the rest of the cell's row tables reads "no row"
         sm.node[tid] = -1;
         sm.src0[tid] = 0;

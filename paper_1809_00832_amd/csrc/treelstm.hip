@@ -888,7 +888,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     if (flow) {
-        f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) ? 2 : 1;
+        f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0 && ws_range) ? 2 : 1;
         f.flow_roots = f.n_int > 0 && !need_levels ? 1 : 0;      // (with no internal node the data-flow kernel is not launched)
         f.flow_seen = reinterpret_cast<int32_t *>(ctx->flow_ws);
         f.flow_list = reinterpret_cast<int4 *>(ctx->flow_ws + align256((size_t)ctx->n_cg * ctx->cap_nodes * sizeof(int32_t)));
@@ -938,7 +938,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     if (prof) TL_HIP(hipEventRecord(ev[1], st));
 
     // ---- leaves ------------------------------------------------------------------------
-    if (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0) {
+    if (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0 && ws_range) {          // (its cell addresses h and c with 32-bit offsets)
         hipLaunchKernelGGL(bf16 ? leaf_ws_bf_kernel(ctx->spw_leaf) : leaf_ws_kernel(ctx->spw_leaf), dim3(ctx->leaf_grid),
                            dim3(WG_THREADS), ws_lds_bytes(ctx->spw_leaf, bf16), st, f);
     } else if (cfg.cell == TL_TREELSTM) {
