@@ -480,7 +480,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     // h, c and the bf16 copy of h as raw buffers (the caller guarantees that they are smaller than 4 GiB)
     const __amdgpu_buffer_rsrc_t rs_h = buf_of(f.h, (unsigned long long)f.n_nodes * H * 4), rs_c = buf_of(f.c, (unsigned long long)f.n_nodes * H * 4),
                                  rs_hb = buf_of(f.hb, (unsigned long long)f.n_nodes * f.hs * 2);
-    const unsigned row_b = (unsigned)H * 4u, hu_b = (unsigned)(hu_ok ? hu : 0) * 4u;
+    const unsigned row_b = (unsigned)H * 4u, hu_b = (unsigned)(hu_ok ? hu : 0) * 4u, hb_row_b = (unsigned)f.hs * 2u;
 
     WsRowRequest<SEG, S, unsigned short> req;
     req.init(sm, f, table, table_rows, stride, stride, wave, lane);
@@ -565,7 +565,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
                 hh = tanh_f(gate[0]);
             }
             buf_st_f<COH>(rs_h, o, hh);
-            if (f.hb) buf_st_h<COH>(rs_hb, ((unsigned)enode * (unsigned)f.hs + (unsigned)hu) * 2u, bf16_bits(hh));
+            if (f.hb) buf_st_h<COH>(rs_hb, (unsigned)enode * hb_row_b + (hu_b >> 1), bf16_bits(hh));
         }
     }
     __syncthreads();

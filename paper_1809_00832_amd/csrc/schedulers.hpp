@@ -466,7 +466,7 @@ struct FlowTicket {
 __device__ inline FlowTicket flow_count_at_parent(const Fwd &f, unsigned *seen, int p, unsigned stamp)
 {
     FlowTicket t{-1, 0, -1, -1, -1};
-    const int lane = threadIdx.x;
+    const int lane = (int)__lane_id();                // (recomputed: a value kept across the cell's loop would be spilled)
     if (p >= 0) {
         // counter word: children counted (2 bits) | lane of the first one (6 bits) | stamp of its group (24 bits)
         const unsigned old = __hip_atomic_fetch_add(&seen[p], 1u | (unsigned)lane << 2 | stamp << 8, __ATOMIC_RELAXED,
@@ -486,24 +486,26 @@ __device__ inline FlowTicket flow_count_at_parent(const Fwd &f, unsigned *seen, 
 // Parents that have become ready go to the end of this workgroup's list (its length is kept in LDS), in key order.
 // `scratch`: two words of LDS that only this wave uses (the set of keys is put together there: LDS operations of one
 // wave are executed in the order in which they are issued).
-// Entries that fall into the window of FLOW_NXT_ROWS list positions from `win0` on also go to the LDS tables `nxt`
-// (node, first and second source, parent): the next piece is taken from there when it lies in that window entirely.
-__device__ inline void flow_append(int4 *list, int capacity, int *len, volatile unsigned *scratch, const FlowTicket &t,
+typedef __attribute__((address_space(3))) unsigned lds_uint;
+__device__ inline void flow_append(int4 *list, int capacity, int *len, unsigned *scratch_generic, const FlowTicket &t,
                                    int (*nxt)[FLOW_NXT_ROWS], int win0)
 {
     const int lane = threadIdx.x;
     const bool ready = t.p >= 0;
     const unsigned long long own = __ballot(ready && t.key == lane);
     unsigned long long keys = own;
-    if (__ballot(ready && t.key != lane) != 0ull) {           // a parent listed under its other child's lane: rare
+    if (__ballot(ready && t.key != lane) != 0ull) {           // a parent listed under its other child's lane
+        lds_uint *scratch = (lds_uint *)scratch_generic;      // (known to be LDS: plain ds_ instructions, no memory waits)
         if (lane == 0) {
             scratch[0] = 0u;
             scratch[1] = 0u;
         }
-        if (ready) __hip_atomic_fetch_or(const_cast<unsigned *>(&scratch[t.key >> 5]), 1u << (t.key & 31), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        if (ready) __hip_atomic_fetch_or(&scratch[t.key >> 5], 1u << (t.key & 31), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        keys = (unsigned long long)scratch[1] << 32 | scratch[0];
+        const unsigned lo = __hip_atomic_load(&scratch[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        const unsigned hi = __hip_atomic_load(&scratch[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        keys = (unsigned long long)hi << 32 | lo;
     }
     if (keys == 0ull) return;
     int base = 0;
@@ -638,13 +640,14 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
         const int win0 = takes_all ? begin + count : -(1 << 30);
         __syncthreads();
         // Wave 0 counts the piece's rows at their parents, 64 rows (four blocks) at a time; the parent of a row comes with
-        // its list entry.  The count (a chain of two memory round trips) is sent when the group's first block starts -
-        // for the first group: as soon as the first row requests are out - and what it brings back is used with the
-        // group's last block, or after the last matrix instructions of the piece, to list the parents that have
-        // become ready: the cell never waits for it.
+        // its list entry.  The count (a chain of two memory round trips) is sent when the group's first block has its
+        // rows - for the first group: as soon as the first row requests are out - and what it brings back is used with
+        // the group's last block, or after the last matrix instructions of the piece, to list the parents that have
+        // become ready.  (Using it one block after the count instead, right after that block's rows have arrived,
+        // was measured: slower, the count's answers are not always there by then.)
         FlowTicket ticket{-1, 0, -1, -1, -1};
         const unsigned stamp0 = (unsigned)pieces * (WS_TABLE_ROWS / 64) + 1u;
-        volatile unsigned *scratch = reinterpret_cast<volatile unsigned *>(&sm.cmd[5]);
+        unsigned *scratch = reinterpret_cast<unsigned *>(&sm.cmd[5]);
         auto hook = [&](int where) {
             if (tid >= 64) return;
             if (where == -1) {
