@@ -178,6 +178,12 @@ template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowR
     }
 };
 
+// Lane J of every group of four lanes, to all four.
+template <int J> __device__ inline float quad_bcast(float x)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), J * 0x55, 0xF, 0xF, true));
+}
+
 // ---- validity carried by the data itself (data-flow scheduler) -----------------------------
 // Before the kernel starts, every row that an internal node will produce (its c row and the h row
 // its parent gathers) is filled with a bit pattern that no cell ever stores: all ones, a NaN (h
@@ -347,7 +353,12 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     float p_cl = 0.f, p_cr = 0.f;
     int p_erow = 0;
     constexpr int FINISH_AFTER = SPW > 1 ? 1 : 0;               // k-step after which the previous block is finished
-    for (int rb = 0; rb < nrb; ++rb) {
+    // A piece's last block with few rows takes the narrow form below the loop (data-flow scheduler only).
+    constexpr int NARROW_MAX_RG = NG >= 3 ? 3 : 2;              // groups of four rows up to which that form is the faster one
+    const int n_rg = (count - (nrb - 1) * 16 + 3) >> 2;         // groups of four rows in the last block
+    const bool last_narrow = FLOW && nrb > 0 && n_rg <= NARROW_MAX_RG;
+    const int nrb_full = last_narrow ? nrb - 1 : nrb;
+    for (int rb = 0; rb < nrb_full; ++rb) {
         float *red = sm.red[rb & 1];
         if constexpr (FLOW) {                               // the rows are there only when their producers have stored them
             if (!flow_wait_rows<float, COH, WsRowRequest<SEG, SPW, float, TAIL>, NL, WsLoadGeom<SPW>::RPL>(f, req, rows, req.sub))
@@ -408,6 +419,134 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
         // the two reduction buffers alternate: buffer rb & 1 is written again at the end of block
         // rb + 2, after every wave has passed the barrier inside block rb + 2, hence after it has
         // read this buffer (inside block rb + 1)
+    }
+    if constexpr (FLOW) {
+        // The 16x16x4 instruction takes 32 cycles however many of its 16 rows exist, and the dependent steps of a deep tree
+        // are blocks of one to four rows.  The 4x4x1 instruction (16 independent 4x4 products, 8 cycles) takes the same B
+        // operands - lane l holds U[k(l >> 4)][l & 15] - when its 16 products are read as (k class l >> 4) x (four hidden
+        // units): with A = a[4 rg + (l & 3)][k(l >> 4)] it accumulates, for rows 4 rg .. 4 rg + 3, the sum over the k of
+        // class l >> 4.  A group of four rows so costs a quarter of a block (measured: 4.1 ns per instruction against
+        // 14.6), and the four class sums of a wave are added when the row is finished.  A node's sum is then rounded in
+        // another order than in a full block; which form evaluates a node depends on its place in the list alone, which
+        // does not change from run to run.
+        if (last_narrow) {
+            const int rb = nrb - 1;
+            // Lane l of wave w finishes row w of a group of four rows for hidden unit l >> 2, from wave (l & 3)'s four class
+            // sums; the four lanes of a quad then add theirs in wave order.  (What is computed from the lane number here starts
+            // from a copy the compiler cannot see through: held in registers across the whole kernel, these few values made it
+            // spill others in the loop above.)
+            int nl = lane;
+            asm volatile("" : "+v"(nl));
+            const int n_hu = cg * HU + (nl >> 2);
+            const bool n_hu_ok = n_hu < H;
+            const unsigned n_hu_b = (unsigned)(n_hu_ok ? n_hu : 0) * 4u;
+            auto finish_narrow = [&](const float *red, int enode, bool ev, float cl, float cr, int erow, const float (&bias)[NG]) {
+                float gate[NG];
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const floatx4 p = *reinterpret_cast<const floatx4 *>(&red[(((((nl & 3) * NG + g) * 4 + wave) * 16) + (nl >> 2)) * 4]);
+                    const float q = ((p.x + p.y) + p.z) + p.w;
+                    gate[g] = (((quad_bcast<0>(q) + quad_bcast<1>(q)) + quad_bcast<2>(q)) + quad_bcast<3>(q)) + bias[g];
+                }
+                if (ev) {
+                    const unsigned o = (unsigned)enode * row_b + n_hu_b;
+                    if constexpr (FLOW && EPI == EPI_LSTM_INNER) {
+                        cl = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + n_hu_b, cl);
+                        cr = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + n_hu_b, cr);
+                    }
+                    const bool writer = (nl & 3) == 0;               // the four lanes of a quad hold the same result
+                    if constexpr (EPI == EPI_LSTM_INNER) {
+                        float cc, hh;
+                        lstm_inner_out(gate[0], gate[1], gate[2], gate[3], gate[NG - 1], cl, cr, &cc, &hh, writer ? kept_gates(f, enode, n_hu) : nullptr, H);
+                        if (writer) {
+                            buf_st_f<COH>(rs_c, o, cc);
+                            buf_st_f<COH>(rs_h, o, hh);
+                        }
+                    } else if constexpr (EPI == EPI_LSTM_LEAF) {
+                        float cc, hh;
+                        lstm_leaf_out(gate[0], gate[1], gate[NG - 1], &cc, &hh, writer ? kept_gates(f, enode, n_hu) : nullptr, H);
+                        if (writer) {
+                            buf_st_f<COH>(rs_c, o, cc);
+                            buf_st_f<COH>(rs_h, o, hh);
+                        }
+                    } else if constexpr (EPI == EPI_TD_CHILD) {
+                        const float i = sigmoid_f(gate[0]), fg = sigmoid_f(gate[1]), og = sigmoid_f(gate[2]), u = tanh_f(gate[3]);
+                        const float cc = __builtin_fmaf(fg, cl, i * u);
+                        if (writer) {
+                            buf_st_f<COH>(rs_c, o, cc);
+                            buf_st_f<COH>(rs_h, o, og * tanh_f(cc));
+                        }
+                    } else {
+                        if (writer) buf_st_f<COH>(rs_h, o, tanh_f(gate[0]));
+                    }
+                }
+            };
+
+            int n_enode = -1, n_erow = 0;
+            bool n_ev = false;
+            float n_cl = 0.f, n_cr = 0.f, n_bias[NG];
+            // the row a lane finishes in group rg, and its c operands (a value that shows "not written" is asked for again
+            // when the row is finished)
+            auto request_c = [&](int rg) {
+                n_erow = rb * 16 + rg * 4 + wave;
+                n_enode = n_erow < count ? sm.node[n_erow] : -1;
+                n_ev = n_enode >= 0 && n_hu_ok;
+                if (EPI == EPI_LSTM_INNER) {
+                    n_cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[n_erow & (WS_TABLE_ROWS - 1)] * row_b + n_hu_b);
+                    n_cr = buf_ld_f<COH>(rs_c, (unsigned)sm.src1[n_erow & (WS_TABLE_ROWS - 1)] * row_b + n_hu_b);
+                } else if (EPI == EPI_TD_CHILD) {
+                    n_cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[n_erow & (WS_TABLE_ROWS - 1)] * row_b + n_hu_b);
+                }
+            };
+            if (!flow_wait_rows<float, COH, WsRowRequest<SEG, SPW, float, TAIL>, NL, WsLoadGeom<SPW>::RPL>(f, req, rows, req.sub))
+                sm.cmd[7] = 1;
+            ws_park_rows<SPW>(sm, rows, wave, lane);
+            hook(rb);
+            request_c(0);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) n_bias[g] = __shfl(w.bias[g], nl >> 2);
+#pragma unroll 1
+            for (int rg = 0; rg < n_rg; ++rg) {
+                if (rg > 0) {
+                    __syncthreads();                        // every wave has written its partial sums of group rg - 1
+                    finish_narrow(sm.red[(rb + rg - 1) & 1], n_enode, n_ev, n_cl, n_cr, n_erow, n_bias);
+                    request_c(rg);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                floatx4 acc[NG];
+#pragma unroll
+                for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+                const float *a4 = &sm.a[wave][(rg * 4 + (nl & 3)) * WsSmemT<SPW>::A_LD + (nl >> 4) * 4];
+                floatx4 av_next = *reinterpret_cast<const floatx4 *>(a4);
+#pragma unroll
+                for (int s = 0; s < SPW; ++s) {
+                    const floatx4 av = av_next;
+                    if (s + 1 < SPW) av_next = *reinterpret_cast<const floatx4 *>(a4 + (s + 1) * STEP_K);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int g = 0; g < NG; ++g)
+                            acc[g] = __builtin_amdgcn_mfma_f32_4x4x1f32(av[i], w.b[s][g][i], acc[g], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (s == FINISH_AFTER && rg == 0 && rb > 0) {
+                        __syncthreads();                    // every wave has written its partial sums of block rb - 1
+                        finish(sm.red[(rb - 1) & 1], p_enode, p_ev, p_cl, p_cr, p_erow);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                // [wave][gate][row][hidden unit][k class]: the four class sums of an element lie side by side
+                float *nred = sm.red[(rb + rg) & 1];
+#pragma unroll
+                for (int g = 0; g < NG; ++g)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) nred[((((wave * NG + g) * 4 + v) * 16) + (nl & 15)) * 4 + (nl >> 4)] = acc[g][v];
+            }
+            hook(-2);
+            __syncthreads();
+            finish_narrow(sm.red[(rb + n_rg - 1) & 1], n_enode, n_ev, n_cl, n_cr, n_erow, n_bias);
+            __syncthreads();
+            return;
+        }
     }
     hook(-2);
     __syncthreads();

@@ -124,7 +124,7 @@ def test_whole_batch_reference_equals_the_checker_in_one_piece():
         assert np.abs(many[k] - one[k]).max() <= 1e-6 * max(np.abs(one[k]).max(), 1e-30), k
 
 
-@pytest.mark.parametrize("scheduler", ["level_device", "ready", "level_host"])
+@pytest.mark.parametrize("scheduler", ["level_device", "ready", "level_host", "dataflow"])
 def test_backward_from_kept_gate_activations(scheduler):
     """Training mode: the forward keeps every node's gate activations and the backward takes them instead of
     recomputing the contraction.  Same bar against the checker, for every forward data path (weight-stationary cell

@@ -126,9 +126,12 @@ def test_host_side_argument_checks():
 @pytest.mark.parametrize("name", ["sentence", "throughput", "treernn"])
 def test_results_do_not_depend_on_the_schedule(name, precision):
     """Every data path sums a node's contraction in the same order (four quarters of the K axis,
-    each in k order, added in quarter order), whatever rows share its tile.  So the three schedulers agree bit
+    each in k order, added in quarter order), whatever rows share its tile.  So the schedulers agree bit
     for bit with each other and from run to run, although the ready scheduler forms different tiles every time.
-    (Same recursion, different execution order, identical numbers: the claim of Section 5's numerical check.)"""
+    (Same recursion, different execution order, identical numbers: the claim of Section 5's numerical check.)
+    One exception: in fp32 the data-flow scheduler evaluates a piece's last block of up to 12 rows with the 4x4x1
+    matrix instruction, which sums every quarter as four interleaved chains; which nodes those are is fixed by the
+    batch, so it still repeats its own bits from run to run, and agrees with the others to rounding."""
     print("case determinism", name, precision, flush=True)
     w = synth.workload(name)
     outs = []
@@ -148,6 +151,11 @@ def test_results_do_not_depend_on_the_schedule(name, precision):
         finally:
             net.close()
     for sched, h, c in outs[1:]:
+        if sched == "dataflow" and precision == "f32":
+            np.testing.assert_allclose(h, outs[0][1], rtol=2e-5, atol=2e-6, err_msg="dataflow vs ready: h")
+            if c is not None:
+                np.testing.assert_allclose(c, outs[0][2], rtol=2e-5, atol=2e-6, err_msg="dataflow vs ready: c")
+            continue
         diff = int((h != outs[0][1]).sum())
         assert diff == 0, "%s vs ready: %d h elements differ, max %.3e" % (sched, diff, np.abs(h - outs[0][1]).max())
         assert c is None or np.array_equal(c, outs[0][2]), "%s vs ready: c differs" % sched

@@ -255,7 +255,7 @@ def test_hidden_sizes_between_the_register_layouts(sched):
 def test_wide_frontiers_at_a_hidden_size_with_uneven_slots():
     """H = 440: 28 column groups, so the 256 workgroups of the level scheduler form 9 slots and 4 stay idle; 100 trees give
     frontiers of several steps of those slots, whose remainders the scheduler leaves to the next frontier.  Every
-    node against the checker, all schedulers bit for bit."""
+    node against the checker, all schedulers bit for bit (the data-flow scheduler: to rounding)."""
     say("case wide frontiers, H=440")
     params = synth.make_treelstm_params(71, 400, 52, 440, "xavier")
     leaves = [int(v) for v in synth.Stream(71, "sizes").integers(5, 50, 100)]
@@ -269,7 +269,11 @@ def test_wide_frontiers_at_a_hidden_size_with_uneven_slots():
             check_against_oracle(params, trees, got, ref, "H=440/%s" % sched)
             if first is None:
                 first = got
-            assert np.array_equal(got["h"], first["h"]) and np.array_equal(got["c"], first["c"]), sched
+            if sched == "dataflow":      # narrow last blocks of its pieces sum in another order (fp32): equal to rounding
+                np.testing.assert_allclose(got["h"], first["h"], rtol=2e-5, atol=2e-6, err_msg=sched)
+                np.testing.assert_allclose(got["c"], first["c"], rtol=2e-5, atol=2e-6, err_msg=sched)
+            else:
+                assert np.array_equal(got["h"], first["h"]) and np.array_equal(got["c"], first["c"]), sched
             say("   ", sched, binding.tl_last_stats(net.ctx))
         finally:
             net.close()
