@@ -111,7 +111,12 @@ enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
  *                        used (TL_RNTN, hidden > 512, odd hidden in TL_F32, tl_forward_noalloc)
  *                        TL_SCHED_LEVEL_DEVICE stands in.  Unreachable nodes: TL_ESTRUCT.
  * Results do not depend on the scheduler: all paths of one precision sum a node's
- * contraction in the same order, so all of them agree bit for bit. */
+ * contraction in the same order, so all of them agree bit for bit and repeat their bits from
+ * run to run.  One exception: in TL_F32, TL_SCHED_DATAFLOW evaluates the dependent steps of few
+ * rows (the last block of up to 12 rows of each piece of its lists) with a narrower matrix
+ * instruction that rounds the same sum in another order; which nodes those are is fixed by the
+ * batch, so it repeats its own bits from run to run and agrees with the other schedulers to
+ * rounding (relative 2e-5 in the tests). */
 enum tl_scheduler { TL_SCHED_READY = 0, TL_SCHED_LEVEL_DEVICE = 1, TL_SCHED_LEVEL_HOST = 2, TL_SCHED_READY_PRIORITY = 3,
                     TL_SCHED_DATAFLOW = 4 };
 
