@@ -593,12 +593,16 @@ template <int NG, int S>
 __device__ inline void ws_load(WsWeightsBf<NG, S> &w, WsSmemBfT<S> &sm, const Gemm &gm, int cg, int wave, int lane)
 {
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(gm.wp) + ((size_t)cg * 4 * S + (size_t)wave * S) * NG * 64 + lane;
+    // the bias is requested first: its way into LDS then waits for nothing but itself (loads return in order)
+    const int t = wave * 64 + lane;
+    float bias = 0.f;
+    if (t < NG * HU) bias = gm.bp[cg * NG * HU + t];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s = 0; s < S; ++s)
 #pragma unroll
         for (int g = 0; g < NG; ++g) w.b[s][g] = wp[(size_t)(s * NG + g) * 64];
-    const int t = wave * 64 + lane;
-    if (t < NG * HU) sm.bias[t] = gm.bp[cg * NG * HU + t];
+    if (t < NG * HU) sm.bias[t] = bias;
 }
 
 template <int EPI, bool COH, int S, bool FLOW = false, typename Hook = WsNoHook>

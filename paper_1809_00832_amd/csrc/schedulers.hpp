@@ -540,21 +540,31 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     const int n_slots = gridDim.x / f.n_cg;
     const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;
     const int my_cg = member;
-    PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;
-    if constexpr (BF16) ws_load(w, sm, f.inner, my_cg, tid >> 6, tid & 63);
-    else ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+    PersistentWeights<EpiTraits<EPI>::NG, SPW, BF16> w;        // (loaded below, behind the first requests of the scan)
 
-    // the slot's trees: [t_lo, t_hi), cut where the node count passes slot / n_slots of the batch
-    auto first_tree_at = [&](int s) {
-        const long long bound = ((long long)s * f.n_nodes + n_slots - 1) / n_slots;
-        int lo = 0, hi = f.n_trees;                   // smallest t with tree_off[t] >= bound; tree_off[n_trees] = n_nodes
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (f.tree_off[mid] >= bound) hi = mid; else lo = mid + 1;
+    // the slot's trees: [t_lo, t_hi), cut where the node count passes slot / n_slots of the batch.  Both cuts are
+    // looked for at once, lanes 0-31 of every wave for this slot's and lanes 32-63 for the next one's, 32 candidates per
+    // round trip (a bisection is one dependent load per halving).
+    int t_lo, t_hi;
+    {
+        const int lane = tid & 63, half = lane >> 5, i = lane & 31;
+        const long long bound = ((long long)(slot + half) * f.n_nodes + n_slots - 1) / n_slots;
+        int lo = 0, hi = f.n_trees;                   // smallest t with tree_off[t] >= bound is in [lo, hi]; tree_off[n_trees] = n_nodes >= bound
+        while (__ballot(lo < hi) != 0ull) {
+            const int step = (hi - lo + 30) / 31;     // candidates lo, lo + step, ..., the last one clamped to hi
+            const int cand = min(lo + i * step, hi);
+            const bool ge = cand >= hi || f.tree_off[cand] >= bound;                    // (at hi it holds by the invariant)
+            const unsigned long long m = __ballot(ge) >> (32 * half) & 0xFFFFFFFFull;   // never empty: the last candidate is hi
+            const int k = __builtin_ctzll(m);         // first candidate at or above the cut
+            if (lo < hi) {
+                const int new_hi = min(lo + k * step, hi);
+                lo = k == 0 ? lo : min(lo + (k - 1) * step, hi) + 1;                    // (k == 0: the cut is lo itself)
+                hi = new_hi;
+            }
         }
-        return lo;
-    };
-    const int t_lo = first_tree_at(slot), t_hi = first_tree_at(slot + 1);
+        t_lo = __builtin_amdgcn_readlane(lo, 0);      // (scalar values, like everything derived from them)
+        t_hi = __builtin_amdgcn_readlane(lo, 32);
+    }
     const int nb = f.tree_off[t_lo], ne = f.tree_off[t_hi];
     const int slot_internal = ((ne - nb) - (t_hi - t_lo)) / 2;      // full binary trees
     if (ne <= nb) return;
@@ -566,38 +576,65 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
         sm.cmd[7] = 0;                                // a wait was abandoned
     }
     __syncthreads();
-    for (int n = nb + tid; n < ne; n += WG_THREADS) seen[n] = 0u;
     // the list starts with the slot's nodes over two leaves, in node order.  The same pass over the slot's nodes counts
     // the roots (nodes without a parent): there must be one per tree (a second one in a tree is caught where the roots
-    // are copied out, after the last piece).
-    int n_listed = 0, n_roots = 0;
-    for (int base = nb; base < ne; base += WG_THREADS) {
-        const int n = base + tid;
-        int l = -1, r = -1, up = 0;
-        bool seed = false;
-        if (n < ne) {
-            l = f.left[n];
-            r = f.right[n];
-            up = f.parent[n];
-            seed = l >= 0 && f.pending[n] == 0;
+    // are copied out, after the last piece).  A thread looks at four consecutive nodes per round, all their loads in
+    // flight together: a round costs a memory round trip and two barriers however many nodes it covers.
+    constexpr int SCAN_Q = 4;
+    int l[SCAN_Q], r[SCAN_Q], up[SCAN_Q], pend[SCAN_Q];
+    auto scan_requests = [&](int base) {
+#pragma unroll
+        for (int j = 0; j < SCAN_Q; ++j) {
+            const int n = min(base + tid * SCAN_Q + j, ne - 1);       // (ne > nb here)
+            l[j] = f.left[n];
+            r[j] = f.right[n];
+            up[j] = f.parent[n];
+            pend[j] = f.pending[n];
         }
-        if (f.flow_roots) {
-            const bool is_root = n < ne && up < 0;
-            n_roots += __popcll(__ballot(is_root));           // (every wave counts its own; added up below)
-            if (is_root) {
-                const int at = atomicAdd(&sm.cmd[6], 1);
-                if (at < FLOW_ROOTS_KEPT) sm.roots[at] = n;
+    };
+    // The first round's requests go out in front of the weights' (a wave's loads return in order): the scan of a slot
+    // of up to 1 024 nodes then runs while the weights arrive, instead of behind them.
+    scan_requests(nb);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (BF16) ws_load(w, sm, f.inner, my_cg, tid >> 6, tid & 63);
+    else ws_load(w, f.inner, my_cg, tid >> 6, tid & 63);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int n = nb + tid; n < ne; n += WG_THREADS) seen[n] = 0u;
+    int n_listed = 0, n_roots = 0;
+    for (int base = nb; base < ne; base += WG_THREADS * SCAN_Q) {
+        const int n0 = base + tid * SCAN_Q;
+        if (base != nb) scan_requests(base);
+        unsigned seeds = 0u;
+        const unsigned long long below = (1ull << (tid & 63)) - 1ull;
+        int before = 0, in_wave = 0;                  // seeds of lower lanes of this wave, and of the whole wave
+#pragma unroll
+        for (int j = 0; j < SCAN_Q; ++j) {
+            const bool here = n0 + j < ne;
+            const bool seed = here && l[j] >= 0 && pend[j] == 0;
+            const unsigned long long mask = __ballot(seed);
+            before += __popcll(mask & below);
+            in_wave += __popcll(mask);
+            seeds |= (seed ? 1u : 0u) << j;
+            if (f.flow_roots) {
+                const bool is_root = here && up[j] < 0;
+                n_roots += __popcll(__ballot(is_root));       // (every wave counts its own; added up below)
+                if (is_root) {
+                    const int at = atomicAdd(&sm.cmd[6], 1);
+                    if (at < FLOW_ROOTS_KEPT) sm.roots[at] = n0 + j;
+                }
             }
         }
-        const unsigned long long mask = __ballot(seed);
         __syncthreads();                              // (the counts of the previous round have been read)
-        if ((tid & 63) == 0) sm.cmd[tid >> 6] = __popcll(mask);
+        if ((tid & 63) == 0) sm.cmd[tid >> 6] = in_wave;
         __syncthreads();
-        int at = n_listed;
+        int at = n_listed + before;
         for (int wv = 0; wv < (tid >> 6); ++wv) at += sm.cmd[wv];
-        if (seed) {
-            const int pos = at + __popcll(mask & ((1ull << (tid & 63)) - 1ull));
-            if (pos < slot_internal) list[pos] = int4{n, l, r, up};
+#pragma unroll
+        for (int j = 0; j < SCAN_Q; ++j) {
+            if (seeds >> j & 1u) {
+                if (at < slot_internal) list[at] = int4{n0 + j, l[j], r[j], up[j]};
+                at += 1;
+            }
         }
         n_listed += sm.cmd[0] + sm.cmd[1] + sm.cmd[2] + sm.cmd[3];
     }
