@@ -108,11 +108,31 @@ def time_graph_replays(net, steps):
     return (time.perf_counter() - t0) / steps
 
 
+PREHEAT_MS = 40.0
+
+
+def preheat(net, ms):
+    """Forwards of the same batch until the device has been busy for `ms` milliseconds, before the warm-up steps: a GPU
+    that has been idle runs its first few milliseconds of work at a lower clock (measured: the first ten forwards of a
+    process take up to 15 % longer), and a timed region of a few milliseconds would report that ramp instead of the
+    sustained rate.  Not part of the warm-up or the timed steps; the figure is reported in the JSON line."""
+    import torch
+    if ms <= 0:
+        return
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(8):
+            net.forward()
+        torch.cuda.synchronize()
+
+
 def run_scheduler(w, sched, precision, steps, warmup, graph=False):
     from paper_1809_00832_amd import binding
     net = binding.TreeNet(w.params, scheduler=sched, precision=precision)
     try:
         net.load(w.trees)
+        preheat(net, PREHEAT_MS)
         for _ in range(warmup):
             net.forward()
         code = binding.tl_status(net.ctx)
@@ -403,6 +423,8 @@ def main():
     ap.add_argument("--no-compare", action="store_true", help="skip the other two schedulers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads / precisions")
+    ap.add_argument("--preheat-ms", type=float, default=PREHEAT_MS,
+                    help="milliseconds of untimed forwards before the warm-up steps, so that the device has left its idle clock state (0: none)")
     ap.add_argument("--head", type=int, default=5, help="classes of the per-node classifier head timed as an extra stage (0: skip)")
     ap.add_argument("--backward", action="store_true", help="also time tl_backward on the same batch (TreeLSTM, fp32)")
     ap.add_argument("--length-sweep", action="store_true",
@@ -414,6 +436,7 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of known size (reference reading for the HBM byte counters)")
     args = ap.parse_args()
+    globals()["PREHEAT_MS"] = args.preheat_ms
     if args.gpus != 1:
         sys.exit("bench.py: the forward pass is evaluated on ONE GPU only (trees are independent: a batch shards by tree, "
                  "with no exchange between GPUs); run with --gpus 1")
@@ -454,7 +477,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": args.precision, "data": "synthetic",
+        "dtype": args.precision, "data": "synthetic", "preheat_ms": args.preheat_ms,
         "config": {"workload": args.workload, "scheduler": args.scheduler, "trees": t.n_trees, "nodes": t.n_nodes,
                    "leaves": t.n_leaves, "hidden": w.params.hidden, "embed_dim": w.params.embed_dim,
                    "vocab": w.params.vocab},
