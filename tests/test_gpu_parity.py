@@ -434,3 +434,60 @@ def test_two_contexts_on_two_streams_ordered_by_events(sched):
     finally:
         a.close()
         b.close()
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_dataflow_on_many_batch_shapes(precision):
+    """The data-flow scheduler cuts its private lists into pieces whose composition depends on the shapes of the trees,
+    their number and the hidden size (slots per device, rows per slot, narrow last blocks).  Thirty seeded batches that
+    vary all of these - single-node trees, chains, balanced and random trees, one tree or hundreds, nodes renumbered
+    inside their trees - against the level scheduler on the same batch: identical bits with bf16 operands and in every
+    run of its own, equal to rounding in fp32 (narrow blocks sum in another order); a sample against the checker."""
+    import torch
+    prec = binding.TL_F32 if precision == "f32" else binding.TL_BF16_IN
+    pick = synth.Stream(977, "batch shapes")
+    hiddens = [16, 40, 64, 150, 256, 512] if precision == "f32" else [64, 256, 512]
+    for case in range(30):
+        H = hiddens[case % len(hiddens)]
+        E = [20, 52, 300][case % 3]
+        B = int(pick.integers(1, [3, 40, 300][case % 3], 1)[0])
+        kind = ["random", "chain", "balanced", "mixed"][case % 4]
+        hi = [2, 12, 70][(case // 2) % 3] if kind != "chain" else 40
+        leaves = [int(v) for v in pick.integers(1, hi, B)]
+        shapes = [kind if kind != "mixed" else ["random", "chain", "balanced"][int(v)] for v in pick.integers(0, 2, B)]
+        trees = synth.make_trees(2000 + case, leaves, shapes, 300)
+        if case % 5 == 4:
+            trees, _ = synth.renumber(trees, "random", seed=case)
+        elif case % 5 == 2:
+            trees, _ = synth.renumber(trees, "post")
+        params = synth.make_treelstm_params(3000 + case, 300, E, H, "xavier")
+        say("case shapes", precision, case, "H", H, "E", E, "trees", B, kind, "nodes", trees.n_nodes)
+        outs = {}
+        for sched in ("level_device", "dataflow"):
+            net = binding.TreeNet(params, scheduler=sched, precision=prec)
+            try:
+                outs[sched] = net.run(trees)
+                if sched == "dataflow":
+                    for _ in range(2):
+                        net.batch["h"].fill_(float("nan"))
+                        net.batch["c"].fill_(float("nan"))
+                        net.forward()
+                        assert binding.tl_status(net.ctx) == 0
+                        assert np.array_equal(net.batch["h"].cpu().numpy(), outs[sched]["h"]), "run-to-run bits, case %d" % case
+            finally:
+                net.close()
+        a, b = outs["dataflow"], outs["level_device"]
+        assert np.array_equal(a["root"], b["root"])
+        for key in ("h", "c", "h_root", "c_root"):
+            if precision == "bf16":
+                assert np.array_equal(a[key], b[key]), "case %d %s" % (case, key)
+            else:
+                np.testing.assert_allclose(a[key], b[key], rtol=2e-5, atol=2e-6, err_msg="case %d %s" % (case, key))
+        if case % 6 == 0:
+            what = "shapes case %d / dataflow / %s" % (case, precision)
+            if precision == "f32":
+                check_against_oracle(params, trees, a, None, what)
+            else:
+                ref = oracle.forward_params(round_params_bf16(params), trees, n_threads=8, round_bf16=True)
+                assert_close_bf16(a["h"], ref["h"], what + " h")
+                assert_close_bf16(a["c"], ref["c"], what + " c")
