@@ -228,7 +228,7 @@ def backward_stage(w, n_classes, reps=10):
     recomputes the head's forward), tree backward, back to back on one stream."""
     import torch
     from paper_1809_00832_amd import binding
-    net = binding.TreeNet(w.params, scheduler="level_device")
+    net = binding.TreeNet(w.params, scheduler=DEFAULT_SCHEDULER)
     try:
         b = net.load(w.trees)
         net.forward()
