@@ -337,9 +337,10 @@ def topdown_bench(steps, warmup, with_cpu):
 
 
 def other_configs(steps, warmup):
-    """The evaluation workloads other than the headline one, a few steps each: ms per step, trees/s, nodes/s and the
+    """The evaluation workloads other than the headline one, a few steps each: ms per step, trees/s, nodes/s, the
     internal-node kernel's fraction of the matrix peak of its precision (algorithmic flops over its mean duration from
-    the library's stage events), for the default scheduler; on `sentence`, `throughput` and `stress` also for the
+    the library's stage events) and the step's algorithmic bytes per second (the small and the TreeRNN workloads are
+    bound by latency and memory, not by the matrix units), for the default scheduler; on `sentence`, `throughput` and `stress` also for the
     ready-queue scheduler and the two level-wise ones (Section 4.1 against the depth-wise batching of Section 6.3)."""
     from paper_1809_00832_amd import binding, synth
     rows = []
@@ -348,7 +349,7 @@ def other_configs(steps, warmup):
     for name, dtype in cases:
         w = synth.workload(name)
         t = w.trees
-        f_int, f_leaf, _ = algorithmic_work(w)
+        f_int, f_leaf, alg_bytes = algorithmic_work(w)
         prec = binding.TL_F32 if dtype == "f32" else binding.TL_BF16_IN
         heavy = name == "stress"
         k, wu = (min(steps, 5), min(warmup, 2)) if heavy else (min(steps, 20), min(warmup, 5))
@@ -362,7 +363,9 @@ def other_configs(steps, warmup):
             row["schedulers"][sched] = {
                 "ms_per_step": r["sec"] * 1e3, "trees_per_sec": t.n_trees / r["sec"], "nodes_per_sec": t.n_nodes / r["sec"],
                 "internal_ms": kernel_ms, "internal_frac_mfma_peak": f_int / (kernel_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
-                "step_frac_mfma_peak": (f_int + f_leaf) / r["sec"] / 1e12 / PEAK_TFLOPS[dtype], "stage_ms": r["stage_ms"]}
+                "step_frac_mfma_peak": (f_int + f_leaf) / r["sec"] / 1e12 / PEAK_TFLOPS[dtype],
+                "step_algorithmic_gbs": alg_bytes / r["sec"] / 1e9, "step_frac_hbm_peak": alg_bytes / r["sec"] / 1e9 / HBM_GBS,
+                "stage_ms": r["stage_ms"]}
         rows.append(row)
     return rows
 
