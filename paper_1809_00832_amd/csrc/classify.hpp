@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void k_head_weight_grad(const float *__restric
             s_g[r][c] = (r < nr && c < C) ? d_logits[(size_t)(r0 + r) * C + c] : 0.f;
         }
         __syncthreads();
-        if (blockIdx.x == 0 && threadIdx.x < C)
+        if (blockIdx.x == 0 && (int)threadIdx.x < C)
             for (int r = 0; r < nr; ++r) bsum += s_g[r][threadIdx.x];
         if (mine) {
             const int w0 = wave * HW_ROWS;
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(256) void k_head_weight_grad(const float *__restric
         for (int c = 0; c < CT; ++c)
             if (c < C) atomicAdd(&d_w_s[(size_t)k * C + c], (acc[c] + s_red[0][c][lane]) + (s_red[1][c][lane] + s_red[2][c][lane]));
     }
-    if (blockIdx.x == 0 && threadIdx.x < C) atomicAdd(&d_b_s[threadIdx.x], bsum);
+    if (blockIdx.x == 0 && (int)threadIdx.x < C) atomicAdd(&d_b_s[threadIdx.x], bsum);
 }
 
 }  // namespace tl

@@ -931,7 +931,6 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
-    Ctl *ctl = f.ctl;
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     const int n_compute = f.n_gangs * f.gang_size;
