@@ -134,7 +134,8 @@ template <int SEG, int SPW, typename T = float, bool TAIL = false> struct WsRowR
         const int k = 4 * EPL * SPW * wave + (lane % G::LPR) * EPL;   // position on the padded K axis
         const int seg = (SEG == 2 && k >= Lp) ? 1 : 0;
         const int o = min(k - seg * Lp, (stride - EPL + 3) & ~3);
-        src = seg ? sm.src1 : sm.src0;
+        if constexpr (SEG == 2) src = seg ? sm.src1 : sm.src0;
+        else src = sm.src0;
         lane_off = (unsigned)o * (unsigned)sizeof(T);
         row_bytes = (unsigned)stride * (unsigned)sizeof(T);
         const bool tail = TAIL && o + EPL > stride;
@@ -566,17 +567,23 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
 // to nearest even) is the same as converting at gather time.
 constexpr int WSB_MAX_S = 8;
 
-template <int S> struct WsSmemBfT {
-    static constexpr int A_LD = 32 * S + 8;                // LDS row stride of a wave's A block, bf16 elements
-    unsigned short a[4][16 * A_LD];
-    float red[2][WS_RED_FLOATS];
-    int node[WS_TABLE_ROWS];
-    int src0[WS_TABLE_ROWS];
+// What only cells of internal nodes need in LDS: the second source of a row, and the data-flow scheduler's tables (see
+// WsSmemT).  The leaf kernel, which is bound by the latency of a block's phases and gains from every further resident
+// workgroup, does without them and with reduction buffers for its three gates: four workgroups fit on a CU.
+template <bool INNER_TABLES> struct WsFlowTables {
     int src1[WS_TABLE_ROWS];
     int par[WS_TABLE_ROWS];
     int nxt[4][FLOW_NXT_ROWS];
     int roots[FLOW_ROOTS_KEPT];
-    float bias[MAX_GATES * HU];        // the column group's bias (ws_load puts it here: a load of it from memory after the barrier would
+};
+template <> struct WsFlowTables<false> {};
+template <int S, int NGM = MAX_GATES, bool FLOW_TABLES = true> struct WsSmemBfT : WsFlowTables<FLOW_TABLES> {
+    static constexpr int A_LD = 32 * S + 8;                // LDS row stride of a wave's A block, bf16 elements
+    unsigned short a[4][16 * A_LD];
+    float red[2][4 * NGM * 4 * 64];    // K-split partial sums, alternating per block: [wave][gate][v][lane]
+    int node[WS_TABLE_ROWS];
+    int src0[WS_TABLE_ROWS];
+    float bias[NGM * HU];              // the column group's bias (ws_load puts it here: a load of it from memory after the barrier would
                                        // have to wait for the row requests issued before it, and registers are short in this form)
     int cmd[8];
 };
@@ -589,8 +596,8 @@ template <int NG> struct WsWeightsBf<NG, 0> {};
 // k-steps (of 32) [wave*S, (wave+1)*S) of column group cg; the packed matrix has exactly 4*S of them.
 // Called by all threads of the workgroup; a barrier must be passed before the first ws_tile (its own first barrier
 // comes before the bias is read).
-template <int NG, int S>
-__device__ inline void ws_load(WsWeightsBf<NG, S> &w, WsSmemBfT<S> &sm, const Gemm &gm, int cg, int wave, int lane)
+template <int NG, int S, int NGM, bool FT>
+__device__ inline void ws_load(WsWeightsBf<NG, S> &w, WsSmemBfT<S, NGM, FT> &sm, const Gemm &gm, int cg, int wave, int lane)
 {
     const bf16x8 *wp = reinterpret_cast<const bf16x8 *>(gm.wp) + ((size_t)cg * 4 * S + (size_t)wave * S) * NG * 64 + lane;
     // the bias is requested first: its way into LDS then waits for nothing but itself (loads return in order)
@@ -605,12 +612,13 @@ __device__ inline void ws_load(WsWeightsBf<NG, S> &w, WsSmemBfT<S> &sm, const Ge
     if (t < NG * HU) sm.bias[t] = bias;
 }
 
-template <int EPI, bool COH, int S, bool FLOW = false, typename Hook = WsNoHook>
-__device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
+template <int EPI, bool COH, int S, bool FLOW = false, typename Hook = WsNoHook, int NGM = MAX_GATES, bool FT = true>
+__device__ inline void ws_tile(WsSmemBfT<S, NGM, FT> &sm, const Fwd &f, const Gemm &gm, const unsigned short *__restrict__ table,
                                int table_rows, int stride, int count, int cg, const WsWeightsBf<EpiTraits<EPI>::NG, S> &w,
                                Hook hook = Hook())
 {
     constexpr int NG = EpiTraits<EPI>::NG;
+    static_assert(NG <= NGM, "reduction buffers and bias of the LDS layout are sized for NGM gates");
     constexpr int SEG = EpiTraits<EPI>::SEG;
     using G = WsLoadGeom<S>;
     constexpr int NL = G::NL;
@@ -619,7 +627,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
     const int H = f.H;
     const int hu = cg * HU + (lane & 15);
     const bool hu_ok = hu < H;
-    const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
+    const unsigned short *a_lane = &sm.a[wave][(lane & 15) * WsSmemBfT<S, NGM, FT>::A_LD + (lane >> 4) * 8];   // + 32 s: operand of k-step s
     // h, c and the bf16 copy of h as raw buffers (the caller guarantees that they are smaller than 4 GiB)
     const __amdgpu_buffer_rsrc_t rs_h = buf_of(f.h, (unsigned long long)f.n_nodes * H * 4), rs_c = buf_of(f.c, (unsigned long long)f.n_nodes * H * 4),
                                  rs_hb = buf_of(f.hb, (unsigned long long)f.n_nodes * f.hs * 2);
@@ -643,7 +651,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
 #pragma unroll
             for (int j = 0; j < NL; ++j) {
                 const int r = j * G::RPL + sub;
-                if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WsSmemBfT<S>::A_LD + kk]) = rows[j];
+                if (sub < G::RPL && r < 16) *reinterpret_cast<floatx4 *>(&sm.a[wave][r * WsSmemBfT<S, NGM, FT>::A_LD + kk]) = rows[j];
             }
         }
         req.prepare((rb + 1) * 16);
@@ -653,7 +661,7 @@ __device__ inline void ws_tile(WsSmemBfT<S> &sm, const Fwd &f, const Gemm &gm, c
         const bool ev = enode >= 0 && hu_ok;
         // c operands of the row this lane finishes: requested before the MFMAs, used after them
         float cl = 0.f, cr = 0.f;
-        if (EPI == EPI_LSTM_INNER) {
+        if constexpr (EPI == EPI_LSTM_INNER) {
             cl = buf_ld_f<COH>(rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
             cr = buf_ld_f<COH>(rs_c, (unsigned)sm.src1[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b);
         }

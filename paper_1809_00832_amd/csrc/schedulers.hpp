@@ -75,11 +75,14 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws(Fwd f)
 
 // The same with bf16 operands: rows come from a bf16 copy of the embedding table (rows padded with
 // zeros to a multiple of 8 elements).
+// (Four workgroups per CU: the matrix instructions of a block of leaves take 0.1 us, the block's phases - rows, park,
+// barrier, gates - 1.2 us.)
+template <int S> using LeafSmemBf = WsSmemBfT<S, EpiTraits<EPI_LSTM_LEAF>::NG, false>;
 template <int S>
-__global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
+__global__ __launch_bounds__(WG_THREADS, 4) void k_leaf_ws_bf(Fwd f)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    WsSmemBfT<S> &sm = *reinterpret_cast<WsSmemBfT<S> *>(smem_raw);
+    LeafSmemBf<S> &sm = *reinterpret_cast<LeafSmemBf<S> *>(smem_raw);
     if (batch_rejected(f)) return;
     const int tid = threadIdx.x;
     if (f.flow == 2) flow_fill(f, (size_t)blockIdx.x * 4 + (tid >> 6), (size_t)gridDim.x * 4);
@@ -94,7 +97,6 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_leaf_ws_bf(Fwd f)
         const int node = tid < count ? f.leaf_list[piece + tid] : -1;
         sm.node[tid] = node;
         sm.src0[tid] = node >= 0 ? f.word[node] : 0;
-        sm.src1[tid] = 0;
         __syncthreads();
         ws_tile<EPI_LSTM_LEAF, false, S>(sm, f, f.leaf, f.embb, f.vocab, f.es, count, cg, w);
     }

@@ -241,6 +241,8 @@ fwd_kernel leaf_ws_bf_kernel(int s)
     }
 }
 // LDS bytes of the weight-stationary kernels
+// LDS of the leaf kernel: the bf16 form has a leaner layout of its own (three gates, no scheduler tables)
+size_t leaf_lds_bytes(int spw, bool bf16);
 size_t ws_lds_bytes(int spw, bool bf16)
 {
     if (bf16) {
@@ -260,6 +262,18 @@ size_t ws_lds_bytes(int spw, bool bf16)
     case 5: return sizeof(WsSmemT<5>);
     case 8: return sizeof(WsSmemT<8>);
     default: return sizeof(WsSmemT<16>);
+    }
+}
+size_t leaf_lds_bytes(int spw, bool bf16)
+{
+    if (!bf16) return ws_lds_bytes(spw, false);
+    switch (spw) {
+    case 1: return sizeof(LeafSmemBf<1>);
+    case 2: return sizeof(LeafSmemBf<2>);
+    case 3: return sizeof(LeafSmemBf<3>);
+    case 4: return sizeof(LeafSmemBf<4>);
+    case 6: return sizeof(LeafSmemBf<6>);
+    default: return sizeof(LeafSmemBf<8>);
     }
 }
 template <bool BF16> tiles_kernel static_kernel_p(int epi, bool vec4)
@@ -710,12 +724,13 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     }
 
     if (ctx->spw_leaf > 0) {
-        const size_t lds = ws_lds_bytes(ctx->spw_leaf, bf16);
+        const size_t lds = leaf_lds_bytes(ctx->spw_leaf, bf16);
         const fwd_kernel lk = bf16 ? leaf_ws_bf_kernel(ctx->spw_leaf) : leaf_ws_kernel(ctx->spw_leaf);
         if ((rc = allow_lds(lk, lds)) != TL_OK) return rc;
         int o = 0;
         TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(lk), WG_THREADS, lds));
-        if (o > 2) o = 2;
+        const int o_max = bf16 ? 4 : 2;      // fp32: bound by its instruction stream, a third workgroup brings nothing; bf16: by latency
+        if (o > o_max) o = o_max;
         ctx->leaf_grid = o * ctx->n_cu / ctx->n_cg * ctx->n_cg;
         if (ctx->leaf_grid < ctx->n_cg) ctx->spw_leaf = 0;
     }
@@ -940,7 +955,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     // ---- leaves ------------------------------------------------------------------------
     if (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0 && ws_range) {          // (its cell addresses h and c with 32-bit offsets)
         hipLaunchKernelGGL(bf16 ? leaf_ws_bf_kernel(ctx->spw_leaf) : leaf_ws_kernel(ctx->spw_leaf), dim3(ctx->leaf_grid),
-                           dim3(WG_THREADS), ws_lds_bytes(ctx->spw_leaf, bf16), st, f);
+                           dim3(WG_THREADS), leaf_lds_bytes(ctx->spw_leaf, bf16), st, f);
     } else if (cfg.cell == TL_TREELSTM) {
         const LevelPlan plan = plan_level(f.n_leaf, f.cap_tiles);
         hipLaunchKernelGGL(static_kernel(EPI_LSTM_LEAF, vec4_leaf, bf16), dim3(plan.n_tiles * ctx->n_cg), dim3(WG_THREADS),
