@@ -204,7 +204,7 @@ def length_sweep(steps, warmup):
         for leaves in (2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
             trees = synth.make_trees(100 + leaves, [leaves], [shape], base.params.vocab)
             row = {"shape": shape, "leaves": leaves, "height": int(heights_of(trees).max())}
-            for sched in ("level_device", "ready"):
+            for sched in ("dataflow", "level_device", "ready"):
                 net = binding.TreeNet(base.params, scheduler=sched)
                 try:
                     net.load(trees)

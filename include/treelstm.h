@@ -109,7 +109,14 @@ enum tl_precision { TL_F32 = 0, TL_BF16_IN = 1 };
  *                        embeddings hold NaNs whose bits are all ones, a forward ends with
  *                        TL_ESTALL instead of NaN results.  Where the weight-stationary cell is not
  *                        used (TL_RNTN, hidden > 512, odd hidden in TL_F32, tl_forward_noalloc)
- *                        TL_SCHED_LEVEL_DEVICE stands in.  Unreachable nodes: TL_ESTRUCT.
+ *                        TL_SCHED_LEVEL_DEVICE stands in.  Whole trees are dealt to the sets, so a
+ *                        batch of fewer trees than the device has sets leaves sets idle; if its trees
+ *                        have 256 nodes or more on average, both this kernel and that of
+ *                        TL_SCHED_LEVEL_DEVICE are launched and the device picks one by the width of
+ *                        the first frontier (more than 16 ready nodes per tree: bushy trees, level by
+ *                        level on all sets; otherwise deep narrow ones, data-flow).  A batch in which
+ *                        one large bushy tree stands beside many small ones is better served by
+ *                        TL_SCHED_LEVEL_DEVICE.  Unreachable nodes: TL_ESTRUCT.
  * Results do not depend on the scheduler: all paths of one precision sum a node's
  * contraction in the same order, so all of them agree bit for bit and repeat their bits from
  * run to run.  One exception: in TL_F32, TL_SCHED_DATAFLOW evaluates the dependent steps of few

@@ -144,6 +144,7 @@ struct Fwd {
     int4 *flow_list;
     int flow_roots;                   // data-flow scheduler: roots are found and their states copied out by the cell kernels (no separate passes)
     int flow;                         // data-flow scheduler: who fills the rows of internal nodes with the "not written" pattern: 1 the reset kernel, 2 the leaf kernel
+    int pick;                         // batch of few large trees, both internal-node kernels launched: 1 this one runs if the trees are narrow, 2 if they are not (see internal_kernel_skipped)
 };
 
 // ---- device-scope accesses -------------------------------------------------------------
@@ -259,6 +260,20 @@ __device__ inline bool batch_rejected(const Fwd &f)
 }
 
 __device__ inline void backoff() { __builtin_amdgcn_s_sleep(2); }
+
+// A batch of fewer trees than the device has sets of workgroups, of large trees: the data-flow scheduler keeps a tree on
+// one set, which is the faster way if the trees are deep and narrow (a step costs a round trip, not a barrier) and
+// the slower one by the number of idle sets if they are bushy.  The host does not know the shapes; the structure pass
+// does: the internal nodes over two leaves are the first frontier, and if that has no more than 16 rows per tree a
+// tree's ready nodes fit the blocks of one set anyway.  Both kernels are launched and every workgroup takes the same
+// decision from that count (n_seed, final since the root pass).
+constexpr int FLOW_NARROW_SEEDS_PER_TREE = 16;
+__device__ inline bool internal_kernel_skipped(const Fwd &f)
+{
+    if (f.pick == 0) return false;
+    const bool narrow = (long long)f.ctl->n_seed <= (long long)FLOW_NARROW_SEEDS_PER_TREE * f.n_trees;
+    return f.pick == 1 ? !narrow : narrow;
+}
 
 // Rows per tile when `avail` ready rows meet room for `free_tiles` more tiles: spread the rows
 // over the free room in units of 16, at most TILE_ROWS.

@@ -269,7 +269,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
-    if (batch_rejected(f)) return;
+    if (batch_rejected(f) || internal_kernel_skipped(f)) return;
     const int tid = threadIdx.x;
     // A slot is a set of workgroups that covers all column groups; the workgroups of a slot gather the same child rows.
     // (Putting every slot on one L2 domain, so that its rows cross the fabric once instead of once per domain that
@@ -537,7 +537,7 @@ __global__ __launch_bounds__(WG_THREADS, BF16 ? 2 : 1) void k_flow_persistent(Fw
     using Smem = PersistentSmem<SPW, BF16>;
     Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
     Ctl *ctl = f.ctl;
-    if (batch_rejected(f)) return;
+    if (batch_rejected(f) || internal_kernel_skipped(f)) return;
     const int tid = threadIdx.x;
     const int n_slots = gridDim.x / f.n_cg;
     const int member = blockIdx.x % f.n_cg, slot = blockIdx.x / f.n_cg;

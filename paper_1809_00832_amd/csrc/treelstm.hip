@@ -23,6 +23,7 @@ using namespace tl;
 namespace {
 
 constexpr int DEFAULT_SPIN_LIMIT = 1 << 20;
+constexpr int FLOW_LARGE_TREE_NODES = 256;      // mean nodes per tree from which a batch of fewer trees than sets of workgroups has the device pick its kernel
 
 struct DevBuf {
     void *p = nullptr;
@@ -870,8 +871,16 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     const int spw = ((bf16 || pair_inner) && ws_range) ? ctx->spw : 0;     // weight-stationary cell in the persistent kernels
     const bool persistent = cfg.scheduler != TL_SCHED_LEVEL_HOST;
     // the data-flow scheduler needs the weight-stationary cell and its private lists; without them (RNTN, sizes the
-    // cell does not take, the fixed workspace) the level scheduler on the device stands in
+    // cell does not take, the fixed workspace) the level scheduler on the device stands in.
     const bool flow = cfg.scheduler == TL_SCHED_DATAFLOW && spw > 0 && !static_ws && ctx->flow_ws != nullptr;
+    // A batch of few large trees: the data-flow scheduler deals whole trees to its sets of workgroups, so with fewer
+    // trees than sets the others stay idle: one bushy tree of 16 384 leaves takes 3.5 ms on one set against 0.34 ms
+    // level by level on all of them, while a deep chain of 2 048 leaves takes 6.4 ms data-flow and 11.8 ms level by
+    // level.  The host does not know the shapes, so both kernels are launched and the device picks
+    // (internal_kernel_skipped: by the width of the first frontier).  Small trees - a sentence, say - are left with
+    // the data-flow kernel alone: one set holds all that is ready of such a tree.
+    const int flow_sets = ctx->n_cg > 0 ? ctx->ws_grid / ctx->n_cg : 0;
+    const bool flow_or_levels = flow && n_trees < flow_sets && n_nodes / (n_trees > 0 ? n_trees : 1) >= FLOW_LARGE_TREE_NODES;
     if (persistent && spw > 0 && bf16) {
         f.hb = static_ws ? reinterpret_cast<unsigned short *>(ctx->scratch + NOALLOC_WS_BYTES) : ctx->hb;
         f.hs = ctx->hs;
@@ -891,6 +900,15 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
         if (per_cu * ctx->n_cu < grid_p) grid_p = per_cu * ctx->n_cu;
         if (grid_p < (spw > 0 ? ctx->n_cg : 1) + (ready_sched ? 1 : 0)) return TL_EHIP;
     }
+    int grid_l2 = 0;                                  // grid of the level kernel where it is launched beside the data-flow kernel
+    if (flow_or_levels) {
+        int per_cu = 0;
+        if ((rc = resident_per_cu(ctx, levels_kernel(cfg.cell, vec4_inner, spw, bf16), kern_lds, &per_cu)) != TL_OK) return rc;
+        grid_l2 = ctx->ws_grid;
+        if (per_cu * ctx->n_cu < grid_l2) grid_l2 = per_cu * ctx->n_cu;
+        grid_l2 = grid_l2 / ctx->n_cg * ctx->n_cg;
+        if (grid_l2 < ctx->n_cg) return TL_EHIP;
+    }
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
     // RNTN: a frontier of at most rntn_units tiles is cut into RNTN_PARTS workgroups per tile and column group
     f.rntn_part = ctx->rntn_part; f.rntn_done = ctx->rntn_done;
@@ -904,7 +922,8 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     f.priority = cfg.scheduler == TL_SCHED_READY_PRIORITY ? 1 : 0;
     if (flow) {
         f.flow = (cfg.cell == TL_TREELSTM && ctx->spw_leaf > 0 && ws_range) ? 2 : 1;
-        f.flow_roots = f.n_int > 0 && !need_levels ? 1 : 0;      // (with no internal node the data-flow kernel is not launched)
+        // (with no internal node the data-flow kernel is not launched; where the level kernel may run instead, the root passes do)
+        f.flow_roots = f.n_int > 0 && !need_levels && !flow_or_levels ? 1 : 0;
         f.flow_seen = reinterpret_cast<int32_t *>(ctx->flow_ws);
         f.flow_list = reinterpret_cast<int4 *>(ctx->flow_ws + align256((size_t)ctx->n_cg * ctx->cap_nodes * sizeof(int32_t)));
     }
@@ -975,7 +994,15 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
         } else if (cfg.scheduler == TL_SCHED_LEVEL_DEVICE || cfg.scheduler == TL_SCHED_DATAFLOW) {
             // weight-stationary cell: every workgroup is tied to one column group, so whole sets only
             const int grid_l = spw > 0 ? grid_p / ctx->n_cg * ctx->n_cg : grid_p;
-            hipLaunchKernelGGL(kern, dim3(grid_l), dim3(WG_THREADS), kern_lds, st, f);
+            if (flow_or_levels) {                     // both kernels; every workgroup of the one that is not picked returns at once
+                Fwd g = f;
+                g.pick = 1;
+                hipLaunchKernelGGL(kern, dim3(grid_l), dim3(WG_THREADS), kern_lds, st, g);
+                g.pick = 2;
+                hipLaunchKernelGGL(levels_kernel(cfg.cell, vec4_inner, spw, bf16), dim3(grid_l2), dim3(WG_THREADS), kern_lds, st, g);
+            } else {
+                hipLaunchKernelGGL(kern, dim3(grid_l), dim3(WG_THREADS), kern_lds, st, f);
+            }
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists

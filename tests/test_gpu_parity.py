@@ -491,3 +491,31 @@ def test_dataflow_on_many_batch_shapes(precision):
                 ref = oracle.forward_params(round_params_bf16(params), trees, n_threads=8, round_bf16=True)
                 assert_close_bf16(a["h"], ref["h"], what + " h")
                 assert_close_bf16(a["c"], ref["c"], what + " c")
+
+
+@pytest.mark.parametrize("shape", ["balanced", "random", "chain"])
+def test_few_large_trees_under_the_dataflow_scheduler(shape):
+    """One or two trees of thousands of nodes: fewer trees than the device has sets of workgroups.  The data-flow
+    scheduler deals whole trees to the sets, which suits deep narrow trees and would leave the device idle under a
+    bushy one, so for such a batch both internal-node kernels are launched and the device picks by the width of the
+    first frontier: bushy trees go level by level (the same bits as the level scheduler), chains stay data-flow
+    (equal to rounding).  Every node against the checker either way."""
+    say("case few large trees", shape)
+    params = synth.make_treelstm_params(61, 500, 40, 256, "xavier")
+    for B, L in ((1, 3000), (2, 1500)):
+        trees = synth.make_trees(62 + B, [L] * B, [shape] * B, 500)
+        ref = oracle.forward_params(params, trees, n_threads=8)
+        outs = {}
+        for sched in ("dataflow", "level_device"):
+            net = binding.TreeNet(params, scheduler=sched)
+            try:
+                outs[sched] = net.run(trees)
+                check_against_oracle(params, trees, outs[sched], ref, "%d x %d leaves %s / %s" % (B, L, shape, sched))
+            finally:
+                net.close()
+        if shape == "chain":
+            np.testing.assert_allclose(outs["dataflow"]["h"], outs["level_device"]["h"], rtol=2e-5, atol=2e-6)
+            assert not np.array_equal(outs["dataflow"]["h"], outs["level_device"]["h"]), "the data-flow kernel was expected to run"
+        else:
+            assert np.array_equal(outs["dataflow"]["h"], outs["level_device"]["h"])
+            assert np.array_equal(outs["dataflow"]["c"], outs["level_device"]["c"])
