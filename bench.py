@@ -340,7 +340,7 @@ def other_configs(steps, warmup):
     """The evaluation workloads other than the headline one, a few steps each: ms per step, trees/s, nodes/s, the
     internal-node kernel's fraction of the matrix peak of its precision (algorithmic flops over its mean duration from
     the library's stage events) and the step's algorithmic bytes per second (the small and the TreeRNN workloads are
-    bound by latency and memory, not by the matrix units), for the default scheduler; on `sentence`, `throughput` and `stress` also for the
+    bound by latency and memory, not by the matrix units), for the default scheduler, the
     ready-queue scheduler and the two level-wise ones (Section 4.1 against the depth-wise batching of Section 6.3)."""
     from paper_1809_00832_amd import binding, synth
     rows = []
@@ -353,9 +353,7 @@ def other_configs(steps, warmup):
         prec = binding.TL_F32 if dtype == "f32" else binding.TL_BF16_IN
         heavy = name == "stress"
         k, wu = (min(steps, 5), min(warmup, 2)) if heavy else (min(steps, 20), min(warmup, 5))
-        scheds = [DEFAULT_SCHEDULER]
-        if name in ("sentence", "throughput", "stress"):
-            scheds += ["ready", "level_device", "level_host"]
+        scheds = [DEFAULT_SCHEDULER, "ready", "level_device", "level_host"]
         row = {"workload": name, "dtype": dtype, "trees": t.n_trees, "nodes": t.n_nodes, "hidden": w.params.hidden, "schedulers": {}}
         for sched in scheds:
             r = run_scheduler(w, sched, prec, k, wu)
