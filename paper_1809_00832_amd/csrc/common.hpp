@@ -144,6 +144,7 @@ struct Fwd {
     int4 *flow_list;
     int flow_roots;                   // data-flow scheduler: roots are found and their states copied out by the cell kernels (no separate passes)
     int flow;                         // data-flow scheduler: who fills the rows of internal nodes with the "not written" pattern: 1 the reset kernel, 2 the leaf kernel
+    int gang_parts;                   // ready scheduler, RNTN cell: workgroups per tile and column group (each adds up a part of the slices), 1 or RNTN_PARTS
     int pick;                         // batch of few large trees, both internal-node kernels launched: 1 this one runs if the trees are narrow, 2 if they are not (see internal_kernel_skipped)
 };
 

@@ -973,7 +973,10 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
             else sm.src1[tid - 2 * TILE_ROWS] = SPW > 0 ? max(value, 0) : value;
             if (tid == 0) {
                 sm.cmd[0] = (int)((entry >> 32) & 0xffu);
-                sm.cmd[5] = -1;                             // RNTN cell: this workgroup adds up all parts itself
+                // RNTN cell: this workgroup adds up all parts itself, or (gangs of several workgroups per column group)
+                // its own part, in the scratch unit of this gang and ring slot
+                sm.cmd[5] = f.gang_parts > 1 ? member / f.n_cg : -1;
+                sm.cmd[6] = gang * GANG_RING + (int)(seq % GANG_RING);
             }
         }
         __syncthreads();
@@ -987,8 +990,12 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_read
         } else if constexpr (SPW > 0) {
             ws_tile<EPI, true, SPW, !VEC4>(sm, f, f.inner, f.h, f.n_nodes, count, my_cg, w);
         } else {
-            for (int j = member; j < f.n_cg; j += f.gang_size)
-                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
+            if (f.gang_parts > 1) {
+                cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, member % f.n_cg);
+            } else {
+                for (int j = member; j < f.n_cg; j += f.gang_size)
+                    cell_tile<EPI, VEC4, true, BF16>(sm, f, f.inner, f.h, count, gang_cg(j, f.gang_size, f.n_cg));
+            }
         }
 
         // ---- completion: the tile's h/c rows are in memory before the scheduler hears of it -----

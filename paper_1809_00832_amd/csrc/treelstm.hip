@@ -916,6 +916,21 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     // ready scheduler: gangs of gang_size compute workgroups plus one scheduler workgroup each
     f.gang_size = ctx->n_cg + 1 <= grid_p ? ctx->n_cg : grid_p - 1;
     f.n_gangs = grid_p / (f.gang_size + 1) < MAX_GANGS ? grid_p / (f.gang_size + 1) : MAX_GANGS;
+    f.gang_parts = 1;
+    // RNTN: with few column groups (d = 64: four) a gang of one workgroup per column group leaves a tile's 129 slices to
+    // four workgroups; as under the level scheduler, RNTN_PARTS workgroups per column group each add up a part of the
+    // slices and the last one to arrive adds the parts (one unit of the scratch area per gang and tile in flight)
+    if (cfg.cell == TL_RNTN && ready_sched && ctx->rntn_part != nullptr) {
+        const int gs = ctx->n_cg * RNTN_PARTS;
+        int gangs = grid_p / (gs + 1);
+        if (gangs > MAX_GANGS) gangs = MAX_GANGS;
+        if (gangs > ctx->rntn_units / GANG_RING) gangs = ctx->rntn_units / GANG_RING;
+        if (gangs >= 1) {
+            f.gang_size = gs;
+            f.n_gangs = gangs;
+            f.gang_parts = RNTN_PARTS;
+        }
+    }
 
     // heights and per-height node lists: for the host-driven scheduler, and as the check for cycles
     const bool need_levels = cfg.scheduler == TL_SCHED_LEVEL_HOST || cfg.validate != 0;

@@ -281,8 +281,9 @@ def test_wide_frontiers_at_a_hidden_size_with_uneven_slots():
 
 def test_rntn_schedulers_agree_bit_for_bit():
     """RNTN: the level schedulers cut a frontier of few tiles into four workgroups per tile and column group (each
-    adds up a quarter of the slices, the last one to finish adds the quarters); the ready schedulers and the large
-    frontiers do not.  The order of summation is the same either way, so all four give the same bits, run after run."""
+    adds up a quarter of the slices, the last one to finish adds the quarters), and so do the gangs of the ready
+    schedulers for every tile; large frontiers do not.  The order of summation is the same either way, so all
+    schedulers give the same bits, run after run."""
     say("case rntn bits")
     w, ref = reference("rntn")
     first = None
