@@ -333,7 +333,7 @@ def topdown_bench(steps, warmup, with_cpu):
         finally:
             binding.tl_td_destroy(ctx)
     print(json.dumps({"topdown": rows, "dtype": "f32", "data": "synthetic",
-                      "note": "tl_td_generate, root states resident; trees are grown breadth first, two grid barriers per depth"}))
+                      "note": "tl_td_generate, root states resident; td64: breadth first, two grid barriers per depth; td1 (batches of up to 32 roots): no frontiers, children computed while the parent is scored"}))
 
 
 def other_configs(steps, warmup):

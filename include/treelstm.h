@@ -384,14 +384,18 @@ int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *
                  tl_td_ctx **out);
 
 /*
- * Grows n_trees trees breadth first in one persistent kernel, asynchronously on hip_stream.
+ * Grows n_trees trees in one persistent kernel, asynchronously on hip_stream: batches of up to 32 roots (H a
+ * multiple of 4, rows 16-byte aligned) without frontiers - a node is expanded as soon as its own parent has been
+ * decided, and its children are computed while it is still being scored -, larger ones breadth first, frontier by
+ * frontier, with two grid barriers per depth.
  *   h, c     [max_nodes x H] fp32: rows 0 .. n_trees-1 hold the root states on entry (node t is
  *            the root of tree t); every other used row is written                       DEVICE
  *   parent, left, right, depth  [max_nodes] int32 out: links (-1: none) and depth       DEVICE
  *   score    [max_nodes] fp32 out                                                       DEVICE
  *   counts   [4] int32 out: nodes, nodes that would have expanded but found no two free
  *            rows, frontiers walked, 0                                                  DEVICE
- * Rows beyond counts[0] are not written.  The two children of a node are consecutive rows, left
+ * Rows beyond counts[0] hold no result (the call may have overwritten them: of h and c up to 16 MiB, of the
+ * int32 arrays all max_nodes entries).  The two children of a node are consecutive rows, left
  * first; which rows they are depends on timing and differs from run to run, the trees (and each
  * node's state, bit for bit) do not.  Nothing is allocated.  fp32 arithmetic on the matrix units.
  * The kernel needs the device to itself (all its workgroups resident), like the persistent

@@ -283,6 +283,12 @@ __device__ inline void ws_park_rows(Smem &sm, const floatx4 (&regs)[WsLoadGeom<S
 struct WsNoHook {
     __device__ inline void operator()(int) const {}
 };
+// Top-down generation, data-flow form (EPI_TD_CHILD with FLOW): a row of sm.node may hold WS_ROW_PENDING instead of the
+// child's row: the parent (sm.src0) has been reserved but whether it gets children is not known yet.  Its contraction is
+// computed all the same, and when the row is finished the hook says where the result goes: ahead_of(tile row) is what
+// it asked for when the block's rows arrived, ask(parent) asks again; `undecided` is the answer "not known yet", -1 means
+// no children, any other value is the left child's row, `side` is added for this workgroup's child.
+constexpr int WS_ROW_PENDING = -3;
 template <int EPI, bool COH, int SPW, bool TAIL = false, bool FLOW = false, typename Hook = WsNoHook>
 __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, const float *__restrict__ table, int table_rows,
                                int count, int cg, const WsWeights<EpiTraits<EPI>::NG, SPW> &w, Hook hook = Hook())
@@ -311,6 +317,40 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
             sum += red[((2 * NG + g) * 4 + wave) * 64 + lane];
             sum += red[((3 * NG + g) * 4 + wave) * 64 + lane];
             gate[g] = sum + w.bias[g];
+        }
+        if constexpr (FLOW && EPI == EPI_TD_CHILD) {
+            // The result of a row is stored the moment its own decision is known: a lane never holds a decided row back
+            // while it waits for another row's decision (whoever decides that one may be waiting for this store).
+            const bool pending = enode == WS_ROW_PENDING && hu_ok;
+            if (ev || pending) {
+                cl = flow_wait_c<COH>(f, rs_c, (unsigned)sm.src0[erow & (WS_TABLE_ROWS - 1)] * row_b + hu_b, cl);   // the parent's c element may arrive after its h row
+                const float i = sigmoid_f(gate[0]), fg = sigmoid_f(gate[1]), og = sigmoid_f(gate[2]), u = tanh_f(gate[3]);
+                const float cc = __builtin_fmaf(fg, cl, i * u);
+                const float hh = og * tanh_f(cc);
+                int child = pending ? hook.ahead_of(erow) : enode;
+                bool open = true;
+                // (The loop condition is the same for all lanes of the wave on purpose.  A loop that each lane leaves on its
+                // own is compiled into one whose lanes meet again behind it, with the stores moved there: the coupling this
+                // is meant to avoid.)
+                for (int spins = 0;; ++spins) {
+                    if (open && child != hook.undecided) {
+                        if (child >= 0) {
+                            const unsigned o = (unsigned)(pending ? child + hook.side : child) * row_b + hu_b;
+                            buf_st_f<COH>(rs_c, o, cc);
+                            buf_st_f<COH>(rs_h, o, hh);
+                        }
+                        open = false;
+                    }
+                    if (__ballot(open) == 0ull) break;
+                    if (spins > f.spin_limit || ((spins & 63) == 63 && ld_dev(&f.ctl->abort.v) != 0u)) {
+                        if (open) flow_give_up(f);
+                        break;
+                    }
+                    backoff();
+                    if (open) child = hook.ask(sm.src0[erow & (WS_TABLE_ROWS - 1)]);
+                }
+            }
+            return;
         }
         if (ev) {
             const unsigned o = (unsigned)enode * row_b + hu_b;
@@ -357,7 +397,8 @@ __device__ inline void ws_tile(WsSmemT<SPW> &sm, const Fwd &f, const Gemm &gm, c
     // A piece's last block with few rows takes the narrow form below the loop (data-flow scheduler only).
     constexpr int NARROW_MAX_RG = NG >= 3 ? 3 : 2;              // groups of four rows up to which that form is the faster one
     const int n_rg = (count - (nrb - 1) * 16 + 3) >> 2;         // groups of four rows in the last block
-    const bool last_narrow = FLOW && nrb > 0 && n_rg <= NARROW_MAX_RG;
+    // (not in top-down generation: there the place of a node in a tile depends on timing, and its bits must not)
+    const bool last_narrow = FLOW && EPI != EPI_TD_CHILD && nrb > 0 && n_rg <= NARROW_MAX_RG;
     const int nrb_full = last_narrow ? nrb - 1 : nrb;
     for (int rb = 0; rb < nrb_full; ++rb) {
         float *red = sm.red[rb & 1];

@@ -52,6 +52,10 @@ struct alignas(LINE) Ctl {
     Line tiles;                   // tiles formed (statistics only)
     Line direct;                  // nodes that a scheduler handed to its own gang without passing the queue
     Line truncated;               // top-down generation: nodes that would have expanded but found no free rows
+    // top-down generation, data-flow form: rows reserved for children so far (low half; the roots' rows are not counted)
+    // and rows whose decision has been taken and published (high half); the largest depth of a reserved row
+    Line64 td_rows;
+    Line td_depth;
     // priority variant of the ready scheduler: sum of all nodes' (capped) distances from their roots, and the
     // critical / other seeds placed so far
     Line64 depth_sum;

@@ -98,6 +98,7 @@ struct tl_ctx {
 struct tl_td_ctx {
     int device = 0, n_cu = 0, H = 0, n_cg = 0, spin_limit = 0;
     int spw = 0;                      // k-steps per wave of the weight-stationary expansion step (0: streaming cell only)
+    int flow_grid = 0;                // workgroups of the data-flow form that are resident together (0: that form is not used)
     tl::Gemm side[2]{};
     void *wp[2] = {nullptr, nullptr};
     float *bp[2] = {nullptr, nullptr};
@@ -1409,6 +1410,24 @@ td_kernel td_ws_kernel(int spw)
     default: return tl::k_td_generate<true, 16>;
     }
 }
+td_kernel td_flow_kernel(int spw)
+{
+    switch (spw) {
+    case 1: return tl::k_td_flow<1>;
+    case 2: return tl::k_td_flow<2>;
+    case 4: return tl::k_td_flow<4>;
+    case 5: return tl::k_td_flow<5>;
+    case 8: return tl::k_td_flow<8>;
+    default: return tl::k_td_flow<16>;
+    }
+}
+// Data-flow form of the generator: workgroups that decide beside the sets that expand; rows of h and c that the reset
+// kernel marks per call (16 MiB of the two arrays together, at least 1 024 rows; rows beyond are marked when reserved).
+// It is the faster form while the trees in flight keep the sets of workgroups less than busy, i.e. for small batches
+// (measured at H = 512: 1.3x at 1 to 4 roots, level at 32, 0.9x at 64): batches of more roots take the form with frontiers.
+constexpr int TD_MIN_DECIDERS = 8, TD_MAX_DECIDERS = 64;
+constexpr long long TD_MARK_BYTES = 16ll << 20;
+constexpr int TD_FLOW_MAX_TREES = 32;
 }  // namespace
 
 int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *w_stop, float b_stop, int spin_limit,
@@ -1461,9 +1480,20 @@ int tl_td_create(int hidden, const float *u_td, const float *b_td, const float *
                                    (int)TILE_SMEM_BYTES));
         TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(k_td_generate<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)TILE_SMEM_BYTES));
-        if (ctx->spw > 0)
+        if (ctx->spw > 0) {
             TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(td_ws_kernel(ctx->spw)), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)ws_lds_bytes(ctx->spw, false)));
+            TL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(td_flow_kernel(ctx->spw)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)ws_lds_bytes(ctx->spw, false)));
+            // every workgroup of the data-flow form waits for others: all of them must be resident together
+            int occ = 0;
+            TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void *>(td_flow_kernel(ctx->spw)), WG_THREADS,
+                                                                ws_lds_bytes(ctx->spw, false)));
+            // one workgroup per CU where that holds a set and the deciders (measured: a second one per CU, for more sets, is no
+            // faster), two where it takes them
+            const int needed = 2 * ctx->n_cg + TD_MIN_DECIDERS;
+            ctx->flow_grid = occ >= 1 && ctx->n_cu >= needed ? ctx->n_cu : occ >= 2 && 2 * ctx->n_cu >= needed ? 2 * ctx->n_cu : 0;
+        }
         TL_HIP(hipDeviceSynchronize());
         return TL_OK;
     }();
@@ -1494,10 +1524,22 @@ int tl_td_generate(tl_td_ctx *ctx, int n_trees, int max_nodes, int max_depth, fl
     int grid = ctx->n_cu < (int)FLAT_BARRIER_MAX ? ctx->n_cu : (int)FLAT_BARRIER_MAX;
     if (grid < 1) grid = 1;
     const bool vec4 = ctx->H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
-    hipLaunchKernelGGL(k_td_reset, dim3(4), dim3(256), 0, st, a);
     // the weight-stationary cell addresses rows with 24-bit row numbers and 32-bit byte offsets
     const bool ws_range = max_nodes < (1 << 24) && (unsigned long long)max_nodes * ctx->H * 4ull < (1ull << 32);
-    if (vec4 && ctx->spw > 0 && ws_range && grid >= 2 * ctx->n_cg)
+    const bool flow = vec4 && ctx->spw > 0 && ws_range && ctx->flow_grid > 0 && n_trees <= TD_FLOW_MAX_TREES;
+    if (flow) {
+        const int combos = 2 * ctx->n_cg;
+        a.n_slots = (ctx->flow_grid - TD_MIN_DECIDERS) / combos;
+        a.n_dec = ctx->flow_grid - a.n_slots * combos < TD_MAX_DECIDERS ? ctx->flow_grid - a.n_slots * combos : TD_MAX_DECIDERS;
+        long long marked = TD_MARK_BYTES / (8ll * ctx->H);
+        if (marked < n_trees + 1024) marked = n_trees + 1024;
+        a.marked_rows = marked < max_nodes ? (int)marked : max_nodes;
+    }
+    hipLaunchKernelGGL(k_td_reset, dim3(flow ? 2 * ctx->n_cu : 4), dim3(256), 0, st, a);
+    if (flow)
+        hipLaunchKernelGGL(td_flow_kernel(ctx->spw), dim3(a.n_slots * 2 * ctx->n_cg + a.n_dec), dim3(WG_THREADS), ws_lds_bytes(ctx->spw, false),
+                           st, a);
+    else if (vec4 && ctx->spw > 0 && ws_range && grid >= 2 * ctx->n_cg)
         hipLaunchKernelGGL(td_ws_kernel(ctx->spw), dim3(grid), dim3(WG_THREADS), ws_lds_bytes(ctx->spw, false), st, a);
     else if (vec4)
         hipLaunchKernelGGL(k_td_generate<true>, dim3(grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, a);

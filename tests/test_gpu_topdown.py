@@ -152,6 +152,69 @@ def test_full_size_batch_of_64():
         got["n_nodes"], gold["n_nodes"], compared, undecided), flush=True)
 
 
+@pytest.mark.parametrize("B", [1, 7, 32])
+def test_small_batches_take_the_data_flow_form(B):
+    """Batches of up to 32 roots at H = 512 grow without frontiers (deciders beside expanders, children computed while
+    their parent is being scored): the B largest trees of the batch of 64 against the checker's trees (those without
+    a decision near zero, at least half of them), node by node by
+    path, every node against the checker's step, and the same bits from run to run although rows and tiles differ."""
+    print("case topdown data-flow form", B, flush=True)
+    w = synth.topdown_workload("td64")
+    with open(os.path.join(HERE, "golden", "topdown_td64.json")) as fh:
+        gold = json.load(fh)
+    pick = sorted(range(64), key=lambda t: -gold["trees"][t]["nodes"])[:B]
+    w.h_root, w.c_root = w.h_root[pick].copy(), w.c_root[pick].copy()
+    ref = oracle.td_generate(w.u_td, w.b_td, w.w_stop, w.b_stop, w.h_root, w.c_root, w.max_depth, w.max_nodes)
+    got = generate(w)
+    gk, rk = paths(got, B), paths(ref, B)
+    shaky = {rk[v][0] for v in range(ref["n_nodes"]) if abs(float(ref["score"][v])) <= MARGIN}
+    gmap = {k: v for v, k in enumerate(gk)}
+    rmap = {k: v for v, k in enumerate(rk)}
+    assert 2 * len(shaky) <= B
+    for t in range(B):
+        if t not in shaky:
+            assert {k for k in gmap if k[0] == t} == {k for k in rmap if k[0] == t}, "tree %d has another shape" % t
+    for k, v in rmap.items():
+        if k[0] not in shaky:
+            g = gmap[k]
+            assert close(got["h"][g], ref["h"][v]) and close(got["c"][g], ref["c"][v]), k
+            assert got["depth"][g] == ref["depth"][v] and (got["left"][g] >= 0) == (ref["left"][v] >= 0)
+    if not shaky:
+        assert got["n_nodes"] == ref["n_nodes"] and got["frontiers"] == int(ref["depth"].max()) + 1
+    assert got["truncated"] == 0
+    check_steps(w, got, range(0, got["n_nodes"], 1 if B < 32 else 2))
+    for _ in range(3):
+        again = generate(w)
+        amap = {k: v for v, k in enumerate(paths(again, B))}
+        assert again["n_nodes"] == got["n_nodes"]
+        order = np.array([amap[k] for k in gk])
+        assert np.array_equal(again["h"][order], got["h"]) and np.array_equal(again["c"][order], got["c"])
+        assert np.array_equal(again["score"][order], got["score"])
+    print("    nodes %d (checker %d), trees with a decision within the margin %d" % (got["n_nodes"], ref["n_nodes"], len(shaky)),
+          flush=True)
+
+
+def test_data_flow_form_beyond_the_rows_marked_in_advance():
+    """The data-flow form marks 16 MiB of rows as "not written" before it starts and later rows when they are reserved:
+    full trees of 2 x 32 767 nodes at H = 64 (32 768 rows are marked in advance), closed forms and sampled steps; then
+    the same with room for half of them."""
+    print("case topdown rows marked when reserved", flush=True)
+    B, H, D = 2, 64, 14
+    full_n = B * (2 ** (D + 1) - 1)
+    w = synth.make_topdown(77, "case", B, H, D, full_n + 5, 6.0, 0.0)
+    zero = np.zeros_like(w.w_stop)
+    full = generate(w, w_stop=zero, b_stop=1.0)
+    assert full["n_nodes"] == full_n and full["truncated"] == 0 and full["frontiers"] == D + 1
+    assert np.array_equal(np.bincount(full["depth"]), B * 2 ** np.arange(D + 1))
+    paths(full, B)
+    check_steps(w, full, range(0, full_n, 97), w_stop=zero, b_stop=1.0)
+    check_steps(w, full, range(full_n - 40, full_n), w_stop=zero, b_stop=1.0)
+    half = generate(w, w_stop=zero, b_stop=1.0, max_nodes=full_n // 2)
+    assert half["n_nodes"] == B + 2 * ((full_n // 2 - B) // 2) and half["truncated"] >= 1
+    paths(half, B)
+    check_steps(w, half, range(0, half["n_nodes"], 211), w_stop=zero, b_stop=1.0)
+
+
 def test_closed_forms_limits_and_ragged_sizes():
     print("case topdown closed forms", flush=True)
     # (H = 64, 100, 320: the expansion step on the weight-stationary cell, the last two with a padded K axis)
