@@ -279,6 +279,12 @@ def backward_stage(w, n_classes, reps=10):
             out["sgd_update_ms"] = wall(lambda: binding.tl_sgd_update(net.ctx, 0.0, b, grads0), reps)
             step_ms = wall(train_step, reps)
             out["train_step_ms"] = step_ms
+            if w.params.cell != 2:
+                # the same with a backward that does not wait for the device (all heights in one persistent kernel)
+                binding.tl_set_async_backward(net.ctx, True)
+                out["ms_without_waiting"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
+                out["train_step_ms_without_waiting"] = wall(train_step, reps)
+                binding.tl_set_async_backward(net.ctx, False)
             out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
             out["train_step_note"] = ("forward (a TreeLSTM keeps its gate activations) + head backward + tree backward + SGD update "
                                       "of all parameters (embedding rows included) and re-packing of the weights")

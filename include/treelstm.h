@@ -275,7 +275,8 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
  * kept them (tl_set_keep_gates); TreeRNN and RNTN need nothing but h.  The RNTN path is a first
  * version: it materialises a row of d * 2d + d values per internal node (workspace of that size).
  * Work is enqueued on hip_stream, but the call waits for the structure pass (it needs the
- * number of heights) and returns the deferred structure status: TL_OK, TL_ESTRUCT, ...
+ * number of heights and their sizes for its launches, one pair per height) and returns the deferred
+ * structure status: TL_OK, TL_ESTRUCT, ...  With tl_set_async_backward it does not wait.
  * The first call for a larger batch than any before allocates workspace (TL_ENOMEM if the RNTN
  * rows would take more than 64 GiB).  TL_BF16_IN: TL_EINVAL.
  */
@@ -322,6 +323,19 @@ int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf,
  * accepted, no effect.  Off by default.
  */
 int tl_set_keep_gates(tl_ctx *ctx, int on);
+
+/*
+ * For callers that must not be held up by tl_backward (the recursion of Section 4.2.2 walked without the host):
+ * with on != 0, a tl_backward that needs no contraction for its gate gradients - TreeLSTM from kept gate
+ * activations (tl_set_keep_gates), TreeRNN - walks all heights in one persistent kernel that finds the
+ * per-height lists on the device.  Nothing is read back and the call returns without waiting; a malformed
+ * batch is then reported by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results
+ * as the per-height launches (same contractions in the same order).  Measured 13 % slower than those (a
+ * grid barrier and device-scope traffic per height instead of a launch), hence off by default.  Like the
+ * persistent schedulers of tl_forward, the kernel needs all its workgroups resident.  Other cases
+ * (recomputed gates, TL_RNTN) keep the launches per height and wait as before.
+ */
+int tl_set_async_backward(tl_ctx *ctx, int on);
 
 /*
  * Per-node classifier head (Section 6.1: the evaluated networks label all nodes of a parse

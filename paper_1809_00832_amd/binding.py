@@ -23,7 +23,7 @@ SCHEDULERS = {"ready": TL_SCHED_READY, "level_device": TL_SCHED_LEVEL_DEVICE, "l
               "ready_priority": TL_SCHED_READY_PRIORITY, "dataflow": TL_SCHED_DATAFLOW}
 
 EXPORTS = ("tl_create", "tl_forward", "tl_forward_noalloc", "tl_status", "tl_set_profiling", "tl_stage_ms", "tl_last_stats", "tl_backward",
-           "tl_set_keep_gates", "tl_sgd_update", "tl_get_params", "tl_classify", "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
+           "tl_set_keep_gates", "tl_set_async_backward", "tl_sgd_update", "tl_get_params", "tl_classify", "tl_classify_backward", "tl_td_create", "tl_td_generate", "tl_td_status", "tl_td_destroy", "tl_strerror", "tl_destroy")
 
 
 class tl_config(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib():
         L.tl_get_params.argtypes = [vp] * 7
         L.tl_set_keep_gates.restype = ci
         L.tl_set_keep_gates.argtypes = [vp, ci]
+        L.tl_set_async_backward.restype = ci
+        L.tl_set_async_backward.argtypes = [vp, ci]
         L.tl_td_create.restype = ci
         L.tl_td_create.argtypes = [ci, vp, vp, vp, ctypes.c_float, ci, ctypes.POINTER(vp)]
         L.tl_td_generate.restype = ci
@@ -213,6 +215,10 @@ def tl_get_params(ctx, vocab, embed_dim, hidden, cell=TL_TREELSTM, stream=None):
 
 def tl_set_keep_gates(ctx, on: bool) -> None:
     _check(lib().tl_set_keep_gates(ctx, 1 if on else 0), "tl_set_keep_gates")
+
+
+def tl_set_async_backward(ctx, on: bool) -> None:
+    _check(lib().tl_set_async_backward(ctx, 1 if on else 0), "tl_set_async_backward")
 
 
 def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):

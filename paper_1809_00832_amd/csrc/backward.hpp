@@ -17,10 +17,13 @@
 #pragma once
 
 #include "cell_tile.hpp"
+#include "schedulers.hpp"
 
 namespace tl {
 
-template <int EPI, int NG>
+// COH: the rows of dh that the operand gradient adds to are read by other workgroups of the same kernel (the
+// persistent form below): device-scope accesses, as in the forward's persistent kernels.
+template <int EPI, int NG, bool COH>
 __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG], int rb,
                                     int count, int cg, int lane)
 {
@@ -81,7 +84,7 @@ __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm
                 if constexpr (INNER) {
                     const int child = oc < H ? f.left[node] : f.right[node];
                     float *p = f.dh + (size_t)child * H + (oc < H ? oc : oc - H);
-                    *p += acc[g][v];
+                    st_f<COH>(p, ld_f<COH>(p) + acc[g][v]);
                 } else {
                     f.d_x[(size_t)node * f.E + oc] = acc[g][v];
                 }
@@ -94,13 +97,15 @@ __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm
 // of bwd_epilogue without the contraction in front of it.  One thread per (row of `list`, group of
 // V hidden units); same outputs as the EPI_BWD_*_GATES epilogues (dg rows by list position from
 // pos0 on, dc of the children).
-template <bool INNER, int V>
-__global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+// (COH: dh, dc and dg are exchanged between workgroups of one kernel, see the persistent form below.)
+template <bool INNER, int V, bool COH>
+__device__ inline void gate_grad_kept_rows(const Fwd &f, const int32_t *__restrict__ list, int n_rows, int pos0, long long first,
+                                           long long stride)
 {
     const int H = f.H, per_row = H / V;
     const int NG = INNER ? 5 : 3;
     const long long total = (long long)n_rows * per_row;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+    for (long long e = first; e < total; e += stride) {
         const int row = (int)(e / per_row), col = (int)(e - (long long)row * per_row) * V;
         const int node = list[row];
         const size_t o = (size_t)node * H + col;
@@ -113,11 +118,21 @@ __global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__
             if constexpr (V == 4) { const floatx4 t = *reinterpret_cast<const floatx4 *>(src); dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w; }
             else dst[0] = *src;
         };
-        auto store = [&](float *dst, const float (&src)[V]) {
-            if constexpr (V == 4) *reinterpret_cast<floatx4 *>(dst) = floatx4{src[0], src[1], src[2], src[3]};
-            else *dst = src[0];
+        auto load_x = [&](float (&dst)[V], const float *src) {      // what another workgroup may have written
+            if constexpr (V == 4) { const floatx4 t = ld_f4<COH>(src); dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w; }
+            else dst[0] = ld_f<COH>(src);
         };
-        load(cn, f.c + o); load(dh, f.dh + o); load(dc, f.dc + o);
+        auto store = [&](float *dst, const float (&src)[V]) {       // ... and what another one will read
+            if constexpr (V == 4 && COH) {
+                st_dev(reinterpret_cast<unsigned long long *>(dst), pack2(__float_as_uint(src[0]), __float_as_uint(src[1])));
+                st_dev(reinterpret_cast<unsigned long long *>(dst) + 1, pack2(__float_as_uint(src[2]), __float_as_uint(src[3])));
+            } else if constexpr (V == 4) {
+                *reinterpret_cast<floatx4 *>(dst) = floatx4{src[0], src[1], src[2], src[3]};
+            } else {
+                st_f<COH>(dst, src[0]);
+            }
+        };
+        load(cn, f.c + o); load_x(dh, f.dh + o); load_x(dc, f.dc + o);
 #pragma unroll
         for (int q = 0; q < NG; ++q) load(g[q], kept + (size_t)q * H);
         if (INNER) { load(cl, f.c + (size_t)l * H + col); load(cr, f.c + (size_t)r * H + col); }
@@ -147,27 +162,46 @@ __global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__
         if (INNER) { store(f.dc + (size_t)l * H + col, dcl); store(f.dc + (size_t)r * H + col, dcr); }
     }
 }
+template <bool INNER, int V>
+__global__ __launch_bounds__(256) void k_gate_grad_kept(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+{
+    gate_grad_kept_rows<INNER, V, false>(f, list, n_rows, pos0, (long long)blockIdx.x * blockDim.x + threadIdx.x,
+                                         (long long)gridDim.x * blockDim.x);
+}
 
 // TreeRNN (h = tanh(a W + b), leaves h = x): the gradient of the pre-activation needs only the stored h,
 // dpre = dh (1 - h^2), one row of H values per listed node (by list position from pos0 on).
-template <int V>
-__global__ __launch_bounds__(256) void k_rnn_gate_grad(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+template <int V, bool COH>
+__device__ inline void rnn_gate_grad_rows(const Fwd &f, const int32_t *__restrict__ list, int n_rows, int pos0, long long first,
+                                          long long stride)
 {
     const int H = f.H, per_row = H / V;
     const long long total = (long long)n_rows * per_row;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+    for (long long e = first; e < total; e += stride) {
         const int row = (int)(e / per_row), col = (int)(e - (long long)row * per_row) * V;
         const size_t o = (size_t)list[row] * H + col;
         float *dg = f.dg + (size_t)(pos0 + row) * H + col;
         if constexpr (V == 4) {
-            const floatx4 hv = *reinterpret_cast<const floatx4 *>(f.h + o), dh = *reinterpret_cast<const floatx4 *>(f.dh + o);
-            *reinterpret_cast<floatx4 *>(dg) = floatx4{dh.x * (1.f - hv.x * hv.x), dh.y * (1.f - hv.y * hv.y),
-                                                      dh.z * (1.f - hv.z * hv.z), dh.w * (1.f - hv.w * hv.w)};
+            const floatx4 hv = *reinterpret_cast<const floatx4 *>(f.h + o), dh = ld_f4<COH>(f.dh + o);
+            const floatx4 out = {dh.x * (1.f - hv.x * hv.x), dh.y * (1.f - hv.y * hv.y), dh.z * (1.f - hv.z * hv.z),
+                                 dh.w * (1.f - hv.w * hv.w)};
+            if constexpr (COH) {
+                st_dev(reinterpret_cast<unsigned long long *>(dg), pack2(__float_as_uint(out.x), __float_as_uint(out.y)));
+                st_dev(reinterpret_cast<unsigned long long *>(dg) + 1, pack2(__float_as_uint(out.z), __float_as_uint(out.w)));
+            } else {
+                *reinterpret_cast<floatx4 *>(dg) = out;
+            }
         } else {
             const float hv = f.h[o];
-            *dg = f.dh[o] * (1.f - hv * hv);
+            st_f<COH>(dg, ld_f<COH>(f.dh + o) * (1.f - hv * hv));
         }
     }
+}
+template <int V>
+__global__ __launch_bounds__(256) void k_rnn_gate_grad(Fwd f, const int32_t *__restrict__ list, int n_rows, int pos0)
+{
+    rnn_gate_grad_rows<V, false>(f, list, n_rows, pos0, (long long)blockIdx.x * blockDim.x + threadIdx.x,
+                                 (long long)gridDim.x * blockDim.x);
 }
 
 // TreeRNN leaves: the embedding row is the state itself, so its gradient is the row of dh.
@@ -421,6 +455,71 @@ __global__ void k_sgd_embedding(float *__restrict__ emb, const float *__restrict
         const int w = word[n];
         if (w < 0 || w >= vocab) continue;
         atomicAdd(&emb[(size_t)w * E + j], -(lr * d_x[e]));
+    }
+}
+
+// ---- all heights in one launch ------------------------------------------------------------------
+// The walk over the heights above as one persistent kernel: the per-height lists are on the device already (the
+// counting sort of the structure pass), so the host needs neither the number of heights nor their sizes and
+// tl_backward returns without waiting for the device.  Per height, from the roots down:
+//   gate gradients   from the gate activations that the forward kept (TreeLSTM) or from h (TreeRNN), elementwise, the
+//                    rows shared out over all threads of the grid
+//   (grid barrier)
+//   operand gradient tiles of the height's rows x column groups on the streaming cell, as in the per-height launches
+//                    (four column blocks per group for heights of more than 64 rows, one otherwise)
+//   (grid barrier)
+// What one phase writes and the next reads on another workgroup (dg, dh, dc) goes through device-scope stores and
+// loads; the barrier is the bounded one of the level scheduler.  (Gate gradients that recompute the forward
+// contraction, and the RNTN cell, keep the per-height launches.)
+struct BwdHeights {
+    Gemm bwd4, bwd1;              // packed U^T with four column blocks per group / with one
+    int ng_inner;                 // 4: both forms exist, 1: only bwd4 holds weights (one block per group)
+    float *dg_int;
+    int kept_v4;                  // rows of h, c, gates and dg are 16-byte aligned and H % 4 == 0
+};
+
+template <bool LSTM, bool VEC4>
+__global__ __launch_bounds__(WG_THREADS, 2) void k_backward_heights(Fwd f, BwdHeights b)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    TileSmem &sm = *reinterpret_cast<TileSmem *>(smem_raw);
+    if (batch_rejected(f)) return;
+    const int tid = threadIdx.x;
+    const int H = f.H;
+    const int n_levels = f.ctl->n_levels;
+    const long long first = (long long)blockIdx.x * blockDim.x + tid, stride = (long long)gridDim.x * blockDim.x;
+    unsigned epoch = 0, unused = 0;
+    Fwd g = f;
+    g.dg = b.dg_int;
+    g.out_cols = 2 * H;
+    for (int lvl = n_levels - 1; lvl >= 1; --lvl) {         // roots first: a parent is always higher than its children
+        const int lo = f.level_off[lvl], rows = f.level_off[lvl + 1] - lo;
+        const int32_t *list = f.level_nodes + lo;
+        g.pos0 = lo;
+        if constexpr (LSTM) {
+            if (b.kept_v4) gate_grad_kept_rows<true, 4, true>(g, list, rows, lo, first, stride);
+            else gate_grad_kept_rows<true, 1, true>(g, list, rows, lo, first, stride);
+        } else {
+            if (b.kept_v4) rnn_gate_grad_rows<4, true>(g, list, rows, lo, first, stride);
+            else rnn_gate_grad_rows<1, true>(g, list, rows, lo, first, stride);
+        }
+        if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
+        const int ng = (b.ng_inner == 4 && rows > 64) ? 4 : 1;
+        g.bwd = (b.ng_inner == 4 && ng == 1) ? b.bwd1 : b.bwd4;
+        g.n_cg = (2 * H / ng + HU - 1) / HU;
+        const LevelPlan plan = plan_level(rows, f.cap_tiles);
+        for (int item = blockIdx.x; item < plan.n_tiles * g.n_cg; item += gridDim.x) {
+            const int tile = item / g.n_cg, cg = item - tile * g.n_cg;
+            int start, count;
+            plan_tile(plan, rows, tile, &start, &count);
+            __syncthreads();                                // the row tables are free
+            tile_set_rows<EPI_BWD_INNER_OPERAND>(sm, g, tid, tid < count ? list[start + tid] : -1, lo + start + tid);
+            if (tid == 0) sm.cmd[3] = lo + start;
+            __syncthreads();
+            if (ng == 4) cell_tile<EPI_BWD_INNER_OPERAND4, VEC4, true>(sm, g, g.bwd, g.dg, count, cg);
+            else cell_tile<EPI_BWD_INNER_OPERAND, VEC4, true>(sm, g, g.bwd, g.dg, count, cg);
+        }
+        if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
     }
 }
 

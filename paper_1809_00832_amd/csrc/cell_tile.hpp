@@ -165,7 +165,7 @@ __device__ inline floatx4 load_a_granule(const float *__restrict__ table, const 
     return v;
 }
 
-template <int EPI, int NG>
+template <int EPI, int NG, bool COH>
 __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm &gm, const floatx4 (&acc)[NG], int rb,
                                     int count, int cg, int lane);   // backward.hpp
 
@@ -175,7 +175,7 @@ __device__ inline void tile_epilogue(const TileSmem &sm, const Fwd &f, const Gem
                                      int rb, int count, int cg, int lane)
 {
     if constexpr (epi_is_backward(EPI)) {
-        bwd_epilogue<EPI, NG>(sm, f, gm, acc, rb, count, cg, lane);
+        bwd_epilogue<EPI, NG, COH>(sm, f, gm, acc, rb, count, cg, lane);
         return;
     }
     const int hu = cg * HU + (lane & 15);

@@ -68,6 +68,7 @@ struct tl_ctx {
     // backward pass (TreeLSTM, fp32): transposed weights packed like the forward ones, workspace
     void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr, *wp_bwd_inner1 = nullptr;
     float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr, *bp_bwd_inner1 = nullptr;
+    int bw_grid = 0;                  // workgroups of the backward kernel that walks all heights (0: per-height launches)
     Gemm g_bwd_inner1{};              // U^T once more with one column block per group: more workgroups for heights of few rows
     Gemm g_bwd_inner{}, g_bwd_leaf{};
     int ng_bwd_inner = 1, ng_bwd_leaf = 1;    // blocks of output columns per column group of the operand-gradient contractions
@@ -82,6 +83,7 @@ struct tl_ctx {
     float *rntn_acc = nullptr;        // RNTN backward: [2d x (d * 2d + d)] weight-gradient contraction and its column sums
     int ws_steps16 = 0;
     bool keep_gates = false;          // tl_set_keep_gates
+    bool async_backward = false;      // tl_set_async_backward
     float *gates = nullptr;           // [gates_cap x 5H] gate activations of the last forward that kept them
     int gates_cap = 0;
     int gates_nodes = 0;              // nodes of that forward, 0: nothing kept
@@ -701,6 +703,21 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     if (occ < 1) return TL_EHIP;
     if (occ > 2) occ = 2;
     ctx->persistent_grid = occ * ctx->n_cu;
+    ctx->bw_grid = 0;
+    if (!bf16 && cfg->cell != TL_RNTN) {
+        // the backward kernel that walks all heights waits on a grid barrier: all its workgroups must be resident
+        typedef void (*bwh_kernel)(Fwd, BwdHeights);
+        const bwh_kernel ks[4] = {k_backward_heights<true, true>, k_backward_heights<true, false>, k_backward_heights<false, true>,
+                                  k_backward_heights<false, false>};
+        int o_min = 2;
+        for (const bwh_kernel k : ks) {
+            if ((rc = allow_lds(k)) != TL_OK) return rc;
+            int o = 0;
+            TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(k), WG_THREADS, TILE_SMEM_BYTES));
+            if (o < o_min) o_min = o;
+        }
+        ctx->bw_grid = o_min * ctx->n_cu;
+    }
     if (ctx->spw > 0) {
         ctx->ws_lds = ws_lds_bytes(ctx->spw, bf16);
         for (int v = 0; v < 2; ++v) {   // fp32: rows 16-byte aligned / 8-byte aligned
@@ -1190,14 +1207,31 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         hipLaunchKernelGGL(k_zero_many, dim3(1024), dim3(256), 0, st, z);
     }
     TL_HIP(hipGetLastError());
-    if ((rc = read_ctl(ctx)) != TL_OK) return rc;
-    if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
-    const int n_levels = ctx->host_ctl->n_levels;
     const bool vec4 = H % 4 == 0 && (((uintptr_t)h & 15) == 0);
     // gate activations of the forward that wrote these h rows, if it kept them: no contraction to recompute
     const bool kept = lstm && ctx->gates_nodes == n_nodes && ctx->gates_h == h && ctx->gates != nullptr;
     const bool kept_v4 = H % 4 == 0 && (((uintptr_t)h | (uintptr_t)c) & 15) == 0;
     f.gates = kept ? ctx->gates : nullptr;
+    // On request (tl_set_async_backward), gate gradients that need no contraction (kept activations; TreeRNN): all heights in
+    // one persistent kernel, which finds the per-height lists on the device.  Nothing is read back, the call does not wait;
+    // what the structure pass finds wrong with the batch is latched for tl_status, and every kernel below leaves at once.
+    const bool heights_on_device = ctx->async_backward && ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
+    int n_levels = 0;
+    if (heights_on_device) {
+        BwdHeights b{};
+        b.bwd4 = ctx->g_bwd_inner; b.bwd1 = ctx->g_bwd_inner1; b.ng_inner = ctx->ng_bwd_inner;
+        b.dg_int = dg_int;
+        b.kept_v4 = lstm ? (kept_v4 ? 1 : 0) : (vec4 ? 1 : 0);
+        const bool v4 = vec4 && dg_cols % 4 == 0;
+        typedef void (*bwh_kernel)(Fwd, BwdHeights);
+        const bwh_kernel k = lstm ? (v4 ? bwh_kernel(k_backward_heights<true, true>) : bwh_kernel(k_backward_heights<true, false>))
+                                  : (v4 ? bwh_kernel(k_backward_heights<false, true>) : bwh_kernel(k_backward_heights<false, false>));
+        hipLaunchKernelGGL(k, dim3(ctx->bw_grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f, b);
+    } else {
+        if ((rc = read_ctl(ctx)) != TL_OK) return rc;
+        if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
+        n_levels = ctx->host_ctl->n_levels;
+    }
     auto gate_grad_kept = [&](bool inner, const Fwd &g, const int32_t *list, int rows) {
         typedef void (*kept_kernel)(Fwd, const int32_t *, int, int);
         const kept_kernel k = inner ? (kept_v4 ? kept_kernel(k_gate_grad_kept<true, 4>) : kept_kernel(k_gate_grad_kept<true, 1>))
@@ -1341,6 +1375,13 @@ int tl_set_keep_gates(tl_ctx *ctx, int on)
     if (!ctx) return TL_EINVAL;
     ctx->keep_gates = on != 0;
     if (!ctx->keep_gates) ctx->gates_nodes = 0;
+    return TL_OK;
+}
+
+int tl_set_async_backward(tl_ctx *ctx, int on)
+{
+    if (!ctx) return TL_EINVAL;
+    ctx->async_backward = on != 0;
     return TL_OK;
 }
 

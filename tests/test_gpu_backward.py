@@ -175,6 +175,44 @@ def test_backward_from_kept_gate_activations(scheduler):
         net.close()
 
 
+@pytest.mark.parametrize("name", ["sentence", "throughput", "stress", "treernn"])
+def test_backward_that_does_not_wait_gives_the_same_bits(name):
+    """tl_set_async_backward: all heights in one persistent kernel (TreeLSTM from kept gate activations, TreeRNN), no read-back
+    of the heights.  Same contractions in the same order as the per-height launches, so the gradients that reach the leaves
+    must agree bit for bit; a malformed batch is then reported by tl_status, not by the call."""
+    print("case backward without waiting", name, flush=True)
+    w = synth.workload(name)
+    net = binding.TreeNet(w.params, scheduler="dataflow")
+    try:
+        b = net.load(w.trees)
+        binding.tl_set_keep_gates(net.ctx, True)
+        net.forward()
+        g_h = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda", generator=torch.Generator("cuda").manual_seed(3))
+        waited = {k: v.clone() for k, v in binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim).items()}
+        binding.tl_set_async_backward(net.ctx, True)
+        for _ in range(2):
+            got = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
+            assert binding.tl_status(net.ctx) == 0
+            assert set(got) == set(waited)
+            # d_x is the end of the chain of gate and operand gradients and is summed in a fixed order; the parameter
+            # gradients are added up over the nodes with atomics, in an order that differs from run to run
+            assert torch.equal(got["d_x"], waited["d_x"])
+            for k in got:
+                scale = float(waited[k].abs().max())
+                assert float((got[k] - waited[k]).abs().max()) <= 2e-5 * max(scale, 1e-6), k
+        if name == "sentence":
+            bad = dict(b)
+            bad["left"] = b["left"].clone()
+            bad["left"][w.trees.n_nodes - 1] = 0             # node 0 gets a second parent
+            binding.tl_backward(net.ctx, bad, g_h, w.params.embed_dim)
+            assert binding.tl_status(net.ctx) == binding.TL_ESTRUCT
+            binding.tl_set_async_backward(net.ctx, False)
+            with pytest.raises(RuntimeError):
+                binding.tl_backward(net.ctx, bad, g_h, w.params.embed_dim)
+    finally:
+        net.close()
+
+
 def test_backward_argument_checks():
     print("case backward arguments", flush=True)
     w = synth.workload("tiny")
