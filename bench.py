@@ -282,6 +282,7 @@ def backward_stage(w, n_classes, reps=10):
             if w.params.cell != 2:
                 # the same with a backward that does not wait for the device (all heights in one persistent kernel)
                 binding.tl_set_async_backward(net.ctx, True)
+                net.forward()                                          # (the update above has made the kept activations stale)
                 out["ms_without_waiting"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
                 out["train_step_ms_without_waiting"] = wall(train_step, reps)
                 binding.tl_set_async_backward(net.ctx, False)
