@@ -285,7 +285,11 @@ def backward_stage(w, n_classes, reps=10):
                 net.forward()                                          # (the update above has made the kept activations stale)
                 out["ms_without_waiting"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
                 out["train_step_ms_without_waiting"] = wall(train_step, reps)
-                binding.tl_set_async_backward(net.ctx, False)
+                # and with launches per height whatever the number of heights (the default takes them up to 64 heights)
+                binding.tl_set_async_backward(net.ctx, -1)
+                net.forward()
+                out["ms_launches_per_height"] = wall(lambda: binding.tl_backward(net.ctx, b, g_h, E), reps)
+                binding.tl_set_async_backward(net.ctx, 0)
             out["train_trees_per_s"] = w.trees.n_trees / (step_ms * 1e-3)
             out["train_step_note"] = ("forward (a TreeLSTM keeps its gate activations) + head backward + tree backward + SGD update "
                                       "of all parameters (embedding rows included) and re-packing of the weights")

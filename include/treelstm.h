@@ -326,14 +326,17 @@ int tl_set_keep_gates(tl_ctx *ctx, int on);
 
 /*
  * For callers that must not be held up by tl_backward (the recursion of Section 4.2.2 walked without the host):
- * with on != 0, a tl_backward that needs no contraction for its gate gradients - TreeLSTM from kept gate
+ * with on > 0, a tl_backward that needs no contraction for its gate gradients - TreeLSTM from kept gate
  * activations (tl_set_keep_gates), TreeRNN - walks all heights in one persistent kernel that finds the
- * per-height lists on the device.  Nothing is read back and the call returns without waiting; a malformed
- * batch is then reported by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results
- * as the per-height launches (same contractions in the same order).  Measured 13 % slower than those (a
- * grid barrier and device-scope traffic per height instead of a launch), hence off by default.  Like the
- * persistent schedulers of tl_forward, the kernel needs all its workgroups resident.  Other cases
- * (recomputed gates, TL_RNTN) keep the launches per height and wait as before.
+ * per-height lists on the device (TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary
+ * workgroups).  Nothing is read back and the call returns without waiting; a malformed batch is then reported
+ * by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results as the per-height launches
+ * (same contractions in the same order).  On batches of shallow trees it is measured 4 % slower than those (a
+ * grid barrier and device-scope traffic per height instead of a launch), on deep trees faster (1 024 heights:
+ * 14.4 against 16.9 ms).  Hence the default, on == 0: the call waits for the number of heights and takes the
+ * persistent kernel for more than 64 of them, launches per height otherwise.  on < 0: always launches per
+ * height.  Like the persistent schedulers of tl_forward, the kernel needs all its workgroups resident.  Other
+ * cases (recomputed gates, TL_RNTN) keep the launches per height and wait as before.
  */
 int tl_set_async_backward(tl_ctx *ctx, int on);
 

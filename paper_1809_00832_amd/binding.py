@@ -217,8 +217,9 @@ def tl_set_keep_gates(ctx, on: bool) -> None:
     _check(lib().tl_set_keep_gates(ctx, 1 if on else 0), "tl_set_keep_gates")
 
 
-def tl_set_async_backward(ctx, on: bool) -> None:
-    _check(lib().tl_set_async_backward(ctx, 1 if on else 0), "tl_set_async_backward")
+def tl_set_async_backward(ctx, on) -> None:
+    """True / 1: never waits; False / 0: the default (picks by the number of heights); -1: always launches per height."""
+    _check(lib().tl_set_async_backward(ctx, int(on)), "tl_set_async_backward")
 
 
 def tl_classify(ctx, h, w_s, b_s, probs=None, stream=None):

@@ -523,6 +523,142 @@ __global__ __launch_bounds__(WG_THREADS, 2) void k_backward_heights(Fwd f, BwdHe
     }
 }
 
+// The same walk with the operand gradient on weight-stationary workgroups (TreeLSTM from kept activations, 5 H a
+// multiple of 128).  U^T is the one matrix that every height multiplies, so a workgroup owns 16 of the 2 H output
+// columns for the whole call and keeps its slice of U^T in registers: the K axis (5 H) in four quarters, one per wave,
+// 5 H / 64 k-steps x 4 registers each (160 at H = 512).  The rows of dG are long (5 H floats), so a block of 16 rows
+// passes through LDS in two halves of each wave's quarter: while the matrix instructions of one half run, the other
+// half (or the next block's first) is on its way.  A wave adds up its quarter in k order on one accumulator, the four
+// quarters meet in LDS and are added in wave order: the order of every other data path, so the same bits.  Sets of
+// 2 H / 16 workgroups share the blocks of a height.
+template <int SPW2> struct OperandWsSmem {
+    static constexpr int A_LD = STEP_K * SPW2 + 4;          // LDS row stride of half a quarter of a row, floats
+    float a[4][16 * A_LD];
+    float red[4 * 4 * 64];                                  // [wave][v][lane]
+    int child[2][16];                                       // left / right child of the block's nodes
+    int cmd[8];
+};
+
+template <int SPW2>
+__global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, BwdHeights b)
+{
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    using Smem = OperandWsSmem<SPW2>;
+    Smem &sm = *reinterpret_cast<Smem *>(smem_raw);
+    if (batch_rejected(f)) return;
+    constexpr int NLB = SPW2;                               // row loads per lane and half: 16 rows x 4 SPW2 pieces / 64 lanes
+    constexpr int PPR = 4 * SPW2;                           // 16-byte pieces of a row in one half of a wave's quarter
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int H = f.H, K = 5 * H;
+    const int n_cg = 2 * H / HU;
+    const int cg = (int)blockIdx.x % n_cg, slot = (int)blockIdx.x / n_cg, n_slots = (int)gridDim.x / n_cg;
+    const int n_levels = f.ctl->n_levels;
+    const long long first = (long long)blockIdx.x * blockDim.x + tid, stride = (long long)gridDim.x * blockDim.x;
+    WsWeights<1, 2 * SPW2> w;
+    {                                                       // (the grid is a whole number of sets)
+        ws_load(w, b.bwd1, cg, wave, lane);
+        // the weights live in the accumulation registers (a matrix instruction takes its B operand from either file), the
+        // vector registers are for the rows in flight
+#pragma unroll
+        for (int s = 0; s < 2 * SPW2; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float x = w.b[s][0][i];
+                asm volatile("" : "+a"(x));                     // no instruction: a register-class constraint only
+                w.b[s][0][i] = x;
+            }
+    }
+    const unsigned row_b = (unsigned)K * 4u;
+    float *a_w = sm.a[wave];
+    const float *a_lane = &a_w[(lane & 15) * Smem::A_LD + (lane >> 4) * 4];
+    const __amdgpu_buffer_rsrc_t rs_dg = buf_of(b.dg_int, (unsigned long long)f.n_int * K * 4);
+    floatx4 rows[NLB];
+    // 16 rows of dG from row `base` on, half `half` of this wave's quarter.  (Rows past the end of the height are other
+    // nodes' rows, past the end of the table they read as zero; every output row depends on its own row only, and the
+    // results of such rows are dropped.)
+    // Piece j * 64 + lane of a half is piece c of row r, PPR pieces to a row: (r, c) is walked along with j instead of
+    // being kept per piece (the registers are needed for the weights and the rows in flight).
+    auto request = [&](int base, int half) {
+        const unsigned off = (unsigned)base * row_b + (unsigned)((wave * 2 + half) * SPW2 * STEP_K) * 4u;
+        int r = lane / PPR, c = lane % PPR;
+#pragma unroll
+        for (int j = 0; j < NLB; ++j) {
+            typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+            const uintx4 u = __builtin_amdgcn_raw_buffer_load_b128(rs_dg, (int)(off + (unsigned)r * row_b + (unsigned)c * 16u), 0, 16);
+            rows[j] = floatx4{__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w)};
+            c += 64;
+            r += c / PPR;
+            c %= PPR;
+        }
+    };
+    auto park = [&]() {
+        int r = lane / PPR, c = lane % PPR;
+#pragma unroll
+        for (int j = 0; j < NLB; ++j) {
+            *reinterpret_cast<floatx4 *>(&a_w[r * Smem::A_LD + c * 4]) = rows[j];
+            c += 64;
+            r += c / PPR;
+            c %= PPR;
+        }
+    };
+    unsigned epoch = 0, unused = 0;
+    Fwd g = f;
+    g.dg = b.dg_int;
+#pragma unroll 1
+    for (int lvl = n_levels - 1; lvl >= 1; --lvl) {
+        const int lo = f.level_off[lvl], n_rows = f.level_off[lvl + 1] - lo;
+        const int32_t *list = f.level_nodes + lo;
+        gate_grad_kept_rows<true, 4, true>(g, list, n_rows, lo, first, stride);         // (H % 128 == 0; the host has checked the alignment)
+        if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
+        const int n_blocks = (n_rows + 15) >> 4;
+        if (slot < n_blocks) request(lo + slot * 16, 0);
+#pragma unroll 1
+        for (int blk = slot; blk < n_blocks; blk += n_slots) {
+            const int cnt = min(16, n_rows - blk * 16);
+            if (tid < 32) {                                 // the children that this block's results are added to
+                const int r = tid & 15;
+                const int node = r < cnt ? list[blk * 16 + r] : -1;
+                sm.child[tid >> 4][r] = node < 0 ? -1 : (tid < 16 ? f.left[node] : f.right[node]);
+            }
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                park();
+                // (the last block asks for rows that nobody uses: past the end of the table they read as zero)
+                request(lo + (half == 0 ? blk : blk + n_slots) * 16, half == 0 ? 1 : 0);
+                __builtin_amdgcn_sched_barrier(0);
+                floatx4 av_next = *reinterpret_cast<const floatx4 *>(a_lane);
+#pragma unroll
+                for (int s = 0; s < SPW2; ++s) {
+                    const floatx4 av = av_next;
+                    if (s + 1 < SPW2) av_next = *reinterpret_cast<const floatx4 *>(a_lane + (s + 1) * STEP_K);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], w.b[half * SPW2 + s][0][i], acc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sm.red[(wave * 4 + v) * 64 + lane] = acc[v];
+            __syncthreads();
+            {
+                // wave w finishes accumulator row w of every group of four rows: the quarters in wave order
+                float sum = sm.red[(0 * 4 + wave) * 64 + lane];
+                sum += sm.red[(1 * 4 + wave) * 64 + lane];
+                sum += sm.red[(2 * 4 + wave) * 64 + lane];
+                sum += sm.red[(3 * 4 + wave) * 64 + lane];
+                const int row = (lane >> 4) * 4 + wave, oc = cg * HU + (lane & 15);
+                const int child = sm.child[oc < H ? 0 : 1][row];
+                if (child >= 0) {
+                    float *p = f.dh + (size_t)child * H + (oc < H ? oc : oc - H);
+                    st_dev(p, ld_dev(p) + sum);
+                }
+            }
+            __syncthreads();                                // red and child are free again
+        }
+        if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
+    }
+}
+
 // Zeroes up to six arrays in one launch (outputs and workspace of the backward pass).
 struct ZeroList {
     float *p[6];

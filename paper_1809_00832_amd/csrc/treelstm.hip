@@ -23,6 +23,7 @@ using namespace tl;
 namespace {
 
 constexpr int DEFAULT_SPIN_LIMIT = 1 << 20;
+constexpr int BW_PERSISTENT_MIN_LEVELS = 64;    // heights from which the backward pass walks them in one persistent kernel rather than in launches per height
 constexpr int FLOW_LARGE_TREE_NODES = 256;      // mean nodes per tree from which a batch of fewer trees than sets of workgroups has the device pick its kernel
 
 struct DevBuf {
@@ -69,6 +70,7 @@ struct tl_ctx {
     void *wp_bwd_inner = nullptr, *wp_bwd_leaf = nullptr, *wp_bwd_inner1 = nullptr;
     float *bp_bwd_inner = nullptr, *bp_bwd_leaf = nullptr, *bp_bwd_inner1 = nullptr;
     int bw_grid = 0;                  // workgroups of the backward kernel that walks all heights (0: per-height launches)
+    int bw_ws_grid = 0, bw_spw2 = 0;  // ... of its form with the operand gradient on weight-stationary workgroups (0: none)
     Gemm g_bwd_inner1{};              // U^T once more with one column block per group: more workgroups for heights of few rows
     Gemm g_bwd_inner{}, g_bwd_leaf{};
     int ng_bwd_inner = 1, ng_bwd_leaf = 1;    // blocks of output columns per column group of the operand-gradient contractions
@@ -83,7 +85,7 @@ struct tl_ctx {
     float *rntn_acc = nullptr;        // RNTN backward: [2d x (d * 2d + d)] weight-gradient contraction and its column sums
     int ws_steps16 = 0;
     bool keep_gates = false;          // tl_set_keep_gates
-    bool async_backward = false;      // tl_set_async_backward
+    int async_backward = 0;           // tl_set_async_backward: 1 never waits, -1 always launches per height, 0 picks by the number of heights
     float *gates = nullptr;           // [gates_cap x 5H] gate activations of the last forward that kept them
     int gates_cap = 0;
     int gates_nodes = 0;              // nodes of that forward, 0: nothing kept
@@ -717,6 +719,20 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
             if (o < o_min) o_min = o;
         }
         ctx->bw_grid = o_min * ctx->n_cu;
+        // weight-stationary operand gradient: 5 H / 128 k-steps per wave and half of its quarter of the K axis
+        ctx->bw_ws_grid = 0;
+        const int H_ = cfg->hidden, n_cg_b = 2 * H_ / HU;
+        if (cfg->cell == TL_TREELSTM && H_ % 128 == 0 && (H_ == 128 || H_ == 256 || H_ == 512) && ctx->n_cu >= n_cg_b) {
+            ctx->bw_spw2 = 5 * H_ / 128;
+            typedef void (*bwh_kernel)(Fwd, BwdHeights);
+            const bwh_kernel k = ctx->bw_spw2 == 5 ? bwh_kernel(k_backward_heights_ws<5>)
+                                 : ctx->bw_spw2 == 10 ? bwh_kernel(k_backward_heights_ws<10>) : bwh_kernel(k_backward_heights_ws<20>);
+            const size_t lds = ctx->bw_spw2 == 5 ? sizeof(OperandWsSmem<5>) : ctx->bw_spw2 == 10 ? sizeof(OperandWsSmem<10>) : sizeof(OperandWsSmem<20>);
+            if ((rc = allow_lds(k, lds)) != TL_OK) return rc;
+            int o = 0;
+            TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(k), WG_THREADS, lds));
+            if (o >= 1) ctx->bw_ws_grid = ctx->n_cu / n_cg_b * n_cg_b;
+        }
     }
     if (ctx->spw > 0) {
         ctx->ws_lds = ws_lds_bytes(ctx->spw, bf16);
@@ -1215,9 +1231,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     // On request (tl_set_async_backward), gate gradients that need no contraction (kept activations; TreeRNN): all heights in
     // one persistent kernel, which finds the per-height lists on the device.  Nothing is read back, the call does not wait;
     // what the structure pass finds wrong with the batch is latched for tl_status, and every kernel below leaves at once.
-    const bool heights_on_device = ctx->async_backward && ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
-    int n_levels = 0;
-    if (heights_on_device) {
+    const bool persistent_ok = ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
+    const bool heights_on_device = ctx->async_backward > 0 && persistent_ok;
+    auto launch_all_heights = [&]() {
         BwdHeights b{};
         b.bwd4 = ctx->g_bwd_inner; b.bwd1 = ctx->g_bwd_inner1; b.ng_inner = ctx->ng_bwd_inner;
         b.dg_int = dg_int;
@@ -1226,11 +1242,30 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         typedef void (*bwh_kernel)(Fwd, BwdHeights);
         const bwh_kernel k = lstm ? (v4 ? bwh_kernel(k_backward_heights<true, true>) : bwh_kernel(k_backward_heights<true, false>))
                                   : (v4 ? bwh_kernel(k_backward_heights<false, true>) : bwh_kernel(k_backward_heights<false, false>));
-        hipLaunchKernelGGL(k, dim3(ctx->bw_grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f, b);
+        // TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
+        const bool ws = lstm && kept_v4 && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 && (unsigned long long)n_int * 5ull * H * 4ull < (1ull << 32);
+        if (ws) {
+            const bwh_kernel kw = ctx->bw_spw2 == 5 ? bwh_kernel(k_backward_heights_ws<5>)
+                                  : ctx->bw_spw2 == 10 ? bwh_kernel(k_backward_heights_ws<10>) : bwh_kernel(k_backward_heights_ws<20>);
+            const size_t lds = ctx->bw_spw2 == 5 ? sizeof(OperandWsSmem<5>) : ctx->bw_spw2 == 10 ? sizeof(OperandWsSmem<10>) : sizeof(OperandWsSmem<20>);
+            hipLaunchKernelGGL(kw, dim3(ctx->bw_ws_grid), dim3(WG_THREADS), lds, st, f, b);
+        } else {
+            hipLaunchKernelGGL(k, dim3(ctx->bw_grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f, b);
+        }
+    };
+    int n_levels = 0;
+    if (heights_on_device) {
+        launch_all_heights();
     } else {
         if ((rc = read_ctl(ctx)) != TL_OK) return rc;
         if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
         n_levels = ctx->host_ctl->n_levels;
+        // Deep trees: two launches per height cost more than the persistent kernel's two grid barriers (a height of a few rows
+        // takes 16 us in launches, 14 in the kernel), while the wide heights of shallow trees run faster as launches of their own.
+        if (persistent_ok && ctx->async_backward == 0 && n_levels > BW_PERSISTENT_MIN_LEVELS) {
+            launch_all_heights();
+            n_levels = 0;
+        }
     }
     auto gate_grad_kept = [&](bool inner, const Fwd &g, const int32_t *list, int rows) {
         typedef void (*kept_kernel)(Fwd, const int32_t *, int, int);
@@ -1381,7 +1416,7 @@ int tl_set_keep_gates(tl_ctx *ctx, int on)
 int tl_set_async_backward(tl_ctx *ctx, int on)
 {
     if (!ctx) return TL_EINVAL;
-    ctx->async_backward = on != 0;
+    ctx->async_backward = on > 0 ? 1 : on < 0 ? -1 : 0;
     return TL_OK;
 }
 

@@ -175,22 +175,31 @@ def test_backward_from_kept_gate_activations(scheduler):
         net.close()
 
 
-@pytest.mark.parametrize("name", ["sentence", "throughput", "stress", "treernn"])
+def _workload_h128():
+    """37 trees of mixed shapes (a single leaf, chains, balanced and random trees) at H = 128: the smallest hidden size whose
+    operand gradient runs on weight-stationary workgroups."""
+    counts = [1, 2, 3, 17, 64, 100, 33] + list(synth.Stream(7, "leaves").integers(2, 60, 30))
+    shapes = ["random", "chain", "balanced", "chain", "balanced", "random", "chain"] + ["random"] * 30
+    return synth.Workload("h128", synth.make_trees(7, counts, shapes, 1000), synth.make_treelstm_params(7, 1000, 64, 128, "xavier"))
+
+
+@pytest.mark.parametrize("name", ["sentence", "throughput", "stress", "treernn", "h128"])
 def test_backward_that_does_not_wait_gives_the_same_bits(name):
     """tl_set_async_backward: all heights in one persistent kernel (TreeLSTM from kept gate activations, TreeRNN), no read-back
     of the heights.  Same contractions in the same order as the per-height launches, so the gradients that reach the leaves
     must agree bit for bit; a malformed batch is then reported by tl_status, not by the call."""
     print("case backward without waiting", name, flush=True)
-    w = synth.workload(name)
+    w = _workload_h128() if name == "h128" else synth.workload(name)
     net = binding.TreeNet(w.params, scheduler="dataflow")
     try:
         b = net.load(w.trees)
         binding.tl_set_keep_gates(net.ctx, True)
         net.forward()
         g_h = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda", generator=torch.Generator("cuda").manual_seed(3))
+        binding.tl_set_async_backward(net.ctx, -1)           # launches per height whatever the number of heights
         waited = {k: v.clone() for k, v in binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim).items()}
-        binding.tl_set_async_backward(net.ctx, True)
-        for _ in range(2):
+        for mode in (1, 0):                                  # 0: the default picks the kernel by the number of heights
+            binding.tl_set_async_backward(net.ctx, mode)
             got = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)
             assert binding.tl_status(net.ctx) == 0
             assert set(got) == set(waited)
@@ -200,10 +209,16 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
             for k in got:
                 scale = float(waited[k].abs().max())
                 assert float((got[k] - waited[k]).abs().max()) <= 2e-5 * max(scale, 1e-6), k
+        if name == "h128":                                   # this size against the checker as well, through the call that does not wait
+            g = g_h.cpu().numpy()
+            ref = oracle.backward(w.params, w.trees, b["h"].cpu().numpy(), b["c"].cpu().numpy(), g)
+            for k in ref:
+                assert_grad_close(got[k].cpu().numpy(), ref[k], "h128 without waiting %s" % k)
         if name == "sentence":
             bad = dict(b)
             bad["left"] = b["left"].clone()
             bad["left"][w.trees.n_nodes - 1] = 0             # node 0 gets a second parent
+            binding.tl_set_async_backward(net.ctx, 1)
             binding.tl_backward(net.ctx, bad, g_h, w.params.embed_dim)
             assert binding.tl_status(net.ctx) == binding.TL_ESTRUCT
             binding.tl_set_async_backward(net.ctx, False)
