@@ -94,6 +94,7 @@ __global__ void k_reset(Fwd f, int with_levels)
     size_t total = (size_t)N + 1;
     if (total < ctl_words) total = ctl_words;
     if (total < gang_words) total = gang_words;
+    if (f.rntn_done && total < (size_t)f.rntn_units * f.n_cg) total = (size_t)f.rntn_units * f.n_cg;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         if (i < (size_t)N) {
             f.parent[i] = -1;

@@ -771,10 +771,11 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
     }
 
     if (cfg->cell == TL_RNTN) {
-        // frontiers of so few tiles that half the workgroups would idle are cut into parts (cell_rntn.hpp);
-        // one unit of the scratch area per tile of such a frontier
+        // frontiers of so few tiles that whole tiles would give the workgroups fewer than two rounds of work are cut into
+        // parts (cell_rntn.hpp): with whole tiles the last, partly filled round and the two workgroups that share a CU's matrix
+        // units decide the time of such a frontier.  One unit of the scratch area per tile of such a frontier
         const int grid = ctx->persistent_grid > ctx->ws_grid ? ctx->persistent_grid : ctx->ws_grid;
-        const int units = grid / (2 * ctx->n_cg);
+        const int units = 2 * grid / ctx->n_cg;
         if (units > 0) {
             const size_t per_unit = (size_t)ctx->n_cg * RNTN_PARTS * RNTN_PART_FLOATS * sizeof(float);
             TL_HIP(hipMalloc(&ctx->rntn_part, units * per_unit));
@@ -946,7 +947,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
     f.cap_tiles = grid_p / ctx->n_cg > 0 ? grid_p / ctx->n_cg : 1;
     // RNTN: a frontier of at most rntn_units tiles is cut into RNTN_PARTS workgroups per tile and column group
     f.rntn_part = ctx->rntn_part; f.rntn_done = ctx->rntn_done;
-    f.rntn_units = cfg.cell == TL_RNTN ? (grid_p / (2 * ctx->n_cg) < ctx->rntn_units ? grid_p / (2 * ctx->n_cg) : ctx->rntn_units) : 0;
+    f.rntn_units = cfg.cell == TL_RNTN ? (2 * grid_p / ctx->n_cg < ctx->rntn_units ? 2 * grid_p / ctx->n_cg : ctx->rntn_units) : 0;
     // ready scheduler: gangs of gang_size compute workgroups plus one scheduler workgroup each
     f.gang_size = ctx->n_cg + 1 <= grid_p ? ctx->n_cg : grid_p - 1;
     f.n_gangs = grid_p / (f.gang_size + 1) < MAX_GANGS ? grid_p / (f.gang_size + 1) : MAX_GANGS;
