@@ -57,6 +57,13 @@ __global__ void k_pack_rntn(const float *__restrict__ v, const float *__restrict
 // groups, and a block of 16 rows costs 129 slices x 32 MFMAs whatever the number of rows.
 constexpr int RNTN_PARTS = 4;
 constexpr int RNTN_PART_FLOATS = TILE_ROWS * HU;            // one part of one tile and column group in the scratch area
+// Tiles that the grid works on at once when a tile and column group is shared by RNTN_PARTS workgroups: a frontier is cut
+// (plan_level) so that its tiles fill one round of the grid where they can - a second round of small tiles costs a whole
+// item's latency more (records, child rows, first slice, exchange, scratch area), taller tiles only their matrix instructions.
+__host__ __device__ inline int rntn_cap_tiles(int cap_tiles, int rntn_units)
+{
+    return rntn_units > 0 && cap_tiles >= RNTN_PARTS ? cap_tiles / RNTN_PARTS : cap_tiles;
+}
 
 template <int NS, bool VEC4, bool COH>
 __device__ inline void rntn_tile(TileSmem &sm, const Fwd &f, const Gemm &gm, int count, int cg)

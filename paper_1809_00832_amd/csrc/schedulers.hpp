@@ -343,7 +343,7 @@ __global__ __launch_bounds__(WG_THREADS, (SPW > 0 && !BF16) ? 1 : 2) void k_leve
                 if (j_mine >= 0) appended += frontier_push(f, ticket);
             }
         } else {
-            const LevelPlan plan = plan_level(rows, f.cap_tiles);
+            const LevelPlan plan = plan_level(rows, EPI == EPI_RNTN_INNER ? rntn_cap_tiles(f.cap_tiles, f.rntn_units) : f.cap_tiles);
             // tile T of a frontier: its rows' parents are looked after by the workgroup that computes
             // column group T % n_cg of it
             const int parts = (EPI == EPI_RNTN_INNER && plan.n_tiles <= f.rntn_units) ? RNTN_PARTS : 1;

@@ -1065,7 +1065,7 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
                 for (int lvl = 1; lvl < n_levels; ++lvl) {
                     const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
                     if (rows <= 0 || lo < 0 || lo + rows > f.n_int) return TL_EHIP;
-                    const LevelPlan plan = plan_level(rows, f.cap_tiles);
+                    const LevelPlan plan = plan_level(rows, cfg.cell == TL_RNTN ? rntn_cap_tiles(f.cap_tiles, f.rntn_units) : f.cap_tiles);
                     const int parts = plan.n_tiles <= f.rntn_units ? RNTN_PARTS : 1;
                     hipLaunchKernelGGL(static_kernel(inner_epi, vec4_inner, bf16), dim3(plan.n_tiles * ctx->n_cg * parts), dim3(WG_THREADS),
                                        TILE_SMEM_BYTES, st, f, (const int32_t *)(f.level_nodes + lo), rows, plan);
