@@ -23,6 +23,7 @@ using namespace tl;
 namespace {
 
 constexpr int DEFAULT_SPIN_LIMIT = 1 << 20;
+constexpr int LEVELS_AHEAD = 66;                // offsets of the per-height lists read back before the number of heights is known
 constexpr int BW_PERSISTENT_MIN_LEVELS = 64;    // heights from which the backward pass walks them in one persistent kernel rather than in launches per height
 constexpr int FLOW_LARGE_TREE_NODES = 256;      // mean nodes per tree from which a batch of fewer trees than sets of workgroups has the device pick its kernel
 
@@ -802,9 +803,13 @@ void td_free(tl_td_ctx *ctx)
     delete ctx;
 }
 
-int read_ctl(tl_ctx *ctx)
+// levels > 0: the first `levels` offsets of the per-height lists come along in the same wait (shallow batches then need no
+// second round trip for them).
+int read_ctl(tl_ctx *ctx, int levels = 0)
 {
     TL_HIP(hipMemcpyAsync(ctx->host_ctl, ctx->last.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, ctx->last_stream));
+    if (levels > 0)
+        TL_HIP(hipMemcpyAsync(ctx->host_levels, ctx->last.level_off, (size_t)levels * 4, hipMemcpyDeviceToHost, ctx->last_stream));
     TL_HIP(hipStreamSynchronize(ctx->last_stream));
     // a tree without a root shows as a root count below the number of trees
     if (ctx->host_ctl->status == 0 && !ctx->last.flow_roots && ctx->host_ctl->n_roots != ctx->last.n_trees) ctx->host_ctl->status = TL_ESTRUCT;
@@ -1056,11 +1061,14 @@ int forward_impl(tl_ctx *ctx, bool static_ws, int n_trees, int n_nodes, const in
             ctx->last_grid = grid_l;
         } else {
             // the host needs the number of heights and the offsets of their node lists
-            if ((rc = read_ctl(ctx)) != TL_OK) return rc;
+            const int levels_ahead = n_nodes + 2 < LEVELS_AHEAD ? n_nodes + 2 : LEVELS_AHEAD;
+            if ((rc = read_ctl(ctx, levels_ahead)) != TL_OK) return rc;
             const int n_levels = ctx->host_ctl->status == 0 ? ctx->host_ctl->n_levels : 0;
             if (n_levels > 1) {
-                TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
-                TL_HIP(hipStreamSynchronize(st));
+                if (n_levels + 1 > levels_ahead) {
+                    TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
+                    TL_HIP(hipStreamSynchronize(st));
+                }
                 int max_grid = 0;
                 for (int lvl = 1; lvl < n_levels; ++lvl) {
                     const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
@@ -1255,10 +1263,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         }
     };
     int n_levels = 0;
+    const int levels_ahead = n_nodes + 2 < LEVELS_AHEAD ? n_nodes + 2 : LEVELS_AHEAD;   // offsets read back together with the control block
     if (heights_on_device) {
         launch_all_heights();
     } else {
-        if ((rc = read_ctl(ctx)) != TL_OK) return rc;
+        if ((rc = read_ctl(ctx, levels_ahead)) != TL_OK) return rc;
         if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
         n_levels = ctx->host_ctl->n_levels;
         // Deep trees: two launches per height cost more than the persistent kernel's two grid barriers (a height of a few rows
@@ -1277,8 +1286,10 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(256), 0, st, g, list, rows, g.pos0);
     };
     if (n_levels > 1) {
-        TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
-        TL_HIP(hipStreamSynchronize(st));
+        if (n_levels + 1 > levels_ahead) {
+            TL_HIP(hipMemcpyAsync(ctx->host_levels, f.level_off, (size_t)(n_levels + 1) * 4, hipMemcpyDeviceToHost, st));
+            TL_HIP(hipStreamSynchronize(st));
+        }
         for (int lvl = n_levels - 1; lvl >= 1; --lvl) {     // roots first: a parent is always higher than its children
             const int lo = ctx->host_levels[lvl], rows = ctx->host_levels[lvl + 1] - lo;
             if (rows <= 0 || lo < 0 || lo + rows > n_int) return TL_EHIP;
