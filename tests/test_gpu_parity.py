@@ -400,6 +400,28 @@ def test_rntn_other_sizes(sched):
             net.close()
 
 
+@pytest.mark.parametrize("sched", ["level_device", "level_host", "ready"])
+def test_rntn_wide_frontiers(sched):
+    """RNTN, d = 64, 34 balanced trees of 1 024 leaves and three others: heights of 17 700, 8 900, 4 400 ... rows, so that every way a
+    frontier is cut is taken - whole tiles with one workgroup per column group (more tiles than the scratch area has units),
+    rounds of whole tiles plus a round of smaller ones shared by four workgroups per column group, one round of small tiles."""
+    say("case rntn wide", sched)
+    d = 64
+    p = synth.make_rnn_params(77, synth.CELL_RNTN, 300, d, scale=0.05)
+    p = synth.Params(p.cell, p.vocab, d, d, p.emb * 8, None, None, p.u * 2, p.b + 0.05, p.v * (40.0 / d))
+    trees = synth.make_trees(77, [1024] * 34 + [700, 3, 1], ["balanced"] * 34 + ["random"] * 3, 300)
+    if "rntn wide" not in _ref_cache:
+        _ref_cache["rntn wide"] = oracle.forward_params(p, trees, n_threads=8)
+    net = binding.TreeNet(p, scheduler=sched)
+    try:
+        got = net.run(trees)
+        check_against_oracle(p, trees, got, _ref_cache["rntn wide"], "rntn wide/%s" % sched)
+        again = net.run(trees)
+        assert np.array_equal(got["h"], again["h"])
+    finally:
+        net.close()
+
+
 @pytest.mark.parametrize("sched", ["dataflow", "level_device", "ready"])
 def test_two_contexts_on_two_streams_ordered_by_events(sched):
     """The documented way to use several contexts on one device: their forwards (persistent kernels that need the
