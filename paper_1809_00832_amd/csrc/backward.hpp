@@ -572,13 +572,15 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
     float *a_w = sm.a[wave];
     const float *a_lane = &a_w[(lane & 15) * Smem::A_LD + (lane >> 4) * 4];
     const __amdgpu_buffer_rsrc_t rs_dg = buf_of(b.dg_int, (unsigned long long)f.n_int * K * 4);
-    floatx4 rows[NLB];
+    // Rows in flight: one set of registers per half, so that a half is requested a whole block (both halves' matrix
+    // instructions) before it is parked - the latency of a request is longer than one half's matrix instructions.
+    floatx4 rows0[NLB], rows1[NLB];
     // 16 rows of dG from row `base` on, half `half` of this wave's quarter.  (Rows past the end of the height are other
     // nodes' rows, past the end of the table they read as zero; every output row depends on its own row only, and the
     // results of such rows are dropped.)
     // Piece j * 64 + lane of a half is piece c of row r, PPR pieces to a row: (r, c) is walked along with j instead of
     // being kept per piece (the registers are needed for the weights and the rows in flight).
-    auto request = [&](int base, int half) {
+    auto request = [&](floatx4 (&rows)[NLB], int base, int half) {
         const unsigned off = (unsigned)base * row_b + (unsigned)((wave * 2 + half) * SPW2 * STEP_K) * 4u;
         int r = lane / PPR, c = lane % PPR;
 #pragma unroll
@@ -591,7 +593,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
             c %= PPR;
         }
     };
-    auto park = [&]() {
+    auto park = [&](const floatx4 (&rows)[NLB]) {
         int r = lane / PPR, c = lane % PPR;
 #pragma unroll
         for (int j = 0; j < NLB; ++j) {
@@ -611,7 +613,10 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
         gate_grad_kept_rows<true, 4, true>(g, list, n_rows, lo, first, stride);         // (H % 128 == 0; the host has checked the alignment)
         if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
         const int n_blocks = (n_rows + 15) >> 4;
-        if (slot < n_blocks) request(lo + slot * 16, 0);
+        if (slot < n_blocks) {
+            request(rows0, lo + slot * 16, 0);
+            request(rows1, lo + slot * 16, 1);
+        }
 #pragma unroll 1
         for (int blk = slot; blk < n_blocks; blk += n_slots) {
             const int cnt = min(16, n_rows - blk * 16);
@@ -623,9 +628,14 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                park();
                 // (the last block asks for rows that nobody uses: past the end of the table they read as zero)
-                request(lo + (half == 0 ? blk : blk + n_slots) * 16, half == 0 ? 1 : 0);
+                if (half == 0) {
+                    park(rows0);
+                    request(rows0, lo + (blk + n_slots) * 16, 0);
+                } else {
+                    park(rows1);
+                    request(rows1, lo + (blk + n_slots) * 16, 1);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 floatx4 av_next = *reinterpret_cast<const floatx4 *>(a_lane);
 #pragma unroll
