@@ -96,6 +96,7 @@ struct tl_ctx {
     // profiling
     int profiling = 0;
     hipEvent_t ev[TL_PROFILE_RING][TL_N_STAGES]{};   // created on first use
+    hipEvent_t ev_ctl = nullptr;      // tl_backward: behind the copy of the structure pass's verdict, in front of the kernels that do not need the host
     long long n_recorded = 0;                        // forwards recorded since profiling was switched on
 };
 
@@ -566,6 +567,7 @@ void free_all(tl_ctx *ctx)
     for (auto &set : ctx->ev)
         for (auto &e : set)
             if (e) (void)hipEventDestroy(e);
+    if (ctx->ev_ctl) (void)hipEventDestroy(ctx->ev_ctl);
     delete ctx;
 }
 
@@ -1241,6 +1243,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     // one persistent kernel, which finds the per-height lists on the device.  Nothing is read back, the call does not wait;
     // what the structure pass finds wrong with the batch is latched for tl_status, and every kernel below leaves at once.
     const bool persistent_ok = ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
+    // TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
+    const bool ws = persistent_ok && lstm && kept_v4 && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 &&
+                    (unsigned long long)n_int * 5ull * H * 4ull < (1ull << 32);
     const bool heights_on_device = ctx->async_backward > 0 && persistent_ok;
     auto launch_all_heights = [&]() {
         BwdHeights b{};
@@ -1251,8 +1256,6 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         typedef void (*bwh_kernel)(Fwd, BwdHeights);
         const bwh_kernel k = lstm ? (v4 ? bwh_kernel(k_backward_heights<true, true>) : bwh_kernel(k_backward_heights<true, false>))
                                   : (v4 ? bwh_kernel(k_backward_heights<false, true>) : bwh_kernel(k_backward_heights<false, false>));
-        // TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
-        const bool ws = lstm && kept_v4 && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 && (unsigned long long)n_int * 5ull * H * 4ull < (1ull << 32);
         if (ws) {
             const bwh_kernel kw = ctx->bw_spw2 == 5 ? bwh_kernel(k_backward_heights_ws<5>)
                                   : ctx->bw_spw2 == 10 ? bwh_kernel(k_backward_heights_ws<10>) : bwh_kernel(k_backward_heights_ws<20>);
@@ -1264,7 +1267,17 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     };
     int n_levels = 0;
     const int levels_ahead = n_nodes + 2 < LEVELS_AHEAD ? n_nodes + 2 : LEVELS_AHEAD;   // offsets read back together with the control block
+    bool verdict_pending = false;
     if (heights_on_device) {
+        launch_all_heights();
+    } else if (ws && ctx->async_backward == 0) {
+        // The weight-stationary form is the faster one whatever the number of heights, and needs nothing from the host: the
+        // structure pass's verdict is copied out in front of it, everything is enqueued, and the call then waits for that copy
+        // alone (the device works on meanwhile) to return the verdict as it always has.
+        if (!ctx->ev_ctl) TL_HIP(hipEventCreateWithFlags(&ctx->ev_ctl, hipEventDisableTiming));
+        TL_HIP(hipMemcpyAsync(ctx->host_ctl, f.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+        TL_HIP(hipEventRecord(ctx->ev_ctl, st));
+        verdict_pending = true;
         launch_all_heights();
     } else {
         if ((rc = read_ctl(ctx, levels_ahead)) != TL_OK) return rc;
@@ -1371,6 +1384,11 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                            d_b_leaf);
     }
     TL_HIP(hipGetLastError());
+    if (verdict_pending) {
+        TL_HIP(hipEventSynchronize(ctx->ev_ctl));
+        if (ctx->host_ctl->status == 0 && !f.flow_roots && ctx->host_ctl->n_roots != n_trees) ctx->host_ctl->status = TL_ESTRUCT;
+        if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;
+    }
     return TL_OK;
 }
 

@@ -214,6 +214,18 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
             ref = oracle.backward(w.params, w.trees, b["h"].cpu().numpy(), b["c"].cpu().numpy(), g)
             for k in ref:
                 assert_grad_close(got[k].cpu().numpy(), ref[k], "h128 without waiting %s" % k)
+        if name == "h128":
+            # default mode at a size of the weight-stationary form: everything is enqueued before the call waits for the
+            # structure pass's verdict, which it still returns
+            bad = dict(b)
+            bad["left"] = b["left"].clone()
+            bad["left"][w.trees.n_nodes - 1] = 0             # the last leaf gets one child, and that in another tree
+            binding.tl_set_async_backward(net.ctx, 0)
+            with pytest.raises(RuntimeError):
+                binding.tl_backward(net.ctx, bad, g_h, w.params.embed_dim)
+            assert binding.tl_status(net.ctx) == binding.TL_ESTRUCT
+            again = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)        # and the context goes on
+            assert torch.equal(again["d_x"], waited["d_x"])
         if name == "sentence":
             bad = dict(b)
             bad["left"] = b["left"].clone()
