@@ -84,7 +84,9 @@ __device__ inline void bwd_epilogue(const TileSmem &sm, const Fwd &f, const Gemm
                 if constexpr (INNER) {
                     const int child = oc < H ? f.left[node] : f.right[node];
                     float *p = f.dh + (size_t)child * H + (oc < H ? oc : oc - H);
-                    st_f<COH>(p, ld_f<COH>(p) + acc[g][v]);
+                    // one contribution per element (a node has one parent): inside a persistent kernel it is added at the memory side
+                    if constexpr (COH) (void)add_dev(p, acc[g][v]);
+                    else *p += acc[g][v];
                 } else {
                     f.d_x[(size_t)node * f.E + oc] = acc[g][v];
                 }
@@ -659,8 +661,10 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
                 const int row = (lane >> 4) * 4 + wave, oc = cg * HU + (lane & 15);
                 const int child = sm.child[oc < H ? 0 : 1][row];
                 if (child >= 0) {
+                    // (one contribution per element, from the node's only parent: an addition at the memory side gives the bits
+                    // of load, add, store, and the wave does not wait for a load behind the rows it has requested ahead)
                     float *p = f.dh + (size_t)child * H + (oc < H ? oc : oc - H);
-                    st_dev(p, ld_dev(p) + sum);
+                    (void)add_dev(p, sum);
                 }
             }
             __syncthreads();                                // red and child are free again
