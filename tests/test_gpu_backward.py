@@ -209,6 +209,18 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
             for k in got:
                 scale = float(waited[k].abs().max())
                 assert float((got[k] - waited[k]).abs().max()) <= 2e-5 * max(scale, 1e-6), k
+        # another upstream gradient through the same context and workspace: nothing of the first call's intermediate rows may
+        # be seen again (the persistent kernel reads them through the caches)
+        g_h2 = torch.randn((w.trees.n_nodes, w.params.hidden), device="cuda", generator=torch.Generator("cuda").manual_seed(4))
+        binding.tl_set_async_backward(net.ctx, -1)
+        waited2 = {k: v.clone() for k, v in binding.tl_backward(net.ctx, b, g_h2, w.params.embed_dim).items()}
+        for mode in (1, 0):
+            binding.tl_set_async_backward(net.ctx, mode)
+            got2 = binding.tl_backward(net.ctx, b, g_h2, w.params.embed_dim)
+            assert torch.equal(got2["d_x"], waited2["d_x"])
+            assert not torch.equal(got2["d_x"], waited["d_x"])
+            got = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)       # and back
+            assert torch.equal(got["d_x"], waited["d_x"])
         if name == "h128":                                   # this size against the checker as well, through the call that does not wait
             g = g_h.cpu().numpy()
             ref = oracle.backward(w.params, w.trees, b["h"].cpu().numpy(), b["c"].cpu().numpy(), g)
