@@ -221,6 +221,11 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
             assert not torch.equal(got2["d_x"], waited["d_x"])
             got = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)       # and back
             assert torch.equal(got["d_x"], waited["d_x"])
+        if name in ("throughput", "h128", "treernn"):         # twenty more calls of the persistent kernel: the same bits every time
+            binding.tl_set_async_backward(net.ctx, 1)
+            for _ in range(20):
+                assert torch.equal(binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)["d_x"], waited["d_x"])
+            assert binding.tl_status(net.ctx) == 0
         if name == "h128":                                   # this size against the checker as well, through the call that does not wait
             g = g_h.cpu().numpy()
             ref = oracle.backward(w.params, w.trees, b["h"].cpu().numpy(), b["c"].cpu().numpy(), g)
