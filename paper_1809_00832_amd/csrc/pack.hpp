@@ -74,6 +74,51 @@ __global__ void k_pack_bias(const float *__restrict__ b, float *__restrict__ bp,
     }
 }
 
+// Several fp32 matrices packed over in one launch (the re-packing after a parameter update: the buffers exist, only their
+// contents change).  A job is what k_pack_f32 and k_pack_bias do for one matrix; element (row, col) of the matrix to pack
+// is src[row * rs + col * cs], so the transposed matrices of the backward pass are read straight from the parameters
+// (rs = 1, cs = number of rows) with no transposed copy in between.
+struct PackJob {
+    const float *w;
+    float *wp;
+    const float *b;         // null: the bias is not touched (the backward pass's contractions have none)
+    float *bp;
+    int NG, H, SEG, L, Lp, n_steps, n_cg;
+    long long rs, cs;
+};
+constexpr int PACK_JOBS = 6;
+struct PackList {
+    PackJob job[PACK_JOBS];
+    int n;
+};
+__global__ void k_pack_many(PackList pl)
+{
+    for (int a = 0; a < pl.n; ++a) {
+        const PackJob &j = pl.job[a];
+        const size_t total = (size_t)j.n_cg * j.n_steps * j.NG * 64 * 4;
+        for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+            const int i = (int)(e & 3), lane = (int)((e >> 2) & 63);
+            size_t r = e >> 8;
+            const int g = (int)(r % j.NG);
+            r /= j.NG;
+            const int s = (int)(r % j.n_steps), cg = (int)(r / j.n_steps);
+            const int k = 16 * s + 4 * (lane >> 4) + i, hu = cg * HU + (lane & 15);
+            const int seg = k / j.Lp, off = k - seg * j.Lp;
+            float v = 0.f;
+            if (seg < j.SEG && off < j.L && hu < j.H) v = j.w[(long long)(seg * j.L + off) * j.rs + (long long)(g * j.H + hu) * j.cs];
+            j.wp[e] = v;
+        }
+        if (j.b) {
+            const int nb = j.n_cg * j.NG * HU;
+            for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < nb; e += gridDim.x * blockDim.x) {
+                const int q = e % HU, g = (e / HU) % j.NG, cg = e / (HU * j.NG);
+                const int hu = cg * HU + q;
+                j.bp[e] = hu < j.H ? j.b[g * j.H + hu] : 0.f;
+            }
+        }
+    }
+}
+
 // bf16 copy of a row-major table with rows padded to Ls elements (pads zero)
 __global__ void k_pad_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, size_t rows, int L, int Ls)
 {

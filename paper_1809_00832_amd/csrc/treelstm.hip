@@ -376,6 +376,44 @@ int pack_treelstm_f32(tl_ctx *ctx, hipStream_t st)
     return TL_OK;
 }
 
+// One job of k_pack_many for a matrix that pack_gemm has packed before (g says how): [SEG * L x NG * H], from w as it is
+// stored (row-major) or, transposed = true, from the stored [NG * H x SEG * L] matrix whose transpose it is.
+PackJob repack_job(const Gemm &g, const float *w, const float *b, float *bp, int NG, int H, int SEG, int n_cg, bool transposed)
+{
+    PackJob j{};
+    j.w = w; j.wp = (float *)const_cast<void *>(g.wp); j.b = b; j.bp = bp;
+    j.NG = NG; j.H = H; j.SEG = SEG; j.L = g.L; j.Lp = g.Lp; j.n_steps = g.n_chunks * (KC / STEP_K); j.n_cg = n_cg;
+    j.rs = transposed ? 1 : (long long)NG * H;
+    j.cs = transposed ? (long long)SEG * g.L : 1;
+    return j;
+}
+
+// After a parameter update of an fp32 TreeLSTM or TreeRNN context: everything pack_treelstm_f32 / pack_treernn_f32 derive
+// from the parameters, packed over in one launch.
+int repack_f32(tl_ctx *ctx, hipStream_t st)
+{
+    const int H = ctx->cfg.hidden, E = ctx->cfg.embed_dim;
+    const bool lstm = ctx->cfg.cell == TL_TREELSTM;
+    const int ng_cell = lstm ? 5 : 1;
+    if (!ctx->wp_inner || !ctx->wp_bwd_inner || (lstm && (!ctx->wp_leaf || !ctx->wp_bwd_leaf))) return TL_EINVAL;
+    PackList pl{};
+    int n = 0;
+    if (lstm) pl.job[n++] = repack_job(ctx->g_leaf, ctx->m_w_leaf, ctx->m_b_leaf, ctx->bp_leaf, 3, H, 1, ctx->n_cg, false);
+    pl.job[n++] = repack_job(ctx->g_inner, ctx->m_u, ctx->m_b, ctx->bp_inner, ng_cell, H, 2, ctx->n_cg, false);
+    // backward pass: U^T [ng_cell H x 2H] and W_leaf^T [3H x E]
+    pl.job[n++] = repack_job(ctx->g_bwd_inner, ctx->m_u, nullptr, nullptr, ctx->ng_bwd_inner, 2 * H / ctx->ng_bwd_inner, 1,
+                             (2 * H / ctx->ng_bwd_inner + HU - 1) / HU, true);
+    if (ctx->ng_bwd_inner == 4)
+        pl.job[n++] = repack_job(ctx->g_bwd_inner1, ctx->m_u, nullptr, nullptr, 1, 2 * H, 1, (2 * H + HU - 1) / HU, true);
+    if (lstm)
+        pl.job[n++] = repack_job(ctx->g_bwd_leaf, ctx->m_w_leaf, nullptr, nullptr, ctx->ng_bwd_leaf, E / ctx->ng_bwd_leaf, 1,
+                                 (E / ctx->ng_bwd_leaf + HU - 1) / HU, true);
+    pl.n = n;
+    hipLaunchKernelGGL(k_pack_many, dim3(2048), dim3(256), 0, st, pl);
+    TL_HIP(hipGetLastError());
+    return TL_OK;
+}
+
 // The same for an fp32 TreeRNN context: forward weights and W^T of the backward pass.
 int pack_treernn_f32(tl_ctx *ctx, hipStream_t st)
 {
@@ -1413,7 +1451,7 @@ int tl_sgd_update(tl_ctx *ctx, float lr, int n_nodes, const int32_t *left, const
     if (d_x) hipLaunchKernelGGL(k_sgd_embedding, dim3(1024), dim3(256), 0, st, ctx->emb, d_x, left, word, n_nodes, E, cfg.vocab, lr);
     TL_HIP(hipGetLastError());
     ctx->gates_nodes = 0;             // what a forward kept belongs to the old parameters
-    return lstm ? pack_treelstm_f32(ctx, st) : rntn ? pack_rntn_f32(ctx, st) : pack_treernn_f32(ctx, st);
+    return rntn ? pack_rntn_f32(ctx, st) : repack_f32(ctx, st);
 }
 
 int tl_get_params(tl_ctx *ctx, float *u, float *b, float *w_leaf, float *b_leaf, float *emb, void *hip_stream)
