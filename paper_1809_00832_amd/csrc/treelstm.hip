@@ -1390,9 +1390,12 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         g.bwd = ctx->g_bwd_leaf;
         g.out_cols = E;
         g.n_cg = (E / ctx->ng_bwd_leaf + HU - 1) / HU;
+        // this contraction has few column groups (E = 300: five), so a round of the device's workgroups (two per CU) takes
+        // more tiles than one of the forward's: the leaves are cut for that round, else a few tiles too many cost a second one
+        const LevelPlan plan_op = plan_level(n_leaf, 2 * ctx->n_cu / g.n_cg > 0 ? 2 * ctx->n_cu / g.n_cg : 1);
         hipLaunchKernelGGL(backward_kernel(ctx->ng_bwd_leaf == 4 ? EPI_BWD_LEAF_OPERAND4 : EPI_BWD_LEAF_OPERAND, H % 4 == 0),
-                           dim3(plan.n_tiles * g.n_cg), dim3(WG_THREADS),
-                           TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan);
+                           dim3(plan_op.n_tiles * g.n_cg), dim3(WG_THREADS),
+                           TILE_SMEM_BYTES, st, g, (const int32_t *)f.leaf_list, n_leaf, plan_op);
     }
     // weight and bias gradients: contractions over all nodes, the node axis cut into slices so that a few
     // thousand workgroups are in flight
