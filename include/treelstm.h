@@ -274,9 +274,10 @@ int tl_last_stats(tl_ctx *ctx, int *n_levels, int *n_tiles, int *n_workgroups);
  * fp32 arithmetic; the TreeLSTM gate activations are recomputed from h / c unless the forward
  * kept them (tl_set_keep_gates); TreeRNN and RNTN need nothing but h.  The RNTN path is a first
  * version: it materialises a row of d * 2d + d values per internal node (workspace of that size).
- * Work is enqueued on hip_stream, but the call waits for the structure pass (it needs the
- * number of heights and their sizes for its launches, one pair per height) and returns the deferred
- * structure status: TL_OK, TL_ESTRUCT, ...  With tl_set_async_backward it does not wait.
+ * Work is enqueued on hip_stream, but the call waits for the structure pass and returns the deferred
+ * structure status: TL_OK, TL_ESTRUCT, ... (where the heights are walked by launches, one pair per height,
+ * it needs their number and sizes first; where one persistent kernel walks them, it has enqueued all its
+ * work by then and the device is not held up).  With tl_set_async_backward(ctx, 1) it does not wait.
  * The first call for a larger batch than any before allocates workspace (TL_ENOMEM if the RNTN
  * rows would take more than 64 GiB).  TL_BF16_IN: TL_EINVAL.
  */
