@@ -298,7 +298,7 @@ def backward_stage(w, n_classes, reps=10):
         net.close()
 
 
-def topdown_bench(steps, warmup, with_cpu):
+def topdown_rows(steps, warmup, with_cpu):
     """Top-down generation of dynamically structured trees (the experiment of Table 3: batch sizes 1 and 64): instances
     per second of tl_td_generate with the root states resident, kernel time from events on the launch stream, the
     algorithmic flops (8 H^2 per generated child plus 2 H per scored node) and the dependent frontiers that bound it."""
@@ -343,8 +343,15 @@ def topdown_bench(steps, warmup, with_cpu):
             rows.append(row)
         finally:
             binding.tl_td_destroy(ctx)
-    print(json.dumps({"topdown": rows, "dtype": "f32", "data": "synthetic",
-                      "note": "tl_td_generate, root states resident; td64: breadth first, two grid barriers per depth; td1 (batches of up to 32 roots): no frontiers, children computed while the parent is scored"}))
+    return rows
+
+
+TOPDOWN_NOTE = ("tl_td_generate, root states resident; td64: breadth first, two grid barriers per depth; td1 (batches of up to 32 "
+                "roots): no frontiers, children computed while the parent is scored")
+
+
+def topdown_bench(steps, warmup, with_cpu):
+    print(json.dumps({"topdown": topdown_rows(steps, warmup, with_cpu), "dtype": "f32", "data": "synthetic", "note": TOPDOWN_NOTE}))
 
 
 def other_configs(steps, warmup):
@@ -531,6 +538,11 @@ def main():
         out["comparison"] = comp
     if not args.no_others and args.workload == "throughput" and args.precision == "f32":
         out["other_configs"] = other_configs(args.steps, args.warmup)
+        if "backward" not in out:
+            # the backward pass and a training step on the same batch (a few calls each: a fraction of a second)
+            out["training"] = backward_stage(w, args.head if args.head > 0 else 5)
+        # top-down generation of dynamically structured trees (batches of 64 roots and of one), a few calls each
+        out["topdown"] = {"rows": topdown_rows(min(args.steps, 20), min(args.warmup, 5), False), "note": TOPDOWN_NOTE}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
