@@ -333,10 +333,10 @@ int tl_set_keep_gates(tl_ctx *ctx, int on);
  * workgroups).  Nothing is read back and the call returns without waiting; a malformed batch is then reported
  * by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results as the per-height launches
  * (same contractions in the same order).
- * on == 0, the default: tl_backward returns the structure pass's verdict itself, as described there.  Where the
+ * on == 0, the default: tl_backward returns the structure pass's status itself, as described there.  Where the
  * weight-stationary form applies it is the fastest form whatever the shape of the trees (H = 512, 256 trees:
  * 1.26 ms per call against 1.27 with launches per height; 64 trees of 1 024 heights: 13.9 against 16.9 ms), so
- * the call enqueues all its work and then waits only for the copy of the verdict, which sits in front of that
+ * the call enqueues all its work and then waits only for the copy of that status, which sits in front of that
  * kernel.  Otherwise (other hidden sizes, TreeRNN: the persistent kernel with the streaming cell is 13 % slower
  * than the launches on shallow batches and faster on deep ones) the call waits for the number of heights and
  * takes the persistent kernel for more than 64 of them, launches per height up to there.

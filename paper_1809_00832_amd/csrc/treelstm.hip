@@ -96,7 +96,7 @@ struct tl_ctx {
     // profiling
     int profiling = 0;
     hipEvent_t ev[TL_PROFILE_RING][TL_N_STAGES]{};   // created on first use
-    hipEvent_t ev_ctl = nullptr;      // tl_backward: behind the copy of the structure pass's verdict, in front of the kernels that do not need the host
+    hipEvent_t ev_ctl = nullptr;      // tl_backward: behind the copy of the structure pass's status, in front of the kernels that do not need the host
     long long n_recorded = 0;                        // forwards recorded since profiling was switched on
 };
 
@@ -1305,17 +1305,17 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     };
     int n_levels = 0;
     const int levels_ahead = n_nodes + 2 < LEVELS_AHEAD ? n_nodes + 2 : LEVELS_AHEAD;   // offsets read back together with the control block
-    bool verdict_pending = false;
+    bool status_pending = false;
     if (heights_on_device) {
         launch_all_heights();
     } else if (ws && ctx->async_backward == 0) {
         // The weight-stationary form is the faster one whatever the number of heights, and needs nothing from the host: the
-        // structure pass's verdict is copied out in front of it, everything is enqueued, and the call then waits for that copy
-        // alone (the device works on meanwhile) to return the verdict as it always has.
+        // structure pass's status is copied out in front of it, everything is enqueued, and the call then waits for that copy
+        // alone (the device works on meanwhile) to return that status as it always has.
         if (!ctx->ev_ctl) TL_HIP(hipEventCreateWithFlags(&ctx->ev_ctl, hipEventDisableTiming));
         TL_HIP(hipMemcpyAsync(ctx->host_ctl, f.ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
         TL_HIP(hipEventRecord(ctx->ev_ctl, st));
-        verdict_pending = true;
+        status_pending = true;
         launch_all_heights();
     } else {
         if ((rc = read_ctl(ctx, levels_ahead)) != TL_OK) return rc;
@@ -1425,7 +1425,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                            d_b_leaf);
     }
     TL_HIP(hipGetLastError());
-    if (verdict_pending) {
+    if (status_pending) {
         TL_HIP(hipEventSynchronize(ctx->ev_ctl));
         if (ctx->host_ctl->status == 0 && !f.flow_roots && ctx->host_ctl->n_roots != n_trees) ctx->host_ctl->status = TL_ESTRUCT;
         if (ctx->host_ctl->status != 0) return ctx->host_ctl->status;

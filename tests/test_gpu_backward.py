@@ -233,7 +233,7 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
                 assert_grad_close(got[k].cpu().numpy(), ref[k], "h128 without waiting %s" % k)
         if name == "h128":
             # default mode at a size of the weight-stationary form: everything is enqueued before the call waits for the
-            # structure pass's verdict, which it still returns
+            # structure pass's status, which it still returns
             bad = dict(b)
             bad["left"] = b["left"].clone()
             bad["left"][w.trees.n_nodes - 1] = 0             # the last leaf gets one child, and that in another tree
