@@ -329,7 +329,7 @@ int tl_set_keep_gates(tl_ctx *ctx, int on);
  * For callers that must not be held up by tl_backward (the recursion of Section 4.2.2 walked without the host):
  * with on > 0, a tl_backward that needs no contraction for its gate gradients - TreeLSTM from kept gate
  * activations (tl_set_keep_gates), TreeRNN - walks all heights in one persistent kernel that finds the
- * per-height lists on the device (TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary
+ * per-height lists on the device (TreeLSTM with H = 128, 256, 384 or 512: the operand gradient on weight-stationary
  * workgroups).  Nothing is read back and the call returns without waiting; a malformed batch is then reported
  * by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results as the per-height launches
  * (same contractions in the same order).

@@ -609,6 +609,20 @@ void free_all(tl_ctx *ctx)
     delete ctx;
 }
 
+// The persistent backward kernel with the weight-stationary operand gradient for 5 H / 128 = spw2 (H = 128, 256, 384, 512),
+// and the LDS it takes.
+typedef void (*bwh_ws_kernel)(Fwd, BwdHeights);
+bwh_ws_kernel backward_ws_kernel(int spw2, size_t *lds)
+{
+    switch (spw2) {
+    case 5:  *lds = sizeof(OperandWsSmem<5>);  return bwh_ws_kernel(k_backward_heights_ws<5>);
+    case 10: *lds = sizeof(OperandWsSmem<10>); return bwh_ws_kernel(k_backward_heights_ws<10>);
+    case 15: *lds = sizeof(OperandWsSmem<15>); return bwh_ws_kernel(k_backward_heights_ws<15>);
+    case 20: *lds = sizeof(OperandWsSmem<20>); return bwh_ws_kernel(k_backward_heights_ws<20>);
+    default: *lds = 0; return nullptr;
+    }
+}
+
 int create_impl(const tl_config *cfg, tl_ctx *ctx)
 {
     ctx->cfg = *cfg;
@@ -763,12 +777,10 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         // weight-stationary operand gradient: 5 H / 128 k-steps per wave and half of its quarter of the K axis
         ctx->bw_ws_grid = 0;
         const int H_ = cfg->hidden, n_cg_b = 2 * H_ / HU;
-        if (cfg->cell == TL_TREELSTM && H_ % 128 == 0 && (H_ == 128 || H_ == 256 || H_ == 512) && ctx->n_cu >= n_cg_b) {
+        if (cfg->cell == TL_TREELSTM && H_ % 128 == 0 && H_ <= 512 && ctx->n_cu >= n_cg_b) {
             ctx->bw_spw2 = 5 * H_ / 128;
-            typedef void (*bwh_kernel)(Fwd, BwdHeights);
-            const bwh_kernel k = ctx->bw_spw2 == 5 ? bwh_kernel(k_backward_heights_ws<5>)
-                                 : ctx->bw_spw2 == 10 ? bwh_kernel(k_backward_heights_ws<10>) : bwh_kernel(k_backward_heights_ws<20>);
-            const size_t lds = ctx->bw_spw2 == 5 ? sizeof(OperandWsSmem<5>) : ctx->bw_spw2 == 10 ? sizeof(OperandWsSmem<10>) : sizeof(OperandWsSmem<20>);
+            size_t lds = 0;
+            const bwh_ws_kernel k = backward_ws_kernel(ctx->bw_spw2, &lds);
             if ((rc = allow_lds(k, lds)) != TL_OK) return rc;
             int o = 0;
             TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(k), WG_THREADS, lds));
@@ -1281,7 +1293,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     // one persistent kernel, which finds the per-height lists on the device.  Nothing is read back, the call does not wait;
     // what the structure pass finds wrong with the batch is latched for tl_status, and every kernel below leaves at once.
     const bool persistent_ok = ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
-    // TreeLSTM with H = 128, 256 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
+    // TreeLSTM with H = 128, 256, 384 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
     const bool ws = persistent_ok && lstm && kept_v4 && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 &&
                     (unsigned long long)n_int * 5ull * H * 4ull < (1ull << 32);
     const bool heights_on_device = ctx->async_backward > 0 && persistent_ok;
@@ -1295,9 +1307,8 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
         const bwh_kernel k = lstm ? (v4 ? bwh_kernel(k_backward_heights<true, true>) : bwh_kernel(k_backward_heights<true, false>))
                                   : (v4 ? bwh_kernel(k_backward_heights<false, true>) : bwh_kernel(k_backward_heights<false, false>));
         if (ws) {
-            const bwh_kernel kw = ctx->bw_spw2 == 5 ? bwh_kernel(k_backward_heights_ws<5>)
-                                  : ctx->bw_spw2 == 10 ? bwh_kernel(k_backward_heights_ws<10>) : bwh_kernel(k_backward_heights_ws<20>);
-            const size_t lds = ctx->bw_spw2 == 5 ? sizeof(OperandWsSmem<5>) : ctx->bw_spw2 == 10 ? sizeof(OperandWsSmem<10>) : sizeof(OperandWsSmem<20>);
+            size_t lds = 0;
+            const bwh_ws_kernel kw = backward_ws_kernel(ctx->bw_spw2, &lds);
             hipLaunchKernelGGL(kw, dim3(ctx->bw_ws_grid), dim3(WG_THREADS), lds, st, f, b);
         } else {
             hipLaunchKernelGGL(k, dim3(ctx->bw_grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f, b);

@@ -175,21 +175,21 @@ def test_backward_from_kept_gate_activations(scheduler):
         net.close()
 
 
-def _workload_h128():
-    """37 trees of mixed shapes (a single leaf, chains, balanced and random trees) at H = 128: the smallest hidden size whose
-    operand gradient runs on weight-stationary workgroups."""
+def _workload_ws(H):
+    """37 trees of mixed shapes (a single leaf, chains, balanced and random trees) at H = 128, the smallest hidden size whose
+    operand gradient runs on weight-stationary workgroups, or 384, the one whose pieces of a row are not a power of two."""
     counts = [1, 2, 3, 17, 64, 100, 33] + list(synth.Stream(7, "leaves").integers(2, 60, 30))
     shapes = ["random", "chain", "balanced", "chain", "balanced", "random", "chain"] + ["random"] * 30
-    return synth.Workload("h128", synth.make_trees(7, counts, shapes, 1000), synth.make_treelstm_params(7, 1000, 64, 128, "xavier"))
+    return synth.Workload("h%d" % H, synth.make_trees(7, counts, shapes, 1000), synth.make_treelstm_params(7, 1000, 64, H, "xavier"))
 
 
-@pytest.mark.parametrize("name", ["sentence", "throughput", "stress", "treernn", "h128"])
+@pytest.mark.parametrize("name", ["sentence", "throughput", "stress", "treernn", "h128", "h384"])
 def test_backward_that_does_not_wait_gives_the_same_bits(name):
     """tl_set_async_backward: all heights in one persistent kernel (TreeLSTM from kept gate activations, TreeRNN), no read-back
     of the heights.  Same contractions in the same order as the per-height launches, so the gradients that reach the leaves
     must agree bit for bit; a malformed batch is then reported by tl_status, not by the call."""
     print("case backward without waiting", name, flush=True)
-    w = _workload_h128() if name == "h128" else synth.workload(name)
+    w = _workload_ws(int(name[1:])) if name in ("h128", "h384") else synth.workload(name)
     net = binding.TreeNet(w.params, scheduler="dataflow")
     try:
         b = net.load(w.trees)
@@ -221,16 +221,16 @@ def test_backward_that_does_not_wait_gives_the_same_bits(name):
             assert not torch.equal(got2["d_x"], waited["d_x"])
             got = binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)       # and back
             assert torch.equal(got["d_x"], waited["d_x"])
-        if name in ("throughput", "h128", "treernn"):         # twenty more calls of the persistent kernel: the same bits every time
+        if name in ("throughput", "h128", "h384", "treernn"):  # twenty more calls of the persistent kernel: the same bits every time
             binding.tl_set_async_backward(net.ctx, 1)
             for _ in range(20):
                 assert torch.equal(binding.tl_backward(net.ctx, b, g_h, w.params.embed_dim)["d_x"], waited["d_x"])
             assert binding.tl_status(net.ctx) == 0
-        if name == "h128":                                   # this size against the checker as well, through the call that does not wait
+        if name in ("h128", "h384"):                         # these sizes against the checker as well, through the call that does not wait
             g = g_h.cpu().numpy()
             ref = oracle.backward(w.params, w.trees, b["h"].cpu().numpy(), b["c"].cpu().numpy(), g)
             for k in ref:
-                assert_grad_close(got[k].cpu().numpy(), ref[k], "h128 without waiting %s" % k)
+                assert_grad_close(got[k].cpu().numpy(), ref[k], "%s without waiting %s" % (name, k))
         if name == "h128":
             # default mode at a size of the weight-stationary form: everything is enqueued before the call waits for the
             # structure pass's status, which it still returns
