@@ -329,7 +329,7 @@ int tl_set_keep_gates(tl_ctx *ctx, int on);
  * For callers that must not be held up by tl_backward (the recursion of Section 4.2.2 walked without the host):
  * with on > 0, a tl_backward that needs no contraction for its gate gradients - TreeLSTM from kept gate
  * activations (tl_set_keep_gates), TreeRNN - walks all heights in one persistent kernel that finds the
- * per-height lists on the device (TreeLSTM with H = 128, 256, 384 or 512: the operand gradient on weight-stationary
+ * per-height lists on the device (TreeLSTM and TreeRNN with H = 128, 256, 384 or 512: the operand gradient on weight-stationary
  * workgroups).  Nothing is read back and the call returns without waiting; a malformed batch is then reported
  * by tl_status (TL_ESTRUCT, gradients undefined), not by tl_backward.  Same results as the per-height launches
  * (same contractions in the same order).
@@ -337,7 +337,7 @@ int tl_set_keep_gates(tl_ctx *ctx, int on);
  * weight-stationary form applies it is the fastest form whatever the shape of the trees (H = 512, 256 trees:
  * 1.26 ms per call against 1.27 with launches per height; 64 trees of 1 024 heights: 13.9 against 16.9 ms), so
  * the call enqueues all its work and then waits only for the copy of that status, which sits in front of that
- * kernel.  Otherwise (other hidden sizes, TreeRNN: the persistent kernel with the streaming cell is 13 % slower
+ * kernel.  Otherwise (other hidden sizes: the persistent kernel with the streaming cell is 5 % slower
  * than the launches on shallow batches and faster on deep ones) the call waits for the number of heights and
  * takes the persistent kernel for more than 64 of them, launches per height up to there.
  * on < 0: always launches per height.  Like the persistent schedulers of tl_forward, the kernel needs all its

@@ -541,7 +541,8 @@ template <int SPW2> struct OperandWsSmem {
     int cmd[8];
 };
 
-template <int SPW2>
+// (LSTM = false: TreeRNN, whose rows of dG have H values, so K = H: a multiple of 128, SPW2 = H / 128.)
+template <int SPW2, bool LSTM = true>
 __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, BwdHeights b)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -551,7 +552,7 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
     constexpr int NLB = SPW2;                               // row loads per lane and half: 16 rows x 4 SPW2 pieces / 64 lanes
     constexpr int PPR = 4 * SPW2;                           // 16-byte pieces of a row in one half of a wave's quarter
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int H = f.H, K = 5 * H;
+    const int H = f.H, K = (LSTM ? 5 : 1) * H;
     const int n_cg = 2 * H / HU;
     const int cg = (int)blockIdx.x % n_cg, slot = (int)blockIdx.x / n_cg, n_slots = (int)gridDim.x / n_cg;
     const int n_levels = f.ctl->n_levels;
@@ -612,7 +613,9 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
     for (int lvl = n_levels - 1; lvl >= 1; --lvl) {
         const int lo = f.level_off[lvl], n_rows = f.level_off[lvl + 1] - lo;
         const int32_t *list = f.level_nodes + lo;
-        gate_grad_kept_rows<true, 4, true>(g, list, n_rows, lo, first, stride);         // (H % 128 == 0; the host has checked the alignment)
+        // (H % 128 == 0; the host has checked the alignment)
+        if constexpr (LSTM) gate_grad_kept_rows<true, 4, true>(g, list, n_rows, lo, first, stride);
+        else rnn_gate_grad_rows<4, true>(g, list, n_rows, lo, first, stride);
         if (!grid_barrier(sm, f, epoch, 0u, 0u, &unused)) return;
         const int n_blocks = (n_rows + 15) >> 4;
         if (slot < n_blocks) {

@@ -609,18 +609,30 @@ void free_all(tl_ctx *ctx)
     delete ctx;
 }
 
-// The persistent backward kernel with the weight-stationary operand gradient for 5 H / 128 = spw2 (H = 128, 256, 384, 512),
-// and the LDS it takes.
+// The persistent backward kernel with the weight-stationary operand gradient, and the LDS it takes: TreeLSTM with
+// 5 H / 128 = spw2 (H = 128, 256, 384, 512), TreeRNN with H / 128 = spw2 (the same sizes).
 typedef void (*bwh_ws_kernel)(Fwd, BwdHeights);
-bwh_ws_kernel backward_ws_kernel(int spw2, size_t *lds)
+bwh_ws_kernel backward_ws_kernel(bool lstm, int spw2, size_t *lds)
 {
-    switch (spw2) {
-    case 5:  *lds = sizeof(OperandWsSmem<5>);  return bwh_ws_kernel(k_backward_heights_ws<5>);
-    case 10: *lds = sizeof(OperandWsSmem<10>); return bwh_ws_kernel(k_backward_heights_ws<10>);
-    case 15: *lds = sizeof(OperandWsSmem<15>); return bwh_ws_kernel(k_backward_heights_ws<15>);
-    case 20: *lds = sizeof(OperandWsSmem<20>); return bwh_ws_kernel(k_backward_heights_ws<20>);
-    default: *lds = 0; return nullptr;
+    if (lstm) {
+        switch (spw2) {
+        case 5:  *lds = sizeof(OperandWsSmem<5>);  return bwh_ws_kernel(k_backward_heights_ws<5, true>);
+        case 10: *lds = sizeof(OperandWsSmem<10>); return bwh_ws_kernel(k_backward_heights_ws<10, true>);
+        case 15: *lds = sizeof(OperandWsSmem<15>); return bwh_ws_kernel(k_backward_heights_ws<15, true>);
+        case 20: *lds = sizeof(OperandWsSmem<20>); return bwh_ws_kernel(k_backward_heights_ws<20, true>);
+        default: break;
+        }
+    } else {
+        switch (spw2) {
+        case 1: *lds = sizeof(OperandWsSmem<1>); return bwh_ws_kernel(k_backward_heights_ws<1, false>);
+        case 2: *lds = sizeof(OperandWsSmem<2>); return bwh_ws_kernel(k_backward_heights_ws<2, false>);
+        case 3: *lds = sizeof(OperandWsSmem<3>); return bwh_ws_kernel(k_backward_heights_ws<3, false>);
+        case 4: *lds = sizeof(OperandWsSmem<4>); return bwh_ws_kernel(k_backward_heights_ws<4, false>);
+        default: break;
+        }
     }
+    *lds = 0;
+    return nullptr;
 }
 
 int create_impl(const tl_config *cfg, tl_ctx *ctx)
@@ -777,10 +789,10 @@ int create_impl(const tl_config *cfg, tl_ctx *ctx)
         // weight-stationary operand gradient: 5 H / 128 k-steps per wave and half of its quarter of the K axis
         ctx->bw_ws_grid = 0;
         const int H_ = cfg->hidden, n_cg_b = 2 * H_ / HU;
-        if (cfg->cell == TL_TREELSTM && H_ % 128 == 0 && H_ <= 512 && ctx->n_cu >= n_cg_b) {
-            ctx->bw_spw2 = 5 * H_ / 128;
+        if ((cfg->cell == TL_TREELSTM || cfg->cell == TL_TREERNN) && H_ % 128 == 0 && H_ <= 512 && ctx->n_cu >= n_cg_b) {
+            ctx->bw_spw2 = (cfg->cell == TL_TREELSTM ? 5 : 1) * H_ / 128;
             size_t lds = 0;
-            const bwh_ws_kernel k = backward_ws_kernel(ctx->bw_spw2, &lds);
+            const bwh_ws_kernel k = backward_ws_kernel(cfg->cell == TL_TREELSTM, ctx->bw_spw2, &lds);
             if ((rc = allow_lds(k, lds)) != TL_OK) return rc;
             int o = 0;
             TL_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&o, reinterpret_cast<const void *>(k), WG_THREADS, lds));
@@ -1294,8 +1306,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     // what the structure pass finds wrong with the batch is latched for tl_status, and every kernel below leaves at once.
     const bool persistent_ok = ctx->bw_grid > 0 && !rntn && (kept || !lstm) && n_int > 0;
     // TreeLSTM with H = 128, 256, 384 or 512: the operand gradient on weight-stationary workgroups (row offsets of dG in 32 bits)
-    const bool ws = persistent_ok && lstm && kept_v4 && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 &&
-                    (unsigned long long)n_int * 5ull * H * 4ull < (1ull << 32);
+    // (TreeRNN: the same sizes, K = H)
+    const bool ws = persistent_ok && (lstm ? kept_v4 : vec4) && ctx->bw_ws_grid > 0 && ctx->ng_bwd_inner == 4 &&
+                    (unsigned long long)n_int * (unsigned long long)dg_cols * 4ull < (1ull << 32);
     const bool heights_on_device = ctx->async_backward > 0 && persistent_ok;
     auto launch_all_heights = [&]() {
         BwdHeights b{};
@@ -1308,7 +1321,7 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
                                   : (v4 ? bwh_kernel(k_backward_heights<false, true>) : bwh_kernel(k_backward_heights<false, false>));
         if (ws) {
             size_t lds = 0;
-            const bwh_ws_kernel kw = backward_ws_kernel(ctx->bw_spw2, &lds);
+            const bwh_ws_kernel kw = backward_ws_kernel(lstm, ctx->bw_spw2, &lds);
             hipLaunchKernelGGL(kw, dim3(ctx->bw_ws_grid), dim3(WG_THREADS), lds, st, f, b);
         } else {
             hipLaunchKernelGGL(k, dim3(ctx->bw_grid), dim3(WG_THREADS), TILE_SMEM_BYTES, st, f, b);

@@ -418,7 +418,7 @@ def test_treernn_backward_matches_oracle():
 def test_deep_trees_take_the_persistent_kernel_by_default():
     """More than 64 heights: tl_backward in its default mode walks them in one persistent kernel.  Chains of 100 to 300 leaves
     beside shallow trees, against the checker: TreeLSTM from kept activations at a hidden size of the streaming form (72) and
-    of the weight-stationary form (128), and TreeRNN (d = 40, 64)."""
+    of the weight-stationary form (128), and TreeRNN (d = 40, 64, 128)."""
     print("case backward, deep trees, default mode", flush=True)
     leaves = [300, 1, 7, 100, 33, 150, 2]
     shapes = ["chain", "random", "balanced", "chain", "random", "chain", "random"]
@@ -426,7 +426,7 @@ def test_deep_trees_take_the_persistent_kernel_by_default():
         params = synth.make_treelstm_params(120 + i, 60, 24, H, "xavier")
         trees = synth.make_trees(120 + i, leaves, shapes, 60)
         run_case(params, trees, 120 + i, "deep lstm H=%d" % H, keep=True, scheduler="dataflow")
-    for i, d in enumerate([40, 64]):
+    for i, d in enumerate([40, 64, 128]):                   # (128: weight-stationary form of the persistent kernel)
         params = synth.make_rnn_params(130 + i, synth.CELL_TREERNN, 60, d, scale=0.4)
         trees = synth.make_trees(130 + i, leaves, shapes, 60)
         run_rnn_case(params, trees, 130 + i, "deep rnn d=%d" % d)
