@@ -680,13 +680,23 @@ __global__ __launch_bounds__(WG_THREADS, 1) void k_backward_heights_ws(Fwd f, Bw
 struct ZeroList {
     float *p[6];
     size_t n[6];
+    const float *src;       // and one copy in the same launch: dst[0 .. n_copy) = src (n_copy = 0: none); a multiple of
+    float *dst;             // four floats with both ends 16-byte aligned is moved 16 bytes at a time
+    size_t n_copy;
 };
 __global__ void k_zero_many(ZeroList z)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x, first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (z.n_copy % 4 == 0 && (((uintptr_t)z.src | (uintptr_t)z.dst) & 15) == 0) {
+        const floatx4 *s4 = reinterpret_cast<const floatx4 *>(z.src);
+        floatx4 *d4 = reinterpret_cast<floatx4 *>(z.dst);
+        for (size_t e = first; e < z.n_copy / 4; e += stride) d4[e] = s4[e];
+    } else {
+        for (size_t e = first; e < z.n_copy; e += stride) z.dst[e] = z.src[e];
+    }
 #pragma unroll
     for (int a = 0; a < 6; ++a)
-        for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < z.n[a]; e += stride) z.p[a][e] = 0.f;
+        for (size_t e = first; e < z.n[a]; e += stride) z.p[a][e] = 0.f;
 }
 
 }  // namespace tl

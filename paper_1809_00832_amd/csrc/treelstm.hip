@@ -1284,9 +1284,9 @@ int tl_backward(tl_ctx *ctx, int n_trees, int n_nodes, const int32_t *tree_off, 
     hipLaunchKernelGGL(k_scan_levels, dim3(1), dim3(1024), 0, st, f);
     hipLaunchKernelGGL(k_fill_levels, dim3(nb_nodes), dim3(256), 0, st, f);
     // dh starts as the upstream gradient of every node, dc as zero; d_x rows of internal nodes stay zero
-    TL_HIP(hipMemcpyAsync(f.dh, g_h, (size_t)n_nodes * H * sizeof(float), hipMemcpyDeviceToDevice, st));
     {
         ZeroList z{};
+        z.src = g_h; z.dst = f.dh; z.n_copy = (size_t)n_nodes * H;
         z.p[0] = f.dc;     z.n[0] = lstm ? (size_t)n_nodes * H : 0;
         z.p[1] = d_x;      z.n[1] = (size_t)n_nodes * E;
         z.p[2] = d_b;      z.n[2] = (size_t)ng_cell * H;
